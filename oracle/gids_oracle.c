@@ -1,0 +1,454 @@
+/* CPU oracle for the minibatch feature gather of the GIDS dataloader.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Plain, single-threaded, deliberately slow C that
+ * the tests, the smoke check and the benchmark's cpu_baseline leg compare the
+ * HIP library against.  It shares no code with the HIP path and the HIP path
+ * never calls it.
+ *
+ * What it covers, and the passage of the paper each part follows:
+ *   - seeded power-law graph generator and feature closed form (synthetic
+ *     stand-ins for the datasets of Section 4.1, Tables 2-3);
+ *   - neighbourhood sampler: up to `fanout` neighbours per node per layer,
+ *     uniformly at random (Section 2.2.2 and its two-layer worked example);
+ *   - feature aggregation: out[j] = feature row of the j-th distinct node ID
+ *     of the minibatch, ascending (Section 2.2.3);
+ *   - constant CPU buffer: IDs pinned there are redirected to it and never
+ *     enter the GPU cache (Section 3.3);
+ *   - set-associative software cache with window buffering: a per-node count
+ *     of the buffered future minibatches that reuse the node; lines whose
+ *     count is positive are in the "USE" state and are not evicted, count 0 is
+ *     "safe to evict" (Section 3.4, Fig. 6 steps 1-5);
+ *   - the overlapped-access model N = r/(1-r) * IOPS * (Ti + Tt) (Section 3.2,
+ *     Eq. 2-3).
+ *
+ * Parity pins (see tests/): brute-force row equality, count conservation,
+ * cache >= store => only first-touch misses, depth 0 == textbook per-set LRU
+ * by batch, pinned lines never evicted, CPU-buffer hits == |U ∩ P|, a
+ * hand-traced fully-associative case, the sampler's worked example.  The
+ * tie-breaks of the replacement policy (lowest way first, ascending ID first,
+ * bypass when nothing is evictable) are fixed by this project, not the paper:
+ * for those constants alone, parity unpinned.
+ *
+ * The replacement policy is batch-synchronous: every ID of a minibatch is
+ * classified against the cache state at the start of the minibatch, then the
+ * misses are installed set by set.  The paper's base policy is random
+ * eviction; here it is least-recently-used by minibatch stamp so that two
+ * implementations can agree bit for bit.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define GO_OK 0
+#define GO_E_INVAL (-1)
+#define GO_E_NOMEM (-2)
+#define GO_E_RANGE (-3)
+#define GO_E_ORDER (-4)
+#define GO_E_FULL (-5)
+
+/* ---------------------------------------------------------------- hashing */
+
+static uint64_t mix64(uint64_t z) {
+    z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ull;
+    z ^= z >> 27; z *= 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return z;
+}
+
+enum { TAG_DEG = 1, TAG_EDGE = 2, TAG_FEAT = 3, TAG_SEED = 4, TAG_NBR = 5 };
+
+static uint64_t key0(uint64_t seed, uint64_t tag) {
+    return mix64(seed + tag * 0x9E3779B97F4A7C15ull);
+}
+
+uint64_t go_mix64(uint64_t z) { return mix64(z); }
+
+/* ------------------------------------------------------------------ graph */
+
+typedef struct {
+    int64_t n, e;
+    int64_t* indptr;   /* n + 1 */
+    int64_t* indices;  /* e */
+    uint64_t seed;
+} go_graph;
+
+static int64_t degree_of(uint64_t seed, int64_t v, double ell, int p4, int64_t d_max) {
+    uint64_t h = mix64(key0(seed, TAG_DEG) ^ (uint64_t)v);
+    double x = ((double)(h >> 32) + 1.0) / 4294967296.0;   /* (0, 1] */
+    double q = sqrt(sqrt(x));
+    double y = q;
+    for (int i = 1; i < p4; i++) y = y * q;                /* x^(p4/4) */
+    double d = floor(ell / y);
+    if (d < 1.0) d = 1.0;
+    if (d > (double)d_max) d = (double)d_max;
+    return (int64_t)d;
+}
+
+/* the node u with indptr[u] <= slot < indptr[u+1] */
+static int64_t owner_of(const int64_t* indptr, int64_t n, int64_t slot) {
+    int64_t lo = 0, hi = n;            /* answer in [lo, hi) */
+    while (hi - lo > 1) {
+        int64_t mid = lo + (hi - lo) / 2;
+        if (indptr[mid] <= slot) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+go_graph* go_graph_create(uint64_t seed, int64_t n, double ell, int p4, int64_t d_max) {
+    if (n < 2 || p4 < 1 || d_max < 1) return NULL;
+    go_graph* g = (go_graph*)calloc(1, sizeof(go_graph));
+    if (!g) return NULL;
+    g->n = n; g->seed = seed;
+    g->indptr = (int64_t*)malloc((size_t)(n + 1) * sizeof(int64_t));
+    if (!g->indptr) { free(g); return NULL; }
+    g->indptr[0] = 0;
+    for (int64_t v = 0; v < n; v++) g->indptr[v + 1] = g->indptr[v] + degree_of(seed, v, ell, p4, d_max);
+    g->e = g->indptr[n];
+    g->indices = (int64_t*)malloc((size_t)g->e * sizeof(int64_t));
+    if (!g->indices) { free(g->indptr); free(g); return NULL; }
+    uint64_t k = key0(seed, TAG_EDGE);
+    for (int64_t e = 0; e < g->e; e++) {
+        int64_t slot = (int64_t)(mix64(k ^ (uint64_t)e) % (uint64_t)g->e);
+        g->indices[e] = owner_of(g->indptr, n, slot);
+    }
+    return g;
+}
+
+/* a graph from caller-given CSR arrays (copied); for hand-built test cases */
+go_graph* go_graph_from_csr(int64_t n, const int64_t* indptr, const int64_t* indices) {
+    if (n < 1 || indptr[0] != 0) return NULL;
+    go_graph* g = (go_graph*)calloc(1, sizeof(go_graph));
+    if (!g) return NULL;
+    g->n = n; g->e = indptr[n];
+    g->indptr = (int64_t*)malloc((size_t)(n + 1) * sizeof(int64_t));
+    g->indices = (int64_t*)malloc((size_t)(g->e > 0 ? g->e : 1) * sizeof(int64_t));
+    if (!g->indptr || !g->indices) { free(g->indptr); free(g->indices); free(g); return NULL; }
+    memcpy(g->indptr, indptr, (size_t)(n + 1) * sizeof(int64_t));
+    memcpy(g->indices, indices, (size_t)g->e * sizeof(int64_t));
+    return g;
+}
+
+void go_graph_free(go_graph* g) { if (g) { free(g->indptr); free(g->indices); free(g); } }
+int64_t go_graph_edges(const go_graph* g) { return g->e; }
+const int64_t* go_graph_indptr(const go_graph* g) { return g->indptr; }
+const int64_t* go_graph_indices(const go_graph* g) { return g->indices; }
+
+typedef struct { int64_t indeg, id; } hot_key;
+static int cmp_hot(const void* a, const void* b) {
+    const hot_key* x = (const hot_key*)a; const hot_key* y = (const hot_key*)b;
+    if (x->indeg != y->indeg) return x->indeg > y->indeg ? -1 : 1;   /* larger in-degree first */
+    return (x->id > y->id) - (x->id < y->id);                        /* then lower ID */
+}
+
+/* the k nodes of highest in-degree, ties to the lower ID (the configurations'
+ * stand-in for the paper's reverse-PageRank hot-node ranking, Section 3.3) */
+int go_hot_nodes(const go_graph* g, int64_t k, int64_t* out) {
+    if (k < 0 || k > g->n) return GO_E_INVAL;
+    hot_key* a = (hot_key*)malloc((size_t)g->n * sizeof(hot_key));
+    if (!a) return GO_E_NOMEM;
+    for (int64_t v = 0; v < g->n; v++) { a[v].indeg = 0; a[v].id = v; }
+    for (int64_t e = 0; e < g->e; e++) a[g->indices[e]].indeg++;
+    qsort(a, (size_t)g->n, sizeof(hot_key), cmp_hot);
+    for (int64_t i = 0; i < k; i++) out[i] = a[i].id;
+    free(a);
+    return GO_OK;
+}
+
+/* ----------------------------------------------------------- sort-unique */
+
+static int cmp_i64(const void* a, const void* b) {
+    int64_t x = *(const int64_t*)a, y = *(const int64_t*)b;
+    return (x > y) - (x < y);
+}
+
+/* ascending distinct values of raw[0..n); returns their count */
+int64_t go_sort_unique(const int64_t* raw, int64_t n, int64_t* out) {
+    if (n <= 0) return 0;
+    memcpy(out, raw, (size_t)n * sizeof(int64_t));
+    qsort(out, (size_t)n, sizeof(int64_t), cmp_i64);
+    int64_t m = 1;
+    for (int64_t i = 1; i < n; i++) if (out[i] != out[m - 1]) out[m++] = out[i];
+    return m;
+}
+
+/* ---------------------------------------------------------------- sampler */
+
+/* Raw node-ID list of minibatch `batch` (Section 2.2.2): the seed nodes, then
+ * for each layer the sampled neighbours of every frontier node (frontier in
+ * ascending ID order), duplicates kept.  A node of degree <= fanout gives all
+ * of its neighbours; otherwise `fanout` distinct adjacency slots are drawn
+ * without replacement (Floyd's subset sampling on hashed draws).  The next
+ * frontier is the distinct set of nodes this hop sampled.
+ * Returns the raw count, or a negative error when `cap` is too small. */
+int64_t go_sample(const go_graph* g, uint64_t seed, int64_t batch, const int32_t* fanouts, int n_layers,
+                  int64_t n_seeds, int64_t* out, int64_t cap) {
+    if (n_seeds < 0 || n_seeds > cap) return GO_E_INVAL;
+    uint64_t ks = mix64(key0(seed, TAG_SEED) ^ (uint64_t)batch);
+    for (int64_t i = 0; i < n_seeds; i++) out[i] = (int64_t)(mix64(ks ^ (uint64_t)i) % (uint64_t)g->n);
+    int64_t n_raw = n_seeds;
+    int64_t* frontier = (int64_t*)malloc((size_t)(cap > 0 ? cap : 1) * sizeof(int64_t));
+    if (!frontier) return GO_E_NOMEM;
+    int64_t n_front = go_sort_unique(out, n_seeds, frontier);
+    int64_t chosen[64];
+    for (int layer = 0; layer < n_layers; layer++) {
+        int64_t f = fanouts[layer];
+        if (f < 1 || f > 64) { free(frontier); return GO_E_INVAL; }
+        uint64_t kl = mix64(mix64(key0(seed, TAG_NBR) ^ (uint64_t)batch) ^ (uint64_t)layer);
+        int64_t layer_begin = n_raw;
+        for (int64_t i = 0; i < n_front; i++) {
+            int64_t v = frontier[i];
+            int64_t start = g->indptr[v], deg = g->indptr[v + 1] - start;
+            int64_t take = deg <= f ? deg : f;
+            if (n_raw + take > cap) { free(frontier); return GO_E_FULL; }
+            if (deg <= f) {
+                for (int64_t s = 0; s < deg; s++) out[n_raw++] = g->indices[start + s];
+            } else {
+                uint64_t kv = mix64(kl ^ (uint64_t)v);
+                int64_t m = 0;
+                for (int64_t j = deg - f; j < deg; j++) {
+                    int64_t t = (int64_t)(mix64(kv ^ (uint64_t)j) % (uint64_t)(j + 1));
+                    int seen = 0;
+                    for (int64_t c = 0; c < m; c++) if (chosen[c] == t) seen = 1;
+                    chosen[m++] = seen ? j : t;
+                }
+                for (int64_t c = 0; c < m; c++) out[n_raw++] = g->indices[start + chosen[c]];
+            }
+        }
+        /* next frontier = the distinct nodes reached by this hop (the worked
+         * example expands 1 -> 3 -> 6: only the previous hop's nodes) */
+        n_front = go_sort_unique(out + layer_begin, n_raw - layer_begin, frontier);
+    }
+    free(frontier);
+    return n_raw;
+}
+
+/* --------------------------------------------------------------- features */
+
+/* feat(v, c) for c = 0..dim-1 into out: four table indices per hashed word */
+void go_feat_row(uint64_t seed, int64_t v, int32_t dim, int32_t itemsize, const void* table, void* out) {
+    uint64_t kv = mix64(key0(seed, TAG_FEAT) ^ (uint64_t)v);
+    for (int32_t c = 0; c < dim; c++) {
+        uint64_t w = mix64(kv ^ (uint64_t)(c >> 2));
+        uint32_t idx = (uint32_t)((w >> (16 * (c & 3))) & 0xFFFF);
+        memcpy((char*)out + (size_t)c * itemsize, (const char*)table + (size_t)idx * itemsize, (size_t)itemsize);
+    }
+}
+
+/* ----------------------------------------------- overlapped-access model */
+
+/* Section 3.2, Eq. 2-3: N = IOPS_achieved * (Ti + Ts + Tt) * n_ssd with
+ * Ts = N / (IOPS_peak * n_ssd) (per-SSD peak; all SSDs serve the N accesses
+ * together).  Solved for N at IOPS_achieved = ratio * IOPS_peak. */
+double go_accum_threshold(double iops_peak, double t_initial, double t_termination, double ratio, int n_ssd) {
+    return ratio / (1.0 - ratio) * iops_peak * (double)n_ssd * (t_initial + t_termination);
+}
+
+/* -------------------------------------------------------------- simulator */
+
+typedef struct {
+    int64_t n_rows, lines, n_sets;
+    int32_t ways, window;              /* window = number of future minibatches visible */
+    int64_t row_bytes, line_bytes;
+    int64_t t;                         /* index of the next minibatch to gather */
+    int64_t* tag;                      /* lines, -1 = empty */
+    int64_t* stamp;                    /* lines, -1 = never used */
+    int32_t* reuse;                    /* n_rows: buffered future minibatches that contain the node */
+    int64_t* hot_slot;                 /* n_rows: slot in the CPU buffer or -1 */
+    int64_t n_hot;
+    /* FIFO of buffered minibatch ID lists: the one to gather next + `window` later ones */
+    int64_t** win_ids; int64_t* win_n; int32_t win_count;
+    /* optional data plane */
+    const char* store; char* cache_data; char* cpu_buf;
+} go_sim;
+
+void go_sim_free(go_sim* s) {
+    if (!s) return;
+    for (int i = 0; i < s->win_count; i++) free(s->win_ids[i]);
+    free(s->win_ids); free(s->win_n);
+    free(s->tag); free(s->stamp); free(s->reuse); free(s->hot_slot); free(s->cache_data); free(s->cpu_buf);
+    free(s);
+}
+
+/* store == NULL: counts only (no row is moved). */
+go_sim* go_sim_create(int64_t n_rows, int64_t lines, int32_t ways, int32_t window, int64_t row_bytes,
+                      int64_t line_bytes, const void* store) {
+    if (n_rows < 1 || lines < 1 || ways < 1 || lines % ways || window < 0 || window > 254) return NULL;
+    if (store && (line_bytes < row_bytes || row_bytes < 1)) return NULL;
+    go_sim* s = (go_sim*)calloc(1, sizeof(go_sim));
+    if (!s) return NULL;
+    s->n_rows = n_rows; s->lines = lines; s->ways = ways; s->n_sets = lines / ways; s->window = window;
+    s->row_bytes = row_bytes; s->line_bytes = line_bytes; s->store = (const char*)store;
+    s->tag = (int64_t*)malloc((size_t)lines * sizeof(int64_t));
+    s->stamp = (int64_t*)malloc((size_t)lines * sizeof(int64_t));
+    s->reuse = (int32_t*)calloc((size_t)n_rows, sizeof(int32_t));
+    s->hot_slot = (int64_t*)malloc((size_t)n_rows * sizeof(int64_t));
+    s->win_ids = (int64_t**)calloc((size_t)window + 1, sizeof(int64_t*));
+    s->win_n = (int64_t*)calloc((size_t)window + 1, sizeof(int64_t));
+    if (store) s->cache_data = (char*)malloc((size_t)lines * (size_t)line_bytes);
+    if (!s->tag || !s->stamp || !s->reuse || !s->hot_slot || !s->win_ids || !s->win_n || (store && !s->cache_data)) {
+        go_sim_free(s); return NULL;
+    }
+    for (int64_t i = 0; i < lines; i++) { s->tag[i] = -1; s->stamp[i] = -1; }
+    for (int64_t v = 0; v < n_rows; v++) s->hot_slot[v] = -1;
+    return s;
+}
+
+/* Section 3.3: pin the rows of `ids` in the constant CPU buffer (slot = position in the list) */
+int go_sim_set_hot(go_sim* s, const int64_t* ids, int64_t k) {
+    if (s->n_hot || s->t) return GO_E_INVAL;
+    for (int64_t i = 0; i < k; i++) {
+        if (ids[i] < 0 || ids[i] >= s->n_rows) return GO_E_RANGE;
+        if (s->hot_slot[ids[i]] >= 0) return GO_E_INVAL;
+        s->hot_slot[ids[i]] = i;
+    }
+    s->n_hot = k;
+    if (s->store && k) {
+        s->cpu_buf = (char*)malloc((size_t)k * (size_t)s->row_bytes);
+        if (!s->cpu_buf) return GO_E_NOMEM;
+        for (int64_t i = 0; i < k; i++)
+            memcpy(s->cpu_buf + (size_t)i * s->row_bytes, s->store + (size_t)ids[i] * s->row_bytes, (size_t)s->row_bytes);
+    }
+    return GO_OK;
+}
+
+static int ids_in_range(const go_sim* s, const int64_t* raw, int64_t n) {
+    for (int64_t i = 0; i < n; i++) if (raw[i] < 0 || raw[i] >= s->n_rows) return 0;
+    return 1;
+}
+
+/* Fig. 6 steps 1-4: buffer the ID list of a future minibatch and count, per
+ * node, one more future reuse.  The FIFO holds the minibatch to gather next
+ * plus at most `window` later ones. */
+int go_sim_push(go_sim* s, const int64_t* raw, int64_t n) {
+    if (n < 0) return GO_E_INVAL;
+    if (s->window == 0) return GO_E_INVAL;
+    if (s->win_count == s->window + 1) return GO_E_FULL;
+    if (!ids_in_range(s, raw, n)) return GO_E_RANGE;
+    int64_t* u = (int64_t*)malloc((size_t)(n > 0 ? n : 1) * sizeof(int64_t));
+    if (!u) return GO_E_NOMEM;
+    int64_t m = go_sort_unique(raw, n, u);
+    for (int64_t i = 0; i < m; i++) s->reuse[u[i]]++;
+    s->win_ids[s->win_count] = u; s->win_n[s->win_count] = m; s->win_count++;
+    return GO_OK;
+}
+
+typedef struct { int64_t set, id, j; } miss_rec;
+static int cmp_miss(const void* a, const void* b) {
+    const miss_rec* x = (const miss_rec*)a; const miss_rec* y = (const miss_rec*)b;
+    if (x->set != y->set) return x->set < y->set ? -1 : 1;
+    return (x->id > y->id) - (x->id < y->id);
+}
+typedef struct { int64_t stamp; int32_t way; } victim_rec;
+static int cmp_victim(const void* a, const void* b) {
+    const victim_rec* x = (const victim_rec*)a; const victim_rec* y = (const victim_rec*)b;
+    if (x->stamp != y->stamp) return x->stamp < y->stamp ? -1 : 1;
+    return (x->way > y->way) - (x->way < y->way);
+}
+
+enum { GO_CLS_HIT = 0, GO_CLS_CPU = 1, GO_CLS_MISS = 2, GO_CLS_BYPASS = 3 };
+
+/* Gather minibatch t.
+ *   unique_out  >= n entries; receives the ascending distinct IDs
+ *   out_rows    NULL, or >= n * row_bytes: row j = feature row of unique_out[j]
+ *   stats       {n_unique, hits, cpu_hits, misses (installed + bypass), bypasses}
+ *   cls_out     NULL, or >= n entries: class of each distinct ID (GO_CLS_*)
+ * Returns the distinct count or a negative error (state untouched on error). */
+int64_t go_sim_gather(go_sim* s, const int64_t* raw, int64_t n, int64_t* unique_out, void* out_rows,
+                      int64_t* stats, int32_t* cls_out) {
+    if (n < 0) return GO_E_INVAL;
+    if (!ids_in_range(s, raw, n)) return GO_E_RANGE;
+    int64_t m = go_sort_unique(raw, n, unique_out);
+    const int64_t t = s->t;
+
+    /* window: the buffered head must be this minibatch; drop it and take back
+     * its reuse counts ("decreased each time the node is reused") */
+    if (s->window > 0) {
+        if (s->win_count == 0) return GO_E_ORDER;
+        if (s->win_n[0] != m || memcmp(s->win_ids[0], unique_out, (size_t)m * sizeof(int64_t))) return GO_E_ORDER;
+        for (int64_t i = 0; i < m; i++) s->reuse[unique_out[i]]--;
+        free(s->win_ids[0]);
+        for (int i = 1; i < s->win_count; i++) { s->win_ids[i - 1] = s->win_ids[i]; s->win_n[i - 1] = s->win_n[i]; }
+        s->win_count--; s->win_ids[s->win_count] = NULL;
+    }
+
+    int64_t hits = 0, cpu_hits = 0, misses = 0, bypasses = 0;
+    miss_rec* miss = (miss_rec*)malloc((size_t)(m > 0 ? m : 1) * sizeof(miss_rec));
+    int64_t* src_line = (int64_t*)malloc((size_t)(m > 0 ? m : 1) * sizeof(int64_t));   /* cache line serving j, or -1 */
+    int32_t* cls = (int32_t*)malloc((size_t)(m > 0 ? m : 1) * sizeof(int32_t));
+    victim_rec* vict = (victim_rec*)malloc((size_t)s->ways * sizeof(victim_rec));
+    if (!miss || !src_line || !cls || !vict) { free(miss); free(src_line); free(cls); free(vict); return GO_E_NOMEM; }
+
+    /* classify every ID against the state at the start of the minibatch */
+    for (int64_t j = 0; j < m; j++) {
+        int64_t v = unique_out[j];
+        src_line[j] = -1;
+        if (s->hot_slot[v] >= 0) { cls[j] = GO_CLS_CPU; cpu_hits++; continue; }
+        int64_t set = v % s->n_sets;
+        int32_t way = -1;
+        for (int32_t w = 0; w < s->ways; w++) if (s->tag[set * s->ways + w] == v) way = w;
+        if (way >= 0) {
+            cls[j] = GO_CLS_HIT; hits++;
+            s->stamp[set * s->ways + way] = t;
+            src_line[j] = set * s->ways + way;
+        } else {
+            cls[j] = GO_CLS_MISS;
+            miss[misses].set = set; miss[misses].id = v; miss[misses].j = j; misses++;
+        }
+    }
+
+    /* install, set by set: the k-th miss (ascending ID) takes the k-th
+     * evictable way in (stamp, way) order; a way is evictable when it was not
+     * touched in this minibatch and is empty or holds a node no buffered
+     * future minibatch reuses; misses beyond that bypass the cache */
+    qsort(miss, (size_t)misses, sizeof(miss_rec), cmp_miss);
+    for (int64_t a = 0; a < misses;) {
+        int64_t b = a;
+        while (b < misses && miss[b].set == miss[a].set) b++;
+        int64_t set = miss[a].set;
+        int32_t n_vict = 0;
+        for (int32_t w = 0; w < s->ways; w++) {
+            int64_t line = set * s->ways + w;
+            if (s->stamp[line] == t) continue;
+            if (s->tag[line] != -1 && s->reuse[s->tag[line]] != 0) continue;
+            vict[n_vict].stamp = s->stamp[line]; vict[n_vict].way = w; n_vict++;
+        }
+        qsort(vict, (size_t)n_vict, sizeof(victim_rec), cmp_victim);
+        for (int64_t k = a; k < b; k++) {
+            if (k - a < n_vict) {
+                int64_t line = set * s->ways + vict[k - a].way;
+                s->tag[line] = miss[k].id; s->stamp[line] = t;
+                src_line[miss[k].j] = line;
+            } else {
+                cls[miss[k].j] = GO_CLS_BYPASS; bypasses++;
+            }
+        }
+        a = b;
+    }
+
+    /* data: fills first (store -> cache line), then every row to the output */
+    if (s->store && out_rows) {
+        for (int64_t j = 0; j < m; j++)
+            if (cls[j] == GO_CLS_MISS)
+                memcpy(s->cache_data + (size_t)src_line[j] * s->line_bytes,
+                       s->store + (size_t)unique_out[j] * s->row_bytes, (size_t)s->row_bytes);
+        for (int64_t j = 0; j < m; j++) {
+            const char* src;
+            if (cls[j] == GO_CLS_CPU) src = s->cpu_buf + (size_t)s->hot_slot[unique_out[j]] * s->row_bytes;
+            else if (cls[j] == GO_CLS_BYPASS) src = s->store + (size_t)unique_out[j] * s->row_bytes;
+            else src = s->cache_data + (size_t)src_line[j] * s->line_bytes;
+            memcpy((char*)out_rows + (size_t)j * s->row_bytes, src, (size_t)s->row_bytes);
+        }
+    }
+    if (cls_out) memcpy(cls_out, cls, (size_t)m * sizeof(int32_t));
+    if (stats) { stats[0] = m; stats[1] = hits; stats[2] = cpu_hits; stats[3] = misses; stats[4] = bypasses; }
+    free(miss); free(src_line); free(cls); free(vict);
+    s->t = t + 1;
+    return m;
+}
+
+const int64_t* go_sim_tags(const go_sim* s) { return s->tag; }
+const int64_t* go_sim_stamps(const go_sim* s) { return s->stamp; }
+const int32_t* go_sim_reuse(const go_sim* s) { return s->reuse; }
+int64_t go_sim_batch(const go_sim* s) { return s->t; }
+int32_t go_sim_window_count(const go_sim* s) { return s->win_count; }

@@ -1,0 +1,397 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix.
+
+Each test checks the oracle against something other than itself: the plain
+definition of a gather, a set-based dedup, an independently written textbook
+LRU, brute force over the future ID lists, closed forms, a hand-traced table,
+and the numbers of the paper's worked examples."""
+from collections import OrderedDict
+
+import numpy as np
+import pytest
+
+import os
+
+GOLDEN = {}
+with open(os.path.join(os.path.dirname(__file__), "golden", "paper_values.txt")) as fh:
+    for line in fh:
+        if line.strip() and not line.startswith("#"):
+            k, v = line.split("#")[0].split("=")
+            GOLDEN[k.strip()] = float(v)
+
+
+# ------------------------------------------------------------------ helpers
+
+def tiny_setup(oracle, n=400, dim=8, lines=32, ways=4, window=2, n_hot=10, seed=3, store=True):
+    rng = np.random.default_rng(seed)
+    feats = rng.standard_normal((n, dim)).astype(np.float32)
+    sim = oracle.Sim(n, lines, ways, window, dim * 4, dim * 4, feats if store else None)
+    hot = rng.choice(n, size=n_hot, replace=False).astype(np.int64)
+    if n_hot:
+        sim.set_hot(hot)
+    return rng, feats, sim, hot
+
+
+def run_stream(sim, batches, window):
+    """Push `window` + 1 lists ahead, gather in order; returns per-batch results."""
+    res = []
+    pushed = 0
+    for t in range(len(batches)):
+        while window and pushed < len(batches) and pushed <= t + window:
+            sim.push(batches[pushed])
+            pushed += 1
+        res.append(sim.gather(batches[t], want_cls=True))
+    return res
+
+
+def zipf_batches(rng, n, n_batches, size, a=1.3):
+    out = []
+    for _ in range(n_batches):
+        out.append(np.minimum(rng.zipf(a, size=size) - 1, n - 1).astype(np.int64))
+    return out
+
+
+# ------------------------------------------------- the plain definitions
+
+def test_sort_unique_vs_set(oracle_mod):
+    rng = np.random.default_rng(0)
+    for n in (0, 1, 2, 17, 1000):
+        raw = rng.integers(0, 50, size=n)
+        want = np.array(sorted(set(raw.tolist())), dtype=np.int64)
+        np.testing.assert_array_equal(oracle_mod.sort_unique(raw), want)
+
+
+@pytest.mark.parametrize("window", [0, 3])
+def test_rows_equal_store_rows_brute_force(oracle_mod, window):
+    """Section 2.2.3: the gather returns, for every distinct ID, that node's feature row."""
+    rng, feats, sim, hot = tiny_setup(oracle_mod, window=window)
+    batches = zipf_batches(rng, 400, 25, 120)
+    for (uniq, rows, stats, cls), raw in zip(run_stream(sim, batches, window), batches):
+        want_ids = sorted(set(raw.tolist()))
+        assert uniq.tolist() == want_ids
+        for j, v in enumerate(want_ids):                   # row by row, the definition itself
+            assert rows[j].tobytes() == feats[v].tobytes()
+        assert stats[0] == len(want_ids)
+        assert stats[1] + stats[2] + stats[3] == stats[0]  # hits + CPU-buffer hits + misses = unique IDs
+        assert stats[4] <= stats[3]
+        assert np.sum(cls == oracle_mod.CLS_HIT) == stats[1]
+        assert np.sum(cls == oracle_mod.CLS_CPU) == stats[2]
+        assert np.sum((cls == oracle_mod.CLS_MISS) | (cls == oracle_mod.CLS_BYPASS)) == stats[3]
+        assert np.sum(cls == oracle_mod.CLS_BYPASS) == stats[4]
+
+
+def test_cpu_buffer_hits_closed_form(oracle_mod):
+    """Section 3.3: an ID pinned in the CPU buffer is always served from it, whatever the cache holds."""
+    rng, feats, sim, hot = tiny_setup(oracle_mod, n_hot=40, window=2)
+    batches = zipf_batches(rng, 400, 20, 150)
+    hotset = set(hot.tolist())
+    for (uniq, rows, stats, cls), raw in zip(run_stream(sim, batches, 2), batches):
+        assert stats[2] == len(set(raw.tolist()) & hotset)
+        assert all((c == oracle_mod.CLS_CPU) == (v in hotset) for v, c in zip(uniq.tolist(), cls.tolist()))
+    assert not (set(sim.tags.tolist()) & hotset)           # hot rows never enter the GPU cache
+
+
+def test_permutation_and_duplication_invariance(oracle_mod):
+    rng = np.random.default_rng(5)
+    batches = zipf_batches(rng, 300, 12, 90)
+    runs = []
+    for variant in range(3):
+        sim = oracle_mod.Sim(300, 24, 4, 2)
+        sim.set_hot(np.arange(0, 300, 37))
+        bs = []
+        for b in batches:
+            if variant == 1:
+                b = rng.permutation(b)
+            elif variant == 2:
+                b = np.concatenate([b, b[::3], b[:5]])
+            bs.append(b)
+        runs.append([(u.tolist(), s.tolist(), c.tolist()) for u, _, s, c in run_stream(sim, bs, 2)])
+    assert runs[0] == runs[1] == runs[2]
+
+
+# ------------------------------------------------------ cache >= store
+
+@pytest.mark.parametrize("window", [0, 4])
+def test_cache_as_large_as_store_misses_only_first_touch(oracle_mod, window):
+    n, ways = 240, 4
+    n_sets = 60                                            # ceil(n / n_sets) = 4 = ways: modulo sets never overflow
+    sim = oracle_mod.Sim(n, n_sets * ways, ways, window)
+    rng = np.random.default_rng(1)
+    batches = [rng.integers(0, n, size=70) for _ in range(40)]
+    seen = set()
+    total_miss = 0
+    for (uniq, _, stats, cls), raw in zip(run_stream(sim, batches, window), batches):
+        first = set(uniq.tolist()) - seen
+        assert stats[3] == len(first) and stats[4] == 0    # a miss only on a node's first touch, never a bypass
+        assert stats[1] == len(uniq) - len(first)
+        seen |= first
+        total_miss += stats[3]
+    assert total_miss == len(seen)
+    assert sorted(t for t in sim.tags.tolist() if t >= 0) == sorted(seen)
+
+
+# ---------------------------------------------- window depth 0 == LRU
+
+def test_depth0_single_id_batches_is_textbook_lru(oracle_mod):
+    """With one ID per minibatch, least-recently-used-by-batch is exactly LRU."""
+    n, n_sets, ways = 200, 4, 3
+    sim = oracle_mod.Sim(n, n_sets * ways, ways, 0)
+    lru = [OrderedDict() for _ in range(n_sets)]
+    rng = np.random.default_rng(2)
+    for v in np.minimum(rng.zipf(1.2, size=3000) - 1, n - 1):
+        _, _, stats, _ = sim.gather(np.array([v]), want_cls=True)
+        d = lru[v % n_sets]
+        if v in d:
+            d.move_to_end(v)
+            want_hit = 1
+        else:
+            if len(d) == ways:
+                d.popitem(last=False)
+            d[v] = True
+            want_hit = 0
+        assert stats[1] == want_hit and stats[3] == 1 - want_hit
+    for s in range(n_sets):
+        assert set(sim.tags[s * ways:(s + 1) * ways].tolist()) - {-1} == set(int(k) for k in lru[s])
+
+
+class BatchLRU:
+    """Independent model of LRU-by-batch for multi-ID minibatches: per set a
+    list of resident IDs ordered from least to most recently used, where all
+    IDs touched by one minibatch count as used at the same time and ties are
+    ordered by way index; IDs touched in the current minibatch are not victims."""
+
+    def __init__(self, n_sets, ways):
+        self.n_sets, self.ways = n_sets, ways
+        self.way_of = [dict() for _ in range(n_sets)]       # id -> way
+        self.last = [dict() for _ in range(n_sets)]         # id -> last batch
+        self.t = 0
+
+    def gather(self, ids):
+        hits = misses = bypass = 0
+        ids = sorted(set(ids))
+        missing = {}
+        for v in ids:
+            s = v % self.n_sets
+            if v in self.way_of[s]:
+                hits += 1
+                self.last[s][v] = self.t
+            else:
+                missing.setdefault(s, []).append(v)
+        for s, vs in missing.items():
+            free = [w for w in range(self.ways) if w not in self.way_of[s].values()]
+            old = sorted((self.last[s][v], self.way_of[s][v], v) for v in self.way_of[s] if self.last[s][v] != self.t)
+            victims = [(w, None) for w in free] + [(w, v) for _, w, v in old]
+            for k, v in enumerate(vs):
+                misses += 1
+                if k < len(victims):
+                    w, gone = victims[k]
+                    if gone is not None:
+                        del self.way_of[s][gone], self.last[s][gone]
+                    self.way_of[s][v] = w
+                    self.last[s][v] = self.t
+                else:
+                    bypass += 1
+        self.t += 1
+        return len(ids), hits, misses, bypass
+
+
+def test_depth0_multi_id_batches_vs_independent_model(oracle_mod):
+    n, n_sets, ways = 500, 8, 4
+    sim = oracle_mod.Sim(n, n_sets * ways, ways, 0)
+    model = BatchLRU(n_sets, ways)
+    rng = np.random.default_rng(4)
+    for raw in zipf_batches(rng, n, 60, 40, a=1.15):
+        _, _, stats, _ = sim.gather(raw, want_cls=True)
+        u, h, m, b = model.gather(raw.tolist())
+        assert (stats[0], stats[1], stats[3], stats[4]) == (u, h, m, b)
+    for s in range(n_sets):
+        for v, w in model.way_of[s].items():
+            assert sim.tags[s * ways + w] == v
+
+
+# ------------------------------------------------------------- window
+
+def test_window_never_evicts_a_line_with_a_buffered_future_use(oracle_mod):
+    """Section 3.4: a cached node that one of the buffered future minibatches
+    reuses stays in the 'USE' state and is not evicted."""
+    n, lines, ways, window = 300, 32, 4, 3
+    rng = np.random.default_rng(9)
+    batches = zipf_batches(rng, n, 50, 60, a=1.2)
+    usets = [set(b.tolist()) for b in batches]
+    sim = oracle_mod.Sim(n, lines, ways, window)
+    pushed, evicted_any = 0, 0
+    for t in range(len(batches)):
+        while pushed < len(batches) and pushed <= t + window:
+            sim.push(batches[pushed])
+            pushed += 1
+        before = set(sim.tags.tolist()) - {-1}
+        sim.gather(batches[t], want_rows=False)
+        after = set(sim.tags.tolist()) - {-1}
+        future = set().union(*usets[t + 1:t + 1 + window]) if t + 1 < len(batches) else set()
+        gone = before - after
+        evicted_any += len(gone)
+        assert not (gone & future), (t, gone & future)
+        assert not (gone & usets[t])                        # nor a line used by this very minibatch
+        # the per-node counter is the number of buffered future minibatches that contain the node
+        reuse = sim.reuse
+        for v in range(n):
+            assert reuse[v] == sum(v in u for u in usets[t + 1:pushed])
+    assert evicted_any > 0
+
+
+def test_window_raises_hit_count_on_a_cyclic_stream(oracle_mod):
+    """A stream that cycles through more lines than one set holds thrashes LRU
+    completely; with look-ahead the lines reused soonest are kept."""
+    n, ways = 64, 4
+    cycle = [np.array([v]) for v in range(0, 6)] * 12       # 6 IDs, one set of 4 ways
+    hits = {}
+    for window in (0, 4):
+        sim = oracle_mod.Sim(n, ways, ways, window)
+        hits[window] = sum(int(r[2][1]) for r in run_stream(sim, cycle, window))
+    assert hits[0] == 0
+    assert hits[4] > 20
+
+
+# -------------------------------------------------- hand-traced table
+
+def test_hand_traced_fully_associative_case(oracle_mod):
+    """One set of four ways, look-ahead of two minibatches, node 7 in the CPU
+    buffer; expected tags / stamps / counts worked out by hand from the rules:
+    classify against the state at the start, USE lines (future count > 0) and
+    lines touched in this minibatch are not victims, victims in (stamp, way)
+    order go to the misses in ascending ID order, the rest bypass."""
+    sim = oracle_mod.Sim(50, 4, 4, 2)
+    sim.set_hot(np.array([7]))
+    B = [[3, 1, 2, 7, 1], [5, 2, 4], [9, 8, 6, 1], [10, 3, 2, 2], [11, 1], [13, 12]]
+    trace = []
+
+    def g(i):
+        _, _, st, _ = sim.gather(np.array(B[i]), want_cls=True)
+        trace.append((st.tolist(), sim.tags.tolist(), sim.stamps.tolist()))
+
+    for i in (0, 1, 2):
+        sim.push(np.array(B[i]))
+    g(0); sim.push(np.array(B[3]))
+    g(1); sim.push(np.array(B[4]))
+    g(2); sim.push(np.array(B[5]))
+    g(3); g(4); g(5)
+    want = [
+        ([4, 0, 1, 3, 0], [1, 2, 3, -1], [0, 0, 0, -1]),
+        ([3, 1, 0, 2, 1], [1, 2, 3, 4], [0, 1, 0, 1]),      # 1 and 3 are USE, 5 bypasses
+        ([4, 1, 0, 3, 2], [1, 2, 3, 6], [2, 1, 0, 2]),      # only way 3 (node 4) is safe to evict
+        ([3, 2, 0, 1, 0], [1, 2, 3, 10], [2, 3, 3, 3]),
+        ([2, 1, 0, 1, 0], [1, 11, 3, 10], [4, 4, 3, 3]),    # three ways tie on stamp 3: lowest way goes
+        ([2, 0, 0, 2, 0], [1, 11, 12, 13], [4, 4, 5, 5]),   # oldest stamps first
+    ]
+    assert trace == want
+
+
+# --------------------------------------------------------------- errors
+
+def test_protocol_errors(oracle_mod):
+    sim = oracle_mod.Sim(20, 4, 2, 1)
+    with pytest.raises(oracle_mod.OracleError) as e:
+        sim.gather(np.array([1]))
+    assert e.value.code == oracle_mod.E_ORDER                # nothing buffered
+    sim.push(np.array([1, 2]))
+    sim.push(np.array([3]))
+    with pytest.raises(oracle_mod.OracleError) as e:
+        sim.push(np.array([4]))
+    assert e.value.code == oracle_mod.E_FULL                 # current + 1 future already buffered
+    with pytest.raises(oracle_mod.OracleError) as e:
+        sim.gather(np.array([3]))
+    assert e.value.code == oracle_mod.E_ORDER                # not the head
+    with pytest.raises(oracle_mod.OracleError) as e:
+        sim.gather(np.array([1, 20]))
+    assert e.value.code == oracle_mod.E_RANGE
+    assert sim.batch == 0 and sim.window_count == 2          # failed calls leave the state alone
+    sim.gather(np.array([2, 1, 1]))
+    assert sim.batch == 1
+    with pytest.raises(oracle_mod.OracleError):
+        oracle_mod.Sim(20, 5, 2, 0)                          # lines not a multiple of ways
+    with pytest.raises(oracle_mod.OracleError):
+        oracle_mod.Sim(20, 4, 2, 0).push(np.array([1]))      # depth 0 takes no pushes
+
+
+# -------------------------------------------------------------- sampler
+
+def _tree(first_hop_degree):
+    """node 0 -> 1..5; node i in 1..5 -> `first_hop_degree` leaves of its own."""
+    indptr, indices, nxt = [0], [], 6
+    indices += [1, 2, 3, 4, 5]
+    indptr.append(len(indices))
+    for _ in range(1, 6):
+        indices += list(range(nxt, nxt + first_hop_degree))
+        nxt += first_hop_degree
+        indptr.append(len(indices))
+    while len(indptr) < nxt + 1:
+        indptr.append(len(indices))
+    return nxt, np.array(indptr), np.array(indices)
+
+
+def test_sampler_worked_example(oracle_mod):
+    """Section 2.2.2: fanout 3, two layers, one target node: 1 + 3 + 6 = 10
+    vertices and 9 edges when the first-hop nodes have two neighbours each
+    ('up to three'), and at most 1 + 3 + 9."""
+    n, indptr, indices = _tree(2)
+    g = oracle_mod.Graph(0, n, csr=(indptr, indices))
+    g13 = oracle_mod.Graph(0, *(_tree(4)[:1]), csr=_tree(4)[1:])
+    # the single seed is hashed over all nodes: keep the minibatches whose seed is the tree's root
+    hits = 0
+    for batch in range(400):
+        raw = g.sample(11, batch, [3, 3], 1)
+        if raw[0] != 0:
+            continue
+        hits += 1
+        assert len(set(raw.tolist())) == GOLDEN["sampling_example_vertices"]
+        assert len(raw) - 1 == GOLDEN["sampling_example_edges"]
+        first = raw[1:4].tolist()
+        assert len(set(first)) == 3 and set(first) <= {1, 2, 3, 4, 5}
+        for v in first:                                              # degree <= fanout: all neighbours
+            assert set(indices[indptr[v]:indptr[v + 1]].tolist()) <= set(raw[4:].tolist())
+        raw13 = g13.sample(11, batch, [3, 3], 1)
+        if raw13[0] == 0:
+            assert len(raw13) == 13 and len(set(raw13.tolist())) == 13   # the bound 1 + 3 + 9
+    assert hits > 0
+
+
+def test_sampler_is_uniform_without_replacement(oracle_mod):
+    deg, f = 12, 5
+    indptr = np.array([0, deg] + [deg] * deg)
+    indices = np.arange(1, deg + 1)
+    g = oracle_mod.Graph(0, deg + 1, csr=(indptr, indices))
+    counts = np.zeros(deg + 1)
+    pair = np.zeros((deg + 1, deg + 1))
+    trials = 0
+    for batch in range(60000):
+        raw = g.sample(99, batch, [f], 1)
+        if raw[0] != 0:
+            continue
+        trials += 1
+        nb = raw[1:]
+        assert len(nb) == f and len(set(nb.tolist())) == f          # distinct slots
+        counts[nb] += 1
+        pair[np.ix_(nb, nb)] += 1
+    assert trials > 3000
+    p = f / deg
+    sigma = np.sqrt(trials * p * (1 - p))
+    assert np.all(np.abs(counts[1:] - trials * p) < 5 * sigma)      # every slot equally likely
+    p2 = f * (f - 1) / (deg * (deg - 1))                             # every pair equally likely
+    off = pair[1:, 1:][~np.eye(deg, dtype=bool)]
+    assert np.all(np.abs(off - trials * p2) < 5 * np.sqrt(trials * p2))
+
+
+# ------------------------------------------------------------- Eq. 2-3
+
+def test_overlapped_access_model(oracle_mod):
+    """Section 3.2 Eq. 2-3 and the Section 4.2 example: Optane, 1.5 M IOPS at
+    4 KB, 25 us initial + 5 us termination latency, 95 % of peak.  The paper
+    prints 812 accesses; its text does not say which latency terms entered, and
+    the formula with the stated 25 + 5 us gives 855 (5 % apart)."""
+    iops, ti, tt, r = GOLDEN["optane_peak_iops"], GOLDEN["initial_latency_s"], GOLDEN["termination_latency_s"], 0.95
+    n = oracle_mod.accum_threshold(iops, ti, tt, r, 1)
+    assert abs(n - 855.0) < 1e-6
+    assert abs(n - GOLDEN["optane_95pct_accesses"]) / GOLDEN["optane_95pct_accesses"] < 0.06
+    # the defining fixed point: N = IOPS_achieved * (Ti + N / IOPS_peak + Tt)
+    assert abs(n - r * iops * (ti + n / iops + tt)) < 1e-6
+    # SSDs add up: twice the drives need twice the accesses in flight
+    assert abs(oracle_mod.accum_threshold(iops, ti, tt, r, 2) - 2 * n) < 1e-6
