@@ -1,0 +1,171 @@
+/* gids.h - C ABI of the MI355X minibatch feature-gather library (libgids.so).
+ *
+ * The library implements the feature-aggregation ("gather") stage of a GNN
+ * dataloader as the GIDS paper (arxiv 2306.16384) poses it: the node IDs a
+ * neighbourhood sampler produced for one minibatch are deduplicated, and the
+ * feature row of every distinct ID is fetched into a minibatch buffer in GPU
+ * memory (Section 2.2.3), looking first in a set-associative software cache in
+ * GPU memory whose eviction is steered by a window of future minibatches
+ * (Section 3.4), then in a constant buffer of hot rows pinned in CPU memory
+ * (Section 3.3), then in the backing feature store.  The backing store here is
+ * a host-pinned buffer that kernels read zero-copy over the host link; it
+ * stands in for the paper's SSDs.  Fills from the store can be batched across
+ * minibatches by an accumulator (Section 3.2).
+ *
+ * Conventions
+ *   - Every function returns 0 (GIDS_OK) or a negative GIDS_E_* code;
+ *     gids_last_error() returns a thread-local text for the last failure.
+ *   - Handles are opaque and owned by the library.  Every buffer named in an
+ *     argument is owned by the caller.  "dev" = device (HBM) pointer, "host" =
+ *     ordinary host pointer unless stated otherwise.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls that take a stream only enqueue work on it and return; they never
+ *     block on the device unless an internal buffer has to grow (avoid that
+ *     with gids_cache_reserve).  All calls on one cache must use one stream,
+ *     or streams the caller orders.
+ *   - IDs are signed integers of the width fixed at store creation (4 or 8
+ *     bytes), valid range [0, n_rows).
+ *   - Errors found by the device (an ID out of range, a gather that does not
+ *     match the buffered window head, an output buffer too small) cannot be
+ *     returned by the enqueueing call.  The failing operation changes nothing,
+ *     the error is recorded in that minibatch's gids_stats.status, and it is
+ *     sticky: once the host has seen it (gids_stats_read, gids_flush) every
+ *     later call on the cache returns it.
+ */
+#ifndef GIDS_H
+#define GIDS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GIDS_OK 0
+#define GIDS_E_INVAL (-1) /* bad argument or call out of protocol            */
+#define GIDS_E_NOMEM (-2) /* host or device allocation failed                */
+#define GIDS_E_RANGE (-3) /* a node ID outside [0, n_rows)                   */
+#define GIDS_E_ORDER (-4) /* gather does not match the head of the window    */
+#define GIDS_E_FULL (-5)  /* window already holds window_depth + 1 lists     */
+#define GIDS_E_HIP (-6)   /* HIP runtime error, text in gids_last_error()    */
+#define GIDS_E_SPACE (-7) /* caller's output buffer has too few rows         */
+
+typedef struct gids_store gids_store;
+typedef struct gids_cache gids_cache;
+
+/* Per-minibatch counters (the paper's reported quantity is the hit ratio,
+ * Section 4.5).  n_hit + n_cpu_hit + n_miss == n_unique.  n_bypass (a subset of
+ * n_miss) counts misses that found no evictable line and were served from the
+ * store without being installed.  n_pending = fills still queued in the
+ * accumulator when the gather's kernels ended; `flushed` is 1 when every row
+ * of this minibatch's output was written by the end of the gather call's own
+ * work on the stream, 0 when some await a later flush. */
+typedef struct gids_stats {
+    uint64_t seq;       /* 0-based index of the gather call on this cache */
+    uint64_t n_unique;
+    uint64_t n_hit;
+    uint64_t n_cpu_hit;
+    uint64_t n_miss;
+    uint64_t n_bypass;
+    uint64_t n_pending;
+    int32_t flushed;
+    int32_t status;     /* GIDS_OK or the GIDS_E_* the device found */
+} gids_stats;
+
+/* The feature table (Section 2.1: an N x D matrix, one row per node).
+ * n_rows x row_bytes bytes in pinned host memory that the GPU reads zero-copy.
+ * row_bytes must be a multiple of 16.  id_bytes is 4 or 8.
+ * host_ptr_or_null: NULL - the library allocates pinned memory (free with
+ * gids_store_destroy; fill it through gids_store_host_ptr before the first
+ * gather); otherwise memory the caller already allocated with hipHostMalloc
+ * (e.g. a pinned torch tensor) holding the table, which must outlive the store.
+ * Ordinary pageable memory is rejected with GIDS_E_HIP. */
+int gids_store_create(uint64_t n_rows, uint32_t row_bytes, uint32_t id_bytes, void* host_ptr_or_null,
+                      gids_store** out);
+void* gids_store_host_ptr(gids_store* store);
+int gids_store_destroy(gids_store* store);
+
+/* The GPU software cache over a store (Section 3.4) plus its window buffer
+ * and fill accumulator (Section 3.2).
+ *   lines          cache lines, a multiple of `ways`; one node row per line
+ *   ways           associativity, a power of two in [1, 64]; set = id mod (lines / ways)
+ *   line_bytes     slot stride in HBM, >= row_bytes, multiple of 16
+ *   window_depth   W in [0, 254]: how many minibatches beyond the one being
+ *                  gathered are buffered.  A cached row that one of them reuses
+ *                  is not evicted.  W = 0: no window, plain LRU by minibatch.
+ *   accum_threshold  0: every gather moves its own rows before it ends.
+ *                  > 0: rows that must cross the host link are queued and moved
+ *                  once at least this many are pending (or at gids_flush); the
+ *                  counters and the final contents of every output are the same
+ *                  for any threshold.
+ * Device memory taken: lines * line_bytes for the data plus about
+ * 12-16 bytes per line, n_rows / 8 * 3 bytes of bitmaps and n_rows bytes of
+ * reuse counters. */
+int gids_cache_create(gids_store* store, uint64_t lines, uint32_t ways, uint32_t line_bytes,
+                      uint32_t window_depth, uint64_t accum_threshold, gids_cache** out);
+int gids_cache_destroy(gids_cache* cache);
+
+/* Pre-size the internal per-minibatch buffers for ID lists of up to
+ * max_ids_per_minibatch entries, so that no later call allocates. */
+int gids_cache_reserve(gids_cache* cache, uint64_t max_ids_per_minibatch);
+
+/* Constant CPU buffer (Section 3.3): copy the rows of `ids_host` (n distinct
+ * IDs, any order) from the store into a second pinned host buffer.  From then
+ * on these IDs are served from it and never enter the GPU cache.  Call once,
+ * before the first push or gather. */
+int gids_cpu_buffer_pin(gids_cache* cache, const void* ids_host, uint64_t n);
+
+/* Window buffer (Section 3.4, Fig. 6 steps 1-4): append the raw ID list
+ * (duplicates allowed) of a future minibatch.  Lists are gathered in push
+ * order.  GIDS_E_FULL when window_depth + 1 lists are already buffered;
+ * GIDS_E_INVAL when window_depth == 0. */
+int gids_window_push(gids_cache* cache, const void* ids_dev, uint64_t n, void* stream);
+
+/* Gather one minibatch.
+ *   ids_dev, n       the raw ID list.  With window_depth > 0 it must have the
+ *                    same distinct IDs as the oldest buffered list (else
+ *                    GIDS_E_ORDER in stats), or be NULL (n ignored) to gather
+ *                    that list as it was pushed.
+ *   out_dev          receives row j = feature row of the j-th smallest distinct
+ *                    ID, rows packed at row_bytes; out_capacity_rows rows are
+ *                    available (GIDS_E_SPACE in stats when there are more
+ *                    distinct IDs; n rows always suffice)
+ *   unique_dev       NULL, or room for min(n, out_capacity_rows)... at least as
+ *                    many IDs as there are distinct ones (n always suffices):
+ *                    receives them ascending
+ *   inverse_dev      NULL, or n uint32: inverse_dev[i] = j with
+ *                    unique[j] == ids_dev[i] (requires ids_dev)
+ * With accum_threshold > 0 the output buffers of gathers not yet flushed must
+ * stay untouched until they are (stats.flushed / gids_flush). */
+int gids_gather(gids_cache* cache, const void* ids_dev, uint64_t n, void* out_dev, uint64_t out_capacity_rows,
+                void* unique_dev, void* inverse_dev, void* stream);
+
+/* Move every queued row now.  After the stream reaches the end of this call's
+ * work the output of every earlier gather is complete.  Does not block. */
+int gids_flush(gids_cache* cache, void* stream);
+
+/* Wait for gather number `seq` (0-based) to finish on the device and return
+ * its counters.  Only the most recent 64 gathers are kept.  Returns
+ * stats->status. */
+int gids_stats_read(gids_cache* cache, uint64_t seq, gids_stats* stats);
+
+/* Number of gathers enqueued so far (the next gather's seq). */
+uint64_t gids_cache_gathers(const gids_cache* cache);
+
+/* Inspection for tests and tools: blocks until the stream is idle, then copies
+ * the tag (int64, -1 = empty) and last-use stamp (int64, -1 = never) of every
+ * line to host arrays of `lines` entries each.  Either may be NULL. */
+int gids_cache_snapshot(gids_cache* cache, int64_t* tags_host, int64_t* stamps_host);
+
+/* Number of in-flight fills an accumulator needs so that a storage device of
+ * `iops_peak` requests/s per device sustains `ratio` of its peak, given the
+ * latency of the initial and termination phases in seconds (Section 3.2,
+ * Eq. 2-3).  Pure host arithmetic; a helper for choosing accum_threshold. */
+double gids_accum_threshold(double iops_peak, double t_initial, double t_termination, double ratio, int n_ssd);
+
+const char* gids_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GIDS_H */

@@ -1,0 +1,143 @@
+"""ctypes binding of libgids.so: the C ABI of include/gids.h under the same
+names, argument marshalling only.  Every step of the gather runs in the HIP
+kernels of the library; there is no fallback, a missing library is an error."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgids.so")
+
+GIDS_OK = 0
+GIDS_E_INVAL, GIDS_E_NOMEM, GIDS_E_RANGE, GIDS_E_ORDER, GIDS_E_FULL, GIDS_E_HIP, GIDS_E_SPACE = -1, -2, -3, -4, -5, -6, -7
+
+EXPORTS = [
+    "gids_store_create", "gids_store_host_ptr", "gids_store_destroy", "gids_cache_create", "gids_cache_destroy",
+    "gids_cache_reserve", "gids_cpu_buffer_pin", "gids_window_push", "gids_gather", "gids_flush", "gids_stats_read",
+    "gids_cache_gathers", "gids_cache_snapshot", "gids_accum_threshold", "gids_last_error",
+]
+
+
+class gids_stats(C.Structure):
+    _fields_ = [("seq", C.c_uint64), ("n_unique", C.c_uint64), ("n_hit", C.c_uint64), ("n_cpu_hit", C.c_uint64),
+                ("n_miss", C.c_uint64), ("n_bypass", C.c_uint64), ("n_pending", C.c_uint64),
+                ("flushed", C.c_int32), ("status", C.c_int32)]
+
+    def as_tuple(self):
+        """(n_unique, hits, CPU-buffer hits, misses, bypasses)"""
+        return (self.n_unique, self.n_hit, self.n_cpu_hit, self.n_miss, self.n_bypass)
+
+
+class GidsError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"gids error {code}: {text}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2306_16384_amd.build` "
+                               "(there is no CPU fallback)")
+        L = C.CDLL(LIB_PATH)
+        vp, u64, u32 = C.c_void_p, C.c_uint64, C.c_uint32
+        L.gids_store_create.argtypes = [u64, u32, u32, vp, C.POINTER(vp)]
+        L.gids_store_host_ptr.restype = vp
+        L.gids_store_host_ptr.argtypes = [vp]
+        L.gids_store_destroy.argtypes = [vp]
+        L.gids_cache_create.argtypes = [vp, u64, u32, u32, u32, u64, C.POINTER(vp)]
+        L.gids_cache_destroy.argtypes = [vp]
+        L.gids_cache_reserve.argtypes = [vp, u64]
+        L.gids_cpu_buffer_pin.argtypes = [vp, vp, u64]
+        L.gids_window_push.argtypes = [vp, vp, u64, vp]
+        L.gids_gather.argtypes = [vp, vp, u64, vp, u64, vp, vp, vp]
+        L.gids_flush.argtypes = [vp, vp]
+        L.gids_stats_read.argtypes = [vp, u64, C.POINTER(gids_stats)]
+        L.gids_cache_gathers.restype = u64
+        L.gids_cache_gathers.argtypes = [vp]
+        L.gids_cache_snapshot.argtypes = [vp, vp, vp]
+        L.gids_accum_threshold.restype = C.c_double
+        L.gids_accum_threshold.argtypes = [C.c_double, C.c_double, C.c_double, C.c_double, C.c_int]
+        L.gids_last_error.restype = C.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != GIDS_OK:
+        raise GidsError(rc, lib().gids_last_error().decode())
+
+
+def gids_store_create(n_rows: int, row_bytes: int, id_bytes: int, host_ptr: int | None = None) -> int:
+    h = C.c_void_p()
+    _check(lib().gids_store_create(n_rows, row_bytes, id_bytes, host_ptr, C.byref(h)))
+    return h.value
+
+
+def gids_store_host_ptr(store: int) -> int:
+    return lib().gids_store_host_ptr(store)
+
+
+def gids_store_destroy(store: int) -> None:
+    _check(lib().gids_store_destroy(store))
+
+
+def gids_cache_create(store: int, lines: int, ways: int, line_bytes: int, window_depth: int = 0,
+                      accum_threshold: int = 0) -> int:
+    h = C.c_void_p()
+    _check(lib().gids_cache_create(store, lines, ways, line_bytes, window_depth, accum_threshold, C.byref(h)))
+    return h.value
+
+
+def gids_cache_destroy(cache: int) -> None:
+    _check(lib().gids_cache_destroy(cache))
+
+
+def gids_cache_reserve(cache: int, max_ids: int) -> None:
+    _check(lib().gids_cache_reserve(cache, max_ids))
+
+
+def gids_cpu_buffer_pin(cache: int, ids_host_ptr: int, n: int) -> None:
+    _check(lib().gids_cpu_buffer_pin(cache, ids_host_ptr, n))
+
+
+def gids_window_push(cache: int, ids_dev_ptr: int, n: int, stream: int = 0) -> None:
+    _check(lib().gids_window_push(cache, ids_dev_ptr, n, stream))
+
+
+def gids_gather(cache: int, ids_dev_ptr: int | None, n: int, out_dev_ptr: int, out_capacity_rows: int,
+                unique_dev_ptr: int | None = None, inverse_dev_ptr: int | None = None, stream: int = 0) -> None:
+    _check(lib().gids_gather(cache, ids_dev_ptr, n, out_dev_ptr, out_capacity_rows, unique_dev_ptr, inverse_dev_ptr,
+                             stream))
+
+
+def gids_flush(cache: int, stream: int = 0) -> None:
+    _check(lib().gids_flush(cache, stream))
+
+
+def gids_stats_read(cache: int, seq: int) -> gids_stats:
+    st = gids_stats()
+    _check(lib().gids_stats_read(cache, seq, C.byref(st)))
+    return st
+
+
+def gids_cache_gathers(cache: int) -> int:
+    return int(lib().gids_cache_gathers(cache))
+
+
+def gids_cache_snapshot(cache: int, tags_host_ptr: int | None, stamps_host_ptr: int | None) -> None:
+    _check(lib().gids_cache_snapshot(cache, tags_host_ptr, stamps_host_ptr))
+
+
+def gids_accum_threshold(iops_peak: float, t_initial: float, t_termination: float, ratio: float, n_ssd: int = 1) -> float:
+    return float(lib().gids_accum_threshold(iops_peak, t_initial, t_termination, ratio, n_ssd))
+
+
+def gids_last_error() -> str:
+    return lib().gids_last_error().decode()

@@ -1,0 +1,542 @@
+// The C ABI of libgids.so (declared in include/gids.h): argument checks, buffer
+// ownership, the window FIFO and the order in which the kernels of one push or
+// gather are enqueued.  No step of the gather itself runs on the host.
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <thread>
+#include <vector>
+
+#include "../../include/gids.h"
+#include "gids_dev.h"
+
+namespace gids {
+uint32_t scan_blocks(uint64_t n_words);
+}
+
+using namespace gids;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                           \
+    do {                                                                                        \
+        hipError_t e_ = (expr);                                                                 \
+        if (e_ != hipSuccess) {                                                                 \
+            (void)hipGetLastError();                                                            \
+            return fail(e_ == hipErrorOutOfMemory ? GIDS_E_NOMEM : GIDS_E_HIP, "%s: %s", #expr, \
+                        hipGetErrorString(e_));                                                 \
+        }                                                                                       \
+    } while (0)
+
+constexpr int STATS_RING = 64;
+
+template <typename T>
+int dev_alloc(T** p, uint64_t count) {
+    *p = nullptr;
+    if (count == 0) count = 1;
+    HIP_TRY(hipMalloc(reinterpret_cast<void**>(p), count * sizeof(T)));
+    return GIDS_OK;
+}
+
+template <typename T>
+void dev_free(T*& p) {
+    if (p) (void)hipFree(p);
+    p = nullptr;
+}
+
+}  // namespace
+
+struct gids_store {
+    uint64_t n_rows = 0;
+    uint32_t row_bytes = 0, id_bytes = 0;
+    void* host = nullptr;   // host address of the table
+    void* dev = nullptr;    // the same memory as the GPU sees it
+    bool owned = false;
+};
+
+struct WindowSlot {
+    void* ids = nullptr;    // distinct IDs, ascending (device)
+    uint64_t cap = 0;       // entries allocated
+    uint64_t n_raw = 0;     // length of the raw list that was pushed (bounds the distinct count)
+};
+
+struct gids_cache {
+    virtual ~gids_cache() {}
+    virtual int init() = 0;
+    virtual int reserve(uint64_t n) = 0;
+    virtual int pin(const void* ids_host, uint64_t n) = 0;
+    virtual int push(const void* ids, uint64_t n, hipStream_t s) = 0;
+    virtual int gather(const void* ids, uint64_t n, void* out, uint64_t out_cap, void* unique, void* inverse,
+                       hipStream_t s) = 0;
+    virtual int flush(hipStream_t s) = 0;
+    virtual int snapshot(int64_t* tags, int64_t* stamps) = 0;
+
+    gids_store* store = nullptr;
+    uint64_t lines = 0, n_sets = 0, threshold = 0, n_words = 0;
+    uint32_t ways = 0, lg_ways = 0, line_bytes = 0, window = 0, words_per_set = 0;
+    int sticky = GIDS_OK;
+    uint64_t seq = 0;
+    StatsRec* ring_host = nullptr;
+    StatsRec* ring_dev = nullptr;
+    hipEvent_t events[STATS_RING] = {};
+    hipStream_t last_stream = nullptr;
+    int move_blocks = 2048;
+};
+
+namespace {
+
+template <typename IdT>
+struct CacheT final : gids_cache {
+    // device state
+    IdT* tags = nullptr;
+    int32_t* stamps = nullptr;
+    uint32_t* pending = nullptr;
+    uint8_t* reuse = nullptr;
+    uint64_t* missmask = nullptr;
+    uint64_t* bitmap = nullptr;
+    uint32_t* wrank = nullptr;
+    uint64_t* hotbits = nullptr;
+    uint32_t* hotrank = nullptr;
+    char* cache_data = nullptr;
+    Ctl* ctl = nullptr;
+    uint32_t* blocksum = nullptr;
+    uint32_t* blockoff = nullptr;
+    // per-minibatch scratch, sized for the longest raw list seen
+    uint64_t cap_n = 0;
+    IdT* ubuf = nullptr;
+    uint64_t* plan = nullptr;
+    uint32_t* misslist = nullptr;
+    // accumulator queues
+    uint64_t queue_cap = 0;
+    FillOp* fills = nullptr;
+    CopyOp* copies = nullptr;
+    // window FIFO (host bookkeeping; lists live on the device)
+    std::vector<WindowSlot> slots;
+    uint32_t head = 0, count = 0;
+    // constant CPU buffer
+    void* cpubuf_host = nullptr;
+    void* cpubuf_dev = nullptr;
+    uint64_t n_hot = 0;
+
+    ~CacheT() override {
+        (void)hipDeviceSynchronize();
+        dev_free(tags); dev_free(stamps); dev_free(pending); dev_free(reuse); dev_free(missmask); dev_free(bitmap);
+        dev_free(wrank); dev_free(hotbits); dev_free(hotrank); dev_free(cache_data); dev_free(ctl);
+        dev_free(blocksum); dev_free(blockoff); dev_free(ubuf); dev_free(plan); dev_free(misslist);
+        dev_free(fills); dev_free(copies);
+        for (auto& s : slots) if (s.ids) (void)hipFree(s.ids);
+        if (cpubuf_host) (void)hipHostFree(cpubuf_host);
+        if (ring_host) (void)hipHostFree(ring_host);
+        for (auto& e : events) if (e) (void)hipEventDestroy(e);
+    }
+
+    CacheView<IdT> view() const {
+        CacheView<IdT> v;
+        v.n_rows = store->n_rows; v.n_sets = n_sets; v.ways = ways; v.lg_ways = lg_ways;
+        v.row_bytes = store->row_bytes; v.line_bytes = line_bytes; v.words_per_set = words_per_set;
+        v.use32 = store->n_rows < (1ull << 32) ? 1u : 0u;
+        v.tags = tags; v.stamps = stamps; v.pending = pending; v.reuse = reuse; v.missmask = missmask;
+        v.hotbits = n_hot ? hotbits : nullptr; v.hotrank = hotrank;
+        v.cache_data = cache_data; v.store = static_cast<const char*>(store->dev);
+        v.cpubuf = static_cast<const char*>(cpubuf_dev); v.ctl = ctl;
+        return v;
+    }
+
+    int init() override {
+        const uint64_t n_rows = store->n_rows;
+        n_words = (n_rows + 63) / 64;
+        const uint64_t rounds = (n_rows + n_sets - 1) / n_sets;     // IDs that share one set
+        words_per_set = (uint32_t)((rounds + 63) / 64);
+        int rc;
+        if ((rc = dev_alloc(&tags, lines))) return rc;
+        if ((rc = dev_alloc(&stamps, lines))) return rc;
+        if (threshold && (rc = dev_alloc(&pending, lines))) return rc;
+        if ((rc = dev_alloc(&reuse, n_rows))) return rc;
+        if ((rc = dev_alloc(&missmask, n_sets * words_per_set))) return rc;
+        if ((rc = dev_alloc(&bitmap, n_words))) return rc;
+        if ((rc = dev_alloc(&cache_data, lines * (uint64_t)line_bytes))) return rc;
+        if ((rc = dev_alloc(&ctl, 1))) return rc;
+        const uint32_t nb = scan_blocks(n_words);
+        if ((rc = dev_alloc(&blocksum, nb))) return rc;
+        if ((rc = dev_alloc(&blockoff, nb))) return rc;
+        if (sizeof(IdT) == 8) launch_fill_i64(reinterpret_cast<int64_t*>(tags), lines, -1, nullptr);
+        else launch_fill_u32(reinterpret_cast<uint32_t*>(tags), lines, 0xFFFFFFFFu, nullptr);
+        launch_fill_u32(reinterpret_cast<uint32_t*>(stamps), lines, 0xFFFFFFFFu, nullptr);
+        if (pending) launch_fill_u32(pending, lines, NO_OP, nullptr);
+        HIP_TRY(hipMemset(reuse, 0, n_rows));
+        HIP_TRY(hipMemset(missmask, 0, n_sets * words_per_set * sizeof(uint64_t)));
+        HIP_TRY(hipMemset(bitmap, 0, n_words * sizeof(uint64_t)));
+        HIP_TRY(hipMemset(ctl, 0, sizeof(Ctl)));
+        HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&ring_host), STATS_RING * sizeof(StatsRec), hipHostMallocMapped));
+        memset(ring_host, 0xFF, STATS_RING * sizeof(StatsRec));
+        HIP_TRY(hipHostGetDevicePointer(reinterpret_cast<void**>(&ring_dev), ring_host, 0));
+        for (auto& e : events) HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        slots.resize(window ? window + 1 : 0);
+        if (const char* env = getenv("GIDS_MOVE_BLOCKS")) {
+            const int b = atoi(env);
+            if (b >= 1 && b <= 65536) move_blocks = b;
+        }
+        HIP_TRY(hipDeviceSynchronize());
+        return GIDS_OK;
+    }
+
+    // scratch for lists of up to n raw IDs; queues for threshold + n rows
+    int ensure_scratch(uint64_t n) {
+        if (n < 1) n = 1;
+        if (n > cap_n) {
+            HIP_TRY(hipDeviceSynchronize());
+            dev_free(ubuf); dev_free(plan); dev_free(misslist);
+            const uint64_t want = std::max<uint64_t>(n, cap_n + cap_n / 2);
+            int rc;
+            if ((rc = dev_alloc(&ubuf, want))) return rc;
+            if ((rc = dev_alloc(&plan, want))) return rc;
+            if ((rc = dev_alloc(&misslist, want))) return rc;
+            cap_n = want;
+        }
+        if (threshold && threshold + n > queue_cap) {
+            HIP_TRY(hipDeviceSynchronize());
+            const uint64_t want = std::max<uint64_t>(threshold + n, queue_cap + queue_cap / 2);
+            FillOp* nf = nullptr;
+            CopyOp* nc = nullptr;
+            int rc;
+            if ((rc = dev_alloc(&nf, want))) return rc;
+            if ((rc = dev_alloc(&nc, want))) { dev_free(nf); return rc; }
+            if (queue_cap) {                                  // queued rows survive the move
+                HIP_TRY(hipMemcpy(nf, fills, queue_cap * sizeof(FillOp), hipMemcpyDeviceToDevice));
+                HIP_TRY(hipMemcpy(nc, copies, queue_cap * sizeof(CopyOp), hipMemcpyDeviceToDevice));
+            }
+            dev_free(fills); dev_free(copies);
+            fills = nf; copies = nc; queue_cap = want;
+        }
+        return GIDS_OK;
+    }
+
+    int ensure_slot(WindowSlot& s, uint64_t n) {
+        if (n < 1) n = 1;
+        if (n <= s.cap) return GIDS_OK;
+        HIP_TRY(hipDeviceSynchronize());
+        if (s.ids) (void)hipFree(s.ids);
+        s.ids = nullptr; s.cap = 0;
+        HIP_TRY(hipMalloc(&s.ids, n * sizeof(IdT)));
+        s.cap = n;
+        return GIDS_OK;
+    }
+
+    int reserve(uint64_t n) override {
+        int rc = ensure_scratch(n);
+        if (rc) return rc;
+        for (auto& s : slots) {
+            // only lists that are not in use may move
+            bool live = false;
+            for (uint32_t k = 0; k < count; k++) live |= (&s == &slots[(head + k) % slots.size()]);
+            if (!live && (rc = ensure_slot(s, n))) return rc;
+        }
+        return GIDS_OK;
+    }
+
+    int pin(const void* ids_host, uint64_t n) override {
+        if (n_hot || seq || count) return fail(GIDS_E_INVAL, "gids_cpu_buffer_pin: call once, before any push or gather");
+        if (n == 0) return GIDS_OK;
+        if (!ids_host) return fail(GIDS_E_INVAL, "gids_cpu_buffer_pin: ids_host is NULL");
+        const IdT* ids = static_cast<const IdT*>(ids_host);
+        std::vector<uint64_t> sorted(n);
+        for (uint64_t i = 0; i < n; i++) {
+            if (ids[i] < 0 || (uint64_t)ids[i] >= store->n_rows) return fail(GIDS_E_RANGE, "gids_cpu_buffer_pin: ID %lld out of range", (long long)ids[i]);
+            sorted[i] = (uint64_t)ids[i];
+        }
+        std::sort(sorted.begin(), sorted.end());
+        for (uint64_t i = 1; i < n; i++)
+            if (sorted[i] == sorted[i - 1]) return fail(GIDS_E_INVAL, "gids_cpu_buffer_pin: ID %llu listed twice", (unsigned long long)sorted[i]);
+        const uint64_t rb = store->row_bytes;
+        HIP_TRY(hipHostMalloc(&cpubuf_host, n * rb, hipHostMallocMapped));
+        HIP_TRY(hipHostGetDevicePointer(&cpubuf_dev, cpubuf_host, 0));
+        // rows in ascending ID order: slot = rank of the ID among the pinned ones
+        {
+            const unsigned hw = std::max(1u, std::min(16u, std::thread::hardware_concurrency()));
+            const unsigned nt = (unsigned)std::min<uint64_t>(hw, std::max<uint64_t>(1, n * rb >> 24));
+            std::vector<std::thread> pool;
+            const char* src = static_cast<const char*>(store->host);
+            char* dst = static_cast<char*>(cpubuf_host);
+            for (unsigned t = 0; t < nt; t++)
+                pool.emplace_back([&, t]() {
+                    for (uint64_t i = n * t / nt; i < n * (t + 1) / nt; i++) memcpy(dst + i * rb, src + sorted[i] * rb, rb);
+                });
+            for (auto& th : pool) th.join();
+        }
+        std::vector<uint64_t> bits(n_words, 0);
+        std::vector<uint32_t> rank(n_words, 0);
+        for (uint64_t v : sorted) bits[v >> 6] |= 1ull << (v & 63);
+        uint32_t run = 0;
+        for (uint64_t w = 0; w < n_words; w++) { rank[w] = run; run += (uint32_t)__builtin_popcountll(bits[w]); }
+        int rc;
+        if ((rc = dev_alloc(&hotbits, n_words))) return rc;
+        if ((rc = dev_alloc(&hotrank, n_words))) return rc;
+        HIP_TRY(hipMemcpy(hotbits, bits.data(), n_words * sizeof(uint64_t), hipMemcpyHostToDevice));
+        HIP_TRY(hipMemcpy(hotrank, rank.data(), n_words * sizeof(uint32_t), hipMemcpyHostToDevice));
+        n_hot = n;
+        return GIDS_OK;
+    }
+
+    // ascending distinct IDs of ids[0..n) -> dst; count -> *n_out (device)
+    void dedup(const IdT* ids, uint64_t n, IdT* dst, uint32_t* n_out, uint8_t* reuse_inc, bool keep_bitmap,
+               hipStream_t s) {
+        launch_mark<IdT>(ids, n, store->n_rows, bitmap, ctl, s);
+        launch_count(bitmap, n_words, blocksum, blockoff, ctl, n_out, s);
+        launch_emit<IdT>(bitmap, n_words, store->n_rows, blockoff, dst, reuse_inc, keep_bitmap ? wrank : nullptr,
+                         !keep_bitmap, ctl, s);
+    }
+
+    int push(const void* ids, uint64_t n, hipStream_t s) override {
+        if (window == 0) return fail(GIDS_E_INVAL, "gids_window_push: the cache was created with window_depth 0");
+        if (count == slots.size()) return fail(GIDS_E_FULL, "gids_window_push: %u lists already buffered", count);
+        if (n && !ids) return fail(GIDS_E_INVAL, "gids_window_push: ids_dev is NULL");
+        const uint32_t slot = (head + count) % slots.size();
+        int rc = ensure_slot(slots[slot], n);
+        if (rc) return rc;
+        slots[slot].n_raw = n;
+        dedup(static_cast<const IdT*>(ids), n, static_cast<IdT*>(slots[slot].ids), &ctl->win_n[slot], reuse, false, s);
+        count++;
+        last_stream = s;
+        return GIDS_OK;
+    }
+
+    int gather(const void* ids_v, uint64_t n, void* out, uint64_t out_cap, void* unique, void* inverse,
+               hipStream_t s) override {
+        const IdT* ids = static_cast<const IdT*>(ids_v);
+        if (!out && out_cap) return fail(GIDS_E_INVAL, "gids_gather: out_dev is NULL");
+        if (inverse && !ids) return fail(GIDS_E_INVAL, "gids_gather: inverse_dev needs ids_dev");
+        const IdT* U;
+        const uint32_t* n_u;
+        uint64_t n_upper;
+        bool pop = false;
+        if (window) {
+            if (count == 0) return fail(GIDS_E_ORDER, "gids_gather: no minibatch is buffered in the window");
+            WindowSlot& h = slots[head];
+            if (!ids) n = 0;
+            int rc = ensure_scratch(std::max(n, h.n_raw));
+            if (rc) return rc;
+            if (ids) {
+                if (inverse && !wrank && (rc = dev_alloc(&wrank, n_words))) return rc;
+                dedup(ids, n, ubuf, &ctl->n_unique, nullptr, inverse != nullptr, s);
+                launch_verify<IdT>(ubuf, static_cast<const IdT*>(h.ids), &ctl->win_n[head], ctl, std::min(n, h.n_raw), s);
+                if (inverse) {
+                    launch_inverse<IdT>(ids, n, bitmap, wrank, static_cast<uint32_t*>(inverse), ctl, s);
+                    launch_clear<IdT>(bitmap, ubuf, &ctl->n_unique, n, s);
+                }
+            }
+            U = static_cast<const IdT*>(h.ids);
+            n_u = &ctl->win_n[head];
+            n_upper = h.n_raw;
+            pop = true;
+        } else {
+            if (!ids && n) return fail(GIDS_E_INVAL, "gids_gather: ids_dev is NULL and there is no window to take the list from");
+            int rc = ensure_scratch(n);
+            if (rc) return rc;
+            if (inverse && !wrank && (rc = dev_alloc(&wrank, n_words))) return rc;
+            dedup(ids, n, ubuf, &ctl->n_unique, nullptr, inverse != nullptr, s);
+            if (inverse) {
+                launch_inverse<IdT>(ids, n, bitmap, wrank, static_cast<uint32_t*>(inverse), ctl, s);
+                launch_clear<IdT>(bitmap, ubuf, &ctl->n_unique, n, s);
+            }
+            U = ubuf;
+            n_u = &ctl->n_unique;
+            n_upper = n;
+        }
+        n_upper = std::min<uint64_t>(n_upper, store->n_rows);
+        const CacheView<IdT> c = view();
+        launch_probe<IdT>(c, U, n_u, n_upper, out_cap, static_cast<IdT*>(unique), pop, plan, misslist, s);
+        launch_victim<IdT>(c, U, n_upper, plan, misslist, s);
+        if (threshold == 0) {
+            launch_move<IdT>(c, U, n_u, n_upper, plan, static_cast<char*>(out), move_blocks, s);
+        } else {
+            launch_queue<IdT>(c, U, n_u, n_upper, plan, static_cast<char*>(out), fills, copies, (uint32_t)queue_cap,
+                              move_blocks, s);
+            launch_flush<IdT>(c, fills, copies, threshold, false, move_blocks, s);
+        }
+        const int r = (int)(seq % STATS_RING);
+        launch_finalize(ctl, ring_dev + r, seq, n_u, s);
+        HIP_TRY(hipEventRecord(events[r], s));
+        seq++;
+        if (window) { head = (head + 1) % slots.size(); count--; }
+        last_stream = s;
+        return GIDS_OK;
+    }
+
+    int flush(hipStream_t s) override {
+        if (threshold) launch_flush<IdT>(view(), fills, copies, threshold, true, move_blocks, s);
+        last_stream = s;
+        return GIDS_OK;
+    }
+
+    int snapshot(int64_t* tags_host, int64_t* stamps_host) override {
+        HIP_TRY(hipDeviceSynchronize());
+        if (tags_host) {
+            std::vector<IdT> t(lines);
+            HIP_TRY(hipMemcpy(t.data(), tags, lines * sizeof(IdT), hipMemcpyDeviceToHost));
+            for (uint64_t i = 0; i < lines; i++) tags_host[i] = (int64_t)t[i];
+        }
+        if (stamps_host) {
+            std::vector<int32_t> t(lines);
+            HIP_TRY(hipMemcpy(t.data(), stamps, lines * sizeof(int32_t), hipMemcpyDeviceToHost));
+            for (uint64_t i = 0; i < lines; i++) stamps_host[i] = (int64_t)t[i];
+        }
+        return GIDS_OK;
+    }
+};
+
+}  // namespace
+
+extern "C" {
+
+const char* gids_last_error(void) { return g_err; }
+
+int gids_store_create(uint64_t n_rows, uint32_t row_bytes, uint32_t id_bytes, void* host_ptr_or_null,
+                      gids_store** out) {
+    if (!out) return fail(GIDS_E_INVAL, "gids_store_create: out is NULL");
+    *out = nullptr;
+    if (n_rows == 0 || row_bytes == 0 || row_bytes % 16) return fail(GIDS_E_INVAL, "gids_store_create: row_bytes must be a positive multiple of 16 and n_rows > 0");
+    if (id_bytes != 4 && id_bytes != 8) return fail(GIDS_E_INVAL, "gids_store_create: id_bytes must be 4 or 8");
+    if (id_bytes == 4 && n_rows > 0x7FFFFFFFull) return fail(GIDS_E_INVAL, "gids_store_create: n_rows does not fit 4-byte IDs");
+    if (n_rows > 0xFFFFFFFF00ull) return fail(GIDS_E_INVAL, "gids_store_create: n_rows too large");
+    gids_store* st = new (std::nothrow) gids_store();
+    if (!st) return fail(GIDS_E_NOMEM, "gids_store_create: out of host memory");
+    st->n_rows = n_rows; st->row_bytes = row_bytes; st->id_bytes = id_bytes;
+    if (host_ptr_or_null) {
+        st->host = host_ptr_or_null;
+        hipError_t e = hipHostGetDevicePointer(&st->dev, host_ptr_or_null, 0);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            delete st;
+            return fail(GIDS_E_HIP, "gids_store_create: host_ptr is not pinned, GPU-visible memory (%s)", hipGetErrorString(e));
+        }
+    } else {
+        hipError_t e = hipHostMalloc(&st->host, n_rows * (uint64_t)row_bytes, hipHostMallocMapped);
+        if (e == hipSuccess) e = hipHostGetDevicePointer(&st->dev, st->host, 0);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            if (st->host) (void)hipHostFree(st->host);
+            delete st;
+            return fail(GIDS_E_NOMEM, "gids_store_create: cannot pin %llu bytes of host memory (%s)",
+                        (unsigned long long)(n_rows * (uint64_t)row_bytes), hipGetErrorString(e));
+        }
+        st->owned = true;
+    }
+    *out = st;
+    return GIDS_OK;
+}
+
+void* gids_store_host_ptr(gids_store* store) { return store ? store->host : nullptr; }
+
+int gids_store_destroy(gids_store* store) {
+    if (!store) return GIDS_OK;
+    if (store->owned && store->host) (void)hipHostFree(store->host);
+    delete store;
+    return GIDS_OK;
+}
+
+int gids_cache_create(gids_store* store, uint64_t lines, uint32_t ways, uint32_t line_bytes, uint32_t window_depth,
+                      uint64_t accum_threshold, gids_cache** out) {
+    if (!out) return fail(GIDS_E_INVAL, "gids_cache_create: out is NULL");
+    *out = nullptr;
+    if (!store) return fail(GIDS_E_INVAL, "gids_cache_create: store is NULL");
+    if (ways == 0 || ways > 64 || (ways & (ways - 1))) return fail(GIDS_E_INVAL, "gids_cache_create: ways must be a power of two in [1, 64]");
+    if (lines == 0 || lines % ways) return fail(GIDS_E_INVAL, "gids_cache_create: lines must be a positive multiple of ways");
+    if (line_bytes < store->row_bytes || line_bytes % 16) return fail(GIDS_E_INVAL, "gids_cache_create: line_bytes must be a multiple of 16 and >= row_bytes");
+    if (window_depth > 254) return fail(GIDS_E_INVAL, "gids_cache_create: window_depth must be <= 254");
+    if (lines >= (1ull << 40) || accum_threshold >= (1ull << 31)) return fail(GIDS_E_INVAL, "gids_cache_create: lines or accum_threshold too large");
+    gids_cache* c = store->id_bytes == 4 ? static_cast<gids_cache*>(new (std::nothrow) CacheT<int32_t>())
+                                         : static_cast<gids_cache*>(new (std::nothrow) CacheT<int64_t>());
+    if (!c) return fail(GIDS_E_NOMEM, "gids_cache_create: out of host memory");
+    c->store = store; c->lines = lines; c->ways = ways; c->line_bytes = line_bytes; c->window = window_depth;
+    c->threshold = accum_threshold; c->n_sets = lines / ways;
+    c->lg_ways = 0;
+    while ((1u << c->lg_ways) < ways) c->lg_ways++;
+    const int rc = c->init();
+    if (rc) { delete c; return rc; }
+    *out = c;
+    return GIDS_OK;
+}
+
+int gids_cache_destroy(gids_cache* cache) {
+    delete cache;
+    return GIDS_OK;
+}
+
+#define CHECK_CACHE(c)                                                         \
+    if (!(c)) return fail(GIDS_E_INVAL, "%s: cache is NULL", __func__);        \
+    if ((c)->sticky) return fail((c)->sticky, "%s: an earlier operation on this cache failed on the device (%d)", __func__, (c)->sticky)
+
+int gids_cache_reserve(gids_cache* cache, uint64_t max_ids) {
+    CHECK_CACHE(cache);
+    if (max_ids > 0xFFFFFFF0ull) return fail(GIDS_E_INVAL, "gids_cache_reserve: list too long");
+    return cache->reserve(max_ids);
+}
+
+int gids_cpu_buffer_pin(gids_cache* cache, const void* ids_host, uint64_t n) {
+    CHECK_CACHE(cache);
+    return cache->pin(ids_host, n);
+}
+
+int gids_window_push(gids_cache* cache, const void* ids_dev, uint64_t n, void* stream) {
+    CHECK_CACHE(cache);
+    if (n > 0xFFFFFFF0ull) return fail(GIDS_E_INVAL, "gids_window_push: list too long");
+    return cache->push(ids_dev, n, static_cast<hipStream_t>(stream));
+}
+
+int gids_gather(gids_cache* cache, const void* ids_dev, uint64_t n, void* out_dev, uint64_t out_capacity_rows,
+                void* unique_dev, void* inverse_dev, void* stream) {
+    CHECK_CACHE(cache);
+    if (n > 0xFFFFFFF0ull) return fail(GIDS_E_INVAL, "gids_gather: list too long");
+    return cache->gather(ids_dev, n, out_dev, out_capacity_rows, unique_dev, inverse_dev, static_cast<hipStream_t>(stream));
+}
+
+int gids_flush(gids_cache* cache, void* stream) {
+    CHECK_CACHE(cache);
+    return cache->flush(static_cast<hipStream_t>(stream));
+}
+
+int gids_stats_read(gids_cache* cache, uint64_t seq, gids_stats* stats) {
+    if (!cache || !stats) return fail(GIDS_E_INVAL, "gids_stats_read: NULL argument");
+    if (seq >= cache->seq || seq + STATS_RING < cache->seq) return fail(GIDS_E_INVAL, "gids_stats_read: gather %llu is not available", (unsigned long long)seq);
+    const int r = (int)(seq % STATS_RING);
+    HIP_TRY(hipEventSynchronize(cache->events[r]));
+    const StatsRec rec = cache->ring_host[r];
+    if (rec.seq != seq) return fail(GIDS_E_INVAL, "gids_stats_read: record of gather %llu was overwritten", (unsigned long long)seq);
+    stats->seq = rec.seq; stats->n_unique = rec.n_unique; stats->n_hit = rec.n_hit; stats->n_cpu_hit = rec.n_cpu_hit;
+    stats->n_miss = rec.n_miss; stats->n_bypass = rec.n_bypass; stats->n_pending = rec.n_pending;
+    stats->flushed = rec.flushed; stats->status = rec.status;
+    if (rec.status) {
+        cache->sticky = rec.status;
+        return fail(rec.status, "gather %llu failed on the device with code %d", (unsigned long long)seq, rec.status);
+    }
+    return GIDS_OK;
+}
+
+uint64_t gids_cache_gathers(const gids_cache* cache) { return cache ? cache->seq : 0; }
+
+int gids_cache_snapshot(gids_cache* cache, int64_t* tags_host, int64_t* stamps_host) {
+    if (!cache) return fail(GIDS_E_INVAL, "gids_cache_snapshot: cache is NULL");
+    return cache->snapshot(tags_host, stamps_host);
+}
+
+double gids_accum_threshold(double iops_peak, double t_initial, double t_termination, double ratio, int n_ssd) {
+    // N = IOPS_achieved * (Ti + Ts + Tt) * n_ssd with Ts = N / (IOPS_peak * n_ssd), at IOPS_achieved = ratio * IOPS_peak
+    if (!(ratio > 0.0) || !(ratio < 1.0) || n_ssd < 1) return -1.0;
+    const double busy = iops_peak * (double)n_ssd;
+    return ratio * busy * (t_initial + t_termination) / (1.0 - ratio);
+}
+
+}  // extern "C"

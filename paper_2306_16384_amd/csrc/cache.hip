@@ -1,0 +1,232 @@
+// Set-associative tag probe and victim selection of the GPU software cache
+// with window buffering (GIDS paper, Section 3.4; CPU-buffer redirection,
+// Section 3.3).
+//
+// The policy is batch-synchronous, so no lock is ever taken:
+//   probe   every distinct ID of the minibatch is classified against the cache
+//           state at the start of the minibatch.  `ways` adjacent lanes of a
+//           wavefront compare one set's tags in one coalesced load and a ballot
+//           names the matching way.  Hits stamp their line with the minibatch
+//           index; misses set one bit (set, id / n_sets) in a per-set miss
+//           mask and join the miss list.  The probe also takes this
+//           minibatch's own entry out of the per-node future-reuse counters
+//           ("decreased each time the node is reused").
+//   victim  a miss's rank among the misses of its set is a popcount of the
+//           mask below its own bit (ascending ID order without any sort); the
+//           lanes of its group rank the set's evictable ways by (stamp, way)
+//           with cross-lane permutes, and the rank-th evictable way is its
+//           victim.  A way is evictable when this minibatch did not touch it
+//           and it is empty or its node's future-reuse counter is zero ("safe
+//           to evict"); a positive counter is the "USE" state.  With more
+//           misses than evictable ways the rest bypass the cache.
+// Neither kernel writes a tag: the row mover does, when it fills the line.
+#include "gids_dev.h"
+
+namespace gids {
+
+namespace {
+
+constexpr int CT_THREADS = 256;
+
+__device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63; }
+
+template <typename IdT>
+__device__ __forceinline__ void set_and_round(const CacheView<IdT>& c, uint64_t v, uint64_t* set, uint64_t* round) {
+    if (c.use32) {
+        const uint32_t q = (uint32_t)v / (uint32_t)c.n_sets;
+        *round = q;
+        *set = (uint32_t)v - q * (uint32_t)c.n_sets;
+    } else {
+        const uint64_t q = v / c.n_sets;
+        *round = q;
+        *set = v - q * c.n_sets;
+    }
+}
+
+// bits of a 64-lane ballot that belong to this lane's group of `ways` lanes
+__device__ __forceinline__ uint64_t group_bits(uint64_t ballot, uint32_t ways) {
+    const uint32_t base = lane_id() & ~(ways - 1);
+    const uint64_t mask = ways == 64 ? ~0ull : ((1ull << ways) - 1);
+    return (ballot >> base) & mask;
+}
+
+template <typename IdT>
+__global__ __launch_bounds__(CT_THREADS) void probe_kernel(CacheView<IdT> c, const IdT* __restrict__ unique,
+                                                           const uint32_t* __restrict__ n_u_ptr, uint64_t out_capacity,
+                                                           IdT* __restrict__ unique_out, int pop_window,
+                                                           uint64_t* __restrict__ plan, uint32_t* __restrict__ misslist) {
+    Ctl* ctl = c.ctl;
+    if (ctl->error) return;                                  // set only by earlier kernels: uniform
+    const uint32_t n_u = *n_u_ptr;
+    if (n_u > out_capacity) {                                // the same verdict in every thread
+        if (blockIdx.x == 0 && threadIdx.x == 0) ctl->error = 7u; /* -GIDS_E_SPACE; finalize reports it */
+        return;
+    }
+    const uint32_t ways = c.ways, lg = c.lg_ways;
+    const uint32_t per_wave = 64u >> lg;                     // IDs a wavefront classifies at once
+    const uint32_t sub = lane_id() & (ways - 1);             // this lane's way
+    const bool leader = sub == 0;
+    const uint32_t stamp = ctl->stamp;
+    const uint64_t wave0 = ((uint64_t)blockIdx.x * CT_THREADS + threadIdx.x) >> 6;
+    const uint64_t n_waves = ((uint64_t)gridDim.x * CT_THREADS) >> 6;
+    uint32_t hits = 0, cpus = 0, misses = 0;
+    for (uint64_t chunk = wave0; chunk * per_wave < n_u; chunk += n_waves) {
+        const uint64_t j = chunk * per_wave + (lane_id() >> lg);
+        const bool valid = j < n_u;
+        const uint64_t v = valid ? (uint64_t)unique[j] : 0;
+        // leader: CPU-buffer membership, window pop, copy to the caller's ID list
+        uint32_t hot = 0, slot = 0;
+        if (valid && leader) {
+            if (unique_out) unique_out[j] = (IdT)v;
+            if (pop_window) c.reuse[v] = (uint8_t)(c.reuse[v] - 1);
+            if (c.hotbits) {
+                const uint64_t hw = c.hotbits[v >> 6];
+                const uint64_t bit = 1ull << (v & 63);
+                if (hw & bit) {
+                    hot = 1;
+                    slot = c.hotrank[v >> 6] + (uint32_t)__popcll(hw & (bit - 1));
+                }
+            }
+        }
+        hot = __shfl(hot, (int)(lane_id() & ~(ways - 1)));
+        uint64_t set = 0, round = 0;
+        set_and_round(c, v, &set, &round);
+        bool match = false;
+        if (valid && !hot) match = (uint64_t)c.tags[set * ways + sub] == v;   // empty lines hold -1
+        const uint64_t gb = group_bits(__ballot(match), ways);
+        const bool is_hit = gb != 0;
+        const bool is_miss = valid && leader && !hot && !is_hit;
+        // wave-aggregated append to the miss list
+        const uint64_t mb = __ballot(is_miss);
+        uint32_t mbase = 0;
+        if (mb) {
+            if (lane_id() == (uint32_t)(__ffsll((unsigned long long)mb) - 1))
+                mbase = atomicAdd(&ctl->n_miss, (uint32_t)__popcll(mb));
+            mbase = __shfl(mbase, __ffsll((unsigned long long)mb) - 1);
+        }
+        if (valid && leader) {
+            if (hot) {
+                plan[j] = (PLAN_CPU << PLAN_SHIFT) | slot;
+                cpus++;
+            } else if (is_hit) {
+                const uint64_t line = set * ways + (uint32_t)(__ffsll((unsigned long long)gb) - 1);
+                c.stamps[line] = (int32_t)stamp;
+                plan[j] = (PLAN_HIT << PLAN_SHIFT) | line;
+                hits++;
+            } else {
+                plan[j] = PLAN_MISS_TBD << PLAN_SHIFT;
+                atomicOr(reinterpret_cast<unsigned long long*>(c.missmask) + set * c.words_per_set + (round >> 6),
+                         1ull << (round & 63));
+                misslist[mbase + (uint32_t)__popcll(mb & ((1ull << lane_id()) - 1))] = (uint32_t)j;
+                misses++;
+            }
+        }
+    }
+    // one atomic per wave and counter
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        hits += __shfl_down(hits, d);
+        cpus += __shfl_down(cpus, d);
+        misses += __shfl_down(misses, d);
+    }
+    if (lane_id() == 0) {
+        if (hits) atomicAdd(&ctl->cnt_hit, hits);
+        if (cpus) atomicAdd(&ctl->cnt_cpu, cpus);
+        if (misses) atomicAdd(&ctl->cnt_miss, misses);
+    }
+}
+
+template <typename IdT>
+__global__ __launch_bounds__(CT_THREADS) void victim_kernel(CacheView<IdT> c, const IdT* __restrict__ unique,
+                                                            uint64_t* __restrict__ plan,
+                                                            const uint32_t* __restrict__ misslist) {
+    Ctl* ctl = c.ctl;
+    if (ctl->error) return;
+    const uint32_t n_miss = ctl->n_miss;
+    const uint32_t ways = c.ways, lg = c.lg_ways;
+    const uint32_t per_wave = 64u >> lg;
+    const uint32_t sub = lane_id() & (ways - 1);
+    const uint32_t group_base = lane_id() & ~(ways - 1);
+    const int32_t stamp = (int32_t)ctl->stamp;
+    const uint64_t wave0 = ((uint64_t)blockIdx.x * CT_THREADS + threadIdx.x) >> 6;
+    const uint64_t n_waves = ((uint64_t)gridDim.x * CT_THREADS) >> 6;
+    uint32_t bypasses = 0;
+    for (uint64_t chunk = wave0; chunk * per_wave < n_miss; chunk += n_waves) {
+        const uint64_t i = chunk * per_wave + (lane_id() >> lg);
+        const bool valid = i < n_miss;
+        const uint32_t j = valid ? misslist[i] : 0;
+        const uint64_t v = valid ? (uint64_t)unique[j] : 0;
+        uint64_t set = 0, round = 0;
+        set_and_round(c, v, &set, &round);
+        // this lane's way: evictable?
+        const uint64_t line = set * ways + sub;
+        bool ev = false;
+        int32_t st = 0;
+        if (valid) {
+            const IdT tg = c.tags[line];
+            st = c.stamps[line];
+            ev = st != stamp && (tg < 0 || c.reuse[(uint64_t)tg] == 0);
+        }
+        // order of this way among the set's evictable ways by (stamp, way)
+        const uint64_t key = ev ? (((uint64_t)(uint32_t)(st + 1)) << 8) | sub : ~0ull;
+        uint32_t way_rank = 0;
+        for (uint32_t o = 0; o < ways; o++) {
+            const uint64_t other = __shfl(key, (int)(group_base + o));
+            way_rank += other < key;
+        }
+        const uint32_t n_ev = (uint32_t)__popcll(group_bits(__ballot(ev), ways));
+        // rank of this miss among its set's misses in ascending ID order
+        uint32_t k = 0;
+        if (valid && sub == 0) {
+            const uint64_t* m = c.missmask + set * c.words_per_set;
+            const uint32_t wi = (uint32_t)(round >> 6);
+            for (uint32_t x = 0; x < wi; x++) k += (uint32_t)__popcll(m[x]);
+            k += (uint32_t)__popcll(m[wi] & ((1ull << (round & 63)) - 1));
+        }
+        k = __shfl(k, (int)group_base);
+        if (valid) {
+            if (ev && way_rank == k) plan[j] = (PLAN_INSTALL << PLAN_SHIFT) | line;
+            if (sub == 0 && k >= n_ev) {
+                plan[j] = PLAN_BYPASS << PLAN_SHIFT;
+                bypasses++;
+            }
+        }
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) bypasses += __shfl_down(bypasses, d);
+    if (lane_id() == 0 && bypasses) atomicAdd(&ctl->cnt_bypass, bypasses);
+}
+
+inline uint32_t grid_for(uint64_t groups, uint32_t ways, uint32_t cap) {
+    const uint64_t per_block = (uint64_t)(CT_THREADS / 64) * (64 / ways);
+    uint64_t b = (groups + per_block - 1) / per_block;
+    if (b < 1) b = 1;
+    return (uint32_t)(b > cap ? cap : b);
+}
+
+}  // namespace
+
+template <typename IdT>
+void launch_probe(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_u, uint64_t n_upper,
+                  uint64_t out_capacity, IdT* unique_out, bool pop_window, uint64_t* plan, uint32_t* misslist,
+                  hipStream_t s) {
+    hipLaunchKernelGGL(probe_kernel<IdT>, dim3(grid_for(n_upper, c.ways, 4096)), dim3(CT_THREADS), 0, s, c, unique,
+                       n_u, out_capacity, unique_out, pop_window ? 1 : 0, plan, misslist);
+}
+
+template <typename IdT>
+void launch_victim(const CacheView<IdT>& c, const IdT* unique, uint64_t n_upper, uint64_t* plan,
+                   const uint32_t* misslist, hipStream_t s) {
+    hipLaunchKernelGGL(victim_kernel<IdT>, dim3(grid_for(n_upper, c.ways, 4096)), dim3(CT_THREADS), 0, s, c, unique,
+                       plan, misslist);
+}
+
+#define GIDS_INSTANTIATE(IdT)                                                                                       \
+    template void launch_probe<IdT>(const CacheView<IdT>&, const IdT*, const uint32_t*, uint64_t, uint64_t, IdT*,   \
+                                    bool, uint64_t*, uint32_t*, hipStream_t);                                       \
+    template void launch_victim<IdT>(const CacheView<IdT>&, const IdT*, uint64_t, uint64_t*, const uint32_t*,       \
+                                     hipStream_t);
+GIDS_INSTANTIATE(int32_t)
+GIDS_INSTANTIATE(int64_t)
+
+}  // namespace gids

@@ -1,0 +1,128 @@
+// Internal declarations shared by the library's translation units: the
+// device-resident control block, the plan encoding, and the host-side launchers
+// of every kernel.  Nothing here is part of the C ABI (see include/gids.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gids {
+
+// ---- plan entry: what the row mover does for the j-th distinct ID ----------
+// bits 63..61 = kind, bits 60..0 = cache line index (HIT, INSTALL) or CPU-buffer
+// slot (CPU); BYPASS and MISS_TBD carry no index.
+constexpr uint64_t PLAN_HIT = 0, PLAN_CPU = 1, PLAN_INSTALL = 2, PLAN_BYPASS = 3, PLAN_MISS_TBD = 4;
+constexpr int PLAN_SHIFT = 61;
+constexpr uint64_t PLAN_INDEX_MASK = (1ull << PLAN_SHIFT) - 1;
+
+constexpr uint32_t NO_OP = 0xFFFFFFFFu;       // "no pending fill" marker of a cache line
+constexpr uint64_t NO_LINE = ~0ull;           // a queued fill that installs nothing
+
+constexpr int MAX_WINDOW_SLOTS = 256;
+
+// Device-resident control block of one cache.  Kernels read every count from
+// here, so the host never has to wait for a count before launching the next.
+struct Ctl {
+    uint32_t n_unique;      // distinct IDs of the list deduplicated last
+    uint32_t error;         // first error a kernel found (-GIDS_E_*), 0 = none; sticky
+    uint32_t ticket;        // arrival counter for "last block does the scan"
+    uint32_t n_miss;        // entries in the miss list of the current gather
+    uint32_t stamp;         // index of the minibatch being gathered (successful gathers so far)
+    uint32_t cnt_hit, cnt_cpu, cnt_miss, cnt_bypass;
+    uint32_t pend_fill;     // queued host-link rows (accumulator)
+    uint32_t pend_copy;     // queued HBM copies that wait for a queued fill
+    uint32_t do_flush;      // decision of the accumulator for this gather
+    uint32_t deferred;      // rows of the current gather left in the queues
+    uint32_t win_n[MAX_WINDOW_SLOTS];   // distinct count of each buffered list
+};
+
+// One queued row move of the accumulator.
+struct FillOp {
+    const void* src;        // host store row or CPU-buffer row (device-visible address)
+    void* dst_out;          // row in a caller's output tensor
+    uint64_t dst_line;      // cache line to fill as well, or NO_LINE
+};
+struct CopyOp {
+    const void* src;        // output row that a queued fill will write
+    void* dst_out;
+};
+
+// Mirror of gids_stats in host-mapped memory, written by the finalize kernel.
+struct StatsRec {
+    uint64_t seq, n_unique, n_hit, n_cpu_hit, n_miss, n_bypass, n_pending;
+    int32_t flushed, status;
+};
+
+// Everything the gather kernels need about one cache.
+template <typename IdT>
+struct CacheView {
+    uint64_t n_rows;        // rows of the store
+    uint64_t n_sets;
+    uint32_t ways, lg_ways;
+    uint32_t row_bytes, line_bytes;
+    uint32_t words_per_set; // 64-bit words of the miss mask per set
+    uint32_t use32;         // n_rows < 2^32: set index with 32-bit arithmetic
+    IdT* tags;              // lines, -1 = empty
+    int32_t* stamps;        // lines, -1 = never used
+    uint32_t* pending;      // lines: index of the queued fill that will write the line, or NO_OP
+    uint8_t* reuse;         // n_rows: buffered future minibatches that contain the node
+    uint64_t* missmask;     // n_sets * words_per_set
+    const uint64_t* hotbits;    // n_rows / 64 words, or nullptr when no CPU buffer
+    const uint32_t* hotrank;    // exclusive popcount prefix of hotbits
+    char* cache_data;       // lines * line_bytes
+    const char* store;      // device-visible address of the host store
+    const char* cpubuf;     // device-visible address of the CPU buffer rows (ascending ID order)
+    Ctl* ctl;
+};
+
+// ---- launchers (defined in the .hip files) ---------------------------------
+
+template <typename IdT>
+void launch_mark(const IdT* ids, uint64_t n, uint64_t n_rows, uint64_t* bitmap, Ctl* ctl, hipStream_t s);
+
+void launch_count(const uint64_t* bitmap, uint64_t n_words, uint32_t* blocksum, uint32_t* blockoff, Ctl* ctl,
+                  uint32_t* n_out, hipStream_t s);
+
+template <typename IdT>
+void launch_emit(uint64_t* bitmap, uint64_t n_words, uint64_t n_rows, const uint32_t* blockoff, IdT* dst,
+                 uint8_t* reuse_inc, uint32_t* wrank, bool clear, Ctl* ctl, hipStream_t s);
+
+template <typename IdT>
+void launch_verify(const IdT* fresh, const IdT* head, const uint32_t* head_n, Ctl* ctl, uint64_t n_upper,
+                   hipStream_t s);
+
+template <typename IdT>
+void launch_inverse(const IdT* ids, uint64_t n, const uint64_t* bitmap, const uint32_t* wrank, uint32_t* inverse,
+                    Ctl* ctl, hipStream_t s);
+
+template <typename IdT>
+void launch_clear(uint64_t* bitmap, const IdT* unique, const uint32_t* n_u, uint64_t n_upper, hipStream_t s);
+
+template <typename IdT>
+void launch_probe(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_u, uint64_t n_upper,
+                  uint64_t out_capacity, IdT* unique_out, bool pop_window, uint64_t* plan, uint32_t* misslist,
+                  hipStream_t s);
+
+template <typename IdT>
+void launch_victim(const CacheView<IdT>& c, const IdT* unique, uint64_t n_upper, uint64_t* plan,
+                   const uint32_t* misslist, hipStream_t s);
+
+template <typename IdT>
+void launch_move(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_u, uint64_t n_upper,
+                 const uint64_t* plan, char* out, int blocks, hipStream_t s);
+
+template <typename IdT>
+void launch_queue(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_u, uint64_t n_upper,
+                  const uint64_t* plan, char* out, FillOp* fills, CopyOp* copies, uint32_t queue_cap, int blocks,
+                  hipStream_t s);
+
+template <typename IdT>
+void launch_flush(const CacheView<IdT>& c, FillOp* fills, CopyOp* copies, uint64_t threshold, bool force,
+                  int blocks, hipStream_t s);
+
+void launch_finalize(Ctl* ctl, StatsRec* rec, uint64_t seq, const uint32_t* n_u, hipStream_t s);
+
+void launch_fill_u32(uint32_t* p, uint64_t n, uint32_t value, hipStream_t s);
+void launch_fill_i64(int64_t* p, uint64_t n, int64_t value, hipStream_t s);
+
+}  // namespace gids

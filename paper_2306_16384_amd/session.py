@@ -1,0 +1,110 @@
+"""A convenience wrapper for harnesses (tests, benchmark, smoke check): owns
+the store / cache handles and the torch tensors whose device pointers go
+through the C ABI.  It moves arguments only; it computes nothing."""
+from __future__ import annotations
+
+import ctypes as C
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+class GatherSession:
+    def __init__(self, n_rows: int, row_bytes: int, id_dtype, lines: int, ways: int, line_bytes: int,
+                 window: int = 0, accum_threshold: int = 0, host_store: torch.Tensor | None = None):
+        if not torch.cuda.is_available():
+            raise RuntimeError("GatherSession needs a GPU: the gather has no CPU path")
+        self.n_rows, self.row_bytes = n_rows, row_bytes
+        self.id_dtype = np.dtype(id_dtype)
+        self.torch_id = torch.int32 if self.id_dtype.itemsize == 4 else torch.int64
+        self.window = window
+        self._host_store = host_store
+        self.store = B.gids_store_create(n_rows, row_bytes, self.id_dtype.itemsize,
+                                         None if host_store is None else host_store.data_ptr())
+        self.cache = None
+        try:
+            self.cache = B.gids_cache_create(self.store, lines, ways, line_bytes, window, accum_threshold)
+        except Exception:
+            B.gids_store_destroy(self.store)
+            self.store = None
+            raise
+        self.lines = lines
+        self._keep = []          # tensors the library may still read or write (outputs awaiting a flush)
+
+    # -- the host table ----------------------------------------------------
+    def store_view(self) -> np.ndarray:
+        """The pinned host table as a uint8 array [n_rows, row_bytes] (to fill it)."""
+        ptr = B.gids_store_host_ptr(self.store)
+        buf = (C.c_uint8 * (self.n_rows * self.row_bytes)).from_address(ptr)
+        return np.ctypeslib.as_array(buf).reshape(self.n_rows, self.row_bytes)
+
+    def store_address(self) -> int:
+        return B.gids_store_host_ptr(self.store)
+
+    def pin_hot(self, ids) -> None:
+        ids = np.ascontiguousarray(np.asarray(ids, dtype=self.id_dtype))
+        B.gids_cpu_buffer_pin(self.cache, ids.ctypes.data, len(ids))
+
+    def reserve(self, max_ids: int) -> None:
+        B.gids_cache_reserve(self.cache, max_ids)
+
+    # -- device-side calls -------------------------------------------------
+    def to_device(self, raw) -> torch.Tensor:
+        raw = np.ascontiguousarray(np.asarray(raw, dtype=self.id_dtype))
+        return torch.from_numpy(raw).cuda() if len(raw) else torch.empty(0, dtype=self.torch_id, device="cuda")
+
+    def push(self, ids_dev: torch.Tensor) -> None:
+        stream = torch.cuda.current_stream().cuda_stream
+        B.gids_window_push(self.cache, ids_dev.data_ptr() if ids_dev.numel() else None, ids_dev.numel(), stream)
+        self._keep.append(ids_dev)
+
+    def gather(self, ids_dev: torch.Tensor | None, out: torch.Tensor, unique: torch.Tensor | None = None,
+               inverse: torch.Tensor | None = None) -> int:
+        """Enqueue one gather; returns its sequence number (for stats)."""
+        stream = torch.cuda.current_stream().cuda_stream
+        seq = B.gids_cache_gathers(self.cache)
+        n = 0 if ids_dev is None else ids_dev.numel()
+        if n == 0:
+            inverse = None
+        B.gids_gather(self.cache, ids_dev.data_ptr() if n else None, n, out.data_ptr(), out.shape[0],
+                      None if unique is None else unique.data_ptr(), None if inverse is None else inverse.data_ptr(),
+                      stream)
+        if len(self._keep) > 64:
+            del self._keep[:-64]
+        return seq
+
+    def flush(self) -> None:
+        B.gids_flush(self.cache, torch.cuda.current_stream().cuda_stream)
+
+    def stats(self, seq: int) -> B.gids_stats:
+        return B.gids_stats_read(self.cache, seq)
+
+    def snapshot(self):
+        tags = np.empty(self.lines, dtype=np.int64)
+        stamps = np.empty(self.lines, dtype=np.int64)
+        B.gids_cache_snapshot(self.cache, tags.ctypes.data, stamps.ctypes.data)
+        return tags, stamps
+
+    def close(self) -> None:
+        if self.cache:
+            torch.cuda.synchronize()
+            B.gids_cache_destroy(self.cache)
+            self.cache = None
+        if self.store:
+            B.gids_store_destroy(self.store)
+            self.store = None
+        self._keep.clear()
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

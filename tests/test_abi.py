@@ -1,0 +1,47 @@
+"""The C-ABI library loads and exports every symbol include/gids.h declares
+(no compute call: this runs without a GPU)."""
+import os
+import re
+
+import pytest
+
+import paper_2306_16384_amd as gids
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "gids.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gids_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = gids.lib()
+    names = declared_symbols()
+    assert len(names) >= 14
+    for name in names:
+        assert hasattr(L, name), name
+    assert sorted(gids.EXPORTS) == names
+
+
+def test_binding_has_the_same_names():
+    for name in declared_symbols():
+        assert callable(getattr(gids, name)), name
+
+
+def test_host_only_entry_points():
+    # pure host arithmetic (Section 3.2, Eq. 2-3): N = r / (1 - r) * IOPS * (Ti + Tt)
+    n = gids.gids_accum_threshold(1.5e6, 25e-6, 5e-6, 0.95, 1)
+    assert abs(n - 855.0) < 1e-6
+    assert gids.gids_accum_threshold(1.5e6, 25e-6, 5e-6, 1.0, 1) < 0
+    # argument validation happens before any device call
+    with pytest.raises(gids.GidsError) as e:
+        gids.gids_store_create(100, 24, 8)
+    assert e.value.code == gids.GIDS_E_INVAL
+    with pytest.raises(gids.GidsError) as e:
+        gids.gids_store_create(100, 64, 3)
+    assert e.value.code == gids.GIDS_E_INVAL
+    with pytest.raises(gids.GidsError) as e:
+        gids.gids_cache_create(None, 16, 4, 64)
+    assert e.value.code == gids.GIDS_E_INVAL

@@ -1,0 +1,267 @@
+"""Parity of the HIP library (through its C ABI) with the CPU oracle: gathered
+tensor, distinct-ID list and per-minibatch hit / CPU-buffer-hit / miss / bypass
+counts, all bit-exact, plus the final tag and stamp of every cache line."""
+import numpy as np
+import pytest
+
+import workload as wl
+from workload import CONFIGS
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU (no CPU fallback exists)")
+    import paper_2306_16384_amd as gids
+    from paper_2306_16384_amd.session import GatherSession
+    gids.lib()
+    return torch, gids, GatherSession
+
+
+def run_case(gpu, oracle, feats, batches, *, id_dtype, lines, ways, line_bytes, window, threshold=0, hot=None,
+             use_head=False, with_inverse=False, check_state=True, label=""):
+    """Feeds the same raw ID lists to both implementations, protocol: keep window + 1 lists buffered."""
+    torch, gids, GatherSession = gpu
+    n_rows = feats.shape[0]
+    feats_u8 = np.ascontiguousarray(feats).view(np.uint8).reshape(n_rows, -1)
+    row_bytes = feats_u8.shape[1]
+    sim = oracle.Sim(n_rows, lines, ways, window, row_bytes, line_bytes, feats_u8)
+    print(f"[case {label}] rows={n_rows} R={row_bytes} L={line_bytes} lines={lines} ways={ways} W={window} "
+          f"thr={threshold} ids={np.dtype(id_dtype).name} batches={len(batches)}", flush=True)
+    if hot is not None and len(hot):
+        sim.set_hot(hot)
+    # the oracle's pass, on its own
+    want, pushed = [], 0
+    for t, raw in enumerate(batches):
+        while window and pushed < len(batches) and pushed <= t + window:
+            sim.push(batches[pushed])
+            pushed += 1
+        want.append(sim.gather(raw))
+    with GatherSession(n_rows, row_bytes, id_dtype, lines, ways, line_bytes, window, threshold) as ses:
+        ses.store_view()[:] = feats_u8
+        if hot is not None and len(hot):
+            ses.pin_hot(hot)
+        dev = [ses.to_device(b) for b in batches]
+        outs, uniqs, invs, seqs = [], [], [], []
+        pushed = 0
+        for t, raw in enumerate(batches):
+            while window and pushed < len(batches) and pushed <= t + window:
+                ses.push(dev[pushed])
+                pushed += 1
+            cap = max(len(raw), 1)
+            out = torch.full((cap, row_bytes), 0xA5, dtype=torch.uint8, device="cuda")
+            uq = torch.full((cap,), -7, dtype=ses.torch_id, device="cuda")
+            inv = torch.full((cap,), -1, dtype=torch.int32, device="cuda") if with_inverse else None
+            ids_arg = None if (use_head and window) else dev[t]
+            seqs.append(ses.gather(ids_arg, out, uq, inv if ids_arg is not None else None))
+            outs.append(out); uniqs.append(uq); invs.append(inv if ids_arg is not None else None)
+        ses.flush()
+        torch.cuda.synchronize()
+        for t, raw in enumerate(batches):
+            want_u, want_rows, want_stats = want[t]
+            st = ses.stats(seqs[t])
+            assert st.status == 0
+            assert st.as_tuple() == tuple(int(x) for x in want_stats), (label, t, st.as_tuple(), want_stats.tolist())
+            m = len(want_u)
+            got_u = uniqs[t][:m].cpu().numpy()
+            np.testing.assert_array_equal(got_u, want_u.astype(got_u.dtype), err_msg=f"{label} batch {t} unique")
+            got_rows = outs[t][:m].cpu().numpy()
+            assert np.array_equal(got_rows, want_rows), f"{label} batch {t}: gathered rows differ"
+            if m < outs[t].shape[0]:                          # nothing written past the distinct count
+                assert bool((outs[t][m:] == 0xA5).all())
+            if invs[t] is not None:
+                inv = invs[t][:len(raw)].cpu().numpy()
+                np.testing.assert_array_equal(want_u[inv], np.asarray(raw, dtype=np.int64))
+            if threshold == 0:
+                assert st.flushed == 1 and st.n_pending == 0
+        if check_state:
+            tags, stamps = ses.snapshot()
+            np.testing.assert_array_equal(tags, sim.tags, err_msg=f"{label} tags")
+            np.testing.assert_array_equal(stamps, sim.stamps, err_msg=f"{label} stamps")
+
+
+def zipf_batches(rng, n, n_batches, size, a=1.3):
+    return [np.minimum(rng.zipf(a, size=int(rng.integers(size // 2, size + 1))) - 1, n - 1).astype(np.int64)
+            for _ in range(n_batches)]
+
+
+def rand_feats(rng, n, row_bytes):
+    return rng.integers(0, 256, size=(n, row_bytes), dtype=np.uint8)
+
+
+# ------------------------------------------------------------------ configs
+
+def test_tiny_config_full_parity(gpu, oracle_mod):
+    cfg = CONFIGS["tiny"]
+    g = wl.make_graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max)
+    table = wl.normal_table(np.float32)
+    feats = wl.feature_rows(cfg.seed, np.arange(cfg.n_nodes), cfg.dim, table)
+    hot = wl.hot_nodes(g, cfg.cpu_rows)
+    batches = [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds) for b in range(cfg.n_batches)]
+    run_case(gpu, oracle_mod, feats, batches, id_dtype=np.int32, lines=cfg.cache_lines, ways=cfg.ways,
+             line_bytes=cfg.line_bytes, window=cfg.window, hot=hot, with_inverse=True, label="tiny")
+    run_case(gpu, oracle_mod, feats, batches, id_dtype=np.int32, lines=cfg.cache_lines, ways=cfg.ways,
+             line_bytes=cfg.line_bytes, window=cfg.window, hot=hot, use_head=True, label="tiny/head")
+
+
+def test_tiny_config_oracle_generated_inputs(gpu, oracle_mod):
+    """End to end from the seed with the oracle's own generator and sampler."""
+    cfg = CONFIGS["tiny"]
+    g = oracle_mod.Graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max)
+    table = wl.normal_table(np.float32)
+    feats = oracle_mod.feat_rows(cfg.seed, np.arange(cfg.n_nodes), cfg.dim, table)
+    batches = [g.sample(cfg.seed, b, cfg.fanouts, cfg.n_seeds) for b in range(cfg.n_batches)]
+    run_case(gpu, oracle_mod, feats, batches, id_dtype=np.int32, lines=cfg.cache_lines, ways=cfg.ways,
+             line_bytes=cfg.line_bytes, window=cfg.window, hot=g.hot_nodes(cfg.cpu_rows), label="tiny/oracle-inputs")
+
+
+def test_medium_config_first_batches(gpu, oracle_mod):
+    cfg = CONFIGS["medium"]
+    n = 200_000                                               # one fifth of the node count, every ratio kept
+    c = wl.scaled(cfg, n)
+    g = wl.make_graph(c.seed, n, c.ell, c.p4, min(n - 1, 65535))
+    table = wl.normal_table(np.float16)
+    feats = np.empty((n, c.dim), dtype=np.float16)
+    wl.fill_store(c.seed, n, c.dim, table, feats)
+    hot = wl.hot_nodes(g, c.cpu_rows)
+    batches = [wl.sample_minibatch(g, c.seed, b, c.fanouts, c.n_seeds) for b in range(24)]
+    run_case(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=c.cache_lines, ways=c.ways,
+             line_bytes=c.line_bytes, window=c.window, hot=hot, label="medium/5")
+
+
+# ------------------------------------------------------- shapes and policies
+
+@pytest.mark.parametrize("ways", [1, 2, 4, 8, 16, 64])
+def test_associativity_sweep(gpu, oracle_mod, ways):
+    rng = np.random.default_rng(100 + ways)
+    n = 3000
+    feats = rand_feats(rng, n, 256)
+    lines = ways * 37                                          # 37 sets: not a power of two
+    run_case(gpu, oracle_mod, feats, zipf_batches(rng, n, 14, 700, a=1.2), id_dtype=np.int64, lines=lines, ways=ways,
+             line_bytes=256, window=2, hot=rng.choice(n, 50, replace=False), label=f"ways{ways}")
+
+
+@pytest.mark.parametrize("window", [0, 1, 3, 9])
+@pytest.mark.parametrize("id_dtype", [np.int32, np.int64])
+def test_window_depths_and_id_widths(gpu, oracle_mod, window, id_dtype):
+    rng = np.random.default_rng(7 * window + np.dtype(id_dtype).itemsize)
+    n = 5000
+    feats = rand_feats(rng, n, 512)
+    run_case(gpu, oracle_mod, feats, zipf_batches(rng, n, 16, 900, a=1.15), id_dtype=id_dtype, lines=512, ways=4,
+             line_bytes=512, window=window, hot=rng.choice(n, 80, replace=False), label=f"W{window}")
+
+
+@pytest.mark.parametrize("row_bytes,line_bytes", [(16, 16), (64, 128), (528, 1024), (2048, 2048), (3072, 4096), (4096, 4096)])
+def test_row_and_line_sizes(gpu, oracle_mod, row_bytes, line_bytes):
+    rng = np.random.default_rng(row_bytes)
+    n = 2000
+    feats = rand_feats(rng, n, row_bytes)
+    run_case(gpu, oracle_mod, feats, zipf_batches(rng, n, 10, 600, a=1.25), id_dtype=np.int64, lines=256, ways=8,
+             line_bytes=line_bytes, window=2, hot=rng.choice(n, 30, replace=False), label=f"R{row_bytes}")
+
+
+def test_many_ids_per_set_needs_multiword_miss_mask(gpu, oracle_mod):
+    """A small cache over a long table: more than 64 IDs share a set."""
+    rng = np.random.default_rng(11)
+    n = 20_000
+    feats = rand_feats(rng, n, 64)
+    batches = [rng.integers(0, n, size=5000) for _ in range(8)]        # ~20 % of all IDs per minibatch: heavy bypass
+    run_case(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=4 * 50, ways=4, line_bytes=64, window=1,
+             label="multiword")
+
+
+def test_cache_as_large_as_store_all_hits_after_warmup(gpu, oracle_mod):
+    rng = np.random.default_rng(12)
+    n, ways, n_sets = 4096, 16, 256
+    feats = rand_feats(rng, n, 768)
+    batches = [rng.integers(0, n, size=6000) for _ in range(12)] + [np.arange(n)] * 2
+    run_case(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=ways * n_sets, ways=ways, line_bytes=1024,
+             window=3, label="resident")
+
+
+def test_degenerate_inputs(gpu, oracle_mod):
+    rng = np.random.default_rng(13)
+    n = 1000
+    feats = rand_feats(rng, n, 128)
+    batches = [np.array([], dtype=np.int64), np.array([n - 1]), np.full(5000, 17), np.arange(n), np.array([0, n - 1, 0]),
+               np.array([], dtype=np.int64), rng.integers(0, n, 257), rng.integers(0, n, 2049)]
+    for window in (0, 2):
+        run_case(gpu, oracle_mod, feats, batches, id_dtype=np.int32, lines=64, ways=4, line_bytes=128, window=window,
+                 hot=np.array([0, 17, n - 1]), with_inverse=True, label=f"degenerate/W{window}")
+
+
+def test_long_raw_list_many_tiles(gpu, oracle_mod):
+    """Raw lists spanning many workgroup tiles with heavy repetition (hub nodes)."""
+    rng = np.random.default_rng(14)
+    n = 300_000
+    feats = rand_feats(rng, n, 64)
+    batches = [np.minimum(rng.zipf(1.1, size=700_001) - 1, n - 1) for _ in range(3)]
+    run_case(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=8 * 1024, ways=8, line_bytes=64, window=1,
+             hot=np.arange(0, 2000, 3), with_inverse=True, label="long")
+
+
+# ---------------------------------------------------------------- accumulator
+
+@pytest.mark.parametrize("threshold", [1, 300, 100_000])
+@pytest.mark.parametrize("window", [0, 3])
+def test_accumulator_changes_nothing(gpu, oracle_mod, threshold, window):
+    """Section 3.2: merging the fills of consecutive minibatches is a scheduling
+    choice; counters and tensors are those of the unmerged run."""
+    rng = np.random.default_rng(1000 + threshold + window)
+    n = 6000
+    feats = rand_feats(rng, n, 256)
+    run_case(gpu, oracle_mod, feats, zipf_batches(rng, n, 30, 400, a=1.2), id_dtype=np.int64, lines=128, ways=4,
+             line_bytes=256, window=window, threshold=threshold, hot=rng.choice(n, 60, replace=False),
+             label=f"accum{threshold}/W{window}")
+
+
+# ------------------------------------------------------------------- errors
+
+def test_device_found_errors(gpu, oracle_mod):
+    torch, gids, GatherSession = gpu
+    feats = np.arange(100 * 64, dtype=np.uint8).reshape(100, 64)
+
+    def fresh(window):
+        s = GatherSession(100, 64, np.int64, 16, 4, 64, window)
+        s.store_view()[:] = feats
+        return s
+
+    out = torch.zeros((8, 64), dtype=torch.uint8, device="cuda")
+    # an ID outside the table
+    with fresh(0) as s:
+        seq = s.gather(s.to_device([1, 100]), out)
+        with pytest.raises(gids.GidsError) as e:
+            s.stats(seq)
+        assert e.value.code == gids.GIDS_E_RANGE
+        with pytest.raises(gids.GidsError) as e:                # sticky afterwards
+            s.gather(s.to_device([1]), out)
+        assert e.value.code == gids.GIDS_E_RANGE
+    # more distinct IDs than output rows
+    with fresh(0) as s:
+        seq = s.gather(s.to_device(np.arange(9)), out)
+        with pytest.raises(gids.GidsError) as e:
+            s.stats(seq)
+        assert e.value.code == gids.GIDS_E_SPACE
+        assert bool((out == 0).all())
+    # window protocol
+    with fresh(1) as s:
+        with pytest.raises(gids.GidsError) as e:
+            s.gather(s.to_device([1]), out)
+        assert e.value.code == gids.GIDS_E_ORDER                # nothing buffered
+        s.push(s.to_device([1, 2]))
+        s.push(s.to_device([3]))
+        with pytest.raises(gids.GidsError) as e:
+            s.push(s.to_device([4]))
+        assert e.value.code == gids.GIDS_E_FULL
+        seq = s.gather(s.to_device([3]), out)                   # not the head
+        with pytest.raises(gids.GidsError) as e:
+            s.stats(seq)
+        assert e.value.code == gids.GIDS_E_ORDER
+        assert bool((out == 0).all())
+    with fresh(0) as s:
+        with pytest.raises(gids.GidsError) as e:
+            s.push(s.to_device([1]))
+        assert e.value.code == gids.GIDS_E_INVAL
