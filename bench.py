@@ -1,0 +1,269 @@
+#!/usr/bin/env python3
+"""Benchmark of the minibatch feature gather on one MI355X.
+
+One "step" = one pass of the whole hot path over one minibatch of synthetic
+input: the gather of minibatch t (ID dedup/sort, window pop, CPU-buffer lookup,
+tag probe, victim selection, line fills from the host store, hit scatter,
+counters) plus the window push of minibatch t + W + 1 that keeps the look-ahead
+full.  Sampling and graph generation are outside the timed region; every input
+(raw ID lists, feature store) is resident before it starts (ID lists in HBM, the
+store in pinned host memory, where the method keeps it).
+
+Prints ONE JSON line: gathered GB/s (distinct IDs x row bytes / time), with the
+hit/miss-weighted roofline (HBM peak for bytes that stay in HBM, host-link peak
+for bytes that cross the link), the row mover's own roofline from HIP events on
+the launch stream, and the CPU oracle timed on the machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+LINK_PEAK_GBS = 64.0         # PCIe Gen5 x16, nominal per direction (the box negotiates 32 GT/s x16)
+
+# HBM traffic of the row mover per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# command (see profiles/); None until such a run exists for the workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(*a):
+    print("[bench]", *a, file=sys.stderr, flush=True)
+
+
+def pick_scale(cfg, wl, max_pinned_gib: float):
+    """Largest node count whose store + CPU buffer fit the pinned-memory limit, ratios kept."""
+    need = lambda c: (c.n_nodes * c.row_bytes + c.cpu_rows * c.row_bytes) / 2**30
+    if need(cfg) <= max_pinned_gib:
+        return cfg
+    n = cfg.n_nodes
+    while True:
+        n = int(n * 0.9) // 1_000_000 * 1_000_000 if n > 2_000_000 else int(n * 0.9)
+        c = wl.scaled(cfg, n)
+        if need(c) <= max_pinned_gib:
+            return c
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=12)
+    ap.add_argument("--workload", default="large", choices=["tiny", "medium", "large", "resident", "skew"])
+    ap.add_argument("--nodes", type=int, default=0, help="override the node count (ratios kept)")
+    ap.add_argument("--max-pinned-gib", type=float, default=60.0,
+                    help="pinned host memory the box grants one process (store + CPU buffer must fit)")
+    ap.add_argument("--window", type=int, default=-1, help="override the window depth")
+    ap.add_argument("--accum", type=int, default=0, help="accumulator threshold (0 = every gather moves its own rows)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="time budget of the oracle leg")
+    ap.add_argument("--pass-ids", action="store_true",
+                    help="hand the raw ID list to gather again (it is then deduplicated a second time and checked "
+                         "against the window head); default with a window: gather the buffered head list")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-check", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the gather shards by minibatch, one cache per GPU; "
+              "no multi-GPU path is built). Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+    import workload as wl
+    import paper_2306_16384_amd as gids
+    from paper_2306_16384_amd.session import GatherSession
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the gather has no CPU path", file=sys.stderr)
+        return 2
+    gids.lib()
+    wl.native.build()
+
+    base = wl.CONFIGS[args.workload]
+    cfg = wl.scaled(base, args.nodes) if args.nodes else pick_scale(base, wl, args.max_pinned_gib)
+    window = cfg.window if args.window < 0 else args.window
+    R = cfg.row_bytes
+    steps, warmup = args.steps, args.warmup
+    n_batches = warmup + 2 * steps + window + 1                # timed pass + profiled pass + look-ahead
+    log(f"workload {cfg.name}: N={cfg.n_nodes} R={R} lines={cfg.cache_lines} ways={cfg.ways} L={cfg.line_bytes} "
+        f"cpu_rows={cfg.cpu_rows} W={window} fanouts={cfg.fanouts} seeds={cfg.n_seeds}")
+
+    t0 = time.time()
+    g = wl.make_graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max, np.dtype(cfg.index_dtype), native=True)
+    log(f"graph: {g.n_edges} edges, mean degree {g.n_edges / g.n:.2f} ({time.time() - t0:.1f} s)")
+    t0 = time.time()
+    hot = wl.hot_nodes(g, cfg.cpu_rows)
+    log(f"hot nodes: {len(hot)} ({time.time() - t0:.1f} s)")
+    rank_table = wl.synth.zipf_rank_table(cfg.n_nodes, cfg.seed_zipf_s) if cfg.seed_zipf_s is not None else None
+    t0 = time.time()
+    raws = [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds, rank_table) for b in range(n_batches)]
+    max_raw = max(len(r) for r in raws)
+    log(f"sampled {n_batches} minibatches, raw IDs per minibatch <= {max_raw} ({time.time() - t0:.1f} s)")
+
+    table = wl.normal_table(np.dtype(cfg.feat_dtype))
+    t0 = time.time()
+    ses = GatherSession(cfg.n_nodes, R, np.dtype(cfg.index_dtype), cfg.cache_lines, cfg.ways, cfg.line_bytes, window,
+                        args.accum)
+    wl.fill_store(cfg.seed, cfg.n_nodes, cfg.dim, table, ses.store_address())
+    log(f"store: {cfg.n_nodes * R / 1e9:.2f} GB pinned and filled ({time.time() - t0:.1f} s)")
+    t0 = time.time()
+    ses.pin_hot(hot)
+    ses.reserve(max_raw)
+    log(f"CPU buffer pinned: {len(hot) * R / 1e9:.2f} GB ({time.time() - t0:.1f} s)")
+
+    dev = [ses.to_device(r) for r in raws]
+    cap_rows = max(len(np.unique(r)) for r in raws)
+    # outputs rotate; with the accumulator on, an output must survive until the flush that completes it
+    ring = 2 if args.accum == 0 else 32
+    outs = [torch.empty((cap_rows, R), dtype=torch.uint8, device="cuda") for _ in range(ring)]
+    uniq = torch.empty(cap_rows, dtype=ses.torch_id, device="cuda")
+    torch.cuda.synchronize()
+
+    pushed = 0
+
+    def keep_window_full(t):
+        nonlocal pushed
+        while window and pushed < n_batches and pushed <= t + window:
+            ses.push(dev[pushed])
+            pushed += 1
+
+    def step(t):
+        keep_window_full(t)                                     # push of minibatch t + W (+1 at start-up)
+        seq = ses.gather(dev[t] if (args.pass_ids or not window) else None, outs[t % ring], uniq)
+        if args.accum and t % ring == ring - 2:
+            ses.flush()
+        return seq
+
+    seqs = {}
+    for t in range(warmup):
+        seqs[t] = step(t)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for t in range(warmup, warmup + steps):
+        seqs[t] = step(t)
+    ses.flush()
+    e1.record()
+    torch.cuda.synchronize()
+    total_ms = e0.elapsed_time(e1)
+
+    stats = {t: ses.stats(seqs[t]) for t in range(max(0, warmup + steps - 60), warmup + steps)}
+    timed = [stats[t] for t in range(warmup, warmup + steps) if t in stats]
+    if len(timed) != steps:
+        log("note: only the last 60 gathers keep their counters; use --steps <= 60 for exact accounting")
+    n_unique = sum(s.n_unique for s in timed)
+    n_hit = sum(s.n_hit for s in timed)
+    n_cpu = sum(s.n_cpu_hit for s in timed)
+    n_miss = sum(s.n_miss for s in timed)
+    n_byp = sum(s.n_bypass for s in timed)
+    scale = steps / max(1, len(timed))
+    link_bytes = (n_cpu + n_miss) * R * scale
+    hbm_bytes = (2 * n_hit + n_cpu + 2 * (n_miss - n_byp) + n_byp) * R * scale
+    gathered_bytes = n_unique * R * scale
+    t_roof_ms = (link_bytes / (LINK_PEAK_GBS * 1e9) + hbm_bytes / (HBM_PEAK_GBS * 1e9)) * 1e3
+    t_overlap_ms = max(link_bytes / (LINK_PEAK_GBS * 1e9), hbm_bytes / (HBM_PEAK_GBS * 1e9)) * 1e3
+    value = gathered_bytes / (total_ms * 1e-3) / 1e9
+
+    # second pass with per-phase HIP events (on the launch stream) for the row mover's own roofline
+    gids.gids_profile_enable(ses.cache, True)
+    pseq = {}
+    for t in range(warmup + steps, warmup + 2 * steps):
+        pseq[t] = step(t)
+    ses.flush()
+    torch.cuda.synchronize()
+    gids.gids_profile_enable(ses.cache, False)
+    keep = sorted(pseq)[-min(steps, 60):]
+    ph = np.array([gids.gids_profile_read(ses.cache, pseq[t]) for t in keep])
+    pst = [ses.stats(pseq[t]) for t in keep]
+    mv_ms = float(ph[:, 2].mean())
+    mv_link = np.mean([(s.n_cpu_hit + s.n_miss) * R for s in pst])
+    mv_hbm = np.mean([(2 * s.n_hit + s.n_cpu_hit + 2 * (s.n_miss - s.n_bypass) + s.n_bypass) * R for s in pst])
+    link_bound = mv_link / LINK_PEAK_GBS >= mv_hbm / HBM_PEAK_GBS
+    if link_bound:
+        roof = {"bound": "host_link", "achieved": mv_link / (mv_ms * 1e-3) / 1e9, "peak": LINK_PEAK_GBS}
+    else:
+        roof = {"bound": "hbm", "achieved": mv_hbm / (mv_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS}
+    roof.update({"unit": "GB/s", "frac": roof["achieved"] / roof["peak"], "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
+                 "kernel": "move_kernel", "avg_ms": mv_ms, "link_bytes_per_launch": float(mv_link),
+                 "hbm_bytes_per_launch": float(mv_hbm),
+                 "phase_ms": {"dedup": float(ph[:, 0].mean()), "probe_victim": float(ph[:, 1].mean()), "move": mv_ms}})
+
+    result = {
+        "metric": "gathered feature GB/s per minibatch (distinct IDs x row bytes / time), steady state",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": total_ms / steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "unique_ids_per_s": n_unique * scale / (total_ms * 1e-3),
+        "config": {"workload": cfg.name, "n_nodes": cfg.n_nodes, "row_bytes": R, "cache_lines": cfg.cache_lines,
+                   "ways": cfg.ways, "line_bytes": cfg.line_bytes, "cpu_buffer_rows": cfg.cpu_rows, "window": window,
+                   "fanouts": list(cfg.fanouts), "seeds_per_batch": cfg.n_seeds, "accum_threshold": args.accum,
+                   "id_dtype": cfg.index_dtype, "scaled_from": base.n_nodes if cfg.n_nodes != base.n_nodes else None},
+        "per_step": {"unique": n_unique * scale / steps, "hit": n_hit * scale / steps, "cpu_hit": n_cpu * scale / steps,
+                     "miss": n_miss * scale / steps, "bypass": n_byp * scale / steps},
+        "weighted_roofline": {"hbm_peak_GBs": HBM_PEAK_GBS, "link_peak_GBs": LINK_PEAK_GBS,
+                              "t_roof_ms_per_step": t_roof_ms / steps, "frac": t_roof_ms / total_ms,
+                              "frac_overlap_bound": t_overlap_ms / total_ms,
+                              "roofline_gathered_GBs": gathered_bytes / (t_roof_ms * 1e-3) / 1e9},
+        "roofline": roof,
+    }
+
+    # sampled check of the timed configuration against the definition (row = closed-form feature row)
+    if not args.no_check:
+        import oracle
+        t_last = warmup + 2 * steps - 1
+        st = ses.stats(pseq[t_last])
+        u = uniq[:st.n_unique].cpu().numpy().astype(np.int64)
+        assert np.array_equal(u, np.unique(raws[t_last])), "distinct-ID list differs from sort-unique of the input"
+        pick = np.unique(np.linspace(0, len(u) - 1, 64).astype(np.int64))
+        got = outs[t_last % ring][torch.from_numpy(pick).cuda()].cpu().numpy()
+        want = oracle.feat_rows(cfg.seed, u[pick], cfg.dim, table).view(np.uint8).reshape(len(pick), R)
+        assert np.array_equal(got, want), "gathered rows differ from the closed-form feature rows"
+        result["check"] = f"last minibatch: ID list exact, {len(pick)} sampled rows equal the oracle's closed form"
+
+    # the oracle on this machine's host cores, same ID lists, bounded time
+    if not args.no_cpu:
+        import oracle
+        oracle.build()
+        store_np = ses.store_view()
+        sim = oracle.Sim(cfg.n_nodes, cfg.cache_lines, cfg.ways, window, R, cfg.line_bytes, store_np)
+        sim.set_hot(hot)
+        opushed, done, o_unique, o_time = 0, 0, 0, 0.0
+        mismatches = 0
+        budget_end = time.time() + args.cpu_seconds
+        for t in range(warmup + steps):
+            while window and opushed < n_batches and opushed <= t + window:
+                sim.push(raws[opushed])
+                opushed += 1
+            ts = time.perf_counter()
+            u, rows, ost = sim.gather(raws[t])
+            dt = time.perf_counter() - ts
+            if t in stats and tuple(int(x) for x in ost) != stats[t].as_tuple():
+                mismatches += 1
+            if t >= min(warmup, 2):                             # skip the cold start like the GPU leg
+                o_unique += len(u)
+                o_time += dt
+                done += 1
+            if time.time() > budget_end and done >= 1:
+                break
+        result["cpu_baseline"] = {
+            "value": o_unique * R / o_time / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "unique_ids_per_s": o_unique / o_time, "host_cores_on_box": os.cpu_count(),
+            "sample": f"{done} minibatches of this workload (gather only: sort-unique, cache simulation, row copy; "
+                      f"window pushes and sampling excluded), single thread",
+            "count_mismatches_vs_gpu": mismatches}
+        if mismatches:
+            log(f"WARNING: {mismatches} minibatches differ from the oracle's counters")
+    ses.close()
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

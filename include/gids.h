@@ -130,9 +130,9 @@ int gids_window_push(gids_cache* cache, const void* ids_dev, uint64_t n, void* s
  *                    ID, rows packed at row_bytes; out_capacity_rows rows are
  *                    available (GIDS_E_SPACE in stats when there are more
  *                    distinct IDs; n rows always suffice)
- *   unique_dev       NULL, or room for min(n, out_capacity_rows)... at least as
- *                    many IDs as there are distinct ones (n always suffices):
- *                    receives them ascending
+ *   unique_dev       NULL, or room for min(n, out_capacity_rows) IDs (with
+ *                    ids_dev == NULL: out_capacity_rows IDs): receives the
+ *                    distinct IDs, ascending
  *   inverse_dev      NULL, or n uint32: inverse_dev[i] = j with
  *                    unique[j] == ids_dev[i] (requires ids_dev)
  * With accum_threshold > 0 the output buffers of gathers not yet flushed must
@@ -156,6 +156,16 @@ uint64_t gids_cache_gathers(const gids_cache* cache);
  * the tag (int64, -1 = empty) and last-use stamp (int64, -1 = never) of every
  * line to host arrays of `lines` entries each.  Either may be NULL. */
 int gids_cache_snapshot(gids_cache* cache, int64_t* tags_host, int64_t* stamps_host);
+
+/* Per-phase device time of each gather, for benchmarks and profiling.  When
+ * enabled, gids_gather records HIP events on the caller's stream between its
+ * three phases; gids_profile_read waits for gather `seq` and writes
+ * milliseconds to ms3: [0] ID dedup/sort (+ window check, inverse map),
+ * [1] CPU-buffer lookup + tag probe + victim selection, [2] row movement
+ * (hit scatter, line fills, CPU-buffer rows; the accumulator's queueing and
+ * flush when accum_threshold > 0).  Off by default. */
+int gids_profile_enable(gids_cache* cache, int on);
+int gids_profile_read(gids_cache* cache, uint64_t seq, float* ms3);
 
 /* Number of in-flight fills an accumulator needs so that a storage device of
  * `iops_peak` requests/s per device sustains `ratio` of its peak, given the

@@ -15,7 +15,7 @@ GIDS_E_INVAL, GIDS_E_NOMEM, GIDS_E_RANGE, GIDS_E_ORDER, GIDS_E_FULL, GIDS_E_HIP,
 EXPORTS = [
     "gids_store_create", "gids_store_host_ptr", "gids_store_destroy", "gids_cache_create", "gids_cache_destroy",
     "gids_cache_reserve", "gids_cpu_buffer_pin", "gids_window_push", "gids_gather", "gids_flush", "gids_stats_read",
-    "gids_cache_gathers", "gids_cache_snapshot", "gids_accum_threshold", "gids_last_error",
+    "gids_cache_gathers", "gids_cache_snapshot", "gids_profile_enable", "gids_profile_read", "gids_accum_threshold", "gids_last_error",
 ]
 
 
@@ -62,6 +62,8 @@ def lib() -> C.CDLL:
         L.gids_cache_gathers.restype = u64
         L.gids_cache_gathers.argtypes = [vp]
         L.gids_cache_snapshot.argtypes = [vp, vp, vp]
+        L.gids_profile_enable.argtypes = [vp, C.c_int]
+        L.gids_profile_read.argtypes = [vp, u64, C.POINTER(C.c_float)]
         L.gids_accum_threshold.restype = C.c_double
         L.gids_accum_threshold.argtypes = [C.c_double, C.c_double, C.c_double, C.c_double, C.c_int]
         L.gids_last_error.restype = C.c_char_p
@@ -133,6 +135,17 @@ def gids_cache_gathers(cache: int) -> int:
 
 def gids_cache_snapshot(cache: int, tags_host_ptr: int | None, stamps_host_ptr: int | None) -> None:
     _check(lib().gids_cache_snapshot(cache, tags_host_ptr, stamps_host_ptr))
+
+
+def gids_profile_enable(cache: int, on: bool) -> None:
+    _check(lib().gids_profile_enable(cache, 1 if on else 0))
+
+
+def gids_profile_read(cache: int, seq: int):
+    """-> (dedup ms, probe + victim ms, row movement ms) of gather `seq`"""
+    ms = (C.c_float * 3)()
+    _check(lib().gids_profile_read(cache, seq, ms))
+    return tuple(float(x) for x in ms)
 
 
 def gids_accum_threshold(iops_peak: float, t_initial: float, t_termination: float, ratio: float, n_ssd: int = 1) -> float:

@@ -94,6 +94,16 @@ struct gids_cache {
     hipEvent_t events[STATS_RING] = {};
     hipStream_t last_stream = nullptr;
     int move_blocks = 2048;
+    // optional per-phase timing of each gather (events on the caller's stream)
+    bool profile = false;
+    hipEvent_t prof_events[STATS_RING][4] = {};
+    bool prof_valid[STATS_RING] = {};
+    int mark_phase(int ring, int phase, hipStream_t s) {
+        if (!profile) return GIDS_OK;
+        if (!prof_events[ring][phase]) HIP_TRY(hipEventCreate(&prof_events[ring][phase]));
+        HIP_TRY(hipEventRecord(prof_events[ring][phase], s));
+        return GIDS_OK;
+    }
 };
 
 namespace {
@@ -118,7 +128,6 @@ struct CacheT final : gids_cache {
     uint64_t cap_n = 0;
     IdT* ubuf = nullptr;
     uint64_t* plan = nullptr;
-    uint32_t* misslist = nullptr;
     // accumulator queues
     uint64_t queue_cap = 0;
     FillOp* fills = nullptr;
@@ -135,12 +144,13 @@ struct CacheT final : gids_cache {
         (void)hipDeviceSynchronize();
         dev_free(tags); dev_free(stamps); dev_free(pending); dev_free(reuse); dev_free(missmask); dev_free(bitmap);
         dev_free(wrank); dev_free(hotbits); dev_free(hotrank); dev_free(cache_data); dev_free(ctl);
-        dev_free(blocksum); dev_free(blockoff); dev_free(ubuf); dev_free(plan); dev_free(misslist);
+        dev_free(blocksum); dev_free(blockoff); dev_free(ubuf); dev_free(plan);
         dev_free(fills); dev_free(copies);
         for (auto& s : slots) if (s.ids) (void)hipFree(s.ids);
         if (cpubuf_host) (void)hipHostFree(cpubuf_host);
         if (ring_host) (void)hipHostFree(ring_host);
         for (auto& e : events) if (e) (void)hipEventDestroy(e);
+        for (auto& row : prof_events) for (auto& e : row) if (e) (void)hipEventDestroy(e);
     }
 
     CacheView<IdT> view() const {
@@ -198,12 +208,11 @@ struct CacheT final : gids_cache {
         if (n < 1) n = 1;
         if (n > cap_n) {
             HIP_TRY(hipDeviceSynchronize());
-            dev_free(ubuf); dev_free(plan); dev_free(misslist);
+            dev_free(ubuf); dev_free(plan);
             const uint64_t want = std::max<uint64_t>(n, cap_n + cap_n / 2);
             int rc;
             if ((rc = dev_alloc(&ubuf, want))) return rc;
             if ((rc = dev_alloc(&plan, want))) return rc;
-            if ((rc = dev_alloc(&misslist, want))) return rc;
             cap_n = want;
         }
         if (threshold && threshold + n > queue_cap) {
@@ -322,6 +331,10 @@ struct CacheT final : gids_cache {
         const uint32_t* n_u;
         uint64_t n_upper;
         bool pop = false;
+        const int r = (int)(seq % STATS_RING);
+        prof_valid[r] = false;
+        int prc = mark_phase(r, 0, s);
+        if (prc) return prc;
         if (window) {
             if (count == 0) return fail(GIDS_E_ORDER, "gids_gather: no minibatch is buffered in the window");
             WindowSlot& h = slots[head];
@@ -357,8 +370,10 @@ struct CacheT final : gids_cache {
         }
         n_upper = std::min<uint64_t>(n_upper, store->n_rows);
         const CacheView<IdT> c = view();
-        launch_probe<IdT>(c, U, n_u, n_upper, out_cap, static_cast<IdT*>(unique), pop, plan, misslist, s);
-        launch_victim<IdT>(c, U, n_upper, plan, misslist, s);
+        if ((prc = mark_phase(r, 1, s))) return prc;
+        launch_probe<IdT>(c, U, n_u, n_upper, out_cap, static_cast<IdT*>(unique), pop, plan, s);
+        launch_victim<IdT>(c, U, n_u, n_upper, plan, s);
+        if ((prc = mark_phase(r, 2, s))) return prc;
         if (threshold == 0) {
             launch_move<IdT>(c, U, n_u, n_upper, plan, static_cast<char*>(out), move_blocks, s);
         } else {
@@ -366,7 +381,8 @@ struct CacheT final : gids_cache {
                               move_blocks, s);
             launch_flush<IdT>(c, fills, copies, threshold, false, move_blocks, s);
         }
-        const int r = (int)(seq % STATS_RING);
+        if ((prc = mark_phase(r, 3, s))) return prc;
+        prof_valid[r] = profile;
         launch_finalize(ctl, ring_dev + r, seq, n_u, s);
         HIP_TRY(hipEventRecord(events[r], s));
         seq++;
@@ -522,6 +538,22 @@ int gids_stats_read(gids_cache* cache, uint64_t seq, gids_stats* stats) {
         cache->sticky = rec.status;
         return fail(rec.status, "gather %llu failed on the device with code %d", (unsigned long long)seq, rec.status);
     }
+    return GIDS_OK;
+}
+
+int gids_profile_enable(gids_cache* cache, int on) {
+    if (!cache) return fail(GIDS_E_INVAL, "gids_profile_enable: cache is NULL");
+    cache->profile = on != 0;
+    return GIDS_OK;
+}
+
+int gids_profile_read(gids_cache* cache, uint64_t seq, float* ms3) {
+    if (!cache || !ms3) return fail(GIDS_E_INVAL, "gids_profile_read: NULL argument");
+    if (seq >= cache->seq || seq + STATS_RING < cache->seq) return fail(GIDS_E_INVAL, "gids_profile_read: gather %llu is not available", (unsigned long long)seq);
+    const int r = (int)(seq % STATS_RING);
+    if (!cache->prof_valid[r]) return fail(GIDS_E_INVAL, "gids_profile_read: gather %llu was not profiled", (unsigned long long)seq);
+    HIP_TRY(hipEventSynchronize(cache->prof_events[r][3]));
+    for (int k = 0; k < 3; k++) HIP_TRY(hipEventElapsedTime(&ms3[k], cache->prof_events[r][k], cache->prof_events[r][k + 1]));
     return GIDS_OK;
 }
 

@@ -8,7 +8,7 @@
 //           wavefront compare one set's tags in one coalesced load and a ballot
 //           names the matching way.  Hits stamp their line with the minibatch
 //           index; misses set one bit (set, id / n_sets) in a per-set miss
-//           mask and join the miss list.  The probe also takes this
+//           mask.  The probe also takes this
 //           minibatch's own entry out of the per-node future-reuse counters
 //           ("decreased each time the node is reused").
 //   victim  a miss's rank among the misses of its set is a popcount of the
@@ -54,7 +54,8 @@ template <typename IdT>
 __global__ __launch_bounds__(CT_THREADS) void probe_kernel(CacheView<IdT> c, const IdT* __restrict__ unique,
                                                            const uint32_t* __restrict__ n_u_ptr, uint64_t out_capacity,
                                                            IdT* __restrict__ unique_out, int pop_window,
-                                                           uint64_t* __restrict__ plan, uint32_t* __restrict__ misslist) {
+                                                           uint64_t* __restrict__ plan) {
+    __shared__ uint32_t block_cnt[3];
     Ctl* ctl = c.ctl;
     if (ctl->error) return;                                  // set only by earlier kernels: uniform
     const uint32_t n_u = *n_u_ptr;
@@ -62,6 +63,8 @@ __global__ __launch_bounds__(CT_THREADS) void probe_kernel(CacheView<IdT> c, con
         if (blockIdx.x == 0 && threadIdx.x == 0) ctl->error = 7u; /* -GIDS_E_SPACE; finalize reports it */
         return;
     }
+    if (threadIdx.x < 3) block_cnt[threadIdx.x] = 0;
+    __syncthreads();
     const uint32_t ways = c.ways, lg = c.lg_ways;
     const uint32_t per_wave = 64u >> lg;                     // IDs a wavefront classifies at once
     const uint32_t sub = lane_id() & (ways - 1);             // this lane's way
@@ -95,15 +98,6 @@ __global__ __launch_bounds__(CT_THREADS) void probe_kernel(CacheView<IdT> c, con
         if (valid && !hot) match = (uint64_t)c.tags[set * ways + sub] == v;   // empty lines hold -1
         const uint64_t gb = group_bits(__ballot(match), ways);
         const bool is_hit = gb != 0;
-        const bool is_miss = valid && leader && !hot && !is_hit;
-        // wave-aggregated append to the miss list
-        const uint64_t mb = __ballot(is_miss);
-        uint32_t mbase = 0;
-        if (mb) {
-            if (lane_id() == (uint32_t)(__ffsll((unsigned long long)mb) - 1))
-                mbase = atomicAdd(&ctl->n_miss, (uint32_t)__popcll(mb));
-            mbase = __shfl(mbase, __ffsll((unsigned long long)mb) - 1);
-        }
         if (valid && leader) {
             if (hot) {
                 plan[j] = (PLAN_CPU << PLAN_SHIFT) | slot;
@@ -117,12 +111,11 @@ __global__ __launch_bounds__(CT_THREADS) void probe_kernel(CacheView<IdT> c, con
                 plan[j] = PLAN_MISS_TBD << PLAN_SHIFT;
                 atomicOr(reinterpret_cast<unsigned long long*>(c.missmask) + set * c.words_per_set + (round >> 6),
                          1ull << (round & 63));
-                misslist[mbase + (uint32_t)__popcll(mb & ((1ull << lane_id()) - 1))] = (uint32_t)j;
                 misses++;
             }
         }
     }
-    // one atomic per wave and counter
+    // one global atomic per block and counter (same-address atomics serialise in L2)
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) {
         hits += __shfl_down(hits, d);
@@ -130,19 +123,28 @@ __global__ __launch_bounds__(CT_THREADS) void probe_kernel(CacheView<IdT> c, con
         misses += __shfl_down(misses, d);
     }
     if (lane_id() == 0) {
-        if (hits) atomicAdd(&ctl->cnt_hit, hits);
-        if (cpus) atomicAdd(&ctl->cnt_cpu, cpus);
-        if (misses) atomicAdd(&ctl->cnt_miss, misses);
+        if (hits) atomicAdd(&block_cnt[0], hits);
+        if (cpus) atomicAdd(&block_cnt[1], cpus);
+        if (misses) atomicAdd(&block_cnt[2], misses);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        if (block_cnt[0]) atomicAdd(&ctl->cnt_hit, block_cnt[0]);
+        if (block_cnt[1]) atomicAdd(&ctl->cnt_cpu, block_cnt[1]);
+        if (block_cnt[2]) atomicAdd(&ctl->cnt_miss, block_cnt[2]);
     }
 }
 
 template <typename IdT>
 __global__ __launch_bounds__(CT_THREADS) void victim_kernel(CacheView<IdT> c, const IdT* __restrict__ unique,
-                                                            uint64_t* __restrict__ plan,
-                                                            const uint32_t* __restrict__ misslist) {
+                                                            const uint32_t* __restrict__ n_u_ptr,
+                                                            uint64_t* __restrict__ plan) {
+    __shared__ uint32_t block_byp;
     Ctl* ctl = c.ctl;
-    if (ctl->error) return;
-    const uint32_t n_miss = ctl->n_miss;
+    if (ctl->error || ctl->cnt_miss == 0) return;            // cnt_miss is final: the probe has ended
+    if (threadIdx.x == 0) block_byp = 0;
+    __syncthreads();
+    const uint32_t n_u = *n_u_ptr;
     const uint32_t ways = c.ways, lg = c.lg_ways;
     const uint32_t per_wave = 64u >> lg;
     const uint32_t sub = lane_id() & (ways - 1);
@@ -151,10 +153,10 @@ __global__ __launch_bounds__(CT_THREADS) void victim_kernel(CacheView<IdT> c, co
     const uint64_t wave0 = ((uint64_t)blockIdx.x * CT_THREADS + threadIdx.x) >> 6;
     const uint64_t n_waves = ((uint64_t)gridDim.x * CT_THREADS) >> 6;
     uint32_t bypasses = 0;
-    for (uint64_t chunk = wave0; chunk * per_wave < n_miss; chunk += n_waves) {
-        const uint64_t i = chunk * per_wave + (lane_id() >> lg);
-        const bool valid = i < n_miss;
-        const uint32_t j = valid ? misslist[i] : 0;
+    for (uint64_t chunk = wave0; chunk * per_wave < n_u; chunk += n_waves) {
+        const uint64_t j = chunk * per_wave + (lane_id() >> lg);
+        const bool valid = j < n_u && (plan[j] >> PLAN_SHIFT) == PLAN_MISS_TBD;
+        if (!__ballot(valid)) continue;                      // no miss among this wave's IDs
         const uint64_t v = valid ? (uint64_t)unique[j] : 0;
         uint64_t set = 0, round = 0;
         set_and_round(c, v, &set, &round);
@@ -194,7 +196,9 @@ __global__ __launch_bounds__(CT_THREADS) void victim_kernel(CacheView<IdT> c, co
     }
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) bypasses += __shfl_down(bypasses, d);
-    if (lane_id() == 0 && bypasses) atomicAdd(&ctl->cnt_bypass, bypasses);
+    if (lane_id() == 0 && bypasses) atomicAdd(&block_byp, bypasses);
+    __syncthreads();
+    if (threadIdx.x == 0 && block_byp) atomicAdd(&ctl->cnt_bypass, block_byp);
 }
 
 inline uint32_t grid_for(uint64_t groups, uint32_t ways, uint32_t cap) {
@@ -208,23 +212,22 @@ inline uint32_t grid_for(uint64_t groups, uint32_t ways, uint32_t cap) {
 
 template <typename IdT>
 void launch_probe(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_u, uint64_t n_upper,
-                  uint64_t out_capacity, IdT* unique_out, bool pop_window, uint64_t* plan, uint32_t* misslist,
-                  hipStream_t s) {
-    hipLaunchKernelGGL(probe_kernel<IdT>, dim3(grid_for(n_upper, c.ways, 4096)), dim3(CT_THREADS), 0, s, c, unique,
-                       n_u, out_capacity, unique_out, pop_window ? 1 : 0, plan, misslist);
+                  uint64_t out_capacity, IdT* unique_out, bool pop_window, uint64_t* plan, hipStream_t s) {
+    hipLaunchKernelGGL(probe_kernel<IdT>, dim3(grid_for(n_upper, c.ways, 2048)), dim3(CT_THREADS), 0, s, c, unique,
+                       n_u, out_capacity, unique_out, pop_window ? 1 : 0, plan);
 }
 
 template <typename IdT>
-void launch_victim(const CacheView<IdT>& c, const IdT* unique, uint64_t n_upper, uint64_t* plan,
-                   const uint32_t* misslist, hipStream_t s) {
-    hipLaunchKernelGGL(victim_kernel<IdT>, dim3(grid_for(n_upper, c.ways, 4096)), dim3(CT_THREADS), 0, s, c, unique,
-                       plan, misslist);
+void launch_victim(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_u, uint64_t n_upper,
+                   uint64_t* plan, hipStream_t s) {
+    hipLaunchKernelGGL(victim_kernel<IdT>, dim3(grid_for(n_upper, c.ways, 2048)), dim3(CT_THREADS), 0, s, c, unique,
+                       n_u, plan);
 }
 
 #define GIDS_INSTANTIATE(IdT)                                                                                       \
     template void launch_probe<IdT>(const CacheView<IdT>&, const IdT*, const uint32_t*, uint64_t, uint64_t, IdT*,   \
-                                    bool, uint64_t*, uint32_t*, hipStream_t);                                       \
-    template void launch_victim<IdT>(const CacheView<IdT>&, const IdT*, uint64_t, uint64_t*, const uint32_t*,       \
+                                    bool, uint64_t*, hipStream_t);                                                  \
+    template void launch_victim<IdT>(const CacheView<IdT>&, const IdT*, const uint32_t*, uint64_t, uint64_t*,       \
                                      hipStream_t);
 GIDS_INSTANTIATE(int32_t)
 GIDS_INSTANTIATE(int64_t)

@@ -18,8 +18,8 @@ namespace gids {
 namespace {
 
 constexpr int DD_THREADS = 256;
-constexpr int MARK_ITEMS = 8;            // raw IDs per thread per tile
-constexpr int TAB_LOG = 12;              // LDS hash set: 4096 slots x 8 B = 32 KiB
+constexpr int MARK_ITEMS = 4;            // raw IDs per thread per tile
+constexpr int TAB_LOG = 11;              // LDS hash set: 2048 slots x 8 B = 16 KiB
 constexpr int TAB_SLOTS = 1 << TAB_LOG;
 constexpr int TAB_PROBES = 4;
 constexpr unsigned long long TAB_EMPTY = ~0ull;

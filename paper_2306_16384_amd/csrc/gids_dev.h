@@ -26,7 +26,7 @@ struct Ctl {
     uint32_t n_unique;      // distinct IDs of the list deduplicated last
     uint32_t error;         // first error a kernel found (-GIDS_E_*), 0 = none; sticky
     uint32_t ticket;        // arrival counter for "last block does the scan"
-    uint32_t n_miss;        // entries in the miss list of the current gather
+    uint32_t reserved0;
     uint32_t stamp;         // index of the minibatch being gathered (successful gathers so far)
     uint32_t cnt_hit, cnt_cpu, cnt_miss, cnt_bypass;
     uint32_t pend_fill;     // queued host-link rows (accumulator)
@@ -100,12 +100,11 @@ void launch_clear(uint64_t* bitmap, const IdT* unique, const uint32_t* n_u, uint
 
 template <typename IdT>
 void launch_probe(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_u, uint64_t n_upper,
-                  uint64_t out_capacity, IdT* unique_out, bool pop_window, uint64_t* plan, uint32_t* misslist,
-                  hipStream_t s);
+                  uint64_t out_capacity, IdT* unique_out, bool pop_window, uint64_t* plan, hipStream_t s);
 
 template <typename IdT>
-void launch_victim(const CacheView<IdT>& c, const IdT* unique, uint64_t n_upper, uint64_t* plan,
-                   const uint32_t* misslist, hipStream_t s);
+void launch_victim(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_u, uint64_t n_upper,
+                   uint64_t* plan, hipStream_t s);
 
 template <typename IdT>
 void launch_move(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_u, uint64_t n_upper,

@@ -214,7 +214,6 @@ __global__ void finalize_kernel(Ctl* ctl, StatsRec* rec, uint64_t seq, const uin
     __threadfence_system();
     if (!err) ctl->stamp += 1;
     ctl->cnt_hit = ctl->cnt_cpu = ctl->cnt_miss = ctl->cnt_bypass = 0;
-    ctl->n_miss = 0;
     ctl->deferred = 0;
 }
 

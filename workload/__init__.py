@@ -11,3 +11,4 @@ from .synth import (  # noqa: F401
     sample_minibatch, normal_table, feature_rows, fill_store, TAGS,
 )
 from .configs import CONFIGS, Config, scaled  # noqa: F401
+from . import native, synth  # noqa: F401,E402

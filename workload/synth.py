@@ -104,15 +104,25 @@ def _threads() -> int:
 
 
 def make_graph(seed: int, n: int, ell: float, p4: int, d_max: int | None = None,
-               index_dtype=np.int64, chunk: int = 1 << 24) -> Graph:
-    """Power-law out-degrees, destinations proportional to out-degree, CSR."""
+               index_dtype=np.int64, chunk: int = 1 << 24, native: bool = False) -> Graph:
+    """Power-law out-degrees, destinations proportional to out-degree, CSR.
+    native=True computes the destinations with the multi-threaded C helper
+    (same definition, for the multi-million-node configurations)."""
     if d_max is None:
         d_max = min(n - 1, 65535)
-    deg = degrees_for(seed, n, ell, p4, d_max)
     indptr = np.zeros(n + 1, dtype=np.int64)
-    np.cumsum(deg, out=indptr[1:])
+    with ThreadPoolExecutor(_threads()) as ex:
+        parts = list(ex.map(lambda r: degrees_for(seed, n, ell, p4, d_max, r[0], r[1]), _chunks(n, 1 << 22)))
+    np.cumsum(np.concatenate(parts), out=indptr[1:])
+    del parts
     e_total = int(indptr[-1])
     indices = np.empty(e_total, dtype=index_dtype)
+    if native:
+        lib = _native_fill()
+        lib.wl_make_edges(ctypes.c_uint64(seed), ctypes.c_int64(n), indptr.ctypes.data_as(ctypes.c_void_p),
+                          ctypes.c_int64(0), ctypes.c_int64(e_total), indices.ctypes.data_as(ctypes.c_void_p),
+                          ctypes.c_uint32(indices.dtype.itemsize), ctypes.c_int(_threads()))
+        return Graph(n=n, indptr=indptr, indices=indices, seed=seed)
 
     def work(rng):
         lo, hi = rng
@@ -130,8 +140,14 @@ def hot_nodes(g: Graph, k: int) -> np.ndarray:
     if k <= 0:
         return np.empty(0, dtype=np.int64)
     indeg = np.bincount(g.indices, minlength=g.n).astype(np.int64)
-    order = np.lexsort((np.arange(g.n, dtype=np.int64), -indeg))
-    return order[:k].astype(np.int64)
+    if k < g.n // 4:
+        # only nodes at or above the k-th largest in-degree can be in the answer
+        kth = np.partition(indeg, g.n - k)[g.n - k]
+        cand = np.flatnonzero(indeg >= kth).astype(np.int64)
+    else:
+        cand = np.arange(g.n, dtype=np.int64)
+    order = np.lexsort((cand, -indeg[cand]))
+    return cand[order[:k]]
 
 
 def zipf_rank_table(n: int, s: float) -> np.ndarray:

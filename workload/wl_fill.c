@@ -43,3 +43,29 @@ void wl_fill_store(uint64_t seed, uint64_t row_lo, uint64_t n_rows, uint32_t dim
         }
     }
 }
+
+/* Destinations of edge slots lo..hi-1 (same definition as make_graph in
+ * synth.py): the node that owns edge slot (H(seed, EDGE, e) mod E). */
+void wl_make_edges(uint64_t seed, int64_t n, const int64_t* indptr, int64_t lo, int64_t hi, void* indices,
+                   uint32_t itemsize, int threads) {
+    const uint64_t k = mix64(seed + 2ull * 0x9E3779B97F4A7C15ull);   /* tag EDGE = 2 */
+    const uint64_t e_total = (uint64_t)indptr[n];
+    if (threads < 1) threads = 1;
+    #pragma omp parallel for num_threads(threads) schedule(static)
+    for (int64_t e = lo; e < hi; e++) {
+        const int64_t slot = (int64_t)(mix64(k ^ (uint64_t)e) % e_total);
+        int64_t a = 0, b = n;
+        while (b - a > 1) {
+            const int64_t mid = a + (b - a) / 2;
+            if (indptr[mid] <= slot) a = mid; else b = mid;
+        }
+        if (itemsize == 4) ((int32_t*)indices)[e] = (int32_t)a;
+        else ((int64_t*)indices)[e] = a;
+    }
+}
+
+/* In-degree histogram of an int64 / int32 destination array. */
+void wl_indegree(const void* indices, int64_t e_total, uint32_t itemsize, int64_t* indeg) {
+    if (itemsize == 4) for (int64_t e = 0; e < e_total; e++) indeg[((const int32_t*)indices)[e]]++;
+    else for (int64_t e = 0; e < e_total; e++) indeg[((const int64_t*)indices)[e]]++;
+}
