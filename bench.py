@@ -32,7 +32,7 @@ LINK_PEAK_GBS = 64.0         # PCIe Gen5 x16, nominal per direction (the box neg
 
 # HBM traffic of the row mover per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # command (see profiles/); None until such a run exists for the workload.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {"large@28000000": 583.1e6}     # profiles/move_kernel_large_pmc.txt
 
 
 def log(*a):
@@ -67,6 +67,13 @@ def main() -> int:
     ap.add_argument("--pass-ids", action="store_true",
                     help="hand the raw ID list to gather again (it is then deduplicated a second time and checked "
                          "against the window head); default with a window: gather the buffered head list")
+    ap.add_argument("--prewarm", type=int, default=-1,
+                    help="before the warm-up minibatches, gather every node once in lists of this many consecutive "
+                         "IDs (0 = off; default: on for the cache-resident workload, whose steady state is 'the "
+                         "cache holds the whole store')")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a plain 1 GiB device copy three times (the known-size kernel that scales the "
+                         "FETCH_SIZE / WRITE_SIZE counters) and exit")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     args = ap.parse_args()
@@ -83,6 +90,14 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the gather has no CPU path", file=sys.stderr)
         return 2
+    if args.calibrate_copy:
+        a = torch.full((1 << 30,), 1, dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes": 1 << 30, "copies": 3}))
+        return 0
     gids.lib()
     wl.native.build()
 
@@ -91,6 +106,9 @@ def main() -> int:
     window = cfg.window if args.window < 0 else args.window
     R = cfg.row_bytes
     steps, warmup = args.steps, args.warmup
+    prewarm = args.prewarm if args.prewarm >= 0 else (1_000_000 if args.workload == "resident" else 0)
+    n_pre = (cfg.n_nodes + prewarm - 1) // prewarm if prewarm else 0
+    warmup += n_pre
     n_batches = warmup + 2 * steps + window + 1                # timed pass + profiled pass + look-ahead
     log(f"workload {cfg.name}: N={cfg.n_nodes} R={R} lines={cfg.cache_lines} ways={cfg.ways} L={cfg.line_bytes} "
         f"cpu_rows={cfg.cpu_rows} W={window} fanouts={cfg.fanouts} seeds={cfg.n_seeds}")
@@ -103,7 +121,9 @@ def main() -> int:
     log(f"hot nodes: {len(hot)} ({time.time() - t0:.1f} s)")
     rank_table = wl.synth.zipf_rank_table(cfg.n_nodes, cfg.seed_zipf_s) if cfg.seed_zipf_s is not None else None
     t0 = time.time()
-    raws = [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds, rank_table) for b in range(n_batches)]
+    id_np = np.dtype(cfg.index_dtype)
+    raws = [np.arange(b * prewarm, min(cfg.n_nodes, (b + 1) * prewarm), dtype=np.int64) for b in range(n_pre)]
+    raws += [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds, rank_table) for b in range(n_batches - n_pre)]
     max_raw = max(len(r) for r in raws)
     log(f"sampled {n_batches} minibatches, raw IDs per minibatch <= {max_raw} ({time.time() - t0:.1f} s)")
 
@@ -197,13 +217,13 @@ def main() -> int:
 
     result = {
         "metric": "gathered feature GB/s per minibatch (distinct IDs x row bytes / time), steady state",
-        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
         "ms_per_step": total_ms / steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u8", "data": "synthetic",
         "unique_ids_per_s": n_unique * scale / (total_ms * 1e-3),
         "config": {"workload": cfg.name, "n_nodes": cfg.n_nodes, "row_bytes": R, "cache_lines": cfg.cache_lines,
                    "ways": cfg.ways, "line_bytes": cfg.line_bytes, "cpu_buffer_rows": cfg.cpu_rows, "window": window,
-                   "fanouts": list(cfg.fanouts), "seeds_per_batch": cfg.n_seeds, "accum_threshold": args.accum,
+                   "fanouts": list(cfg.fanouts), "seeds_per_batch": cfg.n_seeds, "accum_threshold": args.accum, "prewarm_lists": n_pre,
                    "id_dtype": cfg.index_dtype, "scaled_from": base.n_nodes if cfg.n_nodes != base.n_nodes else None},
         "per_step": {"unique": n_unique * scale / steps, "hit": n_hit * scale / steps, "cpu_hit": n_cpu * scale / steps,
                      "miss": n_miss * scale / steps, "bypass": n_byp * scale / steps},

@@ -93,7 +93,8 @@ struct gids_cache {
     StatsRec* ring_dev = nullptr;
     hipEvent_t events[STATS_RING] = {};
     hipStream_t last_stream = nullptr;
-    int move_blocks = 2048;
+    int move_blocks = 2048;     // workgroups of the row mover for rows that stay in HBM
+    int link_blocks = 384;      // ... for rows that cross the host link
     // optional per-phase timing of each gather (events on the caller's stream)
     bool profile = false;
     hipEvent_t prof_events[STATS_RING][4] = {};
@@ -198,6 +199,10 @@ struct CacheT final : gids_cache {
         if (const char* env = getenv("GIDS_MOVE_BLOCKS")) {
             const int b = atoi(env);
             if (b >= 1 && b <= 65536) move_blocks = b;
+        }
+        if (const char* env = getenv("GIDS_LINK_BLOCKS")) {
+            const int b = atoi(env);
+            if (b >= 1 && b <= 65536) link_blocks = b;
         }
         HIP_TRY(hipDeviceSynchronize());
         return GIDS_OK;
@@ -375,7 +380,7 @@ struct CacheT final : gids_cache {
         launch_victim<IdT>(c, U, n_u, n_upper, plan, s);
         if ((prc = mark_phase(r, 2, s))) return prc;
         if (threshold == 0) {
-            launch_move<IdT>(c, U, n_u, n_upper, plan, static_cast<char*>(out), move_blocks, s);
+            launch_move<IdT>(c, U, n_u, n_upper, plan, static_cast<char*>(out), move_blocks, link_blocks, s);
         } else {
             launch_queue<IdT>(c, U, n_u, n_upper, plan, static_cast<char*>(out), fills, copies, (uint32_t)queue_cap,
                               move_blocks, s);

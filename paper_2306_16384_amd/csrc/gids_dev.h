@@ -108,7 +108,7 @@ void launch_victim(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n
 
 template <typename IdT>
 void launch_move(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_u, uint64_t n_upper,
-                 const uint64_t* plan, char* out, int blocks, hipStream_t s);
+                 const uint64_t* plan, char* out, int blocks, int link_blocks_max, hipStream_t s);
 
 template <typename IdT>
 void launch_queue(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_u, uint64_t n_upper,

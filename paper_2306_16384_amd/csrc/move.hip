@@ -60,21 +60,30 @@ __device__ __forceinline__ void clear_miss_bit_word(const CacheView<IdT>& c, uin
     c.missmask[set * c.words_per_set + (round >> 6)] = 0ull;
 }
 
+// The first `link_blocks` workgroups move the rows that cross the host link
+// (CPU-buffer rows, store rows), the others the rows that stay in HBM (hits).
+// The link is saturated by a few hundred workgroups and loses a few percent
+// with thousands, while HBM needs thousands; both halves run concurrently.
 template <typename IdT, int G>
 __global__ __launch_bounds__(MV_THREADS) void move_kernel(CacheView<IdT> c, const IdT* __restrict__ unique,
                                                           const uint32_t* __restrict__ n_u_ptr,
-                                                          const uint64_t* __restrict__ plan, char* __restrict__ out) {
+                                                          const uint64_t* __restrict__ plan, char* __restrict__ out,
+                                                          uint32_t link_blocks) {
     const Ctl* ctl = c.ctl;
     if (ctl->error) return;
     const uint32_t n_u = *n_u_ptr;
     const uint32_t row_u4 = c.row_bytes >> 4;
     const uint32_t sub = threadIdx.x % G;
     const int32_t stamp = (int32_t)ctl->stamp;
-    const uint64_t g0 = ((uint64_t)blockIdx.x * MV_THREADS + threadIdx.x) / G;
-    const uint64_t n_groups = (uint64_t)gridDim.x * MV_THREADS / G;
+    const bool link_role = blockIdx.x < link_blocks;
+    const uint32_t role_block = link_role ? blockIdx.x : blockIdx.x - link_blocks;
+    const uint32_t role_blocks = link_role ? link_blocks : gridDim.x - link_blocks;
+    const uint64_t g0 = ((uint64_t)role_block * MV_THREADS + threadIdx.x) / G;
+    const uint64_t n_groups = (uint64_t)role_blocks * MV_THREADS / G;
     for (uint64_t j = g0; j < n_u; j += n_groups) {
         const uint64_t e = plan[j];
         const uint64_t kind = e >> PLAN_SHIFT, idx = e & PLAN_INDEX_MASK;
+        if ((kind != PLAN_HIT) != link_role) continue;
         const uint64_t v = (uint64_t)unique[j];
         const char* src;
         char* line = nullptr;
@@ -243,11 +252,12 @@ inline uint32_t row_grid(uint64_t rows, int g, int blocks) {
 
 template <typename IdT>
 void launch_move(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_u, uint64_t n_upper,
-                 const uint64_t* plan, char* out, int blocks, hipStream_t s) {
+                 const uint64_t* plan, char* out, int blocks, int link_blocks_max, hipStream_t s) {
     const int g = lanes_per_row(c.row_bytes);
-    const uint32_t grid = row_grid(n_upper, g, blocks);
-    GIDS_DISPATCH_G(g, hipLaunchKernelGGL((move_kernel<IdT, G>), dim3(grid), dim3(MV_THREADS), 0, s, c, unique, n_u,
-                                          plan, out));
+    const uint32_t hbm_blocks = row_grid(n_upper, g, blocks);
+    const uint32_t link_blocks = row_grid(n_upper, g, link_blocks_max);
+    GIDS_DISPATCH_G(g, hipLaunchKernelGGL((move_kernel<IdT, G>), dim3(link_blocks + hbm_blocks), dim3(MV_THREADS), 0,
+                                          s, c, unique, n_u, plan, out, link_blocks));
 }
 
 template <typename IdT>
@@ -278,7 +288,7 @@ void launch_finalize(Ctl* ctl, StatsRec* rec, uint64_t seq, const uint32_t* n_u,
 
 #define GIDS_INSTANTIATE(IdT)                                                                                       \
     template void launch_move<IdT>(const CacheView<IdT>&, const IdT*, const uint32_t*, uint64_t, const uint64_t*,   \
-                                   char*, int, hipStream_t);                                                        \
+                                   char*, int, int, hipStream_t);                                                        \
     template void launch_queue<IdT>(const CacheView<IdT>&, const IdT*, const uint32_t*, uint64_t, const uint64_t*,  \
                                     char*, FillOp*, CopyOp*, uint32_t, int, hipStream_t);                           \
     template void launch_flush<IdT>(const CacheView<IdT>&, FillOp*, CopyOp*, uint64_t, bool, int, hipStream_t);
