@@ -426,12 +426,16 @@ int64_t go_sim_gather(go_sim* s, const int64_t* raw, int64_t n, int64_t* unique_
         a = b;
     }
 
-    /* data: fills first (store -> cache line), then every row to the output */
-    if (s->store && out_rows) {
+    /* data: fills first (store -> cache line; an installed miss always fills
+     * its line, whether or not the caller wants the output rows), then every
+     * row to the output */
+    if (s->store) {
         for (int64_t j = 0; j < m; j++)
             if (cls[j] == GO_CLS_MISS)
                 memcpy(s->cache_data + (size_t)src_line[j] * s->line_bytes,
                        s->store + (size_t)unique_out[j] * s->row_bytes, (size_t)s->row_bytes);
+    }
+    if (s->store && out_rows) {
         for (int64_t j = 0; j < m; j++) {
             const char* src;
             if (cls[j] == GO_CLS_CPU) src = s->cpu_buf + (size_t)s->hot_slot[unique_out[j]] * s->row_bytes;

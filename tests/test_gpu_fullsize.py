@@ -1,0 +1,111 @@
+"""Parity at the benchmark's sizes and launch configuration: Medium at full
+size (every counter of every minibatch, full tensors on a subset) and Large at
+the node count the benchmark runs (counters of every minibatch, distinct-ID
+lists exact, sampled rows against the oracle's closed-form feature rows)."""
+import numpy as np
+import pytest
+
+import workload as wl
+from workload import CONFIGS
+
+pytestmark = pytest.mark.gpu
+
+
+def drive(ses, torch, raws, window, cap_rows, row_bytes, keep):
+    """Benchmark protocol: keep window + 1 lists buffered, gather the head list."""
+    dev = [ses.to_device(r) for r in raws]
+    ses.reserve(max(len(r) for r in raws))
+    outs, uniqs, seqs, pushed = {}, {}, [], 0
+    scratch = [torch.empty((cap_rows, row_bytes), dtype=torch.uint8, device="cuda") for _ in range(2)]
+    uq_scratch = torch.empty(cap_rows, dtype=ses.torch_id, device="cuda")
+    for t in range(len(raws)):
+        while window and pushed < len(raws) and pushed <= t + window:
+            ses.push(dev[pushed])
+            pushed += 1
+        if t in keep:
+            outs[t] = torch.empty((cap_rows, row_bytes), dtype=torch.uint8, device="cuda")
+            uniqs[t] = torch.empty(cap_rows, dtype=ses.torch_id, device="cuda")
+            seqs.append(ses.gather(None if window else dev[t], outs[t], uniqs[t]))
+        else:
+            seqs.append(ses.gather(None if window else dev[t], scratch[t & 1], uq_scratch))
+    torch.cuda.synchronize()
+    return outs, uniqs, seqs
+
+
+def test_medium_full_size(oracle_mod):
+    import torch
+    from paper_2306_16384_amd.session import GatherSession
+    cfg = CONFIGS["medium"]
+    n_b = 48
+    print(f"[fullsize medium] N={cfg.n_nodes} batches={n_b}", flush=True)
+    g = wl.make_graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max, native=True)
+    table = wl.normal_table(np.float16)
+    hot = wl.hot_nodes(g, cfg.cpu_rows)
+    raws = [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds) for b in range(n_b)]
+    cap = max(len(np.unique(r)) for r in raws)
+    keep = {0, 1, 9, 10, 23, n_b - 1}
+    with GatherSession(cfg.n_nodes, cfg.row_bytes, np.int64, cfg.cache_lines, cfg.ways, cfg.line_bytes,
+                       cfg.window) as ses:
+        wl.fill_store(cfg.seed, cfg.n_nodes, cfg.dim, table, ses.store_address())
+        ses.pin_hot(hot)
+        outs, uniqs, seqs = drive(ses, torch, raws, cfg.window, cap, cfg.row_bytes, keep)
+        sim = oracle_mod.Sim(cfg.n_nodes, cfg.cache_lines, cfg.ways, cfg.window, cfg.row_bytes, cfg.line_bytes,
+                             ses.store_view())
+        sim.set_hot(hot)
+        pushed = 0
+        for t, raw in enumerate(raws):
+            while pushed < n_b and pushed <= t + cfg.window:
+                sim.push(raws[pushed])
+                pushed += 1
+            u, rows, stats = sim.gather(raw, want_rows=t in keep)
+            st = ses.stats(seqs[t])
+            assert st.as_tuple() == tuple(int(x) for x in stats), (t, st.as_tuple(), stats.tolist())
+            if t in keep:
+                assert np.array_equal(uniqs[t][:len(u)].cpu().numpy(), u)
+                assert np.array_equal(outs[t][:len(u)].cpu().numpy(), rows), f"minibatch {t}"
+        tags, stamps = ses.snapshot()
+        assert np.array_equal(tags, sim.tags) and np.array_equal(stamps, sim.stamps)
+
+
+def test_large_at_benchmark_size(oracle_mod):
+    import torch
+    from paper_2306_16384_amd.session import GatherSession
+    cfg = wl.scaled(CONFIGS["large"], 28_000_000)
+    n_b = 20
+    print(f"[fullsize large] N={cfg.n_nodes} lines={cfg.cache_lines} cpu_rows={cfg.cpu_rows} batches={n_b}", flush=True)
+    g = wl.make_graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max, native=True)
+    table = wl.normal_table(np.float16)
+    hot = wl.hot_nodes(g, cfg.cpu_rows)
+    raws = [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds) for b in range(n_b)]
+    cap = max(len(np.unique(r)) for r in raws)
+    keep = {0, 9, n_b - 1}
+    with GatherSession(cfg.n_nodes, cfg.row_bytes, np.int64, cfg.cache_lines, cfg.ways, cfg.line_bytes,
+                       cfg.window) as ses:
+        wl.fill_store(cfg.seed, cfg.n_nodes, cfg.dim, table, ses.store_address())
+        ses.pin_hot(hot)
+        outs, uniqs, seqs = drive(ses, torch, raws, cfg.window, cap, cfg.row_bytes, keep)
+        sim = oracle_mod.Sim(cfg.n_nodes, cfg.cache_lines, cfg.ways, cfg.window)      # counts only
+        sim.set_hot(hot)
+        rng = np.random.default_rng(0)
+        pushed = 0
+        for t, raw in enumerate(raws):
+            while pushed < n_b and pushed <= t + cfg.window:
+                sim.push(raws[pushed])
+                pushed += 1
+            u, _, stats, cls = sim.gather(raw, want_rows=False, want_cls=True)
+            st = ses.stats(seqs[t])
+            assert st.as_tuple() == tuple(int(x) for x in stats), (t, st.as_tuple(), stats.tolist())
+            if t in keep:
+                assert np.array_equal(uniqs[t][:len(u)].cpu().numpy(), u)
+                # rows of every class (hit, CPU buffer, installed miss, bypass), sampled, against the closed form
+                pick = []
+                for k in range(4):
+                    idx = np.flatnonzero(cls == k)
+                    if len(idx):
+                        pick.append(rng.choice(idx, size=min(48, len(idx)), replace=False))
+                pick = np.sort(np.concatenate(pick))
+                got = outs[t][torch.from_numpy(pick).cuda()].cpu().numpy()
+                want = oracle_mod.feat_rows(cfg.seed, u[pick], cfg.dim, table).view(np.uint8).reshape(len(pick), -1)
+                assert np.array_equal(got, want), f"minibatch {t}"
+        tags, stamps = ses.snapshot()
+        assert np.array_equal(tags, sim.tags) and np.array_equal(stamps, sim.stamps)

@@ -395,3 +395,14 @@ def test_overlapped_access_model(oracle_mod):
     assert abs(n - r * iops * (ti + n / iops + tt)) < 1e-6
     # SSDs add up: twice the drives need twice the accesses in flight
     assert abs(oracle_mod.accum_threshold(iops, ti, tt, r, 2) - 2 * n) < 1e-6
+
+
+def test_line_fills_happen_without_output_rows(oracle_mod):
+    """A minibatch gathered for its counters only still fills the lines it
+    installs: later hits on them must return the store's bytes."""
+    rng, feats, sim, hot = tiny_setup(oracle_mod, n=200, lines=64, ways=4, window=0, n_hot=0)
+    first = np.arange(0, 40)
+    sim.gather(first, want_rows=False)                       # installs 40 lines, rows not requested
+    uniq, rows, stats, cls = sim.gather(first, want_cls=True)
+    assert stats[1] == 40 and np.all(cls == oracle_mod.CLS_HIT)
+    assert rows.tobytes() == feats[first].tobytes()
