@@ -19,10 +19,17 @@
  *     argument is owned by the caller.  "dev" = device (HBM) pointer, "host" =
  *     ordinary host pointer unless stated otherwise.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *     Calls that take a stream only enqueue work on it and return; they never
- *     block on the device unless an internal buffer has to grow (avoid that
- *     with gids_cache_reserve).  All calls on one cache must use one stream,
- *     or streams the caller orders.
+ *     Calls that take a stream only enqueue work and return; they never block
+ *     on the device unless an internal buffer has to grow (avoid that with
+ *     gids_cache_reserve).  Inputs are read, and outputs are complete, in the
+ *     order of the stream given to the call.  With accum_threshold == 0 the
+ *     library runs dedup, probe and victim selection on a stream of its own
+ *     and orders it against the caller's streams with events, so that the
+ *     classification of one minibatch overlaps the row movement of the
+ *     previous one; to let it overlap, give gids_window_push a different stream
+ *     (the one the sampler fills ID lists on) than gids_gather (the one that
+ *     consumes the rows).  All gathers of one cache use one stream, all pushes
+ *     one stream (the same or another).
  *   - IDs are signed integers of the width fixed at store creation (4 or 8
  *     bytes), valid range [0, n_rows).
  *   - Errors found by the device (an ID out of range, a gather that does not
@@ -158,12 +165,14 @@ uint64_t gids_cache_gathers(const gids_cache* cache);
 int gids_cache_snapshot(gids_cache* cache, int64_t* tags_host, int64_t* stamps_host);
 
 /* Per-phase device time of each gather, for benchmarks and profiling.  When
- * enabled, gids_gather records HIP events on the caller's stream between its
- * three phases; gids_profile_read waits for gather `seq` and writes
- * milliseconds to ms3: [0] ID dedup/sort (+ window check, inverse map),
- * [1] CPU-buffer lookup + tag probe + victim selection, [2] row movement
- * (hit scatter, line fills, CPU-buffer rows; the accumulator's queueing and
- * flush when accum_threshold > 0).  Off by default. */
+ * enabled, gids_gather records HIP events around its three phases, each pair
+ * on the stream the phase's kernels are launched on; gids_profile_read waits
+ * for gather `seq` and writes milliseconds to ms3: [0] ID dedup/sort (+ window
+ * check, inverse map), [1] CPU-buffer lookup + tag probe + victim selection +
+ * commit + counters, [2] row movement (hit scatter, line fills, CPU-buffer
+ * rows; the accumulator's queueing and flush when accum_threshold > 0).
+ * Phases of consecutive gathers overlap, so the three do not add up to the
+ * step time.  Off by default. */
 int gids_profile_enable(gids_cache* cache, int on);
 int gids_profile_read(gids_cache* cache, uint64_t seq, float* ms3);
 

@@ -71,6 +71,7 @@ struct WindowSlot {
     void* ids = nullptr;    // distinct IDs, ascending (device)
     uint64_t cap = 0;       // entries allocated
     uint64_t n_raw = 0;     // length of the raw list that was pushed (bounds the distinct count)
+    int64_t last_reader = -1;   // seq of the gather whose row mover read this list last
 };
 
 struct gids_cache {
@@ -91,13 +92,37 @@ struct gids_cache {
     uint64_t seq = 0;
     StatsRec* ring_host = nullptr;
     StatsRec* ring_dev = nullptr;
-    hipEvent_t events[STATS_RING] = {};
+    hipEvent_t events[STATS_RING] = {};       // gather seq: its rows have moved (recorded on the caller's stream)
+    hipEvent_t ev_meta[STATS_RING] = {};      // gather seq: its metadata kernels and counters are done
+    hipEvent_t ev_hop[16] = {};               // short-lived cross-stream edges
+    uint32_t hop = 0;
+    // With accum_threshold == 0 the metadata kernels (dedup, probe, victim, commit, counters) run on an
+    // internal stream so that they overlap the row movement of earlier gathers on the caller's stream.
+    hipStream_t meta = nullptr;
+    bool pipelined = false;
     hipStream_t last_stream = nullptr;
-    int move_blocks = 2048;     // workgroups of the row mover for rows that stay in HBM
-    int link_blocks = 384;      // ... for rows that cross the host link
+    bool have_last = false;
+    // Without the internal stream every kernel runs on the stream of its call: a call on another stream
+    // than the previous one is ordered after it.
+    int follow(hipStream_t s) {
+        int rc = GIDS_OK;
+        if (!pipelined && have_last && s != last_stream) rc = edge(last_stream, s);
+        last_stream = s;
+        have_last = true;
+        return rc;
+    }
+    // stream `to` waits for everything enqueued on `from` so far
+    int edge(hipStream_t from, hipStream_t to) {
+        hipEvent_t e = ev_hop[hop++ % 16];
+        HIP_TRY(hipEventRecord(e, from));
+        HIP_TRY(hipStreamWaitEvent(to, e, 0));
+        return GIDS_OK;
+    }
+    int move_blocks = 65536;    // most workgroups the row mover uses for rows that stay in HBM
+    int link_blocks = 96;       // ... for rows that cross the host link (persistent, grid-stride)
     // optional per-phase timing of each gather (events on the caller's stream)
     bool profile = false;
-    hipEvent_t prof_events[STATS_RING][4] = {};
+    hipEvent_t prof_events[STATS_RING][5] = {};   // dedup start, dedup end, metadata end, move start, move end
     bool prof_valid[STATS_RING] = {};
     int mark_phase(int ring, int phase, hipStream_t s) {
         if (!profile) return GIDS_OK;
@@ -127,8 +152,9 @@ struct CacheT final : gids_cache {
     uint32_t* blockoff = nullptr;
     // per-minibatch scratch, sized for the longest raw list seen
     uint64_t cap_n = 0;
-    IdT* ubuf = nullptr;
-    uint64_t* plan = nullptr;
+    IdT* ubuf[2] = {nullptr, nullptr};       // alternate per gather: gather t+1 is classified while the rows
+    uint64_t* plan[2] = {nullptr, nullptr};  // of gather t are still moving
+    BatchHdr* hdr = nullptr;                 // two entries
     // accumulator queues
     uint64_t queue_cap = 0;
     FillOp* fills = nullptr;
@@ -145,12 +171,16 @@ struct CacheT final : gids_cache {
         (void)hipDeviceSynchronize();
         dev_free(tags); dev_free(stamps); dev_free(pending); dev_free(reuse); dev_free(missmask); dev_free(bitmap);
         dev_free(wrank); dev_free(hotbits); dev_free(hotrank); dev_free(cache_data); dev_free(ctl);
-        dev_free(blocksum); dev_free(blockoff); dev_free(ubuf); dev_free(plan);
+        dev_free(blocksum); dev_free(blockoff); dev_free(hdr);
+        for (int k = 0; k < 2; k++) { dev_free(ubuf[k]); dev_free(plan[k]); }
         dev_free(fills); dev_free(copies);
         for (auto& s : slots) if (s.ids) (void)hipFree(s.ids);
         if (cpubuf_host) (void)hipHostFree(cpubuf_host);
         if (ring_host) (void)hipHostFree(ring_host);
         for (auto& e : events) if (e) (void)hipEventDestroy(e);
+        for (auto& e : ev_meta) if (e) (void)hipEventDestroy(e);
+        for (auto& e : ev_hop) if (e) (void)hipEventDestroy(e);
+        if (meta) (void)hipStreamDestroy(meta);
         for (auto& row : prof_events) for (auto& e : row) if (e) (void)hipEventDestroy(e);
     }
 
@@ -195,7 +225,18 @@ struct CacheT final : gids_cache {
         memset(ring_host, 0xFF, STATS_RING * sizeof(StatsRec));
         HIP_TRY(hipHostGetDevicePointer(reinterpret_cast<void**>(&ring_dev), ring_host, 0));
         for (auto& e : events) HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
-        slots.resize(window ? window + 1 : 0);
+        for (auto& e : ev_meta) HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        for (auto& e : ev_hop) HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        if ((rc = dev_alloc(&hdr, 2))) return rc;
+        HIP_TRY(hipMemset(hdr, 0, 2 * sizeof(BatchHdr)));
+        // Overlap costs a handful of cross-stream events per call: worth it when minibatches move megabytes.
+        // Default: on for caches of 32 MiB and more; GIDS_PIPELINE=0/1 overrides.
+        pipelined = threshold == 0 && lines * (uint64_t)line_bytes >= (32ull << 20);
+        if (const char* env = getenv("GIDS_PIPELINE")) pipelined = threshold == 0 && atoi(env) != 0;
+        if (pipelined) HIP_TRY(hipStreamCreateWithFlags(&meta, hipStreamNonBlocking));
+        // one slot more than lists can be buffered: the slot a push overwrites was then read by the gather
+        // before the previous one, whose rows have long moved, and not by the one still moving
+        slots.resize(window ? window + 2 : 0);
         if (const char* env = getenv("GIDS_MOVE_BLOCKS")) {
             const int b = atoi(env);
             if (b >= 1 && b <= 65536) move_blocks = b;
@@ -213,11 +254,14 @@ struct CacheT final : gids_cache {
         if (n < 1) n = 1;
         if (n > cap_n) {
             HIP_TRY(hipDeviceSynchronize());
-            dev_free(ubuf); dev_free(plan);
             const uint64_t want = std::max<uint64_t>(n, cap_n + cap_n / 2);
-            int rc;
-            if ((rc = dev_alloc(&ubuf, want))) return rc;
-            if ((rc = dev_alloc(&plan, want))) return rc;
+            cap_n = 0;
+            for (int k = 0; k < 2; k++) {
+                dev_free(ubuf[k]); dev_free(plan[k]);
+                int rc;
+                if ((rc = dev_alloc(&ubuf[k], want))) return rc;
+                if ((rc = dev_alloc(&plan[k], want))) return rc;
+            }
             cap_n = want;
         }
         if (threshold && threshold + n > queue_cap) {
@@ -315,15 +359,25 @@ struct CacheT final : gids_cache {
 
     int push(const void* ids, uint64_t n, hipStream_t s) override {
         if (window == 0) return fail(GIDS_E_INVAL, "gids_window_push: the cache was created with window_depth 0");
-        if (count == slots.size()) return fail(GIDS_E_FULL, "gids_window_push: %u lists already buffered", count);
+        if (count == window + 1) return fail(GIDS_E_FULL, "gids_window_push: %u lists already buffered", count);
         if (n && !ids) return fail(GIDS_E_INVAL, "gids_window_push: ids_dev is NULL");
         const uint32_t slot = (head + count) % slots.size();
-        int rc = ensure_slot(slots[slot], n);
+        WindowSlot& sl = slots[slot];
+        int rc = ensure_slot(sl, n);
         if (rc) return rc;
-        slots[slot].n_raw = n;
-        dedup(static_cast<const IdT*>(ids), n, static_cast<IdT*>(slots[slot].ids), &ctl->win_n[slot], reuse, false, s);
+        sl.n_raw = n;
+        if ((rc = follow(s))) return rc;
+        hipStream_t m = s;
+        if (pipelined) {
+            m = meta;
+            // the list this slot held may still be read by its gather's row mover
+            if (sl.last_reader >= 0) HIP_TRY(hipStreamWaitEvent(meta, events[sl.last_reader % STATS_RING], 0));
+            if ((rc = edge(s, meta))) return rc;              // the caller's IDs are ready in its stream's order
+        }
+        dedup(static_cast<const IdT*>(ids), n, static_cast<IdT*>(sl.ids), &ctl->win_n[slot], reuse, false, m);
+        if (pipelined && (rc = edge(meta, s))) return rc;     // the caller may reuse its ID buffer in stream order
+        sl.last_reader = -1;
         count++;
-        last_stream = s;
         return GIDS_OK;
     }
 
@@ -332,73 +386,90 @@ struct CacheT final : gids_cache {
         const IdT* ids = static_cast<const IdT*>(ids_v);
         if (!out && out_cap) return fail(GIDS_E_INVAL, "gids_gather: out_dev is NULL");
         if (inverse && !ids) return fail(GIDS_E_INVAL, "gids_gather: inverse_dev needs ids_dev");
+        if (window && count == 0) return fail(GIDS_E_ORDER, "gids_gather: no minibatch is buffered in the window");
+        if (!window && !ids && n) return fail(GIDS_E_INVAL, "gids_gather: ids_dev is NULL and there is no window to take the list from");
+        if (!ids) n = 0;
+        int rc = ensure_scratch(window ? std::max(n, slots[head].n_raw) : n);
+        if (rc) return rc;
+        if (inverse && !wrank && (rc = dev_alloc(&wrank, n_words))) return rc;
+
+        const int r = (int)(seq % STATS_RING);
+        const int par = (int)(seq & 1);
+        if ((rc = follow(s))) return rc;
+        hipStream_t m = s;
+        if (pipelined) {
+            m = meta;
+            // plan / ID scratch / header of this parity were last read by the row mover of gather seq - 2
+            if (seq >= 2) HIP_TRY(hipStreamWaitEvent(meta, events[(seq - 2) % STATS_RING], 0));
+            if (ids && (rc = edge(s, meta))) return rc;       // the caller's IDs are ready in its stream's order
+        }
+        prof_valid[r] = false;
+        if ((rc = mark_phase(r, 0, m))) return rc;
+
         const IdT* U;
         const uint32_t* n_u;
         uint64_t n_upper;
-        bool pop = false;
-        const int r = (int)(seq % STATS_RING);
-        prof_valid[r] = false;
-        int prc = mark_phase(r, 0, s);
-        if (prc) return prc;
-        if (window) {
-            if (count == 0) return fail(GIDS_E_ORDER, "gids_gather: no minibatch is buffered in the window");
-            WindowSlot& h = slots[head];
-            if (!ids) n = 0;
-            int rc = ensure_scratch(std::max(n, h.n_raw));
-            if (rc) return rc;
-            if (ids) {
-                if (inverse && !wrank && (rc = dev_alloc(&wrank, n_words))) return rc;
-                dedup(ids, n, ubuf, &ctl->n_unique, nullptr, inverse != nullptr, s);
-                launch_verify<IdT>(ubuf, static_cast<const IdT*>(h.ids), &ctl->win_n[head], ctl, std::min(n, h.n_raw), s);
-                if (inverse) {
-                    launch_inverse<IdT>(ids, n, bitmap, wrank, static_cast<uint32_t*>(inverse), ctl, s);
-                    launch_clear<IdT>(bitmap, ubuf, &ctl->n_unique, n, s);
-                }
-            }
-            U = static_cast<const IdT*>(h.ids);
-            n_u = &ctl->win_n[head];
-            n_upper = h.n_raw;
-            pop = true;
-        } else {
-            if (!ids && n) return fail(GIDS_E_INVAL, "gids_gather: ids_dev is NULL and there is no window to take the list from");
-            int rc = ensure_scratch(n);
-            if (rc) return rc;
-            if (inverse && !wrank && (rc = dev_alloc(&wrank, n_words))) return rc;
-            dedup(ids, n, ubuf, &ctl->n_unique, nullptr, inverse != nullptr, s);
+        if (ids || !window) {                                 // (an empty list without a window still sets the count)
+            dedup(ids, n, ubuf[par], &ctl->n_unique, nullptr, inverse != nullptr, m);
+            if (window)
+                launch_verify<IdT>(ubuf[par], static_cast<const IdT*>(slots[head].ids), &ctl->win_n[head], ctl,
+                                   std::min(n, slots[head].n_raw), m);
             if (inverse) {
-                launch_inverse<IdT>(ids, n, bitmap, wrank, static_cast<uint32_t*>(inverse), ctl, s);
-                launch_clear<IdT>(bitmap, ubuf, &ctl->n_unique, n, s);
+                launch_inverse<IdT>(ids, n, bitmap, wrank, static_cast<uint32_t*>(inverse), ctl, m);
+                launch_clear<IdT>(bitmap, ubuf[par], &ctl->n_unique, n, m);
             }
-            U = ubuf;
+        }
+        if (window) {                                         // the buffered head list is the minibatch
+            U = static_cast<const IdT*>(slots[head].ids);
+            n_u = &ctl->win_n[head];
+            n_upper = slots[head].n_raw;
+        } else {
+            U = ubuf[par];
             n_u = &ctl->n_unique;
             n_upper = n;
         }
         n_upper = std::min<uint64_t>(n_upper, store->n_rows);
         const CacheView<IdT> c = view();
-        if ((prc = mark_phase(r, 1, s))) return prc;
-        launch_probe<IdT>(c, U, n_u, n_upper, out_cap, static_cast<IdT*>(unique), pop, plan, s);
-        launch_victim<IdT>(c, U, n_u, n_upper, plan, s);
-        if ((prc = mark_phase(r, 2, s))) return prc;
+        if ((rc = mark_phase(r, 1, m))) return rc;
+        launch_probe<IdT>(c, U, n_u, n_upper, out_cap, window != 0, plan[par], m);
+        launch_victim<IdT>(c, U, n_u, n_upper, plan[par], m);
+        launch_commit<IdT>(c, U, n_u, n_upper, plan[par], hdr + par, m);
         if (threshold == 0) {
-            launch_move<IdT>(c, U, n_u, n_upper, plan, static_cast<char*>(out), move_blocks, link_blocks, s);
+            launch_finalize(ctl, ring_dev + r, seq, n_u, m);
+            if ((rc = mark_phase(r, 2, m))) return rc;
+            if (pipelined) {
+                HIP_TRY(hipEventRecord(ev_meta[r], meta));
+                HIP_TRY(hipStreamWaitEvent(s, ev_meta[r], 0));
+            }
+            if ((rc = mark_phase(r, 3, s))) return rc;
+            launch_move<IdT>(c, U, hdr + par, n_upper, plan[par], static_cast<char*>(out), static_cast<IdT*>(unique),
+                             move_blocks, link_blocks, s);
+            if ((rc = mark_phase(r, 4, s))) return rc;
         } else {
-            launch_queue<IdT>(c, U, n_u, n_upper, plan, static_cast<char*>(out), fills, copies, (uint32_t)queue_cap,
-                              move_blocks, s);
+            if ((rc = mark_phase(r, 2, s))) return rc;
+            if ((rc = mark_phase(r, 3, s))) return rc;
+            launch_queue<IdT>(c, U, hdr + par, n_upper, plan[par], static_cast<char*>(out), static_cast<IdT*>(unique),
+                              fills, copies, move_blocks, s);
             launch_flush<IdT>(c, fills, copies, threshold, false, move_blocks, s);
+            if ((rc = mark_phase(r, 4, s))) return rc;
+            launch_finalize(ctl, ring_dev + r, seq, n_u, s);
         }
-        if ((prc = mark_phase(r, 3, s))) return prc;
         prof_valid[r] = profile;
-        launch_finalize(ctl, ring_dev + r, seq, n_u, s);
         HIP_TRY(hipEventRecord(events[r], s));
+        if (window) {
+            slots[head].last_reader = (int64_t)seq;
+            head = (head + 1) % slots.size();
+            count--;
+        }
         seq++;
-        if (window) { head = (head + 1) % slots.size(); count--; }
-        last_stream = s;
         return GIDS_OK;
     }
 
     int flush(hipStream_t s) override {
-        if (threshold) launch_flush<IdT>(view(), fills, copies, threshold, true, move_blocks, s);
-        last_stream = s;
+        if (!threshold) return GIDS_OK;
+        const int rc = follow(s);
+        if (rc) return rc;
+        launch_flush<IdT>(view(), fills, copies, threshold, true, move_blocks, s);
         return GIDS_OK;
     }
 
@@ -533,6 +604,7 @@ int gids_stats_read(gids_cache* cache, uint64_t seq, gids_stats* stats) {
     if (!cache || !stats) return fail(GIDS_E_INVAL, "gids_stats_read: NULL argument");
     if (seq >= cache->seq || seq + STATS_RING < cache->seq) return fail(GIDS_E_INVAL, "gids_stats_read: gather %llu is not available", (unsigned long long)seq);
     const int r = (int)(seq % STATS_RING);
+    if (cache->pipelined) HIP_TRY(hipEventSynchronize(cache->ev_meta[r]));
     HIP_TRY(hipEventSynchronize(cache->events[r]));
     const StatsRec rec = cache->ring_host[r];
     if (rec.seq != seq) return fail(GIDS_E_INVAL, "gids_stats_read: record of gather %llu was overwritten", (unsigned long long)seq);
@@ -557,8 +629,11 @@ int gids_profile_read(gids_cache* cache, uint64_t seq, float* ms3) {
     if (seq >= cache->seq || seq + STATS_RING < cache->seq) return fail(GIDS_E_INVAL, "gids_profile_read: gather %llu is not available", (unsigned long long)seq);
     const int r = (int)(seq % STATS_RING);
     if (!cache->prof_valid[r]) return fail(GIDS_E_INVAL, "gids_profile_read: gather %llu was not profiled", (unsigned long long)seq);
-    HIP_TRY(hipEventSynchronize(cache->prof_events[r][3]));
-    for (int k = 0; k < 3; k++) HIP_TRY(hipEventElapsedTime(&ms3[k], cache->prof_events[r][k], cache->prof_events[r][k + 1]));
+    HIP_TRY(hipEventSynchronize(cache->prof_events[r][2]));
+    HIP_TRY(hipEventSynchronize(cache->prof_events[r][4]));
+    HIP_TRY(hipEventElapsedTime(&ms3[0], cache->prof_events[r][0], cache->prof_events[r][1]));
+    HIP_TRY(hipEventElapsedTime(&ms3[1], cache->prof_events[r][1], cache->prof_events[r][2]));
+    HIP_TRY(hipEventElapsedTime(&ms3[2], cache->prof_events[r][3], cache->prof_events[r][4]));
     return GIDS_OK;
 }
 

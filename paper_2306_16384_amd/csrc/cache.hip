@@ -19,7 +19,9 @@
 //           and it is empty or its node's future-reuse counter is zero ("safe
 //           to evict"); a positive counter is the "USE" state.  With more
 //           misses than evictable ways the rest bypass the cache.
-// Neither kernel writes a tag: the row mover does, when it fills the line.
+//   commit  writes the tag and stamp of every line a miss was given and clears
+//           the miss mask; only then is the cache's metadata that of the next
+//           minibatch's start.  The bytes follow in the row mover.
 #include "gids_dev.h"
 
 namespace gids {
@@ -53,8 +55,7 @@ __device__ __forceinline__ uint64_t group_bits(uint64_t ballot, uint32_t ways) {
 template <typename IdT>
 __global__ __launch_bounds__(CT_THREADS) void probe_kernel(CacheView<IdT> c, const IdT* __restrict__ unique,
                                                            const uint32_t* __restrict__ n_u_ptr, uint64_t out_capacity,
-                                                           IdT* __restrict__ unique_out, int pop_window,
-                                                           uint64_t* __restrict__ plan) {
+                                                           int pop_window, uint64_t* __restrict__ plan) {
     __shared__ uint32_t block_cnt[3];
     Ctl* ctl = c.ctl;
     if (ctl->error) return;                                  // set only by earlier kernels: uniform
@@ -77,10 +78,9 @@ __global__ __launch_bounds__(CT_THREADS) void probe_kernel(CacheView<IdT> c, con
         const uint64_t j = chunk * per_wave + (lane_id() >> lg);
         const bool valid = j < n_u;
         const uint64_t v = valid ? (uint64_t)unique[j] : 0;
-        // leader: CPU-buffer membership, window pop, copy to the caller's ID list
+        // leader: CPU-buffer membership, window pop
         uint32_t hot = 0, slot = 0;
         if (valid && leader) {
-            if (unique_out) unique_out[j] = (IdT)v;
             if (pop_window) c.reuse[v] = (uint8_t)(c.reuse[v] - 1);
             if (c.hotbits) {
                 const uint64_t hw = c.hotbits[v >> 6];
@@ -201,6 +201,40 @@ __global__ __launch_bounds__(CT_THREADS) void victim_kernel(CacheView<IdT> c, co
     if (threadIdx.x == 0 && block_byp) atomicAdd(&ctl->cnt_bypass, block_byp);
 }
 
+// Publishes the gather's decisions: tag and stamp of every line a miss will
+// fill, the miss mask back to zero, and the header the row mover reads.  After
+// this kernel the next minibatch may be classified, whether or not the rows of
+// this one have moved yet.
+template <typename IdT>
+__global__ __launch_bounds__(CT_THREADS) void commit_kernel(CacheView<IdT> c, const IdT* __restrict__ unique,
+                                                            const uint32_t* __restrict__ n_u_ptr,
+                                                            const uint64_t* __restrict__ plan, BatchHdr* hdr) {
+    const Ctl* ctl = c.ctl;
+    const bool ok = ctl->error == 0;
+    const uint32_t n_u = ok ? *n_u_ptr : 0;
+    const uint32_t stamp = ctl->stamp;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        hdr->ok = ok ? 1u : 0u;
+        hdr->n_u = n_u;
+        hdr->stamp = stamp;
+    }
+    if (!ok || ctl->cnt_miss == 0) return;
+    for (uint64_t j = (uint64_t)blockIdx.x * CT_THREADS + threadIdx.x; j < n_u; j += (uint64_t)gridDim.x * CT_THREADS) {
+        const uint64_t e = plan[j];
+        const uint64_t kind = e >> PLAN_SHIFT;
+        if (kind < PLAN_INSTALL) continue;
+        const uint64_t v = (uint64_t)unique[j];
+        if (kind == PLAN_INSTALL) {
+            const uint64_t line = e & PLAN_INDEX_MASK;
+            c.tags[line] = (IdT)v;
+            c.stamps[line] = (int32_t)stamp;
+        }
+        uint64_t set, round;
+        set_and_round(c, v, &set, &round);
+        c.missmask[set * c.words_per_set + (round >> 6)] = 0ull;
+    }
+}
+
 inline uint32_t grid_for(uint64_t groups, uint32_t ways, uint32_t cap) {
     const uint64_t per_block = (uint64_t)(CT_THREADS / 64) * (64 / ways);
     uint64_t b = (groups + per_block - 1) / per_block;
@@ -212,9 +246,18 @@ inline uint32_t grid_for(uint64_t groups, uint32_t ways, uint32_t cap) {
 
 template <typename IdT>
 void launch_probe(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_u, uint64_t n_upper,
-                  uint64_t out_capacity, IdT* unique_out, bool pop_window, uint64_t* plan, hipStream_t s) {
+                  uint64_t out_capacity, bool pop_window, uint64_t* plan, hipStream_t s) {
     hipLaunchKernelGGL(probe_kernel<IdT>, dim3(grid_for(n_upper, c.ways, 2048)), dim3(CT_THREADS), 0, s, c, unique,
-                       n_u, out_capacity, unique_out, pop_window ? 1 : 0, plan);
+                       n_u, out_capacity, pop_window ? 1 : 0, plan);
+}
+
+template <typename IdT>
+void launch_commit(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_u, uint64_t n_upper,
+                   const uint64_t* plan, BatchHdr* hdr, hipStream_t s) {
+    uint64_t b = (n_upper + CT_THREADS - 1) / CT_THREADS;
+    if (b < 1) b = 1;
+    if (b > 1024) b = 1024;
+    hipLaunchKernelGGL(commit_kernel<IdT>, dim3((uint32_t)b), dim3(CT_THREADS), 0, s, c, unique, n_u, plan, hdr);
 }
 
 template <typename IdT>
@@ -225,8 +268,10 @@ void launch_victim(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n
 }
 
 #define GIDS_INSTANTIATE(IdT)                                                                                       \
-    template void launch_probe<IdT>(const CacheView<IdT>&, const IdT*, const uint32_t*, uint64_t, uint64_t, IdT*,   \
-                                    bool, uint64_t*, hipStream_t);                                                  \
+    template void launch_probe<IdT>(const CacheView<IdT>&, const IdT*, const uint32_t*, uint64_t, uint64_t, bool,   \
+                                    uint64_t*, hipStream_t);                                                        \
+    template void launch_commit<IdT>(const CacheView<IdT>&, const IdT*, const uint32_t*, uint64_t, const uint64_t*, \
+                                     BatchHdr*, hipStream_t);                                                       \
     template void launch_victim<IdT>(const CacheView<IdT>&, const IdT*, const uint32_t*, uint64_t, uint64_t*,       \
                                      hipStream_t);
 GIDS_INSTANTIATE(int32_t)

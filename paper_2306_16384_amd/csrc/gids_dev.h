@@ -18,7 +18,7 @@ constexpr uint64_t PLAN_INDEX_MASK = (1ull << PLAN_SHIFT) - 1;
 constexpr uint32_t NO_OP = 0xFFFFFFFFu;       // "no pending fill" marker of a cache line
 constexpr uint64_t NO_LINE = ~0ull;           // a queued fill that installs nothing
 
-constexpr int MAX_WINDOW_SLOTS = 256;
+constexpr int MAX_WINDOW_SLOTS = 256;      // window_depth <= 254, + 2
 
 // Device-resident control block of one cache.  Kernels read every count from
 // here, so the host never has to wait for a count before launching the next.
@@ -34,6 +34,16 @@ struct Ctl {
     uint32_t do_flush;      // decision of the accumulator for this gather
     uint32_t deferred;      // rows of the current gather left in the queues
     uint32_t win_n[MAX_WINDOW_SLOTS];   // distinct count of each buffered list
+};
+
+// What the row mover needs to know about one gather, frozen by the commit
+// kernel so that the next gather's metadata kernels may already run while the
+// rows of this one are still moving.
+struct BatchHdr {
+    uint32_t ok;            // 0: the gather failed or an earlier error is pending: move nothing
+    uint32_t n_u;           // distinct IDs
+    uint32_t stamp;         // minibatch index
+    uint32_t pad;
 };
 
 // One queued row move of the accumulator.
@@ -100,19 +110,23 @@ void launch_clear(uint64_t* bitmap, const IdT* unique, const uint32_t* n_u, uint
 
 template <typename IdT>
 void launch_probe(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_u, uint64_t n_upper,
-                  uint64_t out_capacity, IdT* unique_out, bool pop_window, uint64_t* plan, hipStream_t s);
+                  uint64_t out_capacity, bool pop_window, uint64_t* plan, hipStream_t s);
 
 template <typename IdT>
 void launch_victim(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_u, uint64_t n_upper,
                    uint64_t* plan, hipStream_t s);
 
 template <typename IdT>
-void launch_move(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_u, uint64_t n_upper,
-                 const uint64_t* plan, char* out, int blocks, int link_blocks_max, hipStream_t s);
+void launch_commit(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_u, uint64_t n_upper,
+                   const uint64_t* plan, BatchHdr* hdr, hipStream_t s);
 
 template <typename IdT>
-void launch_queue(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_u, uint64_t n_upper,
-                  const uint64_t* plan, char* out, FillOp* fills, CopyOp* copies, uint32_t queue_cap, int blocks,
+void launch_move(const CacheView<IdT>& c, const IdT* unique, const BatchHdr* hdr, uint64_t n_upper,
+                 const uint64_t* plan, char* out, IdT* unique_out, int blocks, int link_blocks_max, hipStream_t s);
+
+template <typename IdT>
+void launch_queue(const CacheView<IdT>& c, const IdT* unique, const BatchHdr* hdr, uint64_t n_upper,
+                  const uint64_t* plan, char* out, IdT* unique_out, FillOp* fills, CopyOp* copies, int blocks,
                   hipStream_t s);
 
 template <typename IdT>

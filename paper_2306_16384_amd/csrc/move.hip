@@ -6,8 +6,8 @@
 //             a hit copies cache line -> output (HBM -> HBM); a CPU-buffer hit
 //             copies pinned host row -> output; a miss reads the host store row
 //             once and writes it to the output and, when a victim line was
-//             found, to that line (the "line fill"), then publishes the line's
-//             tag and stamp.
+//             found, to that line (the "line fill").  Tags were published by
+//             the commit kernel before; only bytes move here.
 //   queue     the accumulator's variant: rows that cross the host link are not
 //             moved but appended to a fill queue; a hit on a line whose fill is
 //             still queued becomes a queued copy from the output row that fill
@@ -25,97 +25,107 @@ namespace {
 constexpr int MV_THREADS = 256;
 constexpr int MV_UNROLL = 4;
 
+// Rows are streamed: read once, written once or twice, far larger in total than
+// L2 or the memory-side cache, so every access carries the non-temporal hint.
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+
 template <int G>
-__device__ __forceinline__ void copy_row(const uint4* __restrict__ src, uint4* __restrict__ dst,
-                                         uint4* __restrict__ dst2, uint32_t row_u4, uint32_t sub) {
+__device__ __forceinline__ void copy_row(const v4u* __restrict__ src, v4u* __restrict__ dst,
+                                         v4u* __restrict__ dst2, uint32_t row_u4, uint32_t sub) {
     for (uint32_t k0 = 0; k0 < row_u4; k0 += G * MV_UNROLL) {
-        uint4 buf[MV_UNROLL];
+        v4u buf[MV_UNROLL];
 #pragma unroll
         for (int u = 0; u < MV_UNROLL; u++) {
             const uint32_t k = k0 + u * G + sub;
-            if (k < row_u4) buf[u] = src[k];
+            if (k < row_u4) buf[u] = __builtin_nontemporal_load(src + k);
         }
 #pragma unroll
         for (int u = 0; u < MV_UNROLL; u++) {
             const uint32_t k = k0 + u * G + sub;
             if (k < row_u4) {
-                dst[k] = buf[u];
-                if (dst2) dst2[k] = buf[u];
+                __builtin_nontemporal_store(buf[u], dst + k);
+                if (dst2) __builtin_nontemporal_store(buf[u], dst2 + k);
             }
         }
     }
 }
 
-template <typename IdT>
-__device__ __forceinline__ void clear_miss_bit_word(const CacheView<IdT>& c, uint64_t v) {
-    uint64_t set, round;
-    if (c.use32) {
-        const uint32_t q = (uint32_t)v / (uint32_t)c.n_sets;
-        round = q;
-        set = (uint32_t)v - q * (uint32_t)c.n_sets;
-    } else {
-        round = v / c.n_sets;
-        set = v - round * c.n_sets;
-    }
-    c.missmask[set * c.words_per_set + (round >> 6)] = 0ull;
+// position of the n-th (0-based) set bit of mask, or 64 when there are fewer
+__device__ __forceinline__ uint32_t nth_set_bit(uint64_t mask, uint32_t n) {
+    for (uint32_t i = 0; i < n; i++) mask &= mask - 1;
+    return mask ? (uint32_t)(__ffsll((unsigned long long)mask) - 1) : 64u;
 }
 
 // The first `link_blocks` workgroups move the rows that cross the host link
 // (CPU-buffer rows, store rows), the others the rows that stay in HBM (hits).
-// The link is saturated by a few hundred workgroups and loses a few percent
-// with thousands, while HBM needs thousands; both halves run concurrently.
+// The link is saturated by about a hundred persistent workgroups, and more of
+// them only crowd the memory pipeline for everybody else, while HBM wants
+// thousands of waves; both halves run concurrently.
+// A wave reads CH plan entries with one coalesced load, ballots which of them
+// belong to its half, and then moves those rows 64 / G at a time, so scanning
+// past the other half's rows costs one load per CH rows.
 template <typename IdT, int G>
 __global__ __launch_bounds__(MV_THREADS) void move_kernel(CacheView<IdT> c, const IdT* __restrict__ unique,
-                                                          const uint32_t* __restrict__ n_u_ptr,
+                                                          const BatchHdr* __restrict__ hdr,
                                                           const uint64_t* __restrict__ plan, char* __restrict__ out,
-                                                          uint32_t link_blocks) {
-    const Ctl* ctl = c.ctl;
-    if (ctl->error) return;
-    const uint32_t n_u = *n_u_ptr;
+                                                          IdT* __restrict__ unique_out, uint32_t link_blocks,
+                                                          uint32_t link_ch) {
+    if (!hdr->ok) return;
+    const uint32_t n_u = hdr->n_u;
     const uint32_t row_u4 = c.row_bytes >> 4;
-    const uint32_t sub = threadIdx.x % G;
-    const int32_t stamp = (int32_t)ctl->stamp;
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t sub = lane % G, grp = lane / G;
+    constexpr uint32_t PER_ITER = 64 / G;                     // rows a wave moves at once
     const bool link_role = blockIdx.x < link_blocks;
+    const uint32_t ch = link_role ? link_ch : 16u;            // plan entries a wave scans per step
     const uint32_t role_block = link_role ? blockIdx.x : blockIdx.x - link_blocks;
     const uint32_t role_blocks = link_role ? link_blocks : gridDim.x - link_blocks;
-    const uint64_t g0 = ((uint64_t)role_block * MV_THREADS + threadIdx.x) / G;
-    const uint64_t n_groups = (uint64_t)role_blocks * MV_THREADS / G;
-    for (uint64_t j = g0; j < n_u; j += n_groups) {
-        const uint64_t e = plan[j];
-        const uint64_t kind = e >> PLAN_SHIFT, idx = e & PLAN_INDEX_MASK;
-        if ((kind != PLAN_HIT) != link_role) continue;
-        const uint64_t v = (uint64_t)unique[j];
-        const char* src;
-        char* line = nullptr;
-        if (kind == PLAN_HIT) src = c.cache_data + idx * c.line_bytes;
-        else if (kind == PLAN_CPU) src = c.cpubuf + idx * c.row_bytes;
-        else {
-            src = c.store + v * c.row_bytes;
-            if (kind == PLAN_INSTALL) line = c.cache_data + idx * c.line_bytes;
+    const uint64_t wave0 = ((uint64_t)role_block * MV_THREADS + threadIdx.x) >> 6;
+    const uint64_t n_waves = ((uint64_t)role_blocks * MV_THREADS) >> 6;
+    for (uint64_t base = wave0 * ch; base < n_u; base += n_waves * ch) {
+        const uint64_t jl = base + lane;
+        uint64_t e = 0, v = 0;
+        bool mine = false;
+        if (lane < ch && jl < n_u) {
+            e = plan[jl];
+            v = (uint64_t)unique[jl];
+            mine = ((e >> PLAN_SHIFT) != PLAN_HIT) == link_role;
+            if (!link_role && unique_out) unique_out[jl] = (IdT)v;   // the HBM half sees every j exactly once
         }
-        copy_row<G>(reinterpret_cast<const uint4*>(src), reinterpret_cast<uint4*>(out + j * c.row_bytes),
-                    reinterpret_cast<uint4*>(line), row_u4, sub);
-        if (sub == 0 && kind >= PLAN_INSTALL) {
-            if (kind == PLAN_INSTALL) {
-                c.tags[idx] = (IdT)v;
-                c.stamps[idx] = stamp;
+        uint64_t todo = __ballot(mine);
+        while (todo) {
+            const uint32_t pick = nth_set_bit(todo, grp);
+#pragma unroll
+            for (uint32_t i = 0; i < PER_ITER; i++) todo &= todo - 1;    // (clearing bits of 0 leaves 0)
+            const uint64_t e_p = __shfl(e, (int)(pick & 63));
+            const uint64_t v_p = __shfl(v, (int)(pick & 63));
+            if (pick == 64u) continue;
+            const uint64_t kind = e_p >> PLAN_SHIFT, idx = e_p & PLAN_INDEX_MASK;
+            const char* src;
+            char* line = nullptr;
+            if (kind == PLAN_HIT) src = c.cache_data + idx * c.line_bytes;
+            else if (kind == PLAN_CPU) src = c.cpubuf + idx * c.row_bytes;
+            else {
+                src = c.store + v_p * c.row_bytes;
+                if (kind == PLAN_INSTALL) line = c.cache_data + idx * c.line_bytes;
             }
-            clear_miss_bit_word(c, v);
+            copy_row<G>(reinterpret_cast<const v4u*>(src), reinterpret_cast<v4u*>(out + (base + pick) * c.row_bytes),
+                        reinterpret_cast<v4u*>(line), row_u4, sub);
         }
     }
 }
 
 template <typename IdT, int G>
 __global__ __launch_bounds__(MV_THREADS) void queue_kernel(CacheView<IdT> c, const IdT* __restrict__ unique,
-                                                           const uint32_t* __restrict__ n_u_ptr,
+                                                           const BatchHdr* __restrict__ hdr,
                                                            const uint64_t* __restrict__ plan, char* __restrict__ out,
-                                                           FillOp* __restrict__ fills, CopyOp* __restrict__ copies) {
+                                                           IdT* __restrict__ unique_out, FillOp* __restrict__ fills,
+                                                           CopyOp* __restrict__ copies) {
     Ctl* ctl = c.ctl;
-    if (ctl->error) return;
-    const uint32_t n_u = *n_u_ptr;
+    if (!hdr->ok) return;
+    const uint32_t n_u = hdr->n_u;
     const uint32_t row_u4 = c.row_bytes >> 4;
     const uint32_t sub = threadIdx.x % G;
-    const int32_t stamp = (int32_t)ctl->stamp;
     const uint64_t g0 = ((uint64_t)blockIdx.x * MV_THREADS + threadIdx.x) / G;
     const uint64_t n_groups = (uint64_t)gridDim.x * MV_THREADS / G;
     for (uint64_t j = g0; j < n_u; j += n_groups) {
@@ -123,11 +133,12 @@ __global__ __launch_bounds__(MV_THREADS) void queue_kernel(CacheView<IdT> c, con
         const uint64_t kind = e >> PLAN_SHIFT, idx = e & PLAN_INDEX_MASK;
         const uint64_t v = (uint64_t)unique[j];
         char* dst = out + j * c.row_bytes;
+        if (sub == 0 && unique_out) unique_out[j] = (IdT)v;
         if (kind == PLAN_HIT) {
             const uint32_t p = c.pending[idx];             // written only by earlier gathers or flushes
             if (p == NO_OP) {
-                copy_row<G>(reinterpret_cast<const uint4*>(c.cache_data + idx * c.line_bytes),
-                            reinterpret_cast<uint4*>(dst), nullptr, row_u4, sub);
+                copy_row<G>(reinterpret_cast<const v4u*>(c.cache_data + idx * c.line_bytes),
+                            reinterpret_cast<v4u*>(dst), nullptr, row_u4, sub);
             } else if (sub == 0) {                         // the line's bytes are still on their way
                 const uint32_t q = atomicAdd(&ctl->pend_copy, 1u);
                 copies[q].src = fills[p].dst_out;
@@ -151,10 +162,7 @@ __global__ __launch_bounds__(MV_THREADS) void queue_kernel(CacheView<IdT> c, con
             if (old != NO_OP) fills[old].dst_line = NO_LINE;   // superseded before it ever ran: output only
             fills[q].dst_line = idx;
             c.pending[idx] = q;
-            c.tags[idx] = (IdT)v;
-            c.stamps[idx] = stamp;
         }
-        clear_miss_bit_word(c, v);
     }
 }
 
@@ -175,8 +183,8 @@ __global__ __launch_bounds__(MV_THREADS) void flush_fill_kernel(CacheView<IdT> c
     for (uint64_t i = g0; i < n; i += n_groups) {
         const FillOp op = fills[i];
         char* line = op.dst_line == NO_LINE ? nullptr : c.cache_data + op.dst_line * c.line_bytes;
-        copy_row<G>(reinterpret_cast<const uint4*>(op.src), reinterpret_cast<uint4*>(op.dst_out),
-                    reinterpret_cast<uint4*>(line), row_u4, sub);
+        copy_row<G>(reinterpret_cast<const v4u*>(op.src), reinterpret_cast<v4u*>(op.dst_out),
+                    reinterpret_cast<v4u*>(line), row_u4, sub);
         if (sub == 0 && line) c.pending[op.dst_line] = NO_OP;
     }
 }
@@ -193,7 +201,7 @@ __global__ __launch_bounds__(MV_THREADS) void flush_copy_kernel(CacheView<IdT> c
     const uint64_t n_groups = (uint64_t)gridDim.x * MV_THREADS / G;
     for (uint64_t i = g0; i < n; i += n_groups) {
         const CopyOp op = copies[i];
-        copy_row<G>(reinterpret_cast<const uint4*>(op.src), reinterpret_cast<uint4*>(op.dst_out), nullptr, row_u4,
+        copy_row<G>(reinterpret_cast<const v4u*>(op.src), reinterpret_cast<v4u*>(op.dst_out), nullptr, row_u4,
                     sub);
     }
 }
@@ -251,23 +259,28 @@ inline uint32_t row_grid(uint64_t rows, int g, int blocks) {
 }  // namespace
 
 template <typename IdT>
-void launch_move(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_u, uint64_t n_upper,
-                 const uint64_t* plan, char* out, int blocks, int link_blocks_max, hipStream_t s) {
+void launch_move(const CacheView<IdT>& c, const IdT* unique, const BatchHdr* hdr, uint64_t n_upper,
+                 const uint64_t* plan, char* out, IdT* unique_out, int blocks, int link_blocks_max, hipStream_t s) {
     const int g = lanes_per_row(c.row_bytes);
-    const uint32_t hbm_blocks = row_grid(n_upper, g, blocks);
-    const uint32_t link_blocks = row_grid(n_upper, g, link_blocks_max);
+    // a wave of the HBM half takes 16 plan entries per step, one of the link half 64
+    const uint32_t hbm_blocks = row_grid(n_upper, 4, blocks);             // 4 waves x 16 rows per workgroup step
+    // the link half scans 64 entries per wave step when the list is long enough to keep all its waves busy
+    // that way, fewer otherwise (short lists are latency-bound: spread them over more waves)
+    uint32_t link_ch = 64;
+    while (link_ch > 4 && n_upper / link_ch < (uint64_t)link_blocks_max * (MV_THREADS / 64)) link_ch >>= 1;
+    const uint32_t link_blocks = row_grid(n_upper, 64 / (int)link_ch, link_blocks_max);
     GIDS_DISPATCH_G(g, hipLaunchKernelGGL((move_kernel<IdT, G>), dim3(link_blocks + hbm_blocks), dim3(MV_THREADS), 0,
-                                          s, c, unique, n_u, plan, out, link_blocks));
+                                          s, c, unique, hdr, plan, out, unique_out, link_blocks, link_ch));
 }
 
 template <typename IdT>
-void launch_queue(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_u, uint64_t n_upper,
-                  const uint64_t* plan, char* out, FillOp* fills, CopyOp* copies, uint32_t, int blocks,
+void launch_queue(const CacheView<IdT>& c, const IdT* unique, const BatchHdr* hdr, uint64_t n_upper,
+                  const uint64_t* plan, char* out, IdT* unique_out, FillOp* fills, CopyOp* copies, int blocks,
                   hipStream_t s) {
     const int g = lanes_per_row(c.row_bytes);
     const uint32_t grid = row_grid(n_upper, g, blocks);
     GIDS_DISPATCH_G(g, hipLaunchKernelGGL((queue_kernel<IdT, G>), dim3(grid), dim3(MV_THREADS), 0, s, c, unique,
-                                          n_u, plan, out, fills, copies));
+                                          hdr, plan, out, unique_out, fills, copies));
 }
 
 template <typename IdT>
@@ -287,10 +300,10 @@ void launch_finalize(Ctl* ctl, StatsRec* rec, uint64_t seq, const uint32_t* n_u,
 }
 
 #define GIDS_INSTANTIATE(IdT)                                                                                       \
-    template void launch_move<IdT>(const CacheView<IdT>&, const IdT*, const uint32_t*, uint64_t, const uint64_t*,   \
-                                   char*, int, int, hipStream_t);                                                        \
-    template void launch_queue<IdT>(const CacheView<IdT>&, const IdT*, const uint32_t*, uint64_t, const uint64_t*,  \
-                                    char*, FillOp*, CopyOp*, uint32_t, int, hipStream_t);                           \
+    template void launch_move<IdT>(const CacheView<IdT>&, const IdT*, const BatchHdr*, uint64_t, const uint64_t*,   \
+                                   char*, IdT*, int, int, hipStream_t);                                             \
+    template void launch_queue<IdT>(const CacheView<IdT>&, const IdT*, const BatchHdr*, uint64_t, const uint64_t*,  \
+                                    char*, IdT*, FillOp*, CopyOp*, int, hipStream_t);                               \
     template void launch_flush<IdT>(const CacheView<IdT>&, FillOp*, CopyOp*, uint64_t, bool, int, hipStream_t);
 GIDS_INSTANTIATE(int32_t)
 GIDS_INSTANTIATE(int64_t)

@@ -55,15 +55,15 @@ class GatherSession:
         raw = np.ascontiguousarray(np.asarray(raw, dtype=self.id_dtype))
         return torch.from_numpy(raw).cuda() if len(raw) else torch.empty(0, dtype=self.torch_id, device="cuda")
 
-    def push(self, ids_dev: torch.Tensor) -> None:
-        stream = torch.cuda.current_stream().cuda_stream
+    def push(self, ids_dev: torch.Tensor, stream: torch.cuda.Stream | None = None) -> None:
+        stream = (stream or torch.cuda.current_stream()).cuda_stream
         B.gids_window_push(self.cache, ids_dev.data_ptr() if ids_dev.numel() else None, ids_dev.numel(), stream)
         self._keep.append(ids_dev)
 
     def gather(self, ids_dev: torch.Tensor | None, out: torch.Tensor, unique: torch.Tensor | None = None,
-               inverse: torch.Tensor | None = None) -> int:
+               inverse: torch.Tensor | None = None, stream: torch.cuda.Stream | None = None) -> int:
         """Enqueue one gather; returns its sequence number (for stats)."""
-        stream = torch.cuda.current_stream().cuda_stream
+        stream = (stream or torch.cuda.current_stream()).cuda_stream
         seq = B.gids_cache_gathers(self.cache)
         n = 0 if ids_dev is None else ids_dev.numel()
         if n == 0:

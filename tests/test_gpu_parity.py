@@ -22,7 +22,7 @@ def gpu():
 
 
 def run_case(gpu, oracle, feats, batches, *, id_dtype, lines, ways, line_bytes, window, threshold=0, hot=None,
-             use_head=False, with_inverse=False, check_state=True, label=""):
+             use_head=False, with_inverse=False, check_state=True, two_streams=False, label=""):
     """Feeds the same raw ID lists to both implementations, protocol: keep window + 1 lists buffered."""
     torch, gids, GatherSession = gpu
     n_rows = feats.shape[0]
@@ -45,11 +45,13 @@ def run_case(gpu, oracle, feats, batches, *, id_dtype, lines, ways, line_bytes, 
         if hot is not None and len(hot):
             ses.pin_hot(hot)
         dev = [ses.to_device(b) for b in batches]
+        torch.cuda.synchronize()
+        push_stream = torch.cuda.Stream() if two_streams else None
         outs, uniqs, invs, seqs = [], [], [], []
         pushed = 0
         for t, raw in enumerate(batches):
             while window and pushed < len(batches) and pushed <= t + window:
-                ses.push(dev[pushed])
+                ses.push(dev[pushed], stream=push_stream)
                 pushed += 1
             cap = max(len(raw), 1)
             out = torch.full((cap, row_bytes), 0xA5, dtype=torch.uint8, device="cuda")
@@ -105,6 +107,31 @@ def test_tiny_config_full_parity(gpu, oracle_mod):
              line_bytes=cfg.line_bytes, window=cfg.window, hot=hot, with_inverse=True, label="tiny")
     run_case(gpu, oracle_mod, feats, batches, id_dtype=np.int32, lines=cfg.cache_lines, ways=cfg.ways,
              line_bytes=cfg.line_bytes, window=cfg.window, hot=hot, use_head=True, label="tiny/head")
+
+
+@pytest.mark.parametrize("window,use_head", [(4, True), (4, False), (1, True), (12, True)])
+def test_pushes_on_their_own_stream(gpu, oracle_mod, window, use_head):
+    """The documented way to overlap classification with row movement: window
+    pushes on one stream, gathers on another, many minibatches in flight."""
+    rng = np.random.default_rng(77 + window)
+    n = 40_000
+    feats = rand_feats(rng, n, 1024)
+    batches = zipf_batches(rng, n, 40, 6000, a=1.12)
+    run_case(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=4096, ways=8, line_bytes=1024, window=window,
+             hot=rng.choice(n, 800, replace=False), use_head=use_head, two_streams=True, label=f"2streams/W{window}")
+
+
+def test_two_streams_without_the_internal_stream(gpu, oracle_mod):
+    """Small caches and accumulating caches run every kernel on the stream of the
+    call; calls that alternate between two streams must still be ordered."""
+    rng = np.random.default_rng(5150)
+    n = 8000
+    feats = rand_feats(rng, n, 256)
+    batches = zipf_batches(rng, n, 24, 1500, a=1.15)
+    for threshold in (0, 500):
+        run_case(gpu, oracle_mod, feats, batches, id_dtype=np.int32, lines=512, ways=4, line_bytes=256, window=3,
+                 threshold=threshold, hot=rng.choice(n, 100, replace=False), use_head=True, two_streams=True,
+                 label=f"2streams-small/thr{threshold}")
 
 
 def test_tiny_config_oracle_generated_inputs(gpu, oracle_mod):
