@@ -75,6 +75,9 @@ def main() -> int:
                     help="run only a plain 1 GiB device copy three times (the known-size kernel that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
     ap.add_argument("--one-stream", action="store_true", help="issue pushes and gathers on the same stream")
+    ap.add_argument("--sweep-skew", action="store_true",
+                    help="run the skew sweep (seed Zipf s in {0, 0.8, 1.2} x window depth in {0, 4, 16}) on the "
+                         "chosen workload's graph and store, one cache per point; prints one JSON object")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     args = ap.parse_args()
@@ -104,43 +107,78 @@ def main() -> int:
 
     base = wl.CONFIGS[args.workload]
     cfg = wl.scaled(base, args.nodes) if args.nodes else pick_scale(base, wl, args.max_pinned_gib)
-    window = cfg.window if args.window < 0 else args.window
     R = cfg.row_bytes
-    steps, warmup = args.steps, args.warmup
-    prewarm = args.prewarm if args.prewarm >= 0 else (1_000_000 if args.workload == "resident" else 0)
-    n_pre = (cfg.n_nodes + prewarm - 1) // prewarm if prewarm else 0
-    warmup += n_pre
-    n_batches = warmup + 2 * steps + window + 1                # timed pass + profiled pass + look-ahead
     log(f"workload {cfg.name}: N={cfg.n_nodes} R={R} lines={cfg.cache_lines} ways={cfg.ways} L={cfg.line_bytes} "
-        f"cpu_rows={cfg.cpu_rows} W={window} fanouts={cfg.fanouts} seeds={cfg.n_seeds}")
-
+        f"cpu_rows={cfg.cpu_rows} fanouts={cfg.fanouts} seeds={cfg.n_seeds}")
     t0 = time.time()
     g = wl.make_graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max, np.dtype(cfg.index_dtype), native=True)
     log(f"graph: {g.n_edges} edges, mean degree {g.n_edges / g.n:.2f} ({time.time() - t0:.1f} s)")
     t0 = time.time()
     hot = wl.hot_nodes(g, cfg.cpu_rows)
     log(f"hot nodes: {len(hot)} ({time.time() - t0:.1f} s)")
-    rank_table = wl.synth.zipf_rank_table(cfg.n_nodes, cfg.seed_zipf_s) if cfg.seed_zipf_s is not None else None
-    t0 = time.time()
-    id_np = np.dtype(cfg.index_dtype)
-    raws = [np.arange(b * prewarm, min(cfg.n_nodes, (b + 1) * prewarm), dtype=np.int64) for b in range(n_pre)]
-    raws += [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds, rank_table) for b in range(n_batches - n_pre)]
-    max_raw = max(len(r) for r in raws)
-    log(f"sampled {n_batches} minibatches, raw IDs per minibatch <= {max_raw} ({time.time() - t0:.1f} s)")
-
     table = wl.normal_table(np.dtype(cfg.feat_dtype))
     t0 = time.time()
-    ses = GatherSession(cfg.n_nodes, R, np.dtype(cfg.index_dtype), cfg.cache_lines, cfg.ways, cfg.line_bytes, window,
-                        args.accum)
-    wl.fill_store(cfg.seed, cfg.n_nodes, cfg.dim, table, ses.store_address())
+    store = gids.gids_store_create(cfg.n_nodes, R, np.dtype(cfg.index_dtype).itemsize)   # pinned by the library
+    wl.fill_store(cfg.seed, cfg.n_nodes, cfg.dim, table, gids.gids_store_host_ptr(store))
     log(f"store: {cfg.n_nodes * R / 1e9:.2f} GB pinned and filled ({time.time() - t0:.1f} s)")
+    env = dict(torch=torch, wl=wl, gids=gids, GatherSession=GatherSession, g=g, hot=hot, table=table, store=store,
+               base=base)
+
+    if args.sweep_skew:
+        # BASELINE's skew sweep: seed IDs Zipf(s) over a seeded permutation of the nodes, window depth 0 / 4 / 16
+        points = []
+        for s_exp in (0.0, 0.8, 1.2):
+            rank_table = wl.synth.zipf_rank_table(cfg.n_nodes, s_exp)
+            n_b = args.warmup + 2 * args.steps + 16 + 1
+            t0 = time.time()
+            raws = [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds, rank_table) for b in range(n_b)]
+            log(f"zipf s={s_exp}: sampled {n_b} minibatches ({time.time() - t0:.1f} s)")
+            for w in (0, 4, 16):
+                res = run_point(args, env, cfg, w, raws, 0)
+                res["config"]["seed_zipf_s"] = s_exp
+                hit = res["per_step"]["hit"] / max(1.0, res["per_step"]["unique"])
+                points.append({"zipf_s": s_exp, "window": w, "gathered_GBs": res["value"], "hit_rate": hit,
+                               "cpu_buffer_rate": res["per_step"]["cpu_hit"] / max(1.0, res["per_step"]["unique"]),
+                               "ms_per_step": res["ms_per_step"], "weighted_roofline_frac": res["weighted_roofline"]["frac"],
+                               "oracle_count_mismatches": res.get("cpu_baseline", {}).get("count_mismatches_vs_gpu")})
+                log(json.dumps(points[-1]))
+        print(json.dumps({"metric": "skew sweep: gathered GB/s and hit rate per (zipf s, window depth)", "n_gpus": 1,
+                          "config": {"workload": cfg.name, "n_nodes": cfg.n_nodes, "steps": args.steps,
+                                     "warmup": args.warmup}, "points": points}))
+        return 0
+
+    window = cfg.window if args.window < 0 else args.window
+    prewarm = args.prewarm if args.prewarm >= 0 else (1_000_000 if args.workload == "resident" else 0)
+    n_pre = (cfg.n_nodes + prewarm - 1) // prewarm if prewarm else 0
+    n_batches = n_pre + args.warmup + 2 * args.steps + window + 1      # timed pass + event-timed pass + look-ahead
+    rank_table = wl.synth.zipf_rank_table(cfg.n_nodes, cfg.seed_zipf_s) if cfg.seed_zipf_s is not None else None
     t0 = time.time()
+    raws = [np.arange(b * prewarm, min(cfg.n_nodes, (b + 1) * prewarm), dtype=np.int64) for b in range(n_pre)]
+    raws += [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds, rank_table) for b in range(n_batches - n_pre)]
+    log(f"sampled {n_batches - n_pre} minibatches, raw IDs per minibatch <= {max(len(r) for r in raws)} "
+        f"({time.time() - t0:.1f} s)")
+    print(json.dumps(run_point(args, env, cfg, window, raws, n_pre)))
+    return 0
+
+
+def run_point(args, env, cfg, window, raws, n_pre):
+    """One timed run of `cfg` with window depth `window` over the raw ID lists `raws`
+    (the first n_pre of them pre-warm lists)."""
+    torch, wl, gids, GatherSession = env["torch"], env["wl"], env["gids"], env["GatherSession"]
+    hot, table, base = env["hot"], env["table"], env["base"]
+    R = cfg.row_bytes
+    steps, warmup = args.steps, args.warmup + n_pre
+    n_batches = warmup + 2 * steps + window + 1
+    assert len(raws) >= n_batches
+    max_raw = max(len(r) for r in raws[:n_batches])
+    t0 = time.time()
+    ses = GatherSession(cfg.n_nodes, R, np.dtype(cfg.index_dtype), cfg.cache_lines, cfg.ways, cfg.line_bytes, window,
+                        args.accum, store_handle=env["store"])
     ses.pin_hot(hot)
     ses.reserve(max_raw)
-    log(f"CPU buffer pinned: {len(hot) * R / 1e9:.2f} GB ({time.time() - t0:.1f} s)")
-
-    dev = [ses.to_device(r) for r in raws]
-    cap_rows = max(len(np.unique(r)) for r in raws)
+    log(f"cache W={window}: created, CPU buffer {len(hot) * R / 1e9:.2f} GB pinned ({time.time() - t0:.1f} s)")
+    dev = [ses.to_device(r) for r in raws[:n_batches]]
+    cap_rows = max(len(np.unique(r)) for r in raws[:n_batches])
     # outputs rotate; with the accumulator on, an output must survive until the flush that completes it
     ring = 2 if args.accum == 0 else 32
     outs = [torch.empty((cap_rows, R), dtype=torch.uint8, device="cuda") for _ in range(ring)]
@@ -287,8 +325,9 @@ def main() -> int:
         if mismatches:
             log(f"WARNING: {mismatches} minibatches differ from the oracle's counters")
     ses.close()
-    print(json.dumps(result))
-    return 0
+    return result
+
+
 
 
 if __name__ == "__main__":

@@ -181,11 +181,25 @@ int64_t go_sort_unique(const int64_t* raw, int64_t n, int64_t* out) {
  * without replacement (Floyd's subset sampling on hashed draws).  The next
  * frontier is the distinct set of nodes this hop sampled.
  * Returns the raw count, or a negative error when `cap` is too small. */
-int64_t go_sample(const go_graph* g, uint64_t seed, int64_t batch, const int32_t* fanouts, int n_layers,
-                  int64_t n_seeds, int64_t* out, int64_t cap) {
+static int64_t sample_impl(const go_graph* g, uint64_t seed, int64_t batch, const int32_t* fanouts, int n_layers,
+                           int64_t n_seeds, const uint64_t* rank_table, int64_t perm_mult, int64_t perm_add,
+                           int64_t* out, int64_t cap) {
     if (n_seeds < 0 || n_seeds > cap) return GO_E_INVAL;
     uint64_t ks = mix64(key0(seed, TAG_SEED) ^ (uint64_t)batch);
-    for (int64_t i = 0; i < n_seeds; i++) out[i] = (int64_t)(mix64(ks ^ (uint64_t)i) % (uint64_t)g->n);
+    for (int64_t i = 0; i < n_seeds; i++) {
+        uint64_t h = mix64(ks ^ (uint64_t)i);
+        if (!rank_table) { out[i] = (int64_t)(h % (uint64_t)g->n); continue; }
+        /* skewed seeds: rank r = number of cumulative thresholds <= (h >> 1), then the
+         * seeded affine permutation (r * mult + add) mod n maps the rank to a node */
+        uint64_t u = h >> 1;
+        int64_t lo = 0, hi = g->n;                 /* first index with table[index] > u */
+        while (lo < hi) {
+            int64_t mid = lo + (hi - lo) / 2;
+            if (rank_table[mid] <= u) lo = mid + 1; else hi = mid;
+        }
+        int64_t r = lo < g->n - 1 ? lo : g->n - 1;
+        out[i] = (int64_t)(((unsigned __int128)(uint64_t)r * (uint64_t)perm_mult + (uint64_t)perm_add) % (uint64_t)g->n);
+    }
     int64_t n_raw = n_seeds;
     int64_t* frontier = (int64_t*)malloc((size_t)(cap > 0 ? cap : 1) * sizeof(int64_t));
     if (!frontier) return GO_E_NOMEM;
@@ -221,6 +235,19 @@ int64_t go_sample(const go_graph* g, uint64_t seed, int64_t batch, const int32_t
     }
     free(frontier);
     return n_raw;
+}
+
+int64_t go_sample(const go_graph* g, uint64_t seed, int64_t batch, const int32_t* fanouts, int n_layers,
+                  int64_t n_seeds, int64_t* out, int64_t cap) {
+    return sample_impl(g, seed, batch, fanouts, n_layers, n_seeds, NULL, 0, 0, out, cap);
+}
+
+/* the same with seed nodes drawn Zipf-ranked: rank_table[r] = floor(2^63 * CDF(r + 1)) over g->n ranks */
+int64_t go_sample_skewed(const go_graph* g, uint64_t seed, int64_t batch, const int32_t* fanouts, int n_layers,
+                         int64_t n_seeds, const uint64_t* rank_table, int64_t perm_mult, int64_t perm_add,
+                         int64_t* out, int64_t cap) {
+    if (!rank_table) return GO_E_INVAL;
+    return sample_impl(g, seed, batch, fanouts, n_layers, n_seeds, rank_table, perm_mult, perm_add, out, cap);
 }
 
 /* --------------------------------------------------------------- features */

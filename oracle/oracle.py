@@ -53,6 +53,10 @@ def lib() -> C.CDLL:
         L.go_sample.restype = C.c_int64
         L.go_sample.argtypes = [C.c_void_p, C.c_uint64, C.c_int64, np.ctypeslib.ndpointer(dtype=np.int32),
                                 C.c_int, C.c_int64, _i64p, C.c_int64]
+        L.go_sample_skewed.restype = C.c_int64
+        L.go_sample_skewed.argtypes = [C.c_void_p, C.c_uint64, C.c_int64, np.ctypeslib.ndpointer(dtype=np.int32),
+                                       C.c_int, C.c_int64, np.ctypeslib.ndpointer(dtype=np.uint64), C.c_int64,
+                                       C.c_int64, _i64p, C.c_int64]
         L.go_feat_row.argtypes = [C.c_uint64, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         L.go_accum_threshold.restype = C.c_double
         L.go_accum_threshold.argtypes = [C.c_double, C.c_double, C.c_double, C.c_double, C.c_int]
@@ -113,14 +117,21 @@ class Graph:
             raise OracleError(rc)
         return out
 
-    def sample(self, seed: int, batch: int, fanouts, n_seeds: int, cap: int | None = None) -> np.ndarray:
+    def sample(self, seed: int, batch: int, fanouts, n_seeds: int, cap: int | None = None,
+               rank_table: np.ndarray | None = None, perm=None) -> np.ndarray:
+        """rank_table / perm = (mult, add): seed nodes Zipf-ranked through an affine permutation"""
         if cap is None:
             cap, w = n_seeds, n_seeds
             for f in fanouts:
                 w *= f
                 cap += w
         out = np.empty(max(cap, 1), dtype=np.int64)
-        n = lib().go_sample(self._h, seed, batch, np.asarray(fanouts, dtype=np.int32), len(fanouts), n_seeds, out, cap)
+        f32 = np.asarray(fanouts, dtype=np.int32)
+        if rank_table is None:
+            n = lib().go_sample(self._h, seed, batch, f32, len(fanouts), n_seeds, out, cap)
+        else:
+            n = lib().go_sample_skewed(self._h, seed, batch, f32, len(fanouts), n_seeds,
+                                       np.ascontiguousarray(rank_table, dtype=np.uint64), perm[0], perm[1], out, cap)
         if n < 0:
             raise OracleError(int(n))
         return out[:n].copy()

@@ -13,7 +13,8 @@ from . import binding as B
 
 class GatherSession:
     def __init__(self, n_rows: int, row_bytes: int, id_dtype, lines: int, ways: int, line_bytes: int,
-                 window: int = 0, accum_threshold: int = 0, host_store: torch.Tensor | None = None):
+                 window: int = 0, accum_threshold: int = 0, host_store: torch.Tensor | None = None,
+                 store_handle: int | None = None):
         if not torch.cuda.is_available():
             raise RuntimeError("GatherSession needs a GPU: the gather has no CPU path")
         self.n_rows, self.row_bytes = n_rows, row_bytes
@@ -21,13 +22,15 @@ class GatherSession:
         self.torch_id = torch.int32 if self.id_dtype.itemsize == 4 else torch.int64
         self.window = window
         self._host_store = host_store
-        self.store = B.gids_store_create(n_rows, row_bytes, self.id_dtype.itemsize,
-                                         None if host_store is None else host_store.data_ptr())
+        self._owns_store = store_handle is None
+        self.store = store_handle if store_handle is not None else B.gids_store_create(
+            n_rows, row_bytes, self.id_dtype.itemsize, None if host_store is None else host_store.data_ptr())
         self.cache = None
         try:
             self.cache = B.gids_cache_create(self.store, lines, ways, line_bytes, window, accum_threshold)
         except Exception:
-            B.gids_store_destroy(self.store)
+            if self._owns_store:
+                B.gids_store_destroy(self.store)
             self.store = None
             raise
         self.lines = lines
@@ -93,7 +96,8 @@ class GatherSession:
             B.gids_cache_destroy(self.cache)
             self.cache = None
         if self.store:
-            B.gids_store_destroy(self.store)
+            if self._owns_store:
+                B.gids_store_destroy(self.store)
             self.store = None
         self._keep.clear()
 

@@ -107,3 +107,16 @@ def test_zipf_seed_draw_is_skewed():
     assert abs(counts.max() / len(seeds) - w[0] / w.sum()) < 0.02
     uni = np.concatenate([wl.minibatch_seeds(5, n, b, 2048, wl.synth.zipf_rank_table(n, 0.0)) for b in range(20)])
     assert np.unique(uni).size > 0.8 * uni.size
+
+
+def test_skewed_seed_samplers_agree(oracle_mod):
+    cfg = CONFIGS["medium"]
+    n = 50_000
+    g_np, g_c = _both_graphs(oracle_mod, cfg, n)
+    for s_exp in (0.0, 0.8, 1.2):
+        tab = wl.synth.zipf_rank_table(n, s_exp)
+        perm = wl.synth.perm_params(cfg.seed, n)
+        for b in (0, 3):
+            raw_np = wl.sample_minibatch(g_np, cfg.seed, b, (25, 10), 512, tab)
+            raw_c = g_c.sample(cfg.seed, b, (25, 10), 512, rank_table=tab, perm=perm)
+            np.testing.assert_array_equal(raw_np, raw_c)

@@ -175,7 +175,7 @@ def minibatch_seeds(seed: int, n: int, batch: int, n_seeds: int, rank_table: np.
     r = np.searchsorted(rank_table, u, side="right").astype(np.int64)
     r = np.minimum(r, n - 1)
     mult, add = perm_params(seed, n)
-    return ((r.astype(object) * mult + add) % n).astype(np.int64)
+    return np.array([(int(x) * mult + add) % n for x in r], dtype=np.int64)
 
 
 def perm_params(seed: int, n: int):
