@@ -128,6 +128,11 @@ int gids_cpu_buffer_pin(gids_cache* cache, const void* ids_host, uint64_t n);
  * GIDS_E_INVAL when window_depth == 0. */
 int gids_window_push(gids_cache* cache, const void* ids_dev, uint64_t n, void* stream);
 
+/* The same with the list's length in device memory (*n_dev <= n_max entries of
+ * ids_dev are valid): for ID lists a GPU sampler produced, whose length the host
+ * never learns.  n_max bounds the work and sizes the window slot. */
+int gids_window_push_dev(gids_cache* cache, const void* ids_dev, uint64_t n_max, const uint32_t* n_dev, void* stream);
+
 /* Gather one minibatch.
  *   ids_dev, n       the raw ID list.  With window_depth > 0 it must have the
  *                    same distinct IDs as the oldest buffered list (else
@@ -175,6 +180,44 @@ int gids_cache_snapshot(gids_cache* cache, int64_t* tags_host, int64_t* stamps_h
  * step time.  Off by default. */
 int gids_profile_enable(gids_cache* cache, int on);
 int gids_profile_read(gids_cache* cache, uint64_t seq, float* ms3);
+
+/* ---- GPU neighbourhood sampler (the stage before the gather) ----------------
+ * Graph structure in CSR form for sampling by GPU threads (Section 3.5: the
+ * structure data is a few percent of the dataset and is kept out of storage).
+ *   indptr_host    n_nodes + 1 int64, indptr[0] == 0
+ *   indices_host   indptr[n_nodes] neighbour IDs of id_bytes each
+ *   zero_copy      0: both arrays are copied into GPU memory (they may be freed
+ *                  after the call); 1: they stay where they are and are read
+ *                  zero-copy, as in the paper - they must then be hipHostMalloc
+ *                  memory that outlives the graph */
+typedef struct gids_graph gids_graph;
+int gids_graph_create(uint64_t n_nodes, const int64_t* indptr_host, const void* indices_host, uint32_t id_bytes,
+                      int zero_copy, gids_graph** out);
+int gids_graph_destroy(gids_graph* graph);
+
+/* Largest raw list a minibatch can have: n_seeds * (1 + f0 + f0*f1 + ...). */
+uint64_t gids_sample_capacity(const uint32_t* fanouts_host, uint32_t n_layers, uint64_t n_seeds);
+
+/* Sample minibatch number `batch` (Section 2.2.2: up to fanout neighbours per
+ * node per layer, uniformly at random, without replacement; each hop expands
+ * the distinct nodes the previous hop reached).  Every draw is a counter-based
+ * hash of (seed, batch, layer, node, draw), so the list is a pure function of
+ * the arguments: seed node i = H(seed, 4, batch, i) mod n_nodes, or, with a
+ * rank table (n_nodes ascending uint64 thresholds, CDF scaled to 2^63, in
+ * device memory), rank = #{thresholds <= H >> 1} mapped to node
+ * (rank * perm_mult + perm_add) mod n_nodes; a node of degree d > fanout f gets
+ * f distinct adjacency slots by Floyd's subset sampling with draws
+ * H(seed, 5, batch, layer, node, j) mod (j + 1), j = d-f .. d-1.  H chains the
+ * SplitMix64 output function; the formulas are spelled out in csrc/sampler.hip.
+ *   raw_dev        receives the seeds, then each hop's neighbours in (node
+ *                  ascending, draw) order, duplicates kept; raw_capacity must
+ *                  be >= gids_sample_capacity(...) (else GIDS_E_SPACE)
+ *   n_raw_dev      device uint32: receives the list's length
+ * Feed the result to gids_window_push_dev / gids_gather.  Calls on one graph
+ * must be ordered by the caller (one stream). */
+int gids_sample(gids_graph* graph, uint64_t seed, uint64_t batch, const uint32_t* fanouts_host, uint32_t n_layers,
+                uint64_t n_seeds, const uint64_t* rank_table_dev, uint64_t perm_mult, uint64_t perm_add, void* raw_dev,
+                uint64_t raw_capacity, uint32_t* n_raw_dev, void* stream);
 
 /* Number of in-flight fills an accumulator needs so that a storage device of
  * `iops_peak` requests/s per device sustains `ratio` of its peak, given the

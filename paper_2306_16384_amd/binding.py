@@ -15,7 +15,8 @@ GIDS_E_INVAL, GIDS_E_NOMEM, GIDS_E_RANGE, GIDS_E_ORDER, GIDS_E_FULL, GIDS_E_HIP,
 EXPORTS = [
     "gids_store_create", "gids_store_host_ptr", "gids_store_destroy", "gids_cache_create", "gids_cache_destroy",
     "gids_cache_reserve", "gids_cpu_buffer_pin", "gids_window_push", "gids_gather", "gids_flush", "gids_stats_read",
-    "gids_cache_gathers", "gids_cache_snapshot", "gids_profile_enable", "gids_profile_read", "gids_accum_threshold", "gids_last_error",
+    "gids_cache_gathers", "gids_cache_snapshot", "gids_profile_enable", "gids_profile_read", "gids_window_push_dev",
+    "gids_graph_create", "gids_graph_destroy", "gids_sample_capacity", "gids_sample", "gids_accum_threshold", "gids_last_error",
 ]
 
 
@@ -62,6 +63,12 @@ def lib() -> C.CDLL:
         L.gids_cache_gathers.restype = u64
         L.gids_cache_gathers.argtypes = [vp]
         L.gids_cache_snapshot.argtypes = [vp, vp, vp]
+        L.gids_window_push_dev.argtypes = [vp, vp, u64, vp, vp]
+        L.gids_graph_create.argtypes = [u64, vp, vp, u32, C.c_int, C.POINTER(vp)]
+        L.gids_graph_destroy.argtypes = [vp]
+        L.gids_sample_capacity.restype = u64
+        L.gids_sample_capacity.argtypes = [C.POINTER(u32), u32, u64]
+        L.gids_sample.argtypes = [vp, u64, u64, C.POINTER(u32), u32, u64, vp, u64, u64, vp, u64, vp, vp]
         L.gids_profile_enable.argtypes = [vp, C.c_int]
         L.gids_profile_read.argtypes = [vp, u64, C.POINTER(C.c_float)]
         L.gids_accum_threshold.restype = C.c_double
@@ -135,6 +142,40 @@ def gids_cache_gathers(cache: int) -> int:
 
 def gids_cache_snapshot(cache: int, tags_host_ptr: int | None, stamps_host_ptr: int | None) -> None:
     _check(lib().gids_cache_snapshot(cache, tags_host_ptr, stamps_host_ptr))
+
+
+def gids_window_push_dev(cache: int, ids_dev_ptr: int, n_max: int, n_dev_ptr: int, stream: int = 0) -> None:
+    _check(lib().gids_window_push_dev(cache, ids_dev_ptr, n_max, n_dev_ptr, stream))
+
+
+def gids_graph_create(n_nodes: int, indptr_host_ptr: int, indices_host_ptr: int, id_bytes: int,
+                      zero_copy: bool = False) -> int:
+    h = C.c_void_p()
+    _check(lib().gids_graph_create(n_nodes, indptr_host_ptr, indices_host_ptr, id_bytes, 1 if zero_copy else 0,
+                                   C.byref(h)))
+    return h.value
+
+
+def gids_graph_destroy(graph: int) -> None:
+    _check(lib().gids_graph_destroy(graph))
+
+
+def _fanouts(fanouts):
+    arr = (C.c_uint32 * len(fanouts))(*[int(f) for f in fanouts])
+    return arr, len(fanouts)
+
+
+def gids_sample_capacity(fanouts, n_seeds: int) -> int:
+    arr, n = _fanouts(fanouts)
+    return int(lib().gids_sample_capacity(arr, n, n_seeds))
+
+
+def gids_sample(graph: int, seed: int, batch: int, fanouts, n_seeds: int, raw_dev_ptr: int, raw_capacity: int,
+                n_raw_dev_ptr: int, stream: int = 0, rank_table_dev_ptr: int | None = None, perm_mult: int = 0,
+                perm_add: int = 0) -> None:
+    arr, n = _fanouts(fanouts)
+    _check(lib().gids_sample(graph, seed, batch, arr, n, n_seeds, rank_table_dev_ptr, perm_mult, perm_add, raw_dev_ptr,
+                             raw_capacity, n_raw_dev_ptr, stream))
 
 
 def gids_profile_enable(cache: int, on: bool) -> None:

@@ -79,7 +79,7 @@ struct gids_cache {
     virtual int init() = 0;
     virtual int reserve(uint64_t n) = 0;
     virtual int pin(const void* ids_host, uint64_t n) = 0;
-    virtual int push(const void* ids, uint64_t n, hipStream_t s) = 0;
+    virtual int push(const void* ids, uint64_t n, const uint32_t* n_dev, hipStream_t s) = 0;
     virtual int gather(const void* ids, uint64_t n, void* out, uint64_t out_cap, void* unique, void* inverse,
                        hipStream_t s) = 0;
     virtual int flush(hipStream_t s) = 0;
@@ -118,7 +118,7 @@ struct gids_cache {
         HIP_TRY(hipStreamWaitEvent(to, e, 0));
         return GIDS_OK;
     }
-    int move_blocks = 65536;    // most workgroups the row mover uses for rows that stay in HBM
+    int move_blocks = 1 << 20;  // most workgroups the row mover uses for rows that stay in HBM
     int link_blocks = 96;       // ... for rows that cross the host link (persistent, grid-stride)
     // optional per-phase timing of each gather (events on the caller's stream)
     bool profile = false;
@@ -239,7 +239,7 @@ struct CacheT final : gids_cache {
         slots.resize(window ? window + 2 : 0);
         if (const char* env = getenv("GIDS_MOVE_BLOCKS")) {
             const int b = atoi(env);
-            if (b >= 1 && b <= 65536) move_blocks = b;
+            if (b >= 1 && b <= (1 << 20)) move_blocks = b;
         }
         if (const char* env = getenv("GIDS_LINK_BLOCKS")) {
             const int b = atoi(env);
@@ -350,14 +350,14 @@ struct CacheT final : gids_cache {
 
     // ascending distinct IDs of ids[0..n) -> dst; count -> *n_out (device)
     void dedup(const IdT* ids, uint64_t n, IdT* dst, uint32_t* n_out, uint8_t* reuse_inc, bool keep_bitmap,
-               hipStream_t s) {
-        launch_mark<IdT>(ids, n, store->n_rows, bitmap, ctl, s);
+               hipStream_t s, const uint32_t* n_dev = nullptr) {
+        launch_mark<IdT>(ids, n, n_dev, store->n_rows, bitmap, ctl, s);
         launch_count(bitmap, n_words, blocksum, blockoff, ctl, n_out, s);
         launch_emit<IdT>(bitmap, n_words, store->n_rows, blockoff, dst, reuse_inc, keep_bitmap ? wrank : nullptr,
                          !keep_bitmap, ctl, s);
     }
 
-    int push(const void* ids, uint64_t n, hipStream_t s) override {
+    int push(const void* ids, uint64_t n, const uint32_t* n_dev, hipStream_t s) override {
         if (window == 0) return fail(GIDS_E_INVAL, "gids_window_push: the cache was created with window_depth 0");
         if (count == window + 1) return fail(GIDS_E_FULL, "gids_window_push: %u lists already buffered", count);
         if (n && !ids) return fail(GIDS_E_INVAL, "gids_window_push: ids_dev is NULL");
@@ -374,7 +374,7 @@ struct CacheT final : gids_cache {
             if (sl.last_reader >= 0) HIP_TRY(hipStreamWaitEvent(meta, events[sl.last_reader % STATS_RING], 0));
             if ((rc = edge(s, meta))) return rc;              // the caller's IDs are ready in its stream's order
         }
-        dedup(static_cast<const IdT*>(ids), n, static_cast<IdT*>(sl.ids), &ctl->win_n[slot], reuse, false, m);
+        dedup(static_cast<const IdT*>(ids), n, static_cast<IdT*>(sl.ids), &ctl->win_n[slot], reuse, false, m, n_dev);
         if (pipelined && (rc = edge(meta, s))) return rc;     // the caller may reuse its ID buffer in stream order
         sl.last_reader = -1;
         count++;
@@ -491,6 +491,100 @@ struct CacheT final : gids_cache {
 
 }  // namespace
 
+
+// ---------------------------------------------------------------- sampler
+
+struct gids_graph {
+    uint64_t n_nodes = 0, n_edges = 0, n_words = 0;
+    uint32_t id_bytes = 0;
+    bool zero_copy = false;
+    const int64_t* indptr = nullptr;     // device-visible
+    const void* indices = nullptr;       // device-visible
+    void* indptr_owned = nullptr;
+    void* indices_owned = nullptr;
+    uint64_t* bitmap = nullptr;
+    uint32_t* blocksum = nullptr;        // bitmap scan
+    uint32_t* blockoff = nullptr;
+    uint32_t* hop_blocksum = nullptr;    // per-hop offsets
+    uint32_t* hop_blockoff = nullptr;
+    uint64_t hop_blocks_cap = 0;
+    Ctl* ctl = nullptr;
+    SamplerState* st = nullptr;
+    void* frontier = nullptr;
+    void* hop_out = nullptr;
+    uint64_t cap_ids = 0;
+
+    ~gids_graph() {
+        (void)hipDeviceSynchronize();
+        if (indptr_owned) (void)hipFree(indptr_owned);
+        if (indices_owned) (void)hipFree(indices_owned);
+        dev_free(bitmap); dev_free(blocksum); dev_free(blockoff); dev_free(hop_blocksum); dev_free(hop_blockoff);
+        dev_free(ctl); dev_free(st);
+        if (frontier) (void)hipFree(frontier);
+        if (hop_out) (void)hipFree(hop_out);
+    }
+
+    int ensure(uint64_t ids, uint64_t hop_blocks) {
+        if (ids > cap_ids) {
+            HIP_TRY(hipDeviceSynchronize());
+            if (frontier) (void)hipFree(frontier);
+            if (hop_out) (void)hipFree(hop_out);
+            frontier = hop_out = nullptr; cap_ids = 0;
+            HIP_TRY(hipMalloc(&frontier, ids * id_bytes));
+            HIP_TRY(hipMalloc(&hop_out, ids * id_bytes));
+            cap_ids = ids;
+        }
+        if (hop_blocks > hop_blocks_cap) {
+            HIP_TRY(hipDeviceSynchronize());
+            dev_free(hop_blocksum); dev_free(hop_blockoff);
+            hop_blocks_cap = 0;
+            int rc;
+            if ((rc = dev_alloc(&hop_blocksum, hop_blocks))) return rc;
+            if ((rc = dev_alloc(&hop_blockoff, hop_blocks))) return rc;
+            hop_blocks_cap = hop_blocks;
+        }
+        return GIDS_OK;
+    }
+
+    template <typename IdT>
+    int sample(uint64_t seed, uint64_t batch, const uint32_t* fanouts, uint32_t n_layers, uint64_t n_seeds,
+               const uint64_t* rank_table, uint64_t perm_mult, uint64_t perm_add, IdT* raw, uint32_t* n_raw_dev,
+               hipStream_t s) {
+        // bounds known on the host: hop l has at most n_seeds * f_0 * ... * f_(l-1) frontier nodes
+        uint64_t front = std::min<uint64_t>(n_seeds, n_nodes), max_ids = std::max<uint64_t>(n_seeds, 1);
+        for (uint32_t l = 0; l < n_layers; l++) {
+            const uint64_t produced = front * fanouts[l];
+            max_ids = std::max(max_ids, produced);
+            front = std::min<uint64_t>(produced, n_nodes);
+        }
+        const uint64_t max_front = std::min<uint64_t>(max_ids, n_nodes);
+        int rc = ensure(max_ids, (max_front + 255) / 256 + 1);
+        if (rc) return rc;
+        const uint64_t ks = sampler_mix(sampler_key(seed, 4) ^ batch);
+        launch_seeds<IdT>(ks, n_seeds, n_nodes, rank_table, perm_mult, perm_add, raw, st, s);
+        const IdT* hop_in = raw;                        // hop 0 expands the distinct seeds
+        uint64_t in_upper = n_seeds;
+        const uint32_t* in_count = nullptr;             // seeds: count known on the host
+        front = std::min<uint64_t>(n_seeds, n_nodes);
+        for (uint32_t l = 0; l < n_layers; l++) {
+            // frontier = ascending distinct IDs of the previous hop's output
+            launch_mark<IdT>(hop_in, in_upper, in_count, n_nodes, bitmap, ctl, s);
+            launch_count(bitmap, n_words, blocksum, blockoff, ctl, &ctl->n_unique, s);
+            launch_emit<IdT>(bitmap, n_words, n_nodes, blockoff, static_cast<IdT*>(frontier), nullptr, nullptr, true, ctl, s);
+            const uint64_t kl = sampler_mix(sampler_mix(sampler_key(seed, 5) ^ batch) ^ (uint64_t)l);
+            launch_hop<IdT>(static_cast<const IdT*>(frontier), &ctl->n_unique, front, indptr,
+                            static_cast<const IdT*>(indices), fanouts[l], kl, hop_blocksum, hop_blockoff, raw,
+                            static_cast<IdT*>(hop_out), st, s);
+            hop_in = static_cast<const IdT*>(hop_out);
+            in_upper = front * fanouts[l];
+            in_count = &st->layer_count;
+            front = std::min<uint64_t>(in_upper, n_nodes);
+        }
+        HIP_TRY(hipMemcpyAsync(n_raw_dev, &st->n_raw, sizeof(uint32_t), hipMemcpyDeviceToDevice, s));
+        return GIDS_OK;
+    }
+};
+
 extern "C" {
 
 const char* gids_last_error(void) { return g_err; }
@@ -585,7 +679,14 @@ int gids_cpu_buffer_pin(gids_cache* cache, const void* ids_host, uint64_t n) {
 int gids_window_push(gids_cache* cache, const void* ids_dev, uint64_t n, void* stream) {
     CHECK_CACHE(cache);
     if (n > 0xFFFFFFF0ull) return fail(GIDS_E_INVAL, "gids_window_push: list too long");
-    return cache->push(ids_dev, n, static_cast<hipStream_t>(stream));
+    return cache->push(ids_dev, n, nullptr, static_cast<hipStream_t>(stream));
+}
+
+int gids_window_push_dev(gids_cache* cache, const void* ids_dev, uint64_t n_max, const uint32_t* n_dev, void* stream) {
+    CHECK_CACHE(cache);
+    if (n_max > 0xFFFFFFF0ull) return fail(GIDS_E_INVAL, "gids_window_push_dev: list too long");
+    if (!n_dev) return fail(GIDS_E_INVAL, "gids_window_push_dev: n_dev is NULL");
+    return cache->push(ids_dev, n_max, n_dev, static_cast<hipStream_t>(stream));
 }
 
 int gids_gather(gids_cache* cache, const void* ids_dev, uint64_t n, void* out_dev, uint64_t out_capacity_rows,
@@ -642,6 +743,89 @@ uint64_t gids_cache_gathers(const gids_cache* cache) { return cache ? cache->seq
 int gids_cache_snapshot(gids_cache* cache, int64_t* tags_host, int64_t* stamps_host) {
     if (!cache) return fail(GIDS_E_INVAL, "gids_cache_snapshot: cache is NULL");
     return cache->snapshot(tags_host, stamps_host);
+}
+
+
+int gids_graph_create(uint64_t n_nodes, const int64_t* indptr_host, const void* indices_host, uint32_t id_bytes,
+                      int zero_copy, gids_graph** out) {
+    if (!out) return fail(GIDS_E_INVAL, "gids_graph_create: out is NULL");
+    *out = nullptr;
+    if (!indptr_host || !indices_host || n_nodes == 0) return fail(GIDS_E_INVAL, "gids_graph_create: NULL or empty graph");
+    if (id_bytes != 4 && id_bytes != 8) return fail(GIDS_E_INVAL, "gids_graph_create: id_bytes must be 4 or 8");
+    if (id_bytes == 4 && n_nodes > 0x7FFFFFFFull) return fail(GIDS_E_INVAL, "gids_graph_create: n_nodes does not fit 4-byte IDs");
+    if (indptr_host[0] != 0 || indptr_host[n_nodes] < 0) return fail(GIDS_E_INVAL, "gids_graph_create: indptr must start at 0");
+    gids_graph* g = new (std::nothrow) gids_graph();
+    if (!g) return fail(GIDS_E_NOMEM, "gids_graph_create: out of host memory");
+    g->n_nodes = n_nodes; g->n_edges = (uint64_t)indptr_host[n_nodes]; g->id_bytes = id_bytes; g->zero_copy = zero_copy != 0;
+    g->n_words = (n_nodes + 63) / 64;
+    auto bail = [&](int rc) { delete g; return rc; };
+    if (zero_copy) {
+        void *p = nullptr, *q = nullptr;
+        hipError_t e = hipHostGetDevicePointer(&p, const_cast<int64_t*>(indptr_host), 0);
+        if (e == hipSuccess) e = hipHostGetDevicePointer(&q, const_cast<void*>(indices_host), 0);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            return bail(fail(GIDS_E_HIP, "gids_graph_create: zero_copy needs arrays allocated with hipHostMalloc (%s)", hipGetErrorString(e)));
+        }
+        g->indptr = static_cast<const int64_t*>(p); g->indices = q;
+    } else {
+        hipError_t e = hipMalloc(&g->indptr_owned, (n_nodes + 1) * sizeof(int64_t));
+        if (e == hipSuccess) e = hipMalloc(&g->indices_owned, std::max<uint64_t>(g->n_edges, 1) * id_bytes);
+        if (e == hipSuccess) e = hipMemcpy(g->indptr_owned, indptr_host, (n_nodes + 1) * sizeof(int64_t), hipMemcpyHostToDevice);
+        if (e == hipSuccess && g->n_edges) e = hipMemcpy(g->indices_owned, indices_host, g->n_edges * id_bytes, hipMemcpyHostToDevice);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            return bail(fail(e == hipErrorOutOfMemory ? GIDS_E_NOMEM : GIDS_E_HIP, "gids_graph_create: %s", hipGetErrorString(e)));
+        }
+        g->indptr = static_cast<const int64_t*>(g->indptr_owned); g->indices = g->indices_owned;
+    }
+    int rc;
+    if ((rc = dev_alloc(&g->bitmap, g->n_words))) return bail(rc);
+    const uint32_t nb = scan_blocks(g->n_words);
+    if ((rc = dev_alloc(&g->blocksum, nb))) return bail(rc);
+    if ((rc = dev_alloc(&g->blockoff, nb))) return bail(rc);
+    if ((rc = dev_alloc(&g->ctl, 1))) return bail(rc);
+    if ((rc = dev_alloc(&g->st, 1))) return bail(rc);
+    hipError_t e = hipMemset(g->bitmap, 0, g->n_words * sizeof(uint64_t));
+    if (e == hipSuccess) e = hipMemset(g->ctl, 0, sizeof(Ctl));
+    if (e == hipSuccess) e = hipMemset(g->st, 0, sizeof(SamplerState));
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) return bail(fail(GIDS_E_HIP, "gids_graph_create: %s", hipGetErrorString(e)));
+    *out = g;
+    return GIDS_OK;
+}
+
+int gids_graph_destroy(gids_graph* graph) {
+    delete graph;
+    return GIDS_OK;
+}
+
+uint64_t gids_sample_capacity(const uint32_t* fanouts, uint32_t n_layers, uint64_t n_seeds) {
+    uint64_t total = n_seeds, width = n_seeds;
+    for (uint32_t l = 0; l < n_layers; l++) {
+        width *= fanouts ? fanouts[l] : 0;
+        total += width;
+    }
+    return total;
+}
+
+int gids_sample(gids_graph* graph, uint64_t seed, uint64_t batch, const uint32_t* fanouts, uint32_t n_layers,
+                uint64_t n_seeds, const uint64_t* rank_table_dev, uint64_t perm_mult, uint64_t perm_add, void* raw_dev,
+                uint64_t raw_capacity, uint32_t* n_raw_dev, void* stream) {
+    if (!graph || !raw_dev || !n_raw_dev) return fail(GIDS_E_INVAL, "gids_sample: NULL argument");
+    if (n_layers > 8 || (n_layers && !fanouts)) return fail(GIDS_E_INVAL, "gids_sample: at most 8 layers");
+    for (uint32_t l = 0; l < n_layers; l++)
+        if (fanouts[l] < 1 || fanouts[l] > 64) return fail(GIDS_E_INVAL, "gids_sample: fanouts must be in [1, 64]");
+    const uint64_t need = gids_sample_capacity(fanouts, n_layers, n_seeds);
+    if (need > 0xFFFFFFF0ull) return fail(GIDS_E_INVAL, "gids_sample: minibatch too large");
+    if (raw_capacity < need) return fail(GIDS_E_SPACE, "gids_sample: raw_dev must hold %llu IDs (gids_sample_capacity)", (unsigned long long)need);
+    if (rank_table_dev && graph->n_nodes >= (1ull << 31)) return fail(GIDS_E_INVAL, "gids_sample: ranked seeds need n_nodes < 2^31");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (graph->id_bytes == 4)
+        return graph->sample<int32_t>(seed, batch, fanouts, n_layers, n_seeds, rank_table_dev, perm_mult, perm_add,
+                                      static_cast<int32_t*>(raw_dev), n_raw_dev, s);
+    return graph->sample<int64_t>(seed, batch, fanouts, n_layers, n_seeds, rank_table_dev, perm_mult, perm_add,
+                                  static_cast<int64_t*>(raw_dev), n_raw_dev, s);
 }
 
 double gids_accum_threshold(double iops_peak, double t_initial, double t_termination, double ratio, int n_ssd) {

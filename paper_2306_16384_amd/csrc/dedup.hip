@@ -12,12 +12,13 @@
 //          its offset: the output is the ascending distinct ID list.
 // No comparison sort, no global hash table, deterministic output.
 #include "gids_dev.h"
+#include "scan.h"
 
 namespace gids {
 
 namespace {
 
-constexpr int DD_THREADS = 256;
+constexpr int DD_THREADS = SCAN_THREADS;
 constexpr int MARK_ITEMS = 4;            // raw IDs per thread per tile
 constexpr int TAB_LOG = 11;              // LDS hash set: 2048 slots x 8 B = 16 KiB
 constexpr int TAB_SLOTS = 1 << TAB_LOG;
@@ -26,39 +27,12 @@ constexpr unsigned long long TAB_EMPTY = ~0ull;
 constexpr int WORDS_PER_THREAD = 4;
 constexpr int WORDS_PER_BLOCK = DD_THREADS * WORDS_PER_THREAD;
 
-__device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63; }
-
-__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x) {
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        uint32_t y = __shfl_up(x, d);
-        if (lane_id() >= (uint32_t)d) x += y;
-    }
-    return x;
-}
-
-// exclusive prefix of x over the 256 threads of the block; *total = block sum
-__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t x, uint32_t* total, uint32_t* smem /* >= 5 */) {
-    const uint32_t incl = wave_inclusive_scan(x);
-    const uint32_t wave = threadIdx.x >> 6;
-    __syncthreads();                      // smem may still be read from a previous call
-    if (lane_id() == 63) smem[wave] = incl;
-    __syncthreads();
-    uint32_t base = 0, sum = 0;
-#pragma unroll
-    for (int w = 0; w < DD_THREADS / 64; w++) {
-        const uint32_t s = smem[w];
-        if ((uint32_t)w < wave) base += s;
-        sum += s;
-    }
-    *total = sum;
-    return base + incl - x;
-}
-
 template <typename IdT>
-__global__ __launch_bounds__(DD_THREADS) void mark_kernel(const IdT* __restrict__ ids, uint64_t n, uint64_t n_rows,
+__global__ __launch_bounds__(DD_THREADS) void mark_kernel(const IdT* __restrict__ ids, uint64_t n,
+                                                          const uint32_t* __restrict__ n_dev, uint64_t n_rows,
                                                           uint64_t* __restrict__ bitmap, Ctl* ctl) {
     __shared__ unsigned long long tab[TAB_SLOTS];
+    if (n_dev) n = *n_dev;                // the list's length is only known on the device (n was its bound)
     __shared__ uint32_t fresh_total;
     for (int i = threadIdx.x; i < TAB_SLOTS; i += DD_THREADS) tab[i] = TAB_EMPTY;
     if (threadIdx.x == 0) fresh_total = 0;
@@ -228,10 +202,11 @@ inline uint32_t blocks_for(uint64_t items, uint64_t per_block, uint32_t cap) {
 uint32_t scan_blocks(uint64_t n_words) { return (uint32_t)((n_words + WORDS_PER_BLOCK - 1) / WORDS_PER_BLOCK); }
 
 template <typename IdT>
-void launch_mark(const IdT* ids, uint64_t n, uint64_t n_rows, uint64_t* bitmap, Ctl* ctl, hipStream_t s) {
+void launch_mark(const IdT* ids, uint64_t n, const uint32_t* n_dev, uint64_t n_rows, uint64_t* bitmap, Ctl* ctl,
+                 hipStream_t s) {
     if (n == 0) return;
     const uint32_t grid = blocks_for(n, (uint64_t)DD_THREADS * MARK_ITEMS, 2048);
-    hipLaunchKernelGGL(mark_kernel<IdT>, dim3(grid), dim3(DD_THREADS), 0, s, ids, n, n_rows, bitmap, ctl);
+    hipLaunchKernelGGL(mark_kernel<IdT>, dim3(grid), dim3(DD_THREADS), 0, s, ids, n, n_dev, n_rows, bitmap, ctl);
 }
 
 void launch_count(const uint64_t* bitmap, uint64_t n_words, uint32_t* blocksum, uint32_t* blockoff, Ctl* ctl,
@@ -278,7 +253,7 @@ void launch_fill_i64(int64_t* p, uint64_t n, int64_t value, hipStream_t s) {
 }
 
 #define GIDS_INSTANTIATE(IdT)                                                                                      \
-    template void launch_mark<IdT>(const IdT*, uint64_t, uint64_t, uint64_t*, Ctl*, hipStream_t);                  \
+    template void launch_mark<IdT>(const IdT*, uint64_t, const uint32_t*, uint64_t, uint64_t*, Ctl*, hipStream_t); \
     template void launch_emit<IdT>(uint64_t*, uint64_t, uint64_t, const uint32_t*, IdT*, uint8_t*, uint32_t*, bool, \
                                    Ctl*, hipStream_t);                                                             \
     template void launch_verify<IdT>(const IdT*, const IdT*, const uint32_t*, Ctl*, uint64_t, hipStream_t);        \

@@ -85,10 +85,19 @@ struct CacheView {
     Ctl* ctl;
 };
 
+// Device-side counters of the neighbour sampler.
+struct SamplerState {
+    uint32_t n_raw;         // raw IDs written so far (seeds + every finished hop)
+    uint32_t layer_base;    // where the current hop's neighbours start in the raw list
+    uint32_t layer_count;   // how many the current hop produced
+    uint32_t ticket;
+};
+
 // ---- launchers (defined in the .hip files) ---------------------------------
 
 template <typename IdT>
-void launch_mark(const IdT* ids, uint64_t n, uint64_t n_rows, uint64_t* bitmap, Ctl* ctl, hipStream_t s);
+void launch_mark(const IdT* ids, uint64_t n, const uint32_t* n_dev, uint64_t n_rows, uint64_t* bitmap, Ctl* ctl,
+                 hipStream_t s);
 
 void launch_count(const uint64_t* bitmap, uint64_t n_words, uint32_t* blocksum, uint32_t* blockoff, Ctl* ctl,
                   uint32_t* n_out, hipStream_t s);
@@ -132,6 +141,19 @@ void launch_queue(const CacheView<IdT>& c, const IdT* unique, const BatchHdr* hd
 template <typename IdT>
 void launch_flush(const CacheView<IdT>& c, FillOp* fills, CopyOp* copies, uint64_t threshold, bool force,
                   int blocks, hipStream_t s);
+
+uint64_t sampler_key(uint64_t seed, uint64_t tag);
+uint64_t sampler_mix(uint64_t z);
+
+template <typename IdT>
+void launch_seeds(uint64_t ks, uint64_t n_seeds, uint64_t n_nodes, const uint64_t* rank_table, uint64_t perm_mult,
+                  uint64_t perm_add, IdT* raw, SamplerState* st, hipStream_t s);
+
+// one hop: frontier -> neighbours appended to raw[] and written to hop_out[] (the next frontier's input)
+template <typename IdT>
+void launch_hop(const IdT* frontier, const uint32_t* n_front, uint64_t front_upper, const int64_t* indptr,
+                const IdT* indices, uint32_t fanout, uint64_t kl, uint32_t* blocksum, uint32_t* blockoff, IdT* raw,
+                IdT* hop_out, SamplerState* st, hipStream_t s);
 
 void launch_finalize(Ctl* ctl, StatsRec* rec, uint64_t seq, const uint32_t* n_u, hipStream_t s);
 

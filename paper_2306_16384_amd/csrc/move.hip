@@ -16,6 +16,8 @@
 //             pending (or on request).
 //   finalize  publishes the minibatch's counters to host-visible memory and
 //             advances the minibatch stamp.
+#include <cstdlib>
+
 #include "gids_dev.h"
 
 namespace gids {
@@ -69,7 +71,7 @@ __global__ __launch_bounds__(MV_THREADS) void move_kernel(CacheView<IdT> c, cons
                                                           const BatchHdr* __restrict__ hdr,
                                                           const uint64_t* __restrict__ plan, char* __restrict__ out,
                                                           IdT* __restrict__ unique_out, uint32_t link_blocks,
-                                                          uint32_t link_ch) {
+                                                          uint32_t link_ch, uint32_t hbm_ch) {
     if (!hdr->ok) return;
     const uint32_t n_u = hdr->n_u;
     const uint32_t row_u4 = c.row_bytes >> 4;
@@ -77,7 +79,7 @@ __global__ __launch_bounds__(MV_THREADS) void move_kernel(CacheView<IdT> c, cons
     const uint32_t sub = lane % G, grp = lane / G;
     constexpr uint32_t PER_ITER = 64 / G;                     // rows a wave moves at once
     const bool link_role = blockIdx.x < link_blocks;
-    const uint32_t ch = link_role ? link_ch : 16u;            // plan entries a wave scans per step
+    const uint32_t ch = link_role ? link_ch : hbm_ch;         // plan entries a wave scans per step
     const uint32_t role_block = link_role ? blockIdx.x : blockIdx.x - link_blocks;
     const uint32_t role_blocks = link_role ? link_blocks : gridDim.x - link_blocks;
     const uint64_t wave0 = ((uint64_t)role_block * MV_THREADS + threadIdx.x) >> 6;
@@ -263,14 +265,19 @@ void launch_move(const CacheView<IdT>& c, const IdT* unique, const BatchHdr* hdr
                  const uint64_t* plan, char* out, IdT* unique_out, int blocks, int link_blocks_max, hipStream_t s) {
     const int g = lanes_per_row(c.row_bytes);
     // a wave of the HBM half takes 16 plan entries per step, one of the link half 64
-    const uint32_t hbm_blocks = row_grid(n_upper, 4, blocks);             // 4 waves x 16 rows per workgroup step
+    static const uint32_t hbm_ch = [] {
+        const char* e = getenv("GIDS_HBM_CHUNK");
+        const int v = e ? atoi(e) : 16;
+        return (uint32_t)((v == 1 || v == 2 || v == 4 || v == 8 || v == 16 || v == 32 || v == 64) ? v : 16);
+    }();
+    const uint32_t hbm_blocks = row_grid(n_upper, 64 / (int)hbm_ch, blocks);   // 4 waves x hbm_ch rows per workgroup step
     // the link half scans 64 entries per wave step when the list is long enough to keep all its waves busy
     // that way, fewer otherwise (short lists are latency-bound: spread them over more waves)
     uint32_t link_ch = 64;
     while (link_ch > 4 && n_upper / link_ch < (uint64_t)link_blocks_max * (MV_THREADS / 64)) link_ch >>= 1;
     const uint32_t link_blocks = row_grid(n_upper, 64 / (int)link_ch, link_blocks_max);
     GIDS_DISPATCH_G(g, hipLaunchKernelGGL((move_kernel<IdT, G>), dim3(link_blocks + hbm_blocks), dim3(MV_THREADS), 0,
-                                          s, c, unique, hdr, plan, out, unique_out, link_blocks, link_ch));
+                                          s, c, unique, hdr, plan, out, unique_out, link_blocks, link_ch, hbm_ch));
 }
 
 template <typename IdT>

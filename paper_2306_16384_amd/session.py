@@ -63,6 +63,12 @@ class GatherSession:
         B.gids_window_push(self.cache, ids_dev.data_ptr() if ids_dev.numel() else None, ids_dev.numel(), stream)
         self._keep.append(ids_dev)
 
+    def push_dev(self, ids_dev: torch.Tensor, n_dev: torch.Tensor, stream: torch.cuda.Stream | None = None) -> None:
+        """Push a list whose length lives in device memory (n_dev: uint32/int32 scalar tensor)."""
+        stream = (stream or torch.cuda.current_stream()).cuda_stream
+        B.gids_window_push_dev(self.cache, ids_dev.data_ptr(), ids_dev.numel(), n_dev.data_ptr(), stream)
+        self._keep.append((ids_dev, n_dev))
+
     def gather(self, ids_dev: torch.Tensor | None, out: torch.Tensor, unique: torch.Tensor | None = None,
                inverse: torch.Tensor | None = None, stream: torch.cuda.Stream | None = None) -> int:
         """Enqueue one gather; returns its sequence number (for stats)."""
@@ -100,6 +106,55 @@ class GatherSession:
                 B.gids_store_destroy(self.store)
             self.store = None
         self._keep.clear()
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class GraphSampler:
+    """Owns a gids_graph handle; argument marshalling for gids_sample."""
+
+    def __init__(self, indptr: np.ndarray, indices: np.ndarray, zero_copy: bool = False):
+        if not torch.cuda.is_available():
+            raise RuntimeError("GraphSampler needs a GPU")
+        self.id_dtype = indices.dtype
+        self.torch_id = torch.int32 if indices.dtype.itemsize == 4 else torch.int64
+        self.n_nodes = len(indptr) - 1
+        if zero_copy:                      # the arrays must live in pinned (hipHostMalloc) memory
+            self._indptr = torch.from_numpy(np.ascontiguousarray(indptr, dtype=np.int64)).pin_memory()
+            self._indices = torch.from_numpy(np.ascontiguousarray(indices)).pin_memory()
+            a, b = self._indptr.data_ptr(), self._indices.data_ptr()
+        else:
+            self._indptr = np.ascontiguousarray(indptr, dtype=np.int64)
+            self._indices = np.ascontiguousarray(indices)
+            a, b = self._indptr.ctypes.data, self._indices.ctypes.data
+        self.graph = B.gids_graph_create(self.n_nodes, a, b, indices.dtype.itemsize, zero_copy)
+        if not zero_copy:
+            self._indptr = self._indices = None
+
+    def capacity(self, fanouts, n_seeds: int) -> int:
+        return B.gids_sample_capacity(fanouts, n_seeds)
+
+    def sample(self, seed: int, batch: int, fanouts, n_seeds: int, raw: torch.Tensor, n_raw: torch.Tensor,
+               stream: torch.cuda.Stream | None = None, rank_table: torch.Tensor | None = None, perm=(0, 0)) -> None:
+        stream = (stream or torch.cuda.current_stream()).cuda_stream
+        B.gids_sample(self.graph, seed, batch, fanouts, n_seeds, raw.data_ptr(), raw.numel(), n_raw.data_ptr(), stream,
+                      None if rank_table is None else rank_table.data_ptr(), perm[0], perm[1])
+
+    def close(self) -> None:
+        if self.graph:
+            torch.cuda.synchronize()
+            B.gids_graph_destroy(self.graph)
+            self.graph = None
 
     def __enter__(self):
         return self
