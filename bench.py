@@ -78,6 +78,9 @@ def main() -> int:
     ap.add_argument("--sweep-skew", action="store_true",
                     help="run the skew sweep (seed Zipf s in {0, 0.8, 1.2} x window depth in {0, 4, 16}) on the "
                          "chosen workload's graph and store, one cache per point; prints one JSON object")
+    ap.add_argument("--gpu-sampler", action="store_true",
+                    help="produce every minibatch's ID list with the library's GPU neighbourhood sampler (graph in "
+                         "HBM) inside the step, and push it without the host seeing it; also times the sampler alone")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     args = ap.parse_args()
@@ -178,6 +181,19 @@ def run_point(args, env, cfg, window, raws, n_pre):
     ses.reserve(max_raw)
     log(f"cache W={window}: created, CPU buffer {len(hot) * R / 1e9:.2f} GB pinned ({time.time() - t0:.1f} s)")
     dev = [ses.to_device(r) for r in raws[:n_batches]]
+    sampler = None
+    if args.gpu_sampler:
+        from paper_2306_16384_amd.session import GraphSampler
+        g = env["g"]
+        t0 = time.time()
+        sampler = GraphSampler(g.indptr, g.indices)
+        cap_raw = sampler.capacity(cfg.fanouts, cfg.n_seeds)
+        ses.reserve(max(max_raw, cap_raw))
+        n_slots = window + 3
+        raw_bufs = [torch.empty(cap_raw, dtype=ses.torch_id, device="cuda") for _ in range(n_slots)]
+        n_bufs = [torch.zeros(1, dtype=torch.int32, device="cuda") for _ in range(n_slots)]
+        log(f"GPU sampler: graph copied to HBM ({(g.indptr.nbytes + g.indices.nbytes) / 1e9:.2f} GB, "
+            f"{time.time() - t0:.1f} s), raw capacity {cap_raw} IDs per minibatch")
     cap_rows = max(len(np.unique(r)) for r in raws[:n_batches])
     # outputs rotate; with the accumulator on, an output must survive until the flush that completes it
     ring = 2 if args.accum == 0 else 32
@@ -194,7 +210,13 @@ def run_point(args, env, cfg, window, raws, n_pre):
     def keep_window_full(t):
         nonlocal pushed
         while window and pushed < n_batches and pushed <= t + window:
-            ses.push(dev[pushed], stream=push_stream)
+            if sampler is not None and pushed >= n_pre:         # list number pushed - n_pre of the sampled sequence
+                k = pushed % n_slots
+                sampler.sample(cfg.seed, pushed - n_pre, cfg.fanouts, cfg.n_seeds, raw_bufs[k], n_bufs[k],
+                               stream=push_stream)
+                ses.push_dev(raw_bufs[k], n_bufs[k], stream=push_stream)
+            else:
+                ses.push(dev[pushed], stream=push_stream)
             pushed += 1
 
     def step(t):
@@ -267,7 +289,7 @@ def run_point(args, env, cfg, window, raws, n_pre):
         "unique_ids_per_s": n_unique * scale / (total_ms * 1e-3),
         "config": {"workload": cfg.name, "n_nodes": cfg.n_nodes, "row_bytes": R, "cache_lines": cfg.cache_lines,
                    "ways": cfg.ways, "line_bytes": cfg.line_bytes, "cpu_buffer_rows": cfg.cpu_rows, "window": window,
-                   "fanouts": list(cfg.fanouts), "seeds_per_batch": cfg.n_seeds, "accum_threshold": args.accum, "prewarm_lists": n_pre,
+                   "fanouts": list(cfg.fanouts), "seeds_per_batch": cfg.n_seeds, "accum_threshold": args.accum, "prewarm_lists": n_pre, "gpu_sampler": bool(args.gpu_sampler),
                    "id_dtype": cfg.index_dtype, "scaled_from": base.n_nodes if cfg.n_nodes != base.n_nodes else None},
         "per_step": {"unique": n_unique * scale / steps, "hit": n_hit * scale / steps, "cpu_hit": n_cpu * scale / steps,
                      "miss": n_miss * scale / steps, "bypass": n_byp * scale / steps},
@@ -277,6 +299,33 @@ def run_point(args, env, cfg, window, raws, n_pre):
                               "roofline_gathered_GBs": gathered_bytes / (t_roof_ms * 1e-3) / 1e9},
         "roofline": roof,
     }
+
+    if sampler is not None:
+        # the sampler alone: back-to-back minibatches on one stream, and the oracle's sampler on the host
+        n_s = min(20, n_batches - n_pre)
+        torch.cuda.synchronize()
+        s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s0.record()
+        for b in range(n_s):
+            sampler.sample(cfg.seed, b, cfg.fanouts, cfg.n_seeds, raw_bufs[0], n_bufs[0])
+        s1.record()
+        torch.cuda.synchronize()
+        gpu_ms = s0.elapsed_time(s1) / n_s
+        last = raw_bufs[0][:int(n_bufs[0].item())].cpu().numpy().astype(np.int64)
+        raw_ids = float(np.mean([len(r) for r in raws[n_pre:n_pre + n_s]]))
+        result["sampler"] = {"gpu_ms_per_minibatch": gpu_ms, "raw_ids_per_minibatch": raw_ids,
+                             "raw_ids_per_s": raw_ids / (gpu_ms * 1e-3), "graph": "CSR in HBM",
+                             "list_equals_reference": bool(np.array_equal(last, raws[n_pre + n_s - 1]))}
+        if not args.no_cpu:
+            import oracle
+            og = oracle.Graph(cfg.seed, cfg.n_nodes, csr=(env["g"].indptr, env["g"].indices))
+            t0 = time.perf_counter()
+            n_o = 0
+            while n_o < n_s and time.perf_counter() - t0 < 10.0:
+                og.sample(cfg.seed, n_o, cfg.fanouts, cfg.n_seeds)
+                n_o += 1
+            result["sampler"]["cpu_oracle_ms_per_minibatch"] = (time.perf_counter() - t0) / n_o * 1e3
+            del og
 
     # sampled check of the timed configuration against the definition (row = closed-form feature row)
     if not args.no_check:
@@ -325,6 +374,8 @@ def run_point(args, env, cfg, window, raws, n_pre):
         if mismatches:
             log(f"WARNING: {mismatches} minibatches differ from the oracle's counters")
     ses.close()
+    if sampler is not None:
+        sampler.close()
     return result
 
 
