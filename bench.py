@@ -128,7 +128,7 @@ def main() -> int:
                base=base)
 
     if args.sweep_skew:
-        # BASELINE's skew sweep: seed IDs Zipf(s) over a seeded permutation of the nodes, window depth 0 / 4 / 16
+        # the skew sweep: seed IDs Zipf(s) over a seeded permutation of the nodes, window depth 0 / 4 / 16
         points = []
         for s_exp in (0.0, 0.8, 1.2):
             rank_table = wl.synth.zipf_rank_table(cfg.n_nodes, s_exp)
