@@ -110,6 +110,16 @@ def main() -> int:
 
     base = wl.CONFIGS[args.workload]
     cfg = wl.scaled(base, args.nodes) if args.nodes else pick_scale(base, wl, args.max_pinned_gib)
+    # pin the store first: a box that grants less pinned memory than assumed runs at half the node count, and so on
+    while True:
+        try:
+            store = gids.gids_store_create(cfg.n_nodes, cfg.row_bytes, np.dtype(cfg.index_dtype).itemsize)
+            break
+        except gids.GidsError as e:
+            if e.code != gids.GIDS_E_NOMEM or cfg.n_nodes < 100_000:
+                raise
+            log(f"cannot pin {cfg.n_nodes * cfg.row_bytes / 1e9:.1f} GB of host memory; halving the node count")
+            cfg = wl.scaled(base, cfg.n_nodes // 2)
     R = cfg.row_bytes
     log(f"workload {cfg.name}: N={cfg.n_nodes} R={R} lines={cfg.cache_lines} ways={cfg.ways} L={cfg.line_bytes} "
         f"cpu_rows={cfg.cpu_rows} fanouts={cfg.fanouts} seeds={cfg.n_seeds}")
@@ -121,7 +131,6 @@ def main() -> int:
     log(f"hot nodes: {len(hot)} ({time.time() - t0:.1f} s)")
     table = wl.normal_table(np.dtype(cfg.feat_dtype))
     t0 = time.time()
-    store = gids.gids_store_create(cfg.n_nodes, R, np.dtype(cfg.index_dtype).itemsize)   # pinned by the library
     wl.fill_store(cfg.seed, cfg.n_nodes, cfg.dim, table, gids.gids_store_host_ptr(store))
     log(f"store: {cfg.n_nodes * R / 1e9:.2f} GB pinned and filled ({time.time() - t0:.1f} s)")
     env = dict(torch=torch, wl=wl, gids=gids, GatherSession=GatherSession, g=g, hot=hot, table=table, store=store,
