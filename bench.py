@@ -62,6 +62,7 @@ def main() -> int:
     ap.add_argument("--max-pinned-gib", type=float, default=60.0,
                     help="pinned host memory the box grants one process (store + CPU buffer must fit)")
     ap.add_argument("--window", type=int, default=-1, help="override the window depth")
+    ap.add_argument("--cache-lines", type=int, default=0, help="override the number of cache lines (rounded to ways)")
     ap.add_argument("--accum", type=int, default=0, help="accumulator threshold (0 = every gather moves its own rows)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="time budget of the oracle leg")
     ap.add_argument("--pass-ids", action="store_true",
@@ -120,6 +121,9 @@ def main() -> int:
                 raise
             log(f"cannot pin {cfg.n_nodes * cfg.row_bytes / 1e9:.1f} GB of host memory; halving the node count")
             cfg = wl.scaled(base, cfg.n_nodes // 2)
+    if args.cache_lines:
+        from dataclasses import replace
+        cfg = replace(cfg, cache_lines=max(cfg.ways, args.cache_lines // cfg.ways * cfg.ways))
     R = cfg.row_bytes
     log(f"workload {cfg.name}: N={cfg.n_nodes} R={R} lines={cfg.cache_lines} ways={cfg.ways} L={cfg.line_bytes} "
         f"cpu_rows={cfg.cpu_rows} fanouts={cfg.fanouts} seeds={cfg.n_seeds}")

@@ -188,7 +188,7 @@ struct CacheT final : gids_cache {
         CacheView<IdT> v;
         v.n_rows = store->n_rows; v.n_sets = n_sets; v.ways = ways; v.lg_ways = lg_ways;
         v.row_bytes = store->row_bytes; v.line_bytes = line_bytes; v.words_per_set = words_per_set;
-        v.use32 = store->n_rows < (1ull << 32) ? 1u : 0u;
+        v.use32 = (store->n_rows < (1ull << 32) && n_sets < (1ull << 32)) ? 1u : 0u;
         v.tags = tags; v.stamps = stamps; v.pending = pending; v.reuse = reuse; v.missmask = missmask;
         v.hotbits = n_hot ? hotbits : nullptr; v.hotrank = hotrank;
         v.cache_data = cache_data; v.store = static_cast<const char*>(store->dev);

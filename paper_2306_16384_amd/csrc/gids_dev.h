@@ -26,12 +26,10 @@ struct Ctl {
     uint32_t n_unique;      // distinct IDs of the list deduplicated last
     uint32_t error;         // first error a kernel found (-GIDS_E_*), 0 = none; sticky
     uint32_t ticket;        // arrival counter for "last block does the scan"
-    uint32_t reserved0;
     uint32_t stamp;         // index of the minibatch being gathered (successful gathers so far)
     uint32_t cnt_hit, cnt_cpu, cnt_miss, cnt_bypass;
     uint32_t pend_fill;     // queued host-link rows (accumulator)
     uint32_t pend_copy;     // queued HBM copies that wait for a queued fill
-    uint32_t do_flush;      // decision of the accumulator for this gather
     uint32_t deferred;      // rows of the current gather left in the queues
     uint32_t win_n[MAX_WINDOW_SLOTS];   // distinct count of each buffered list
 };
@@ -71,7 +69,7 @@ struct CacheView {
     uint32_t ways, lg_ways;
     uint32_t row_bytes, line_bytes;
     uint32_t words_per_set; // 64-bit words of the miss mask per set
-    uint32_t use32;         // n_rows < 2^32: set index with 32-bit arithmetic
+    uint32_t use32;         // n_rows and n_sets < 2^32: set index with 32-bit arithmetic
     IdT* tags;              // lines, -1 = empty
     int32_t* stamps;        // lines, -1 = never used
     uint32_t* pending;      // lines: index of the queued fill that will write the line, or NO_OP
