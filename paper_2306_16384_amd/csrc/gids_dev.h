@@ -41,7 +41,7 @@ struct BatchHdr {
     uint32_t ok;            // 0: the gather failed or an earlier error is pending: move nothing
     uint32_t n_u;           // distinct IDs
     uint32_t stamp;         // minibatch index
-    uint32_t pad;
+    uint32_t next_chunk;    // work counter of the row mover's link half (reset by the commit kernel)
 };
 
 // One queued row move of the accumulator.
@@ -128,7 +128,7 @@ void launch_commit(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n
                    const uint64_t* plan, BatchHdr* hdr, hipStream_t s);
 
 template <typename IdT>
-void launch_move(const CacheView<IdT>& c, const IdT* unique, const BatchHdr* hdr, uint64_t n_upper,
+void launch_move(const CacheView<IdT>& c, const IdT* unique, BatchHdr* hdr, uint64_t n_upper,
                  const uint64_t* plan, char* out, IdT* unique_out, int blocks, int link_blocks_max, hipStream_t s);
 
 template <typename IdT>

@@ -68,7 +68,7 @@ __device__ __forceinline__ uint32_t nth_set_bit(uint64_t mask, uint32_t n) {
 // past the other half's rows costs one load per CH rows.
 template <typename IdT, int G>
 __global__ __launch_bounds__(MV_THREADS) void move_kernel(CacheView<IdT> c, const IdT* __restrict__ unique,
-                                                          const BatchHdr* __restrict__ hdr,
+                                                          BatchHdr* __restrict__ hdr,
                                                           const uint64_t* __restrict__ plan, char* __restrict__ out,
                                                           IdT* __restrict__ unique_out, uint32_t link_blocks,
                                                           uint32_t link_ch, uint32_t hbm_ch) {
@@ -84,7 +84,16 @@ __global__ __launch_bounds__(MV_THREADS) void move_kernel(CacheView<IdT> c, cons
     const uint32_t role_blocks = link_role ? link_blocks : gridDim.x - link_blocks;
     const uint64_t wave0 = ((uint64_t)role_block * MV_THREADS + threadIdx.x) >> 6;
     const uint64_t n_waves = ((uint64_t)role_blocks * MV_THREADS) >> 6;
-    for (uint64_t base = wave0 * ch; base < n_u; base += n_waves * ch) {
+    // HBM half: chunk = wave index, strided.  Link half: the persistent waves draw chunks from a counter, so
+    // that none is left with a long tail of slow rows while the others have run out of work.
+    uint64_t base = wave0 * ch;
+    for (;;) {
+        if (link_role) {
+            uint32_t chunk = 0;
+            if (lane == 0) chunk = atomicAdd(&hdr->next_chunk, 1u);
+            base = (uint64_t)__shfl(chunk, 0) * ch;
+        }
+        if (base >= n_u) break;
         const uint64_t jl = base + lane;
         uint64_t e = 0, v = 0;
         bool mine = false;
@@ -114,6 +123,7 @@ __global__ __launch_bounds__(MV_THREADS) void move_kernel(CacheView<IdT> c, cons
             copy_row<G>(reinterpret_cast<const v4u*>(src), reinterpret_cast<v4u*>(out + (base + pick) * c.row_bytes),
                         reinterpret_cast<v4u*>(line), row_u4, sub);
         }
+        if (!link_role) base += n_waves * ch;
     }
 }
 
@@ -261,7 +271,7 @@ inline uint32_t row_grid(uint64_t rows, int g, int blocks) {
 }  // namespace
 
 template <typename IdT>
-void launch_move(const CacheView<IdT>& c, const IdT* unique, const BatchHdr* hdr, uint64_t n_upper,
+void launch_move(const CacheView<IdT>& c, const IdT* unique, BatchHdr* hdr, uint64_t n_upper,
                  const uint64_t* plan, char* out, IdT* unique_out, int blocks, int link_blocks_max, hipStream_t s) {
     const int g = lanes_per_row(c.row_bytes);
     // a wave of the HBM half takes 16 plan entries per step, one of the link half 64
@@ -273,7 +283,12 @@ void launch_move(const CacheView<IdT>& c, const IdT* unique, const BatchHdr* hdr
     const uint32_t hbm_blocks = row_grid(n_upper, 64 / (int)hbm_ch, blocks);   // 4 waves x hbm_ch rows per workgroup step
     // the link half scans 64 entries per wave step when the list is long enough to keep all its waves busy
     // that way, fewer otherwise (short lists are latency-bound: spread them over more waves)
-    uint32_t link_ch = 64;
+    static const uint32_t link_ch_max = [] {
+        const char* e = getenv("GIDS_LINK_CHUNK");
+        const int v = e ? atoi(e) : 64;
+        return (uint32_t)((v == 4 || v == 8 || v == 16 || v == 32 || v == 64) ? v : 64);
+    }();
+    uint32_t link_ch = link_ch_max;
     while (link_ch > 4 && n_upper / link_ch < (uint64_t)link_blocks_max * (MV_THREADS / 64)) link_ch >>= 1;
     const uint32_t link_blocks = row_grid(n_upper, 64 / (int)link_ch, link_blocks_max);
     GIDS_DISPATCH_G(g, hipLaunchKernelGGL((move_kernel<IdT, G>), dim3(link_blocks + hbm_blocks), dim3(MV_THREADS), 0,
@@ -307,7 +322,7 @@ void launch_finalize(Ctl* ctl, StatsRec* rec, uint64_t seq, const uint32_t* n_u,
 }
 
 #define GIDS_INSTANTIATE(IdT)                                                                                       \
-    template void launch_move<IdT>(const CacheView<IdT>&, const IdT*, const BatchHdr*, uint64_t, const uint64_t*,   \
+    template void launch_move<IdT>(const CacheView<IdT>&, const IdT*, BatchHdr*, uint64_t, const uint64_t*,         \
                                    char*, IdT*, int, int, hipStream_t);                                             \
     template void launch_queue<IdT>(const CacheView<IdT>&, const IdT*, const BatchHdr*, uint64_t, const uint64_t*,  \
                                     char*, IdT*, FillOp*, CopyOp*, int, hipStream_t);                               \
