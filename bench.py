@@ -106,6 +106,8 @@ def main() -> int:
         torch.cuda.synchronize()
         print(json.dumps({"calibrate_copy_bytes": 1 << 30, "copies": 3}))
         return 0
+    from paper_2306_16384_amd.build import ensure_built
+    ensure_built()
     gids.lib()
     wl.native.build()
 

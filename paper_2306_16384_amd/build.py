@@ -36,5 +36,11 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def ensure_built() -> str:
+    """Build only when no library is there yet (tests, smoke and the benchmark call this;
+    after editing a source, call build() yourself)."""
+    return LIB if os.path.exists(LIB) else build()
+
+
 if __name__ == "__main__":
     build(verbose=True)

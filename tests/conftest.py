@@ -10,6 +10,8 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu on the GPU box)")
+    from paper_2306_16384_amd.build import ensure_built
+    ensure_built()          # hipcc cross-compiles without a GPU; a library that is already there is used as is
 
 
 @pytest.fixture(scope="session")
