@@ -292,3 +292,36 @@ def test_device_found_errors(gpu, oracle_mod):
         with pytest.raises(gids.GidsError) as e:
             s.push(s.to_device([1]))
         assert e.value.code == gids.GIDS_E_INVAL
+
+
+# ------------------------------------------------------------- randomised
+
+@pytest.mark.parametrize("case", range(24))
+def test_random_configurations(gpu, oracle_mod, case):
+    """Seeded random geometry, window, accumulator threshold, stream use and
+    list shapes (the draw is printed, so a failure names its case)."""
+    rng = np.random.default_rng(9000 + case)
+    n = int(rng.choice([63, 64, 65, 1000, 4097, 30_011]))
+    ways = int(rng.choice([1, 2, 4, 8, 16, 32]))
+    n_sets = int(rng.integers(1, max(2, n // (ways * int(rng.integers(1, 80))) + 2)))
+    row_bytes = int(rng.choice([16, 48, 256, 1040, 2048]))
+    line_bytes = row_bytes + 16 * int(rng.integers(0, 3))
+    window = int(rng.choice([0, 0, 1, 2, 5, 11]))
+    threshold = int(rng.choice([0, 0, 0, 7, 900]))
+    id_dtype = np.int32 if rng.random() < 0.5 else np.int64
+    n_hot = int(rng.integers(0, max(1, n // 10)))
+    size = int(rng.integers(1, 4 * n))
+    a = float(rng.choice([1.05, 1.3, 2.0]))
+    batches = []
+    for _ in range(int(rng.integers(3, 22))):
+        m = int(rng.integers(0, size + 1))
+        if rng.random() < 0.5:
+            b = np.minimum(rng.zipf(a, size=m) - 1, n - 1)
+        else:
+            b = rng.integers(0, n, size=m)
+        batches.append(b.astype(np.int64))
+    feats = rand_feats(rng, n, row_bytes)
+    run_case(gpu, oracle_mod, feats, batches, id_dtype=id_dtype, lines=ways * n_sets, ways=ways, line_bytes=line_bytes,
+             window=window, threshold=threshold, hot=rng.choice(n, n_hot, replace=False) if n_hot else None,
+             use_head=bool(window and rng.random() < 0.5), with_inverse=bool(rng.random() < 0.5),
+             two_streams=bool(rng.random() < 0.5), label=f"random{case}")
