@@ -83,6 +83,9 @@ def main() -> int:
     ap.add_argument("--gpu-sampler", action="store_true",
                     help="produce every minibatch's ID list with the library's GPU neighbourhood sampler (graph in "
                          "HBM) inside the step, and push it without the host seeing it; also times the sampler alone")
+    ap.add_argument("--sampler-zero-copy", action="store_true",
+                    help="with --gpu-sampler: leave the CSR graph in pinned host memory and sample it zero-copy "
+                         "(the paper's arrangement) instead of copying it to HBM")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     args = ap.parse_args()
@@ -202,13 +205,13 @@ def run_point(args, env, cfg, window, raws, n_pre):
         from paper_2306_16384_amd.session import GraphSampler
         g = env["g"]
         t0 = time.time()
-        sampler = GraphSampler(g.indptr, g.indices)
+        sampler = GraphSampler(g.indptr, g.indices, zero_copy=args.sampler_zero_copy)
         cap_raw = sampler.capacity(cfg.fanouts, cfg.n_seeds)
         ses.reserve(max(max_raw, cap_raw))
         n_slots = window + 3
         raw_bufs = [torch.empty(cap_raw, dtype=ses.torch_id, device="cuda") for _ in range(n_slots)]
         n_bufs = [torch.zeros(1, dtype=torch.int32, device="cuda") for _ in range(n_slots)]
-        log(f"GPU sampler: graph copied to HBM ({(g.indptr.nbytes + g.indices.nbytes) / 1e9:.2f} GB, "
+        log(f"GPU sampler: graph {'pinned for zero-copy' if args.sampler_zero_copy else 'copied to HBM'} ({(g.indptr.nbytes + g.indices.nbytes) / 1e9:.2f} GB, "
             f"{time.time() - t0:.1f} s), raw capacity {cap_raw} IDs per minibatch")
     cap_rows = max(len(np.unique(r)) for r in raws[:n_batches])
     # outputs rotate; with the accumulator on, an output must survive until the flush that completes it
@@ -330,7 +333,8 @@ def run_point(args, env, cfg, window, raws, n_pre):
         last = raw_bufs[0][:int(n_bufs[0].item())].cpu().numpy().astype(np.int64)
         raw_ids = float(np.mean([len(r) for r in raws[n_pre:n_pre + n_s]]))
         result["sampler"] = {"gpu_ms_per_minibatch": gpu_ms, "raw_ids_per_minibatch": raw_ids,
-                             "raw_ids_per_s": raw_ids / (gpu_ms * 1e-3), "graph": "CSR in HBM",
+                             "raw_ids_per_s": raw_ids / (gpu_ms * 1e-3),
+                             "graph": "CSR in pinned host memory, zero-copy" if args.sampler_zero_copy else "CSR in HBM",
                              "list_equals_reference": bool(np.array_equal(last, raws[n_pre + n_s - 1]))}
         if not args.no_cpu:
             import oracle
