@@ -389,7 +389,7 @@ int64_t go_sim_gather(go_sim* s, const int64_t* raw, int64_t n, int64_t* unique_
     const int64_t t = s->t;
 
     /* window: the buffered head must be this minibatch; drop it and take back
-     * its reuse counts ("decreased each time the node is reused") */
+     * its reuse counts (a reuse consumes one count) */
     if (s->window > 0) {
         if (s->win_count == 0) return GO_E_ORDER;
         if (s->win_n[0] != m || memcmp(s->win_ids[0], unique_out, (size_t)m * sizeof(int64_t))) return GO_E_ORDER;

@@ -10,7 +10,7 @@
 //           index; misses set one bit (set, id / n_sets) in a per-set miss
 //           mask.  The probe also takes this
 //           minibatch's own entry out of the per-node future-reuse counters
-//           ("decreased each time the node is reused").
+//           (a reuse consumes one count, Section 3.4).
 //   victim  a miss's rank among the misses of its set is a popcount of the
 //           mask below its own bit (ascending ID order without any sort); the
 //           lanes of its group rank the set's evictable ways by (stamp, way)
