@@ -63,6 +63,8 @@ def main() -> int:
     ap.add_argument("--max-pinned-gib", type=float, default=60.0,
                     help="pinned host memory the box grants one process (store + CPU buffer must fit)")
     ap.add_argument("--window", type=int, default=-1, help="override the window depth")
+    ap.add_argument("--policy", default="lru", choices=["lru", "random"],
+                    help="base replacement policy: LRU by minibatch, or the paper's seeded random eviction")
     ap.add_argument("--cache-lines", type=int, default=0, help="override the number of cache lines (rounded to ways)")
     ap.add_argument("--accum", type=int, default=0, help="accumulator threshold (0 = every gather moves its own rows)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="time budget of the oracle leg")
@@ -198,6 +200,8 @@ def run_point(args, env, cfg, window, raws, n_pre):
                         args.accum, store_handle=env["store"])
     ses.pin_hot(hot)
     ses.reserve(max_raw)
+    if args.policy == "random":
+        ses.set_policy(gids.GIDS_POLICY_RANDOM, cfg.seed)
     log(f"cache W={window}: created, CPU buffer {len(hot) * R / 1e9:.2f} GB pinned ({time.time() - t0:.1f} s)")
     dev = [ses.to_device(r) for r in raws[:n_batches]]
     sampler = None
@@ -308,7 +312,7 @@ def run_point(args, env, cfg, window, raws, n_pre):
         "unique_ids_per_s": n_unique * scale / (total_ms * 1e-3),
         "config": {"workload": cfg.name, "n_nodes": cfg.n_nodes, "row_bytes": R, "cache_lines": cfg.cache_lines,
                    "ways": cfg.ways, "line_bytes": cfg.line_bytes, "cpu_buffer_rows": cfg.cpu_rows, "window": window,
-                   "fanouts": list(cfg.fanouts), "seeds_per_batch": cfg.n_seeds, "accum_threshold": args.accum, "prewarm_lists": n_pre, "gpu_sampler": bool(args.gpu_sampler),
+                   "fanouts": list(cfg.fanouts), "seeds_per_batch": cfg.n_seeds, "accum_threshold": args.accum, "prewarm_lists": n_pre, "gpu_sampler": bool(args.gpu_sampler), "policy": args.policy,
                    "id_dtype": cfg.index_dtype, "scaled_from": base.n_nodes if cfg.n_nodes != base.n_nodes else None},
         "per_step": {"unique": n_unique * scale / steps, "hit": n_hit * scale / steps, "cpu_hit": n_cpu * scale / steps,
                      "miss": n_miss * scale / steps, "bypass": n_byp * scale / steps},
@@ -367,6 +371,8 @@ def run_point(args, env, cfg, window, raws, n_pre):
         store_np = ses.store_view()
         sim = oracle.Sim(cfg.n_nodes, cfg.cache_lines, cfg.ways, window, R, cfg.line_bytes, store_np)
         sim.set_hot(hot)
+        if args.policy == "random":
+            sim.set_policy(1, cfg.seed)
         opushed, done, o_unique, o_time = 0, 0, 0, 0.0
         mismatches = 0
         budget_end = time.time() + args.cpu_seconds

@@ -112,6 +112,17 @@ int gids_cache_create(gids_store* store, uint64_t lines, uint32_t ways, uint32_t
                       uint32_t window_depth, uint64_t accum_threshold, gids_cache** out);
 int gids_cache_destroy(gids_cache* cache);
 
+/* Base replacement policy, i.e. the order in which the evictable ways of a set
+ * are given to misses (window pinning applies to both; call before the first
+ * gather).  GIDS_POLICY_LRU (default): least recently used by minibatch, ties
+ * to the lowest way.  GIDS_POLICY_RANDOM: the policy of the cache the paper
+ * builds on (Section 3.4; its window-depth-0 baseline, Section 4.5), made
+ * reproducible: empty ways first, then occupied ways in the order of the hash
+ * H(seed, 8, minibatch, set, way) (H as in gids_sample). */
+#define GIDS_POLICY_LRU 0
+#define GIDS_POLICY_RANDOM 1
+int gids_cache_set_policy(gids_cache* cache, int policy, uint64_t seed);
+
 /* Pre-size the internal per-minibatch buffers for ID lists of up to
  * max_ids_per_minibatch entries, so that no later call allocates. */
 int gids_cache_reserve(gids_cache* cache, uint64_t max_ids_per_minibatch);

@@ -287,6 +287,8 @@ typedef struct {
     int64_t** win_ids; int64_t* win_n; int32_t win_count;
     /* optional data plane */
     const char* store; char* cache_data; char* cpu_buf;
+    /* base replacement policy: 0 = least recently used by minibatch, 1 = seeded random (BaM's policy, Section 3.4) */
+    int32_t policy; uint64_t policy_seed;
 } go_sim;
 
 void go_sim_free(go_sim* s) {
@@ -336,6 +338,15 @@ int go_sim_set_hot(go_sim* s, const int64_t* ids, int64_t k) {
         for (int64_t i = 0; i < k; i++)
             memcpy(s->cpu_buf + (size_t)i * s->row_bytes, s->store + (size_t)ids[i] * s->row_bytes, (size_t)s->row_bytes);
     }
+    return GO_OK;
+}
+
+/* Choose the base policy that orders the evictable ways of a set (before the first gather).
+ * Random: occupied evictable ways are ordered by the hash H(seed, 8, minibatch, set, way) instead of by
+ * their last-use stamp; empty ways still go first, in way order.  Window pinning applies to both. */
+int go_sim_set_policy(go_sim* s, int32_t policy, uint64_t seed) {
+    if (s->t || (policy != 0 && policy != 1)) return GO_E_INVAL;
+    s->policy = policy; s->policy_seed = seed;
     return GO_OK;
 }
 
@@ -438,7 +449,14 @@ int64_t go_sim_gather(go_sim* s, const int64_t* raw, int64_t n, int64_t* unique_
             int64_t line = set * s->ways + w;
             if (s->stamp[line] == t) continue;
             if (s->tag[line] != -1 && s->reuse[s->tag[line]] != 0) continue;
-            vict[n_vict].stamp = s->stamp[line]; vict[n_vict].way = w; n_vict++;
+            if (s->policy == 1 && s->tag[line] != -1) {
+                /* random order among occupied ways: a 55-bit hash, never negative, sorts after every empty way (-1) */
+                uint64_t k = mix64(mix64(mix64(key0(s->policy_seed, 8) ^ (uint64_t)t) ^ (uint64_t)set) ^ (uint64_t)w);
+                vict[n_vict].stamp = (int64_t)(k >> 9);
+            } else {
+                vict[n_vict].stamp = s->policy == 1 ? -1 : s->stamp[line];
+            }
+            vict[n_vict].way = w; n_vict++;
         }
         qsort(vict, (size_t)n_vict, sizeof(victim_rec), cmp_victim);
         for (int64_t k = a; k < b; k++) {

@@ -14,7 +14,7 @@ GIDS_E_INVAL, GIDS_E_NOMEM, GIDS_E_RANGE, GIDS_E_ORDER, GIDS_E_FULL, GIDS_E_HIP,
 
 EXPORTS = [
     "gids_store_create", "gids_store_host_ptr", "gids_store_destroy", "gids_cache_create", "gids_cache_destroy",
-    "gids_cache_reserve", "gids_cpu_buffer_pin", "gids_window_push", "gids_gather", "gids_flush", "gids_stats_read",
+    "gids_cache_reserve", "gids_cache_set_policy", "gids_cpu_buffer_pin", "gids_window_push", "gids_gather", "gids_flush", "gids_stats_read",
     "gids_cache_gathers", "gids_cache_snapshot", "gids_profile_enable", "gids_profile_read", "gids_window_push_dev",
     "gids_graph_create", "gids_graph_destroy", "gids_sample_capacity", "gids_sample", "gids_accum_threshold", "gids_last_error",
 ]
@@ -55,6 +55,7 @@ def lib() -> C.CDLL:
         L.gids_cache_create.argtypes = [vp, u64, u32, u32, u32, u64, C.POINTER(vp)]
         L.gids_cache_destroy.argtypes = [vp]
         L.gids_cache_reserve.argtypes = [vp, u64]
+        L.gids_cache_set_policy.argtypes = [vp, C.c_int, u64]
         L.gids_cpu_buffer_pin.argtypes = [vp, vp, u64]
         L.gids_window_push.argtypes = [vp, vp, u64, vp]
         L.gids_gather.argtypes = [vp, vp, u64, vp, u64, vp, vp, vp]
@@ -110,6 +111,13 @@ def gids_cache_destroy(cache: int) -> None:
 
 def gids_cache_reserve(cache: int, max_ids: int) -> None:
     _check(lib().gids_cache_reserve(cache, max_ids))
+
+
+GIDS_POLICY_LRU, GIDS_POLICY_RANDOM = 0, 1
+
+
+def gids_cache_set_policy(cache: int, policy: int, seed: int = 0) -> None:
+    _check(lib().gids_cache_set_policy(cache, policy, seed))
 
 
 def gids_cpu_buffer_pin(cache: int, ids_host_ptr: int, n: int) -> None:

@@ -90,6 +90,8 @@ struct gids_cache {
     uint32_t ways = 0, lg_ways = 0, line_bytes = 0, window = 0, words_per_set = 0;
     int sticky = GIDS_OK;
     uint64_t seq = 0;
+    uint32_t policy = 0;            // GIDS_POLICY_*
+    uint64_t policy_key = 0;
     StatsRec* ring_host = nullptr;
     StatsRec* ring_dev = nullptr;
     hipEvent_t events[STATS_RING] = {};       // gather seq: its rows have moved (recorded on the caller's stream)
@@ -189,6 +191,7 @@ struct CacheT final : gids_cache {
         v.n_rows = store->n_rows; v.n_sets = n_sets; v.ways = ways; v.lg_ways = lg_ways;
         v.row_bytes = store->row_bytes; v.line_bytes = line_bytes; v.words_per_set = words_per_set;
         v.use32 = (store->n_rows < (1ull << 32) && n_sets < (1ull << 32)) ? 1u : 0u;
+        v.policy = policy; v.policy_key = policy_key;
         v.tags = tags; v.stamps = stamps; v.pending = pending; v.reuse = reuse; v.missmask = missmask;
         v.hotbits = n_hot ? hotbits : nullptr; v.hotrank = hotrank;
         v.cache_data = cache_data; v.store = static_cast<const char*>(store->dev);
@@ -694,6 +697,15 @@ int gids_gather(gids_cache* cache, const void* ids_dev, uint64_t n, void* out_de
     CHECK_CACHE(cache);
     if (n > 0xFFFFFFF0ull) return fail(GIDS_E_INVAL, "gids_gather: list too long");
     return cache->gather(ids_dev, n, out_dev, out_capacity_rows, unique_dev, inverse_dev, static_cast<hipStream_t>(stream));
+}
+
+int gids_cache_set_policy(gids_cache* cache, int policy, uint64_t seed) {
+    CHECK_CACHE(cache);
+    if (policy != GIDS_POLICY_LRU && policy != GIDS_POLICY_RANDOM) return fail(GIDS_E_INVAL, "gids_cache_set_policy: unknown policy %d", policy);
+    if (cache->seq) return fail(GIDS_E_INVAL, "gids_cache_set_policy: call before the first gather");
+    cache->policy = (uint32_t)policy;
+    cache->policy_key = sampler_mix(seed + 8ull * 0x9E3779B97F4A7C15ull);
+    return GIDS_OK;
 }
 
 int gids_flush(gids_cache* cache, void* stream) {

@@ -32,6 +32,13 @@ constexpr int CT_THREADS = 256;
 
 __device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63; }
 
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+    z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ull;
+    z ^= z >> 27; z *= 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return z;
+}
+
 template <typename IdT>
 __device__ __forceinline__ void set_and_round(const CacheView<IdT>& c, uint64_t v, uint64_t* set, uint64_t* round) {
     if (c.use32) {
@@ -162,15 +169,20 @@ __global__ __launch_bounds__(CT_THREADS) void victim_kernel(CacheView<IdT> c, co
         set_and_round(c, v, &set, &round);
         // this lane's way: evictable?
         const uint64_t line = set * ways + sub;
-        bool ev = false;
+        bool ev = false, empty = false;
         int32_t st = 0;
         if (valid) {
             const IdT tg = c.tags[line];
             st = c.stamps[line];
-            ev = st != stamp && (tg < 0 || c.reuse[(uint64_t)tg] == 0);
+            empty = tg < 0;
+            ev = st != stamp && (empty || c.reuse[(uint64_t)tg] == 0);
         }
-        // order of this way among the set's evictable ways by (stamp, way)
-        const uint64_t key = ev ? (((uint64_t)(uint32_t)(st + 1)) << 8) | sub : ~0ull;
+        // order of this way among the set's evictable ways: by (stamp, way), empty ways (stamp -1) first;
+        // under the random base policy occupied ways are ordered by a hash of (minibatch, set, way) instead
+        uint64_t order = (uint64_t)(uint32_t)(st + 1);
+        if (c.policy == 1)
+            order = empty ? 0ull : 1ull + (mix64(mix64(mix64(c.policy_key ^ (uint64_t)(uint32_t)stamp) ^ set) ^ sub) >> 9);
+        const uint64_t key = ev ? (order << 8) | sub : ~0ull;
         uint32_t way_rank = 0;
         for (uint32_t o = 0; o < ways; o++) {
             const uint64_t other = __shfl(key, (int)(group_base + o));

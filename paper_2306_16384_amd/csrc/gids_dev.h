@@ -70,6 +70,8 @@ struct CacheView {
     uint32_t row_bytes, line_bytes;
     uint32_t words_per_set; // 64-bit words of the miss mask per set
     uint32_t use32;         // n_rows and n_sets < 2^32: set index with 32-bit arithmetic
+    uint32_t policy;        // order of evictable ways: 0 = last-use stamp (LRU by minibatch), 1 = seeded hash (random)
+    uint64_t policy_key;    // mix64(seed + 8 * golden): prefix of the random policy's hash chain
     IdT* tags;              // lines, -1 = empty
     int32_t* stamps;        // lines, -1 = never used
     uint32_t* pending;      // lines: index of the queued fill that will write the line, or NO_OP

@@ -50,6 +50,9 @@ class GatherSession:
         ids = np.ascontiguousarray(np.asarray(ids, dtype=self.id_dtype))
         B.gids_cpu_buffer_pin(self.cache, ids.ctypes.data, len(ids))
 
+    def set_policy(self, policy: int, seed: int = 0) -> None:
+        B.gids_cache_set_policy(self.cache, policy, seed)
+
     def reserve(self, max_ids: int) -> None:
         B.gids_cache_reserve(self.cache, max_ids)
 

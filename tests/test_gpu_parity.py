@@ -22,7 +22,7 @@ def gpu():
 
 
 def run_case(gpu, oracle, feats, batches, *, id_dtype, lines, ways, line_bytes, window, threshold=0, hot=None,
-             use_head=False, with_inverse=False, check_state=True, two_streams=False, label=""):
+             use_head=False, with_inverse=False, check_state=True, two_streams=False, policy=None, label=""):
     """Feeds the same raw ID lists to both implementations, protocol: keep window + 1 lists buffered."""
     torch, gids, GatherSession = gpu
     n_rows = feats.shape[0]
@@ -33,6 +33,8 @@ def run_case(gpu, oracle, feats, batches, *, id_dtype, lines, ways, line_bytes, 
           f"thr={threshold} ids={np.dtype(id_dtype).name} batches={len(batches)}", flush=True)
     if hot is not None and len(hot):
         sim.set_hot(hot)
+    if policy is not None:
+        sim.set_policy(*policy)
     # the oracle's pass, on its own
     want, pushed = [], 0
     for t, raw in enumerate(batches):
@@ -44,6 +46,8 @@ def run_case(gpu, oracle, feats, batches, *, id_dtype, lines, ways, line_bytes, 
         ses.store_view()[:] = feats_u8
         if hot is not None and len(hot):
             ses.pin_hot(hot)
+        if policy is not None:
+            ses.set_policy(*policy)
         dev = [ses.to_device(b) for b in batches]
         torch.cuda.synchronize()
         push_stream = torch.cuda.Stream() if two_streams else None
@@ -294,6 +298,18 @@ def test_device_found_errors(gpu, oracle_mod):
         assert e.value.code == gids.GIDS_E_INVAL
 
 
+@pytest.mark.parametrize("window,ways", [(0, 4), (3, 8), (0, 64), (2, 1)])
+def test_random_base_policy(gpu, oracle_mod, window, ways):
+    """The paper's base policy (random eviction), seeded: same victims as the oracle."""
+    rng = np.random.default_rng(4242 + window + ways)
+    n = 6000
+    feats = rand_feats(rng, n, 128)
+    for seed in (0, 0xDEADBEEF12345):
+        run_case(gpu, oracle_mod, feats, zipf_batches(rng, n, 25, 700, a=1.15), id_dtype=np.int64, lines=ways * 13,
+                 ways=ways, line_bytes=128, window=window, hot=rng.choice(n, 40, replace=False),
+                 policy=(1, seed), label=f"random-policy/W{window}/ways{ways}")
+
+
 # ------------------------------------------------------------- randomised
 
 @pytest.mark.parametrize("case", range(24))
@@ -324,4 +340,5 @@ def test_random_configurations(gpu, oracle_mod, case):
     run_case(gpu, oracle_mod, feats, batches, id_dtype=id_dtype, lines=ways * n_sets, ways=ways, line_bytes=line_bytes,
              window=window, threshold=threshold, hot=rng.choice(n, n_hot, replace=False) if n_hot else None,
              use_head=bool(window and rng.random() < 0.5), with_inverse=bool(rng.random() < 0.5),
-             two_streams=bool(rng.random() < 0.5), label=f"random{case}")
+             two_streams=bool(rng.random() < 0.5), policy=(1, case) if rng.random() < 0.3 else None,
+             label=f"random{case}")

@@ -11,6 +11,8 @@ import pytest
 
 import os
 
+import workload as wl
+
 GOLDEN = {}
 with open(os.path.join(os.path.dirname(__file__), "golden", "paper_values.txt")) as fh:
     for line in fh:
@@ -406,3 +408,73 @@ def test_line_fills_happen_without_output_rows(oracle_mod):
     uniq, rows, stats, cls = sim.gather(first, want_cls=True)
     assert stats[1] == 40 and np.all(cls == oracle_mod.CLS_HIT)
     assert rows.tobytes() == feats[first].tobytes()
+
+
+# ------------------------------------------------------- random base policy
+
+def test_random_policy_picks_uniformly_and_respects_the_window(oracle_mod):
+    """Section 3.4's base policy: the victim is a random line; with window buffering lines whose
+    node a buffered minibatch reuses are still never evicted, and empty ways are used first."""
+    ways = 8
+    counts = np.zeros(ways)
+    trials = 0
+    for seed in range(1500):
+        sim = oracle_mod.Sim(1000, ways, ways, 0)           # one set
+        sim.set_policy(1, seed)
+        sim.gather(np.arange(ways), want_rows=False)         # fills the empty ways in way order
+        assert sim.tags.tolist() == list(range(ways))
+        sim.gather(np.array([500]), want_rows=False)         # one miss: which way goes?
+        gone = [w for w in range(ways) if sim.tags[w] == 500]
+        assert len(gone) == 1
+        counts[gone[0]] += 1
+        trials += 1
+    p = 1.0 / ways
+    assert np.all(np.abs(counts - trials * p) < 5 * np.sqrt(trials * p * (1 - p)))
+    # pinned lines survive: nodes 0..3 are reused by the buffered next minibatch
+    for seed in range(200):
+        sim = oracle_mod.Sim(1000, ways, ways, 1)
+        sim.set_policy(1, seed)
+        b0, b1, b2 = np.arange(ways), np.array([600, 601, 602, 603]), np.array([0, 1, 2, 3])
+        sim.push(b0); sim.push(b1)
+        sim.gather(b0, want_rows=False)
+        sim.push(b2)
+        sim.gather(b1, want_rows=False)                      # four misses, only ways 4..7 are safe to evict
+        assert sim.tags[:4].tolist() == [0, 1, 2, 3]
+        assert sorted(sim.tags[4:].tolist()) == [600, 601, 602, 603]
+
+
+def test_random_policy_against_an_independent_model(oracle_mod):
+    """Depth 0, random policy: a Python model that orders occupied evictable ways by the documented hash."""
+    n, n_sets, ways, seed = 400, 5, 4, 77
+    sim = oracle_mod.Sim(n, n_sets * ways, ways, 0)
+    sim.set_policy(1, seed)
+    tags = [[-1] * ways for _ in range(n_sets)]
+    rng = np.random.default_rng(8)
+    for t, raw in enumerate(zipf_batches(rng, n, 40, 30, a=1.2)):
+        ids = sorted(set(raw.tolist()))
+        touched = [set() for _ in range(n_sets)]
+        missing = {}
+        hits = 0
+        for v in ids:
+            s = v % n_sets
+            if v in tags[s]:
+                hits += 1
+                touched[s].add(tags[s].index(v))
+            else:
+                missing.setdefault(s, []).append(v)
+        byp = 0
+        for s, vs in missing.items():
+            cand = [w for w in range(ways) if w not in touched[s]]
+            def order(w):
+                if tags[s][w] == -1:
+                    return (-1, w)
+                return (int(wl.hash_chain(seed, 8, t, s, w)) >> 9, w)
+            cand.sort(key=order)
+            for k, v in enumerate(vs):
+                if k < len(cand):
+                    tags[s][cand[k]] = v
+                else:
+                    byp += 1
+        _, _, stats, _ = sim.gather(raw, want_cls=True)
+        assert (stats[0], stats[1], stats[4]) == (len(ids), hits, byp)
+        assert sim.tags.tolist() == [x for row in tags for x in row]
