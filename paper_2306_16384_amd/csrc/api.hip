@@ -161,6 +161,28 @@ struct CacheT final : gids_cache {
     uint64_t queue_cap = 0;
     FillOp* fills = nullptr;
     CopyOp* copies = nullptr;
+    // What the host knows about the queues without waiting: the count the last finished gather reported plus
+    // the list lengths of the gathers enqueued since.  While that bound is below the threshold the flush
+    // kernels (which decide on the real count) need not even be launched.
+    uint64_t known_seq = 0;         // gathers [0, known_seq) are accounted in known_pending
+    uint64_t known_pending = 0;
+    uint32_t upper_since[STATS_RING] = {};   // list length bound of gather seq, by seq % STATS_RING
+
+    uint64_t pending_bound() {
+        // fold in every gather that has finished since (its record carries the real count after it)
+        for (uint64_t g = seq; g-- > known_seq && seq - g <= STATS_RING;) {
+            const StatsRec& rec = ring_host[g % STATS_RING];
+            if (*reinterpret_cast<const volatile uint64_t*>(&rec.seq) == g) {
+                known_pending = *reinterpret_cast<const volatile uint64_t*>(&rec.n_pending);
+                known_seq = g + 1;
+                break;
+            }
+        }
+        if (seq - known_seq > STATS_RING) return ~0ull;      // too far behind to bound: assume a flush is due
+        uint64_t bound = known_pending;
+        for (uint64_t g = known_seq; g < seq; g++) bound += upper_since[g % STATS_RING];
+        return bound;
+    }
     // window FIFO (host bookkeeping; lists live on the device)
     std::vector<WindowSlot> slots;
     uint32_t head = 0, count = 0;
@@ -453,7 +475,9 @@ struct CacheT final : gids_cache {
             if ((rc = mark_phase(r, 3, s))) return rc;
             launch_queue<IdT>(c, U, hdr + par, n_upper, plan[par], static_cast<char*>(out), static_cast<IdT*>(unique),
                               fills, copies, move_blocks, s);
-            launch_flush<IdT>(c, fills, copies, threshold, false, move_blocks, s);
+            upper_since[r] = (uint32_t)n_upper;
+            if (pending_bound() + n_upper >= threshold)
+                launch_flush<IdT>(c, fills, copies, threshold, false, (int)std::min<uint64_t>(queue_cap, 1u << 30), s);
             if ((rc = mark_phase(r, 4, s))) return rc;
             launch_finalize(ctl, ring_dev + r, seq, n_u, s);
         }
@@ -472,7 +496,7 @@ struct CacheT final : gids_cache {
         if (!threshold) return GIDS_OK;
         const int rc = follow(s);
         if (rc) return rc;
-        launch_flush<IdT>(view(), fills, copies, threshold, true, move_blocks, s);
+        launch_flush<IdT>(view(), fills, copies, threshold, true, (int)std::min<uint64_t>(queue_cap, 1u << 30), s);
         return GIDS_OK;
     }
 

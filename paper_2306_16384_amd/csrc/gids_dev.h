@@ -140,7 +140,7 @@ void launch_queue(const CacheView<IdT>& c, const IdT* unique, const BatchHdr* hd
 
 template <typename IdT>
 void launch_flush(const CacheView<IdT>& c, FillOp* fills, CopyOp* copies, uint64_t threshold, bool force,
-                  int blocks, hipStream_t s);
+                  int max_rows, hipStream_t s);
 
 uint64_t sampler_key(uint64_t seed, uint64_t tag);
 uint64_t sampler_mix(uint64_t z);

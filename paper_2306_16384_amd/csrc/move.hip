@@ -127,6 +127,9 @@ __global__ __launch_bounds__(MV_THREADS) void move_kernel(CacheView<IdT> c, cons
     }
 }
 
+// The accumulator's variant of the row mover.  A wave reads 64 plan entries at once; rows that must cross
+// the link are appended to the fill queue with one atomic per wave, hits on lines whose fill is still queued
+// become queued copies, and hits on lines that hold their bytes are copied right away, 64 / G at a time.
 template <typename IdT, int G>
 __global__ __launch_bounds__(MV_THREADS) void queue_kernel(CacheView<IdT> c, const IdT* __restrict__ unique,
                                                            const BatchHdr* __restrict__ hdr,
@@ -137,43 +140,64 @@ __global__ __launch_bounds__(MV_THREADS) void queue_kernel(CacheView<IdT> c, con
     if (!hdr->ok) return;
     const uint32_t n_u = hdr->n_u;
     const uint32_t row_u4 = c.row_bytes >> 4;
-    const uint32_t sub = threadIdx.x % G;
-    const uint64_t g0 = ((uint64_t)blockIdx.x * MV_THREADS + threadIdx.x) / G;
-    const uint64_t n_groups = (uint64_t)gridDim.x * MV_THREADS / G;
-    for (uint64_t j = g0; j < n_u; j += n_groups) {
-        const uint64_t e = plan[j];
-        const uint64_t kind = e >> PLAN_SHIFT, idx = e & PLAN_INDEX_MASK;
-        const uint64_t v = (uint64_t)unique[j];
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t sub = lane % G, grp = lane / G;
+    constexpr uint32_t PER_ITER = 64 / G;
+    const uint64_t wave0 = ((uint64_t)blockIdx.x * MV_THREADS + threadIdx.x) >> 6;
+    const uint64_t n_waves = ((uint64_t)gridDim.x * MV_THREADS) >> 6;
+    for (uint64_t base = wave0 * 64; base < n_u; base += n_waves * 64) {
+        const uint64_t j = base + lane;
+        const bool valid = j < n_u;
+        uint64_t e = 0, v = 0, idx = 0, kind = PLAN_HIT;
+        uint32_t p = NO_OP;
+        if (valid) {
+            e = plan[j];
+            v = (uint64_t)unique[j];
+            kind = e >> PLAN_SHIFT;
+            idx = e & PLAN_INDEX_MASK;
+            if (unique_out) unique_out[j] = (IdT)v;
+            if (kind == PLAN_HIT) p = c.pending[idx];          // written only by earlier gathers or flushes
+        }
+        const bool is_fill = valid && kind != PLAN_HIT;
+        const bool is_wait = valid && kind == PLAN_HIT && p != NO_OP;   // the line's bytes are still on their way
+        const bool is_copy = valid && kind == PLAN_HIT && p == NO_OP;
+        const uint64_t fb = __ballot(is_fill), wb = __ballot(is_wait);
+        uint32_t fbase = 0, wbase = 0;
+        if (lane == 0) {
+            if (fb) fbase = atomicAdd(&ctl->pend_fill, (uint32_t)__popcll(fb));
+            if (wb) wbase = atomicAdd(&ctl->pend_copy, (uint32_t)__popcll(wb));
+            if (fb | wb) atomicAdd(&ctl->deferred, (uint32_t)(__popcll(fb) + __popcll(wb)));
+        }
+        fbase = __shfl(fbase, 0);
+        wbase = __shfl(wbase, 0);
+        const uint64_t below = (1ull << lane) - 1;
         char* dst = out + j * c.row_bytes;
-        if (sub == 0 && unique_out) unique_out[j] = (IdT)v;
-        if (kind == PLAN_HIT) {
-            const uint32_t p = c.pending[idx];             // written only by earlier gathers or flushes
-            if (p == NO_OP) {
-                copy_row<G>(reinterpret_cast<const v4u*>(c.cache_data + idx * c.line_bytes),
-                            reinterpret_cast<v4u*>(dst), nullptr, row_u4, sub);
-            } else if (sub == 0) {                         // the line's bytes are still on their way
-                const uint32_t q = atomicAdd(&ctl->pend_copy, 1u);
-                copies[q].src = fills[p].dst_out;
-                copies[q].dst_out = dst;
-                atomicAdd(&ctl->deferred, 1u);
+        if (is_fill) {
+            const uint32_t q = fbase + (uint32_t)__popcll(fb & below);
+            fills[q].dst_out = dst;
+            fills[q].dst_line = NO_LINE;
+            fills[q].src = kind == PLAN_CPU ? c.cpubuf + idx * c.row_bytes : c.store + v * c.row_bytes;
+            if (kind == PLAN_INSTALL) {
+                const uint32_t old = c.pending[idx];
+                if (old != NO_OP) fills[old].dst_line = NO_LINE;   // superseded before it ever ran: output only
+                fills[q].dst_line = idx;
+                c.pending[idx] = q;
             }
-            continue;
         }
-        if (sub != 0) continue;
-        const uint32_t q = atomicAdd(&ctl->pend_fill, 1u);
-        atomicAdd(&ctl->deferred, 1u);
-        fills[q].dst_out = dst;
-        fills[q].dst_line = NO_LINE;
-        if (kind == PLAN_CPU) {
-            fills[q].src = c.cpubuf + idx * c.row_bytes;
-            continue;
+        if (is_wait) {
+            const uint32_t q = wbase + (uint32_t)__popcll(wb & below);
+            copies[q].src = fills[p].dst_out;
+            copies[q].dst_out = dst;
         }
-        fills[q].src = c.store + v * c.row_bytes;
-        if (kind == PLAN_INSTALL) {
-            const uint32_t old = c.pending[idx];
-            if (old != NO_OP) fills[old].dst_line = NO_LINE;   // superseded before it ever ran: output only
-            fills[q].dst_line = idx;
-            c.pending[idx] = q;
+        uint64_t todo = __ballot(is_copy);
+        while (todo) {
+            const uint32_t pick = nth_set_bit(todo, grp);
+#pragma unroll
+            for (uint32_t i = 0; i < PER_ITER; i++) todo &= todo - 1;
+            const uint64_t idx_p = __shfl(idx, (int)(pick & 63));
+            if (pick == 64u) continue;
+            copy_row<G>(reinterpret_cast<const v4u*>(c.cache_data + idx_p * c.line_bytes),
+                        reinterpret_cast<v4u*>(out + (base + pick) * c.row_bytes), nullptr, row_u4, sub);
         }
     }
 }
@@ -300,16 +324,19 @@ void launch_queue(const CacheView<IdT>& c, const IdT* unique, const BatchHdr* hd
                   const uint64_t* plan, char* out, IdT* unique_out, FillOp* fills, CopyOp* copies, int blocks,
                   hipStream_t s) {
     const int g = lanes_per_row(c.row_bytes);
-    const uint32_t grid = row_grid(n_upper, g, blocks);
+    const uint32_t grid = row_grid(n_upper, 1, blocks < 2048 ? blocks : 2048);   // 4 waves x 64 entries per workgroup step
     GIDS_DISPATCH_G(g, hipLaunchKernelGGL((queue_kernel<IdT, G>), dim3(grid), dim3(MV_THREADS), 0, s, c, unique,
                                           hdr, plan, out, unique_out, fills, copies));
 }
 
 template <typename IdT>
 void launch_flush(const CacheView<IdT>& c, FillOp* fills, CopyOp* copies, uint64_t threshold, bool force,
-                  int blocks, hipStream_t s) {
+                  int max_rows, hipStream_t s) {
     const int g = lanes_per_row(c.row_bytes);
     const int f = force ? 1 : 0;
+    // the queues hold rows that cross the link (fills) or wait for them (copies): a few hundred persistent
+    // workgroups, never more than there can be rows
+    const int blocks = (int)row_grid((uint64_t)(max_rows > 0 ? max_rows : 1), g, 384);
     GIDS_DISPATCH_G(g, hipLaunchKernelGGL((flush_fill_kernel<IdT, G>), dim3(blocks), dim3(MV_THREADS), 0, s, c,
                                           fills, threshold, f));
     GIDS_DISPATCH_G(g, hipLaunchKernelGGL((flush_copy_kernel<IdT, G>), dim3(blocks), dim3(MV_THREADS), 0, s, c,
