@@ -16,6 +16,7 @@ def drive(ses, torch, raws, window, cap_rows, row_bytes, keep):
     dev = [ses.to_device(r) for r in raws]
     ses.reserve(max(len(r) for r in raws))
     outs, uniqs, seqs, pushed = {}, {}, [], 0
+    stats = {}                                                # the library keeps the counters of the last 64 gathers
     scratch = [torch.empty((cap_rows, row_bytes), dtype=torch.uint8, device="cuda") for _ in range(2)]
     uq_scratch = torch.empty(cap_rows, dtype=ses.torch_id, device="cuda")
     for t in range(len(raws)):
@@ -28,27 +29,31 @@ def drive(ses, torch, raws, window, cap_rows, row_bytes, keep):
             seqs.append(ses.gather(None if window else dev[t], outs[t], uniqs[t]))
         else:
             seqs.append(ses.gather(None if window else dev[t], scratch[t & 1], uq_scratch))
+        if t >= 40:
+            stats[t - 40] = ses.stats(seqs[t - 40])
     torch.cuda.synchronize()
-    return outs, uniqs, seqs
+    for t in range(max(0, len(raws) - 40), len(raws)):
+        stats[t] = ses.stats(seqs[t])
+    return outs, uniqs, stats
 
 
 def test_medium_full_size(oracle_mod):
     import torch
     from paper_2306_16384_amd.session import GatherSession
     cfg = CONFIGS["medium"]
-    n_b = 48
+    n_b = cfg.n_batches                                       # all 200 minibatches of the configuration
     print(f"[fullsize medium] N={cfg.n_nodes} batches={n_b}", flush=True)
     g = wl.make_graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max, native=True)
     table = wl.normal_table(np.float16)
     hot = wl.hot_nodes(g, cfg.cpu_rows)
     raws = [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds) for b in range(n_b)]
     cap = max(len(np.unique(r)) for r in raws)
-    keep = {0, 1, 9, 10, 23, n_b - 1}
+    keep = {0, 1, 9, 10, 23, 97, 150, n_b - 1}
     with GatherSession(cfg.n_nodes, cfg.row_bytes, np.int64, cfg.cache_lines, cfg.ways, cfg.line_bytes,
                        cfg.window) as ses:
         wl.fill_store(cfg.seed, cfg.n_nodes, cfg.dim, table, ses.store_address())
         ses.pin_hot(hot)
-        outs, uniqs, seqs = drive(ses, torch, raws, cfg.window, cap, cfg.row_bytes, keep)
+        outs, uniqs, stats_of = drive(ses, torch, raws, cfg.window, cap, cfg.row_bytes, keep)
         sim = oracle_mod.Sim(cfg.n_nodes, cfg.cache_lines, cfg.ways, cfg.window, cfg.row_bytes, cfg.line_bytes,
                              ses.store_view())
         sim.set_hot(hot)
@@ -58,7 +63,7 @@ def test_medium_full_size(oracle_mod):
                 sim.push(raws[pushed])
                 pushed += 1
             u, rows, stats = sim.gather(raw, want_rows=t in keep)
-            st = ses.stats(seqs[t])
+            st = stats_of[t]
             assert st.as_tuple() == tuple(int(x) for x in stats), (t, st.as_tuple(), stats.tolist())
             if t in keep:
                 assert np.array_equal(uniqs[t][:len(u)].cpu().numpy(), u)
@@ -85,19 +90,19 @@ def test_large_at_benchmark_size(oracle_mod):
         break
     else:
         pytest.fail("cannot pin even 14 GB of host memory")
-    n_b = 20
+    n_b = 60
     print(f"[fullsize large] N={cfg.n_nodes} lines={cfg.cache_lines} cpu_rows={cfg.cpu_rows} batches={n_b}", flush=True)
     g = wl.make_graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max, native=True)
     table = wl.normal_table(np.float16)
     hot = wl.hot_nodes(g, cfg.cpu_rows)
     raws = [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds) for b in range(n_b)]
     cap = max(len(np.unique(r)) for r in raws)
-    keep = {0, 9, n_b - 1}
+    keep = {0, 9, 33, n_b - 1}
     with GatherSession(cfg.n_nodes, cfg.row_bytes, np.int64, cfg.cache_lines, cfg.ways, cfg.line_bytes,
                        cfg.window) as ses:
         wl.fill_store(cfg.seed, cfg.n_nodes, cfg.dim, table, ses.store_address())
         ses.pin_hot(hot)
-        outs, uniqs, seqs = drive(ses, torch, raws, cfg.window, cap, cfg.row_bytes, keep)
+        outs, uniqs, stats_of = drive(ses, torch, raws, cfg.window, cap, cfg.row_bytes, keep)
         sim = oracle_mod.Sim(cfg.n_nodes, cfg.cache_lines, cfg.ways, cfg.window)      # counts only
         sim.set_hot(hot)
         rng = np.random.default_rng(0)
@@ -107,7 +112,7 @@ def test_large_at_benchmark_size(oracle_mod):
                 sim.push(raws[pushed])
                 pushed += 1
             u, _, stats, cls = sim.gather(raw, want_rows=False, want_cls=True)
-            st = ses.stats(seqs[t])
+            st = stats_of[t]
             assert st.as_tuple() == tuple(int(x) for x in stats), (t, st.as_tuple(), stats.tolist())
             if t in keep:
                 assert np.array_equal(uniqs[t][:len(u)].cpu().numpy(), u)
