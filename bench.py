@@ -65,6 +65,10 @@ def main() -> int:
     ap.add_argument("--window", type=int, default=-1, help="override the window depth")
     ap.add_argument("--policy", default="lru", choices=["lru", "random"],
                     help="base replacement policy: LRU by minibatch, or the paper's seeded random eviction")
+    ap.add_argument("--hot-by", default="indegree", choices=["indegree", "visits"],
+                    help="what fills the CPU buffer: the nodes of highest in-degree (the configurations' rule) or of "
+                         "highest expected visits under the sampler (gids_graph_visit_scores, the stand-in for the "
+                         "paper's reverse-PageRank ranking)")
     ap.add_argument("--cache-lines", type=int, default=0, help="override the number of cache lines (rounded to ways)")
     ap.add_argument("--accum", type=int, default=0, help="accumulator threshold (0 = every gather moves its own rows)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="time budget of the oracle leg")
@@ -139,8 +143,17 @@ def main() -> int:
     g = wl.make_graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max, np.dtype(cfg.index_dtype), native=True)
     log(f"graph: {g.n_edges} edges, mean degree {g.n_edges / g.n:.2f} ({time.time() - t0:.1f} s)")
     t0 = time.time()
-    hot = wl.hot_nodes(g, cfg.cpu_rows)
-    log(f"hot nodes: {len(hot)} ({time.time() - t0:.1f} s)")
+    if args.hot_by == "visits" and cfg.cpu_rows:
+        from paper_2306_16384_amd.session import GraphSampler
+        with GraphSampler(g.indptr, g.indices) as gs_rank:
+            t1 = time.time()
+            scores = gs_rank.visit_scores(cfg.fanouts, cfg.n_seeds).cpu().numpy().view(np.uint64)
+            log(f"visit scores on the GPU: {time.time() - t1:.2f} s")
+        hot = wl.top_k_by_score(scores, cfg.cpu_rows)
+        del scores
+    else:
+        hot = wl.hot_nodes(g, cfg.cpu_rows)
+    log(f"hot nodes by {args.hot_by}: {len(hot)} ({time.time() - t0:.1f} s)")
     table = wl.normal_table(np.dtype(cfg.feat_dtype))
     t0 = time.time()
     wl.fill_store(cfg.seed, cfg.n_nodes, cfg.dim, table, gids.gids_store_host_ptr(store))
@@ -312,7 +325,7 @@ def run_point(args, env, cfg, window, raws, n_pre):
         "unique_ids_per_s": n_unique * scale / (total_ms * 1e-3),
         "config": {"workload": cfg.name, "n_nodes": cfg.n_nodes, "row_bytes": R, "cache_lines": cfg.cache_lines,
                    "ways": cfg.ways, "line_bytes": cfg.line_bytes, "cpu_buffer_rows": cfg.cpu_rows, "window": window,
-                   "fanouts": list(cfg.fanouts), "seeds_per_batch": cfg.n_seeds, "accum_threshold": args.accum, "prewarm_lists": n_pre, "gpu_sampler": bool(args.gpu_sampler), "policy": args.policy,
+                   "fanouts": list(cfg.fanouts), "seeds_per_batch": cfg.n_seeds, "accum_threshold": args.accum, "prewarm_lists": n_pre, "gpu_sampler": bool(args.gpu_sampler), "policy": args.policy, "hot_by": args.hot_by,
                    "id_dtype": cfg.index_dtype, "scaled_from": base.n_nodes if cfg.n_nodes != base.n_nodes else None},
         "per_step": {"unique": n_unique * scale / steps, "hit": n_hit * scale / steps, "cpu_hit": n_cpu * scale / steps,
                      "miss": n_miss * scale / steps, "bypass": n_byp * scale / steps},

@@ -230,6 +230,20 @@ int gids_sample(gids_graph* graph, uint64_t seed, uint64_t batch, const uint32_t
                 uint64_t n_seeds, const uint64_t* rank_table_dev, uint64_t perm_mult, uint64_t perm_add, void* raw_dev,
                 uint64_t raw_capacity, uint32_t* n_raw_dev, void* stream);
 
+/* Hot-node ranking for gids_cpu_buffer_pin (Section 3.3 ranks nodes by a
+ * weighted reverse PageRank that estimates how often sampling reaches them;
+ * the paper gives no formula, this is the exact expectation for gids_sample's
+ * law with uniform seeds, ignoring only that a hop's frontier is deduplicated
+ * beyond clamping each node's expected presence at 1).
+ * scores_dev receives n_nodes uint64 in 32.32 fixed point: the expected number
+ * of times each node appears in a minibatch's raw list,
+ *   lam_0(v) = n_seeds / n;  lam_(l+1)(u) = sum over adjacency slots v -> u of
+ *   min(1, lam_l(v)) * min(deg v, f_l) / deg v;  score = lam_0 + ... + lam_L,
+ * every product and quotient in integers (floor), so the result is exact and
+ * reproducible.  Blocks until done (a set-up step, not part of the hot path). */
+int gids_graph_visit_scores(gids_graph* graph, const uint32_t* fanouts_host, uint32_t n_layers, uint64_t n_seeds,
+                            uint64_t* scores_dev, void* stream);
+
 /* Number of in-flight fills an accumulator needs so that a storage device of
  * `iops_peak` requests/s per device sustains `ratio` of its peak, given the
  * latency of the initial and termination phases in seconds (Section 3.2,

@@ -250,6 +250,43 @@ int64_t go_sample_skewed(const go_graph* g, uint64_t seed, int64_t batch, const 
     return sample_impl(g, seed, batch, fanouts, n_layers, n_seeds, rank_table, perm_mult, perm_add, out, cap);
 }
 
+/* ------------------------------------------------------- hot-node scores */
+
+/* Expected number of times each node appears in a minibatch's raw list under go_sample's law, in 32.32 fixed
+ * point (a stand-in for the weighted reverse PageRank the paper ranks hot nodes with, Section 3.3: both
+ * estimate how often neighbourhood sampling reaches a node; the paper gives no formula).
+ *   lam_0(v) = n_seeds / n                       (uniform seeds)
+ *   a node expected c = min(1, lam_l(v)) times in the frontier of hop l takes each of its deg(v) adjacency
+ *   slots with probability min(deg, f_l) / deg, so every slot sends w = c * min(deg, f_l) / deg to its
+ *   neighbour: lam_(l+1)(u) = sum of w over the slots that point to u
+ *   score(u) = lam_0(u) + ... + lam_L(u)
+ * Integer arithmetic throughout (floor divisions), so any implementation agrees bit for bit. */
+int go_visit_scores(const go_graph* g, const int32_t* fanouts, int n_layers, int64_t n_seeds, uint64_t* scores) {
+    const uint64_t ONE = 1ull << 32;
+    if (n_seeds < 0 || n_seeds > (1ll << 30)) return GO_E_INVAL;
+    uint64_t* cur = (uint64_t*)malloc((size_t)g->n * sizeof(uint64_t));
+    uint64_t* nxt = (uint64_t*)malloc((size_t)g->n * sizeof(uint64_t));
+    if (!cur || !nxt) { free(cur); free(nxt); return GO_E_NOMEM; }
+    const uint64_t lam0 = ((uint64_t)n_seeds << 32) / (uint64_t)g->n;
+    for (int64_t v = 0; v < g->n; v++) { cur[v] = lam0; scores[v] = lam0; }
+    for (int l = 0; l < n_layers; l++) {
+        const uint64_t f = (uint64_t)fanouts[l];
+        memset(nxt, 0, (size_t)g->n * sizeof(uint64_t));
+        for (int64_t v = 0; v < g->n; v++) {
+            const uint64_t deg = (uint64_t)(g->indptr[v + 1] - g->indptr[v]);
+            if (!deg || !cur[v]) continue;
+            const uint64_t c = cur[v] < ONE ? cur[v] : ONE;
+            const uint64_t take = deg < f ? deg : f;
+            const uint64_t w = c * take / deg;
+            for (int64_t e = g->indptr[v]; e < g->indptr[v + 1]; e++) nxt[g->indices[e]] += w;
+        }
+        for (int64_t v = 0; v < g->n; v++) scores[v] += nxt[v];
+        uint64_t* tmp = cur; cur = nxt; nxt = tmp;
+    }
+    free(cur); free(nxt);
+    return GO_OK;
+}
+
 /* --------------------------------------------------------------- features */
 
 /* feat(v, c) for c = 0..dim-1 into out: four table indices per hashed word */

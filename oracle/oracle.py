@@ -57,6 +57,8 @@ def lib() -> C.CDLL:
         L.go_sample_skewed.argtypes = [C.c_void_p, C.c_uint64, C.c_int64, np.ctypeslib.ndpointer(dtype=np.int32),
                                        C.c_int, C.c_int64, np.ctypeslib.ndpointer(dtype=np.uint64), C.c_int64,
                                        C.c_int64, _i64p, C.c_int64]
+        L.go_visit_scores.argtypes = [C.c_void_p, np.ctypeslib.ndpointer(dtype=np.int32), C.c_int, C.c_int64,
+                                      np.ctypeslib.ndpointer(dtype=np.uint64)]
         L.go_feat_row.argtypes = [C.c_uint64, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         L.go_accum_threshold.restype = C.c_double
         L.go_accum_threshold.argtypes = [C.c_double, C.c_double, C.c_double, C.c_double, C.c_int]
@@ -114,6 +116,14 @@ class Graph:
     def hot_nodes(self, k: int) -> np.ndarray:
         out = np.empty(k, dtype=np.int64)
         rc = lib().go_hot_nodes(self._h, k, out)
+        if rc:
+            raise OracleError(rc)
+        return out
+
+    def visit_scores(self, fanouts, n_seeds: int) -> np.ndarray:
+        """Expected appearances per node in a minibatch's raw list, 32.32 fixed point (uint64)."""
+        out = np.zeros(self.n, dtype=np.uint64)
+        rc = lib().go_visit_scores(self._h, np.asarray(fanouts, dtype=np.int32), len(fanouts), n_seeds, out)
         if rc:
             raise OracleError(rc)
         return out

@@ -864,6 +864,30 @@ int gids_sample(gids_graph* graph, uint64_t seed, uint64_t batch, const uint32_t
                                   static_cast<int64_t*>(raw_dev), n_raw_dev, s);
 }
 
+int gids_graph_visit_scores(gids_graph* graph, const uint32_t* fanouts, uint32_t n_layers, uint64_t n_seeds,
+                            uint64_t* scores_dev, void* stream) {
+    if (!graph || !scores_dev) return fail(GIDS_E_INVAL, "gids_graph_visit_scores: NULL argument");
+    if (n_layers > 8 || (n_layers && !fanouts)) return fail(GIDS_E_INVAL, "gids_graph_visit_scores: at most 8 layers");
+    for (uint32_t l = 0; l < n_layers; l++)
+        if (fanouts[l] < 1 || fanouts[l] > 64) return fail(GIDS_E_INVAL, "gids_graph_visit_scores: fanouts must be in [1, 64]");
+    if (n_seeds > (1ull << 30)) return fail(GIDS_E_INVAL, "gids_graph_visit_scores: n_seeds too large");
+    uint64_t *cur = nullptr, *nxt = nullptr;
+    int rc;
+    if ((rc = dev_alloc(&cur, graph->n_nodes))) return rc;
+    if ((rc = dev_alloc(&nxt, graph->n_nodes))) { dev_free(cur); return rc; }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (graph->id_bytes == 4)
+        launch_visit_scores<int32_t>(graph->indptr, static_cast<const int32_t*>(graph->indices), graph->n_nodes, fanouts,
+                                     n_layers, n_seeds, cur, nxt, scores_dev, s);
+    else
+        launch_visit_scores<int64_t>(graph->indptr, static_cast<const int64_t*>(graph->indices), graph->n_nodes, fanouts,
+                                     n_layers, n_seeds, cur, nxt, scores_dev, s);
+    hipError_t e = hipStreamSynchronize(s);                  // the scratch arrays go away with the call
+    dev_free(cur); dev_free(nxt);
+    if (e != hipSuccess) return fail(GIDS_E_HIP, "gids_graph_visit_scores: %s", hipGetErrorString(e));
+    return GIDS_OK;
+}
+
 double gids_accum_threshold(double iops_peak, double t_initial, double t_termination, double ratio, int n_ssd) {
     // N = IOPS_achieved * (Ti + Ts + Tt) * n_ssd with Ts = N / (IOPS_peak * n_ssd), at IOPS_achieved = ratio * IOPS_peak
     if (!(ratio > 0.0) || !(ratio < 1.0) || n_ssd < 1) return -1.0;

@@ -155,6 +155,12 @@ void launch_hop(const IdT* frontier, const uint32_t* n_front, uint64_t front_upp
                 const IdT* indices, uint32_t fanout, uint64_t kl, uint32_t* blocksum, uint32_t* blockoff, IdT* raw,
                 IdT* hop_out, SamplerState* st, hipStream_t s);
 
+// expected visits per node under the sampler's law; cur / nxt are n-entry scratch arrays
+template <typename IdT>
+void launch_visit_scores(const int64_t* indptr, const IdT* indices, uint64_t n, const uint32_t* fanouts,
+                         uint32_t n_layers, uint64_t n_seeds, uint64_t* cur, uint64_t* nxt, uint64_t* score,
+                         hipStream_t s);
+
 void launch_finalize(Ctl* ctl, StatsRec* rec, uint64_t seq, const uint32_t* n_u, hipStream_t s);
 
 void launch_fill_u32(uint32_t* p, uint64_t n, uint32_t value, hipStream_t s);

@@ -20,6 +20,8 @@
 // turns workgroup sums into offsets (so every node knows where its neighbours
 // go), `sample` draws and writes, then the hop's output is deduplicated into
 // the next frontier with the bitmap kernels of dedup.hip.
+#include <algorithm>
+
 #include "gids_dev.h"
 #include "scan.h"
 
@@ -158,7 +160,67 @@ __global__ __launch_bounds__(SM_THREADS) void sample_kernel(const IdT* __restric
     }
 }
 
+// ---- expected visits per node (hot-node ranking) ---------------------------
+// lam_0 = n_seeds / n for every node; a node expected c = min(1, lam_l) times in hop l's frontier sends
+// w = c * min(deg, f_l) / deg along each adjacency slot; score = sum of lam over the hops.  32.32 fixed
+// point, floor divisions, 64-bit integer atomics: the sums do not depend on the order of the additions.
+
+__global__ void visits_init_kernel(uint64_t* __restrict__ cur, uint64_t* __restrict__ score, uint64_t n, uint64_t lam0) {
+    for (uint64_t v = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n; v += (uint64_t)gridDim.x * blockDim.x) {
+        cur[v] = lam0;
+        score[v] = lam0;
+    }
+}
+
+// one wavefront per node: lanes stride over the node's adjacency slots
+template <typename IdT>
+__global__ __launch_bounds__(SM_THREADS) void visits_hop_kernel(const int64_t* __restrict__ indptr,
+                                                                const IdT* __restrict__ indices, uint64_t n,
+                                                                uint64_t fanout, const uint64_t* __restrict__ cur,
+                                                                unsigned long long* __restrict__ nxt) {
+    const uint64_t ONE = 1ull << 32;
+    const uint64_t wave0 = ((uint64_t)blockIdx.x * SM_THREADS + threadIdx.x) >> 6;
+    const uint64_t n_waves = ((uint64_t)gridDim.x * SM_THREADS) >> 6;
+    for (uint64_t v = wave0; v < n; v += n_waves) {
+        const uint64_t lam = cur[v];
+        const int64_t start = indptr[v];
+        const uint64_t deg = (uint64_t)(indptr[v + 1] - start);
+        if (!lam || !deg) continue;
+        const uint64_t c = lam < ONE ? lam : ONE;
+        const uint64_t take = deg < fanout ? deg : fanout;
+        const uint64_t w = c * take / deg;
+        if (!w) continue;
+        for (uint64_t s = lane_id(); s < deg; s += 64) atomicAdd(&nxt[(uint64_t)indices[start + s]], (unsigned long long)w);
+    }
+}
+
+__global__ void visits_add_kernel(uint64_t* __restrict__ score, const uint64_t* __restrict__ nxt, uint64_t n) {
+    for (uint64_t v = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n; v += (uint64_t)gridDim.x * blockDim.x)
+        score[v] += nxt[v];
+}
+
+__global__ void visits_zero_kernel(uint64_t* __restrict__ p, uint64_t n) {
+    for (uint64_t v = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n; v += (uint64_t)gridDim.x * blockDim.x)
+        p[v] = 0;
+}
+
 }  // namespace
+
+template <typename IdT>
+void launch_visit_scores(const int64_t* indptr, const IdT* indices, uint64_t n, const uint32_t* fanouts,
+                         uint32_t n_layers, uint64_t n_seeds, uint64_t* cur, uint64_t* nxt, uint64_t* score,
+                         hipStream_t s) {
+    const uint32_t flat = (uint32_t)std::min<uint64_t>((n + 255) / 256, 4096);
+    const uint32_t per_node = (uint32_t)std::min<uint64_t>((n + 3) / 4, 1u << 16);
+    hipLaunchKernelGGL(visits_init_kernel, dim3(flat), dim3(256), 0, s, cur, score, n, (n_seeds << 32) / n);
+    for (uint32_t l = 0; l < n_layers; l++) {
+        hipLaunchKernelGGL(visits_zero_kernel, dim3(flat), dim3(256), 0, s, nxt, n);
+        hipLaunchKernelGGL(visits_hop_kernel<IdT>, dim3(per_node), dim3(SM_THREADS), 0, s, indptr, indices, n,
+                           (uint64_t)fanouts[l], cur, reinterpret_cast<unsigned long long*>(nxt));
+        hipLaunchKernelGGL(visits_add_kernel, dim3(flat), dim3(256), 0, s, score, nxt, n);
+        std::swap(cur, nxt);
+    }
+}
 
 uint64_t sampler_key(uint64_t seed, uint64_t tag) { return mix64(seed + tag * GOLDEN); }
 uint64_t sampler_mix(uint64_t z) { return mix64(z); }
@@ -185,6 +247,8 @@ void launch_hop(const IdT* frontier, const uint32_t* n_front, uint64_t front_upp
 #define GIDS_INSTANTIATE(IdT)                                                                                     \
     template void launch_seeds<IdT>(uint64_t, uint64_t, uint64_t, const uint64_t*, uint64_t, uint64_t, IdT*,      \
                                     SamplerState*, hipStream_t);                                                  \
+    template void launch_visit_scores<IdT>(const int64_t*, const IdT*, uint64_t, const uint32_t*, uint32_t,      \
+                                           uint64_t, uint64_t*, uint64_t*, uint64_t*, hipStream_t);              \
     template void launch_hop<IdT>(const IdT*, const uint32_t*, uint64_t, const int64_t*, const IdT*, uint32_t,    \
                                   uint64_t, uint32_t*, uint32_t*, IdT*, IdT*, SamplerState*, hipStream_t);
 GIDS_INSTANTIATE(int32_t)

@@ -153,6 +153,13 @@ class GraphSampler:
         B.gids_sample(self.graph, seed, batch, fanouts, n_seeds, raw.data_ptr(), raw.numel(), n_raw.data_ptr(), stream,
                       None if rank_table is None else rank_table.data_ptr(), perm[0], perm[1])
 
+    def visit_scores(self, fanouts, n_seeds: int) -> torch.Tensor:
+        """Expected appearances per node and minibatch, 32.32 fixed point (int64 tensor on the device)."""
+        scores = torch.empty(self.n_nodes, dtype=torch.int64, device="cuda")
+        B.gids_graph_visit_scores(self.graph, fanouts, n_seeds, scores.data_ptr(),
+                                  torch.cuda.current_stream().cuda_stream)
+        return scores
+
     def close(self) -> None:
         if self.graph:
             torch.cuda.synchronize()

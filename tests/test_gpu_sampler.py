@@ -137,3 +137,16 @@ def test_sample_push_gather_without_the_host(env, oracle_mod):
             assert st.as_tuple() == tuple(int(x) for x in stats), (t, st.as_tuple(), stats.tolist())
             assert np.array_equal(uqs[t][:len(u)].cpu().numpy(), u.astype(np.int32))
             assert np.array_equal(outs[t][:len(u)].cpu().numpy(), rows)
+
+
+@pytest.mark.parametrize("name,n,dtype", [("tiny", None, np.int32), ("medium", 200_000, np.int64), ("large", 250_000, np.int64)])
+def test_visit_scores_equal_the_oracle(env, oracle_mod, name, n, dtype):
+    torch, _, GraphSampler = env
+    cfg = CONFIGS[name]
+    n = n or cfg.n_nodes
+    g = oracle_mod.Graph(cfg.seed, n, cfg.ell, cfg.p4, min(n - 1, 65535))
+    with GraphSampler(g.indptr, g.indices.astype(dtype)) as gs:
+        for fanouts, n_seeds in ((cfg.fanouts, cfg.n_seeds), ((64,), 3), ((), 10), ((1, 1, 1, 1), 100_000)):
+            want = g.visit_scores(fanouts, n_seeds)
+            got = gs.visit_scores(fanouts, n_seeds).cpu().numpy().view(np.uint64)
+            np.testing.assert_array_equal(got, want, err_msg=f"{name} {fanouts}")

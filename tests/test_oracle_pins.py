@@ -12,6 +12,7 @@ import pytest
 import os
 
 import workload as wl
+from workload import CONFIGS
 
 GOLDEN = {}
 with open(os.path.join(os.path.dirname(__file__), "golden", "paper_values.txt")) as fh:
@@ -478,3 +479,35 @@ def test_random_policy_against_an_independent_model(oracle_mod):
         _, _, stats, _ = sim.gather(raw, want_cls=True)
         assert (stats[0], stats[1], stats[4]) == (len(ids), hits, byp)
         assert sim.tags.tolist() == [x for row in tags for x in row]
+
+
+# -------------------------------------------------------- hot-node scores
+
+def test_visit_scores_closed_form_and_against_sampling(oracle_mod):
+    """Expected appearances per node: exact on a hand graph, and equal to the
+    sampler's empirical hop-1 frequencies within sampling error."""
+    one = float(1 << 32)
+    # star: node 0 -> 1..6 (degree 6), every other node has no neighbours; 2 seeds, fanout 3
+    indptr = np.array([0, 6, 6, 6, 6, 6, 6, 6])
+    indices = np.arange(1, 7)
+    g = oracle_mod.Graph(0, 7, csr=(indptr, indices))
+    sc = g.visit_scores([3], 2) / one
+    lam0 = 2 / 7
+    assert abs(sc[0] - lam0) < 1e-6                                  # nobody points to node 0
+    assert np.allclose(sc[1:], lam0 + lam0 * 3 / 6, atol=1e-6)       # seed mass + lam0 * min(6, 3) / 6 per slot
+    # two hops on a chain 0 -> 1 -> 2: mass moves one node per hop, clamped presence <= 1
+    g2 = oracle_mod.Graph(0, 3, csr=(np.array([0, 1, 2, 2]), np.array([1, 2])))
+    sc2 = g2.visit_scores([5, 5], 6) / one                           # lam0 = 2 > 1: presence clamps to 1
+    assert np.allclose(sc2, [2.0, 2.0 + 1.0, 2.0 + 1.0 + 1.0], atol=1e-6)
+    # against the sampler itself (one hop, few seeds: no clamping, no dedup effects)
+    cfg = CONFIGS["tiny"]
+    gt = oracle_mod.Graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max)
+    sc = gt.visit_scores([10], 32) / one
+    cnt = np.zeros(cfg.n_nodes)
+    n_b = 1500
+    for b in range(n_b):
+        cnt += np.bincount(gt.sample(5, b, [10], 32), minlength=cfg.n_nodes)
+    top = np.argsort(-sc)[:40]
+    sigma = np.sqrt(sc[top] / n_b)
+    assert np.all(np.abs(cnt[top] / n_b - sc[top]) < 5 * sigma + 0.02 * sc[top])
+    assert abs(cnt.sum() / n_b - sc.sum()) / sc.sum() < 0.03

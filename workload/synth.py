@@ -150,6 +150,21 @@ def hot_nodes(g: Graph, k: int) -> np.ndarray:
     return cand[order[:k]]
 
 
+def top_k_by_score(score: np.ndarray, k: int) -> np.ndarray:
+    """IDs of the k largest scores (ties: lower ID first)."""
+    n = len(score)
+    if k <= 0:
+        return np.empty(0, dtype=np.int64)
+    if k < n // 4:
+        kth = np.partition(score, n - k)[n - k]
+        cand = np.flatnonzero(score >= kth).astype(np.int64)
+    else:
+        cand = np.arange(n, dtype=np.int64)
+    sc = score[cand]
+    order = np.lexsort((cand, sc.max() - sc))
+    return cand[order[:k]]
+
+
 def zipf_rank_table(n: int, s: float) -> np.ndarray:
     """Cumulative thresholds (uint64, scaled to 2**63) of Zipf(s) over ranks 1..n."""
     w = np.arange(1, n + 1, dtype=np.float64) ** (-s)
