@@ -137,6 +137,9 @@ def main() -> int:
         from dataclasses import replace
         cfg = replace(cfg, cache_lines=max(cfg.ways, args.cache_lines // cfg.ways * cfg.ways))
     R = cfg.row_bytes
+    rate, overhead = gids.gids_store_calibrate(store)
+    log(f"link calibration: {rate * R / 1e9:.1f} GB/s ({rate / 1e6:.1f} M rows/s), overhead {overhead * 1e6:.1f} us; "
+        f"Eq. 2-3: {gids.gids_accum_threshold(rate, overhead, 0.0, 0.95):.0f} link rows in flight for 95 % of it")
     log(f"workload {cfg.name}: N={cfg.n_nodes} R={R} lines={cfg.cache_lines} ways={cfg.ways} L={cfg.line_bytes} "
         f"cpu_rows={cfg.cpu_rows} fanouts={cfg.fanouts} seeds={cfg.n_seeds}")
     t0 = time.time()
@@ -158,7 +161,7 @@ def main() -> int:
     t0 = time.time()
     wl.fill_store(cfg.seed, cfg.n_nodes, cfg.dim, table, gids.gids_store_host_ptr(store))
     log(f"store: {cfg.n_nodes * R / 1e9:.2f} GB pinned and filled ({time.time() - t0:.1f} s)")
-    env = dict(torch=torch, wl=wl, gids=gids, GatherSession=GatherSession, g=g, hot=hot, table=table, store=store,
+    env = dict(link_rows_per_s=rate, link_overhead_s=overhead, torch=torch, wl=wl, gids=gids, GatherSession=GatherSession, g=g, hot=hot, table=table, store=store,
                base=base)
 
     if args.sweep_skew:
@@ -334,6 +337,10 @@ def run_point(args, env, cfg, window, raws, n_pre):
                               "frac_overlap_bound": t_overlap_ms / total_ms,
                               "roofline_gathered_GBs": gathered_bytes / (t_roof_ms * 1e-3) / 1e9},
         "roofline": roof,
+        "link_calibration": {"GBs": env["link_rows_per_s"] * R / 1e9, "overhead_us": env["link_overhead_s"] * 1e6,
+                             "rows_for_95pct_eq2_3": gids.gids_accum_threshold(env["link_rows_per_s"],
+                                                                                env["link_overhead_s"], 0.0, 0.95),
+                             "link_rows_per_step": (n_cpu + n_miss) * scale / steps},
     }
 
     if sampler is not None:

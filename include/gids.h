@@ -92,6 +92,16 @@ int gids_store_create(uint64_t n_rows, uint32_t row_bytes, uint32_t id_bytes, vo
 void* gids_store_host_ptr(gids_store* store);
 int gids_store_destroy(gids_store* store);
 
+/* Measure the store as the row mover sees it, for Eq. 2-3 of Section 3.2: the
+ * library times two copies of hashed rows (2,048 and 65,536 of them) from the
+ * host table to a scratch buffer and fits time = overhead + rows / rate.
+ * *rows_per_s plays the role of IOPS_peak, *overhead_s that of the initial plus
+ * termination latency: gids_accum_threshold(rows_per_s, overhead_s, 0, r, 1) is
+ * then the number of rows a minibatch (or an accumulated group of minibatches)
+ * must send over the link to keep it at the fraction r of its peak.  Blocks;
+ * the table need not be filled. */
+int gids_store_calibrate(gids_store* store, double* rows_per_s, double* overhead_s);
+
 /* The GPU software cache over a store (Section 3.4) plus its window buffer
  * and fill accumulator (Section 3.2).
  *   lines          cache lines, a multiple of `ways`; one node row per line

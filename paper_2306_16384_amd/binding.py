@@ -13,7 +13,7 @@ GIDS_OK = 0
 GIDS_E_INVAL, GIDS_E_NOMEM, GIDS_E_RANGE, GIDS_E_ORDER, GIDS_E_FULL, GIDS_E_HIP, GIDS_E_SPACE = -1, -2, -3, -4, -5, -6, -7
 
 EXPORTS = [
-    "gids_store_create", "gids_store_host_ptr", "gids_store_destroy", "gids_cache_create", "gids_cache_destroy",
+    "gids_store_create", "gids_store_host_ptr", "gids_store_destroy", "gids_store_calibrate", "gids_cache_create", "gids_cache_destroy",
     "gids_cache_reserve", "gids_cache_set_policy", "gids_cpu_buffer_pin", "gids_window_push", "gids_gather", "gids_flush", "gids_stats_read",
     "gids_cache_gathers", "gids_cache_snapshot", "gids_profile_enable", "gids_profile_read", "gids_window_push_dev",
     "gids_graph_create", "gids_graph_destroy", "gids_sample_capacity", "gids_sample", "gids_graph_visit_scores", "gids_accum_threshold", "gids_last_error",
@@ -52,6 +52,7 @@ def lib() -> C.CDLL:
         L.gids_store_host_ptr.restype = vp
         L.gids_store_host_ptr.argtypes = [vp]
         L.gids_store_destroy.argtypes = [vp]
+        L.gids_store_calibrate.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
         L.gids_cache_create.argtypes = [vp, u64, u32, u32, u32, u64, C.POINTER(vp)]
         L.gids_cache_destroy.argtypes = [vp]
         L.gids_cache_reserve.argtypes = [vp, u64]
@@ -93,6 +94,13 @@ def gids_store_create(n_rows: int, row_bytes: int, id_bytes: int, host_ptr: int 
 
 def gids_store_host_ptr(store: int) -> int:
     return lib().gids_store_host_ptr(store)
+
+
+def gids_store_calibrate(store: int):
+    """-> (rows per second over the link, fixed overhead in seconds)"""
+    rate, over = C.c_double(), C.c_double()
+    _check(lib().gids_store_calibrate(store, C.byref(rate), C.byref(over)))
+    return rate.value, over.value
 
 
 def gids_store_destroy(store: int) -> None:

@@ -660,6 +660,44 @@ int gids_store_destroy(gids_store* store) {
     return GIDS_OK;
 }
 
+int gids_store_calibrate(gids_store* store, double* rows_per_s, double* overhead_s) {
+    if (!store || !rows_per_s || !overhead_s) return fail(GIDS_E_INVAL, "gids_store_calibrate: NULL argument");
+    const uint32_t n_small = 2048, n_large = 65536;
+    char* out = nullptr;
+    int rc = dev_alloc(&out, (uint64_t)n_large * store->row_bytes);
+    if (rc) return rc;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    auto cleanup = [&]() {
+        if (e0) (void)hipEventDestroy(e0);
+        if (e1) (void)hipEventDestroy(e1);
+        dev_free(out);
+    };
+    auto timed = [&](uint32_t n, int reps, double* best) -> int {
+        *best = 1e30;
+        for (int i = 0; i < reps + 1; i++) {                  // the first run warms up
+            HIP_TRY(hipEventRecord(e0, nullptr));
+            launch_calibrate(static_cast<const char*>(store->dev), store->n_rows, store->row_bytes, out, n, nullptr);
+            HIP_TRY(hipEventRecord(e1, nullptr));
+            HIP_TRY(hipEventSynchronize(e1));
+            float ms = 0;
+            HIP_TRY(hipEventElapsedTime(&ms, e0, e1));
+            if (i && ms * 1e-3 < *best) *best = ms * 1e-3;
+        }
+        return GIDS_OK;
+    };
+    double t_small = 0, t_large = 0;
+    hipError_t e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    if (e != hipSuccess) { cleanup(); return fail(GIDS_E_HIP, "gids_store_calibrate: %s", hipGetErrorString(e)); }
+    if ((rc = timed(n_small, 5, &t_small)) || (rc = timed(n_large, 3, &t_large))) { cleanup(); return rc; }
+    cleanup();
+    // t(n) = overhead + n / rate
+    const double rate = (double)(n_large - n_small) / (t_large - t_small);
+    *rows_per_s = rate;
+    *overhead_s = t_small - n_small / rate;
+    return GIDS_OK;
+}
+
 int gids_cache_create(gids_store* store, uint64_t lines, uint32_t ways, uint32_t line_bytes, uint32_t window_depth,
                       uint64_t accum_threshold, gids_cache** out) {
     if (!out) return fail(GIDS_E_INVAL, "gids_cache_create: out is NULL");

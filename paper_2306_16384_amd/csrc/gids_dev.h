@@ -161,6 +161,9 @@ void launch_visit_scores(const int64_t* indptr, const IdT* indices, uint64_t n, 
                          uint32_t n_layers, uint64_t n_seeds, uint64_t* cur, uint64_t* nxt, uint64_t* score,
                          hipStream_t s);
 
+void launch_calibrate(const char* store, uint64_t store_rows, uint32_t row_bytes, char* out, uint32_t n,
+                      hipStream_t s);
+
 void launch_finalize(Ctl* ctl, StatsRec* rec, uint64_t seq, const uint32_t* n_u, hipStream_t s);
 
 void launch_fill_u32(uint32_t* p, uint64_t n, uint32_t value, hipStream_t s);

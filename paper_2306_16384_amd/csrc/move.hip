@@ -252,6 +252,24 @@ __global__ void flush_done_kernel(Ctl* ctl, uint64_t threshold, int force) {
     }
 }
 
+// Link calibration: `n` rows of the host table, picked by a hash of their index, copied to a scratch
+// buffer with the link half's shape (persistent workgroups, one wavefront per row).
+template <int G>
+__global__ __launch_bounds__(MV_THREADS) void calibrate_kernel(const char* __restrict__ store, uint64_t store_rows,
+                                                               uint32_t row_bytes, char* __restrict__ out, uint32_t n) {
+    const uint32_t row_u4 = row_bytes >> 4;
+    const uint32_t sub = threadIdx.x % G;
+    const uint64_t g0 = ((uint64_t)blockIdx.x * MV_THREADS + threadIdx.x) / G;
+    const uint64_t n_groups = (uint64_t)gridDim.x * MV_THREADS / G;
+    for (uint64_t j = g0; j < n; j += n_groups) {
+        uint64_t z = (j + 1) * 0x9E3779B97F4A7C15ull;
+        z ^= z >> 29;
+        const uint64_t row = z % store_rows;
+        copy_row<G>(reinterpret_cast<const v4u*>(store + row * row_bytes),
+                    reinterpret_cast<v4u*>(out + j * (uint64_t)row_bytes), nullptr, row_u4, sub);
+    }
+}
+
 __global__ void finalize_kernel(Ctl* ctl, StatsRec* rec, uint64_t seq, const uint32_t* n_u) {
     const uint32_t err = ctl->error;
     rec->n_unique = err ? 0 : *n_u;
@@ -342,6 +360,14 @@ void launch_flush(const CacheView<IdT>& c, FillOp* fills, CopyOp* copies, uint64
     GIDS_DISPATCH_G(g, hipLaunchKernelGGL((flush_copy_kernel<IdT, G>), dim3(blocks), dim3(MV_THREADS), 0, s, c,
                                           copies, threshold, f));
     hipLaunchKernelGGL(flush_done_kernel, dim3(1), dim3(1), 0, s, c.ctl, threshold, f);
+}
+
+void launch_calibrate(const char* store, uint64_t store_rows, uint32_t row_bytes, char* out, uint32_t n,
+                      hipStream_t s) {
+    const int g = lanes_per_row(row_bytes);
+    const uint32_t grid = row_grid(n, g, 96);
+    GIDS_DISPATCH_G(g, hipLaunchKernelGGL((calibrate_kernel<G>), dim3(grid), dim3(MV_THREADS), 0, s, store, store_rows,
+                                          row_bytes, out, n));
 }
 
 void launch_finalize(Ctl* ctl, StatsRec* rec, uint64_t seq, const uint32_t* n_u, hipStream_t s) {

@@ -342,3 +342,18 @@ def test_random_configurations(gpu, oracle_mod, case):
              use_head=bool(window and rng.random() < 0.5), with_inverse=bool(rng.random() < 0.5),
              two_streams=bool(rng.random() < 0.5), policy=(1, case) if rng.random() < 0.3 else None,
              label=f"random{case}")
+
+
+def test_link_calibration_is_sane(gpu):
+    """Eq. 2-3's inputs measured on the box: a rate of the order of the PCIe link and a small fixed overhead."""
+    torch, gids, GatherSession = gpu
+    store = gids.gids_store_create(2_000_000, 2048, 8)         # 4 GB: larger than any on-chip cache
+    try:
+        rate, overhead = gids.gids_store_calibrate(store)
+        gbs = rate * 2048 / 1e9
+        assert 5.0 < gbs < 70.0, gbs                            # a PCIe Gen3 x16 ... Gen5 x16 link
+        assert -50e-6 < overhead < 500e-6, overhead
+        n95 = gids.gids_accum_threshold(rate, max(overhead, 1e-6), 0.0, 0.95)
+        assert 10 < n95 < 1e6
+    finally:
+        gids.gids_store_destroy(store)
