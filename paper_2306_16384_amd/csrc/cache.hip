@@ -22,6 +22,8 @@
 //   commit  writes the tag and stamp of every line a miss was given and clears
 //           the miss mask; only then is the cache's metadata that of the next
 //           minibatch's start.  The bytes follow in the row mover.
+#include <cstdlib>
+
 #include "gids_dev.h"
 
 namespace gids {
@@ -248,6 +250,15 @@ __global__ __launch_bounds__(CT_THREADS) void commit_kernel(CacheView<IdT> c, co
     }
 }
 
+inline uint32_t probe_cap() {
+    static const uint32_t cap = [] {
+        const char* e = getenv("GIDS_PROBE_BLOCKS");
+        const int v = e ? atoi(e) : 2048;
+        return (uint32_t)(v >= 1 && v <= 65536 ? v : 2048);
+    }();
+    return cap;
+}
+
 inline uint32_t grid_for(uint64_t groups, uint32_t ways, uint32_t cap) {
     const uint64_t per_block = (uint64_t)(CT_THREADS / 64) * (64 / ways);
     uint64_t b = (groups + per_block - 1) / per_block;
@@ -260,7 +271,7 @@ inline uint32_t grid_for(uint64_t groups, uint32_t ways, uint32_t cap) {
 template <typename IdT>
 void launch_probe(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_u, uint64_t n_upper,
                   uint64_t out_capacity, bool pop_window, uint64_t* plan, hipStream_t s) {
-    hipLaunchKernelGGL(probe_kernel<IdT>, dim3(grid_for(n_upper, c.ways, 2048)), dim3(CT_THREADS), 0, s, c, unique,
+    hipLaunchKernelGGL(probe_kernel<IdT>, dim3(grid_for(n_upper, c.ways, probe_cap())), dim3(CT_THREADS), 0, s, c, unique,
                        n_u, out_capacity, pop_window ? 1 : 0, plan);
 }
 
@@ -276,7 +287,7 @@ void launch_commit(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n
 template <typename IdT>
 void launch_victim(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_u, uint64_t n_upper,
                    uint64_t* plan, hipStream_t s) {
-    hipLaunchKernelGGL(victim_kernel<IdT>, dim3(grid_for(n_upper, c.ways, 2048)), dim3(CT_THREADS), 0, s, c, unique,
+    hipLaunchKernelGGL(victim_kernel<IdT>, dim3(grid_for(n_upper, c.ways, probe_cap())), dim3(CT_THREADS), 0, s, c, unique,
                        n_u, plan);
 }
 

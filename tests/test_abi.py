@@ -45,3 +45,16 @@ def test_host_only_entry_points():
     with pytest.raises(gids.GidsError) as e:
         gids.gids_cache_create(None, 16, 4, 64)
     assert e.value.code == gids.GIDS_E_INVAL
+
+
+def test_header_is_plain_c_and_links(tmp_path):
+    """include/gids.h compiles as C99 and a C program links against the library."""
+    import subprocess
+    exe = tmp_path / "abi_check"
+    lib_dir = os.path.dirname(gids.LIB_PATH)
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                           os.path.join(ROOT, "tests", "abi_check.c"), "-o", str(exe), "-L", lib_dir, "-lgids",
+                           "-Wl,-rpath," + lib_dir, "-Wl,-rpath,/opt/rocm/lib"])
+    out = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert out.returncode == 0, out.stdout + out.stderr
+    assert out.stdout.startswith("abi ok 64")              # gids_stats is 7 x u64 + 2 x i32
