@@ -287,6 +287,36 @@ int go_visit_scores(const go_graph* g, const int32_t* fanouts, int n_layers, int
     return GO_OK;
 }
 
+/* Weighted reverse PageRank (the metric Section 3.3 names for choosing hot nodes).  Sampling walks from a
+ * node to the nodes in its adjacency list, which is against the direction of the dataset's edges, hence
+ * "reverse"; "weighted" because a node of degree deg passes 1/deg of its rank along each adjacency slot.
+ * Textbook power iteration with damping d = damping_q16 / 65536 and uniform teleport, total mass 2^44:
+ *   base = floor(2^44 / n);  r_0(v) = base;  teleport = floor(base * (65536 - damping_q16) / 65536)
+ *   r_(k+1)(u) = teleport + sum over adjacency slots v -> u of floor(floor(r_k(v) * damping_q16 / 65536) / deg v)
+ * scores = r_(n_iters).  A node without adjacency slots passes nothing on (its damped mass is dropped).
+ * Integer arithmetic throughout, so any implementation agrees bit for bit. */
+int go_reverse_pagerank(const go_graph* g, uint32_t damping_q16, int n_iters, uint64_t* scores) {
+    if (damping_q16 > 65536u || n_iters < 0) return GO_E_INVAL;
+    uint64_t* nxt = (uint64_t*)malloc((size_t)g->n * sizeof(uint64_t));
+    if (!nxt) return GO_E_NOMEM;
+    const uint64_t base = (1ull << 44) / (uint64_t)g->n;
+    const uint64_t teleport = base * (65536u - damping_q16) >> 16;
+    uint64_t* cur = scores;
+    for (int64_t v = 0; v < g->n; v++) cur[v] = base;
+    for (int k = 0; k < n_iters; k++) {
+        for (int64_t v = 0; v < g->n; v++) nxt[v] = teleport;
+        for (int64_t v = 0; v < g->n; v++) {
+            const uint64_t deg = (uint64_t)(g->indptr[v + 1] - g->indptr[v]);
+            if (!deg) continue;
+            const uint64_t w = (cur[v] * damping_q16 >> 16) / deg;
+            for (int64_t e = g->indptr[v]; e < g->indptr[v + 1]; e++) nxt[g->indices[e]] += w;
+        }
+        memcpy(cur, nxt, (size_t)g->n * sizeof(uint64_t));
+    }
+    free(nxt);
+    return GO_OK;
+}
+
 /* --------------------------------------------------------------- features */
 
 /* feat(v, c) for c = 0..dim-1 into out: four table indices per hashed word */

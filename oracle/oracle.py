@@ -59,6 +59,7 @@ def lib() -> C.CDLL:
                                        C.c_int64, _i64p, C.c_int64]
         L.go_visit_scores.argtypes = [C.c_void_p, np.ctypeslib.ndpointer(dtype=np.int32), C.c_int, C.c_int64,
                                       np.ctypeslib.ndpointer(dtype=np.uint64)]
+        L.go_reverse_pagerank.argtypes = [C.c_void_p, C.c_uint32, C.c_int, np.ctypeslib.ndpointer(dtype=np.uint64)]
         L.go_feat_row.argtypes = [C.c_uint64, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         L.go_accum_threshold.restype = C.c_double
         L.go_accum_threshold.argtypes = [C.c_double, C.c_double, C.c_double, C.c_double, C.c_int]
@@ -124,6 +125,14 @@ class Graph:
         """Expected appearances per node in a minibatch's raw list, 32.32 fixed point (uint64)."""
         out = np.zeros(self.n, dtype=np.uint64)
         rc = lib().go_visit_scores(self._h, np.asarray(fanouts, dtype=np.int32), len(fanouts), n_seeds, out)
+        if rc:
+            raise OracleError(rc)
+        return out
+
+    def reverse_pagerank(self, damping_q16: int, n_iters: int) -> np.ndarray:
+        """Weighted reverse PageRank after n_iters power iterations, total mass 2^44 (uint64)."""
+        out = np.zeros(self.n, dtype=np.uint64)
+        rc = lib().go_reverse_pagerank(self._h, damping_q16, n_iters, out)
         if rc:
             raise OracleError(rc)
         return out

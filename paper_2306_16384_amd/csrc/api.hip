@@ -344,8 +344,8 @@ struct CacheT final : gids_cache {
         for (uint64_t i = 1; i < n; i++)
             if (sorted[i] == sorted[i - 1]) return fail(GIDS_E_INVAL, "gids_cpu_buffer_pin: ID %llu listed twice", (unsigned long long)sorted[i]);
         const uint64_t rb = store->row_bytes;
-        HIP_TRY(hipHostMalloc(&cpubuf_host, n * rb, hipHostMallocMapped));
-        HIP_TRY(hipHostGetDevicePointer(&cpubuf_dev, cpubuf_host, 0));
+        const int rc_alloc = pin_alloc(n * rb);
+        if (rc_alloc) { pin_release(); return rc_alloc; }
         // rows in ascending ID order: slot = rank of the ID among the pinned ones
         {
             const unsigned hw = std::max(1u, std::min(16u, std::thread::hardware_concurrency()));
@@ -364,13 +364,30 @@ struct CacheT final : gids_cache {
         for (uint64_t v : sorted) bits[v >> 6] |= 1ull << (v & 63);
         uint32_t run = 0;
         for (uint64_t w = 0; w < n_words; w++) { rank[w] = run; run += (uint32_t)__builtin_popcountll(bits[w]); }
+        const int rc = pin_upload(bits, rank);
+        if (rc) { pin_release(); return rc; }
+        n_hot = n;
+        return GIDS_OK;
+    }
+
+    int pin_alloc(uint64_t bytes) {
+        HIP_TRY(hipHostMalloc(&cpubuf_host, bytes, hipHostMallocMapped));
+        HIP_TRY(hipHostGetDevicePointer(&cpubuf_dev, cpubuf_host, 0));
+        return GIDS_OK;
+    }
+    int pin_upload(const std::vector<uint64_t>& bits, const std::vector<uint32_t>& rank) {
         int rc;
         if ((rc = dev_alloc(&hotbits, n_words))) return rc;
         if ((rc = dev_alloc(&hotrank, n_words))) return rc;
         HIP_TRY(hipMemcpy(hotbits, bits.data(), n_words * sizeof(uint64_t), hipMemcpyHostToDevice));
         HIP_TRY(hipMemcpy(hotrank, rank.data(), n_words * sizeof(uint32_t), hipMemcpyHostToDevice));
-        n_hot = n;
         return GIDS_OK;
+    }
+    // a pin that failed half-way leaves the cache as it was, without a CPU buffer
+    void pin_release() {
+        if (cpubuf_host) (void)hipHostFree(cpubuf_host);
+        cpubuf_host = cpubuf_dev = nullptr;
+        dev_free(hotbits); dev_free(hotrank);
     }
 
     // ascending distinct IDs of ids[0..n) -> dst; count -> *n_out (device)
@@ -401,6 +418,7 @@ struct CacheT final : gids_cache {
         }
         dedup(static_cast<const IdT*>(ids), n, static_cast<IdT*>(sl.ids), &ctl->win_n[slot], reuse, false, m, n_dev);
         if (pipelined && (rc = edge(meta, s))) return rc;     // the caller may reuse its ID buffer in stream order
+        HIP_TRY(hipGetLastError());                           // a kernel launch that was refused
         sl.last_reader = -1;
         count++;
         return GIDS_OK;
@@ -482,6 +500,7 @@ struct CacheT final : gids_cache {
             launch_finalize(ctl, ring_dev + r, seq, n_u, s);
         }
         prof_valid[r] = profile;
+        HIP_TRY(hipGetLastError());                           // a kernel launch that was refused
         HIP_TRY(hipEventRecord(events[r], s));
         if (window) {
             slots[head].last_reader = (int64_t)seq;
@@ -497,6 +516,7 @@ struct CacheT final : gids_cache {
         const int rc = follow(s);
         if (rc) return rc;
         launch_flush<IdT>(view(), fills, copies, threshold, true, (int)std::min<uint64_t>(queue_cap, 1u << 30), s);
+        HIP_TRY(hipGetLastError());
         return GIDS_OK;
     }
 
@@ -607,6 +627,7 @@ struct gids_graph {
             in_count = &st->layer_count;
             front = std::min<uint64_t>(in_upper, n_nodes);
         }
+        HIP_TRY(hipGetLastError());
         HIP_TRY(hipMemcpyAsync(n_raw_dev, &st->n_raw, sizeof(uint32_t), hipMemcpyDeviceToDevice, s));
         return GIDS_OK;
     }

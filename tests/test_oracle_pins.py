@@ -511,3 +511,54 @@ def test_visit_scores_closed_form_and_against_sampling(oracle_mod):
     sigma = np.sqrt(sc[top] / n_b)
     assert np.all(np.abs(cnt[top] / n_b - sc[top]) < 5 * sigma + 0.02 * sc[top])
     assert abs(cnt.sum() / n_b - sc.sum()) / sc.sum() < 0.03
+
+
+def test_reverse_pagerank_against_closed_forms_and_a_linear_solve(oracle_mod):
+    """Weighted reverse PageRank (Section 3.3): uniform on a ring, the geometric series on a chain (which also
+    fixes the direction of the flow), the two-unknown closed form on a star, and the stationary solution of the
+    linear system from numpy on a random multigraph."""
+    total = float(1 << 44)
+    d16, d = 55705, 55705 / 65536
+    # ring v -> v+1: every node keeps 1/n
+    n = 12
+    ring = oracle_mod.Graph(0, n, csr=(np.arange(n + 1), (np.arange(n) + 1) % n))
+    r = ring.reverse_pagerank(d16, 50) / total
+    assert np.allclose(r, 1 / n, rtol=1e-9, atol=1e-11)
+    # chain 0 -> 1 -> ... -> 7, node 7 keeps nothing: r(k) = t * (1 - d^(k+1)) / (1 - d), t = (1 - d) / n
+    n = 8
+    chain = oracle_mod.Graph(0, n, csr=(np.array(list(range(n)) + [n - 1]), np.arange(1, n)))
+    r = chain.reverse_pagerank(d16, 40) / total
+    want = (1 - d) / n * (1 - d ** np.arange(1, n + 1)) / (1 - d)
+    assert np.allclose(r, want, rtol=1e-8, atol=1e-11)
+    assert r[0] < r[1] < r[7]                                        # rank flows along the adjacency slots
+    # star: hub 0 -> leaves 1..6, every leaf -> hub.  h = t + d*6*l, l = t + d*h/6
+    n = 7
+    indptr = np.array([0, 6, 7, 8, 9, 10, 11, 12])
+    indices = np.array([1, 2, 3, 4, 5, 6, 0, 0, 0, 0, 0, 0])
+    star = oracle_mod.Graph(0, n, csr=(indptr, indices))
+    r = star.reverse_pagerank(d16, 400) / total
+    t = (1 - d) / n
+    h = t * (1 + 6 * d) / (1 - d * d)
+    assert abs(r[0] - h) < 1e-9 and np.allclose(r[1:], t + d * h / 6, atol=1e-9)
+    # random multigraph with repeated slots and self-loops: r = t * (I - d P^T)^-1 1, P[v, u] = slots(v -> u) / deg v
+    rng = np.random.default_rng(3)
+    n = 60
+    deg = rng.integers(1, 9, n)
+    indptr = np.concatenate([[0], np.cumsum(deg)])
+    indices = rng.integers(0, n, indptr[-1])
+    g = oracle_mod.Graph(0, n, csr=(indptr, indices))
+    P = np.zeros((n, n))
+    for v in range(n):
+        for u in indices[indptr[v]:indptr[v + 1]]:
+            P[v, u] += 1 / deg[v]
+    want = np.linalg.solve(np.eye(n) - d * P.T, np.full(n, (1 - d) / n))
+    r = g.reverse_pagerank(d16, 300) / total
+    assert np.allclose(r, want, rtol=1e-7, atol=1e-10)
+    assert abs(r.sum() - 1) < 1e-7                                   # no node without slots: mass is kept
+    # a few iterations: equal to the same recurrence in float64
+    x = np.full(n, 1 / n)
+    for _ in range(3):
+        x = (1 - d) / n + d * (P.T @ x)
+    assert np.allclose(g.reverse_pagerank(d16, 3) / total, x, rtol=1e-7)
+    # no damping mass: the uniform start stays
+    assert len(set(g.reverse_pagerank(0, 5).tolist())) == 1
