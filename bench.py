@@ -65,10 +65,10 @@ def main() -> int:
     ap.add_argument("--window", type=int, default=-1, help="override the window depth")
     ap.add_argument("--policy", default="lru", choices=["lru", "random"],
                     help="base replacement policy: LRU by minibatch, or the paper's seeded random eviction")
-    ap.add_argument("--hot-by", default="indegree", choices=["indegree", "visits"],
-                    help="what fills the CPU buffer: the nodes of highest in-degree (the configurations' rule) or of "
-                         "highest expected visits under the sampler (gids_graph_visit_scores, the stand-in for the "
-                         "paper's reverse-PageRank ranking)")
+    ap.add_argument("--hot-by", default="indegree", choices=["indegree", "visits", "pagerank"],
+                    help="what fills the CPU buffer: the nodes of highest in-degree (the configurations' rule), of "
+                         "highest expected visits under the sampler (gids_graph_visit_scores), or of highest "
+                         "weighted reverse PageRank (gids_graph_reverse_pagerank, the metric the paper names)")
     ap.add_argument("--cache-lines", type=int, default=0, help="override the number of cache lines (rounded to ways)")
     ap.add_argument("--accum", type=int, default=0, help="accumulator threshold (0 = every gather moves its own rows)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="time budget of the oracle leg")
@@ -146,12 +146,16 @@ def main() -> int:
     g = wl.make_graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max, np.dtype(cfg.index_dtype), native=True)
     log(f"graph: {g.n_edges} edges, mean degree {g.n_edges / g.n:.2f} ({time.time() - t0:.1f} s)")
     t0 = time.time()
-    if args.hot_by == "visits" and cfg.cpu_rows:
+    if args.hot_by != "indegree" and cfg.cpu_rows:
         from paper_2306_16384_amd.session import GraphSampler
         with GraphSampler(g.indptr, g.indices) as gs_rank:
             t1 = time.time()
-            scores = gs_rank.visit_scores(cfg.fanouts, cfg.n_seeds).cpu().numpy().view(np.uint64)
-            log(f"visit scores on the GPU: {time.time() - t1:.2f} s")
+            if args.hot_by == "visits":
+                scores = gs_rank.visit_scores(cfg.fanouts, cfg.n_seeds)
+            else:
+                scores = gs_rank.reverse_pagerank(55705, 20)         # damping 0.85, 20 power iterations
+            scores = scores.cpu().numpy().view(np.uint64)
+            log(f"{args.hot_by} scores on the GPU: {time.time() - t1:.2f} s")
         hot = wl.top_k_by_score(scores, cfg.cpu_rows)
         del scores
     else:

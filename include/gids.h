@@ -254,6 +254,19 @@ int gids_sample(gids_graph* graph, uint64_t seed, uint64_t batch, const uint32_t
 int gids_graph_visit_scores(gids_graph* graph, const uint32_t* fanouts_host, uint32_t n_layers, uint64_t n_seeds,
                             uint64_t* scores_dev, void* stream);
 
+/* The hot-node metric Section 3.3 names: weighted reverse PageRank.  Rank
+ * flows along the adjacency slots (the way sampling walks, against the
+ * direction of the dataset's edges), a node of degree deg passing 1/deg of its
+ * damped rank along each slot; uniform teleport; nodes without slots pass
+ * nothing on.  Power iteration in integers with total mass 2^44:
+ *   base = floor(2^44 / n);  r_0 = base;  teleport = floor(base * (65536 - damping_q16) / 65536)
+ *   r_(k+1)(u) = teleport + sum over slots v -> u of floor(floor(r_k(v) * damping_q16 / 65536) / deg v)
+ * scores_dev receives r_(n_iters) as n_nodes uint64 (device).  damping_q16 in
+ * [0, 65536], n_iters <= 10000, else GIDS_E_INVAL.  Blocks until done (a
+ * set-up step, not part of the hot path). */
+int gids_graph_reverse_pagerank(gids_graph* graph, uint32_t damping_q16, uint32_t n_iters, uint64_t* scores_dev,
+                                void* stream);
+
 /* Number of in-flight fills an accumulator needs so that a storage device of
  * `iops_peak` requests/s per device sustains `ratio` of its peak, given the
  * latency of the initial and termination phases in seconds (Section 3.2,

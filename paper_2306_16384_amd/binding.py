@@ -16,7 +16,7 @@ EXPORTS = [
     "gids_store_create", "gids_store_host_ptr", "gids_store_destroy", "gids_store_calibrate", "gids_cache_create", "gids_cache_destroy",
     "gids_cache_reserve", "gids_cache_set_policy", "gids_cpu_buffer_pin", "gids_window_push", "gids_gather", "gids_flush", "gids_stats_read",
     "gids_cache_gathers", "gids_cache_snapshot", "gids_profile_enable", "gids_profile_read", "gids_window_push_dev",
-    "gids_graph_create", "gids_graph_destroy", "gids_sample_capacity", "gids_sample", "gids_graph_visit_scores", "gids_accum_threshold", "gids_last_error",
+    "gids_graph_create", "gids_graph_destroy", "gids_sample_capacity", "gids_sample", "gids_graph_visit_scores", "gids_graph_reverse_pagerank", "gids_accum_threshold", "gids_last_error",
 ]
 
 
@@ -72,6 +72,7 @@ def lib() -> C.CDLL:
         L.gids_sample_capacity.argtypes = [C.POINTER(u32), u32, u64]
         L.gids_sample.argtypes = [vp, u64, u64, C.POINTER(u32), u32, u64, vp, u64, u64, vp, u64, vp, vp]
         L.gids_graph_visit_scores.argtypes = [vp, C.POINTER(u32), u32, u64, vp, vp]
+        L.gids_graph_reverse_pagerank.argtypes = [vp, u32, u32, vp, vp]
         L.gids_profile_enable.argtypes = [vp, C.c_int]
         L.gids_profile_read.argtypes = [vp, u64, C.POINTER(C.c_float)]
         L.gids_accum_threshold.restype = C.c_double
@@ -198,6 +199,10 @@ def gids_sample(graph: int, seed: int, batch: int, fanouts, n_seeds: int, raw_de
 def gids_graph_visit_scores(graph: int, fanouts, n_seeds: int, scores_dev_ptr: int, stream: int = 0) -> None:
     arr, n = _fanouts(fanouts)
     _check(lib().gids_graph_visit_scores(graph, arr, n, n_seeds, scores_dev_ptr, stream))
+
+
+def gids_graph_reverse_pagerank(graph: int, damping_q16: int, n_iters: int, scores_dev_ptr: int, stream: int = 0) -> None:
+    _check(lib().gids_graph_reverse_pagerank(graph, damping_q16, n_iters, scores_dev_ptr, stream))
 
 
 def gids_profile_enable(cache: int, on: bool) -> None:

@@ -947,6 +947,27 @@ int gids_graph_visit_scores(gids_graph* graph, const uint32_t* fanouts, uint32_t
     return GIDS_OK;
 }
 
+int gids_graph_reverse_pagerank(gids_graph* graph, uint32_t damping_q16, uint32_t n_iters, uint64_t* scores_dev,
+                                void* stream) {
+    if (!graph || !scores_dev) return fail(GIDS_E_INVAL, "gids_graph_reverse_pagerank: NULL argument");
+    if (damping_q16 > 65536u || n_iters > 10000u) return fail(GIDS_E_INVAL, "gids_graph_reverse_pagerank: damping_q16 must be <= 65536 and n_iters <= 10000");
+    uint64_t* scratch = nullptr;
+    int rc;
+    if ((rc = dev_alloc(&scratch, graph->n_nodes))) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (graph->id_bytes == 4)
+        launch_reverse_pagerank<int32_t>(graph->indptr, static_cast<const int32_t*>(graph->indices), graph->n_nodes,
+                                         damping_q16, n_iters, scratch, scores_dev, s);
+    else
+        launch_reverse_pagerank<int64_t>(graph->indptr, static_cast<const int64_t*>(graph->indices), graph->n_nodes,
+                                         damping_q16, n_iters, scratch, scores_dev, s);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipStreamSynchronize(s);        // the scratch array goes away with the call
+    dev_free(scratch);
+    if (e != hipSuccess) return fail(GIDS_E_HIP, "gids_graph_reverse_pagerank: %s", hipGetErrorString(e));
+    return GIDS_OK;
+}
+
 double gids_accum_threshold(double iops_peak, double t_initial, double t_termination, double ratio, int n_ssd) {
     // N = IOPS_achieved * (Ti + Ts + Tt) * n_ssd with Ts = N / (IOPS_peak * n_ssd), at IOPS_achieved = ratio * IOPS_peak
     if (!(ratio > 0.0) || !(ratio < 1.0) || n_ssd < 1) return -1.0;

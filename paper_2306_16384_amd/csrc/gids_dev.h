@@ -161,6 +161,11 @@ void launch_visit_scores(const int64_t* indptr, const IdT* indices, uint64_t n, 
                          uint32_t n_layers, uint64_t n_seeds, uint64_t* cur, uint64_t* nxt, uint64_t* score,
                          hipStream_t s);
 
+// weighted reverse PageRank after n_iters power iterations; scratch is an n-entry array
+template <typename IdT>
+void launch_reverse_pagerank(const int64_t* indptr, const IdT* indices, uint64_t n, uint32_t damping_q16,
+                             uint32_t n_iters, uint64_t* scratch, uint64_t* score, hipStream_t s);
+
 void launch_calibrate(const char* store, uint64_t store_rows, uint32_t row_bytes, char* out, uint32_t n,
                       hipStream_t s);
 

@@ -204,7 +204,52 @@ __global__ void visits_zero_kernel(uint64_t* __restrict__ p, uint64_t n) {
         p[v] = 0;
 }
 
+// ---- weighted reverse PageRank (hot-node ranking, Section 3.3) ---------------
+// r_(k+1)(u) = teleport + sum over adjacency slots v -> u of floor(floor(r_k(v) * damping / 65536) / deg v),
+// total mass 2^44, integer atomics.
+
+__global__ void rank_fill_kernel(uint64_t* __restrict__ p, uint64_t n, uint64_t value) {
+    for (uint64_t v = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; v < n; v += (uint64_t)gridDim.x * blockDim.x)
+        p[v] = value;
+}
+
+template <typename IdT>
+__global__ __launch_bounds__(SM_THREADS) void rank_step_kernel(const int64_t* __restrict__ indptr,
+                                                               const IdT* __restrict__ indices, uint64_t n,
+                                                               uint64_t damping_q16, const uint64_t* __restrict__ cur,
+                                                               unsigned long long* __restrict__ nxt) {
+    const uint64_t wave0 = ((uint64_t)blockIdx.x * SM_THREADS + threadIdx.x) >> 6;
+    const uint64_t n_waves = ((uint64_t)gridDim.x * SM_THREADS) >> 6;
+    for (uint64_t v = wave0; v < n; v += n_waves) {
+        const int64_t start = indptr[v];
+        const uint64_t deg = (uint64_t)(indptr[v + 1] - start);
+        if (!deg) continue;
+        const uint64_t w = (cur[v] * damping_q16 >> 16) / deg;
+        if (!w) continue;
+        for (uint64_t s = lane_id(); s < deg; s += 64) atomicAdd(&nxt[(uint64_t)indices[start + s]], (unsigned long long)w);
+    }
+}
+
 }  // namespace
+
+template <typename IdT>
+void launch_reverse_pagerank(const int64_t* indptr, const IdT* indices, uint64_t n, uint32_t damping_q16,
+                             uint32_t n_iters, uint64_t* scratch, uint64_t* score, hipStream_t s) {
+    const uint32_t flat = (uint32_t)std::min<uint64_t>((n + 255) / 256, 4096);
+    const uint32_t per_node = (uint32_t)std::min<uint64_t>((n + 3) / 4, 1u << 16);
+    const uint64_t base = (1ull << 44) / n;
+    const uint64_t teleport = base * (65536u - damping_q16) >> 16;
+    // ping-pong so that the last iteration lands in score[]
+    uint64_t* cur = (n_iters & 1) ? scratch : score;
+    uint64_t* nxt = (n_iters & 1) ? score : scratch;
+    hipLaunchKernelGGL(rank_fill_kernel, dim3(flat), dim3(256), 0, s, cur, n, base);
+    for (uint32_t k = 0; k < n_iters; k++) {
+        hipLaunchKernelGGL(rank_fill_kernel, dim3(flat), dim3(256), 0, s, nxt, n, teleport);
+        hipLaunchKernelGGL(rank_step_kernel<IdT>, dim3(per_node), dim3(SM_THREADS), 0, s, indptr, indices, n,
+                           (uint64_t)damping_q16, cur, reinterpret_cast<unsigned long long*>(nxt));
+        std::swap(cur, nxt);
+    }
+}
 
 template <typename IdT>
 void launch_visit_scores(const int64_t* indptr, const IdT* indices, uint64_t n, const uint32_t* fanouts,
@@ -249,6 +294,8 @@ void launch_hop(const IdT* frontier, const uint32_t* n_front, uint64_t front_upp
                                     SamplerState*, hipStream_t);                                                  \
     template void launch_visit_scores<IdT>(const int64_t*, const IdT*, uint64_t, const uint32_t*, uint32_t,      \
                                            uint64_t, uint64_t*, uint64_t*, uint64_t*, hipStream_t);              \
+    template void launch_reverse_pagerank<IdT>(const int64_t*, const IdT*, uint64_t, uint32_t, uint32_t, uint64_t*, \
+                                               uint64_t*, hipStream_t);                                          \
     template void launch_hop<IdT>(const IdT*, const uint32_t*, uint64_t, const int64_t*, const IdT*, uint32_t,    \
                                   uint64_t, uint32_t*, uint32_t*, IdT*, IdT*, SamplerState*, hipStream_t);
 GIDS_INSTANTIATE(int32_t)

@@ -160,6 +160,13 @@ class GraphSampler:
                                   torch.cuda.current_stream().cuda_stream)
         return scores
 
+    def reverse_pagerank(self, damping_q16: int = 55705, n_iters: int = 20) -> torch.Tensor:
+        """Weighted reverse PageRank per node, total mass 2^44 (int64 tensor on the device)."""
+        scores = torch.empty(self.n_nodes, dtype=torch.int64, device="cuda")
+        B.gids_graph_reverse_pagerank(self.graph, damping_q16, n_iters, scores.data_ptr(),
+                                      torch.cuda.current_stream().cuda_stream)
+        return scores
+
     def close(self) -> None:
         if self.graph:
             torch.cuda.synchronize()

@@ -21,6 +21,7 @@ int main(void) {
         const uint32_t f[3] = {10, 10, 10};
         if (gids_sample_capacity(f, 3, 4096) != 4096ull * 1111) return 6;
     }
+    if (gids_graph_reverse_pagerank(NULL, 55705, 10, NULL, NULL) != GIDS_E_INVAL) return 7;
     printf("abi ok %zu\n", sizeof(gids_stats));
     return 0;
 }

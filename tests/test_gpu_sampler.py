@@ -150,3 +150,34 @@ def test_visit_scores_equal_the_oracle(env, oracle_mod, name, n, dtype):
             want = g.visit_scores(fanouts, n_seeds)
             got = gs.visit_scores(fanouts, n_seeds).cpu().numpy().view(np.uint64)
             np.testing.assert_array_equal(got, want, err_msg=f"{name} {fanouts}")
+
+
+@pytest.mark.parametrize("name,n,dtype", [("tiny", None, np.int32), ("medium", 200_000, np.int64), ("large", 250_000, np.int64)])
+def test_reverse_pagerank_equals_the_oracle(env, oracle_mod, name, n, dtype):
+    """Section 3.3's hot-node metric: integer power iteration, bit for bit, odd and even iteration counts."""
+    torch, _, GraphSampler = env
+    cfg = CONFIGS[name]
+    n = n or cfg.n_nodes
+    g = oracle_mod.Graph(cfg.seed, n, cfg.ell, cfg.p4, min(n - 1, 65535))
+    with GraphSampler(g.indptr, g.indices.astype(dtype)) as gs:
+        for d16, iters in ((55705, 0), (55705, 1), (55705, 6), (32768, 3), (65536, 2), (0, 2)):
+            want = g.reverse_pagerank(d16, iters)
+            got = gs.reverse_pagerank(d16, iters).cpu().numpy().view(np.uint64)
+            np.testing.assert_array_equal(got, want, err_msg=f"{name} d16={d16} iters={iters}")
+
+
+def test_reverse_pagerank_on_a_graph_with_empty_adjacency_lists(env, oracle_mod):
+    torch, _, GraphSampler = env
+    rng = np.random.default_rng(11)
+    n = 5000
+    deg = rng.integers(0, 6, n)                                       # a fifth of the nodes has no slots
+    indptr = np.concatenate([[0], np.cumsum(deg)]).astype(np.int64)
+    indices = rng.integers(0, n, indptr[-1]).astype(np.int64)
+    g = oracle_mod.Graph(0, n, csr=(indptr, indices))
+    with GraphSampler(indptr, indices) as gs:
+        want = g.reverse_pagerank(55705, 9)
+        got = gs.reverse_pagerank(55705, 9).cpu().numpy().view(np.uint64)
+        np.testing.assert_array_equal(got, want)
+    with pytest.raises(Exception):
+        with GraphSampler(indptr, indices) as gs:
+            gs.reverse_pagerank(70000, 3)
