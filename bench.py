@@ -69,6 +69,9 @@ def main() -> int:
                     help="what fills the CPU buffer: the nodes of highest in-degree (the configurations' rule), of "
                          "highest expected visits under the sampler (gids_graph_visit_scores), or of highest "
                          "weighted reverse PageRank (gids_graph_reverse_pagerank, the metric the paper names)")
+    ap.add_argument("--layerwise", default="", metavar="S1,S2,..",
+                    help="feed layer-wise sampled ID lists (the second sampler shape of Section 4.7): a fixed number "
+                         "of nodes per layer, drawn by connection count, instead of neighbourhood sampling")
     ap.add_argument("--cache-lines", type=int, default=0, help="override the number of cache lines (rounded to ways)")
     ap.add_argument("--accum", type=int, default=0, help="accumulator threshold (0 = every gather moves its own rows)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="time budget of the oracle leg")
@@ -198,7 +201,14 @@ def main() -> int:
     rank_table = wl.synth.zipf_rank_table(cfg.n_nodes, cfg.seed_zipf_s) if cfg.seed_zipf_s is not None else None
     t0 = time.time()
     raws = [np.arange(b * prewarm, min(cfg.n_nodes, (b + 1) * prewarm), dtype=np.int64) for b in range(n_pre)]
-    raws += [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds, rank_table) for b in range(n_batches - n_pre)]
+    if args.layerwise:
+        layer_sizes = tuple(int(x) for x in args.layerwise.split(","))
+        for b in range(n_batches - n_pre):
+            raws.append(wl.layerwise_minibatch(g, cfg.seed, b, layer_sizes, cfg.n_seeds))
+            if b % 8 == 7:
+                log(f"layer-wise lists: {b + 1} of {n_batches - n_pre} ({time.time() - t0:.0f} s)")
+    else:
+        raws += [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds, rank_table) for b in range(n_batches - n_pre)]
     log(f"sampled {n_batches - n_pre} minibatches, raw IDs per minibatch <= {max(len(r) for r in raws)} "
         f"({time.time() - t0:.1f} s)")
     print(json.dumps(run_point(args, env, cfg, window, raws, n_pre)))
@@ -225,6 +235,8 @@ def run_point(args, env, cfg, window, raws, n_pre):
     log(f"cache W={window}: created, CPU buffer {len(hot) * R / 1e9:.2f} GB pinned ({time.time() - t0:.1f} s)")
     dev = [ses.to_device(r) for r in raws[:n_batches]]
     sampler = None
+    if args.gpu_sampler and args.layerwise:
+        raise SystemExit("--gpu-sampler draws neighbourhood samples; it cannot be combined with --layerwise")
     if args.gpu_sampler:
         from paper_2306_16384_amd.session import GraphSampler
         g = env["g"]
@@ -332,7 +344,7 @@ def run_point(args, env, cfg, window, raws, n_pre):
         "unique_ids_per_s": n_unique * scale / (total_ms * 1e-3),
         "config": {"workload": cfg.name, "n_nodes": cfg.n_nodes, "row_bytes": R, "cache_lines": cfg.cache_lines,
                    "ways": cfg.ways, "line_bytes": cfg.line_bytes, "cpu_buffer_rows": cfg.cpu_rows, "window": window,
-                   "fanouts": list(cfg.fanouts), "seeds_per_batch": cfg.n_seeds, "accum_threshold": args.accum, "prewarm_lists": n_pre, "gpu_sampler": bool(args.gpu_sampler), "policy": args.policy, "hot_by": args.hot_by,
+                   "fanouts": list(cfg.fanouts), "seeds_per_batch": cfg.n_seeds, "accum_threshold": args.accum, "prewarm_lists": n_pre, "gpu_sampler": bool(args.gpu_sampler), "policy": args.policy, "hot_by": args.hot_by, "id_stream": ("layerwise " + args.layerwise) if args.layerwise else "neighbourhood",
                    "id_dtype": cfg.index_dtype, "scaled_from": base.n_nodes if cfg.n_nodes != base.n_nodes else None},
         "per_step": {"unique": n_unique * scale / steps, "hit": n_hit * scale / steps, "cpu_hit": n_cpu * scale / steps,
                      "miss": n_miss * scale / steps, "bypass": n_byp * scale / steps},

@@ -120,3 +120,60 @@ def test_skewed_seed_samplers_agree(oracle_mod):
             raw_np = wl.sample_minibatch(g_np, cfg.seed, b, (25, 10), 512, tab)
             raw_c = g_c.sample(cfg.seed, b, (25, 10), 512, rank_table=tab, perm=perm)
             np.testing.assert_array_equal(raw_np, raw_c)
+
+
+def test_layerwise_minibatch_has_fixed_layers_drawn_by_connection_count():
+    """The layer-wise stream (Section 4.7's second sampler shape): every layer holds exactly its size of
+    distinct nodes, all of them neighbours of the previous layer, and a node is kept with a probability that
+    grows with the number of slots pointing to it."""
+    cfg = CONFIGS["tiny"]
+    g = wl.make_graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max, np.dtype(np.int32))
+    sizes = (100, 150)
+    n_seeds = 64
+    for b in range(5):
+        raw = wl.layerwise_minibatch(g, cfg.seed, b, sizes, n_seeds)
+        assert np.array_equal(raw, wl.layerwise_minibatch(g, cfg.seed, b, sizes, n_seeds))
+        assert len(raw) == n_seeds + sum(sizes)
+        seeds, l1, l2 = raw[:n_seeds], raw[n_seeds:n_seeds + sizes[0]], raw[n_seeds + sizes[0]:]
+        assert len(np.unique(l1)) == sizes[0] and len(np.unique(l2)) == sizes[1]
+        for prev, layer in ((np.unique(seeds), l1), (l1, l2)):
+            nb = np.concatenate([g.indices[g.indptr[v]:g.indptr[v + 1]] for v in prev])
+            assert np.isin(layer, nb).all()
+    # a layer larger than the neighbourhood keeps all of it
+    raw = wl.layerwise_minibatch(g, cfg.seed, 0, (10**6,), n_seeds)
+    nb = np.concatenate([g.indices[g.indptr[v]:g.indptr[v + 1]] for v in np.unique(raw[:n_seeds])])
+    assert np.array_equal(raw[n_seeds:], np.unique(nb))
+    # one layer from a fixed seed set, many minibatch counters: frequency rises with multiplicity
+    hub = np.argsort(-(g.indptr[1:] - g.indptr[:-1]))[:20]
+    nb = np.concatenate([g.indices[g.indptr[v]:g.indptr[v + 1]] for v in hub])
+    ids, mult = np.unique(nb, return_counts=True)
+    kept = np.zeros(cfg.n_nodes)
+    import workload.synth as S
+    orig = S.minibatch_seeds
+    S.minibatch_seeds = lambda seed, n, batch, n_seeds, rank_table=None: hub.astype(np.int64)
+    try:
+        for b in range(300):
+            raw = S.layerwise_minibatch(g, cfg.seed, b, (len(ids) // 4,), len(hub))
+            kept[raw[len(hub):]] += 1
+    finally:
+        S.minibatch_seeds = orig
+    # the definition, slot by slot, where the generator takes its short cut (few kept out of many slots)
+    S.minibatch_seeds = lambda seed, n, batch, n_seeds, rank_table=None: hub.astype(np.int64)
+    try:
+        raw = S.layerwise_minibatch(g, cfg.seed, 7, (16,), len(hub))
+    finally:
+        S.minibatch_seeds = orig
+    best = {}
+    for v in np.unique(hub):
+        for e in range(g.indptr[v], g.indptr[v + 1]):
+            k = int(wl.hash_chain(cfg.seed, 9, 7, 0, e))
+            u = int(g.indices[e])
+            best[u] = min(best.get(u, 1 << 64), k)
+    assert len(nb) > 4 * 16 + 1024
+    want = sorted(sorted(best, key=lambda u: (best[u], u))[:16])
+    assert raw[len(hub):].tolist() == want
+    rate = kept[ids] / 300
+    lo, hi = rate[mult == 1].mean(), rate[mult >= 3].mean()
+    assert hi > lo + 0.2, (lo, hi)
+    # weight-proportional race: P(keep) for multiplicity 1 is below the uniform share, above it for >= 3
+    assert lo < 0.25 < hi

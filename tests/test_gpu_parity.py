@@ -357,3 +357,19 @@ def test_link_calibration_is_sane(gpu):
         assert 10 < n95 < 1e6
     finally:
         gids.gids_store_destroy(store)
+
+
+def test_layerwise_id_streams(gpu, oracle_mod):
+    """The second sampler shape (Section 4.7): fixed-size layers drawn by connection count give
+    lists with much heavier overlap between minibatches than neighbourhood sampling."""
+    cfg = CONFIGS["tiny"]
+    g = wl.make_graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max)
+    table = wl.normal_table(np.float32)
+    feats = wl.feature_rows(cfg.seed, np.arange(cfg.n_nodes), cfg.dim, table)
+    hot = wl.hot_nodes(g, cfg.cpu_rows)
+    batches = [wl.layerwise_minibatch(g, cfg.seed, b, (512, 512), cfg.n_seeds) for b in range(cfg.n_batches)]
+    for window in (0, cfg.window):
+        run_case(gpu, oracle_mod, feats, batches, id_dtype=np.int32, lines=cfg.cache_lines, ways=cfg.ways,
+                 line_bytes=cfg.line_bytes, window=window, hot=hot, label=f"layerwise/W{window}")
+        run_case(gpu, oracle_mod, feats, batches, id_dtype=np.int32, lines=cfg.cache_lines, ways=cfg.ways,
+                 line_bytes=cfg.line_bytes, window=window, label=f"layerwise/nohot/W{window}", policy=(1, 9))

@@ -8,7 +8,7 @@ tests may draw their inputs from it.
 """
 from .synth import (  # noqa: F401
     mix64, hash_chain, Graph, make_graph, hot_nodes, minibatch_seeds,
-    sample_minibatch, normal_table, feature_rows, fill_store, TAGS, top_k_by_score,
+    sample_minibatch, layerwise_minibatch, normal_table, feature_rows, fill_store, TAGS, top_k_by_score,
 )
 from .configs import CONFIGS, Config, scaled  # noqa: F401
 from . import native, synth  # noqa: F401,E402

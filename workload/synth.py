@@ -25,6 +25,15 @@ Definitions (all arithmetic modulo 2**64 unless stated):
   features     feat(v, c) = T[(H(seed, FEAT, v, c >> 2) >> (16 * (c & 3))) & 0xFFFF]
                with T a 65536-entry table of N(0,1) quantiles in the row dtype
 
+  layer-wise   (second workload, Section 4.7) layer l of minibatch b keeps a fixed
+               number s_l of the distinct nodes that the adjacency slots of the
+               previous layer point to: slot e gets key H(seed, LAYER, b, l, e), a
+               node's key is the smallest key among the slots that point to it, and
+               the s_l nodes of smallest key are kept (ties -> lower ID).  The
+               minimum of m uniform keys wins with probability proportional to m,
+               so this is weighted sampling without replacement, weight = number of
+               connections into the previous layer
+
 The sampling workload follows the two-layer neighbourhood sampling example of
 the GraphSAGE description in Section 2.2.2 of the paper ("up to" fanout
 neighbours per node, uniformly at random).
@@ -42,7 +51,7 @@ U64 = np.uint64
 GOLDEN = U64(0x9E3779B97F4A7C15)
 M1 = U64(0xBF58476D1CE4E5B9)
 M2 = U64(0x94D049BB133111EB)
-TAGS = {"DEG": 1, "EDGE": 2, "FEAT": 3, "SEED": 4, "NBR": 5, "PERM": 6, "RANK": 7}
+TAGS = {"DEG": 1, "EDGE": 2, "FEAT": 3, "SEED": 4, "NBR": 5, "PERM": 6, "RANK": 7, "LAYER": 9}
 
 
 def mix64(z):
@@ -248,6 +257,48 @@ def sample_minibatch(g: Graph, seed: int, batch: int, fanouts, n_seeds: int,
         sampled = indices[src].astype(np.int64)
         parts.append(sampled)
         frontier = np.unique(sampled)
+    return np.concatenate(parts)
+
+
+def layerwise_minibatch(g: Graph, seed: int, batch: int, layer_sizes, n_seeds: int) -> np.ndarray:
+    """Raw node-ID list of one minibatch under layer-wise sampling: the seeds, then
+    for each layer a fixed number of nodes drawn from the neighbourhood of the
+    previous layer with probability proportional to how many of its adjacency
+    slots point to them (ascending ID order within a layer)."""
+    seeds = minibatch_seeds(seed, g.n, batch, n_seeds)
+    parts = [seeds]
+    cur = np.unique(seeds)
+    indptr, indices = g.indptr, g.indices
+    for layer, size in enumerate(layer_sizes):
+        start = indptr[cur]
+        deg = indptr[cur + 1] - start
+        total = int(deg.sum())
+        if total == 0:
+            break
+        slot = np.repeat(start, deg) + (np.arange(total, dtype=np.int64) - np.repeat(np.cumsum(deg) - deg, deg))
+        nbr = indices[slot].astype(np.int64)
+        key = hash_chain(seed, TAGS["LAYER"], batch, layer, slot.astype(U64))
+        # Only the slots of smallest key can decide: look at a prefix of the key order first.
+        look = min(total, 4 * size + 1024)
+        while True:
+            if look < total:
+                part = np.argpartition(key, look - 1)[:look]
+                nbr_p, key_p = nbr[part], key[part]
+                bound = key_p.max()                          # every slot outside the prefix has a key >= bound
+            else:
+                nbr_p, key_p, bound = nbr, key, None
+            order = np.lexsort((key_p, nbr_p))               # by node, then key: first of each node = its smallest
+            nbr_s, key_s = nbr_p[order], key_p[order]
+            first = np.concatenate([[True], nbr_s[1:] != nbr_s[:-1]])
+            cand, ckey = nbr_s[first], key_s[first]
+            keep = np.lexsort((cand, ckey))[:size]           # smallest keys, ties -> lower ID
+            # complete when no slot outside the prefix could beat or tie the last one kept
+            if bound is None or (len(keep) == size and ckey[keep[-1]] < bound):
+                break
+            look = min(total, look * 4)
+        chosen = np.sort(cand[keep])
+        parts.append(chosen)
+        cur = chosen
     return np.concatenate(parts)
 
 
