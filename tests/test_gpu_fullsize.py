@@ -1,7 +1,9 @@
 """Parity at the benchmark's sizes and launch configuration: Medium at full
-size (every counter of every minibatch, full tensors on a subset) and Large at
-the node count the benchmark runs (counters of every minibatch, distinct-ID
-lists exact, sampled rows against the oracle's closed-form feature rows)."""
+size (every counter of every minibatch, full tensors on a subset); Large and
+the skew configuration at the node count the benchmark runs, and the
+cache-resident configuration at its full size (counters of every minibatch,
+distinct-ID lists exact, sampled rows of every class against the oracle's
+closed-form feature rows, final tags and stamps)."""
 import numpy as np
 import pytest
 
@@ -72,53 +74,54 @@ def test_medium_full_size(oracle_mod):
         assert np.array_equal(tags, sim.tags) and np.array_equal(stamps, sim.stamps)
 
 
-def test_large_at_benchmark_size(oracle_mod):
-    import torch
-    from paper_2306_16384_amd.session import GatherSession
+def pinnable(cfg_name, sizes):
+    """The configuration at the first of `sizes` whose store this box can pin."""
     import paper_2306_16384_amd as gids
-    # the benchmark's node count; a box that pins less host memory runs the same test at half the size
-    for n_nodes in (28_000_000, 14_000_000, 7_000_000):
-        cfg = wl.scaled(CONFIGS["large"], n_nodes)
+    for n_nodes in sizes:
+        cfg = CONFIGS[cfg_name] if n_nodes == CONFIGS[cfg_name].n_nodes else wl.scaled(CONFIGS[cfg_name], n_nodes)
         try:
             probe = gids.gids_store_create(cfg.n_nodes, cfg.row_bytes, 8)
         except gids.GidsError as e:
             if e.code != gids.GIDS_E_NOMEM:
                 raise
-            print(f"[fullsize large] cannot pin {cfg.n_nodes * cfg.row_bytes / 1e9:.1f} GB, trying smaller", flush=True)
+            print(f"[fullsize {cfg_name}] cannot pin {cfg.n_nodes * cfg.row_bytes / 1e9:.1f} GB, trying smaller", flush=True)
             continue
         gids.gids_store_destroy(probe)
-        break
-    else:
-        pytest.fail("cannot pin even 14 GB of host memory")
-    n_b = 60
-    print(f"[fullsize large] N={cfg.n_nodes} lines={cfg.cache_lines} cpu_rows={cfg.cpu_rows} batches={n_b}", flush=True)
-    g = wl.make_graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max, native=True)
-    table = wl.normal_table(np.float16)
-    hot = wl.hot_nodes(g, cfg.cpu_rows)
-    raws = [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds) for b in range(n_b)]
+        return cfg
+    pytest.fail(f"cannot pin even {sizes[-1]} rows of host memory")
+
+
+def run_big(oracle_mod, cfg, raws, keep, table, hot=None, after_each=None):
+    """Counters of every minibatch, distinct-ID lists exact, rows of every class sampled against the oracle's
+    closed-form feature rows, final tags and stamps."""
+    import torch
+    from paper_2306_16384_amd.session import GatherSession
+    n_b = len(raws)
     cap = max(len(np.unique(r)) for r in raws)
-    keep = {0, 9, 33, n_b - 1}
     with GatherSession(cfg.n_nodes, cfg.row_bytes, np.int64, cfg.cache_lines, cfg.ways, cfg.line_bytes,
                        cfg.window) as ses:
         wl.fill_store(cfg.seed, cfg.n_nodes, cfg.dim, table, ses.store_address())
-        ses.pin_hot(hot)
+        if hot is not None:
+            ses.pin_hot(hot)
         outs, uniqs, stats_of = drive(ses, torch, raws, cfg.window, cap, cfg.row_bytes, keep)
         sim = oracle_mod.Sim(cfg.n_nodes, cfg.cache_lines, cfg.ways, cfg.window)      # counts only
-        sim.set_hot(hot)
+        if hot is not None:
+            sim.set_hot(hot)
         rng = np.random.default_rng(0)
         pushed = 0
         for t, raw in enumerate(raws):
-            while pushed < n_b and pushed <= t + cfg.window:
+            while cfg.window and pushed < n_b and pushed <= t + cfg.window:
                 sim.push(raws[pushed])
                 pushed += 1
             u, _, stats, cls = sim.gather(raw, want_rows=False, want_cls=True)
             st = stats_of[t]
             assert st.as_tuple() == tuple(int(x) for x in stats), (t, st.as_tuple(), stats.tolist())
+            if after_each:
+                after_each(t, st)
             if t in keep:
                 assert np.array_equal(uniqs[t][:len(u)].cpu().numpy(), u)
-                # rows of every class (hit, CPU buffer, installed miss, bypass), sampled, against the closed form
                 pick = []
-                for k in range(4):
+                for k in range(4):                                # hit, CPU buffer, installed miss, bypass
                     idx = np.flatnonzero(cls == k)
                     if len(idx):
                         pick.append(rng.choice(idx, size=min(48, len(idx)), replace=False))
@@ -128,3 +131,48 @@ def test_large_at_benchmark_size(oracle_mod):
                 assert np.array_equal(got, want), f"minibatch {t}"
         tags, stamps = ses.snapshot()
         assert np.array_equal(tags, sim.tags) and np.array_equal(stamps, sim.stamps)
+
+
+def test_large_at_benchmark_size(oracle_mod):
+    # the benchmark's node count; a box that pins less host memory runs the same test at half the size
+    cfg = pinnable("large", (28_000_000, 14_000_000, 7_000_000))
+    n_b = 60
+    print(f"[fullsize large] N={cfg.n_nodes} lines={cfg.cache_lines} cpu_rows={cfg.cpu_rows} batches={n_b}", flush=True)
+    g = wl.make_graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max, native=True)
+    hot = wl.hot_nodes(g, cfg.cpu_rows)
+    raws = [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds) for b in range(n_b)]
+    run_big(oracle_mod, cfg, raws, {0, 9, 33, n_b - 1}, wl.normal_table(np.float16), hot=hot)
+
+
+def test_skew_at_benchmark_size(oracle_mod):
+    """The skew configuration (16 ways, Zipf-ranked seeds, depth 4) at the node count the benchmark runs."""
+    cfg = pinnable("skew", (28_000_000, 14_000_000, 7_000_000))
+    n_b = 40
+    print(f"[fullsize skew] N={cfg.n_nodes} lines={cfg.cache_lines} ways={cfg.ways} batches={n_b}", flush=True)
+    g = wl.make_graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max, native=True)
+    hot = wl.hot_nodes(g, cfg.cpu_rows)
+    rank_table = wl.synth.zipf_rank_table(cfg.n_nodes, cfg.seed_zipf_s)
+    raws = [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds, rank_table) for b in range(n_b)]
+    run_big(oracle_mod, cfg, raws, {0, 5, n_b - 1}, wl.normal_table(np.float16), hot=hot)
+
+
+def test_cache_resident_full_size(oracle_mod):
+    """The cache-resident configuration at its full size (10 M rows of 3 KiB in 4 KiB lines, a cache that holds
+    the whole table): lists that touch every row once, then sampled minibatches, which must all hit."""
+    cfg = pinnable("resident", (10_000_000,))
+    n_b = 24
+    print(f"[fullsize resident] N={cfg.n_nodes} lines={cfg.cache_lines} ways={cfg.ways} batches=10+{n_b}", flush=True)
+    g = wl.make_graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max, native=True)
+    step = 1_000_000
+    raws = [np.arange(b, min(cfg.n_nodes, b + step), dtype=np.int64) for b in range(0, cfg.n_nodes, step)]
+    n_pre = len(raws)
+    raws += [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds) for b in range(n_b)]
+
+    def all_hits_after_coverage(t, st):
+        if t >= n_pre:
+            assert st.n_miss == 0 and st.n_hit == st.n_unique, (t, st.as_tuple())
+        else:
+            assert st.n_miss == st.n_unique and st.n_bypass == 0, (t, st.as_tuple())
+
+    run_big(oracle_mod, cfg, raws, {0, n_pre - 1, n_pre, n_pre + n_b - 1}, wl.normal_table(np.float32),
+            after_each=all_hits_after_coverage)
