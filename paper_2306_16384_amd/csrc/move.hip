@@ -71,7 +71,8 @@ __global__ __launch_bounds__(MV_THREADS) void move_kernel(CacheView<IdT> c, cons
                                                           BatchHdr* __restrict__ hdr,
                                                           const uint64_t* __restrict__ plan, char* __restrict__ out,
                                                           IdT* __restrict__ unique_out, uint32_t link_blocks,
-                                                          uint32_t link_ch, uint32_t hbm_ch) {
+                                                          uint32_t link_ch, uint32_t hbm_ch, uint32_t link_spread,
+                                                          uint32_t link_auto) {
     if (!hdr->ok) return;
     const uint32_t n_u = hdr->n_u;
     const uint32_t row_u4 = c.row_bytes >> 4;
@@ -79,13 +80,28 @@ __global__ __launch_bounds__(MV_THREADS) void move_kernel(CacheView<IdT> c, cons
     const uint32_t sub = lane % G, grp = lane / G;
     constexpr uint32_t PER_ITER = 64 / G;                     // rows a wave moves at once
     const bool link_role = blockIdx.x < link_blocks;
-    const uint32_t ch = link_role ? link_ch : hbm_ch;         // plan entries a wave scans per step
+    // How many of the launched link workgroups take part.  Requests to host memory queue in front of every
+    // other kernel's memory traffic: about fifty workgroups nearly saturate the link, a hundred gain the last
+    // percent but slow the concurrent metadata kernels of the next minibatch several times over, which only a
+    // long transfer hides.
+    uint32_t link_used = link_blocks;
+    if (link_auto) {
+        const uint64_t bytes = (uint64_t)hdr->n_link * c.row_bytes;
+        const uint32_t want = bytes < (32ull << 20) ? 48u : bytes < (128ull << 20) ? 64u : 96u;
+        link_used = want < link_blocks ? want : link_blocks;
+    }
+    if (link_role && blockIdx.x >= link_used) return;
+    uint32_t ch = link_role ? link_ch : hbm_ch;               // plan entries a wave scans per step
     const uint32_t role_block = link_role ? blockIdx.x : blockIdx.x - link_blocks;
-    const uint32_t role_blocks = link_role ? link_blocks : gridDim.x - link_blocks;
+    const uint32_t role_blocks = link_role ? link_used : gridDim.x - link_blocks;
     const uint64_t wave0 = ((uint64_t)role_block * MV_THREADS + threadIdx.x) >> 6;
     const uint64_t n_waves = ((uint64_t)role_blocks * MV_THREADS) >> 6;
     // HBM half: chunk = wave index, strided.  Link half: the persistent waves draw chunks from a counter, so
     // that none is left with a long tail of slow rows while the others have run out of work.
+    // The host sized link_ch for the longest list this call may hold; with the real count known here the
+    // chunks shrink until every link wave can expect a few of them, which is what evens out the finish.
+    if (link_role)
+        while (ch > 4 && n_u / ch < link_spread * n_waves) ch >>= 1;
     uint64_t base = wave0 * ch;
     for (;;) {
         if (link_role) {
@@ -314,7 +330,8 @@ inline uint32_t row_grid(uint64_t rows, int g, int blocks) {
 
 template <typename IdT>
 void launch_move(const CacheView<IdT>& c, const IdT* unique, BatchHdr* hdr, uint64_t n_upper,
-                 const uint64_t* plan, char* out, IdT* unique_out, int blocks, int link_blocks_max, hipStream_t s) {
+                 const uint64_t* plan, char* out, IdT* unique_out, int blocks, int link_blocks_max, bool link_auto,
+                 hipStream_t s) {
     const int g = lanes_per_row(c.row_bytes);
     // a wave of the HBM half takes 16 plan entries per step, one of the link half 64
     static const uint32_t hbm_ch = [] {
@@ -330,11 +347,17 @@ void launch_move(const CacheView<IdT>& c, const IdT* unique, BatchHdr* hdr, uint
         const int v = e ? atoi(e) : 64;
         return (uint32_t)((v == 4 || v == 8 || v == 16 || v == 32 || v == 64) ? v : 64);
     }();
+    static const uint32_t link_spread = [] {                  // chunks a link wave should expect (0: keep link_ch)
+        const char* e = getenv("GIDS_LINK_SPREAD");
+        const int v = e ? atoi(e) : 2;
+        return (uint32_t)((v >= 0 && v <= 64) ? v : 2);
+    }();
     uint32_t link_ch = link_ch_max;
     while (link_ch > 4 && n_upper / link_ch < (uint64_t)link_blocks_max * (MV_THREADS / 64)) link_ch >>= 1;
     const uint32_t link_blocks = row_grid(n_upper, 64 / (int)link_ch, link_blocks_max);
     GIDS_DISPATCH_G(g, hipLaunchKernelGGL((move_kernel<IdT, G>), dim3(link_blocks + hbm_blocks), dim3(MV_THREADS), 0,
-                                          s, c, unique, hdr, plan, out, unique_out, link_blocks, link_ch, hbm_ch));
+                                          s, c, unique, hdr, plan, out, unique_out, link_blocks, link_ch, hbm_ch, link_spread,
+                                          link_auto ? 1u : 0u));
 }
 
 template <typename IdT>
@@ -376,7 +399,7 @@ void launch_finalize(Ctl* ctl, StatsRec* rec, uint64_t seq, const uint32_t* n_u,
 
 #define GIDS_INSTANTIATE(IdT)                                                                                       \
     template void launch_move<IdT>(const CacheView<IdT>&, const IdT*, BatchHdr*, uint64_t, const uint64_t*,         \
-                                   char*, IdT*, int, int, hipStream_t);                                             \
+                                   char*, IdT*, int, int, bool, hipStream_t);                                       \
     template void launch_queue<IdT>(const CacheView<IdT>&, const IdT*, const BatchHdr*, uint64_t, const uint64_t*,  \
                                     char*, IdT*, FillOp*, CopyOp*, int, hipStream_t);                               \
     template void launch_flush<IdT>(const CacheView<IdT>&, FillOp*, CopyOp*, uint64_t, bool, int, hipStream_t);
