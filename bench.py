@@ -95,6 +95,9 @@ def main() -> int:
     ap.add_argument("--sampler-zero-copy", action="store_true",
                     help="with --gpu-sampler: leave the CSR graph in pinned host memory and sample it zero-copy "
                          "(the paper's arrangement) instead of copying it to HBM")
+    ap.add_argument("--repeat", type=int, default=1,
+                    help="run the workload this many times in one process, each with a cache of its own "
+                         "(the last run is the one reported; the others are logged)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     args = ap.parse_args()
@@ -211,6 +214,10 @@ def main() -> int:
         raws += [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds, rank_table) for b in range(n_batches - n_pre)]
     log(f"sampled {n_batches - n_pre} minibatches, raw IDs per minibatch <= {max(len(r) for r in raws)} "
         f"({time.time() - t0:.1f} s)")
+    for k in range(args.repeat - 1):
+        res = run_point(args, env, cfg, window, raws, n_pre)
+        log(f"repeat {k + 1} of {args.repeat}: {res['ms_per_step']:.4f} ms per step, "
+            f"weighted roofline {res['weighted_roofline']['frac']:.4f}, phases {res['roofline']['phase_ms']}")
     print(json.dumps(run_point(args, env, cfg, window, raws, n_pre)))
     return 0
 
@@ -259,7 +266,12 @@ def run_point(args, env, cfg, window, raws, n_pre):
     # pushes go to their own stream (where a sampler would produce ID lists), gathers to the consumer's:
     # the library then overlaps the classification of minibatch t + 1 with the row movement of minibatch t
     one_stream = args.one_stream or cfg.cache_lines * cfg.line_bytes < (32 << 20)   # small caches: the library does not overlap
-    push_stream = torch.cuda.current_stream() if one_stream else torch.cuda.Stream()
+    # One push stream for the whole process: HIP multiplexes streams onto a few hardware queues in creation
+    # order, and a push stream that lands on the gather stream's queue has its event markers stuck behind the
+    # row mover, which serialises the two (seen with the sixth stream created in a sweep).
+    if "push_stream" not in env:
+        env["push_stream"] = torch.cuda.Stream()
+    push_stream = torch.cuda.current_stream() if one_stream else env["push_stream"]
     pushed = 0
 
     def keep_window_full(t):

@@ -146,7 +146,13 @@ int gids_cpu_buffer_pin(gids_cache* cache, const void* ids_host, uint64_t n);
 /* Window buffer (Section 3.4, Fig. 6 steps 1-4): append the raw ID list
  * (duplicates allowed) of a future minibatch.  Lists are gathered in push
  * order.  GIDS_E_FULL when window_depth + 1 lists are already buffered;
- * GIDS_E_INVAL when window_depth == 0. */
+ * GIDS_E_INVAL when window_depth == 0.
+ * To overlap classification with the row movement of earlier gathers, push on
+ * another stream than the one that gathers, and keep that stream for the life
+ * of the process: HIP multiplexes streams onto a few hardware queues
+ * (GPU_MAX_HW_QUEUES, 4 by default) in creation order, and the ordering
+ * markers of a push stream that shares the gather stream's queue wait behind
+ * the row mover, which serialises the two (results stay correct). */
 int gids_window_push(gids_cache* cache, const void* ids_dev, uint64_t n, void* stream);
 
 /* The same with the list's length in device memory (*n_dev <= n_max entries of
