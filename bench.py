@@ -274,9 +274,14 @@ def run_point(args, env, cfg, window, raws, n_pre):
     push_stream = torch.cuda.current_stream() if one_stream else env["push_stream"]
     pushed = 0
 
+    # At depth 0 the list of minibatch t is still pushed just before its gather (it pins nothing), so that its
+    # deduplication overlaps the previous row movement like every other depth's; --pass-ids at depth 0 is the
+    # plain call without any push.
+    use_push = window > 0 or not args.pass_ids
+
     def keep_window_full(t):
         nonlocal pushed
-        while window and pushed < n_batches and pushed <= t + window:
+        while use_push and pushed < n_batches and pushed <= t + window:
             if sampler is not None and pushed >= n_pre:         # list number pushed - n_pre of the sampled sequence
                 k = pushed % n_slots
                 sampler.sample(cfg.seed, pushed - n_pre, cfg.fanouts, cfg.n_seeds, raw_bufs[k], n_bufs[k],
@@ -288,7 +293,7 @@ def run_point(args, env, cfg, window, raws, n_pre):
 
     def step(t):
         keep_window_full(t)                                     # push of minibatch t + W (+1 at start-up)
-        seq = ses.gather(dev[t] if (args.pass_ids or not window) else None, outs[t % ring], uniq)
+        seq = ses.gather(dev[t] if args.pass_ids else None, outs[t % ring], uniq)
         if args.accum and t % ring == ring - 2:
             ses.flush()
         return seq

@@ -30,6 +30,12 @@
  *     (the one the sampler fills ID lists on) than gids_gather (the one that
  *     consumes the rows).  All gathers of one cache use one stream, all pushes
  *     one stream (the same or another).
+ *   - Threads: calls on one cache (or one graph) must not overlap in time;
+ *     the caller serialises them.  Different caches, graphs and stores may be
+ *     used from different threads at once, and several caches may share one
+ *     store (it is only read).  A store must outlive the caches created on it.
+ *     The library works on the device that is current when the store is
+ *     created; keep that device current for every later call.
  *   - IDs are signed integers of the width fixed at store creation (4 or 8
  *     bytes), valid range [0, n_rows).
  *   - Errors found by the device (an ID out of range, a gather that does not
@@ -145,8 +151,10 @@ int gids_cpu_buffer_pin(gids_cache* cache, const void* ids_host, uint64_t n);
 
 /* Window buffer (Section 3.4, Fig. 6 steps 1-4): append the raw ID list
  * (duplicates allowed) of a future minibatch.  Lists are gathered in push
- * order.  GIDS_E_FULL when window_depth + 1 lists are already buffered;
- * GIDS_E_INVAL when window_depth == 0.
+ * order.  GIDS_E_FULL when window_depth + 1 lists are already buffered.
+ * With window_depth == 0 that is one list, the next gather's own: it protects
+ * nothing from eviction and only lets its deduplication run ahead of the
+ * gather call (the gather then takes the pushed list like any window head).
  * To overlap classification with the row movement of earlier gathers, push on
  * another stream than the one that gathers, and keep that stream for the life
  * of the process: HIP multiplexes streams onto a few hardware queues
@@ -161,10 +169,11 @@ int gids_window_push(gids_cache* cache, const void* ids_dev, uint64_t n, void* s
 int gids_window_push_dev(gids_cache* cache, const void* ids_dev, uint64_t n_max, const uint32_t* n_dev, void* stream);
 
 /* Gather one minibatch.
- *   ids_dev, n       the raw ID list.  With window_depth > 0 it must have the
- *                    same distinct IDs as the oldest buffered list (else
- *                    GIDS_E_ORDER in stats), or be NULL (n ignored) to gather
- *                    that list as it was pushed.
+ *   ids_dev, n       the raw ID list.  When a list is buffered (always the
+ *                    case with window_depth > 0; after a push with
+ *                    window_depth == 0) it must have the same distinct IDs as
+ *                    the oldest buffered list (else GIDS_E_ORDER in stats), or
+ *                    be NULL (n ignored) to gather that list as it was pushed.
  *   out_dev          receives row j = feature row of the j-th smallest distinct
  *                    ID, rows packed at row_bytes; out_capacity_rows rows are
  *                    available (GIDS_E_SPACE in stats when there are more

@@ -262,7 +262,7 @@ struct CacheT final : gids_cache {
         if (pipelined) HIP_TRY(hipStreamCreateWithFlags(&meta, hipStreamNonBlocking));
         // one slot more than lists can be buffered: the slot a push overwrites was then read by the gather
         // before the previous one, whose rows have long moved, and not by the one still moving
-        slots.resize(window ? window + 2 : 0);
+        slots.resize(window + 2);
         if (const char* env = getenv("GIDS_MOVE_BLOCKS")) {
             const int b = atoi(env);
             if (b >= 1 && b <= (1 << 20)) move_blocks = b;
@@ -401,7 +401,6 @@ struct CacheT final : gids_cache {
     }
 
     int push(const void* ids, uint64_t n, const uint32_t* n_dev, hipStream_t s) override {
-        if (window == 0) return fail(GIDS_E_INVAL, "gids_window_push: the cache was created with window_depth 0");
         if (count == window + 1) return fail(GIDS_E_FULL, "gids_window_push: %u lists already buffered", count);
         if (n && !ids) return fail(GIDS_E_INVAL, "gids_window_push: ids_dev is NULL");
         const uint32_t slot = (head + count) % slots.size();
@@ -431,9 +430,12 @@ struct CacheT final : gids_cache {
         if (!out && out_cap) return fail(GIDS_E_INVAL, "gids_gather: out_dev is NULL");
         if (inverse && !ids) return fail(GIDS_E_INVAL, "gids_gather: inverse_dev needs ids_dev");
         if (window && count == 0) return fail(GIDS_E_ORDER, "gids_gather: no minibatch is buffered in the window");
-        if (!window && !ids && n) return fail(GIDS_E_INVAL, "gids_gather: ids_dev is NULL and there is no window to take the list from");
+        // With window_depth 0 a list may still have been pushed ahead (it pins nothing: its counters are back
+        // at zero before any victim is chosen); then it is the minibatch, exactly as with a window.
+        const bool head_list = window != 0 || count != 0;
+        if (!head_list && !ids && n) return fail(GIDS_E_INVAL, "gids_gather: ids_dev is NULL and no list was pushed to take it from");
         if (!ids) n = 0;
-        int rc = ensure_scratch(window ? std::max(n, slots[head].n_raw) : n);
+        int rc = ensure_scratch(head_list ? std::max(n, slots[head].n_raw) : n);
         if (rc) return rc;
         if (inverse && !wrank && (rc = dev_alloc(&wrank, n_words))) return rc;
 
@@ -453,9 +455,9 @@ struct CacheT final : gids_cache {
         const IdT* U;
         const uint32_t* n_u;
         uint64_t n_upper;
-        if (ids || !window) {                                 // (an empty list without a window still sets the count)
+        if (ids || !head_list) {                              // (an empty list without a window still sets the count)
             dedup(ids, n, ubuf[par], &ctl->n_unique, nullptr, inverse != nullptr, m);
-            if (window)
+            if (head_list)
                 launch_verify<IdT>(ubuf[par], static_cast<const IdT*>(slots[head].ids), &ctl->win_n[head], ctl,
                                    std::min(n, slots[head].n_raw), m);
             if (inverse) {
@@ -463,7 +465,7 @@ struct CacheT final : gids_cache {
                 launch_clear<IdT>(bitmap, ubuf[par], &ctl->n_unique, n, m);
             }
         }
-        if (window) {                                         // the buffered head list is the minibatch
+        if (head_list) {                                      // the buffered head list is the minibatch
             U = static_cast<const IdT*>(slots[head].ids);
             n_u = &ctl->win_n[head];
             n_upper = slots[head].n_raw;
@@ -475,7 +477,7 @@ struct CacheT final : gids_cache {
         n_upper = std::min<uint64_t>(n_upper, store->n_rows);
         const CacheView<IdT> c = view();
         if ((rc = mark_phase(r, 1, m))) return rc;
-        launch_probe<IdT>(c, U, n_u, n_upper, out_cap, window != 0, plan[par], m);
+        launch_probe<IdT>(c, U, n_u, n_upper, out_cap, head_list, plan[par], m);
         launch_victim<IdT>(c, U, n_u, n_upper, plan[par], m);
         launch_commit<IdT>(c, U, n_u, n_upper, plan[par], hdr + par, m);
         if (threshold == 0) {
@@ -503,7 +505,7 @@ struct CacheT final : gids_cache {
         prof_valid[r] = profile;
         HIP_TRY(hipGetLastError());                           // a kernel launch that was refused
         HIP_TRY(hipEventRecord(events[r], s));
-        if (window) {
+        if (head_list) {
             slots[head].last_reader = (int64_t)seq;
             head = (head + 1) % slots.size();
             count--;

@@ -292,10 +292,13 @@ def test_device_found_errors(gpu, oracle_mod):
             s.stats(seq)
         assert e.value.code == gids.GIDS_E_ORDER
         assert bool((out == 0).all())
-    with fresh(0) as s:
+    with fresh(0) as s:                                         # depth 0 buffers one list, the next gather's
+        s.push(s.to_device([1]))
         with pytest.raises(gids.GidsError) as e:
-            s.push(s.to_device([1]))
-        assert e.value.code == gids.GIDS_E_INVAL
+            s.push(s.to_device([2]))
+        assert e.value.code == gids.GIDS_E_FULL
+        seq = s.gather(None, out)
+        assert s.stats(seq).n_unique == 1
 
 
 @pytest.mark.parametrize("window,ways", [(0, 4), (3, 8), (0, 64), (2, 1)])
@@ -373,3 +376,113 @@ def test_layerwise_id_streams(gpu, oracle_mod):
                  line_bytes=cfg.line_bytes, window=window, hot=hot, label=f"layerwise/W{window}")
         run_case(gpu, oracle_mod, feats, batches, id_dtype=np.int32, lines=cfg.cache_lines, ways=cfg.ways,
                  line_bytes=cfg.line_bytes, window=window, label=f"layerwise/nohot/W{window}", policy=(1, 9))
+
+
+def test_two_caches_share_one_store(gpu, oracle_mod):
+    """Several caches may read one store: two of different shape and policy, calls interleaved on two
+    streams, each equal to its own oracle run."""
+    torch, gids, GatherSession = gpu
+    rng = np.random.default_rng(4242)
+    n, R = 30_000, 512
+    feats = rand_feats(rng, n, R)
+    lists = [zipf_batches(rng, n, 16, 4000, a=1.15) for _ in range(2)]
+    shapes = [dict(lines=2048, ways=8, window=3, policy=None), dict(lines=1024, ways=4, window=0, policy=(1, 5))]
+    want = []
+    for sh, batches in zip(shapes, lists):
+        sim = oracle_mod.Sim(n, sh["lines"], sh["ways"], sh["window"], R, R, feats)
+        if sh["policy"]:
+            sim.set_policy(*sh["policy"])
+        res, pushed = [], 0
+        for t, raw in enumerate(batches):
+            while sh["window"] and pushed < len(batches) and pushed <= t + sh["window"]:
+                sim.push(batches[pushed])
+                pushed += 1
+            res.append(sim.gather(raw))
+        want.append((res, sim))
+    store = gids.gids_store_create(n, R, 8)
+    try:
+        ses = [GatherSession(n, R, np.int64, sh["lines"], sh["ways"], R, sh["window"], store_handle=store)
+               for sh in shapes]
+        ses[0].store_view()[:] = feats
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+        for s, sh in zip(ses, shapes):
+            if sh["policy"]:
+                s.set_policy(*sh["policy"])
+        dev = [[s.to_device(b) for b in batches] for s, batches in zip(ses, lists)]
+        torch.cuda.synchronize()
+        outs = [[], []]
+        pushed = [0, 0]
+        for t in range(16):
+            for k in (0, 1):                                  # alternate between the two caches
+                w = shapes[k]["window"]
+                while w and pushed[k] < 16 and pushed[k] <= t + w:
+                    ses[k].push(dev[k][pushed[k]], stream=streams[k])
+                    pushed[k] += 1
+                cap = len(lists[k][t])
+                out = torch.empty((cap, R), dtype=torch.uint8, device="cuda")
+                uq = torch.empty(cap, dtype=torch.int64, device="cuda")
+                seq = ses[k].gather(None if w else dev[k][t], out, uq, stream=streams[k])
+                outs[k].append((seq, out, uq))
+        torch.cuda.synchronize()
+        for k in (0, 1):
+            res, sim = want[k]
+            for t, (seq, out, uq) in enumerate(outs[k]):
+                u, rows, stats = res[t]
+                assert ses[k].stats(seq).as_tuple() == tuple(int(x) for x in stats), (k, t)
+                assert np.array_equal(uq[:len(u)].cpu().numpy(), u)
+                assert np.array_equal(out[:len(u)].cpu().numpy(), rows), (k, t)
+            tags, stamps = ses[k].snapshot()
+            assert np.array_equal(tags, sim.tags) and np.array_equal(stamps, sim.stamps)
+        for s in ses:
+            s.close()
+    finally:
+        gids.gids_store_destroy(store)
+
+
+@pytest.mark.parametrize("two_streams", [False, True])
+def test_depth_zero_with_lists_pushed_ahead(gpu, oracle_mod, two_streams):
+    """At window depth 0 one list may be pushed before its gather so that its deduplication runs ahead; nothing
+    is pinned, so counters, rows and final tags equal the oracle's depth-0 run (plain LRU), whether a gather
+    takes the pushed list, repeats it as an argument, or comes without a push at all."""
+    torch, gids, GatherSession = gpu
+    rng = np.random.default_rng(606)
+    n, R = 50_000, 1024
+    feats = rand_feats(rng, n, R)
+    batches = zipf_batches(rng, n, 30, 5000, a=1.12)
+    hot = rng.choice(n, 600, replace=False)
+    sim = oracle_mod.Sim(n, 4096, 8, 0, R, R, feats)
+    sim.set_hot(hot)
+    want = [sim.gather(raw) for raw in batches]
+    with GatherSession(n, R, np.int64, 4096, 8, R, 0) as ses:      # 4 MiB cache: single-stream mode ...
+        ses.store_view()[:] = feats
+        ses.pin_hot(hot)
+        check_depth_zero(torch, ses, batches, want, sim, two_streams)
+    sim = oracle_mod.Sim(n, 65536, 8, 0, R, R, feats)
+    sim.set_hot(hot)
+    want = [sim.gather(raw) for raw in batches]
+    with GatherSession(n, R, np.int64, 65536, 8, R, 0) as ses:     # ... 64 MiB: the internal stream is used
+        ses.store_view()[:] = feats
+        ses.pin_hot(hot)
+        check_depth_zero(torch, ses, batches, want, sim, two_streams)
+
+
+def check_depth_zero(torch, ses, batches, want, sim, two_streams):
+    dev = [ses.to_device(b) for b in batches]
+    torch.cuda.synchronize()
+    ps = torch.cuda.Stream() if two_streams else None
+    got = []
+    for t, raw in enumerate(batches):
+        mode = t % 3                                            # 0: push + gather(None), 1: push + gather(ids), 2: no push
+        if mode != 2:
+            ses.push(dev[t], stream=ps)
+        out = torch.full((len(raw), ses.row_bytes), 0x5A, dtype=torch.uint8, device="cuda")
+        uq = torch.empty(len(raw), dtype=torch.int64, device="cuda")
+        got.append((ses.gather(None if mode == 0 else dev[t], out, uq), out, uq))
+    torch.cuda.synchronize()
+    for t, (seq, out, uq) in enumerate(got):
+        u, rows, stats = want[t]
+        assert ses.stats(seq).as_tuple() == tuple(int(x) for x in stats), t
+        assert np.array_equal(uq[:len(u)].cpu().numpy(), u)
+        assert np.array_equal(out[:len(u)].cpu().numpy(), rows), t
+    tags, stamps = ses.snapshot()
+    assert np.array_equal(tags, sim.tags) and np.array_equal(stamps, sim.stamps)
