@@ -22,8 +22,11 @@ def gpu():
 
 
 def run_case(gpu, oracle, feats, batches, *, id_dtype, lines, ways, line_bytes, window, threshold=0, hot=None,
-             use_head=False, with_inverse=False, check_state=True, two_streams=False, policy=None, label=""):
-    """Feeds the same raw ID lists to both implementations, protocol: keep window + 1 lists buffered."""
+             use_head=False, with_inverse=False, check_state=True, two_streams=False, policy=None, label="",
+             pipeline=None, push_depth0=False):
+    """Feeds the same raw ID lists to both implementations, protocol: keep window + 1 lists buffered.
+    pipeline: "0" / "1" forces the library's internal stream off / on for this cache (GIDS_PIPELINE);
+    push_depth0: at window depth 0, push every list just before its gather."""
     torch, gids, GatherSession = gpu
     n_rows = feats.shape[0]
     feats_u8 = np.ascontiguousarray(feats).view(np.uint8).reshape(n_rows, -1)
@@ -42,7 +45,20 @@ def run_case(gpu, oracle, feats, batches, *, id_dtype, lines, ways, line_bytes, 
             sim.push(batches[pushed])
             pushed += 1
         want.append(sim.gather(raw))
-    with GatherSession(n_rows, row_bytes, id_dtype, lines, ways, line_bytes, window, threshold) as ses:
+    import os
+    old_env = os.environ.get("GIDS_PIPELINE")
+    if pipeline is not None:
+        os.environ["GIDS_PIPELINE"] = pipeline               # read when the cache is created
+    try:
+        ses_cm = GatherSession(n_rows, row_bytes, id_dtype, lines, ways, line_bytes, window, threshold)
+    finally:
+        if pipeline is not None:
+            if old_env is None:
+                del os.environ["GIDS_PIPELINE"]
+            else:
+                os.environ["GIDS_PIPELINE"] = old_env
+    buffered = bool(window or push_depth0)
+    with ses_cm as ses:
         ses.store_view()[:] = feats_u8
         if hot is not None and len(hot):
             ses.pin_hot(hot)
@@ -54,14 +70,14 @@ def run_case(gpu, oracle, feats, batches, *, id_dtype, lines, ways, line_bytes, 
         outs, uniqs, invs, seqs = [], [], [], []
         pushed = 0
         for t, raw in enumerate(batches):
-            while window and pushed < len(batches) and pushed <= t + window:
+            while buffered and pushed < len(batches) and pushed <= t + window:
                 ses.push(dev[pushed], stream=push_stream)
                 pushed += 1
             cap = max(len(raw), 1)
             out = torch.full((cap, row_bytes), 0xA5, dtype=torch.uint8, device="cuda")
             uq = torch.full((cap,), -7, dtype=ses.torch_id, device="cuda")
             inv = torch.full((cap,), -1, dtype=torch.int32, device="cuda") if with_inverse else None
-            ids_arg = None if (use_head and window) else dev[t]
+            ids_arg = None if (use_head and buffered) else dev[t]
             seqs.append(ses.gather(ids_arg, out, uq, inv if ids_arg is not None else None))
             outs.append(out); uniqs.append(uq); invs.append(inv if ids_arg is not None else None)
         ses.flush()
@@ -113,8 +129,9 @@ def test_tiny_config_full_parity(gpu, oracle_mod):
              line_bytes=cfg.line_bytes, window=cfg.window, hot=hot, use_head=True, label="tiny/head")
 
 
-@pytest.mark.parametrize("window,use_head", [(4, True), (4, False), (1, True), (12, True)])
-def test_pushes_on_their_own_stream(gpu, oracle_mod, window, use_head):
+@pytest.mark.parametrize("pipeline", ["0", "1"])
+@pytest.mark.parametrize("window,use_head", [(4, True), (4, False), (1, True), (12, True), (0, True)])
+def test_pushes_on_their_own_stream(gpu, oracle_mod, window, use_head, pipeline):
     """The documented way to overlap classification with row movement: window
     pushes on one stream, gathers on another, many minibatches in flight."""
     rng = np.random.default_rng(77 + window)
@@ -122,7 +139,8 @@ def test_pushes_on_their_own_stream(gpu, oracle_mod, window, use_head):
     feats = rand_feats(rng, n, 1024)
     batches = zipf_batches(rng, n, 40, 6000, a=1.12)
     run_case(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=4096, ways=8, line_bytes=1024, window=window,
-             hot=rng.choice(n, 800, replace=False), use_head=use_head, two_streams=True, label=f"2streams/W{window}")
+             hot=rng.choice(n, 800, replace=False), use_head=use_head, two_streams=True, pipeline=pipeline,
+             push_depth0=True, label=f"2streams/W{window}/pipe{pipeline}")
 
 
 def test_two_streams_without_the_internal_stream(gpu, oracle_mod):
@@ -315,7 +333,7 @@ def test_random_base_policy(gpu, oracle_mod, window, ways):
 
 # ------------------------------------------------------------- randomised
 
-@pytest.mark.parametrize("case", range(24))
+@pytest.mark.parametrize("case", range(48))
 def test_random_configurations(gpu, oracle_mod, case):
     """Seeded random geometry, window, accumulator threshold, stream use and
     list shapes (the draw is printed, so a failure names its case)."""
@@ -340,11 +358,18 @@ def test_random_configurations(gpu, oracle_mod, case):
             b = rng.integers(0, n, size=m)
         batches.append(b.astype(np.int64))
     feats = rand_feats(rng, n, row_bytes)
+    # the second half of the cases also draws the stream arrangement inside the library and pushes at depth 0
+    extra = {}
+    if case >= 24:
+        extra = dict(pipeline=str(int(rng.integers(0, 2))), push_depth0=bool(rng.random() < 0.5))
+        if extra["push_depth0"] and window == 0 and rng.random() < 0.5:
+            extra["use_head_override"] = True
+    use_head_override = extra.pop("use_head_override", False)
     run_case(gpu, oracle_mod, feats, batches, id_dtype=id_dtype, lines=ways * n_sets, ways=ways, line_bytes=line_bytes,
              window=window, threshold=threshold, hot=rng.choice(n, n_hot, replace=False) if n_hot else None,
-             use_head=bool(window and rng.random() < 0.5), with_inverse=bool(rng.random() < 0.5),
+             use_head=bool(use_head_override or (window and rng.random() < 0.5)), with_inverse=bool(rng.random() < 0.5),
              two_streams=bool(rng.random() < 0.5), policy=(1, case) if rng.random() < 0.3 else None,
-             label=f"random{case}")
+             label=f"random{case}", **extra)
 
 
 def test_link_calibration_is_sane(gpu):
