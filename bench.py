@@ -95,6 +95,10 @@ def main() -> int:
     ap.add_argument("--sampler-zero-copy", action="store_true",
                     help="with --gpu-sampler: leave the CSR graph in pinned host memory and sample it zero-copy "
                          "(the paper's arrangement) instead of copying it to HBM")
+    ap.add_argument("--consumer-ms", type=float, default=0.0,
+                    help="third pass: a dummy consumer (bf16 matmuls of about this many ms per minibatch, on a "
+                         "stream of its own) reads every gathered minibatch, to show how far the gather for "
+                         "minibatch t + 1 overlaps the consumer of minibatch t (Section 3.2's pipeline)")
     ap.add_argument("--repeat", type=int, default=1,
                     help="run the workload this many times in one process, each with a cache of its own "
                          "(the last run is the one reported; the others are logged)")
@@ -200,7 +204,8 @@ def main() -> int:
     window = cfg.window if args.window < 0 else args.window
     prewarm = args.prewarm if args.prewarm >= 0 else (1_000_000 if args.workload == "resident" else 0)
     n_pre = (cfg.n_nodes + prewarm - 1) // prewarm if prewarm else 0
-    n_batches = n_pre + args.warmup + 2 * args.steps + window + 1      # timed pass + event-timed pass + look-ahead
+    passes = 3 if args.consumer_ms > 0 else 2                           # timed, event-timed (, with a consumer)
+    n_batches = n_pre + args.warmup + passes * args.steps + window + 1  # + look-ahead
     rank_table = wl.synth.zipf_rank_table(cfg.n_nodes, cfg.seed_zipf_s) if cfg.seed_zipf_s is not None else None
     t0 = time.time()
     raws = [np.arange(b * prewarm, min(cfg.n_nodes, (b + 1) * prewarm), dtype=np.int64) for b in range(n_pre)]
@@ -229,7 +234,7 @@ def run_point(args, env, cfg, window, raws, n_pre):
     hot, table, base = env["hot"], env["table"], env["base"]
     R = cfg.row_bytes
     steps, warmup = args.steps, args.warmup + n_pre
-    n_batches = warmup + 2 * steps + window + 1
+    n_batches = warmup + (3 if args.consumer_ms > 0 else 2) * steps + window + 1
     assert len(raws) >= n_batches
     max_raw = max(len(r) for r in raws[:n_batches])
     t0 = time.time()
@@ -265,7 +270,9 @@ def run_point(args, env, cfg, window, raws, n_pre):
 
     # pushes go to their own stream (where a sampler would produce ID lists), gathers to the consumer's:
     # the library then overlaps the classification of minibatch t + 1 with the row movement of minibatch t
-    one_stream = args.one_stream or cfg.cache_lines * cfg.line_bytes < (32 << 20)   # small caches: the library does not overlap
+    # small caches: the library does not overlap (unless GIDS_PIPELINE=1 forces its internal stream on)
+    small = cfg.cache_lines * cfg.line_bytes < (32 << 20) and os.environ.get("GIDS_PIPELINE", "0") == "0"
+    one_stream = args.one_stream or small
     # One push stream for the whole process: HIP multiplexes streams onto a few hardware queues in creation
     # order, and a push stream that lands on the gather stream's queue has its event markers stuck behind the
     # row mover, which serialises the two (seen with the sixth stream created in a sweep).
@@ -353,6 +360,76 @@ def run_point(args, env, cfg, window, raws, n_pre):
                  "hbm_bytes_per_launch": float(mv_hbm),
                  "phase_ms": {"dedup": float(ph[:, 0].mean()), "probe_victim": float(ph[:, 1].mean()), "move": mv_ms}})
 
+    overlap = None
+    if args.consumer_ms > 0:
+        # A stand-in for the training step: matmuls that keep every CU busy, ordered after the gather they
+        # consume; the gather of the next minibatch is free to run beside them.
+        if "consumer_stream" not in env:
+            env["consumer_stream"] = torch.cuda.Stream()
+        cs = env["consumer_stream"]
+        ma = torch.randn(4096, 4096, device="cuda", dtype=torch.bfloat16)
+        mb = torch.randn(4096, 4096, device="cuda", dtype=torch.bfloat16)
+        mc = torch.empty(4096, 4096, device="cuda", dtype=torch.bfloat16)
+        sink = torch.zeros(1, device="cuda", dtype=torch.float32)
+
+        def consume(rows, reps):
+            sink.add_(rows[:256].float().sum())                 # touches the gathered rows
+            for _ in range(reps):
+                torch.mm(ma, mb, out=mc)
+
+        def timed(fn):
+            torch.cuda.synchronize()
+            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a0.record()
+            fn()
+            torch.cuda.current_stream().wait_stream(cs)
+            torch.cuda.current_stream().wait_stream(push_stream)
+            a1.record()
+            torch.cuda.synchronize()
+            return a0.elapsed_time(a1)
+
+        def only_consumer(reps):
+            def run():
+                cs.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(cs):
+                    for k in range(steps):
+                        consume(outs[k % ring], reps)
+            return run
+
+        timed(only_consumer(4))                                 # warm-up (library handles, clocks)
+        per_mm = timed(only_consumer(4)) / (steps * 4)
+        reps = max(1, int(round(args.consumer_ms / per_mm)))
+        cons_ms = timed(only_consumer(reps)) / steps
+        produced = [torch.cuda.Event() for _ in range(ring)]
+        consumed = [torch.cuda.Event() for _ in range(ring)]
+        first = warmup + 2 * steps
+
+        def both():
+            for t in range(first, first + steps):
+                k = t % ring
+                if t >= first + ring:
+                    torch.cuda.current_stream().wait_event(consumed[k])   # the buffer is free again
+                pseq[t] = step(t)
+                produced[k].record()
+                cs.wait_event(produced[k])
+                with torch.cuda.stream(cs):
+                    consume(outs[k], reps)
+                    consumed[k].record()
+            ses.flush()
+
+        gids.gids_profile_enable(ses.cache, True)
+        both_ms = timed(both) / steps
+        gids.gids_profile_enable(ses.cache, False)
+        ph_both = np.array([gids.gids_profile_read(ses.cache, pseq[t]) for t in sorted(pseq)[-min(steps, 60):]])
+        gather_ms = total_ms / steps
+        overlap = {"consumer": f"{reps} bf16 4096^3 matmuls per minibatch on a stream of its own, after a read of the gathered rows",
+                   "consumer_alone_ms": cons_ms, "gather_alone_ms": gather_ms, "both_ms_per_step": both_ms,
+                   "serial_sum_ms": cons_ms + gather_ms, "ideal_overlap_ms": max(cons_ms, gather_ms),
+                   "hidden_fraction_of_the_shorter": (cons_ms + gather_ms - both_ms) / min(cons_ms, gather_ms),
+                   "move_kernel_ms_beside_consumer": float(ph_both[:, 2].mean()), "move_kernel_ms_alone": mv_ms,
+                   "classify_ms_beside_consumer": float(ph_both[:, 1].mean()), "classify_ms_alone": float(ph[:, 1].mean())}
+        log(f"overlap with a consumer: {json.dumps(overlap)}")
+
     result = {
         "metric": "gathered feature GB/s per minibatch (distinct IDs x row bytes / time), steady state",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
@@ -375,6 +452,8 @@ def run_point(args, env, cfg, window, raws, n_pre):
                                                                                 env["link_overhead_s"], 0.0, 0.95),
                              "link_rows_per_step": (n_cpu + n_miss) * scale / steps},
     }
+    if overlap is not None:
+        result["overlap_with_consumer"] = overlap
 
     if sampler is not None:
         # the sampler alone: back-to-back minibatches on one stream, and the oracle's sampler on the host
@@ -407,7 +486,7 @@ def run_point(args, env, cfg, window, raws, n_pre):
     # sampled check of the timed configuration against the definition (row = closed-form feature row)
     if not args.no_check:
         import oracle
-        t_last = warmup + 2 * steps - 1
+        t_last = max(pseq)                                        # the last minibatch gathered
         st = ses.stats(pseq[t_last])
         u = uniq[:st.n_unique].cpu().numpy().astype(np.int64)
         assert np.array_equal(u, np.unique(raws[t_last])), "distinct-ID list differs from sort-unique of the input"

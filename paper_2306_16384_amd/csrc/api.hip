@@ -121,8 +121,7 @@ struct gids_cache {
         return GIDS_OK;
     }
     int move_blocks = 1 << 20;  // most workgroups the row mover uses for rows that stay in HBM
-    int link_blocks = 0;        // ... for rows that cross the host link (persistent); 0 = the kernel decides
-                                // from the bytes the minibatch sends over the link (48, 64 or 96)
+    int link_blocks = 48;       // ... for rows that cross the host link (persistent)
     // optional per-phase timing of each gather (events on the caller's stream)
     bool profile = false;
     hipEvent_t prof_events[STATS_RING][5] = {};   // dedup start, dedup end, metadata end, move start, move end
@@ -489,7 +488,7 @@ struct CacheT final : gids_cache {
             }
             if ((rc = mark_phase(r, 3, s))) return rc;
             launch_move<IdT>(c, U, hdr + par, n_upper, plan[par], static_cast<char*>(out), static_cast<IdT*>(unique),
-                             move_blocks, link_blocks > 0 ? link_blocks : 96, link_blocks == 0, s);
+                             move_blocks, link_blocks, s);
             if ((rc = mark_phase(r, 4, s))) return rc;
         } else {
             if ((rc = mark_phase(r, 2, s))) return rc;

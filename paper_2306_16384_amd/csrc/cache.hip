@@ -232,7 +232,6 @@ __global__ __launch_bounds__(CT_THREADS) void commit_kernel(CacheView<IdT> c, co
         hdr->n_u = n_u;
         hdr->stamp = stamp;
         hdr->next_chunk = 0;
-        hdr->n_link = ctl->cnt_cpu + ctl->cnt_miss;
     }
     if (!ok || ctl->cnt_miss == 0) return;
     for (uint64_t j = (uint64_t)blockIdx.x * CT_THREADS + threadIdx.x; j < n_u; j += (uint64_t)gridDim.x * CT_THREADS) {

@@ -42,7 +42,6 @@ struct BatchHdr {
     uint32_t n_u;           // distinct IDs
     uint32_t stamp;         // minibatch index
     uint32_t next_chunk;    // work counter of the row mover's link half (reset by the commit kernel)
-    uint32_t n_link;        // rows that cross the host link (CPU-buffer hits + misses)
 };
 
 // One queued row move of the accumulator.
@@ -132,8 +131,7 @@ void launch_commit(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n
 
 template <typename IdT>
 void launch_move(const CacheView<IdT>& c, const IdT* unique, BatchHdr* hdr, uint64_t n_upper,
-                 const uint64_t* plan, char* out, IdT* unique_out, int blocks, int link_blocks_max, bool link_auto,
-                 hipStream_t s);
+                 const uint64_t* plan, char* out, IdT* unique_out, int blocks, int link_blocks_max, hipStream_t s);
 
 template <typename IdT>
 void launch_queue(const CacheView<IdT>& c, const IdT* unique, const BatchHdr* hdr, uint64_t n_upper,

@@ -60,9 +60,12 @@ __device__ __forceinline__ uint32_t nth_set_bit(uint64_t mask, uint32_t n) {
 
 // The first `link_blocks` workgroups move the rows that cross the host link
 // (CPU-buffer rows, store rows), the others the rows that stay in HBM (hits).
-// The link is saturated by about a hundred persistent workgroups, and more of
-// them only crowd the memory pipeline for everybody else, while HBM wants
-// thousands of waves; both halves run concurrently.
+// About fifty persistent workgroups (one row in flight per wave) bring the
+// link within half a percent of what a hundred reach; every request beyond
+// what the link can carry only queues in front of the memory traffic of every
+// other kernel on the GPU (the next minibatch's classification, the consumer
+// of the previous one), which a hundred slow down several times over.  HBM
+// wants thousands of waves; both halves run concurrently.
 // A wave reads CH plan entries with one coalesced load, ballots which of them
 // belong to its half, and then moves those rows 64 / G at a time, so scanning
 // past the other half's rows costs one load per CH rows.
@@ -71,8 +74,7 @@ __global__ __launch_bounds__(MV_THREADS) void move_kernel(CacheView<IdT> c, cons
                                                           BatchHdr* __restrict__ hdr,
                                                           const uint64_t* __restrict__ plan, char* __restrict__ out,
                                                           IdT* __restrict__ unique_out, uint32_t link_blocks,
-                                                          uint32_t link_ch, uint32_t hbm_ch, uint32_t link_spread,
-                                                          uint32_t link_auto) {
+                                                          uint32_t link_ch, uint32_t hbm_ch, uint32_t link_spread) {
     if (!hdr->ok) return;
     const uint32_t n_u = hdr->n_u;
     const uint32_t row_u4 = c.row_bytes >> 4;
@@ -80,20 +82,9 @@ __global__ __launch_bounds__(MV_THREADS) void move_kernel(CacheView<IdT> c, cons
     const uint32_t sub = lane % G, grp = lane / G;
     constexpr uint32_t PER_ITER = 64 / G;                     // rows a wave moves at once
     const bool link_role = blockIdx.x < link_blocks;
-    // How many of the launched link workgroups take part.  Requests to host memory queue in front of every
-    // other kernel's memory traffic: about fifty workgroups nearly saturate the link, a hundred gain the last
-    // percent but slow the concurrent metadata kernels of the next minibatch several times over, which only a
-    // long transfer hides.
-    uint32_t link_used = link_blocks;
-    if (link_auto) {
-        const uint64_t bytes = (uint64_t)hdr->n_link * c.row_bytes;
-        const uint32_t want = bytes < (32ull << 20) ? 48u : bytes < (128ull << 20) ? 64u : 96u;
-        link_used = want < link_blocks ? want : link_blocks;
-    }
-    if (link_role && blockIdx.x >= link_used) return;
     uint32_t ch = link_role ? link_ch : hbm_ch;               // plan entries a wave scans per step
     const uint32_t role_block = link_role ? blockIdx.x : blockIdx.x - link_blocks;
-    const uint32_t role_blocks = link_role ? link_used : gridDim.x - link_blocks;
+    const uint32_t role_blocks = link_role ? link_blocks : gridDim.x - link_blocks;
     const uint64_t wave0 = ((uint64_t)role_block * MV_THREADS + threadIdx.x) >> 6;
     const uint64_t n_waves = ((uint64_t)role_blocks * MV_THREADS) >> 6;
     // HBM half: chunk = wave index, strided.  Link half: the persistent waves draw chunks from a counter, so
@@ -330,8 +321,7 @@ inline uint32_t row_grid(uint64_t rows, int g, int blocks) {
 
 template <typename IdT>
 void launch_move(const CacheView<IdT>& c, const IdT* unique, BatchHdr* hdr, uint64_t n_upper,
-                 const uint64_t* plan, char* out, IdT* unique_out, int blocks, int link_blocks_max, bool link_auto,
-                 hipStream_t s) {
+                 const uint64_t* plan, char* out, IdT* unique_out, int blocks, int link_blocks_max, hipStream_t s) {
     const int g = lanes_per_row(c.row_bytes);
     // a wave of the HBM half takes 16 plan entries per step, one of the link half 64
     static const uint32_t hbm_ch = [] {
@@ -356,8 +346,7 @@ void launch_move(const CacheView<IdT>& c, const IdT* unique, BatchHdr* hdr, uint
     while (link_ch > 4 && n_upper / link_ch < (uint64_t)link_blocks_max * (MV_THREADS / 64)) link_ch >>= 1;
     const uint32_t link_blocks = row_grid(n_upper, 64 / (int)link_ch, link_blocks_max);
     GIDS_DISPATCH_G(g, hipLaunchKernelGGL((move_kernel<IdT, G>), dim3(link_blocks + hbm_blocks), dim3(MV_THREADS), 0,
-                                          s, c, unique, hdr, plan, out, unique_out, link_blocks, link_ch, hbm_ch, link_spread,
-                                          link_auto ? 1u : 0u));
+                                          s, c, unique, hdr, plan, out, unique_out, link_blocks, link_ch, hbm_ch, link_spread));
 }
 
 template <typename IdT>
@@ -388,7 +377,7 @@ void launch_flush(const CacheView<IdT>& c, FillOp* fills, CopyOp* copies, uint64
 void launch_calibrate(const char* store, uint64_t store_rows, uint32_t row_bytes, char* out, uint32_t n,
                       hipStream_t s) {
     const int g = lanes_per_row(row_bytes);
-    const uint32_t grid = row_grid(n, g, 96);
+    const uint32_t grid = row_grid(n, g, 48);                 // the row mover's default link half
     GIDS_DISPATCH_G(g, hipLaunchKernelGGL((calibrate_kernel<G>), dim3(grid), dim3(MV_THREADS), 0, s, store, store_rows,
                                           row_bytes, out, n));
 }
@@ -399,7 +388,7 @@ void launch_finalize(Ctl* ctl, StatsRec* rec, uint64_t seq, const uint32_t* n_u,
 
 #define GIDS_INSTANTIATE(IdT)                                                                                       \
     template void launch_move<IdT>(const CacheView<IdT>&, const IdT*, BatchHdr*, uint64_t, const uint64_t*,         \
-                                   char*, IdT*, int, int, bool, hipStream_t);                                       \
+                                   char*, IdT*, int, int, hipStream_t);                                             \
     template void launch_queue<IdT>(const CacheView<IdT>&, const IdT*, const BatchHdr*, uint64_t, const uint64_t*,  \
                                     char*, IdT*, FillOp*, CopyOp*, int, hipStream_t);                               \
     template void launch_flush<IdT>(const CacheView<IdT>&, FillOp*, CopyOp*, uint64_t, bool, int, hipStream_t);
