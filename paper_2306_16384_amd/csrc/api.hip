@@ -122,6 +122,7 @@ struct gids_cache {
     }
     int move_blocks = 1 << 20;  // most workgroups the row mover uses for rows that stay in HBM
     int link_blocks = 48;       // ... for rows that cross the host link (persistent)
+    bool wide_index = false;    // GIDS_WIDE_INDEX=1: 64-bit set arithmetic even where 32 bits would do (for tests)
     // optional per-phase timing of each gather (events on the caller's stream)
     bool profile = false;
     hipEvent_t prof_events[STATS_RING][5] = {};   // dedup start, dedup end, metadata end, move start, move end
@@ -212,7 +213,7 @@ struct CacheT final : gids_cache {
         CacheView<IdT> v;
         v.n_rows = store->n_rows; v.n_sets = n_sets; v.ways = ways; v.lg_ways = lg_ways;
         v.row_bytes = store->row_bytes; v.line_bytes = line_bytes; v.words_per_set = words_per_set;
-        v.use32 = (store->n_rows < (1ull << 32) && n_sets < (1ull << 32)) ? 1u : 0u;
+        v.use32 = (!wide_index && store->n_rows < (1ull << 32) && n_sets < (1ull << 32)) ? 1u : 0u;
         v.policy = policy; v.policy_key = policy_key;
         v.tags = tags; v.stamps = stamps; v.pending = pending; v.reuse = reuse; v.missmask = missmask;
         v.hotbits = n_hot ? hotbits : nullptr; v.hotrank = hotrank;
@@ -262,6 +263,7 @@ struct CacheT final : gids_cache {
         // one slot more than lists can be buffered: the slot a push overwrites was then read by the gather
         // before the previous one, whose rows have long moved, and not by the one still moving
         slots.resize(window + 2);
+        if (const char* env = getenv("GIDS_WIDE_INDEX")) wide_index = atoi(env) != 0;
         if (const char* env = getenv("GIDS_MOVE_BLOCKS")) {
             const int b = atoi(env);
             if (b >= 1 && b <= (1 << 20)) move_blocks = b;

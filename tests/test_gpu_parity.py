@@ -23,7 +23,7 @@ def gpu():
 
 def run_case(gpu, oracle, feats, batches, *, id_dtype, lines, ways, line_bytes, window, threshold=0, hot=None,
              use_head=False, with_inverse=False, check_state=True, two_streams=False, policy=None, label="",
-             pipeline=None, push_depth0=False):
+             pipeline=None, push_depth0=False, wide_index=False):
     """Feeds the same raw ID lists to both implementations, protocol: keep window + 1 lists buffered.
     pipeline: "0" / "1" forces the library's internal stream off / on for this cache (GIDS_PIPELINE);
     push_depth0: at window depth 0, push every list just before its gather."""
@@ -46,17 +46,21 @@ def run_case(gpu, oracle, feats, batches, *, id_dtype, lines, ways, line_bytes, 
             pushed += 1
         want.append(sim.gather(raw))
     import os
-    old_env = os.environ.get("GIDS_PIPELINE")
+    knobs = {}                                               # environment knobs are read when the cache is created
     if pipeline is not None:
-        os.environ["GIDS_PIPELINE"] = pipeline               # read when the cache is created
+        knobs["GIDS_PIPELINE"] = pipeline
+    if wide_index:
+        knobs["GIDS_WIDE_INDEX"] = "1"                       # the arithmetic of stores with 2^32 rows and more
+    old_env = {k: os.environ.get(k) for k in knobs}
+    os.environ.update(knobs)
     try:
         ses_cm = GatherSession(n_rows, row_bytes, id_dtype, lines, ways, line_bytes, window, threshold)
     finally:
-        if pipeline is not None:
-            if old_env is None:
-                del os.environ["GIDS_PIPELINE"]
+        for k, v in old_env.items():
+            if v is None:
+                del os.environ[k]
             else:
-                os.environ["GIDS_PIPELINE"] = old_env
+                os.environ[k] = v
     buffered = bool(window or push_depth0)
     with ses_cm as ses:
         ses.store_view()[:] = feats_u8
@@ -361,7 +365,8 @@ def test_random_configurations(gpu, oracle_mod, case):
     # the second half of the cases also draws the stream arrangement inside the library and pushes at depth 0
     extra = {}
     if case >= 24:
-        extra = dict(pipeline=str(int(rng.integers(0, 2))), push_depth0=bool(rng.random() < 0.5))
+        extra = dict(pipeline=str(int(rng.integers(0, 2))), push_depth0=bool(rng.random() < 0.5),
+                     wide_index=bool(rng.random() < 0.5))
         if extra["push_depth0"] and window == 0 and rng.random() < 0.5:
             extra["use_head_override"] = True
     use_head_override = extra.pop("use_head_override", False)
