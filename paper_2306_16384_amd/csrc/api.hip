@@ -396,9 +396,11 @@ struct CacheT final : gids_cache {
     void dedup(const IdT* ids, uint64_t n, IdT* dst, uint32_t* n_out, uint8_t* reuse_inc, bool keep_bitmap,
                hipStream_t s, const uint32_t* n_dev = nullptr) {
         launch_mark<IdT>(ids, n, n_dev, store->n_rows, bitmap, ctl, s);
-        launch_count(bitmap, n_words, blocksum, blockoff, ctl, n_out, s);
+        // a bitmap that one block scans needs no separate count: that block's total is the distinct count
+        const bool solo = scan_blocks(n_words) == 1;
+        if (!solo) launch_count(bitmap, n_words, blocksum, blockoff, ctl, n_out, s);
         launch_emit<IdT>(bitmap, n_words, store->n_rows, blockoff, dst, reuse_inc, keep_bitmap ? wrank : nullptr,
-                         !keep_bitmap, ctl, s);
+                         !keep_bitmap, ctl, solo ? n_out : nullptr, s);
     }
 
     int push(const void* ids, uint64_t n, const uint32_t* n_dev, hipStream_t s) override {
@@ -621,7 +623,8 @@ struct gids_graph {
             // frontier = ascending distinct IDs of the previous hop's output
             launch_mark<IdT>(hop_in, in_upper, in_count, n_nodes, bitmap, ctl, s);
             launch_count(bitmap, n_words, blocksum, blockoff, ctl, &ctl->n_unique, s);
-            launch_emit<IdT>(bitmap, n_words, n_nodes, blockoff, static_cast<IdT*>(frontier), nullptr, nullptr, true, ctl, s);
+            launch_emit<IdT>(bitmap, n_words, n_nodes, blockoff, static_cast<IdT*>(frontier), nullptr, nullptr, true, ctl,
+                             nullptr, s);
             const uint64_t kl = sampler_mix(sampler_mix(sampler_key(seed, 5) ^ batch) ^ (uint64_t)l);
             launch_hop<IdT>(static_cast<const IdT*>(frontier), &ctl->n_unique, front, indptr,
                             static_cast<const IdT*>(indices), fanouts[l], kl, hop_blocksum, hop_blockoff, raw,

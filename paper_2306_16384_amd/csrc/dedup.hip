@@ -116,11 +116,13 @@ __global__ __launch_bounds__(DD_THREADS) void count_kernel(const uint64_t* __res
     }
 }
 
+// n_out_solo != nullptr: the bitmap fits one block, no count kernel ran; this block's total is the distinct count.
 template <typename IdT>
 __global__ __launch_bounds__(DD_THREADS) void emit_kernel(uint64_t* __restrict__ bitmap, uint64_t n_words,
                                                           const uint32_t* __restrict__ blockoff,
                                                           IdT* __restrict__ dst, uint8_t* __restrict__ reuse_inc,
-                                                          uint32_t* __restrict__ wrank, int clear, const Ctl* ctl) {
+                                                          uint32_t* __restrict__ wrank, int clear, const Ctl* ctl,
+                                                          uint32_t* __restrict__ n_out_solo) {
     __shared__ uint32_t smem[8];
     const bool ok = ctl->error == 0;
     const uint64_t w0 = (uint64_t)blockIdx.x * WORDS_PER_BLOCK + (uint64_t)threadIdx.x * WORDS_PER_THREAD;
@@ -132,19 +134,43 @@ __global__ __launch_bounds__(DD_THREADS) void emit_kernel(uint64_t* __restrict__
         c += __popcll(w[k]);
     }
     uint32_t total;
-    uint32_t pos = blockoff[blockIdx.x] + block_exclusive_scan(c, &total, smem);
+    uint32_t pos = block_exclusive_scan(c, &total, smem);
+    if (n_out_solo) {
+        if (threadIdx.x == 0) *n_out_solo = total;
+    } else {
+        pos += blockoff[blockIdx.x];
+    }
 #pragma unroll
     for (int k = 0; k < WORDS_PER_THREAD; k++) {
         uint64_t x = w[k];
         if (!x) continue;
         if (wrank) wrank[w0 + k] = pos;
         if (ok) {
+            // four set bits at a time: their counter updates are independent (the IDs are distinct, no two
+            // threads share a byte), so the four loads go out together instead of one round trip per ID
             while (x) {
-                const int b = __ffsll((unsigned long long)x) - 1;
-                x &= x - 1;
-                const uint64_t v = (w0 + k) * 64 + (uint64_t)b;
-                dst[pos++] = (IdT)v;
-                if (reuse_inc) reuse_inc[v] = (uint8_t)(reuse_inc[v] + 1);   // IDs are distinct: no two threads share a byte
+                uint64_t v[4];
+                uint8_t r[4];
+                int m = 0;
+#pragma unroll
+                for (int u = 0; u < 4; u++) {
+                    if (x) {
+                        v[u] = (w0 + k) * 64 + (uint64_t)(__ffsll((unsigned long long)x) - 1);
+                        x &= x - 1;
+                        m = u + 1;
+                    }
+                }
+                if (reuse_inc) {
+#pragma unroll
+                    for (int u = 0; u < 4; u++)
+                        if (u < m) r[u] = reuse_inc[v[u]];
+#pragma unroll
+                    for (int u = 0; u < 4; u++)
+                        if (u < m) reuse_inc[v[u]] = (uint8_t)(r[u] + 1);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; u++)
+                    if (u < m) dst[pos++] = (IdT)v[u];
             }
         }
         if (clear) bitmap[w0 + k] = 0ull;
@@ -217,9 +243,9 @@ void launch_count(const uint64_t* bitmap, uint64_t n_words, uint32_t* blocksum, 
 
 template <typename IdT>
 void launch_emit(uint64_t* bitmap, uint64_t n_words, uint64_t, const uint32_t* blockoff, IdT* dst,
-                 uint8_t* reuse_inc, uint32_t* wrank, bool clear, Ctl* ctl, hipStream_t s) {
+                 uint8_t* reuse_inc, uint32_t* wrank, bool clear, Ctl* ctl, uint32_t* n_out_solo, hipStream_t s) {
     hipLaunchKernelGGL(emit_kernel<IdT>, dim3(scan_blocks(n_words)), dim3(DD_THREADS), 0, s, bitmap, n_words,
-                       blockoff, dst, reuse_inc, wrank, clear ? 1 : 0, ctl);
+                       blockoff, dst, reuse_inc, wrank, clear ? 1 : 0, ctl, n_out_solo);
 }
 
 template <typename IdT>
@@ -255,7 +281,7 @@ void launch_fill_i64(int64_t* p, uint64_t n, int64_t value, hipStream_t s) {
 #define GIDS_INSTANTIATE(IdT)                                                                                      \
     template void launch_mark<IdT>(const IdT*, uint64_t, const uint32_t*, uint64_t, uint64_t*, Ctl*, hipStream_t); \
     template void launch_emit<IdT>(uint64_t*, uint64_t, uint64_t, const uint32_t*, IdT*, uint8_t*, uint32_t*, bool, \
-                                   Ctl*, hipStream_t);                                                             \
+                                   Ctl*, uint32_t*, hipStream_t);                                                  \
     template void launch_verify<IdT>(const IdT*, const IdT*, const uint32_t*, Ctl*, uint64_t, hipStream_t);        \
     template void launch_inverse<IdT>(const IdT*, uint64_t, const uint64_t*, const uint32_t*, uint32_t*, Ctl*,     \
                                       hipStream_t);                                                                \

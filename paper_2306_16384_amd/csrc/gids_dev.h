@@ -104,7 +104,7 @@ void launch_count(const uint64_t* bitmap, uint64_t n_words, uint32_t* blocksum, 
 
 template <typename IdT>
 void launch_emit(uint64_t* bitmap, uint64_t n_words, uint64_t n_rows, const uint32_t* blockoff, IdT* dst,
-                 uint8_t* reuse_inc, uint32_t* wrank, bool clear, Ctl* ctl, hipStream_t s);
+                 uint8_t* reuse_inc, uint32_t* wrank, bool clear, Ctl* ctl, uint32_t* n_out_solo, hipStream_t s);
 
 template <typename IdT>
 void launch_verify(const IdT* fresh, const IdT* head, const uint32_t* head_n, Ctl* ctl, uint64_t n_upper,
