@@ -177,3 +177,11 @@ def test_layerwise_minibatch_has_fixed_layers_drawn_by_connection_count():
     assert hi > lo + 0.2, (lo, hi)
     # weight-proportional race: P(keep) for multiplicity 1 is below the uniform share, above it for >= 3
     assert lo < 0.25 < hi
+
+
+def test_frozen_degree_scale_is_what_the_bisection_gives():
+    """workload/configs.py freezes `ell`; workload/calibrate.py is the script that solves it."""
+    from workload import calibrate
+    for name in ("tiny", "medium"):
+        cfg = CONFIGS[name]
+        assert abs(calibrate.solve(name) - cfg.ell) < 1e-9 * cfg.ell
