@@ -43,6 +43,15 @@ int fail(int code, const char* fmt, ...) {
 
 constexpr int STATS_RING = 64;
 
+bool on_device(int device) {
+    int cur = -1;
+    if (hipGetDevice(&cur) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return cur == device;
+}
+
 template <typename T>
 int dev_alloc(T** p, uint64_t count) {
     *p = nullptr;
@@ -65,6 +74,7 @@ struct gids_store {
     void* host = nullptr;   // host address of the table
     void* dev = nullptr;    // the same memory as the GPU sees it
     bool owned = false;
+    int device = 0;         // the device that was current when the store was created
 };
 
 struct WindowSlot {
@@ -655,6 +665,11 @@ int gids_store_create(uint64_t n_rows, uint32_t row_bytes, uint32_t id_bytes, vo
     gids_store* st = new (std::nothrow) gids_store();
     if (!st) return fail(GIDS_E_NOMEM, "gids_store_create: out of host memory");
     st->n_rows = n_rows; st->row_bytes = row_bytes; st->id_bytes = id_bytes;
+    if (hipGetDevice(&st->device) != hipSuccess) {
+        (void)hipGetLastError();
+        delete st;
+        return fail(GIDS_E_HIP, "gids_store_create: no current device");
+    }
     if (host_ptr_or_null) {
         st->host = host_ptr_or_null;
         hipError_t e = hipHostGetDevicePointer(&st->dev, host_ptr_or_null, 0);
@@ -731,6 +746,7 @@ int gids_cache_create(gids_store* store, uint64_t lines, uint32_t ways, uint32_t
     if (!out) return fail(GIDS_E_INVAL, "gids_cache_create: out is NULL");
     *out = nullptr;
     if (!store) return fail(GIDS_E_INVAL, "gids_cache_create: store is NULL");
+    if (!on_device(store->device)) return fail(GIDS_E_INVAL, "gids_cache_create: the current device is not the one the store was created on");
     if (ways == 0 || ways > 64 || (ways & (ways - 1))) return fail(GIDS_E_INVAL, "gids_cache_create: ways must be a power of two in [1, 64]");
     if (lines == 0 || lines % ways) return fail(GIDS_E_INVAL, "gids_cache_create: lines must be a positive multiple of ways");
     if (line_bytes < store->row_bytes || line_bytes % 16) return fail(GIDS_E_INVAL, "gids_cache_create: line_bytes must be a multiple of 16 and >= row_bytes");
@@ -756,6 +772,7 @@ int gids_cache_destroy(gids_cache* cache) {
 
 #define CHECK_CACHE(c)                                                         \
     if (!(c)) return fail(GIDS_E_INVAL, "%s: cache is NULL", __func__);        \
+    if (!on_device((c)->store->device)) return fail(GIDS_E_INVAL, "%s: the current device is not the one the store was created on", __func__); \
     if ((c)->sticky) return fail((c)->sticky, "%s: an earlier operation on this cache failed on the device (%d)", __func__, (c)->sticky)
 
 int gids_cache_reserve(gids_cache* cache, uint64_t max_ids) {
