@@ -356,6 +356,8 @@ typedef struct {
     const char* store; char* cache_data; char* cpu_buf;
     /* base replacement policy: 0 = least recently used by minibatch, 1 = seeded random (BaM's policy, Section 3.4) */
     int32_t policy; uint64_t policy_seed;
+    /* node rows per cache line (1 unless go_sim_set_rows_per_line): line `b` of the store = rows b*P .. b*P+P-1 */
+    int64_t rows_per_line;
 } go_sim;
 
 void go_sim_free(go_sim* s) {
@@ -387,7 +389,20 @@ go_sim* go_sim_create(int64_t n_rows, int64_t lines, int32_t ways, int32_t windo
     }
     for (int64_t i = 0; i < lines; i++) { s->tag[i] = -1; s->stamp[i] = -1; }
     for (int64_t v = 0; v < n_rows; v++) s->hot_slot[v] = -1;
+    s->rows_per_line = 1;
     return s;
+}
+
+/* Cache lines that hold several node rows: the cache the paper builds on keeps the storage's cache-lines
+ * (4 KB in the example of Section 3.3) while a node's feature row is 512 B to 4 KB (Section 2.1), so with
+ * small rows one line holds P consecutive rows and a miss brings all of them in.  The tag of a line is then
+ * the store line number b = id div P, its set b mod n_sets; a line is pinned while any of its rows has a
+ * buffered future use.  Before the first push or gather. */
+int go_sim_set_rows_per_line(go_sim* s, int64_t rows) {
+    if (s->t || s->win_count || rows < 1) return GO_E_INVAL;
+    if (s->store && rows * s->row_bytes > s->line_bytes) return GO_E_INVAL;
+    s->rows_per_line = rows;
+    return GO_OK;
 }
 
 /* Section 3.3: pin the rows of `ids` in the constant CPU buffer (slot = position in the list) */
@@ -465,6 +480,7 @@ int64_t go_sim_gather(go_sim* s, const int64_t* raw, int64_t n, int64_t* unique_
     if (!ids_in_range(s, raw, n)) return GO_E_RANGE;
     int64_t m = go_sort_unique(raw, n, unique_out);
     const int64_t t = s->t;
+    const int64_t P = s->rows_per_line;
 
     /* window: the buffered head must be this minibatch; drop it and take back
      * its reuse counts (a reuse consumes one count) */
@@ -489,23 +505,24 @@ int64_t go_sim_gather(go_sim* s, const int64_t* raw, int64_t n, int64_t* unique_
         int64_t v = unique_out[j];
         src_line[j] = -1;
         if (s->hot_slot[v] >= 0) { cls[j] = GO_CLS_CPU; cpu_hits++; continue; }
-        int64_t set = v % s->n_sets;
+        int64_t blk = v / P;                                 /* the store line that holds the row */
+        int64_t set = blk % s->n_sets;
         int32_t way = -1;
-        for (int32_t w = 0; w < s->ways; w++) if (s->tag[set * s->ways + w] == v) way = w;
+        for (int32_t w = 0; w < s->ways; w++) if (s->tag[set * s->ways + w] == blk) way = w;
         if (way >= 0) {
             cls[j] = GO_CLS_HIT; hits++;
             s->stamp[set * s->ways + way] = t;
             src_line[j] = set * s->ways + way;
         } else {
             cls[j] = GO_CLS_MISS;
-            miss[misses].set = set; miss[misses].id = v; miss[misses].j = j; misses++;
+            miss[misses].set = set; miss[misses].id = blk; miss[misses].j = j; misses++;
         }
     }
 
-    /* install, set by set: the k-th miss (ascending ID) takes the k-th
-     * evictable way in (stamp, way) order; a way is evictable when it was not
-     * touched in this minibatch and is empty or holds a node no buffered
-     * future minibatch reuses; misses beyond that bypass the cache */
+    /* install, set by set: the k-th missing line (ascending; with one row per line that is the k-th missing
+     * ID) takes the k-th evictable way in (stamp, way) order; a way is evictable when it was not touched in
+     * this minibatch and is empty or holds no row that a buffered future minibatch reuses; misses beyond that
+     * bypass the cache.  Every requested row of a missing line counts as a miss of its own. */
     qsort(miss, (size_t)misses, sizeof(miss_rec), cmp_miss);
     for (int64_t a = 0; a < misses;) {
         int64_t b = a;
@@ -515,7 +532,12 @@ int64_t go_sim_gather(go_sim* s, const int64_t* raw, int64_t n, int64_t* unique_
         for (int32_t w = 0; w < s->ways; w++) {
             int64_t line = set * s->ways + w;
             if (s->stamp[line] == t) continue;
-            if (s->tag[line] != -1 && s->reuse[s->tag[line]] != 0) continue;
+            if (s->tag[line] != -1) {
+                int pinned = 0;
+                for (int64_t r = s->tag[line] * P; r < (s->tag[line] + 1) * P && r < s->n_rows; r++)
+                    if (s->reuse[r] != 0) pinned = 1;
+                if (pinned) continue;
+            }
             if (s->policy == 1 && s->tag[line] != -1) {
                 /* random order among occupied ways: a 55-bit hash, never negative, sorts after every empty way (-1) */
                 uint64_t k = mix64(mix64(mix64(key0(s->policy_seed, 8) ^ (uint64_t)t) ^ (uint64_t)set) ^ (uint64_t)w);
@@ -526,9 +548,11 @@ int64_t go_sim_gather(go_sim* s, const int64_t* raw, int64_t n, int64_t* unique_
             vict[n_vict].way = w; n_vict++;
         }
         qsort(vict, (size_t)n_vict, sizeof(victim_rec), cmp_victim);
+        int64_t rank = -1, prev = -1;                        /* rank of the current line among the set's missing lines */
         for (int64_t k = a; k < b; k++) {
-            if (k - a < n_vict) {
-                int64_t line = set * s->ways + vict[k - a].way;
+            if (miss[k].id != prev) { rank++; prev = miss[k].id; }
+            if (rank < n_vict) {
+                int64_t line = set * s->ways + vict[rank].way;
                 s->tag[line] = miss[k].id; s->stamp[line] = t;
                 src_line[miss[k].j] = line;
             } else {
@@ -543,16 +567,19 @@ int64_t go_sim_gather(go_sim* s, const int64_t* raw, int64_t n, int64_t* unique_
      * row to the output */
     if (s->store) {
         for (int64_t j = 0; j < m; j++)
-            if (cls[j] == GO_CLS_MISS)
+            if (cls[j] == GO_CLS_MISS) {                     /* the whole store line (clipped at the table's end) */
+                int64_t first = unique_out[j] / P * P;
+                int64_t rows = first + P <= s->n_rows ? P : s->n_rows - first;
                 memcpy(s->cache_data + (size_t)src_line[j] * s->line_bytes,
-                       s->store + (size_t)unique_out[j] * s->row_bytes, (size_t)s->row_bytes);
+                       s->store + (size_t)first * s->row_bytes, (size_t)(rows * s->row_bytes));
+            }
     }
     if (s->store && out_rows) {
         for (int64_t j = 0; j < m; j++) {
             const char* src;
             if (cls[j] == GO_CLS_CPU) src = s->cpu_buf + (size_t)s->hot_slot[unique_out[j]] * s->row_bytes;
             else if (cls[j] == GO_CLS_BYPASS) src = s->store + (size_t)unique_out[j] * s->row_bytes;
-            else src = s->cache_data + (size_t)src_line[j] * s->line_bytes;
+            else src = s->cache_data + (size_t)src_line[j] * s->line_bytes + (size_t)(unique_out[j] % P) * s->row_bytes;
             memcpy((char*)out_rows + (size_t)j * s->row_bytes, src, (size_t)s->row_bytes);
         }
     }

@@ -68,6 +68,7 @@ def lib() -> C.CDLL:
         L.go_sim_free.argtypes = [C.c_void_p]
         L.go_sim_set_hot.argtypes = [C.c_void_p, _i64p, C.c_int64]
         L.go_sim_set_policy.argtypes = [C.c_void_p, C.c_int32, C.c_uint64]
+        L.go_sim_set_rows_per_line.argtypes = [C.c_void_p, C.c_int64]
         L.go_sim_push.argtypes = [C.c_void_p, _i64p, C.c_int64]
         L.go_sim_gather.restype = C.c_int64
         L.go_sim_gather.argtypes = [C.c_void_p, _i64p, C.c_int64, _i64p, C.c_void_p, _i64p, C.c_void_p]
@@ -205,6 +206,12 @@ class Sim:
     def set_policy(self, policy: int, seed: int = 0) -> None:
         """0 = LRU by minibatch (default), 1 = seeded random eviction"""
         rc = lib().go_sim_set_policy(self._h, policy, seed)
+        if rc:
+            raise OracleError(rc)
+
+    def set_rows_per_line(self, rows: int) -> None:
+        """cache lines hold `rows` consecutive node rows (default 1)"""
+        rc = lib().go_sim_set_rows_per_line(self._h, rows)
         if rc:
             raise OracleError(rc)
 

@@ -562,3 +562,88 @@ def test_reverse_pagerank_against_closed_forms_and_a_linear_solve(oracle_mod):
     assert np.allclose(g.reverse_pagerank(d16, 3) / total, x, rtol=1e-7)
     # no damping mass: the uniform start stays
     assert len(set(g.reverse_pagerank(0, 5).tolist())) == 1
+
+
+# ------------------------------------------------ several rows per cache line
+
+def _drive(sim, lists, window, want_rows=False):
+    """window protocol: keep window + 1 lists buffered; returns per-minibatch (unique, rows, stats, classes)"""
+    res, pushed = [], 0
+    for t, raw in enumerate(lists):
+        while window and pushed < len(lists) and pushed <= t + window:
+            sim.push(lists[pushed])
+            pushed += 1
+        res.append(sim.gather(raw, want_rows=want_rows, want_cls=True))
+    return res
+
+
+@pytest.mark.parametrize("P,window,policy", [(2, 0, None), (8, 3, None), (4, 2, (1, 77)), (8, 0, (1, 5)), (3, 4, None)])
+def test_rows_per_line_reduces_to_one_row_per_line_over_line_numbers(oracle_mod, P, window, policy):
+    """With P rows per line the cache works on store-line numbers b = id div P: its tags and stamps must be those
+    of the (already pinned) one-row-per-line simulator fed the distinct line numbers of every list, and every
+    requested row must have the class its line has there."""
+    rng = np.random.default_rng(1000 + P)
+    n, ways, n_sets = 1003, 4, 11                              # the last line of the table is partial
+    lists = [np.minimum(rng.zipf(1.15, size=int(rng.integers(1, 400))) - 1, n - 1) for _ in range(40)]
+    sim = oracle_mod.Sim(n, ways * n_sets, ways, window)
+    sim.set_rows_per_line(P)
+    ref = oracle_mod.Sim((n + P - 1) // P, ways * n_sets, ways, window)
+    if policy:
+        sim.set_policy(*policy)
+        ref.set_policy(*policy)
+    got = _drive(sim, lists, window)
+    want = _drive(ref, [np.unique(np.asarray(l) // P) for l in lists], window)
+    for t, ((u, _, stats, cls), (ub, _, _, clsb)) in enumerate(zip(got, want)):
+        line_class = dict(zip(ub.tolist(), clsb.tolist()))
+        expect = np.array([line_class[int(v) // P] for v in u])
+        assert np.array_equal(cls, expect), t
+        assert stats.tolist() == [len(u), int((expect == 0).sum()), 0, int((expect >= 2).sum()), int((expect == 3).sum())]
+    assert np.array_equal(sim.tags, ref.tags) and np.array_equal(sim.stamps, ref.stamps)
+
+
+def test_rows_per_line_brings_the_neighbours_in_and_moves_the_right_bytes(oracle_mod):
+    rng = np.random.default_rng(8)
+    n, R, P = 77, 48, 4                                         # 20 lines, the last holds one row
+    store = rng.integers(0, 256, size=(n, R), dtype=np.uint8)
+    sim = oracle_mod.Sim(n, 8, 2, 0, R, P * R + 16, store)
+    sim.set_rows_per_line(P)
+    u, rows, stats = sim.gather([5, 76])                        # lines 1 and 19 come in
+    assert stats.tolist() == [2, 0, 0, 2, 0] and np.array_equal(rows, store[[5, 76]])
+    u, rows, stats = sim.gather([4, 6, 7, 76, 9])               # rows 4, 6, 7 were never asked for: hits all the same
+    assert stats.tolist() == [5, 4, 0, 1, 0] and np.array_equal(rows, store[[4, 6, 7, 9, 76]])
+    # two rows of one missing line in one minibatch: two misses, one line
+    u, rows, stats = sim.gather([40, 41, 43])
+    assert stats.tolist() == [3, 0, 0, 3, 0] and sorted(t for t in sim.tags.tolist() if t >= 0) == [1, 2, 10, 19]
+    # random traffic with a CPU buffer and a window: every gathered row is the store's row
+    sim = oracle_mod.Sim(n, 8, 2, 2, R, P * R, store)
+    sim.set_rows_per_line(P)
+    sim.set_hot([3, 40, 41])
+    lists = [rng.integers(0, n, size=int(rng.integers(1, 60))) for _ in range(30)]
+    for (u, rows, stats, cls), raw in zip(_drive(sim, lists, 2, want_rows=True), lists):
+        assert np.array_equal(u, np.unique(raw)) and np.array_equal(rows, store[u])
+        assert stats[1] + stats[2] + stats[3] == stats[0]
+        assert stats[2] == len(set(u.tolist()) & {3, 40, 41})
+    # a cache with a line for every store line: one row of each line, then nothing misses any more
+    sim = oracle_mod.Sim(n, 20, 4, 0)
+    sim.set_rows_per_line(P)
+    sim.gather(np.arange(0, n, P))
+    u, _, stats = sim.gather(np.arange(n), want_rows=False)
+    assert stats.tolist() == [n, n, 0, 0, 0]
+    # the setting belongs before the first minibatch and must fit the line
+    with pytest.raises(oracle_mod.OracleError):
+        sim.set_rows_per_line(2)
+    with pytest.raises(oracle_mod.OracleError):
+        oracle_mod.Sim(n, 8, 2, 0, R, 2 * R, store).set_rows_per_line(3)
+
+
+def test_rows_per_line_pins_a_line_while_any_of_its_rows_is_needed(oracle_mod):
+    """One set of two ways, lines of two rows: line 0 is needed again two minibatches later through its *other*
+    row, so the window keeps it and the plain LRU does not."""
+    lists = [[0], [2], [4], [1]]                                # lines 0, 1, 2, then line 0 again via row 1
+    for window, last in ((0, [1, 0, 0, 1, 0]), (3, [1, 1, 0, 0, 0])):
+        sim = oracle_mod.Sim(64, 2, 2, window)
+        sim.set_rows_per_line(2)
+        res = _drive(sim, lists, window)
+        assert res[3][2].tolist() == last, window
+        if window:                                              # line 2 took the way of line 1, which nothing needs again
+            assert res[2][2].tolist() == [1, 0, 0, 1, 0]
