@@ -72,6 +72,12 @@ def main() -> int:
     ap.add_argument("--layerwise", default="", metavar="S1,S2,..",
                     help="feed layer-wise sampled ID lists (the second sampler shape of Section 4.7): a fixed number "
                          "of nodes per layer, drawn by connection count, instead of neighbourhood sampling")
+    ap.add_argument("--dim", type=int, default=0,
+                    help="override the feature dimension (row bytes = dim x item size; lines shrink to the row, the "
+                         "cache keeps its size in bytes), e.g. 256 for the 512 B rows of the paper's smaller datasets")
+    ap.add_argument("--rows-per-line", type=int, default=1,
+                    help="cache lines that hold this many consecutive node rows (line_bytes = rows x row_bytes, the "
+                         "cache keeps its size in bytes): a miss brings the whole line in")
     ap.add_argument("--cache-lines", type=int, default=0, help="override the number of cache lines (rounded to ways)")
     ap.add_argument("--accum", type=int, default=0, help="accumulator threshold (0 = every gather moves its own rows)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="time budget of the oracle leg")
@@ -132,7 +138,15 @@ def main() -> int:
     wl.native.build()
 
     base = wl.CONFIGS[args.workload]
-    cfg = wl.scaled(base, args.nodes) if args.nodes else pick_scale(base, wl, args.max_pinned_gib)
+    def with_dim(c):
+        if not args.dim:
+            return c
+        from dataclasses import replace
+        new_r = args.dim * np.dtype(c.feat_dtype).itemsize
+        return replace(c, dim=args.dim, line_bytes=new_r,
+                       cache_lines=max(c.ways, c.cache_lines * c.line_bytes // new_r // c.ways * c.ways))
+
+    cfg = with_dim(wl.scaled(base, args.nodes) if args.nodes else pick_scale(base, wl, args.max_pinned_gib))
     # pin the store first: a box that grants less pinned memory than assumed runs at half the node count, and so on
     while True:
         try:
@@ -142,10 +156,15 @@ def main() -> int:
             if e.code != gids.GIDS_E_NOMEM or cfg.n_nodes < 100_000:
                 raise
             log(f"cannot pin {cfg.n_nodes * cfg.row_bytes / 1e9:.1f} GB of host memory; halving the node count")
-            cfg = wl.scaled(base, cfg.n_nodes // 2)
+            cfg = with_dim(wl.scaled(base, cfg.n_nodes // 2))
     if args.cache_lines:
         from dataclasses import replace
         cfg = replace(cfg, cache_lines=max(cfg.ways, args.cache_lines // cfg.ways * cfg.ways))
+    if args.rows_per_line > 1:
+        from dataclasses import replace
+        P = args.rows_per_line
+        cfg = replace(cfg, line_bytes=P * cfg.row_bytes,
+                      cache_lines=max(cfg.ways, cfg.cache_lines * cfg.line_bytes // (P * cfg.row_bytes) // cfg.ways * cfg.ways))
     R = cfg.row_bytes
     rate, overhead = gids.gids_store_calibrate(store)
     log(f"link calibration: {rate * R / 1e9:.1f} GB/s ({rate / 1e6:.1f} M rows/s), overhead {overhead * 1e6:.1f} us; "
@@ -244,6 +263,8 @@ def run_point(args, env, cfg, window, raws, n_pre):
     ses.reserve(max_raw)
     if args.policy == "random":
         ses.set_policy(gids.GIDS_POLICY_RANDOM, cfg.seed)
+    if args.rows_per_line > 1:
+        ses.set_rows_per_line(args.rows_per_line)
     log(f"cache W={window}: created, CPU buffer {len(hot) * R / 1e9:.2f} GB pinned ({time.time() - t0:.1f} s)")
     dev = [ses.to_device(r) for r in raws[:n_batches]]
     sampler = None
@@ -329,8 +350,19 @@ def run_point(args, env, cfg, window, raws, n_pre):
     n_miss = sum(s.n_miss for s in timed)
     n_byp = sum(s.n_bypass for s in timed)
     scale = steps / max(1, len(timed))
-    link_bytes = (n_cpu + n_miss) * R * scale
-    hbm_bytes = (2 * n_hit + n_cpu + 2 * (n_miss - n_byp) + n_byp) * R * scale
+    # Bytes the method must move.  One row per line: a miss's row is read once and written to the output and
+    # to its line.  Several rows per line: a filled line is read from the store and written to the cache in
+    # full, and contains every missed row of that line, so only CPU-buffer rows and bypassed rows cross the
+    # link besides; every missed row is still written to the output.
+    P = args.rows_per_line
+    n_fills = sum(s.n_line_fills for s in timed)
+
+    def algorithmic_bytes(hit, cpu, miss, byp, fills):
+        if P == 1:
+            return (cpu + miss) * R, (2 * hit + cpu + 2 * (miss - byp) + byp) * R
+        return (cpu + byp + fills * P) * R, (2 * hit + cpu + miss + fills * P) * R
+
+    link_bytes, hbm_bytes = (x * scale for x in algorithmic_bytes(n_hit, n_cpu, n_miss, n_byp, n_fills))
     gathered_bytes = n_unique * R * scale
     t_roof_ms = (link_bytes / (LINK_PEAK_GBS * 1e9) + hbm_bytes / (HBM_PEAK_GBS * 1e9)) * 1e3
     t_overlap_ms = max(link_bytes / (LINK_PEAK_GBS * 1e9), hbm_bytes / (HBM_PEAK_GBS * 1e9)) * 1e3
@@ -348,8 +380,9 @@ def run_point(args, env, cfg, window, raws, n_pre):
     ph = np.array([gids.gids_profile_read(ses.cache, pseq[t]) for t in keep])
     pst = [ses.stats(pseq[t]) for t in keep]
     mv_ms = float(ph[:, 2].mean())
-    mv_link = np.mean([(s.n_cpu_hit + s.n_miss) * R for s in pst])
-    mv_hbm = np.mean([(2 * s.n_hit + s.n_cpu_hit + 2 * (s.n_miss - s.n_bypass) + s.n_bypass) * R for s in pst])
+    per_launch = [algorithmic_bytes(s.n_hit, s.n_cpu_hit, s.n_miss, s.n_bypass, s.n_line_fills) for s in pst]
+    mv_link = np.mean([b[0] for b in per_launch])
+    mv_hbm = np.mean([b[1] for b in per_launch])
     link_bound = mv_link / LINK_PEAK_GBS >= mv_hbm / HBM_PEAK_GBS
     if link_bound:
         roof = {"bound": "host_link", "achieved": mv_link / (mv_ms * 1e-3) / 1e9, "peak": LINK_PEAK_GBS}
@@ -438,10 +471,11 @@ def run_point(args, env, cfg, window, raws, n_pre):
         "unique_ids_per_s": n_unique * scale / (total_ms * 1e-3),
         "config": {"workload": cfg.name, "n_nodes": cfg.n_nodes, "row_bytes": R, "cache_lines": cfg.cache_lines,
                    "ways": cfg.ways, "line_bytes": cfg.line_bytes, "cpu_buffer_rows": cfg.cpu_rows, "window": window,
-                   "fanouts": list(cfg.fanouts), "seeds_per_batch": cfg.n_seeds, "accum_threshold": args.accum, "prewarm_lists": n_pre, "gpu_sampler": bool(args.gpu_sampler), "policy": args.policy, "hot_by": args.hot_by, "id_stream": ("layerwise " + args.layerwise) if args.layerwise else "neighbourhood",
+                   "fanouts": list(cfg.fanouts), "seeds_per_batch": cfg.n_seeds, "accum_threshold": args.accum, "prewarm_lists": n_pre, "gpu_sampler": bool(args.gpu_sampler), "policy": args.policy, "hot_by": args.hot_by, "rows_per_line": args.rows_per_line, "id_stream": ("layerwise " + args.layerwise) if args.layerwise else "neighbourhood",
                    "id_dtype": cfg.index_dtype, "scaled_from": base.n_nodes if cfg.n_nodes != base.n_nodes else None},
         "per_step": {"unique": n_unique * scale / steps, "hit": n_hit * scale / steps, "cpu_hit": n_cpu * scale / steps,
-                     "miss": n_miss * scale / steps, "bypass": n_byp * scale / steps},
+                     "miss": n_miss * scale / steps, "bypass": n_byp * scale / steps,
+                     "line_fills": n_fills * scale / steps},
         "weighted_roofline": {"hbm_peak_GBs": HBM_PEAK_GBS, "link_peak_GBs": LINK_PEAK_GBS,
                               "t_roof_ms_per_step": t_roof_ms / steps, "frac": t_roof_ms / total_ms,
                               "frac_overlap_bound": t_overlap_ms / total_ms,
@@ -503,6 +537,8 @@ def run_point(args, env, cfg, window, raws, n_pre):
         store_np = ses.store_view()
         sim = oracle.Sim(cfg.n_nodes, cfg.cache_lines, cfg.ways, window, R, cfg.line_bytes, store_np)
         sim.set_hot(hot)
+        if args.rows_per_line > 1:
+            sim.set_rows_per_line(args.rows_per_line)
         if args.policy == "random":
             sim.set_policy(1, cfg.seed)
         opushed, done, o_unique, o_time = 0, 0, 0, 0.0

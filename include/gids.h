@@ -72,7 +72,9 @@ typedef struct gids_cache gids_cache;
  * store without being installed.  n_pending = fills still queued in the
  * accumulator when the gather's kernels ended; `flushed` is 1 when every row
  * of this minibatch's output was written by the end of the gather call's own
- * work on the stream, 0 when some await a later flush. */
+ * work on the stream, 0 when some await a later flush.  n_line_fills = cache
+ * lines this minibatch fills from the store: n_miss - n_bypass with one row
+ * per line, fewer when several missing rows share a line. */
 typedef struct gids_stats {
     uint64_t seq;       /* 0-based index of the gather call on this cache */
     uint64_t n_unique;
@@ -83,6 +85,7 @@ typedef struct gids_stats {
     uint64_t n_pending;
     int32_t flushed;
     int32_t status;     /* GIDS_OK or the GIDS_E_* the device found */
+    uint64_t n_line_fills;
 } gids_stats;
 
 /* The feature table (Section 2.1: an N x D matrix, one row per node).
@@ -138,6 +141,19 @@ int gids_cache_destroy(gids_cache* cache);
 #define GIDS_POLICY_LRU 0
 #define GIDS_POLICY_RANDOM 1
 int gids_cache_set_policy(gids_cache* cache, int policy, uint64_t seed);
+
+/* Cache lines that hold several node rows.  The cache the paper builds on keeps
+ * the storage's cache-lines (4 KB in the example of Section 3.3) while a node's
+ * row is 512 B to 4 KB (Section 2.1): with small rows one line holds `rows`
+ * consecutive rows of the table, and a miss on any of them brings the whole
+ * line in, so that its neighbours hit afterwards.  The tag of a line is then
+ * the store line number id div rows, its set that number mod (lines / ways);
+ * a line stays while any of its rows has a buffered future use.  Every
+ * requested row of a missing line counts as a miss of its own (its bytes come
+ * from the store); the line is filled once.  rows * row_bytes <= line_bytes;
+ * not together with accum_threshold > 0; before the first push or gather.
+ * Default 1. */
+int gids_cache_set_rows_per_line(gids_cache* cache, uint32_t rows);
 
 /* Pre-size the internal per-minibatch buffers for ID lists of up to
  * max_ids_per_minibatch entries, so that no later call allocates. */

@@ -94,6 +94,7 @@ struct gids_cache {
                        hipStream_t s) = 0;
     virtual int flush(hipStream_t s) = 0;
     virtual int snapshot(int64_t* tags, int64_t* stamps) = 0;
+    virtual uint32_t window_count() const = 0;
 
     gids_store* store = nullptr;
     uint64_t lines = 0, n_sets = 0, threshold = 0, n_words = 0;
@@ -101,6 +102,7 @@ struct gids_cache {
     int sticky = GIDS_OK;
     uint64_t seq = 0;
     uint32_t policy = 0;            // GIDS_POLICY_*
+    uint32_t rows_per_line = 1;     // node rows one cache line holds
     uint64_t policy_key = 0;
     StatsRec* ring_host = nullptr;
     StatsRec* ring_dev = nullptr;
@@ -224,7 +226,7 @@ struct CacheT final : gids_cache {
         v.n_rows = store->n_rows; v.n_sets = n_sets; v.ways = ways; v.lg_ways = lg_ways;
         v.row_bytes = store->row_bytes; v.line_bytes = line_bytes; v.words_per_set = words_per_set;
         v.use32 = (!wide_index && store->n_rows < (1ull << 32) && n_sets < (1ull << 32)) ? 1u : 0u;
-        v.policy = policy; v.policy_key = policy_key;
+        v.policy = policy; v.policy_key = policy_key; v.rows_per_line = rows_per_line;
         v.tags = tags; v.stamps = stamps; v.pending = pending; v.reuse = reuse; v.missmask = missmask;
         v.hotbits = n_hot ? hotbits : nullptr; v.hotrank = hotrank;
         v.cache_data = cache_data; v.store = static_cast<const char*>(store->dev);
@@ -536,6 +538,8 @@ struct CacheT final : gids_cache {
         return GIDS_OK;
     }
 
+    uint32_t window_count() const override { return count; }
+
     int snapshot(int64_t* tags_host, int64_t* stamps_host) override {
         HIP_TRY(hipDeviceSynchronize());
         if (tags_host) {
@@ -815,6 +819,16 @@ int gids_cache_set_policy(gids_cache* cache, int policy, uint64_t seed) {
     return GIDS_OK;
 }
 
+int gids_cache_set_rows_per_line(gids_cache* cache, uint32_t rows) {
+    CHECK_CACHE(cache);
+    if (rows < 1) return fail(GIDS_E_INVAL, "gids_cache_set_rows_per_line: rows must be >= 1");
+    if ((uint64_t)rows * cache->store->row_bytes > cache->line_bytes) return fail(GIDS_E_INVAL, "gids_cache_set_rows_per_line: %u rows of %u bytes do not fit a line of %u bytes", rows, cache->store->row_bytes, cache->line_bytes);
+    if (cache->threshold && rows > 1) return fail(GIDS_E_INVAL, "gids_cache_set_rows_per_line: not available together with the accumulator");
+    if (cache->seq || cache->window_count()) return fail(GIDS_E_INVAL, "gids_cache_set_rows_per_line: call before the first push or gather");
+    cache->rows_per_line = rows;
+    return GIDS_OK;
+}
+
 int gids_flush(gids_cache* cache, void* stream) {
     CHECK_CACHE(cache);
     return cache->flush(static_cast<hipStream_t>(stream));
@@ -830,7 +844,7 @@ int gids_stats_read(gids_cache* cache, uint64_t seq, gids_stats* stats) {
     if (rec.seq != seq) return fail(GIDS_E_INVAL, "gids_stats_read: record of gather %llu was overwritten", (unsigned long long)seq);
     stats->seq = rec.seq; stats->n_unique = rec.n_unique; stats->n_hit = rec.n_hit; stats->n_cpu_hit = rec.n_cpu_hit;
     stats->n_miss = rec.n_miss; stats->n_bypass = rec.n_bypass; stats->n_pending = rec.n_pending;
-    stats->flushed = rec.flushed; stats->status = rec.status;
+    stats->flushed = rec.flushed; stats->status = rec.status; stats->n_line_fills = rec.n_line_fills;
     if (rec.status) {
         cache->sticky = rec.status;
         return fail(rec.status, "gather %llu failed on the device with code %d", (unsigned long long)seq, rec.status);

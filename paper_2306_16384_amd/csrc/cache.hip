@@ -101,10 +101,11 @@ __global__ __launch_bounds__(CT_THREADS) void probe_kernel(CacheView<IdT> c, con
             }
         }
         hot = __shfl(hot, (int)(lane_id() & ~(ways - 1)));
+        const uint64_t b = store_line_of(c, v);              // the tag: v itself with one row per line
         uint64_t set = 0, round = 0;
-        set_and_round(c, v, &set, &round);
+        set_and_round(c, b, &set, &round);
         bool match = false;
-        if (valid && !hot) match = (uint64_t)c.tags[set * ways + sub] == v;   // empty lines hold -1
+        if (valid && !hot) match = (uint64_t)c.tags[set * ways + sub] == b;   // empty lines hold -1
         const uint64_t gb = group_bits(__ballot(match), ways);
         const bool is_hit = gb != 0;
         if (valid && leader) {
@@ -148,10 +149,10 @@ template <typename IdT>
 __global__ __launch_bounds__(CT_THREADS) void victim_kernel(CacheView<IdT> c, const IdT* __restrict__ unique,
                                                             const uint32_t* __restrict__ n_u_ptr,
                                                             uint64_t* __restrict__ plan) {
-    __shared__ uint32_t block_byp;
+    __shared__ uint32_t block_byp, block_fill;
     Ctl* ctl = c.ctl;
     if (ctl->error || ctl->cnt_miss == 0) return;            // cnt_miss is final: the probe has ended
-    if (threadIdx.x == 0) block_byp = 0;
+    if (threadIdx.x == 0) block_byp = block_fill = 0;
     __syncthreads();
     const uint32_t n_u = *n_u_ptr;
     const uint32_t ways = c.ways, lg = c.lg_ways;
@@ -161,14 +162,16 @@ __global__ __launch_bounds__(CT_THREADS) void victim_kernel(CacheView<IdT> c, co
     const int32_t stamp = (int32_t)ctl->stamp;
     const uint64_t wave0 = ((uint64_t)blockIdx.x * CT_THREADS + threadIdx.x) >> 6;
     const uint64_t n_waves = ((uint64_t)gridDim.x * CT_THREADS) >> 6;
-    uint32_t bypasses = 0;
+    const uint64_t rpl = c.rows_per_line;
+    uint32_t bypasses = 0, fills = 0;
     for (uint64_t chunk = wave0; chunk * per_wave < n_u; chunk += n_waves) {
         const uint64_t j = chunk * per_wave + (lane_id() >> lg);
         const bool valid = j < n_u && (plan[j] >> PLAN_SHIFT) == PLAN_MISS_TBD;
         if (!__ballot(valid)) continue;                      // no miss among this wave's IDs
         const uint64_t v = valid ? (uint64_t)unique[j] : 0;
+        const uint64_t b = store_line_of(c, v);
         uint64_t set = 0, round = 0;
-        set_and_round(c, v, &set, &round);
+        set_and_round(c, b, &set, &round);
         // this lane's way: evictable?
         const uint64_t line = set * ways + sub;
         bool ev = false, empty = false;
@@ -177,7 +180,17 @@ __global__ __launch_bounds__(CT_THREADS) void victim_kernel(CacheView<IdT> c, co
             const IdT tg = c.tags[line];
             st = c.stamps[line];
             empty = tg < 0;
-            ev = st != stamp && (empty || c.reuse[(uint64_t)tg] == 0);
+            bool pinned = false;                             // some row of the line has a buffered future use
+            if (!empty) {
+                if (rpl == 1) {
+                    pinned = c.reuse[(uint64_t)tg] != 0;
+                } else {
+                    const uint64_t r0 = (uint64_t)tg * rpl;
+                    const uint64_t r1 = r0 + rpl < c.n_rows ? r0 + rpl : c.n_rows;
+                    for (uint64_t r = r0; r < r1; r++) pinned |= c.reuse[r] != 0;
+                }
+            }
+            ev = st != stamp && !pinned;
         }
         // order of this way among the set's evictable ways: by (stamp, way), empty ways (stamp -1) first;
         // under the random base policy occupied ways are ordered by a hash of (minibatch, set, way) instead
@@ -200,19 +213,39 @@ __global__ __launch_bounds__(CT_THREADS) void victim_kernel(CacheView<IdT> c, co
             k += (uint32_t)__popcll(m[wi] & ((1ull << (round & 63)) - 1));
         }
         k = __shfl(k, (int)group_base);
+        // With several rows per line the IDs of one missing line sit next to each other in the ascending list
+        // and all find the same way; the first of them that is not served by the CPU buffer fills the line,
+        // the others only fetch their own row.  (Kinds other than CPU are misses here: the line is absent.)
+        uint32_t follow = 0;
+        if (valid && sub == 0 && rpl > 1) {
+            for (uint64_t i = j; i-- > 0;) {
+                if (store_line_of(c, (uint64_t)unique[i]) != b) break;
+                if ((plan[i] >> PLAN_SHIFT) != PLAN_CPU) { follow = 1; break; }
+            }
+        }
+        follow = __shfl(follow, (int)group_base);
         if (valid) {
-            if (ev && way_rank == k) plan[j] = (PLAN_INSTALL << PLAN_SHIFT) | line;
-            if (sub == 0 && k >= n_ev) {
-                plan[j] = PLAN_BYPASS << PLAN_SHIFT;
-                bypasses++;
+            if (ev && way_rank == k) plan[j] = ((follow ? PLAN_FOLLOW : PLAN_INSTALL) << PLAN_SHIFT) | line;
+            if (sub == 0) {
+                if (k >= n_ev) {
+                    plan[j] = PLAN_BYPASS << PLAN_SHIFT;
+                    bypasses++;
+                } else if (!follow) {
+                    fills++;
+                }
             }
         }
     }
 #pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) bypasses += __shfl_down(bypasses, d);
+    for (int d = 32; d >= 1; d >>= 1) {
+        bypasses += __shfl_down(bypasses, d);
+        fills += __shfl_down(fills, d);
+    }
     if (lane_id() == 0 && bypasses) atomicAdd(&block_byp, bypasses);
+    if (lane_id() == 0 && fills) atomicAdd(&block_fill, fills);
     __syncthreads();
     if (threadIdx.x == 0 && block_byp) atomicAdd(&ctl->cnt_bypass, block_byp);
+    if (threadIdx.x == 0 && block_fill) atomicAdd(&ctl->cnt_fill, block_fill);
 }
 
 // Publishes the gather's decisions: tag and stamp of every line a miss will
@@ -238,14 +271,14 @@ __global__ __launch_bounds__(CT_THREADS) void commit_kernel(CacheView<IdT> c, co
         const uint64_t e = plan[j];
         const uint64_t kind = e >> PLAN_SHIFT;
         if (kind < PLAN_INSTALL) continue;
-        const uint64_t v = (uint64_t)unique[j];
+        const uint64_t b = store_line_of(c, (uint64_t)unique[j]);
         if (kind == PLAN_INSTALL) {
             const uint64_t line = e & PLAN_INDEX_MASK;
-            c.tags[line] = (IdT)v;
+            c.tags[line] = (IdT)b;
             c.stamps[line] = (int32_t)stamp;
         }
         uint64_t set, round;
-        set_and_round(c, v, &set, &round);
+        set_and_round(c, b, &set, &round);
         c.missmask[set * c.words_per_set + (round >> 6)] = 0ull;
     }
 }

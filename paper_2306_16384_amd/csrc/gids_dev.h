@@ -10,8 +10,9 @@ namespace gids {
 
 // ---- plan entry: what the row mover does for the j-th distinct ID ----------
 // bits 63..61 = kind, bits 60..0 = cache line index (HIT, INSTALL) or CPU-buffer
-// slot (CPU); BYPASS and MISS_TBD carry no index.
-constexpr uint64_t PLAN_HIT = 0, PLAN_CPU = 1, PLAN_INSTALL = 2, PLAN_BYPASS = 3, PLAN_MISS_TBD = 4;
+// slot (CPU); BYPASS, FOLLOW and MISS_TBD carry no index.  FOLLOW exists only with several rows per cache
+// line: a miss whose line another ID of the same minibatch fills; its own row comes from the store.
+constexpr uint64_t PLAN_HIT = 0, PLAN_CPU = 1, PLAN_INSTALL = 2, PLAN_BYPASS = 3, PLAN_MISS_TBD = 4, PLAN_FOLLOW = 5;
 constexpr int PLAN_SHIFT = 61;
 constexpr uint64_t PLAN_INDEX_MASK = (1ull << PLAN_SHIFT) - 1;
 
@@ -28,6 +29,7 @@ struct Ctl {
     uint32_t ticket;        // arrival counter for "last block does the scan"
     uint32_t stamp;         // index of the minibatch being gathered (successful gathers so far)
     uint32_t cnt_hit, cnt_cpu, cnt_miss, cnt_bypass;
+    uint32_t cnt_fill;      // cache lines this minibatch fills
     uint32_t pend_fill;     // queued host-link rows (accumulator)
     uint32_t pend_copy;     // queued HBM copies that wait for a queued fill
     uint32_t deferred;      // rows of the current gather left in the queues
@@ -59,6 +61,7 @@ struct CopyOp {
 struct StatsRec {
     uint64_t seq, n_unique, n_hit, n_cpu_hit, n_miss, n_bypass, n_pending;
     int32_t flushed, status;
+    uint64_t n_line_fills;
 };
 
 // Everything the gather kernels need about one cache.
@@ -70,6 +73,7 @@ struct CacheView {
     uint32_t row_bytes, line_bytes;
     uint32_t words_per_set; // 64-bit words of the miss mask per set
     uint32_t use32;         // n_rows and n_sets < 2^32: set index with 32-bit arithmetic
+    uint32_t rows_per_line; // node rows one cache line holds (store line b = id div rows_per_line is the tag)
     uint32_t policy;        // order of evictable ways: 0 = last-use stamp (LRU by minibatch), 1 = seeded hash (random)
     uint64_t policy_key;    // mix64(seed + 8 * golden): prefix of the random policy's hash chain
     IdT* tags;              // lines, -1 = empty
@@ -84,6 +88,13 @@ struct CacheView {
     const char* cpubuf;     // device-visible address of the CPU buffer rows (ascending ID order)
     Ctl* ctl;
 };
+
+// the store line (the cache's tag) that holds row v
+template <typename IdT>
+__device__ __forceinline__ uint64_t store_line_of(const CacheView<IdT>& c, uint64_t v) {
+    if (c.rows_per_line == 1) return v;
+    return c.use32 ? (uint64_t)((uint32_t)v / c.rows_per_line) : v / c.rows_per_line;
+}
 
 // Device-side counters of the neighbour sampler.
 struct SamplerState {

@@ -119,16 +119,30 @@ __global__ __launch_bounds__(MV_THREADS) void move_kernel(CacheView<IdT> c, cons
             const uint64_t v_p = __shfl(v, (int)(pick & 63));
             if (pick == 64u) continue;
             const uint64_t kind = e_p >> PLAN_SHIFT, idx = e_p & PLAN_INDEX_MASK;
+            const uint64_t rpl = c.rows_per_line;
             const char* src;
             char* line = nullptr;
-            if (kind == PLAN_HIT) src = c.cache_data + idx * c.line_bytes;
-            else if (kind == PLAN_CPU) src = c.cpubuf + idx * c.row_bytes;
-            else {
+            if (kind == PLAN_HIT) {
+                src = c.cache_data + idx * c.line_bytes;
+                if (rpl > 1) src += (v_p - store_line_of(c, v_p) * rpl) * c.row_bytes;   // the row's place in its line
+            } else if (kind == PLAN_CPU) {
+                src = c.cpubuf + idx * c.row_bytes;
+            } else {
                 src = c.store + v_p * c.row_bytes;
                 if (kind == PLAN_INSTALL) line = c.cache_data + idx * c.line_bytes;
             }
-            copy_row<G>(reinterpret_cast<const v4u*>(src), reinterpret_cast<v4u*>(out + (base + pick) * c.row_bytes),
-                        reinterpret_cast<v4u*>(line), row_u4, sub);
+            v4u* dst = reinterpret_cast<v4u*>(out + (base + pick) * c.row_bytes);
+            if (rpl == 1 || !line) {
+                copy_row<G>(reinterpret_cast<const v4u*>(src), dst, reinterpret_cast<v4u*>(line), row_u4, sub);
+            } else {
+                // several rows per line: the requested row to the output, then the whole store line (clipped at
+                // the table's end) into the cache line
+                copy_row<G>(reinterpret_cast<const v4u*>(src), dst, nullptr, row_u4, sub);
+                const uint64_t first = store_line_of(c, v_p) * rpl;
+                const uint64_t rows = first + rpl <= c.n_rows ? rpl : c.n_rows - first;
+                copy_row<G>(reinterpret_cast<const v4u*>(c.store + first * c.row_bytes), reinterpret_cast<v4u*>(line),
+                            nullptr, (uint32_t)(rows * row_u4), sub);
+            }
         }
         if (!link_role) base += n_waves * ch;
     }
@@ -284,6 +298,7 @@ __global__ void finalize_kernel(Ctl* ctl, StatsRec* rec, uint64_t seq, const uin
     rec->n_cpu_hit = ctl->cnt_cpu;
     rec->n_miss = ctl->cnt_miss;
     rec->n_bypass = ctl->cnt_bypass;
+    rec->n_line_fills = ctl->cnt_fill;
     rec->n_pending = (uint64_t)ctl->pend_fill + ctl->pend_copy;
     rec->flushed = ctl->deferred == 0;
     rec->status = -(int32_t)err;
@@ -291,7 +306,7 @@ __global__ void finalize_kernel(Ctl* ctl, StatsRec* rec, uint64_t seq, const uin
     rec->seq = seq;                       // written last: a record whose seq matches is complete
     __threadfence_system();
     if (!err) ctl->stamp += 1;
-    ctl->cnt_hit = ctl->cnt_cpu = ctl->cnt_miss = ctl->cnt_bypass = 0;
+    ctl->cnt_hit = ctl->cnt_cpu = ctl->cnt_miss = ctl->cnt_bypass = ctl->cnt_fill = 0;
     ctl->deferred = 0;
 }
 

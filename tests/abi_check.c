@@ -22,6 +22,7 @@ int main(void) {
         if (gids_sample_capacity(f, 3, 4096) != 4096ull * 1111) return 6;
     }
     if (gids_graph_reverse_pagerank(NULL, 55705, 10, NULL, NULL) != GIDS_E_INVAL) return 7;
+    if (gids_cache_set_rows_per_line(NULL, 8) != GIDS_E_INVAL) return 8;
     printf("abi ok %zu\n", sizeof(gids_stats));
     return 0;
 }

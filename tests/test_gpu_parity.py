@@ -23,7 +23,7 @@ def gpu():
 
 def run_case(gpu, oracle, feats, batches, *, id_dtype, lines, ways, line_bytes, window, threshold=0, hot=None,
              use_head=False, with_inverse=False, check_state=True, two_streams=False, policy=None, label="",
-             pipeline=None, push_depth0=False, wide_index=False):
+             pipeline=None, push_depth0=False, wide_index=False, rows_per_line=1):
     """Feeds the same raw ID lists to both implementations, protocol: keep window + 1 lists buffered.
     pipeline: "0" / "1" forces the library's internal stream off / on for this cache (GIDS_PIPELINE);
     push_depth0: at window depth 0, push every list just before its gather."""
@@ -38,13 +38,17 @@ def run_case(gpu, oracle, feats, batches, *, id_dtype, lines, ways, line_bytes, 
         sim.set_hot(hot)
     if policy is not None:
         sim.set_policy(*policy)
+    if rows_per_line != 1:
+        sim.set_rows_per_line(rows_per_line)
     # the oracle's pass, on its own
-    want, pushed = [], 0
+    want, line_fills, pushed = [], [], 0
     for t, raw in enumerate(batches):
         while window and pushed < len(batches) and pushed <= t + window:
             sim.push(batches[pushed])
             pushed += 1
-        want.append(sim.gather(raw))
+        u, rows, stats, cls = sim.gather(raw, want_cls=True)
+        want.append((u, rows, stats))
+        line_fills.append(len(np.unique(u[cls == 2] // rows_per_line)))   # distinct store lines among installed misses
     import os
     knobs = {}                                               # environment knobs are read when the cache is created
     if pipeline is not None:
@@ -68,6 +72,8 @@ def run_case(gpu, oracle, feats, batches, *, id_dtype, lines, ways, line_bytes, 
             ses.pin_hot(hot)
         if policy is not None:
             ses.set_policy(*policy)
+        if rows_per_line != 1:
+            ses.set_rows_per_line(rows_per_line)
         dev = [ses.to_device(b) for b in batches]
         torch.cuda.synchronize()
         push_stream = torch.cuda.Stream() if two_streams else None
@@ -91,6 +97,7 @@ def run_case(gpu, oracle, feats, batches, *, id_dtype, lines, ways, line_bytes, 
             st = ses.stats(seqs[t])
             assert st.status == 0
             assert st.as_tuple() == tuple(int(x) for x in want_stats), (label, t, st.as_tuple(), want_stats.tolist())
+            assert st.n_line_fills == line_fills[t], (label, t, st.n_line_fills, line_fills[t])
             m = len(want_u)
             got_u = uniqs[t][:m].cpu().numpy()
             np.testing.assert_array_equal(got_u, want_u.astype(got_u.dtype), err_msg=f"{label} batch {t} unique")
@@ -516,3 +523,46 @@ def check_depth_zero(torch, ses, batches, want, sim, two_streams):
         assert np.array_equal(out[:len(u)].cpu().numpy(), rows), t
     tags, stamps = ses.snapshot()
     assert np.array_equal(tags, sim.tags) and np.array_equal(stamps, sim.stamps)
+
+
+@pytest.mark.parametrize("rows,window,policy,id_dtype", [(8, 3, None, np.int64), (2, 0, None, np.int32), (4, 5, (1, 3), np.int64),
+                                                          (3, 2, None, np.int64), (16, 1, None, np.int32)])
+def test_several_rows_per_cache_line(gpu, oracle_mod, rows, window, policy, id_dtype):
+    """Lines of several node rows (the 4 KB cache-lines of Section 3.3 under 512 B rows): counters, the number of
+    lines filled, every gathered row and the final tags (store line numbers) equal the oracle's."""
+    rng = np.random.default_rng(300 + rows)
+    n, R = 20_011, 64                                          # the table's last line is partial
+    feats = rand_feats(rng, n, R)
+    # neighbourhoods of hubs: many requested rows share a line
+    batches = []
+    for _ in range(18):
+        hubs = np.minimum(rng.zipf(1.2, size=600) - 1, n - 1)
+        near = np.clip(hubs + rng.integers(-6, 7, size=600), 0, n - 1)
+        batches.append(np.concatenate([hubs, near, rng.integers(0, n, size=200)]).astype(np.int64))
+    ways = 4
+    for pipeline in ("0", "1"):
+        run_case(gpu, oracle_mod, feats, batches, id_dtype=id_dtype, lines=ways * 61, ways=ways, line_bytes=rows * R + 16,
+                 window=window, hot=rng.choice(n, 150, replace=False), policy=policy, rows_per_line=rows,
+                 use_head=bool(window), two_streams=True, pipeline=pipeline, label=f"rows{rows}/W{window}/pipe{pipeline}")
+    # a line for every store line: after one row of each, nothing misses
+    lines = ((n + rows - 1) // rows + ways - 1) // ways * ways
+    cover = [np.arange(0, n, rows), np.arange(n), rng.integers(0, n, size=3000)]
+    run_case(gpu, oracle_mod, feats, cover, id_dtype=id_dtype, lines=lines, ways=ways, line_bytes=rows * R, window=0,
+             rows_per_line=rows, label=f"rows{rows}/resident")
+
+
+def test_rows_per_line_argument_checks(gpu):
+    torch, gids, GatherSession = gpu
+    with GatherSession(100, 64, np.int64, 16, 4, 256, 0) as s:
+        with pytest.raises(gids.GidsError):
+            s.set_rows_per_line(5)                             # 5 x 64 B do not fit a 256 B line
+        with pytest.raises(gids.GidsError):
+            s.set_rows_per_line(0)
+        s.set_rows_per_line(4)
+        out = torch.zeros((4, 64), dtype=torch.uint8, device="cuda")
+        s.gather(s.to_device([1]), out)
+        with pytest.raises(gids.GidsError):
+            s.set_rows_per_line(2)                             # only before the first gather
+    with GatherSession(100, 64, np.int64, 16, 4, 256, 0, 50) as s:
+        with pytest.raises(gids.GidsError):
+            s.set_rows_per_line(4)                             # not with the accumulator
