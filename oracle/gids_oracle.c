@@ -19,15 +19,27 @@
  *     count is positive are in the "USE" state and are not evicted, count 0 is
  *     "safe to evict" (Section 3.4, Fig. 6 steps 1-5);
  *   - the overlapped-access model N = r/(1-r) * IOPS * (Ti + Tt) (Section 3.2,
- *     Eq. 2-3).
+ *     Eq. 2-3);
+ *   - the random base policy of the cache the paper builds on (Section 3.4),
+ *     seeded; cache lines that hold several node rows (4 KB cache-lines,
+ *     Section 3.3, under rows of 512 B and more, Section 2.1);
+ *   - hot-node rankings: weighted reverse PageRank (the metric Section 3.3
+ *     names) and the expected visits under this sampler.
  *
  * Parity pins (see tests/): brute-force row equality, count conservation,
  * cache >= store => only first-touch misses, depth 0 == textbook per-set LRU
  * by batch, pinned lines never evicted, CPU-buffer hits == |U ∩ P|, a
- * hand-traced fully-associative case, the sampler's worked example.  The
+ * hand-traced fully-associative case, the sampler's worked example; the
+ * random policy's uniformity and an independent model of its hash order;
+ * several rows per line by reduction to the one-row simulator over line
+ * numbers; PageRank against ring / chain / star closed forms and a linear
+ * solve; visit scores against closed forms and the sampler's frequencies.  The
  * tie-breaks of the replacement policy (lowest way first, ascending ID first,
  * bypass when nothing is evictable) are fixed by this project, not the paper:
- * for those constants alone, parity unpinned.
+ * for those constants alone, parity unpinned.  The same holds for two
+ * readings the paper leaves open: that a line of several rows stays while any
+ * of its rows is needed again, and the exact weighting of the reverse
+ * PageRank (the paper cites the metric without a formula).
  *
  * The replacement policy is batch-synchronous: every ID of a minibatch is
  * classified against the cache state at the start of the minibatch, then the
