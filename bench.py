@@ -32,8 +32,8 @@ LINK_PEAK_GBS = 64.0         # PCIe Gen5 x16, nominal per direction (the box neg
 
 # HBM traffic of the row mover per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # command (see profiles/); None until such a run exists for the workload.
-MEASURED_TRAFFIC_BYTES = {"large@28000000": 583.1e6,     # profiles/move_kernel_large_pmc.txt
-                          "resident": 5246.4e6}           # profiles/move_kernel_resident_pmc.txt
+MEASURED_TRAFFIC_BYTES = {"large@28000000": 572.6e6,     # profiles/move_kernel_large_pmc.txt
+                          "resident": 5266.0e6}           # profiles/move_kernel_resident_pmc.txt
 
 
 def log(*a):
