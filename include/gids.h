@@ -114,11 +114,13 @@ int gids_store_calibrate(gids_store* store, double* rows_per_s, double* overhead
 /* The GPU software cache over a store (Section 3.4) plus its window buffer
  * and fill accumulator (Section 3.2).
  *   lines          cache lines, a multiple of `ways`; one node row per line
+ *                  unless gids_cache_set_rows_per_line says otherwise
  *   ways           associativity, a power of two in [1, 64]; set = id mod (lines / ways)
  *   line_bytes     slot stride in HBM, >= row_bytes, multiple of 16
  *   window_depth   W in [0, 254]: how many minibatches beyond the one being
  *                  gathered are buffered.  A cached row that one of them reuses
- *                  is not evicted.  W = 0: no window, plain LRU by minibatch.
+ *                  is not evicted.  W = 0: no window, plain LRU by minibatch
+ *                  (or the policy set with gids_cache_set_policy).
  *   accum_threshold  0: every gather moves its own rows before it ends.
  *                  > 0: rows that must cross the host link are queued and moved
  *                  once at least this many are pending (or at gids_flush); the
