@@ -566,3 +566,70 @@ def test_rows_per_line_argument_checks(gpu):
     with GatherSession(100, 64, np.int64, 16, 4, 256, 0, 50) as s:
         with pytest.raises(gids.GidsError):
             s.set_rows_per_line(4)                             # not with the accumulator
+
+
+@pytest.mark.parametrize("pipeline", ["0", "1"])
+def test_a_thousand_minibatches(gpu, oracle_mod, pipeline):
+    """A long run on a small cache: the 64-entry rings of events and counters wrap many times, every slot of
+    the window is reused hundreds of times; counters of every minibatch (read with a lag, as a training loop
+    would), sampled tensors and the final tags must still equal the oracle's."""
+    import os
+    torch, gids, GatherSession = gpu
+    cfg = CONFIGS["tiny"]
+    g = wl.make_graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max)
+    table = wl.normal_table(np.float32)
+    feats = wl.feature_rows(cfg.seed, np.arange(cfg.n_nodes), cfg.dim, table).view(np.uint8).reshape(cfg.n_nodes, -1)
+    hot = wl.hot_nodes(g, cfg.cpu_rows)
+    base = [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds) for b in range(37)]
+    n_b, W = 1000, 5
+    lists = [base[(7 * t) % 37] for t in range(n_b)]
+    sim = oracle_mod.Sim(cfg.n_nodes, cfg.cache_lines, cfg.ways, W, cfg.row_bytes, cfg.line_bytes, feats)
+    sim.set_hot(hot)
+    want, pushed = [], 0
+    check_rows = set(range(0, n_b, 97)) | {n_b - 1}
+    for t in range(n_b):
+        while pushed < n_b and pushed <= t + W:
+            sim.push(lists[pushed])
+            pushed += 1
+        want.append(sim.gather(lists[t], want_rows=t in check_rows))
+    old = os.environ.get("GIDS_PIPELINE")
+    os.environ["GIDS_PIPELINE"] = pipeline
+    try:
+        ses = GatherSession(cfg.n_nodes, cfg.row_bytes, np.int32, cfg.cache_lines, cfg.ways, cfg.line_bytes, W)
+    finally:
+        if old is None:
+            del os.environ["GIDS_PIPELINE"]
+        else:
+            os.environ["GIDS_PIPELINE"] = old
+    with ses:
+        ses.store_view()[:] = feats
+        ses.pin_hot(hot)
+        dev = [ses.to_device(b) for b in base]
+        cap = max(len(b) for b in base)
+        ses.reserve(cap)
+        ps = torch.cuda.Stream()
+        ring = [torch.empty((cap, cfg.row_bytes), dtype=torch.uint8, device="cuda") for _ in range(3)]
+        uq = torch.empty(cap, dtype=torch.int32, device="cuda")
+        kept, seqs, pushed = {}, [], 0
+        for t in range(n_b):
+            while pushed < n_b and pushed <= t + W:
+                ses.push(dev[(7 * pushed) % 37], stream=ps)
+                pushed += 1
+            if t in check_rows:
+                kept[t] = (torch.empty((cap, cfg.row_bytes), dtype=torch.uint8, device="cuda"),
+                           torch.empty(cap, dtype=torch.int32, device="cuda"))
+                seqs.append(ses.gather(None, *kept[t]))
+            else:
+                seqs.append(ses.gather(None, ring[t % 3], uq))
+            if t >= 30:
+                k = t - 30
+                assert ses.stats(seqs[k]).as_tuple() == tuple(int(x) for x in want[k][2]), k
+        torch.cuda.synchronize()
+        for k in range(n_b - 30, n_b):
+            assert ses.stats(seqs[k]).as_tuple() == tuple(int(x) for x in want[k][2]), k
+        for t, (out, u_dev) in kept.items():
+            u, rows, _ = want[t]
+            assert np.array_equal(u_dev[:len(u)].cpu().numpy(), u.astype(np.int32))
+            assert np.array_equal(out[:len(u)].cpu().numpy(), rows), t
+        tags, stamps = ses.snapshot()
+        assert np.array_equal(tags, sim.tags) and np.array_equal(stamps, sim.stamps)
