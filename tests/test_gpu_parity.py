@@ -568,8 +568,8 @@ def test_rows_per_line_argument_checks(gpu):
             s.set_rows_per_line(4)                             # not with the accumulator
 
 
-@pytest.mark.parametrize("pipeline", ["0", "1"])
-def test_a_thousand_minibatches(gpu, oracle_mod, pipeline):
+@pytest.mark.parametrize("pipeline,threshold", [("0", 0), ("1", 0), ("0", 2500)])
+def test_a_thousand_minibatches(gpu, oracle_mod, pipeline, threshold):
     """A long run on a small cache: the 64-entry rings of events and counters wrap many times, every slot of
     the window is reused hundreds of times; counters of every minibatch (read with a lag, as a training loop
     would), sampled tensors and the final tags must still equal the oracle's."""
@@ -595,7 +595,8 @@ def test_a_thousand_minibatches(gpu, oracle_mod, pipeline):
     old = os.environ.get("GIDS_PIPELINE")
     os.environ["GIDS_PIPELINE"] = pipeline
     try:
-        ses = GatherSession(cfg.n_nodes, cfg.row_bytes, np.int32, cfg.cache_lines, cfg.ways, cfg.line_bytes, W)
+        ses = GatherSession(cfg.n_nodes, cfg.row_bytes, np.int32, cfg.cache_lines, cfg.ways, cfg.line_bytes, W,
+                            threshold)
     finally:
         if old is None:
             del os.environ["GIDS_PIPELINE"]
@@ -608,7 +609,9 @@ def test_a_thousand_minibatches(gpu, oracle_mod, pipeline):
         cap = max(len(b) for b in base)
         ses.reserve(cap)
         ps = torch.cuda.Stream()
-        ring = [torch.empty((cap, cfg.row_bytes), dtype=torch.uint8, device="cuda") for _ in range(3)]
+        # with the accumulator an output must stay untouched until the flush that completes it
+        n_ring = 16 if threshold else 3
+        ring = [torch.empty((cap, cfg.row_bytes), dtype=torch.uint8, device="cuda") for _ in range(n_ring)]
         uq = torch.empty(cap, dtype=torch.int32, device="cuda")
         kept, seqs, pushed = {}, [], 0
         for t in range(n_b):
@@ -620,10 +623,13 @@ def test_a_thousand_minibatches(gpu, oracle_mod, pipeline):
                            torch.empty(cap, dtype=torch.int32, device="cuda"))
                 seqs.append(ses.gather(None, *kept[t]))
             else:
-                seqs.append(ses.gather(None, ring[t % 3], uq))
+                seqs.append(ses.gather(None, ring[t % n_ring], uq))
+            if threshold and t % n_ring == n_ring - 2:
+                ses.flush()
             if t >= 30:
                 k = t - 30
                 assert ses.stats(seqs[k]).as_tuple() == tuple(int(x) for x in want[k][2]), k
+        ses.flush()
         torch.cuda.synchronize()
         for k in range(n_b - 30, n_b):
             assert ses.stats(seqs[k]).as_tuple() == tuple(int(x) for x in want[k][2]), k
