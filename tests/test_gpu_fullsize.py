@@ -12,6 +12,11 @@ from workload import CONFIGS
 
 pytestmark = pytest.mark.gpu
 
+# GIDS_FULL_PARITY=1 runs every minibatch the configurations name (500 / 300 / 1000; several minutes of host
+# time for sampling and the oracle); the default runs a prefix of each.
+import os
+EVERY = os.environ.get("GIDS_FULL_PARITY", "0") == "1"
+
 
 def drive(ses, torch, raws, window, cap_rows, row_bytes, keep):
     """Benchmark protocol: keep window + 1 lists buffered, gather the head list."""
@@ -91,13 +96,22 @@ def pinnable(cfg_name, sizes):
     pytest.fail(f"cannot pin even {sizes[-1]} rows of host memory")
 
 
+def sample_lists(g, cfg, n_b, rank_table=None):
+    raws = []
+    for b in range(n_b):
+        raws.append(wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds, rank_table))
+        if b % 100 == 99:
+            print(f"[fullsize {cfg.name}] sampled {b + 1} of {n_b} lists", flush=True)
+    return raws
+
+
 def run_big(oracle_mod, cfg, raws, keep, table, hot=None, after_each=None):
     """Counters of every minibatch, distinct-ID lists exact, rows of every class sampled against the oracle's
     closed-form feature rows, final tags and stamps."""
     import torch
     from paper_2306_16384_amd.session import GatherSession
     n_b = len(raws)
-    cap = max(len(np.unique(r)) for r in raws)
+    cap = max(len(r) for r in raws)                           # raw length bounds the distinct count
     with GatherSession(cfg.n_nodes, cfg.row_bytes, np.int64, cfg.cache_lines, cfg.ways, cfg.line_bytes,
                        cfg.window) as ses:
         wl.fill_store(cfg.seed, cfg.n_nodes, cfg.dim, table, ses.store_address())
@@ -114,6 +128,8 @@ def run_big(oracle_mod, cfg, raws, keep, table, hot=None, after_each=None):
                 sim.push(raws[pushed])
                 pushed += 1
             u, _, stats, cls = sim.gather(raw, want_rows=False, want_cls=True)
+            if t % 50 == 49:
+                print(f"[fullsize {cfg.name}] oracle at minibatch {t + 1} of {n_b}", flush=True)
             st = stats_of[t]
             assert st.as_tuple() == tuple(int(x) for x in stats), (t, st.as_tuple(), stats.tolist())
             if after_each:
@@ -136,23 +152,23 @@ def run_big(oracle_mod, cfg, raws, keep, table, hot=None, after_each=None):
 def test_large_at_benchmark_size(oracle_mod):
     # the benchmark's node count; a box that pins less host memory runs the same test at half the size
     cfg = pinnable("large", (28_000_000, 14_000_000, 7_000_000))
-    n_b = 60
+    n_b = CONFIGS["large"].n_batches if EVERY else 150
     print(f"[fullsize large] N={cfg.n_nodes} lines={cfg.cache_lines} cpu_rows={cfg.cpu_rows} batches={n_b}", flush=True)
     g = wl.make_graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max, native=True)
     hot = wl.hot_nodes(g, cfg.cpu_rows)
-    raws = [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds) for b in range(n_b)]
+    raws = sample_lists(g, cfg, n_b)
     run_big(oracle_mod, cfg, raws, {0, 9, 33, n_b - 1}, wl.normal_table(np.float16), hot=hot)
 
 
 def test_skew_at_benchmark_size(oracle_mod):
     """The skew configuration (16 ways, Zipf-ranked seeds, depth 4) at the node count the benchmark runs."""
     cfg = pinnable("skew", (28_000_000, 14_000_000, 7_000_000))
-    n_b = 40
+    n_b = CONFIGS["skew"].n_batches if EVERY else 100
     print(f"[fullsize skew] N={cfg.n_nodes} lines={cfg.cache_lines} ways={cfg.ways} batches={n_b}", flush=True)
     g = wl.make_graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max, native=True)
     hot = wl.hot_nodes(g, cfg.cpu_rows)
     rank_table = wl.synth.zipf_rank_table(cfg.n_nodes, cfg.seed_zipf_s)
-    raws = [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds, rank_table) for b in range(n_b)]
+    raws = sample_lists(g, cfg, n_b, rank_table)
     run_big(oracle_mod, cfg, raws, {0, 5, n_b - 1}, wl.normal_table(np.float16), hot=hot)
 
 
@@ -160,13 +176,13 @@ def test_cache_resident_full_size(oracle_mod):
     """The cache-resident configuration at its full size (10 M rows of 3 KiB in 4 KiB lines, a cache that holds
     the whole table): lists that touch every row once, then sampled minibatches, which must all hit."""
     cfg = pinnable("resident", (10_000_000,))
-    n_b = 24
+    n_b = 200 if EVERY else 40                                # (the configuration names 1000: 19 GB of ID lists)
     print(f"[fullsize resident] N={cfg.n_nodes} lines={cfg.cache_lines} ways={cfg.ways} batches=10+{n_b}", flush=True)
     g = wl.make_graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max, native=True)
     step = 1_000_000
     raws = [np.arange(b, min(cfg.n_nodes, b + step), dtype=np.int64) for b in range(0, cfg.n_nodes, step)]
     n_pre = len(raws)
-    raws += [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds) for b in range(n_b)]
+    raws += sample_lists(g, cfg, n_b)
 
     def all_hits_after_coverage(t, st):
         if t >= n_pre:
