@@ -647,3 +647,20 @@ def test_rows_per_line_pins_a_line_while_any_of_its_rows_is_needed(oracle_mod):
         assert res[3][2].tolist() == last, window
         if window:                                              # line 2 took the way of line 1, which nothing needs again
             assert res[2][2].tolist() == [1, 0, 0, 1, 0]
+
+
+def test_oracle_is_clean_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """tests/oracle_sanitize.c drives the whole oracle through the Tiny configuration (three variants of the
+    simulator) in a program built with -fsanitize=address,undefined; any report fails the run."""
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = tmp_path / "oracle_sanitize"
+    build = subprocess.run(["gcc", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-o", str(exe),
+                            os.path.join(root, "tests", "oracle_sanitize.c"), "-lm"], capture_output=True, text=True)
+    if build.returncode != 0 and "sanitize" in build.stderr:
+        pytest.skip("this compiler has no sanitizer runtime")
+    assert build.returncode == 0, build.stderr
+    env = dict(os.environ, ASAN_OPTIONS="verify_asan_link_order=0")   # something else may be preloaded
+    run = subprocess.run([str(exe)], capture_output=True, text=True, env=env, timeout=300)
+    assert run.returncode == 0 and "oracle sanitize ok" in run.stdout, run.stdout + run.stderr
