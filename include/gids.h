@@ -42,8 +42,10 @@
  *     match the buffered window head, an output buffer too small) cannot be
  *     returned by the enqueueing call.  The failing operation changes nothing,
  *     the error is recorded in that minibatch's gids_stats.status, and it is
- *     sticky: once the host has seen it (gids_stats_read, gids_flush) every
- *     later call on the cache returns it.
+ *     sticky: once the host has seen it (gids_stats_read, or any later
+ *     push, gather or flush called after the failing gather finished) every
+ *     later call on the cache returns it.  A HIP runtime failure in the middle
+ *     of a push or gather closes the cache the same way (GIDS_E_HIP).
  */
 #ifndef GIDS_H
 #define GIDS_H
@@ -186,7 +188,10 @@ int gids_window_push(gids_cache* cache, const void* ids_dev, uint64_t n, void* s
  * never learns.  n_max bounds the work and sizes the window slot. */
 int gids_window_push_dev(gids_cache* cache, const void* ids_dev, uint64_t n_max, const uint32_t* n_dev, void* stream);
 
-/* Gather one minibatch.
+/* Gather one minibatch: feature aggregation as Section 2.2.3 defines it (the
+ * feature rows of the sampled nodes, collected into one minibatch buffer in
+ * GPU memory), served through the cache of Section 3.4 and the CPU buffer of
+ * Section 3.3.
  *   ids_dev, n       the raw ID list.  When a list is buffered (always the
  *                    case with window_depth > 0; after a push with
  *                    window_depth == 0) it must have the same distinct IDs as
@@ -206,11 +211,17 @@ int gids_window_push_dev(gids_cache* cache, const void* ids_dev, uint64_t n_max,
 int gids_gather(gids_cache* cache, const void* ids_dev, uint64_t n, void* out_dev, uint64_t out_capacity_rows,
                 void* unique_dev, void* inverse_dev, void* stream);
 
-/* Move every queued row now.  After the stream reaches the end of this call's
- * work the output of every earlier gather is complete.  Does not block. */
+/* The accumulator's forced launch (Section 3.2: accesses merged over several
+ * minibatches go out in one launch; this is the launch without waiting for
+ * the threshold).  Moves every queued row now: after the stream reaches the
+ * end of this call's work the output of every earlier gather is complete.
+ * Does not block.  Returns the error of an earlier gather if the device has
+ * reported one by now (the rows of a failed gather are never moved). */
 int gids_flush(gids_cache* cache, void* stream);
 
-/* Wait for gather number `seq` (0-based) to finish on the device and return
+/* Hit, CPU-buffer and miss counts per minibatch (the quantities behind the
+ * hit ratios of Section 4.5 and the redirected share of Section 4.4).
+ * Waits for gather number `seq` (0-based) to finish on the device and returns
  * its counters.  Only the most recent 64 gathers are kept.  Returns
  * stats->status. */
 int gids_stats_read(gids_cache* cache, uint64_t seq, gids_stats* stats);

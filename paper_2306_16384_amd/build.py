@@ -36,10 +36,27 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def stale() -> bool:
+    """True when the library is missing or older than any of its sources."""
+    if not os.path.exists(LIB):
+        return True
+    built = os.path.getmtime(LIB)
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".h"))]
+    deps.append(os.path.join(os.path.dirname(HERE), "include", "gids.h"))
+    return any(os.path.getmtime(d) > built for d in deps)
+
+
 def ensure_built() -> str:
-    """Build only when no library is there yet (tests, smoke and the benchmark call this;
-    after editing a source, call build() yourself)."""
-    return LIB if os.path.exists(LIB) else build()
+    """Build when no library is there yet or a source is newer than it (tests, the smoke check and the
+    benchmark call this).  A machine without hipcc uses the library it was given."""
+    if stale():
+        import shutil
+        if shutil.which("hipcc") is None:
+            if os.path.exists(LIB):
+                return LIB
+            raise RuntimeError("libgids.so is missing and hipcc is not on PATH")
+        return build()
+    return LIB
 
 
 if __name__ == "__main__":

@@ -132,6 +132,18 @@ struct gids_cache {
         HIP_TRY(hipStreamWaitEvent(to, e, 0));
         return GIDS_OK;
     }
+    // An error a kernel found stays in the device control block, so the record of the newest finished gather
+    // carries it: calls that enqueue work look there first and refuse once the host can know.
+    void poll_status() {
+        if (sticky || !ring_host) return;
+        for (uint64_t g = seq; g-- > 0 && seq - g <= (uint64_t)STATS_RING;) {
+            const StatsRec& rec = ring_host[g % STATS_RING];
+            if (*reinterpret_cast<const volatile uint64_t*>(&rec.seq) != g) continue;   // not finished yet
+            const int32_t st = *reinterpret_cast<const volatile int32_t*>(&rec.status);
+            if (st) sticky = st;
+            return;
+        }
+    }
     int move_blocks = 1 << 20;  // most workgroups the row mover uses for rows that stay in HBM
     int link_blocks = 48;       // ... for rows that cross the host link (persistent)
     bool wide_index = false;    // GIDS_WIDE_INDEX=1: 64-bit set arithmetic even where 32 bits would do (for tests)
@@ -423,6 +435,15 @@ struct CacheT final : gids_cache {
         int rc = ensure_slot(sl, n);
         if (rc) return rc;
         sl.n_raw = n;
+        // From here on kernels of this push may already be queued when a later HIP call fails: the device
+        // state would then be ahead of the host's bookkeeping, so such a failure closes the cache.
+        if ((rc = push_enqueue(static_cast<const IdT*>(ids), n, n_dev, slot, s))) sticky = rc;
+        return rc;
+    }
+
+    int push_enqueue(const IdT* ids, uint64_t n, const uint32_t* n_dev, uint32_t slot, hipStream_t s) {
+        WindowSlot& sl = slots[slot];
+        int rc;
         if ((rc = follow(s))) return rc;
         hipStream_t m = s;
         if (pipelined) {
@@ -431,7 +452,7 @@ struct CacheT final : gids_cache {
             if (sl.last_reader >= 0) HIP_TRY(hipStreamWaitEvent(meta, events[sl.last_reader % STATS_RING], 0));
             if ((rc = edge(s, meta))) return rc;              // the caller's IDs are ready in its stream's order
         }
-        dedup(static_cast<const IdT*>(ids), n, static_cast<IdT*>(sl.ids), &ctl->win_n[slot], reuse, false, m, n_dev);
+        dedup(ids, n, static_cast<IdT*>(sl.ids), &ctl->win_n[slot], reuse, false, m, n_dev);
         if (pipelined && (rc = edge(meta, s))) return rc;     // the caller may reuse its ID buffer in stream order
         HIP_TRY(hipGetLastError());                           // a kernel launch that was refused
         sl.last_reader = -1;
@@ -453,7 +474,14 @@ struct CacheT final : gids_cache {
         int rc = ensure_scratch(head_list ? std::max(n, slots[head].n_raw) : n);
         if (rc) return rc;
         if (inverse && !wrank && (rc = dev_alloc(&wrank, n_words))) return rc;
+        // (as in push: a HIP failure once kernels may be queued closes the cache)
+        if ((rc = gather_enqueue(ids, n, head_list, out, out_cap, unique, inverse, s))) sticky = rc;
+        return rc;
+    }
 
+    int gather_enqueue(const IdT* ids, uint64_t n, bool head_list, void* out, uint64_t out_cap, void* unique,
+                       void* inverse, hipStream_t s) {
+        int rc;
         const int r = (int)(seq % STATS_RING);
         const int par = (int)(seq & 1);
         if ((rc = follow(s))) return rc;
@@ -531,6 +559,12 @@ struct CacheT final : gids_cache {
 
     int flush(hipStream_t s) override {
         if (!threshold) return GIDS_OK;
+        int rc = flush_enqueue(s);
+        if (rc) sticky = rc;
+        return rc;
+    }
+
+    int flush_enqueue(hipStream_t s) {
         const int rc = follow(s);
         if (rc) return rc;
         launch_flush<IdT>(view(), fills, copies, threshold, true, (int)std::min<uint64_t>(queue_cap, 1u << 30), s);
@@ -777,7 +811,8 @@ int gids_cache_destroy(gids_cache* cache) {
 #define CHECK_CACHE(c)                                                         \
     if (!(c)) return fail(GIDS_E_INVAL, "%s: cache is NULL", __func__);        \
     if (!on_device((c)->store->device)) return fail(GIDS_E_INVAL, "%s: the current device is not the one the store was created on", __func__); \
-    if ((c)->sticky) return fail((c)->sticky, "%s: an earlier operation on this cache failed on the device (%d)", __func__, (c)->sticky)
+    (c)->poll_status();                                                        \
+    if ((c)->sticky) return fail((c)->sticky, "%s: an earlier operation on this cache failed (%d)", __func__, (c)->sticky)
 
 int gids_cache_reserve(gids_cache* cache, uint64_t max_ids) {
     CHECK_CACHE(cache);

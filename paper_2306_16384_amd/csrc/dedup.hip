@@ -145,8 +145,11 @@ __global__ __launch_bounds__(DD_THREADS) void emit_kernel(uint64_t* __restrict__
         uint64_t x = w[k];
         if (!x) continue;
         if (wrank) wrank[w0 + k] = pos;
-        if (ok) {
-            // four set bits at a time: their counter updates are independent (the IDs are distinct, no two
+        {
+            // The list is written even when an error is pending (only valid IDs ever set a bit, and dst holds
+            // every distinct ID of the raw list): the kernels that clear a kept bitmap find its words through
+            // it.  What a failed operation must not change is the future-reuse counters.
+            // Four set bits at a time: their counter updates are independent (the IDs are distinct, no two
             // threads share a byte), so the four loads go out together instead of one round trip per ID
             while (x) {
                 uint64_t v[4];
@@ -160,7 +163,7 @@ __global__ __launch_bounds__(DD_THREADS) void emit_kernel(uint64_t* __restrict__
                         m = u + 1;
                     }
                 }
-                if (reuse_inc) {
+                if (reuse_inc && ok) {
 #pragma unroll
                     for (int u = 0; u < 4; u++)
                         if (u < m) r[u] = reuse_inc[v[u]];

@@ -299,6 +299,34 @@ def test_device_found_errors(gpu, oracle_mod):
         with pytest.raises(gids.GidsError) as e:                # sticky afterwards
             s.gather(s.to_device([1]), out)
         assert e.value.code == gids.GIDS_E_RANGE
+    # the same while the inverse map is asked for: the bitmap is kept beyond the emit kernel and cleared through
+    # the distinct-ID list, which therefore has to be written even for a list that fails
+    with fresh(0) as s:
+        inv = torch.zeros(8, dtype=torch.int32, device="cuda")
+        uq = torch.zeros(8, dtype=torch.int64, device="cuda")
+        seq = s.gather(s.to_device([1, 100, 5, 99, -3]), out, uq, inv)
+        with pytest.raises(gids.GidsError) as e:
+            s.stats(seq)
+        assert e.value.code == gids.GIDS_E_RANGE
+        assert bool((out == 0).all()) and bool((inv == 0).all())
+        with pytest.raises(gids.GidsError) as e:                # sticky afterwards
+            s.gather(s.to_device([1]), out)
+        assert e.value.code == gids.GIDS_E_RANGE
+    with fresh(1) as s:                                         # ... and a list that is not the window head
+        inv = torch.zeros(8, dtype=torch.int32, device="cuda")
+        s.push(s.to_device([1, 2]))
+        seq = s.gather(s.to_device([3, 4, 3]), out, None, inv)
+        with pytest.raises(gids.GidsError) as e:
+            s.stats(seq)
+        assert e.value.code == gids.GIDS_E_ORDER
+        assert bool((out == 0).all())
+    # a device error reaches a caller that never reads counters: the next call after the gather has finished
+    with fresh(0) as s:
+        s.gather(s.to_device([1, 100]), out)
+        torch.cuda.synchronize()
+        with pytest.raises(gids.GidsError) as e:
+            s.flush()
+        assert e.value.code == gids.GIDS_E_RANGE
     # more distinct IDs than output rows
     with fresh(0) as s:
         seq = s.gather(s.to_device(np.arange(9)), out)
