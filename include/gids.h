@@ -211,6 +211,28 @@ int gids_window_push_dev(gids_cache* cache, const void* ids_dev, uint64_t n_max,
 int gids_gather(gids_cache* cache, const void* ids_dev, uint64_t n, void* out_dev, uint64_t out_capacity_rows,
                 void* unique_dev, void* inverse_dev, void* stream);
 
+/* The same gather for callers that cannot allocate device memory: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * gids_gather keeps its per-minibatch buffers (plan, ID scratch, headers) in
+ * device memory it sizes on demand; this entry point keeps them in a fixed
+ * array inside the library instead (32 MiB + 256 B per GPU, held from the
+ * moment the library is loaded on that GPU until the process ends) and calls no
+ * allocating routine.  Arguments and results are those of gids_gather without
+ * the inverse map.  Limits: the raw list (and, when a buffered list is gathered,
+ * the list that was pushed) has at most GIDS_STATIC_MAX_IDS entries, else
+ * GIDS_E_INVAL; not on a cache with accum_threshold > 0 (its queues grow on
+ * demand).  Lists a window buffers are still stored by gids_window_push, which
+ * allocates when a list is longer than any before: call gids_cache_reserve
+ * first.  Every call on a GPU, from whichever cache, shares the one array, and
+ * the array keeps the last call's contents (nothing in it has to start at
+ * zero: each call writes every entry it reads): calls on one cache order
+ * themselves like gids_gather's and may be mixed with them, but calls on
+ * different caches of one GPU race unless the stream of the earlier one has
+ * been synchronised before the later one is made. */
+#define GIDS_STATIC_MAX_IDS (1u << 20)
+int gids_gather_static(gids_cache* cache, const void* ids_dev, uint64_t n, void* out_dev, uint64_t out_capacity_rows,
+                       void* unique_dev, void* stream);
+
 /* The accumulator's forced launch (Section 3.2: accesses merged over several
  * minibatches go out in one launch; this is the launch without waiting for
  * the threshold).  Moves every queued row now: after the stream reaches the

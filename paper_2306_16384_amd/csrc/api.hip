@@ -6,6 +6,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <thread>
 #include <vector>
@@ -42,6 +43,36 @@ int fail(int code, const char* fmt, ...) {
     } while (0)
 
 constexpr int STATS_RING = 64;
+
+// Workspace of gids_gather_static, the gather for callers that must not allocate: what gids_gather keeps in
+// buffers it sizes with hipMalloc (the two gather headers, and per parity the plan and the ID scratch, laid out
+// for 8-byte IDs) lives in this array instead.  Each GPU holds its own copy at its own address; host code uses
+// the address hipGetSymbolAddress returned for the device, never the array's name.
+constexpr uint64_t STATIC_MAX_IDS = GIDS_STATIC_MAX_IDS;
+constexpr uint64_t STATIC_HDR_BYTES = 256;
+constexpr uint64_t STATIC_BYTES = STATIC_HDR_BYTES + 4 * STATIC_MAX_IDS * sizeof(uint64_t);
+static __device__ __align__(256) unsigned char scratch[STATIC_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+std::mutex g_scratch_mutex;
+
+// address of `scratch` on the current device (looked up once per device, with that device current)
+int static_workspace(int device, void** out) {
+    if (device < 0 || device >= MAX_DEVICES) return GIDS_E_INVAL;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return GIDS_E_HIP;
+        }
+        g_scratch_ptr[device] = p;
+    }
+    *out = g_scratch_ptr[device];
+    return GIDS_OK;
+}
 
 bool on_device(int device) {
     int cur = -1;
@@ -91,7 +122,7 @@ struct gids_cache {
     virtual int pin(const void* ids_host, uint64_t n) = 0;
     virtual int push(const void* ids, uint64_t n, const uint32_t* n_dev, hipStream_t s) = 0;
     virtual int gather(const void* ids, uint64_t n, void* out, uint64_t out_cap, void* unique, void* inverse,
-                       hipStream_t s) = 0;
+                       bool no_alloc, hipStream_t s) = 0;
     virtual int flush(hipStream_t s) = 0;
     virtual int snapshot(int64_t* tags, int64_t* stamps) = 0;
     virtual uint32_t window_count() const = 0;
@@ -104,6 +135,7 @@ struct gids_cache {
     uint32_t policy = 0;            // GIDS_POLICY_*
     uint32_t rows_per_line = 1;     // node rows one cache line holds
     uint64_t policy_key = 0;
+    void* static_ws = nullptr;      // this device's copy of the static workspace (gids_gather_static)
     StatsRec* ring_host = nullptr;
     StatsRec* ring_dev = nullptr;
     hipEvent_t events[STATS_RING] = {};       // gather seq: its rows have moved (recorded on the caller's stream)
@@ -460,8 +492,15 @@ struct CacheT final : gids_cache {
         return GIDS_OK;
     }
 
+    // the per-gather buffers of one parity: the library's own, or their places in the static workspace
+    struct GatherBufs {
+        IdT* ub;
+        uint64_t* pl;
+        BatchHdr* hd;
+    };
+
     int gather(const void* ids_v, uint64_t n, void* out, uint64_t out_cap, void* unique, void* inverse,
-               hipStream_t s) override {
+               bool no_alloc, hipStream_t s) override {
         const IdT* ids = static_cast<const IdT*>(ids_v);
         if (!out && out_cap) return fail(GIDS_E_INVAL, "gids_gather: out_dev is NULL");
         if (inverse && !ids) return fail(GIDS_E_INVAL, "gids_gather: inverse_dev needs ids_dev");
@@ -471,19 +510,35 @@ struct CacheT final : gids_cache {
         const bool head_list = window != 0 || count != 0;
         if (!head_list && !ids && n) return fail(GIDS_E_INVAL, "gids_gather: ids_dev is NULL and no list was pushed to take it from");
         if (!ids) n = 0;
-        int rc = ensure_scratch(head_list ? std::max(n, slots[head].n_raw) : n);
-        if (rc) return rc;
-        if (inverse && !wrank && (rc = dev_alloc(&wrank, n_words))) return rc;
+        const uint64_t longest = head_list ? std::max(n, slots[head].n_raw) : n;
+        const int par = (int)(seq & 1);
+        GatherBufs b;
+        int rc;
+        if (no_alloc) {
+            if (threshold) return fail(GIDS_E_INVAL, "gids_gather_static: not on a cache with accum_threshold > 0 (its queues grow on demand)");
+            if (longest > STATIC_MAX_IDS) return fail(GIDS_E_INVAL, "gids_gather_static: a list of %llu IDs exceeds the static workspace (GIDS_STATIC_MAX_IDS = %llu)", (unsigned long long)longest, (unsigned long long)STATIC_MAX_IDS);
+            unsigned char* ws = static_cast<unsigned char*>(static_ws);
+            b.hd = reinterpret_cast<BatchHdr*>(ws) + par;
+            b.pl = reinterpret_cast<uint64_t*>(ws + STATIC_HDR_BYTES) + (uint64_t)par * STATIC_MAX_IDS;
+            b.ub = reinterpret_cast<IdT*>(ws + STATIC_HDR_BYTES + (2 + (uint64_t)par) * STATIC_MAX_IDS * sizeof(uint64_t));
+        } else {
+            if ((rc = ensure_scratch(longest))) return rc;
+            if (inverse && !wrank && (rc = dev_alloc(&wrank, n_words))) return rc;
+            b.hd = hdr + par; b.pl = plan[par]; b.ub = ubuf[par];
+        }
         // (as in push: a HIP failure once kernels may be queued closes the cache)
-        if ((rc = gather_enqueue(ids, n, head_list, out, out_cap, unique, inverse, s))) sticky = rc;
+        const bool was_profiling = profile;
+        if (no_alloc) profile = false;                        // phase events are created on first use
+        rc = gather_enqueue(ids, n, head_list, b, out, out_cap, unique, inverse, s);
+        profile = was_profiling;
+        if (rc) sticky = rc;
         return rc;
     }
 
-    int gather_enqueue(const IdT* ids, uint64_t n, bool head_list, void* out, uint64_t out_cap, void* unique,
-                       void* inverse, hipStream_t s) {
+    int gather_enqueue(const IdT* ids, uint64_t n, bool head_list, const GatherBufs& b, void* out, uint64_t out_cap,
+                       void* unique, void* inverse, hipStream_t s) {
         int rc;
         const int r = (int)(seq % STATS_RING);
-        const int par = (int)(seq & 1);
         if ((rc = follow(s))) return rc;
         hipStream_t m = s;
         if (pipelined) {
@@ -499,13 +554,13 @@ struct CacheT final : gids_cache {
         const uint32_t* n_u;
         uint64_t n_upper;
         if (ids || !head_list) {                              // (an empty list without a window still sets the count)
-            dedup(ids, n, ubuf[par], &ctl->n_unique, nullptr, inverse != nullptr, m);
+            dedup(ids, n, b.ub, &ctl->n_unique, nullptr, inverse != nullptr, m);
             if (head_list)
-                launch_verify<IdT>(ubuf[par], static_cast<const IdT*>(slots[head].ids), &ctl->win_n[head], ctl,
+                launch_verify<IdT>(b.ub, static_cast<const IdT*>(slots[head].ids), &ctl->win_n[head], ctl,
                                    std::min(n, slots[head].n_raw), m);
             if (inverse) {
                 launch_inverse<IdT>(ids, n, bitmap, wrank, static_cast<uint32_t*>(inverse), ctl, m);
-                launch_clear<IdT>(bitmap, ubuf[par], &ctl->n_unique, n, m);
+                launch_clear<IdT>(bitmap, b.ub, &ctl->n_unique, n, m);
             }
         }
         if (head_list) {                                      // the buffered head list is the minibatch
@@ -513,16 +568,16 @@ struct CacheT final : gids_cache {
             n_u = &ctl->win_n[head];
             n_upper = slots[head].n_raw;
         } else {
-            U = ubuf[par];
+            U = b.ub;
             n_u = &ctl->n_unique;
             n_upper = n;
         }
         n_upper = std::min<uint64_t>(n_upper, store->n_rows);
         const CacheView<IdT> c = view();
         if ((rc = mark_phase(r, 1, m))) return rc;
-        launch_probe<IdT>(c, U, n_u, n_upper, out_cap, head_list, plan[par], m);
-        launch_victim<IdT>(c, U, n_u, n_upper, plan[par], m);
-        launch_commit<IdT>(c, U, n_u, n_upper, plan[par], hdr + par, m);
+        launch_probe<IdT>(c, U, n_u, n_upper, out_cap, head_list, b.pl, m);
+        launch_victim<IdT>(c, U, n_u, n_upper, b.pl, m);
+        launch_commit<IdT>(c, U, n_u, n_upper, b.pl, b.hd, m);
         if (threshold == 0) {
             launch_finalize(ctl, ring_dev + r, seq, n_u, m);
             if ((rc = mark_phase(r, 2, m))) return rc;
@@ -531,13 +586,13 @@ struct CacheT final : gids_cache {
                 HIP_TRY(hipStreamWaitEvent(s, ev_meta[r], 0));
             }
             if ((rc = mark_phase(r, 3, s))) return rc;
-            launch_move<IdT>(c, U, hdr + par, n_upper, plan[par], static_cast<char*>(out), static_cast<IdT*>(unique),
+            launch_move<IdT>(c, U, b.hd, n_upper, b.pl, static_cast<char*>(out), static_cast<IdT*>(unique),
                              move_blocks, link_blocks, s);
             if ((rc = mark_phase(r, 4, s))) return rc;
         } else {
             if ((rc = mark_phase(r, 2, s))) return rc;
             if ((rc = mark_phase(r, 3, s))) return rc;
-            launch_queue<IdT>(c, U, hdr + par, n_upper, plan[par], static_cast<char*>(out), static_cast<IdT*>(unique),
+            launch_queue<IdT>(c, U, b.hd, n_upper, b.pl, static_cast<char*>(out), static_cast<IdT*>(unique),
                               fills, copies, move_blocks, s);
             upper_since[r] = (uint32_t)n_upper;
             if (pending_bound() + n_upper >= threshold)
@@ -799,6 +854,8 @@ int gids_cache_create(gids_store* store, uint64_t lines, uint32_t ways, uint32_t
     while ((1u << c->lg_ways) < ways) c->lg_ways++;
     const int rc = c->init();
     if (rc) { delete c; return rc; }
+    // the static workspace's address on this device; a failure here only disables gids_gather_static
+    if (static_workspace(store->device, &c->static_ws) != GIDS_OK) c->static_ws = nullptr;
     *out = c;
     return GIDS_OK;
 }
@@ -842,7 +899,15 @@ int gids_gather(gids_cache* cache, const void* ids_dev, uint64_t n, void* out_de
                 void* unique_dev, void* inverse_dev, void* stream) {
     CHECK_CACHE(cache);
     if (n > 0xFFFFFFF0ull) return fail(GIDS_E_INVAL, "gids_gather: list too long");
-    return cache->gather(ids_dev, n, out_dev, out_capacity_rows, unique_dev, inverse_dev, static_cast<hipStream_t>(stream));
+    return cache->gather(ids_dev, n, out_dev, out_capacity_rows, unique_dev, inverse_dev, false, static_cast<hipStream_t>(stream));
+}
+
+int gids_gather_static(gids_cache* cache, const void* ids_dev, uint64_t n, void* out_dev, uint64_t out_capacity_rows,
+                       void* unique_dev, void* stream) {
+    CHECK_CACHE(cache);
+    if (n > STATIC_MAX_IDS) return fail(GIDS_E_INVAL, "gids_gather_static: a list of %llu IDs exceeds the static workspace (GIDS_STATIC_MAX_IDS = %llu)", (unsigned long long)n, (unsigned long long)STATIC_MAX_IDS);
+    if (!cache->static_ws) return fail(GIDS_E_HIP, "gids_gather_static: the static workspace of this device could not be located when the cache was created");
+    return cache->gather(ids_dev, n, out_dev, out_capacity_rows, unique_dev, nullptr, true, static_cast<hipStream_t>(stream));
 }
 
 int gids_cache_set_policy(gids_cache* cache, int policy, uint64_t seed) {
