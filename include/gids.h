@@ -71,10 +71,11 @@ typedef struct gids_cache gids_cache;
 /* Per-minibatch counters (the paper's reported quantity is the hit ratio,
  * Section 4.5).  n_hit + n_cpu_hit + n_miss == n_unique.  n_bypass (a subset of
  * n_miss) counts misses that found no evictable line and were served from the
- * store without being installed.  n_pending = fills still queued in the
- * accumulator when the gather's kernels ended; `flushed` is 1 when every row
- * of this minibatch's output was written by the end of the gather call's own
- * work on the stream, 0 when some await a later flush.  n_line_fills = cache
+ * store without being installed.  With the accumulator, n_pending = rows (of
+ * this and earlier minibatches) still queued in the open group when the gather
+ * call's own work ends, and `flushed` is 1 when this gather closed its group,
+ * i.e. when every row of its output and of the earlier queued ones has been
+ * written by then; without it they are 0 and 1.  n_line_fills = cache
  * lines this minibatch fills from the store: n_miss - n_bypass with one row
  * per line, fewer when several missing rows share a line. */
 typedef struct gids_stats {
@@ -124,16 +125,46 @@ int gids_store_calibrate(gids_store* store, double* rows_per_s, double* overhead
  *                  is not evicted.  W = 0: no window, plain LRU by minibatch
  *                  (or the policy set with gids_cache_set_policy).
  *   accum_threshold  0: every gather moves its own rows before it ends.
- *                  > 0: rows that must cross the host link are queued and moved
- *                  once at least this many are pending (or at gids_flush); the
- *                  counters and the final contents of every output are the same
- *                  for any threshold.
+ *                  > 0: the storage access accumulator of Section 3.2.
+ *                  Consecutive gathers are merged into a group until the node
+ *                  accesses they bring (entries of their raw ID lists) reach
+ *                  this number; a gather only classifies its minibatch and
+ *                  queues its rows, and when the group closes the rows of all
+ *                  its minibatches move in one launch (two, when some copies
+ *                  depend on others).  A group also closes after
+ *                  GIDS_ACCUM_MAX_MERGE gathers and at gids_flush.  The
+ *                  counters and the final contents of every output are the
+ *                  same for any threshold; what changes is when an output is
+ *                  complete (gids_stats.flushed, gids_flush).  See
+ *                  gids_cache_set_accum_mode for the adaptive threshold.
  * Device memory taken: lines * line_bytes for the data plus about
  * 12-16 bytes per line, n_rows / 8 * 3 bytes of bitmaps and n_rows bytes of
  * reuse counters. */
 int gids_cache_create(gids_store* store, uint64_t lines, uint32_t ways, uint32_t line_bytes,
                       uint32_t window_depth, uint64_t accum_threshold, gids_cache** out);
 int gids_cache_destroy(gids_cache* cache);
+
+/* How the accumulator's threshold is read (call before the first gather).
+ * GIDS_ACCUM_FIXED (default): accum_threshold counts node accesses.
+ * GIDS_ACCUM_ADAPTIVE: accum_threshold is the number of accesses that should
+ * reach the backing store per launch (N of Eq. 2-3, see gids_accum_threshold
+ * and gids_store_calibrate), and the library raises the node-access threshold
+ * by the share of accesses that the GPU cache and the CPU buffer take away
+ * (Section 3.2, last paragraph): with A node accesses and S store accesses
+ * (misses) counted over every gather at least GIDS_ACCUM_LAG calls back,
+ *   threshold = clamp(ceil(accum_threshold * A / S), accum_threshold,
+ *                     GIDS_ACCUM_MAX_RAISE * accum_threshold)
+ * (accum_threshold while A == 0, the upper bound while S == 0).  The fixed lag
+ * makes the grouping a pure function of the ID lists; a gather call waits for
+ * the counters of the gather GIDS_ACCUM_LAG + 1 calls back if the device has
+ * not produced them yet.  For lists pushed with gids_window_push_dev a node
+ * access count is the list's n_max. */
+#define GIDS_ACCUM_FIXED 0
+#define GIDS_ACCUM_ADAPTIVE 1
+#define GIDS_ACCUM_MAX_MERGE 32
+#define GIDS_ACCUM_LAG 16
+#define GIDS_ACCUM_MAX_RAISE 8
+int gids_cache_set_accum_mode(gids_cache* cache, int mode);
 
 /* Base replacement policy, i.e. the order in which the evictable ways of a set
  * are given to misses (window pinning applies to both; call before the first
@@ -206,8 +237,10 @@ int gids_window_push_dev(gids_cache* cache, const void* ids_dev, uint64_t n_max,
  *                    distinct IDs, ascending
  *   inverse_dev      NULL, or n uint32: inverse_dev[i] = j with
  *                    unique[j] == ids_dev[i] (requires ids_dev)
- * With accum_threshold > 0 the output buffers of gathers not yet flushed must
- * stay untouched until they are (stats.flushed / gids_flush). */
+ * With accum_threshold > 0 the output buffers (out_dev, unique_dev) of gathers
+ * whose group has not closed must stay untouched until it has (stats.flushed
+ * of a later gather / gids_flush); they are complete in stream order after
+ * the call that closes the group. */
 int gids_gather(gids_cache* cache, const void* ids_dev, uint64_t n, void* out_dev, uint64_t out_capacity_rows,
                 void* unique_dev, void* inverse_dev, void* stream);
 

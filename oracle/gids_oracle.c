@@ -19,7 +19,9 @@
  *     count is positive are in the "USE" state and are not evicted, count 0 is
  *     "safe to evict" (Section 3.4, Fig. 6 steps 1-5);
  *   - the overlapped-access model N = r/(1-r) * IOPS * (Ti + Tt) (Section 3.2,
- *     Eq. 2-3);
+ *     Eq. 2-3), and the accumulator that merges minibatches until their node
+ *     accesses reach a threshold, fixed or raised by the redirected share
+ *     (Section 3.2);
  *   - the random base policy of the cache the paper builds on (Section 3.4),
  *     seeded; cache lines that hold several node rows (4 KB cache-lines,
  *     Section 3.3, under rows of 512 B and more, Section 2.1);
@@ -370,6 +372,12 @@ typedef struct {
     int32_t policy; uint64_t policy_seed;
     /* node rows per cache line (1 unless go_sim_set_rows_per_line): line `b` of the store = rows b*P .. b*P+P-1 */
     int64_t rows_per_line;
+    /* storage access accumulator (Section 3.2): minibatches are merged until their node accesses reach a
+     * threshold; acc_* describe the open group, hist_* every gather so far, last_* the latest gather */
+    int64_t acc_threshold; int32_t acc_mode;
+    int64_t acc_nodes, acc_rows; int32_t acc_batches;
+    int64_t* hist_nodes; int64_t* hist_store; int64_t hist_cap;
+    int64_t last_pending, last_flushed, last_limit;
 } go_sim;
 
 void go_sim_free(go_sim* s) {
@@ -377,6 +385,7 @@ void go_sim_free(go_sim* s) {
     for (int i = 0; i < s->win_count; i++) free(s->win_ids[i]);
     free(s->win_ids); free(s->win_n);
     free(s->tag); free(s->stamp); free(s->reuse); free(s->hot_slot); free(s->cache_data); free(s->cpu_buf);
+    free(s->hist_nodes); free(s->hist_store);
     free(s);
 }
 
@@ -442,6 +451,81 @@ int go_sim_set_policy(go_sim* s, int32_t policy, uint64_t seed) {
     if (s->t || (policy != 0 && policy != 1)) return GO_E_INVAL;
     s->policy = policy; s->policy_seed = seed;
     return GO_OK;
+}
+
+/* ------------------------------------------------------------ accumulator */
+
+enum { GO_ACC_MAX_MERGE = 32, GO_ACC_LAG = 16, GO_ACC_MAX_RAISE = 8 };
+
+/* Section 3.2.  The dataloader keeps merging the data preparation of consecutive iterations until the number
+ * of node accesses passes a threshold; then the merged accesses are issued together.  The paper counts "node
+ * accesses" per iteration (the sampler's output) and says that the threshold follows the number of accesses
+ * that are redirected to CPU / GPU memory; it gives no formula for that.  Reading taken here:
+ *   - a node access is one entry of a minibatch's raw ID list;
+ *   - mode 0: the threshold is the given number N of node accesses;
+ *   - mode 1: N is the number of accesses that should reach the store (Eq. 2-3's N_access), and the
+ *     node-access threshold is N scaled by node accesses per store access, A / S, where A and S add up the
+ *     raw list lengths and the misses of every gather at least GO_ACC_LAG gathers back (the redirected ones
+ *     are the rest); bounded to [N, GO_ACC_MAX_RAISE * N]; N while nothing has been counted yet, the upper
+ *     bound while no access has reached the store;
+ *   - a group also closes after GO_ACC_MAX_MERGE minibatches (the paper: merging too many iterations costs
+ *     buffer memory) and when go_sim_flush asks for it.
+ * While a group is open the rows of its minibatches wait: pending = distinct IDs of the open group's
+ * minibatches; the gather that closes the group reports flushed = 1 and pending = 0.  None of this touches
+ * tags, counters or rows. */
+int go_sim_set_accum(go_sim* s, int64_t threshold, int32_t mode) {
+    if (s->t || threshold < 0 || (mode != 0 && mode != 1)) return GO_E_INVAL;
+    s->acc_threshold = threshold; s->acc_mode = mode;
+    return GO_OK;
+}
+
+static int64_t accum_limit(const go_sim* s, int64_t t) {
+    const int64_t N = s->acc_threshold;
+    if (s->acc_mode == 0) return N;
+    int64_t A = 0, S = 0;
+    for (int64_t i = 0; i + GO_ACC_LAG < t; i++) { A += s->hist_nodes[i]; S += s->hist_store[i]; }
+    if (A == 0) return N;
+    if (S == 0) return GO_ACC_MAX_RAISE * N;
+    unsigned __int128 want = ((unsigned __int128)N * (uint64_t)A + (uint64_t)S - 1) / (uint64_t)S;   /* ceil(N * A / S) */
+    if (want > (unsigned __int128)(GO_ACC_MAX_RAISE * N)) return GO_ACC_MAX_RAISE * N;
+    return (int64_t)want < N ? N : (int64_t)want;
+}
+
+/* bookkeeping of gather t: n_raw node accesses, n_unique rows, n_miss store accesses */
+static int accum_step(go_sim* s, int64_t t, int64_t n_raw, int64_t n_unique, int64_t n_miss) {
+    if (t >= s->hist_cap) {
+        int64_t cap = s->hist_cap ? 2 * s->hist_cap : 256;
+        int64_t* a = (int64_t*)realloc(s->hist_nodes, (size_t)cap * sizeof(int64_t));
+        if (!a) return GO_E_NOMEM;
+        s->hist_nodes = a;
+        int64_t* b = (int64_t*)realloc(s->hist_store, (size_t)cap * sizeof(int64_t));
+        if (!b) return GO_E_NOMEM;
+        s->hist_store = b; s->hist_cap = cap;
+    }
+    s->hist_nodes[t] = n_raw; s->hist_store[t] = n_miss;
+    if (s->acc_threshold == 0) { s->last_pending = 0; s->last_flushed = 1; s->last_limit = 0; return GO_OK; }
+    s->last_limit = accum_limit(s, t);
+    s->acc_nodes += n_raw; s->acc_rows += n_unique; s->acc_batches++;
+    if (s->acc_nodes >= s->last_limit || s->acc_batches >= GO_ACC_MAX_MERGE) {
+        s->acc_nodes = s->acc_rows = 0; s->acc_batches = 0;
+        s->last_flushed = 1;
+    } else {
+        s->last_flushed = 0;
+    }
+    s->last_pending = s->acc_rows;
+    return GO_OK;
+}
+
+/* close the open group now; returns the rows that were waiting */
+int64_t go_sim_flush(go_sim* s) {
+    int64_t rows = s->acc_rows;
+    s->acc_nodes = s->acc_rows = 0; s->acc_batches = 0;
+    return rows;
+}
+
+/* {rows pending after the latest gather, 1 if it closed its group, the node-access threshold it was held to} */
+void go_sim_accum_last(const go_sim* s, int64_t* out3) {
+    out3[0] = s->last_pending; out3[1] = s->last_flushed; out3[2] = s->last_limit;
 }
 
 static int ids_in_range(const go_sim* s, const int64_t* raw, int64_t n) {
@@ -598,6 +682,7 @@ int64_t go_sim_gather(go_sim* s, const int64_t* raw, int64_t n, int64_t* unique_
     if (cls_out) memcpy(cls_out, cls, (size_t)m * sizeof(int32_t));
     if (stats) { stats[0] = m; stats[1] = hits; stats[2] = cpu_hits; stats[3] = misses; stats[4] = bypasses; }
     free(miss); free(src_line); free(cls); free(vict);
+    if (accum_step(s, t, n, m, misses) != GO_OK) return GO_E_NOMEM;
     s->t = t + 1;
     return m;
 }

@@ -69,6 +69,10 @@ def lib() -> C.CDLL:
         L.go_sim_set_hot.argtypes = [C.c_void_p, _i64p, C.c_int64]
         L.go_sim_set_policy.argtypes = [C.c_void_p, C.c_int32, C.c_uint64]
         L.go_sim_set_rows_per_line.argtypes = [C.c_void_p, C.c_int64]
+        L.go_sim_set_accum.argtypes = [C.c_void_p, C.c_int64, C.c_int32]
+        L.go_sim_flush.restype = C.c_int64
+        L.go_sim_flush.argtypes = [C.c_void_p]
+        L.go_sim_accum_last.argtypes = [C.c_void_p, _i64p]
         L.go_sim_push.argtypes = [C.c_void_p, _i64p, C.c_int64]
         L.go_sim_gather.restype = C.c_int64
         L.go_sim_gather.argtypes = [C.c_void_p, _i64p, C.c_int64, _i64p, C.c_void_p, _i64p, C.c_void_p]
@@ -214,6 +218,24 @@ class Sim:
         rc = lib().go_sim_set_rows_per_line(self._h, rows)
         if rc:
             raise OracleError(rc)
+
+    def set_accum(self, threshold: int, mode: int = 0) -> None:
+        """storage access accumulator: merge minibatches until `threshold` node accesses (mode 0), or until
+        the node accesses that bring `threshold` store accesses (mode 1)"""
+        rc = lib().go_sim_set_accum(self._h, threshold, mode)
+        if rc:
+            raise OracleError(rc)
+
+    def flush(self) -> int:
+        """close the open group; returns the rows that were waiting"""
+        return int(lib().go_sim_flush(self._h))
+
+    @property
+    def accum_last(self):
+        """(rows pending after the latest gather, whether it closed its group, its node-access threshold)"""
+        out = np.zeros(3, dtype=np.int64)
+        lib().go_sim_accum_last(self._h, out)
+        return int(out[0]), int(out[1]), int(out[2])
 
     def push(self, raw) -> None:
         raw = _ids(raw)

@@ -14,7 +14,7 @@ GIDS_E_INVAL, GIDS_E_NOMEM, GIDS_E_RANGE, GIDS_E_ORDER, GIDS_E_FULL, GIDS_E_HIP,
 
 EXPORTS = [
     "gids_store_create", "gids_store_host_ptr", "gids_store_destroy", "gids_store_calibrate", "gids_cache_create", "gids_cache_destroy",
-    "gids_cache_reserve", "gids_cache_set_policy", "gids_cpu_buffer_pin", "gids_window_push", "gids_gather", "gids_gather_static", "gids_flush", "gids_stats_read",
+    "gids_cache_reserve", "gids_cache_set_policy", "gids_cache_set_accum_mode", "gids_cpu_buffer_pin", "gids_window_push", "gids_gather", "gids_gather_static", "gids_flush", "gids_stats_read",
     "gids_cache_gathers", "gids_cache_snapshot", "gids_cache_set_rows_per_line", "gids_profile_enable", "gids_profile_read", "gids_window_push_dev",
     "gids_graph_create", "gids_graph_destroy", "gids_sample_capacity", "gids_sample", "gids_graph_visit_scores", "gids_graph_reverse_pagerank", "gids_accum_threshold", "gids_last_error",
 ]
@@ -58,6 +58,7 @@ def lib() -> C.CDLL:
         L.gids_cache_reserve.argtypes = [vp, u64]
         L.gids_cache_set_policy.argtypes = [vp, C.c_int, u64]
         L.gids_cache_set_rows_per_line.argtypes = [vp, u32]
+        L.gids_cache_set_accum_mode.argtypes = [vp, C.c_int]
         L.gids_cpu_buffer_pin.argtypes = [vp, vp, u64]
         L.gids_window_push.argtypes = [vp, vp, u64, vp]
         L.gids_gather.argtypes = [vp, vp, u64, vp, u64, vp, vp, vp]
@@ -130,6 +131,14 @@ GIDS_POLICY_LRU, GIDS_POLICY_RANDOM = 0, 1
 
 def gids_cache_set_policy(cache: int, policy: int, seed: int = 0) -> None:
     _check(lib().gids_cache_set_policy(cache, policy, seed))
+
+
+GIDS_ACCUM_FIXED, GIDS_ACCUM_ADAPTIVE = 0, 1
+GIDS_ACCUM_MAX_MERGE, GIDS_ACCUM_LAG, GIDS_ACCUM_MAX_RAISE = 32, 16, 8
+
+
+def gids_cache_set_accum_mode(cache: int, mode: int) -> None:
+    _check(lib().gids_cache_set_accum_mode(cache, mode))
 
 
 def gids_cache_set_rows_per_line(cache: int, rows: int) -> None:

@@ -43,6 +43,10 @@ int fail(int code, const char* fmt, ...) {
     } while (0)
 
 constexpr int STATS_RING = 64;
+constexpr uint32_t ACCUM_MAX_MERGE = GIDS_ACCUM_MAX_MERGE;
+constexpr uint32_t ACCUM_LAG = GIDS_ACCUM_LAG;
+constexpr uint64_t ACCUM_MAX_RAISE = GIDS_ACCUM_MAX_RAISE;
+static_assert(GIDS_ACCUM_LAG < STATS_RING, "the adaptive threshold reads counters that must still be in the ring");
 
 // Workspace of gids_gather_static, the gather for callers that must not allocate: what gids_gather keeps in
 // buffers it sizes with hipMalloc (the two gather headers, and per parity the plan and the ID scratch, laid out
@@ -136,6 +140,19 @@ struct gids_cache {
     uint32_t rows_per_line = 1;     // node rows one cache line holds
     uint64_t policy_key = 0;
     void* static_ws = nullptr;      // this device's copy of the static workspace (gids_gather_static)
+    // Accumulator (accum_threshold > 0): the host merges consecutive gathers into groups by the node accesses
+    // (raw list entries) they bring; the rows of a group move when it closes.
+    int accum_mode = GIDS_ACCUM_FIXED;
+    uint32_t group = 0;             // index of the open group (its lists live in the buffers of parity group & 1)
+    uint64_t open_nodes = 0;        // node accesses merged into the open group so far
+    uint64_t open_upper = 0;        // bound on the rows queued in the open group
+    uint32_t open_batches = 0;
+    uint64_t adapt_nodes = 0;       // adaptive mode: node accesses and store accesses of gathers [0, adapt_next)
+    uint64_t adapt_store = 0;
+    uint64_t adapt_next = 0;
+    uint32_t raw_of[STATS_RING] = {};        // raw list length of gather seq, by seq % STATS_RING
+    hipEvent_t ev_flush[2] = {};             // the group mover of the last group of each parity has finished
+    bool flush_recorded[2] = {false, false};
     StatsRec* ring_host = nullptr;
     StatsRec* ring_dev = nullptr;
     hipEvent_t events[STATS_RING] = {};       // gather seq: its rows have moved (recorded on the caller's stream)
@@ -214,31 +231,19 @@ struct CacheT final : gids_cache {
     IdT* ubuf[2] = {nullptr, nullptr};       // alternate per gather: gather t+1 is classified while the rows
     uint64_t* plan[2] = {nullptr, nullptr};  // of gather t are still moving
     BatchHdr* hdr = nullptr;                 // two entries
-    // accumulator queues
+    // accumulator: per-line bookkeeping and the operation lists of the two groups that can exist at a time
+    uint32_t* fillgrp = nullptr;
+    uint32_t* hitgrp = nullptr;
     uint64_t queue_cap = 0;
-    FillOp* fills = nullptr;
-    CopyOp* copies = nullptr;
-    // What the host knows about the queues without waiting: the count the last finished gather reported plus
-    // the list lengths of the gathers enqueued since.  While that bound is below the threshold the flush
-    // kernels (which decide on the real count) need not even be launched.
-    uint64_t known_seq = 0;         // gathers [0, known_seq) are accounted in known_pending
-    uint64_t known_pending = 0;
-    uint32_t upper_since[STATS_RING] = {};   // list length bound of gather seq, by seq % STATS_RING
+    FillOp* fills[2] = {nullptr, nullptr};
+    CopyOp* rcopies[2] = {nullptr, nullptr};
+    CopyOp* wcopies[2] = {nullptr, nullptr};
 
-    uint64_t pending_bound() {
-        // fold in every gather that has finished since (its record carries the real count after it)
-        for (uint64_t g = seq; g-- > known_seq && seq - g <= STATS_RING;) {
-            const StatsRec& rec = ring_host[g % STATS_RING];
-            if (*reinterpret_cast<const volatile uint64_t*>(&rec.seq) == g) {
-                known_pending = *reinterpret_cast<const volatile uint64_t*>(&rec.n_pending);
-                known_seq = g + 1;
-                break;
-            }
-        }
-        if (seq - known_seq > STATS_RING) return ~0ull;      // too far behind to bound: assume a flush is due
-        uint64_t bound = known_pending;
-        for (uint64_t g = known_seq; g < seq; g++) bound += upper_since[g % STATS_RING];
-        return bound;
+    AccumView accum_view() const {
+        AccumView a;
+        for (int k = 0; k < 2; k++) { a.fills[k] = fills[k]; a.rcopies[k] = rcopies[k]; a.wcopies[k] = wcopies[k]; }
+        a.cap = queue_cap;
+        return a;
     }
     // window FIFO (host bookkeeping; lists live on the device)
     std::vector<WindowSlot> slots;
@@ -254,7 +259,9 @@ struct CacheT final : gids_cache {
         dev_free(wrank); dev_free(hotbits); dev_free(hotrank); dev_free(cache_data); dev_free(ctl);
         dev_free(blocksum); dev_free(blockoff); dev_free(hdr);
         for (int k = 0; k < 2; k++) { dev_free(ubuf[k]); dev_free(plan[k]); }
-        dev_free(fills); dev_free(copies);
+        dev_free(fillgrp); dev_free(hitgrp);
+        for (int k = 0; k < 2; k++) { dev_free(fills[k]); dev_free(rcopies[k]); dev_free(wcopies[k]); }
+        for (auto& e : ev_flush) if (e) (void)hipEventDestroy(e);
         for (auto& s : slots) if (s.ids) (void)hipFree(s.ids);
         if (cpubuf_host) (void)hipHostFree(cpubuf_host);
         if (ring_host) (void)hipHostFree(ring_host);
@@ -271,7 +278,8 @@ struct CacheT final : gids_cache {
         v.row_bytes = store->row_bytes; v.line_bytes = line_bytes; v.words_per_set = words_per_set;
         v.use32 = (!wide_index && store->n_rows < (1ull << 32) && n_sets < (1ull << 32)) ? 1u : 0u;
         v.policy = policy; v.policy_key = policy_key; v.rows_per_line = rows_per_line;
-        v.tags = tags; v.stamps = stamps; v.pending = pending; v.reuse = reuse; v.missmask = missmask;
+        v.tags = tags; v.stamps = stamps; v.pending = pending; v.fillgrp = fillgrp; v.hitgrp = hitgrp; v.reuse = reuse;
+        v.missmask = missmask;
         v.hotbits = n_hot ? hotbits : nullptr; v.hotrank = hotrank;
         v.cache_data = cache_data; v.store = static_cast<const char*>(store->dev);
         v.cpubuf = static_cast<const char*>(cpubuf_dev); v.ctl = ctl;
@@ -286,7 +294,11 @@ struct CacheT final : gids_cache {
         int rc;
         if ((rc = dev_alloc(&tags, lines))) return rc;
         if ((rc = dev_alloc(&stamps, lines))) return rc;
-        if (threshold && (rc = dev_alloc(&pending, lines))) return rc;
+        if (threshold) {
+            if ((rc = dev_alloc(&pending, lines))) return rc;
+            if ((rc = dev_alloc(&fillgrp, lines))) return rc;
+            if ((rc = dev_alloc(&hitgrp, lines))) return rc;
+        }
         if ((rc = dev_alloc(&reuse, n_rows))) return rc;
         if ((rc = dev_alloc(&missmask, n_sets * words_per_set))) return rc;
         if ((rc = dev_alloc(&bitmap, n_words))) return rc;
@@ -298,7 +310,12 @@ struct CacheT final : gids_cache {
         if (sizeof(IdT) == 8) launch_fill_i64(reinterpret_cast<int64_t*>(tags), lines, -1, nullptr);
         else launch_fill_u32(reinterpret_cast<uint32_t*>(tags), lines, 0xFFFFFFFFu, nullptr);
         launch_fill_u32(reinterpret_cast<uint32_t*>(stamps), lines, 0xFFFFFFFFu, nullptr);
-        if (pending) launch_fill_u32(pending, lines, NO_OP, nullptr);
+        if (pending) {
+            launch_fill_u32(pending, lines, NO_OP, nullptr);
+            launch_fill_u32(fillgrp, lines, 0xFFFFFFFFu, nullptr);
+            launch_fill_u32(hitgrp, lines, 0xFFFFFFFFu, nullptr);
+            for (auto& e : ev_flush) HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+        }
         HIP_TRY(hipMemset(reuse, 0, n_rows));
         HIP_TRY(hipMemset(missmask, 0, n_sets * words_per_set * sizeof(uint64_t)));
         HIP_TRY(hipMemset(bitmap, 0, n_words * sizeof(uint64_t)));
@@ -313,8 +330,8 @@ struct CacheT final : gids_cache {
         HIP_TRY(hipMemset(hdr, 0, 2 * sizeof(BatchHdr)));
         // Overlap costs a handful of cross-stream events per call: worth it when minibatches move megabytes.
         // Default: on for caches of 32 MiB and more; GIDS_PIPELINE=0/1 overrides.
-        pipelined = threshold == 0 && lines * (uint64_t)line_bytes >= (32ull << 20);
-        if (const char* env = getenv("GIDS_PIPELINE")) pipelined = threshold == 0 && atoi(env) != 0;
+        pipelined = lines * (uint64_t)line_bytes >= (32ull << 20);
+        if (const char* env = getenv("GIDS_PIPELINE")) pipelined = atoi(env) != 0;
         if (pipelined) HIP_TRY(hipStreamCreateWithFlags(&meta, hipStreamNonBlocking));
         // one slot more than lists can be buffered: the slot a push overwrites was then read by the gather
         // before the previous one, whose rows have long moved, and not by the one still moving
@@ -347,21 +364,31 @@ struct CacheT final : gids_cache {
             }
             cap_n = want;
         }
-        if (threshold && threshold + n > queue_cap) {
-            HIP_TRY(hipDeviceSynchronize());
-            const uint64_t want = std::max<uint64_t>(threshold + n, queue_cap + queue_cap / 2);
+        return GIDS_OK;
+    }
+
+    // room for `rows` operations in each list of both groups; what is queued survives a move
+    int ensure_queue(uint64_t rows) {
+        if (rows <= queue_cap) return GIDS_OK;
+        HIP_TRY(hipDeviceSynchronize());
+        const uint64_t want = std::max<uint64_t>(rows, queue_cap + queue_cap / 2);
+        for (int k = 0; k < 2; k++) {
             FillOp* nf = nullptr;
-            CopyOp* nc = nullptr;
+            CopyOp *nr = nullptr, *nw = nullptr;
             int rc;
-            if ((rc = dev_alloc(&nf, want))) return rc;
-            if ((rc = dev_alloc(&nc, want))) { dev_free(nf); return rc; }
-            if (queue_cap) {                                  // queued rows survive the move
-                HIP_TRY(hipMemcpy(nf, fills, queue_cap * sizeof(FillOp), hipMemcpyDeviceToDevice));
-                HIP_TRY(hipMemcpy(nc, copies, queue_cap * sizeof(CopyOp), hipMemcpyDeviceToDevice));
+            if ((rc = dev_alloc(&nf, want)) || (rc = dev_alloc(&nr, want)) || (rc = dev_alloc(&nw, want))) {
+                dev_free(nf); dev_free(nr); dev_free(nw);
+                return rc;
             }
-            dev_free(fills); dev_free(copies);
-            fills = nf; copies = nc; queue_cap = want;
+            if (queue_cap) {
+                HIP_TRY(hipMemcpy(nf, fills[k], queue_cap * sizeof(FillOp), hipMemcpyDeviceToDevice));
+                HIP_TRY(hipMemcpy(nr, rcopies[k], queue_cap * sizeof(CopyOp), hipMemcpyDeviceToDevice));
+                HIP_TRY(hipMemcpy(nw, wcopies[k], queue_cap * sizeof(CopyOp), hipMemcpyDeviceToDevice));
+            }
+            dev_free(fills[k]); dev_free(rcopies[k]); dev_free(wcopies[k]);
+            fills[k] = nf; rcopies[k] = nr; wcopies[k] = nw;
         }
+        queue_cap = want;
         return GIDS_OK;
     }
 
@@ -379,6 +406,12 @@ struct CacheT final : gids_cache {
     int reserve(uint64_t n) override {
         int rc = ensure_scratch(n);
         if (rc) return rc;
+        // a group closes once it holds the threshold's node accesses: at most one list beyond it (the adaptive
+        // mode raises the threshold by up to its bound)
+        if (threshold) {
+            const uint64_t t_max = accum_mode == GIDS_ACCUM_ADAPTIVE ? threshold * ACCUM_MAX_RAISE : threshold;
+            if ((rc = ensure_queue(std::min<uint64_t>(t_max + n, (uint64_t)ACCUM_MAX_MERGE * std::max<uint64_t>(n, 1))))) return rc;
+        }
         for (auto& s : slots) {
             // only lists that are not in use may move
             bool live = false;
@@ -481,7 +514,8 @@ struct CacheT final : gids_cache {
         if (pipelined) {
             m = meta;
             // the list this slot held may still be read by its gather's row mover
-            if (sl.last_reader >= 0) HIP_TRY(hipStreamWaitEvent(meta, events[sl.last_reader % STATS_RING], 0));
+            // (not with the accumulator: there the list is last read by the queue kernel, on this same stream)
+            if (sl.last_reader >= 0 && !threshold) HIP_TRY(hipStreamWaitEvent(meta, events[sl.last_reader % STATS_RING], 0));
             if ((rc = edge(s, meta))) return rc;              // the caller's IDs are ready in its stream's order
         }
         dedup(ids, n, static_cast<IdT*>(sl.ids), &ctl->win_n[slot], reuse, false, m, n_dev);
@@ -515,7 +549,7 @@ struct CacheT final : gids_cache {
         GatherBufs b;
         int rc;
         if (no_alloc) {
-            if (threshold) return fail(GIDS_E_INVAL, "gids_gather_static: not on a cache with accum_threshold > 0 (its queues grow on demand)");
+            if (threshold) return fail(GIDS_E_INVAL, "gids_gather_static: not on a cache with accum_threshold > 0 (its operation lists grow on demand)");
             if (longest > STATIC_MAX_IDS) return fail(GIDS_E_INVAL, "gids_gather_static: a list of %llu IDs exceeds the static workspace (GIDS_STATIC_MAX_IDS = %llu)", (unsigned long long)longest, (unsigned long long)STATIC_MAX_IDS);
             unsigned char* ws = static_cast<unsigned char*>(static_ws);
             b.hd = reinterpret_cast<BatchHdr*>(ws) + par;
@@ -535,24 +569,64 @@ struct CacheT final : gids_cache {
         return rc;
     }
 
+    // Node-access threshold of the open group.  Fixed mode: accum_threshold.  Adaptive mode (Section 3.2, last
+    // paragraph): accum_threshold is the number of store accesses wanted in flight, and since part of the node
+    // accesses is redirected to the GPU cache and the CPU buffer, the node-access threshold is that number times
+    // (node accesses / store accesses), measured over every gather at least ACCUM_LAG calls back (a fixed lag,
+    // so the groups do not depend on how far the device has got; the call waits for those counters if need be).
+    int accum_limit(uint64_t* limit) {
+        *limit = threshold;
+        if (accum_mode != GIDS_ACCUM_ADAPTIVE) return GIDS_OK;
+        while (adapt_next + ACCUM_LAG < seq) {
+            const uint64_t g = adapt_next;
+            const int r = (int)(g % STATS_RING);
+            if (pipelined) HIP_TRY(hipEventSynchronize(ev_meta[r]));
+            HIP_TRY(hipEventSynchronize(events[r]));
+            const StatsRec& rec = ring_host[r];
+            if (*reinterpret_cast<const volatile uint64_t*>(&rec.seq) != g) return fail(GIDS_E_HIP, "the counters of gather %llu are missing", (unsigned long long)g);
+            adapt_nodes += raw_of[r];
+            adapt_store += *reinterpret_cast<const volatile uint64_t*>(&rec.n_miss);
+            adapt_next++;
+        }
+        if (adapt_nodes == 0) return GIDS_OK;
+        const uint64_t top = threshold * ACCUM_MAX_RAISE;
+        if (adapt_store == 0) { *limit = top; return GIDS_OK; }
+        const unsigned __int128 want = ((unsigned __int128)threshold * adapt_nodes + adapt_store - 1) / adapt_store;
+        *limit = want > top ? top : std::max<uint64_t>(threshold, (uint64_t)want);
+        return GIDS_OK;
+    }
+
     int gather_enqueue(const IdT* ids, uint64_t n, bool head_list, const GatherBufs& b, void* out, uint64_t out_cap,
                        void* unique, void* inverse, hipStream_t s) {
         int rc;
         const int r = (int)(seq % STATS_RING);
+        const uint64_t n_raw = head_list ? slots[head].n_raw : n;
+        const uint64_t n_upper = std::min<uint64_t>(n_raw, store->n_rows);
+        // the accumulator's decision, taken here on what the host knows: does this gather close its group?
+        bool opens = false, closes = false;
+        uint64_t limit = 0;
+        if (threshold) {
+            if ((rc = accum_limit(&limit))) return rc;
+            opens = open_batches == 0;
+            if ((rc = ensure_queue(open_upper + n_upper))) return rc;
+            closes = open_nodes + n_raw >= limit || open_batches + 1 >= ACCUM_MAX_MERGE;
+        }
         if ((rc = follow(s))) return rc;
         hipStream_t m = s;
         if (pipelined) {
             m = meta;
             // plan / ID scratch / header of this parity were last read by the row mover of gather seq - 2
-            if (seq >= 2) HIP_TRY(hipStreamWaitEvent(meta, events[(seq - 2) % STATS_RING], 0));
+            // (with the accumulator by this stream's own queue kernel)
+            if (seq >= 2 && !threshold) HIP_TRY(hipStreamWaitEvent(meta, events[(seq - 2) % STATS_RING], 0));
             if (ids && (rc = edge(s, meta))) return rc;       // the caller's IDs are ready in its stream's order
         }
+        // the lists this group will fill were last read by the group mover two groups back
+        if (opens && flush_recorded[group & 1]) HIP_TRY(hipStreamWaitEvent(m, ev_flush[group & 1], 0));
         prof_valid[r] = false;
         if ((rc = mark_phase(r, 0, m))) return rc;
 
         const IdT* U;
         const uint32_t* n_u;
-        uint64_t n_upper;
         if (ids || !head_list) {                              // (an empty list without a window still sets the count)
             dedup(ids, n, b.ub, &ctl->n_unique, nullptr, inverse != nullptr, m);
             if (head_list)
@@ -566,20 +640,17 @@ struct CacheT final : gids_cache {
         if (head_list) {                                      // the buffered head list is the minibatch
             U = static_cast<const IdT*>(slots[head].ids);
             n_u = &ctl->win_n[head];
-            n_upper = slots[head].n_raw;
         } else {
             U = b.ub;
             n_u = &ctl->n_unique;
-            n_upper = n;
         }
-        n_upper = std::min<uint64_t>(n_upper, store->n_rows);
         const CacheView<IdT> c = view();
         if ((rc = mark_phase(r, 1, m))) return rc;
         launch_probe<IdT>(c, U, n_u, n_upper, out_cap, head_list, b.pl, m);
         launch_victim<IdT>(c, U, n_u, n_upper, b.pl, m);
-        launch_commit<IdT>(c, U, n_u, n_upper, b.pl, b.hd, m);
+        launch_commit<IdT>(c, U, n_u, n_upper, b.pl, b.hd, opens ? (int)(group & 1) : -1, m);
         if (threshold == 0) {
-            launch_finalize(ctl, ring_dev + r, seq, n_u, m);
+            launch_finalize(ctl, ring_dev + r, seq, n_u, 0, m);
             if ((rc = mark_phase(r, 2, m))) return rc;
             if (pipelined) {
                 HIP_TRY(hipEventRecord(ev_meta[r], meta));
@@ -590,15 +661,20 @@ struct CacheT final : gids_cache {
                              move_blocks, link_blocks, s);
             if ((rc = mark_phase(r, 4, s))) return rc;
         } else {
-            if ((rc = mark_phase(r, 2, s))) return rc;
+            // nothing moves yet: the minibatch's rows join the open group's lists (on the metadata stream, so
+            // that the next minibatch is classified while an earlier group is still moving)
+            launch_queue<IdT>(c, accum_view(), group, U, b.hd, n_upper, b.pl, static_cast<char*>(out),
+                              static_cast<IdT*>(unique), m);
+            launch_finalize(ctl, ring_dev + r, seq, n_u, 4 | (closes ? 1 : 0) | (opens ? 2 : 0), m);
+            if ((rc = mark_phase(r, 2, m))) return rc;
+            raw_of[r] = (uint32_t)n_raw;
+            open_nodes += n_raw;
+            open_upper += n_upper;
+            open_batches++;
+            if (pipelined) HIP_TRY(hipEventRecord(ev_meta[r], meta));
             if ((rc = mark_phase(r, 3, s))) return rc;
-            launch_queue<IdT>(c, U, b.hd, n_upper, b.pl, static_cast<char*>(out), static_cast<IdT*>(unique),
-                              fills, copies, move_blocks, s);
-            upper_since[r] = (uint32_t)n_upper;
-            if (pending_bound() + n_upper >= threshold)
-                launch_flush<IdT>(c, fills, copies, threshold, false, (int)std::min<uint64_t>(queue_cap, 1u << 30), s);
+            if (closes && (rc = close_group(s, pipelined ? ev_meta[r] : nullptr))) return rc;
             if ((rc = mark_phase(r, 4, s))) return rc;
-            launch_finalize(ctl, ring_dev + r, seq, n_u, s);
         }
         prof_valid[r] = profile;
         HIP_TRY(hipGetLastError());                           // a kernel launch that was refused
@@ -612,19 +688,36 @@ struct CacheT final : gids_cache {
         return GIDS_OK;
     }
 
+    // the rows of the open group move, in two launches on the caller's stream
+    int close_group(hipStream_t s, hipEvent_t after) {
+        const uint32_t par = group & 1;
+        if (after) HIP_TRY(hipStreamWaitEvent(s, after, 0));
+        launch_group_move<IdT>(view(), accum_view(), par, open_upper, move_blocks, link_blocks, s);
+        HIP_TRY(hipGetLastError());
+        HIP_TRY(hipEventRecord(ev_flush[par], s));
+        flush_recorded[par] = true;
+        group++;
+        open_nodes = open_upper = 0;
+        open_batches = 0;
+        return GIDS_OK;
+    }
+
     int flush(hipStream_t s) override {
-        if (!threshold) return GIDS_OK;
+        if (!threshold || open_batches == 0) return GIDS_OK;
         int rc = flush_enqueue(s);
         if (rc) sticky = rc;
         return rc;
     }
 
     int flush_enqueue(hipStream_t s) {
-        const int rc = follow(s);
+        int rc = follow(s);
         if (rc) return rc;
-        launch_flush<IdT>(view(), fills, copies, threshold, true, (int)std::min<uint64_t>(queue_cap, 1u << 30), s);
-        HIP_TRY(hipGetLastError());
-        return GIDS_OK;
+        hipEvent_t after = nullptr;
+        if (pipelined) {                                      // everything the open group's gathers queued
+            after = ev_hop[hop++ % 16];
+            HIP_TRY(hipEventRecord(after, meta));
+        }
+        return close_group(s, after);
     }
 
     uint32_t window_count() const override { return count; }
@@ -916,6 +1009,15 @@ int gids_cache_set_policy(gids_cache* cache, int policy, uint64_t seed) {
     if (cache->seq) return fail(GIDS_E_INVAL, "gids_cache_set_policy: call before the first gather");
     cache->policy = (uint32_t)policy;
     cache->policy_key = sampler_mix(seed + 8ull * 0x9E3779B97F4A7C15ull);
+    return GIDS_OK;
+}
+
+int gids_cache_set_accum_mode(gids_cache* cache, int mode) {
+    CHECK_CACHE(cache);
+    if (mode != GIDS_ACCUM_FIXED && mode != GIDS_ACCUM_ADAPTIVE) return fail(GIDS_E_INVAL, "gids_cache_set_accum_mode: unknown mode %d", mode);
+    if (!cache->threshold) return fail(GIDS_E_INVAL, "gids_cache_set_accum_mode: the cache was created without an accumulator (accum_threshold == 0)");
+    if (cache->seq) return fail(GIDS_E_INVAL, "gids_cache_set_accum_mode: call before the first gather");
+    cache->accum_mode = mode;
     return GIDS_OK;
 }
 

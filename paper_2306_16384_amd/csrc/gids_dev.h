@@ -30,9 +30,13 @@ struct Ctl {
     uint32_t stamp;         // index of the minibatch being gathered (successful gathers so far)
     uint32_t cnt_hit, cnt_cpu, cnt_miss, cnt_bypass;
     uint32_t cnt_fill;      // cache lines this minibatch fills
-    uint32_t pend_fill;     // queued host-link rows (accumulator)
-    uint32_t pend_copy;     // queued HBM copies that wait for a queued fill
-    uint32_t deferred;      // rows of the current gather left in the queues
+    // accumulator: rows of the minibatches merged so far (the open group), and the lengths of the three
+    // operation lists of the two groups that can exist at a time (the open one and the one being moved)
+    uint32_t q_rows;
+    uint32_t q_fill[2];     // rows that cross the host link
+    uint32_t q_rcopy[2];    // hits whose line already holds its bytes
+    uint32_t q_wcopy[2];    // copies that must follow the link rows: hits on lines filled in the same group, ...
+    uint32_t q_chunk[2];    // work counter of the group mover's link half
     uint32_t win_n[MAX_WINDOW_SLOTS];   // distinct count of each buffered list
 };
 
@@ -46,15 +50,18 @@ struct BatchHdr {
     uint32_t next_chunk;    // work counter of the row mover's link half (reset by the commit kernel)
 };
 
-// One queued row move of the accumulator.
+// One queued row move of the accumulator (Section 3.2: the accesses of several minibatches go out in one
+// launch).  A fill crosses the host link; a copy stays in HBM.
 struct FillOp {
     const void* src;        // host store row or CPU-buffer row (device-visible address)
     void* dst_out;          // row in a caller's output tensor
     uint64_t dst_line;      // cache line to fill as well, or NO_LINE
+    uint32_t late;          // index of the late line fill (a copy output row -> line) this fill owns, or NO_OP
+    uint32_t pad;
 };
 struct CopyOp {
-    const void* src;        // output row that a queued fill will write
-    void* dst_out;
+    const void* src;
+    void* dst;              // nullptr: cancelled
 };
 
 // Mirror of gids_stats in host-mapped memory, written by the finalize kernel.
@@ -78,7 +85,9 @@ struct CacheView {
     uint64_t policy_key;    // mix64(seed + 8 * golden): prefix of the random policy's hash chain
     IdT* tags;              // lines, -1 = empty
     int32_t* stamps;        // lines, -1 = never used
-    uint32_t* pending;      // lines: index of the queued fill that will write the line, or NO_OP
+    uint32_t* pending;      // lines: index of the queued fill that will write the line (valid while fillgrp == open group)
+    uint32_t* fillgrp;      // lines: group in which the line's fill was queued
+    uint32_t* hitgrp;       // lines: group in which a copy out of the line was last queued
     uint8_t* reuse;         // n_rows: buffered future minibatches that contain the node
     uint64_t* missmask;     // n_sets * words_per_set
     const uint64_t* hotbits;    // n_rows / 64 words, or nullptr when no CPU buffer
@@ -138,20 +147,27 @@ void launch_victim(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n
 
 template <typename IdT>
 void launch_commit(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_u, uint64_t n_upper,
-                   const uint64_t* plan, BatchHdr* hdr, hipStream_t s);
+                   const uint64_t* plan, BatchHdr* hdr, int reset_parity, hipStream_t s);
 
 template <typename IdT>
 void launch_move(const CacheView<IdT>& c, const IdT* unique, BatchHdr* hdr, uint64_t n_upper,
                  const uint64_t* plan, char* out, IdT* unique_out, int blocks, int link_blocks_max, hipStream_t s);
 
-template <typename IdT>
-void launch_queue(const CacheView<IdT>& c, const IdT* unique, const BatchHdr* hdr, uint64_t n_upper,
-                  const uint64_t* plan, char* out, IdT* unique_out, FillOp* fills, CopyOp* copies, int blocks,
-                  hipStream_t s);
+// what the accumulator's kernels need besides the cache view
+struct AccumView {
+    FillOp* fills[2];
+    CopyOp* rcopies[2];
+    CopyOp* wcopies[2];
+    uint64_t cap;           // entries of each list
+};
 
 template <typename IdT>
-void launch_flush(const CacheView<IdT>& c, FillOp* fills, CopyOp* copies, uint64_t threshold, bool force,
-                  int max_rows, hipStream_t s);
+void launch_queue(const CacheView<IdT>& c, const AccumView& a, uint32_t group, const IdT* unique, const BatchHdr* hdr,
+                  uint64_t n_upper, const uint64_t* plan, char* out, IdT* unique_out, hipStream_t s);
+
+template <typename IdT>
+void launch_group_move(const CacheView<IdT>& c, const AccumView& a, uint32_t parity, uint64_t rows_upper,
+                       int hbm_blocks_max, int link_blocks_max, hipStream_t s);
 
 uint64_t sampler_key(uint64_t seed, uint64_t tag);
 uint64_t sampler_mix(uint64_t z);
@@ -180,7 +196,8 @@ void launch_reverse_pagerank(const int64_t* indptr, const IdT* indices, uint64_t
 void launch_calibrate(const char* store, uint64_t store_rows, uint32_t row_bytes, char* out, uint32_t n,
                       hipStream_t s);
 
-void launch_finalize(Ctl* ctl, StatsRec* rec, uint64_t seq, const uint32_t* n_u, hipStream_t s);
+// accum: 0 = no accumulator, 1 = this gather leaves its rows queued, 2 = this gather closes its group
+void launch_finalize(Ctl* ctl, StatsRec* rec, uint64_t seq, const uint32_t* n_u, int accum, hipStream_t s);
 
 void launch_fill_u32(uint32_t* p, uint64_t n, uint32_t value, hipStream_t s);
 void launch_fill_i64(int64_t* p, uint64_t n, int64_t value, hipStream_t s);

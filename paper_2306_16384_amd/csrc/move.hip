@@ -8,12 +8,11 @@
 //             once and writes it to the output and, when a victim line was
 //             found, to that line (the "line fill").  Tags were published by
 //             the commit kernel before; only bytes move here.
-//   queue     the accumulator's variant: rows that cross the host link are not
-//             moved but appended to a fill queue; a hit on a line whose fill is
-//             still queued becomes a queued copy from the output row that fill
-//             will write.  Hits on lines that hold data are copied at once.
-//   flush     moves every queued fill, then every queued copy, once enough are
-//             pending (or on request).
+//   queue     the accumulator's variant: nothing moves; every row of the
+//             minibatch becomes an operation in the lists of the open group.
+//   group     when a group of minibatches closes, its rows move in two
+//   mover     launches (link rows and plain hit copies; then the copies that
+//             depend on them).
 //   finalize  publishes the minibatch's counters to host-visible memory and
 //             advances the minibatch stamp.
 #include <cstdlib>
@@ -148,128 +147,176 @@ __global__ __launch_bounds__(MV_THREADS) void move_kernel(CacheView<IdT> c, cons
     }
 }
 
-// The accumulator's variant of the row mover.  A wave reads 64 plan entries at once; rows that must cross
-// the link are appended to the fill queue with one atomic per wave, hits on lines whose fill is still queued
-// become queued copies, and hits on lines that hold their bytes are copied right away, 64 / G at a time.
-template <typename IdT, int G>
-__global__ __launch_bounds__(MV_THREADS) void queue_kernel(CacheView<IdT> c, const IdT* __restrict__ unique,
+// The accumulator (Section 3.2: the accesses of consecutive minibatches are merged until enough are in
+// flight, then issued in one launch).  While a group of minibatches is open, the queue kernel turns each
+// minibatch's plan into operations in three lists instead of moving rows:
+//   fills    rows that cross the host link (CPU-buffer rows, store rows), each to its output row and, for an
+//            installed miss, to its cache line;
+//   rcopies  hits on lines that hold their bytes: cache line -> output row;
+//   wcopies  copies that must run after the fills: a hit on a line whose fill is queued in the same group
+//            reads the output row that fill writes; an installed miss whose line a queued rcopy still reads
+//            (the line was hit earlier in the group and evicted since) fills its line late, from its own
+//            output row, so that the rcopy sees the old bytes.
+// When the group closes, the group mover runs fills and rcopies in one launch and wcopies in a second.
+// A line installed twice in one group is filled by the last install only (the earlier fill keeps its output
+// row).  Every line is touched by at most one plan entry per minibatch, so the per-line words below are
+// written without atomics.
+template <typename IdT>
+__global__ __launch_bounds__(MV_THREADS) void queue_kernel(CacheView<IdT> c, AccumView a, uint32_t group,
+                                                           const IdT* __restrict__ unique,
                                                            const BatchHdr* __restrict__ hdr,
                                                            const uint64_t* __restrict__ plan, char* __restrict__ out,
-                                                           IdT* __restrict__ unique_out, FillOp* __restrict__ fills,
-                                                           CopyOp* __restrict__ copies) {
+                                                           IdT* __restrict__ unique_out) {
     Ctl* ctl = c.ctl;
     if (!hdr->ok) return;
     const uint32_t n_u = hdr->n_u;
-    const uint32_t row_u4 = c.row_bytes >> 4;
+    const uint32_t par = group & 1u;
+    FillOp* __restrict__ fills = a.fills[par];
+    CopyOp* __restrict__ rcopies = a.rcopies[par];
+    CopyOp* __restrict__ wcopies = a.wcopies[par];
     const uint32_t lane = threadIdx.x & 63;
-    const uint32_t sub = lane % G, grp = lane / G;
-    constexpr uint32_t PER_ITER = 64 / G;
     const uint64_t wave0 = ((uint64_t)blockIdx.x * MV_THREADS + threadIdx.x) >> 6;
     const uint64_t n_waves = ((uint64_t)gridDim.x * MV_THREADS) >> 6;
     for (uint64_t base = wave0 * 64; base < n_u; base += n_waves * 64) {
         const uint64_t j = base + lane;
         const bool valid = j < n_u;
         uint64_t e = 0, v = 0, idx = 0, kind = PLAN_HIT;
-        uint32_t p = NO_OP;
         if (valid) {
             e = plan[j];
             v = (uint64_t)unique[j];
             kind = e >> PLAN_SHIFT;
             idx = e & PLAN_INDEX_MASK;
             if (unique_out) unique_out[j] = (IdT)v;
-            if (kind == PLAN_HIT) p = c.pending[idx];          // written only by earlier gathers or flushes
         }
+        const bool has_line = valid && (kind == PLAN_HIT || kind == PLAN_INSTALL);
+        uint32_t fg = ~0u, hg = ~0u, pd = NO_OP;
+        if (has_line) {
+            fg = c.fillgrp[idx];
+            hg = c.hitgrp[idx];
+            pd = c.pending[idx];
+        }
+        const bool open_fill = has_line && fg == group;               // the line's fill is queued in this group
         const bool is_fill = valid && kind != PLAN_HIT;
-        const bool is_wait = valid && kind == PLAN_HIT && p != NO_OP;   // the line's bytes are still on their way
-        const bool is_copy = valid && kind == PLAN_HIT && p == NO_OP;
-        const uint64_t fb = __ballot(is_fill), wb = __ballot(is_wait);
-        uint32_t fbase = 0, wbase = 0;
+        const bool is_wait = valid && kind == PLAN_HIT && open_fill;
+        const bool is_ready = valid && kind == PLAN_HIT && !open_fill;
+        const bool is_late = valid && kind == PLAN_INSTALL && hg == group;   // a queued rcopy still reads the old bytes
+        const uint64_t fb = __ballot(is_fill), rb = __ballot(is_ready), wb = __ballot(is_wait || is_late);
+        uint32_t fbase = 0, rbase = 0, wbase = 0;
         if (lane == 0) {
-            if (fb) fbase = atomicAdd(&ctl->pend_fill, (uint32_t)__popcll(fb));
-            if (wb) wbase = atomicAdd(&ctl->pend_copy, (uint32_t)__popcll(wb));
-            if (fb | wb) atomicAdd(&ctl->deferred, (uint32_t)(__popcll(fb) + __popcll(wb)));
+            if (fb) fbase = atomicAdd(&ctl->q_fill[par], (uint32_t)__popcll(fb));
+            if (rb) rbase = atomicAdd(&ctl->q_rcopy[par], (uint32_t)__popcll(rb));
+            if (wb) wbase = atomicAdd(&ctl->q_wcopy[par], (uint32_t)__popcll(wb));
         }
         fbase = __shfl(fbase, 0);
+        rbase = __shfl(rbase, 0);
         wbase = __shfl(wbase, 0);
+        // the host sizes the lists for the group's longest possible content; a list that would overflow all
+        // the same is an error, never a write past its end
+        if ((uint64_t)fbase + __popcll(fb) > a.cap || (uint64_t)rbase + __popcll(rb) > a.cap ||
+            (uint64_t)wbase + __popcll(wb) > a.cap) {
+            if (lane == 0) atomicCAS(&ctl->error, 0u, 7u /* -GIDS_E_SPACE */);
+            continue;
+        }
         const uint64_t below = (1ull << lane) - 1;
         char* dst = out + j * c.row_bytes;
+        const uint32_t w = wbase + (uint32_t)__popcll(wb & below);
         if (is_fill) {
             const uint32_t q = fbase + (uint32_t)__popcll(fb & below);
-            fills[q].dst_out = dst;
-            fills[q].dst_line = NO_LINE;
-            fills[q].src = kind == PLAN_CPU ? c.cpubuf + idx * c.row_bytes : c.store + v * c.row_bytes;
+            FillOp op;
+            op.src = kind == PLAN_CPU ? c.cpubuf + idx * c.row_bytes : c.store + v * c.row_bytes;
+            op.dst_out = dst;
+            op.dst_line = NO_LINE;
+            op.late = NO_OP;
+            op.pad = 0;
             if (kind == PLAN_INSTALL) {
-                const uint32_t old = c.pending[idx];
-                if (old != NO_OP) fills[old].dst_line = NO_LINE;   // superseded before it ever ran: output only
-                fills[q].dst_line = idx;
+                if (open_fill) {                              // superseded before it ever ran: output only
+                    fills[pd].dst_line = NO_LINE;
+                    const uint32_t lt = fills[pd].late;
+                    if (lt != NO_OP) wcopies[lt].dst = nullptr;
+                }
+                char* line = c.cache_data + idx * c.line_bytes;
+                if (is_late) {
+                    wcopies[w].src = dst;
+                    wcopies[w].dst = line;
+                    op.late = w;
+                } else {
+                    op.dst_line = idx;
+                }
+                c.fillgrp[idx] = group;
                 c.pending[idx] = q;
             }
+            fills[q] = op;
         }
         if (is_wait) {
-            const uint32_t q = wbase + (uint32_t)__popcll(wb & below);
-            copies[q].src = fills[p].dst_out;
-            copies[q].dst_out = dst;
+            wcopies[w].src = fills[pd].dst_out;
+            wcopies[w].dst = dst;
         }
-        uint64_t todo = __ballot(is_copy);
-        while (todo) {
-            const uint32_t pick = nth_set_bit(todo, grp);
-#pragma unroll
-            for (uint32_t i = 0; i < PER_ITER; i++) todo &= todo - 1;
-            const uint64_t idx_p = __shfl(idx, (int)(pick & 63));
-            if (pick == 64u) continue;
-            copy_row<G>(reinterpret_cast<const v4u*>(c.cache_data + idx_p * c.line_bytes),
-                        reinterpret_cast<v4u*>(out + (base + pick) * c.row_bytes), nullptr, row_u4, sub);
+        if (is_ready) {
+            const uint32_t r = rbase + (uint32_t)__popcll(rb & below);
+            rcopies[r].src = c.cache_data + idx * c.line_bytes;
+            rcopies[r].dst = dst;
+            c.hitgrp[idx] = group;
         }
     }
 }
 
-__device__ __forceinline__ bool flush_now(const Ctl* ctl, uint64_t threshold, int force) {
-    return force || ((uint64_t)ctl->pend_fill + ctl->pend_copy >= threshold);
-}
-
-template <typename IdT, int G>
-__global__ __launch_bounds__(MV_THREADS) void flush_fill_kernel(CacheView<IdT> c, const FillOp* __restrict__ fills,
-                                                                uint64_t threshold, int force) {
-    const Ctl* ctl = c.ctl;
-    if (ctl->error || !flush_now(ctl, threshold, force)) return;
-    const uint32_t n = ctl->pend_fill;
-    const uint32_t row_u4 = c.row_bytes >> 4;
-    const uint32_t sub = threadIdx.x % G;
-    const uint64_t g0 = ((uint64_t)blockIdx.x * MV_THREADS + threadIdx.x) / G;
-    const uint64_t n_groups = (uint64_t)gridDim.x * MV_THREADS / G;
-    for (uint64_t i = g0; i < n; i += n_groups) {
-        const FillOp op = fills[i];
-        char* line = op.dst_line == NO_LINE ? nullptr : c.cache_data + op.dst_line * c.line_bytes;
-        copy_row<G>(reinterpret_cast<const v4u*>(op.src), reinterpret_cast<v4u*>(op.dst_out),
-                    reinterpret_cast<v4u*>(line), row_u4, sub);
-        if (sub == 0 && line) c.pending[op.dst_line] = NO_OP;
+// The group mover, first launch: the fills and the rcopies of one closed group.  Shaped like the row mover:
+// the first `link_blocks` workgroups are persistent and draw chunks of fills from a counter (rows that cross
+// the host link), the others copy cache lines to output rows.
+template <int G>
+__global__ __launch_bounds__(MV_THREADS) void group_move_kernel(Ctl* ctl, const FillOp* __restrict__ fills,
+                                                                const CopyOp* __restrict__ rcopies,
+                                                                char* __restrict__ cache_data, uint32_t line_bytes,
+                                                                uint32_t row_bytes, uint32_t par, uint32_t link_blocks,
+                                                                uint32_t link_ch, uint32_t link_spread) {
+    const uint32_t row_u4 = row_bytes >> 4;
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t sub = lane % G, grp = lane / G;
+    constexpr uint32_t PER_ITER = 64 / G;
+    if (blockIdx.x < link_blocks) {
+        const uint32_t n = ctl->q_fill[par];
+        const uint64_t n_waves = ((uint64_t)link_blocks * MV_THREADS) >> 6;
+        uint32_t ch = link_ch;
+        while (ch > 4 && n / ch < link_spread * n_waves) ch >>= 1;
+        if (ch < PER_ITER) ch = PER_ITER;
+        for (;;) {
+            uint32_t chunk = 0;
+            if (lane == 0) chunk = atomicAdd(&ctl->q_chunk[par], 1u);
+            const uint64_t base = (uint64_t)__shfl(chunk, 0) * ch;
+            if (base >= n) break;
+            for (uint32_t i = grp; i < ch; i += PER_ITER) {
+                const uint64_t k = base + i;
+                if (k >= n) break;
+                const FillOp op = fills[k];
+                char* line = op.dst_line == NO_LINE ? nullptr : cache_data + op.dst_line * line_bytes;
+                copy_row<G>(reinterpret_cast<const v4u*>(op.src), reinterpret_cast<v4u*>(op.dst_out),
+                            reinterpret_cast<v4u*>(line), row_u4, sub);
+            }
+        }
+    } else {
+        const uint32_t n = ctl->q_rcopy[par];
+        const uint64_t g0 = ((uint64_t)(blockIdx.x - link_blocks) * MV_THREADS + threadIdx.x) / G;
+        const uint64_t n_groups = (uint64_t)(gridDim.x - link_blocks) * MV_THREADS / G;
+        for (uint64_t k = g0; k < n; k += n_groups) {
+            const CopyOp op = rcopies[k];
+            copy_row<G>(reinterpret_cast<const v4u*>(op.src), reinterpret_cast<v4u*>(op.dst), nullptr, row_u4, sub);
+        }
     }
 }
 
-template <typename IdT, int G>
-__global__ __launch_bounds__(MV_THREADS) void flush_copy_kernel(CacheView<IdT> c, const CopyOp* __restrict__ copies,
-                                                                uint64_t threshold, int force) {
-    const Ctl* ctl = c.ctl;
-    if (ctl->error || !flush_now(ctl, threshold, force)) return;
-    const uint32_t n = ctl->pend_copy;
-    const uint32_t row_u4 = c.row_bytes >> 4;
+// second launch: the copies that had to wait for the first
+template <int G>
+__global__ __launch_bounds__(MV_THREADS) void group_copy_kernel(const Ctl* ctl, const CopyOp* __restrict__ wcopies,
+                                                                uint32_t row_bytes, uint32_t par) {
+    const uint32_t n = ctl->q_wcopy[par];
+    const uint32_t row_u4 = row_bytes >> 4;
     const uint32_t sub = threadIdx.x % G;
     const uint64_t g0 = ((uint64_t)blockIdx.x * MV_THREADS + threadIdx.x) / G;
     const uint64_t n_groups = (uint64_t)gridDim.x * MV_THREADS / G;
-    for (uint64_t i = g0; i < n; i += n_groups) {
-        const CopyOp op = copies[i];
-        copy_row<G>(reinterpret_cast<const v4u*>(op.src), reinterpret_cast<v4u*>(op.dst_out), nullptr, row_u4,
-                    sub);
-    }
-}
-
-// after the flush kernels: empty the queues if they ran
-__global__ void flush_done_kernel(Ctl* ctl, uint64_t threshold, int force) {
-    if (ctl->error) return;
-    if (flush_now(ctl, threshold, force)) {
-        ctl->pend_fill = 0;
-        ctl->pend_copy = 0;
-        ctl->deferred = 0;
+    for (uint64_t k = g0; k < n; k += n_groups) {
+        const CopyOp op = wcopies[k];
+        if (!op.dst) continue;                                // cancelled: its line was given away again
+        copy_row<G>(reinterpret_cast<const v4u*>(op.src), reinterpret_cast<v4u*>(op.dst), nullptr, row_u4, sub);
     }
 }
 
@@ -291,23 +338,32 @@ __global__ __launch_bounds__(MV_THREADS) void calibrate_kernel(const char* __res
     }
 }
 
-__global__ void finalize_kernel(Ctl* ctl, StatsRec* rec, uint64_t seq, const uint32_t* n_u) {
+// accum: 0 = no accumulator; otherwise bit 0 = this gather closes its group, bit 1 = it opened the group
+__global__ void finalize_kernel(Ctl* ctl, StatsRec* rec, uint64_t seq, const uint32_t* n_u, int accum) {
     const uint32_t err = ctl->error;
-    rec->n_unique = err ? 0 : *n_u;
+    const uint32_t n = err ? 0 : *n_u;
+    rec->n_unique = n;
     rec->n_hit = ctl->cnt_hit;
     rec->n_cpu_hit = ctl->cnt_cpu;
     rec->n_miss = ctl->cnt_miss;
     rec->n_bypass = ctl->cnt_bypass;
     rec->n_line_fills = ctl->cnt_fill;
-    rec->n_pending = (uint64_t)ctl->pend_fill + ctl->pend_copy;
-    rec->flushed = ctl->deferred == 0;
+    uint32_t queued = 0;
+    int flushed = 1;
+    if (accum) {                          // rows of the open group that have not moved when this gather ends
+        const bool closes = (accum & 1) != 0, opens = (accum & 2) != 0;
+        queued = closes ? 0u : (opens ? 0u : ctl->q_rows) + n;
+        ctl->q_rows = queued;
+        flushed = closes ? 1 : 0;
+    }
+    rec->n_pending = queued;
+    rec->flushed = flushed;
     rec->status = -(int32_t)err;
     __threadfence_system();
     rec->seq = seq;                       // written last: a record whose seq matches is complete
     __threadfence_system();
     if (!err) ctl->stamp += 1;
     ctl->cnt_hit = ctl->cnt_cpu = ctl->cnt_miss = ctl->cnt_bypass = ctl->cnt_fill = 0;
-    ctl->deferred = 0;
 }
 
 inline int lanes_per_row(uint32_t row_bytes) {
@@ -365,28 +421,28 @@ void launch_move(const CacheView<IdT>& c, const IdT* unique, BatchHdr* hdr, uint
 }
 
 template <typename IdT>
-void launch_queue(const CacheView<IdT>& c, const IdT* unique, const BatchHdr* hdr, uint64_t n_upper,
-                  const uint64_t* plan, char* out, IdT* unique_out, FillOp* fills, CopyOp* copies, int blocks,
-                  hipStream_t s) {
-    const int g = lanes_per_row(c.row_bytes);
-    const uint32_t grid = row_grid(n_upper, 1, blocks < 2048 ? blocks : 2048);   // 4 waves x 64 entries per workgroup step
-    GIDS_DISPATCH_G(g, hipLaunchKernelGGL((queue_kernel<IdT, G>), dim3(grid), dim3(MV_THREADS), 0, s, c, unique,
-                                          hdr, plan, out, unique_out, fills, copies));
+void launch_queue(const CacheView<IdT>& c, const AccumView& a, uint32_t group, const IdT* unique, const BatchHdr* hdr,
+                  uint64_t n_upper, const uint64_t* plan, char* out, IdT* unique_out, hipStream_t s) {
+    const uint32_t grid = row_grid(n_upper, 1, 1024);         // 4 waves x 64 entries per workgroup step
+    hipLaunchKernelGGL(queue_kernel<IdT>, dim3(grid), dim3(MV_THREADS), 0, s, c, a, group, unique, hdr, plan, out,
+                       unique_out);
 }
 
 template <typename IdT>
-void launch_flush(const CacheView<IdT>& c, FillOp* fills, CopyOp* copies, uint64_t threshold, bool force,
-                  int max_rows, hipStream_t s) {
+void launch_group_move(const CacheView<IdT>& c, const AccumView& a, uint32_t par, uint64_t rows_upper,
+                       int hbm_blocks_max, int link_blocks_max, hipStream_t s) {
     const int g = lanes_per_row(c.row_bytes);
-    const int f = force ? 1 : 0;
-    // the queues hold rows that cross the link (fills) or wait for them (copies): a few hundred persistent
-    // workgroups, never more than there can be rows
-    const int blocks = (int)row_grid((uint64_t)(max_rows > 0 ? max_rows : 1), g, 384);
-    GIDS_DISPATCH_G(g, hipLaunchKernelGGL((flush_fill_kernel<IdT, G>), dim3(blocks), dim3(MV_THREADS), 0, s, c,
-                                          fills, threshold, f));
-    GIDS_DISPATCH_G(g, hipLaunchKernelGGL((flush_copy_kernel<IdT, G>), dim3(blocks), dim3(MV_THREADS), 0, s, c,
-                                          copies, threshold, f));
-    hipLaunchKernelGGL(flush_done_kernel, dim3(1), dim3(1), 0, s, c.ctl, threshold, f);
+    if (rows_upper < 1) rows_upper = 1;
+    uint32_t link_ch = 64;
+    while (link_ch > 4 && rows_upper / link_ch < (uint64_t)link_blocks_max * (MV_THREADS / 64)) link_ch >>= 1;
+    const uint32_t link_blocks = row_grid(rows_upper, 64 / (int)link_ch, link_blocks_max);
+    const uint32_t hbm_blocks = row_grid(rows_upper, g, hbm_blocks_max < 4096 ? hbm_blocks_max : 4096);
+    GIDS_DISPATCH_G(g, hipLaunchKernelGGL((group_move_kernel<G>), dim3(link_blocks + hbm_blocks), dim3(MV_THREADS), 0,
+                                          s, c.ctl, a.fills[par], a.rcopies[par], c.cache_data, c.line_bytes,
+                                          c.row_bytes, par, link_blocks, link_ch, 2u));
+    const uint32_t copy_blocks = row_grid(rows_upper, g, 256);
+    GIDS_DISPATCH_G(g, hipLaunchKernelGGL((group_copy_kernel<G>), dim3(copy_blocks), dim3(MV_THREADS), 0, s, c.ctl,
+                                          a.wcopies[par], c.row_bytes, par));
 }
 
 void launch_calibrate(const char* store, uint64_t store_rows, uint32_t row_bytes, char* out, uint32_t n,
@@ -397,16 +453,17 @@ void launch_calibrate(const char* store, uint64_t store_rows, uint32_t row_bytes
                                           row_bytes, out, n));
 }
 
-void launch_finalize(Ctl* ctl, StatsRec* rec, uint64_t seq, const uint32_t* n_u, hipStream_t s) {
-    hipLaunchKernelGGL(finalize_kernel, dim3(1), dim3(1), 0, s, ctl, rec, seq, n_u);
+void launch_finalize(Ctl* ctl, StatsRec* rec, uint64_t seq, const uint32_t* n_u, int accum, hipStream_t s) {
+    hipLaunchKernelGGL(finalize_kernel, dim3(1), dim3(1), 0, s, ctl, rec, seq, n_u, accum);
 }
 
 #define GIDS_INSTANTIATE(IdT)                                                                                       \
     template void launch_move<IdT>(const CacheView<IdT>&, const IdT*, BatchHdr*, uint64_t, const uint64_t*,         \
                                    char*, IdT*, int, int, hipStream_t);                                             \
-    template void launch_queue<IdT>(const CacheView<IdT>&, const IdT*, const BatchHdr*, uint64_t, const uint64_t*,  \
-                                    char*, IdT*, FillOp*, CopyOp*, int, hipStream_t);                               \
-    template void launch_flush<IdT>(const CacheView<IdT>&, FillOp*, CopyOp*, uint64_t, bool, int, hipStream_t);
+    template void launch_queue<IdT>(const CacheView<IdT>&, const AccumView&, uint32_t, const IdT*, const BatchHdr*, \
+                                    uint64_t, const uint64_t*, char*, IdT*, hipStream_t);                           \
+    template void launch_group_move<IdT>(const CacheView<IdT>&, const AccumView&, uint32_t, uint64_t, int, int,     \
+                                         hipStream_t);
 GIDS_INSTANTIATE(int32_t)
 GIDS_INSTANTIATE(int64_t)
 

@@ -53,6 +53,9 @@ class GatherSession:
     def set_policy(self, policy: int, seed: int = 0) -> None:
         B.gids_cache_set_policy(self.cache, policy, seed)
 
+    def set_accum_mode(self, mode: int) -> None:
+        B.gids_cache_set_accum_mode(self.cache, mode)
+
     def set_rows_per_line(self, rows: int) -> None:
         B.gids_cache_set_rows_per_line(self.cache, rows)
 

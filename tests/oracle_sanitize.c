@@ -34,6 +34,7 @@ int main(void) {
         CHECK(go_sim_set_hot(s, hot, 500) == GO_OK);
         if (variant == 1) CHECK(go_sim_set_policy(s, 1, 99) == GO_OK);
         if (variant == 2) CHECK(go_sim_set_rows_per_line(s, rows_per_line) == GO_OK);
+        CHECK(go_sim_set_accum(s, variant == 0 ? 9000 : 2000, variant == 1) == GO_OK);   /* the accumulator, both modes */
         enum { NB = 20, CAP = 256 * (1 + 10 + 50) };
         int64_t* raw[NB];
         int64_t len[NB];
@@ -51,9 +52,13 @@ int main(void) {
             int64_t stats[5];
             int64_t m = go_sim_gather(s, raw[t], len[t], uniq, out, stats, cls);
             CHECK(m > 0 && stats[1] + stats[2] + stats[3] == stats[0]);
+            int64_t acc[3];
+            go_sim_accum_last(s, acc);
+            CHECK(acc[0] >= 0 && (acc[1] == 0 || acc[0] == 0) && acc[2] >= 2000);
             for (int64_t j = 0; j < m; j += 97)
                 CHECK(memcmp(out + (size_t)j * dim * 4, store + (size_t)uniq[j] * dim * 4, (size_t)dim * 4) == 0);
         }
+        CHECK(go_sim_flush(s) >= 0);
         CHECK(go_sim_push(s, raw[0], len[0]) == GO_OK);         /* a list left in the window is freed with it */
         for (int b = 0; b < NB; b++) free(raw[b]);
         free(uniq); free(out); free(cls);

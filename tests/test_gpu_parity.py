@@ -23,7 +23,7 @@ def gpu():
 
 def run_case(gpu, oracle, feats, batches, *, id_dtype, lines, ways, line_bytes, window, threshold=0, hot=None,
              use_head=False, with_inverse=False, check_state=True, two_streams=False, policy=None, label="",
-             pipeline=None, push_depth0=False, wide_index=False, rows_per_line=1):
+             pipeline=None, push_depth0=False, wide_index=False, rows_per_line=1, accum_mode=0):
     """Feeds the same raw ID lists to both implementations, protocol: keep window + 1 lists buffered.
     pipeline: "0" / "1" forces the library's internal stream off / on for this cache (GIDS_PIPELINE);
     push_depth0: at window depth 0, push every list just before its gather."""
@@ -40,14 +40,17 @@ def run_case(gpu, oracle, feats, batches, *, id_dtype, lines, ways, line_bytes, 
         sim.set_policy(*policy)
     if rows_per_line != 1:
         sim.set_rows_per_line(rows_per_line)
+    if threshold:
+        sim.set_accum(threshold, accum_mode)
     # the oracle's pass, on its own
-    want, line_fills, pushed = [], [], 0
+    want, line_fills, accum, pushed = [], [], [], 0
     for t, raw in enumerate(batches):
         while window and pushed < len(batches) and pushed <= t + window:
             sim.push(batches[pushed])
             pushed += 1
         u, rows, stats, cls = sim.gather(raw, want_cls=True)
         want.append((u, rows, stats))
+        accum.append(sim.accum_last)
         line_fills.append(len(np.unique(u[cls == 2] // rows_per_line)))   # distinct store lines among installed misses
     import os
     knobs = {}                                               # environment knobs are read when the cache is created
@@ -74,6 +77,8 @@ def run_case(gpu, oracle, feats, batches, *, id_dtype, lines, ways, line_bytes, 
             ses.set_policy(*policy)
         if rows_per_line != 1:
             ses.set_rows_per_line(rows_per_line)
+        if threshold and accum_mode:
+            ses.set_accum_mode(accum_mode)
         dev = [ses.to_device(b) for b in batches]
         torch.cuda.synchronize()
         push_stream = torch.cuda.Stream() if two_streams else None
@@ -108,8 +113,8 @@ def run_case(gpu, oracle, feats, batches, *, id_dtype, lines, ways, line_bytes, 
             if invs[t] is not None:
                 inv = invs[t][:len(raw)].cpu().numpy()
                 np.testing.assert_array_equal(want_u[inv], np.asarray(raw, dtype=np.int64))
-            if threshold == 0:
-                assert st.flushed == 1 and st.n_pending == 0
+            # the accumulator's own behaviour: rows still queued after this gather, and whether it closed its group
+            assert (st.n_pending, st.flushed) == accum[t][:2], (label, t, st.n_pending, st.flushed, accum[t])
         if check_state:
             tags, stamps = ses.snapshot()
             np.testing.assert_array_equal(tags, sim.tags, err_msg=f"{label} tags")
@@ -265,17 +270,38 @@ def test_long_raw_list_many_tiles(gpu, oracle_mod):
 
 # ---------------------------------------------------------------- accumulator
 
-@pytest.mark.parametrize("threshold", [1, 300, 100_000])
+@pytest.mark.parametrize("pipeline", ["0", "1"])
+@pytest.mark.parametrize("threshold,mode", [(1, 0), (300, 0), (2000, 0), (100_000, 0), (150, 1), (40, 1)])
 @pytest.mark.parametrize("window", [0, 3])
-def test_accumulator_changes_nothing(gpu, oracle_mod, threshold, window):
-    """Section 3.2: merging the fills of consecutive minibatches is a scheduling
-    choice; counters and tensors are those of the unmerged run."""
+def test_accumulator_changes_nothing(gpu, oracle_mod, threshold, mode, window, pipeline):
+    """Section 3.2: merging the accesses of consecutive minibatches is a scheduling
+    choice; counters and tensors are those of the unmerged run, and the groups
+    (rows pending after each gather, which gather closes a group) are the oracle's,
+    for a fixed threshold and for one that follows the redirected share."""
     rng = np.random.default_rng(1000 + threshold + window)
     n = 6000
     feats = rand_feats(rng, n, 256)
-    run_case(gpu, oracle_mod, feats, zipf_batches(rng, n, 30, 400, a=1.2), id_dtype=np.int64, lines=128, ways=4,
-             line_bytes=256, window=window, threshold=threshold, hot=rng.choice(n, 60, replace=False),
-             label=f"accum{threshold}/W{window}")
+    run_case(gpu, oracle_mod, feats, zipf_batches(rng, n, 60, 400, a=1.2), id_dtype=np.int64, lines=128, ways=4,
+             line_bytes=256, window=window, threshold=threshold, accum_mode=mode, hot=rng.choice(n, 60, replace=False),
+             pipeline=pipeline, two_streams=pipeline == "1", use_head=bool(window),
+             label=f"accum{threshold}/mode{mode}/W{window}/pipe{pipeline}")
+
+
+@pytest.mark.parametrize("pipeline", ["0", "1"])
+def test_accumulator_lines_reused_inside_a_group(gpu, oracle_mod, pipeline):
+    """A cache of a few lines under long groups: lines are hit, evicted and refilled several times before
+    their group moves (copies out of a line that is refilled later in the group, hits on lines whose fill
+    is still queued, lines installed twice in one group)."""
+    rng = np.random.default_rng(31337)
+    n, R = 300, 64
+    feats = rand_feats(rng, n, R)
+    batches = [rng.integers(0, 40, size=int(rng.integers(3, 25))) for _ in range(60)]   # 40 hot IDs over 8 lines
+    for threshold in (60, 200, 10_000):
+        run_case(gpu, oracle_mod, feats, batches, id_dtype=np.int32, lines=8, ways=2, line_bytes=R, window=0,
+                 threshold=threshold, pipeline=pipeline, label=f"accum-reuse/thr{threshold}/pipe{pipeline}")
+        run_case(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=8, ways=8, line_bytes=R, window=2,
+                 threshold=threshold, pipeline=pipeline, hot=np.array([3, 17]), use_head=True, two_streams=True,
+                 label=f"accum-reuse/W2/thr{threshold}/pipe{pipeline}")
 
 
 # ------------------------------------------------------------------- errors
@@ -384,6 +410,7 @@ def test_random_configurations(gpu, oracle_mod, case):
     line_bytes = row_bytes + 16 * int(rng.integers(0, 3))
     window = int(rng.choice([0, 0, 1, 2, 5, 11]))
     threshold = int(rng.choice([0, 0, 0, 7, 900]))
+    accum_mode = int(case % 2) if threshold else 0
     id_dtype = np.int32 if rng.random() < 0.5 else np.int64
     n_hot = int(rng.integers(0, max(1, n // 10)))
     size = int(rng.integers(1, 4 * n))
@@ -406,7 +433,8 @@ def test_random_configurations(gpu, oracle_mod, case):
             extra["use_head_override"] = True
     use_head_override = extra.pop("use_head_override", False)
     run_case(gpu, oracle_mod, feats, batches, id_dtype=id_dtype, lines=ways * n_sets, ways=ways, line_bytes=line_bytes,
-             window=window, threshold=threshold, hot=rng.choice(n, n_hot, replace=False) if n_hot else None,
+             window=window, threshold=threshold, accum_mode=accum_mode,
+             hot=rng.choice(n, n_hot, replace=False) if n_hot else None,
              use_head=bool(use_head_override or (window and rng.random() < 0.5)), with_inverse=bool(rng.random() < 0.5),
              two_streams=bool(rng.random() < 0.5), policy=(1, case) if rng.random() < 0.3 else None,
              label=f"random{case}", **extra)
@@ -596,7 +624,7 @@ def test_rows_per_line_argument_checks(gpu):
             s.set_rows_per_line(4)                             # not with the accumulator
 
 
-@pytest.mark.parametrize("pipeline,threshold", [("0", 0), ("1", 0), ("0", 2500)])
+@pytest.mark.parametrize("pipeline,threshold", [("0", 0), ("1", 0), ("0", 2500), ("1", 2500)])
 def test_a_thousand_minibatches(gpu, oracle_mod, pipeline, threshold):
     """A long run on a small cache: the 64-entry rings of events and counters wrap many times, every slot of
     the window is reused hundreds of times; counters of every minibatch (read with a lag, as a training loop

@@ -400,6 +400,112 @@ def test_overlapped_access_model(oracle_mod):
     assert abs(oracle_mod.accum_threshold(iops, ti, tt, r, 2) - 2 * n) < 1e-6
 
 
+def test_accumulator_groups_hand_traced(oracle_mod):
+    """Section 3.2: iterations are merged until their node accesses pass the threshold.  A hand-traced run at
+    threshold 10 (node access = raw list entry; pending = distinct IDs of the open group):
+      list                    raw  distinct  nodes in group  closes?  pending after
+      [1 2 3]                  3      3           3            no         3
+      [4 5 6 6 6]              5      3           8            no         6
+      [7]                      1      1           9            no         7
+      [8 .. 18]               11     11          20            yes        0
+      [1]                      1      1           1            no         1
+      (flush)                                                  yes        0   (1 row was waiting)
+      [2 2]                    2      1           2            no         1
+      [3 .. 12]               10     10          12            yes        0
+    """
+    sim = oracle_mod.Sim(100, 16, 4, 0)
+    sim.set_accum(10)
+    lists = [[1, 2, 3], [4, 5, 6, 6, 6], [7], list(range(8, 19)), [1]]
+    want = [(3, 0), (6, 0), (7, 0), (0, 1), (1, 0)]
+    for raw, (pending, flushed) in zip(lists, want):
+        sim.gather(raw)
+        assert sim.accum_last == (pending, flushed, 10)
+    assert sim.flush() == 1 and sim.flush() == 0
+    sim.gather([2, 2])
+    assert sim.accum_last == (1, 0, 10)
+    sim.gather(list(range(3, 13)))
+    assert sim.accum_last == (0, 1, 10)
+    # a group never holds more than 32 minibatches, however high the threshold
+    sim = oracle_mod.Sim(100, 16, 4, 0)
+    sim.set_accum(10**9)
+    flushed = []
+    for t in range(70):
+        sim.gather([t % 100])
+        flushed.append(sim.accum_last[1])
+    assert [t for t, f in enumerate(flushed) if f] == [31, 63]
+    # without an accumulator every gather moves its own rows
+    sim = oracle_mod.Sim(100, 16, 4, 0)
+    sim.gather([1, 2])
+    assert sim.accum_last == (0, 1, 0)
+
+
+@pytest.mark.parametrize("window", [0, 3])
+def test_accumulator_changes_no_result_and_loses_no_row(oracle_mod, window):
+    """Merging is scheduling only: counters, classes, rows and tags are those of the run without it; every
+    distinct ID of every minibatch is pending exactly until its group closes."""
+    rng, feats, plain, hot = tiny_setup(oracle_mod, window=window)
+    _, _, merged, _ = tiny_setup(oracle_mod, window=window)
+    merged.set_accum(700)
+    batches = [rng.integers(0, 400, size=int(rng.integers(1, 300))) for _ in range(40)]
+    a = run_stream(plain, batches, window)
+    open_rows, moved, pushed = 0, 0, 0
+    for t, raw in enumerate(batches):
+        while window and pushed < len(batches) and pushed <= t + window:
+            merged.push(batches[pushed])
+            pushed += 1
+        u, rows, stats = merged.gather(raw)
+        assert np.array_equal(u, a[t][0]) and np.array_equal(rows, a[t][1]) and np.array_equal(stats, a[t][2])
+        pending, flushed, limit = merged.accum_last
+        assert limit == 700
+        open_rows += len(u)
+        if flushed:
+            moved, open_rows = moved + open_rows, 0
+        assert pending == open_rows
+    assert moved + merged.flush() == sum(len(r[0]) for r in a)
+    assert np.array_equal(plain.tags, merged.tags) and np.array_equal(plain.stamps, merged.stamps)
+
+
+def test_adaptive_accumulator_threshold_follows_the_redirected_share(oracle_mod):
+    """Section 3.2, last paragraph: the threshold follows the accesses that are redirected to CPU / GPU
+    memory.  With N store accesses wanted per launch, the node-access threshold is ceil(N * A / S) over the
+    gathers at least 16 back (A node accesses, S store accesses), within [N, 8 N]."""
+    LAG, N = 16, 50
+    # (1) nothing is redirected and lists hold no repeats: every node access is a store access, threshold N
+    sim = oracle_mod.Sim(10_000, 4, 4, 0)                       # a 4-line cache: practically everything misses
+    sim.set_accum(N, 1)
+    for t in range(60):
+        sim.gather(np.arange(100 * t, 100 * t + 20))
+        assert sim.accum_last[2] == N
+    # (2) every ID listed twice: two node accesses per store access, threshold 2 N once counters 16 back exist
+    sim = oracle_mod.Sim(10_000, 4, 4, 0)
+    sim.set_accum(N, 1)
+    for t in range(60):
+        ids = np.arange(100 * t, 100 * t + 20)
+        sim.gather(np.concatenate([ids, ids]))
+        assert sim.accum_last[2] == (N if t <= LAG else 2 * N), t
+    # (3) a quarter of the IDs pinned in the CPU buffer: 4 node accesses per 3 store accesses
+    sim = oracle_mod.Sim(10_000, 4, 4, 0)
+    sim.set_hot(np.arange(0, 10_000, 4))
+    sim.set_accum(N, 1)
+    for t in range(60):
+        sim.gather(np.arange(100 * t, 100 * t + 40))
+        assert sim.accum_last[2] == (N if t <= LAG else -(-N * 4 // 3)), t
+    # (4) a cache that holds everything: store accesses stop, the share redirected tends to 1, bounded at 8 N;
+    #     against the definition written out
+    sim = oracle_mod.Sim(64, 64, 4, 0)
+    sim.set_accum(N, 1)
+    A, S, hist = 0, 0, []
+    for t in range(200):
+        raw = np.arange(64) if t % 2 else np.arange(0, 64, 2)
+        _, _, stats = sim.gather(raw)
+        hist.append((len(raw), int(stats[3])))
+        A = sum(h[0] for h in hist[:max(0, t - LAG)])
+        S = sum(h[1] for h in hist[:max(0, t - LAG)])
+        want = N if A == 0 else (8 * N if S == 0 else min(8 * N, max(N, -(-N * A // S))))
+        assert sim.accum_last[2] == want, t
+    assert sim.accum_last[2] == 8 * N
+
+
 def test_line_fills_happen_without_output_rows(oracle_mod):
     """A minibatch gathered for its counters only still fills the lines it
     installs: later hits on them must return the store's bytes."""
