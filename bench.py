@@ -79,7 +79,12 @@ def main() -> int:
                     help="cache lines that hold this many consecutive node rows (line_bytes = rows x row_bytes, the "
                          "cache keeps its size in bytes): a miss brings the whole line in")
     ap.add_argument("--cache-lines", type=int, default=0, help="override the number of cache lines (rounded to ways)")
-    ap.add_argument("--accum", type=int, default=0, help="accumulator threshold (0 = every gather moves its own rows)")
+    ap.add_argument("--accum", type=int, default=0,
+                    help="accumulator threshold in node accesses (raw list entries) per merged group of minibatches "
+                         "(0 = every gather moves its own rows)")
+    ap.add_argument("--accum-adaptive", action="store_true",
+                    help="read --accum as the store accesses wanted per launch (Eq. 2-3's N) and let the library "
+                         "raise the node-access threshold by the redirected share (Section 3.2)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="time budget of the oracle leg")
     ap.add_argument("--pass-ids", action="store_true",
                     help="hand the raw ID list to gather again (it is then deduplicated a second time and checked "
@@ -265,6 +270,8 @@ def run_point(args, env, cfg, window, raws, n_pre):
         ses.set_policy(gids.GIDS_POLICY_RANDOM, cfg.seed)
     if args.rows_per_line > 1:
         ses.set_rows_per_line(args.rows_per_line)
+    if args.accum and args.accum_adaptive:
+        ses.set_accum_mode(gids.GIDS_ACCUM_ADAPTIVE)
     log(f"cache W={window}: created, CPU buffer {len(hot) * R / 1e9:.2f} GB pinned ({time.time() - t0:.1f} s)")
     dev = [ses.to_device(r) for r in raws[:n_batches]]
     sampler = None
@@ -284,7 +291,8 @@ def run_point(args, env, cfg, window, raws, n_pre):
             f"{time.time() - t0:.1f} s), raw capacity {cap_raw} IDs per minibatch")
     cap_rows = max(len(np.unique(r)) for r in raws[:n_batches])
     # outputs rotate; with the accumulator on, an output must survive until the flush that completes it
-    ring = 2 if args.accum == 0 else 32
+    # (a group holds at most GIDS_ACCUM_MAX_MERGE = 32 minibatches, so a buffer is complete before its turn comes again)
+    ring = 2 if args.accum == 0 else 40
     outs = [torch.empty((cap_rows, R), dtype=torch.uint8, device="cuda") for _ in range(ring)]
     uniq = torch.empty(cap_rows, dtype=ses.torch_id, device="cuda")
     torch.cuda.synchronize()
@@ -321,10 +329,7 @@ def run_point(args, env, cfg, window, raws, n_pre):
 
     def step(t):
         keep_window_full(t)                                     # push of minibatch t + W (+1 at start-up)
-        seq = ses.gather(dev[t] if args.pass_ids else None, outs[t % ring], uniq)
-        if args.accum and t % ring == ring - 2:
-            ses.flush()
-        return seq
+        return ses.gather(dev[t] if args.pass_ids else None, outs[t % ring], uniq)
 
     seqs = {}
     for t in range(warmup):
@@ -471,7 +476,7 @@ def run_point(args, env, cfg, window, raws, n_pre):
         "unique_ids_per_s": n_unique * scale / (total_ms * 1e-3),
         "config": {"workload": cfg.name, "n_nodes": cfg.n_nodes, "row_bytes": R, "cache_lines": cfg.cache_lines,
                    "ways": cfg.ways, "line_bytes": cfg.line_bytes, "cpu_buffer_rows": cfg.cpu_rows, "window": window,
-                   "fanouts": list(cfg.fanouts), "seeds_per_batch": cfg.n_seeds, "accum_threshold": args.accum, "prewarm_lists": n_pre, "gpu_sampler": bool(args.gpu_sampler), "policy": args.policy, "hot_by": args.hot_by, "rows_per_line": args.rows_per_line, "id_stream": ("layerwise " + args.layerwise) if args.layerwise else "neighbourhood",
+                   "fanouts": list(cfg.fanouts), "seeds_per_batch": cfg.n_seeds, "accum_threshold": args.accum, "accum_adaptive": bool(args.accum_adaptive), "prewarm_lists": n_pre, "gpu_sampler": bool(args.gpu_sampler), "policy": args.policy, "hot_by": args.hot_by, "rows_per_line": args.rows_per_line, "id_stream": ("layerwise " + args.layerwise) if args.layerwise else "neighbourhood",
                    "id_dtype": cfg.index_dtype, "scaled_from": base.n_nodes if cfg.n_nodes != base.n_nodes else None},
         "per_step": {"unique": n_unique * scale / steps, "hit": n_hit * scale / steps, "cpu_hit": n_cpu * scale / steps,
                      "miss": n_miss * scale / steps, "bypass": n_byp * scale / steps,

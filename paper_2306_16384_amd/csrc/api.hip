@@ -193,6 +193,7 @@ struct gids_cache {
             return;
         }
     }
+    uint64_t fused_max = 16384; // lists up to this length are classified by the fused kernel (GIDS_FUSED_MAX)
     int move_blocks = 1 << 20;  // most workgroups the row mover uses for rows that stay in HBM
     int link_blocks = 48;       // ... for rows that cross the host link (persistent)
     bool wide_index = false;    // GIDS_WIDE_INDEX=1: 64-bit set arithmetic even where 32 bits would do (for tests)
@@ -337,6 +338,7 @@ struct CacheT final : gids_cache {
         // before the previous one, whose rows have long moved, and not by the one still moving
         slots.resize(window + 2);
         if (const char* env = getenv("GIDS_WIDE_INDEX")) wide_index = atoi(env) != 0;
+        if (const char* env = getenv("GIDS_FUSED_MAX")) fused_max = (uint64_t)std::max(0ll, atoll(env));
         if (const char* env = getenv("GIDS_MOVE_BLOCKS")) {
             const int b = atoi(env);
             if (b >= 1 && b <= (1 << 20)) move_blocks = b;
@@ -646,11 +648,19 @@ struct CacheT final : gids_cache {
         }
         const CacheView<IdT> c = view();
         if ((rc = mark_phase(r, 1, m))) return rc;
-        launch_probe<IdT>(c, U, n_u, n_upper, out_cap, head_list, b.pl, m);
-        launch_victim<IdT>(c, U, n_u, n_upper, b.pl, m);
-        launch_commit<IdT>(c, U, n_u, n_upper, b.pl, b.hd, opens ? (int)(group & 1) : -1, m);
+        const int accum_flags = threshold ? 4 | (closes ? 1 : 0) | (opens ? 2 : 0) : 0;
+        // short lists: classification, queueing and counters in one launch
+        const bool fused = n_upper <= fused_max && ways <= classify_max_ways() && rows_per_line == 1;
+        if (fused) {
+            launch_classify<IdT>(c, accum_view(), group, accum_flags, U, n_u, n_upper, out_cap, head_list, b.pl, b.hd,
+                                 static_cast<char*>(out), static_cast<IdT*>(unique), ring_dev + r, seq, m);
+        } else {
+            launch_probe<IdT>(c, U, n_u, n_upper, out_cap, head_list, b.pl, m);
+            launch_victim<IdT>(c, U, n_u, n_upper, b.pl, m);
+            launch_commit<IdT>(c, U, n_u, n_upper, b.pl, b.hd, m);
+        }
         if (threshold == 0) {
-            launch_finalize(ctl, ring_dev + r, seq, n_u, 0, m);
+            if (!fused) launch_finalize(ctl, ring_dev + r, seq, n_u, 0, m);
             if ((rc = mark_phase(r, 2, m))) return rc;
             if (pipelined) {
                 HIP_TRY(hipEventRecord(ev_meta[r], meta));
@@ -663,9 +673,11 @@ struct CacheT final : gids_cache {
         } else {
             // nothing moves yet: the minibatch's rows join the open group's lists (on the metadata stream, so
             // that the next minibatch is classified while an earlier group is still moving)
-            launch_queue<IdT>(c, accum_view(), group, U, b.hd, n_upper, b.pl, static_cast<char*>(out),
-                              static_cast<IdT*>(unique), m);
-            launch_finalize(ctl, ring_dev + r, seq, n_u, 4 | (closes ? 1 : 0) | (opens ? 2 : 0), m);
+            if (!fused) {
+                launch_queue<IdT>(c, accum_view(), group, U, b.hd, n_upper, b.pl, static_cast<char*>(out),
+                                  static_cast<IdT*>(unique), m);
+                launch_finalize(ctl, ring_dev + r, seq, n_u, accum_flags, m);
+            }
             if ((rc = mark_phase(r, 2, m))) return rc;
             raw_of[r] = (uint32_t)n_raw;
             open_nodes += n_raw;

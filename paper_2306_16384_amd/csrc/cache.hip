@@ -34,26 +34,6 @@ constexpr int CT_THREADS = 256;
 
 __device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63; }
 
-__device__ __forceinline__ uint64_t mix64(uint64_t z) {
-    z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ull;
-    z ^= z >> 27; z *= 0x94D049BB133111EBull;
-    z ^= z >> 31;
-    return z;
-}
-
-template <typename IdT>
-__device__ __forceinline__ void set_and_round(const CacheView<IdT>& c, uint64_t v, uint64_t* set, uint64_t* round) {
-    if (c.use32) {
-        const uint32_t q = (uint32_t)v / (uint32_t)c.n_sets;
-        *round = q;
-        *set = (uint32_t)v - q * (uint32_t)c.n_sets;
-    } else {
-        const uint64_t q = v / c.n_sets;
-        *round = q;
-        *set = v - q * c.n_sets;
-    }
-}
-
 // bits of a 64-lane ballot that belong to this lane's group of `ways` lanes
 __device__ __forceinline__ uint64_t group_bits(uint64_t ballot, uint32_t ways) {
     const uint32_t base = lane_id() & ~(ways - 1);
@@ -255,9 +235,8 @@ __global__ __launch_bounds__(CT_THREADS) void victim_kernel(CacheView<IdT> c, co
 template <typename IdT>
 __global__ __launch_bounds__(CT_THREADS) void commit_kernel(CacheView<IdT> c, const IdT* __restrict__ unique,
                                                             const uint32_t* __restrict__ n_u_ptr,
-                                                            const uint64_t* __restrict__ plan, BatchHdr* hdr,
-                                                            int reset_parity) {
-    Ctl* ctl = c.ctl;
+                                                            const uint64_t* __restrict__ plan, BatchHdr* hdr) {
+    const Ctl* ctl = c.ctl;
     const bool ok = ctl->error == 0;
     const uint32_t n_u = ok ? *n_u_ptr : 0;
     const uint32_t stamp = ctl->stamp;
@@ -266,10 +245,6 @@ __global__ __launch_bounds__(CT_THREADS) void commit_kernel(CacheView<IdT> c, co
         hdr->n_u = n_u;
         hdr->stamp = stamp;
         hdr->next_chunk = 0;
-        if (reset_parity >= 0) {                             // first gather of an accumulator group: empty its lists
-            ctl->q_fill[reset_parity] = ctl->q_rcopy[reset_parity] = ctl->q_wcopy[reset_parity] = 0;
-            ctl->q_chunk[reset_parity] = 0;
-        }
     }
     if (!ok || ctl->cnt_miss == 0) return;
     for (uint64_t j = (uint64_t)blockIdx.x * CT_THREADS + threadIdx.x; j < n_u; j += (uint64_t)gridDim.x * CT_THREADS) {
@@ -315,12 +290,11 @@ void launch_probe(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_
 
 template <typename IdT>
 void launch_commit(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_u, uint64_t n_upper,
-                   const uint64_t* plan, BatchHdr* hdr, int reset_parity, hipStream_t s) {
+                   const uint64_t* plan, BatchHdr* hdr, hipStream_t s) {
     uint64_t b = (n_upper + CT_THREADS - 1) / CT_THREADS;
     if (b < 1) b = 1;
     if (b > 1024) b = 1024;
-    hipLaunchKernelGGL(commit_kernel<IdT>, dim3((uint32_t)b), dim3(CT_THREADS), 0, s, c, unique, n_u, plan, hdr,
-                       reset_parity);
+    hipLaunchKernelGGL(commit_kernel<IdT>, dim3((uint32_t)b), dim3(CT_THREADS), 0, s, c, unique, n_u, plan, hdr);
 }
 
 template <typename IdT>
@@ -334,7 +308,7 @@ void launch_victim(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n
     template void launch_probe<IdT>(const CacheView<IdT>&, const IdT*, const uint32_t*, uint64_t, uint64_t, bool,   \
                                     uint64_t*, hipStream_t);                                                        \
     template void launch_commit<IdT>(const CacheView<IdT>&, const IdT*, const uint32_t*, uint64_t, const uint64_t*, \
-                                     BatchHdr*, int, hipStream_t);                                                       \
+                                     BatchHdr*, hipStream_t);                                                       \
     template void launch_victim<IdT>(const CacheView<IdT>&, const IdT*, const uint32_t*, uint64_t, uint64_t*,       \
                                      hipStream_t);
 GIDS_INSTANTIATE(int32_t)

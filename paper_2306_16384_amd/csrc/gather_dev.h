@@ -1,0 +1,136 @@
+// Device code shared by the per-step kernels and the fused classification
+// kernel: appending one plan entry to the accumulator's lists, and publishing
+// a minibatch's counters.
+#pragma once
+
+#include "gids_dev.h"
+
+namespace gids {
+
+// The accumulator's treatment of plan entry j (Section 3.2: nothing moves while a group of minibatches is
+// open; every row becomes an operation in the group's lists).  Called by all 64 lanes of a wavefront
+// together, `valid` false for lanes without an entry; the lanes' entries may be any distinct j.
+//   fills    rows that cross the host link (CPU-buffer rows, store rows), each to its output row and, for an
+//            installed miss, to its cache line;
+//   rcopies  hits on lines that hold their bytes: cache line -> output row;
+//   wcopies  copies that must run after the fills: a hit on a line whose fill is queued in the same group
+//            reads the output row that fill writes; an installed miss whose line a queued rcopy still reads
+//            (the line was hit earlier in the group and evicted since) fills its line late, from its own
+//            output row, so that the rcopy sees the old bytes.
+// A line installed twice in one group is filled by the last install only (the earlier fill keeps its output
+// row).  Every line is touched by at most one plan entry per minibatch, so the per-line words are written
+// without atomics.
+template <typename IdT>
+__device__ __forceinline__ void queue_entry(const CacheView<IdT>& c, const AccumView& a, uint32_t group, bool valid,
+                                            uint64_t j, uint64_t e, uint64_t v, char* __restrict__ out,
+                                            IdT* __restrict__ unique_out) {
+    Ctl* ctl = c.ctl;
+    const uint32_t par = group & 1u;
+    FillOp* __restrict__ fills = a.fills[par];
+    CopyOp* __restrict__ rcopies = a.rcopies[par];
+    CopyOp* __restrict__ wcopies = a.wcopies[par];
+    const uint32_t lane = threadIdx.x & 63;
+    const uint64_t kind = valid ? e >> PLAN_SHIFT : PLAN_HIT, idx = e & PLAN_INDEX_MASK;
+    if (valid && unique_out) unique_out[j] = (IdT)v;
+    const bool has_line = valid && (kind == PLAN_HIT || kind == PLAN_INSTALL);
+    uint32_t fg = ~0u, hg = ~0u, pd = NO_OP;
+    if (has_line) {
+        fg = c.fillgrp[idx];
+        hg = c.hitgrp[idx];
+        pd = c.pending[idx];
+    }
+    const bool open_fill = has_line && fg == group;               // the line's fill is queued in this group
+    const bool is_fill = valid && kind != PLAN_HIT;
+    const bool is_wait = valid && kind == PLAN_HIT && open_fill;
+    const bool is_ready = valid && kind == PLAN_HIT && !open_fill;
+    const bool is_late = valid && kind == PLAN_INSTALL && hg == group;   // a queued rcopy still reads the old bytes
+    const uint64_t fb = __ballot(is_fill), rb = __ballot(is_ready), wb = __ballot(is_wait || is_late);
+    uint32_t fbase = 0, rbase = 0, wbase = 0;
+    if (lane == 0) {
+        if (fb) fbase = atomicAdd(&ctl->q_fill[par], (uint32_t)__popcll(fb));
+        if (rb) rbase = atomicAdd(&ctl->q_rcopy[par], (uint32_t)__popcll(rb));
+        if (wb) wbase = atomicAdd(&ctl->q_wcopy[par], (uint32_t)__popcll(wb));
+    }
+    fbase = __shfl(fbase, 0);
+    rbase = __shfl(rbase, 0);
+    wbase = __shfl(wbase, 0);
+    // the host sizes the lists for the group's longest possible content; a list that would overflow all
+    // the same is an error, never a write past its end
+    if ((uint64_t)fbase + __popcll(fb) > a.cap || (uint64_t)rbase + __popcll(rb) > a.cap ||
+        (uint64_t)wbase + __popcll(wb) > a.cap) {
+        if (lane == 0) atomicCAS(&ctl->error, 0u, 7u /* -GIDS_E_SPACE */);
+        return;
+    }
+    const uint64_t below = (1ull << lane) - 1;
+    char* dst = out + j * c.row_bytes;
+    const uint32_t w = wbase + (uint32_t)__popcll(wb & below);
+    if (is_fill) {
+        const uint32_t q = fbase + (uint32_t)__popcll(fb & below);
+        FillOp op;
+        op.src = kind == PLAN_CPU ? c.cpubuf + idx * c.row_bytes : c.store + v * c.row_bytes;
+        op.dst_out = dst;
+        op.dst_line = NO_LINE;
+        op.late = NO_OP;
+        op.pad = 0;
+        if (kind == PLAN_INSTALL) {
+            if (open_fill) {                                  // superseded before it ever ran: output only
+                fills[pd].dst_line = NO_LINE;
+                const uint32_t lt = fills[pd].late;
+                if (lt != NO_OP) wcopies[lt].dst = nullptr;
+            }
+            char* line = c.cache_data + idx * c.line_bytes;
+            if (is_late) {
+                wcopies[w].src = dst;
+                wcopies[w].dst = line;
+                op.late = w;
+            } else {
+                op.dst_line = idx;
+            }
+            c.fillgrp[idx] = group;
+            c.pending[idx] = q;
+        }
+        fills[q] = op;
+    }
+    if (is_wait) {
+        wcopies[w].src = fills[pd].dst_out;
+        wcopies[w].dst = dst;
+    }
+    if (is_ready) {
+        const uint32_t r = rbase + (uint32_t)__popcll(rb & below);
+        rcopies[r].src = c.cache_data + idx * c.line_bytes;
+        rcopies[r].dst = dst;
+        c.hitgrp[idx] = group;
+    }
+}
+
+// The counters of one gather go to its record in host-visible memory, the minibatch index advances.
+// accum: 0 = no accumulator; otherwise bit 0 = this gather closes its group, bit 1 = it opened the group.
+// One thread, after every other write of the gather.
+__device__ __forceinline__ void publish_stats(Ctl* ctl, StatsRec* rec, uint64_t seq, uint32_t n_u, int accum) {
+    const uint32_t err = ctl->error;
+    const uint32_t n = err ? 0 : n_u;
+    rec->n_unique = n;
+    rec->n_hit = ctl->cnt_hit;
+    rec->n_cpu_hit = ctl->cnt_cpu;
+    rec->n_miss = ctl->cnt_miss;
+    rec->n_bypass = ctl->cnt_bypass;
+    rec->n_line_fills = ctl->cnt_fill;
+    uint32_t queued = 0;
+    int flushed = 1;
+    if (accum) {                          // rows of the open group that have not moved when this gather ends
+        const bool closes = (accum & 1) != 0, opens = (accum & 2) != 0;
+        queued = closes ? 0u : (opens ? 0u : ctl->q_rows) + n;
+        ctl->q_rows = queued;
+        flushed = closes ? 1 : 0;
+    }
+    rec->n_pending = queued;
+    rec->flushed = flushed;
+    rec->status = -(int32_t)err;
+    __threadfence_system();
+    rec->seq = seq;                       // written last: a record whose seq matches is complete
+    __threadfence_system();
+    if (!err) ctl->stamp += 1;
+    ctl->cnt_hit = ctl->cnt_cpu = ctl->cnt_miss = ctl->cnt_bypass = ctl->cnt_fill = 0;
+}
+
+}  // namespace gids

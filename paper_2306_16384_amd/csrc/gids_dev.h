@@ -27,6 +27,8 @@ struct Ctl {
     uint32_t n_unique;      // distinct IDs of the list deduplicated last
     uint32_t error;         // first error a kernel found (-GIDS_E_*), 0 = none; sticky
     uint32_t ticket;        // arrival counter for "last block does the scan"
+    uint32_t ticket_flush;  // ... for "last block of the group mover empties the group's lists"
+    uint32_t ticket_cls;    // ... for "last block of the fused classification publishes the counters"
     uint32_t stamp;         // index of the minibatch being gathered (successful gathers so far)
     uint32_t cnt_hit, cnt_cpu, cnt_miss, cnt_bypass;
     uint32_t cnt_fill;      // cache lines this minibatch fills
@@ -98,6 +100,27 @@ struct CacheView {
     Ctl* ctl;
 };
 
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+    z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ull;
+    z ^= z >> 27; z *= 0x94D049BB133111EBull;
+    z ^= z >> 31;
+    return z;
+}
+
+// set = v mod n_sets, round = v div n_sets (the position of v among the IDs that share its set)
+template <typename IdT>
+__device__ __forceinline__ void set_and_round(const CacheView<IdT>& c, uint64_t v, uint64_t* set, uint64_t* round) {
+    if (c.use32) {
+        const uint32_t q = (uint32_t)v / (uint32_t)c.n_sets;
+        *round = q;
+        *set = (uint32_t)v - q * (uint32_t)c.n_sets;
+    } else {
+        const uint64_t q = v / c.n_sets;
+        *round = q;
+        *set = v - q * c.n_sets;
+    }
+}
+
 // the store line (the cache's tag) that holds row v
 template <typename IdT>
 __device__ __forceinline__ uint64_t store_line_of(const CacheView<IdT>& c, uint64_t v) {
@@ -147,7 +170,7 @@ void launch_victim(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n
 
 template <typename IdT>
 void launch_commit(const CacheView<IdT>& c, const IdT* unique, const uint32_t* n_u, uint64_t n_upper,
-                   const uint64_t* plan, BatchHdr* hdr, int reset_parity, hipStream_t s);
+                   const uint64_t* plan, BatchHdr* hdr, hipStream_t s);
 
 template <typename IdT>
 void launch_move(const CacheView<IdT>& c, const IdT* unique, BatchHdr* hdr, uint64_t n_upper,
@@ -164,6 +187,13 @@ struct AccumView {
 template <typename IdT>
 void launch_queue(const CacheView<IdT>& c, const AccumView& a, uint32_t group, const IdT* unique, const BatchHdr* hdr,
                   uint64_t n_upper, const uint64_t* plan, char* out, IdT* unique_out, hipStream_t s);
+
+// probe + victim + commit (+ queue) + finalize in one launch, for short lists and ways <= classify_max_ways()
+uint32_t classify_max_ways();
+template <typename IdT>
+void launch_classify(const CacheView<IdT>& c, const AccumView& a, uint32_t group, int accum, const IdT* unique,
+                     const uint32_t* n_u, uint64_t n_upper, uint64_t out_capacity, bool pop_window, uint64_t* plan,
+                     BatchHdr* hdr, char* out, IdT* unique_out, StatsRec* rec, uint64_t seq, hipStream_t s);
 
 template <typename IdT>
 void launch_group_move(const CacheView<IdT>& c, const AccumView& a, uint32_t parity, uint64_t rows_upper,

@@ -18,6 +18,7 @@
 #include <cstdlib>
 
 #include "gids_dev.h"
+#include "gather_dev.h"
 
 namespace gids {
 
@@ -147,116 +148,28 @@ __global__ __launch_bounds__(MV_THREADS) void move_kernel(CacheView<IdT> c, cons
     }
 }
 
-// The accumulator (Section 3.2: the accesses of consecutive minibatches are merged until enough are in
-// flight, then issued in one launch).  While a group of minibatches is open, the queue kernel turns each
-// minibatch's plan into operations in three lists instead of moving rows:
-//   fills    rows that cross the host link (CPU-buffer rows, store rows), each to its output row and, for an
-//            installed miss, to its cache line;
-//   rcopies  hits on lines that hold their bytes: cache line -> output row;
-//   wcopies  copies that must run after the fills: a hit on a line whose fill is queued in the same group
-//            reads the output row that fill writes; an installed miss whose line a queued rcopy still reads
-//            (the line was hit earlier in the group and evicted since) fills its line late, from its own
-//            output row, so that the rcopy sees the old bytes.
-// When the group closes, the group mover runs fills and rcopies in one launch and wcopies in a second.
-// A line installed twice in one group is filled by the last install only (the earlier fill keeps its output
-// row).  Every line is touched by at most one plan entry per minibatch, so the per-line words below are
-// written without atomics.
+// The accumulator's variant of the row mover: one plan entry per lane, appended to the open group's lists
+// (queue_entry).
 template <typename IdT>
 __global__ __launch_bounds__(MV_THREADS) void queue_kernel(CacheView<IdT> c, AccumView a, uint32_t group,
                                                            const IdT* __restrict__ unique,
                                                            const BatchHdr* __restrict__ hdr,
                                                            const uint64_t* __restrict__ plan, char* __restrict__ out,
                                                            IdT* __restrict__ unique_out) {
-    Ctl* ctl = c.ctl;
     if (!hdr->ok) return;
     const uint32_t n_u = hdr->n_u;
-    const uint32_t par = group & 1u;
-    FillOp* __restrict__ fills = a.fills[par];
-    CopyOp* __restrict__ rcopies = a.rcopies[par];
-    CopyOp* __restrict__ wcopies = a.wcopies[par];
     const uint32_t lane = threadIdx.x & 63;
     const uint64_t wave0 = ((uint64_t)blockIdx.x * MV_THREADS + threadIdx.x) >> 6;
     const uint64_t n_waves = ((uint64_t)gridDim.x * MV_THREADS) >> 6;
     for (uint64_t base = wave0 * 64; base < n_u; base += n_waves * 64) {
         const uint64_t j = base + lane;
         const bool valid = j < n_u;
-        uint64_t e = 0, v = 0, idx = 0, kind = PLAN_HIT;
+        uint64_t e = 0, v = 0;
         if (valid) {
             e = plan[j];
             v = (uint64_t)unique[j];
-            kind = e >> PLAN_SHIFT;
-            idx = e & PLAN_INDEX_MASK;
-            if (unique_out) unique_out[j] = (IdT)v;
         }
-        const bool has_line = valid && (kind == PLAN_HIT || kind == PLAN_INSTALL);
-        uint32_t fg = ~0u, hg = ~0u, pd = NO_OP;
-        if (has_line) {
-            fg = c.fillgrp[idx];
-            hg = c.hitgrp[idx];
-            pd = c.pending[idx];
-        }
-        const bool open_fill = has_line && fg == group;               // the line's fill is queued in this group
-        const bool is_fill = valid && kind != PLAN_HIT;
-        const bool is_wait = valid && kind == PLAN_HIT && open_fill;
-        const bool is_ready = valid && kind == PLAN_HIT && !open_fill;
-        const bool is_late = valid && kind == PLAN_INSTALL && hg == group;   // a queued rcopy still reads the old bytes
-        const uint64_t fb = __ballot(is_fill), rb = __ballot(is_ready), wb = __ballot(is_wait || is_late);
-        uint32_t fbase = 0, rbase = 0, wbase = 0;
-        if (lane == 0) {
-            if (fb) fbase = atomicAdd(&ctl->q_fill[par], (uint32_t)__popcll(fb));
-            if (rb) rbase = atomicAdd(&ctl->q_rcopy[par], (uint32_t)__popcll(rb));
-            if (wb) wbase = atomicAdd(&ctl->q_wcopy[par], (uint32_t)__popcll(wb));
-        }
-        fbase = __shfl(fbase, 0);
-        rbase = __shfl(rbase, 0);
-        wbase = __shfl(wbase, 0);
-        // the host sizes the lists for the group's longest possible content; a list that would overflow all
-        // the same is an error, never a write past its end
-        if ((uint64_t)fbase + __popcll(fb) > a.cap || (uint64_t)rbase + __popcll(rb) > a.cap ||
-            (uint64_t)wbase + __popcll(wb) > a.cap) {
-            if (lane == 0) atomicCAS(&ctl->error, 0u, 7u /* -GIDS_E_SPACE */);
-            continue;
-        }
-        const uint64_t below = (1ull << lane) - 1;
-        char* dst = out + j * c.row_bytes;
-        const uint32_t w = wbase + (uint32_t)__popcll(wb & below);
-        if (is_fill) {
-            const uint32_t q = fbase + (uint32_t)__popcll(fb & below);
-            FillOp op;
-            op.src = kind == PLAN_CPU ? c.cpubuf + idx * c.row_bytes : c.store + v * c.row_bytes;
-            op.dst_out = dst;
-            op.dst_line = NO_LINE;
-            op.late = NO_OP;
-            op.pad = 0;
-            if (kind == PLAN_INSTALL) {
-                if (open_fill) {                              // superseded before it ever ran: output only
-                    fills[pd].dst_line = NO_LINE;
-                    const uint32_t lt = fills[pd].late;
-                    if (lt != NO_OP) wcopies[lt].dst = nullptr;
-                }
-                char* line = c.cache_data + idx * c.line_bytes;
-                if (is_late) {
-                    wcopies[w].src = dst;
-                    wcopies[w].dst = line;
-                    op.late = w;
-                } else {
-                    op.dst_line = idx;
-                }
-                c.fillgrp[idx] = group;
-                c.pending[idx] = q;
-            }
-            fills[q] = op;
-        }
-        if (is_wait) {
-            wcopies[w].src = fills[pd].dst_out;
-            wcopies[w].dst = dst;
-        }
-        if (is_ready) {
-            const uint32_t r = rbase + (uint32_t)__popcll(rb & below);
-            rcopies[r].src = c.cache_data + idx * c.line_bytes;
-            rcopies[r].dst = dst;
-            c.hitgrp[idx] = group;
-        }
+        queue_entry(c, a, group, valid, j, e, v, out, unique_out);
     }
 }
 
@@ -304,9 +217,10 @@ __global__ __launch_bounds__(MV_THREADS) void group_move_kernel(Ctl* ctl, const 
     }
 }
 
-// second launch: the copies that had to wait for the first
+// second launch: the copies that had to wait for the first.  The last workgroup to finish empties the group's
+// lists: the next group of this parity starts appending only after this kernel has ended.
 template <int G>
-__global__ __launch_bounds__(MV_THREADS) void group_copy_kernel(const Ctl* ctl, const CopyOp* __restrict__ wcopies,
+__global__ __launch_bounds__(MV_THREADS) void group_copy_kernel(Ctl* ctl, const CopyOp* __restrict__ wcopies,
                                                                 uint32_t row_bytes, uint32_t par) {
     const uint32_t n = ctl->q_wcopy[par];
     const uint32_t row_u4 = row_bytes >> 4;
@@ -317,6 +231,14 @@ __global__ __launch_bounds__(MV_THREADS) void group_copy_kernel(const Ctl* ctl, 
         const CopyOp op = wcopies[k];
         if (!op.dst) continue;                                // cancelled: its line was given away again
         copy_row<G>(reinterpret_cast<const v4u*>(op.src), reinterpret_cast<v4u*>(op.dst), nullptr, row_u4, sub);
+    }
+    __syncthreads();                                          // every thread of the block has read n
+    if (threadIdx.x == 0) {
+        __threadfence();
+        if (atomicAdd(&ctl->ticket_flush, 1u) == gridDim.x - 1) {
+            ctl->q_fill[par] = ctl->q_rcopy[par] = ctl->q_wcopy[par] = ctl->q_chunk[par] = 0;
+            ctl->ticket_flush = 0;
+        }
     }
 }
 
@@ -340,30 +262,7 @@ __global__ __launch_bounds__(MV_THREADS) void calibrate_kernel(const char* __res
 
 // accum: 0 = no accumulator; otherwise bit 0 = this gather closes its group, bit 1 = it opened the group
 __global__ void finalize_kernel(Ctl* ctl, StatsRec* rec, uint64_t seq, const uint32_t* n_u, int accum) {
-    const uint32_t err = ctl->error;
-    const uint32_t n = err ? 0 : *n_u;
-    rec->n_unique = n;
-    rec->n_hit = ctl->cnt_hit;
-    rec->n_cpu_hit = ctl->cnt_cpu;
-    rec->n_miss = ctl->cnt_miss;
-    rec->n_bypass = ctl->cnt_bypass;
-    rec->n_line_fills = ctl->cnt_fill;
-    uint32_t queued = 0;
-    int flushed = 1;
-    if (accum) {                          // rows of the open group that have not moved when this gather ends
-        const bool closes = (accum & 1) != 0, opens = (accum & 2) != 0;
-        queued = closes ? 0u : (opens ? 0u : ctl->q_rows) + n;
-        ctl->q_rows = queued;
-        flushed = closes ? 1 : 0;
-    }
-    rec->n_pending = queued;
-    rec->flushed = flushed;
-    rec->status = -(int32_t)err;
-    __threadfence_system();
-    rec->seq = seq;                       // written last: a record whose seq matches is complete
-    __threadfence_system();
-    if (!err) ctl->stamp += 1;
-    ctl->cnt_hit = ctl->cnt_cpu = ctl->cnt_miss = ctl->cnt_bypass = ctl->cnt_fill = 0;
+    publish_stats(ctl, rec, seq, *n_u, accum);
 }
 
 inline int lanes_per_row(uint32_t row_bytes) {

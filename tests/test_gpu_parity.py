@@ -23,9 +23,10 @@ def gpu():
 
 def run_case(gpu, oracle, feats, batches, *, id_dtype, lines, ways, line_bytes, window, threshold=0, hot=None,
              use_head=False, with_inverse=False, check_state=True, two_streams=False, policy=None, label="",
-             pipeline=None, push_depth0=False, wide_index=False, rows_per_line=1, accum_mode=0):
+             pipeline=None, push_depth0=False, wide_index=False, rows_per_line=1, accum_mode=0, fused=None):
     """Feeds the same raw ID lists to both implementations, protocol: keep window + 1 lists buffered.
     pipeline: "0" / "1" forces the library's internal stream off / on for this cache (GIDS_PIPELINE);
+    fused: True / False forces the fused classification kernel on (any list length) / off (GIDS_FUSED_MAX);
     push_depth0: at window depth 0, push every list just before its gather."""
     torch, gids, GatherSession = gpu
     n_rows = feats.shape[0]
@@ -58,6 +59,8 @@ def run_case(gpu, oracle, feats, batches, *, id_dtype, lines, ways, line_bytes, 
         knobs["GIDS_PIPELINE"] = pipeline
     if wide_index:
         knobs["GIDS_WIDE_INDEX"] = "1"                       # the arithmetic of stores with 2^32 rows and more
+    if fused is not None:
+        knobs["GIDS_FUSED_MAX"] = "1000000000" if fused else "0"   # one fused classification launch, or the kernel per step
     old_env = {k: os.environ.get(k) for k in knobs}
     os.environ.update(knobs)
     try:
@@ -199,14 +202,15 @@ def test_medium_config_first_batches(gpu, oracle_mod):
 
 # ------------------------------------------------------- shapes and policies
 
+@pytest.mark.parametrize("fused", [True, False])
 @pytest.mark.parametrize("ways", [1, 2, 4, 8, 16, 64])
-def test_associativity_sweep(gpu, oracle_mod, ways):
+def test_associativity_sweep(gpu, oracle_mod, ways, fused):
     rng = np.random.default_rng(100 + ways)
     n = 3000
     feats = rand_feats(rng, n, 256)
     lines = ways * 37                                          # 37 sets: not a power of two
     run_case(gpu, oracle_mod, feats, zipf_batches(rng, n, 14, 700, a=1.2), id_dtype=np.int64, lines=lines, ways=ways,
-             line_bytes=256, window=2, hot=rng.choice(n, 50, replace=False), label=f"ways{ways}")
+             line_bytes=256, window=2, hot=rng.choice(n, 50, replace=False), fused=fused, label=f"ways{ways}/fused{fused}")
 
 
 @pytest.mark.parametrize("window", [0, 1, 3, 9])
@@ -234,8 +238,9 @@ def test_many_ids_per_set_needs_multiword_miss_mask(gpu, oracle_mod):
     n = 20_000
     feats = rand_feats(rng, n, 64)
     batches = [rng.integers(0, n, size=5000) for _ in range(8)]        # ~20 % of all IDs per minibatch: heavy bypass
-    run_case(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=4 * 50, ways=4, line_bytes=64, window=1,
-             label="multiword")
+    for fused in (True, False):
+        run_case(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=4 * 50, ways=4, line_bytes=64, window=1,
+                 fused=fused, label=f"multiword/fused{fused}")
 
 
 def test_cache_as_large_as_store_all_hits_after_warmup(gpu, oracle_mod):
@@ -264,8 +269,9 @@ def test_long_raw_list_many_tiles(gpu, oracle_mod):
     n = 300_000
     feats = rand_feats(rng, n, 64)
     batches = [np.minimum(rng.zipf(1.1, size=700_001) - 1, n - 1) for _ in range(3)]
-    run_case(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=8 * 1024, ways=8, line_bytes=64, window=1,
-             hot=np.arange(0, 2000, 3), with_inverse=True, label="long")
+    for fused in (False, True):
+        run_case(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=8 * 1024, ways=8, line_bytes=64, window=1,
+                 hot=np.arange(0, 2000, 3), with_inverse=True, fused=fused, label=f"long/fused{fused}")
 
 
 # ---------------------------------------------------------------- accumulator
@@ -283,7 +289,7 @@ def test_accumulator_changes_nothing(gpu, oracle_mod, threshold, mode, window, p
     feats = rand_feats(rng, n, 256)
     run_case(gpu, oracle_mod, feats, zipf_batches(rng, n, 60, 400, a=1.2), id_dtype=np.int64, lines=128, ways=4,
              line_bytes=256, window=window, threshold=threshold, accum_mode=mode, hot=rng.choice(n, 60, replace=False),
-             pipeline=pipeline, two_streams=pipeline == "1", use_head=bool(window),
+             pipeline=pipeline, two_streams=pipeline == "1", use_head=bool(window), fused=bool(threshold % 7 % 2),
              label=f"accum{threshold}/mode{mode}/W{window}/pipe{pipeline}")
 
 
@@ -298,7 +304,7 @@ def test_accumulator_lines_reused_inside_a_group(gpu, oracle_mod, pipeline):
     batches = [rng.integers(0, 40, size=int(rng.integers(3, 25))) for _ in range(60)]   # 40 hot IDs over 8 lines
     for threshold in (60, 200, 10_000):
         run_case(gpu, oracle_mod, feats, batches, id_dtype=np.int32, lines=8, ways=2, line_bytes=R, window=0,
-                 threshold=threshold, pipeline=pipeline, label=f"accum-reuse/thr{threshold}/pipe{pipeline}")
+                 threshold=threshold, pipeline=pipeline, fused=False, label=f"accum-reuse/thr{threshold}/pipe{pipeline}")
         run_case(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=8, ways=8, line_bytes=R, window=2,
                  threshold=threshold, pipeline=pipeline, hot=np.array([3, 17]), use_head=True, two_streams=True,
                  label=f"accum-reuse/W2/thr{threshold}/pipe{pipeline}")
@@ -384,7 +390,7 @@ def test_device_found_errors(gpu, oracle_mod):
         assert s.stats(seq).n_unique == 1
 
 
-@pytest.mark.parametrize("window,ways", [(0, 4), (3, 8), (0, 64), (2, 1)])
+@pytest.mark.parametrize("window,ways", [(0, 4), (3, 8), (0, 64), (2, 1), (1, 16)])
 def test_random_base_policy(gpu, oracle_mod, window, ways):
     """The paper's base policy (random eviction), seeded: same victims as the oracle."""
     rng = np.random.default_rng(4242 + window + ways)
@@ -393,7 +399,7 @@ def test_random_base_policy(gpu, oracle_mod, window, ways):
     for seed in (0, 0xDEADBEEF12345):
         run_case(gpu, oracle_mod, feats, zipf_batches(rng, n, 25, 700, a=1.15), id_dtype=np.int64, lines=ways * 13,
                  ways=ways, line_bytes=128, window=window, hot=rng.choice(n, 40, replace=False),
-                 policy=(1, seed), label=f"random-policy/W{window}/ways{ways}")
+                 policy=(1, seed), fused=seed == 0, label=f"random-policy/W{window}/ways{ways}")
 
 
 # ------------------------------------------------------------- randomised
@@ -432,6 +438,7 @@ def test_random_configurations(gpu, oracle_mod, case):
         if extra["push_depth0"] and window == 0 and rng.random() < 0.5:
             extra["use_head_override"] = True
     use_head_override = extra.pop("use_head_override", False)
+    extra["fused"] = [None, True, False][case % 3]
     run_case(gpu, oracle_mod, feats, batches, id_dtype=id_dtype, lines=ways * n_sets, ways=ways, line_bytes=line_bytes,
              window=window, threshold=threshold, accum_mode=accum_mode,
              hot=rng.choice(n, n_hot, replace=False) if n_hot else None,
