@@ -16,7 +16,7 @@
 
 namespace gids {
 uint32_t scan_blocks(uint64_t n_words);
-}
+}  // namespace gids
 
 using namespace gids;
 
@@ -193,7 +193,8 @@ struct gids_cache {
             return;
         }
     }
-    uint64_t fused_max = 16384; // lists up to this length are classified by the fused kernel (GIDS_FUSED_MAX)
+    int fuse = 3;               // GIDS_FUSE: bit 0 = commit + queueing + counters in one launch, bit 1 = the bitmap count
+                                // inside the mark kernel (small tables)
     int move_blocks = 1 << 20;  // most workgroups the row mover uses for rows that stay in HBM
     int link_blocks = 48;       // ... for rows that cross the host link (persistent)
     bool wide_index = false;    // GIDS_WIDE_INDEX=1: 64-bit set arithmetic even where 32 bits would do (for tests)
@@ -338,7 +339,7 @@ struct CacheT final : gids_cache {
         // before the previous one, whose rows have long moved, and not by the one still moving
         slots.resize(window + 2);
         if (const char* env = getenv("GIDS_WIDE_INDEX")) wide_index = atoi(env) != 0;
-        if (const char* env = getenv("GIDS_FUSED_MAX")) fused_max = (uint64_t)std::max(0ll, atoll(env));
+        if (const char* env = getenv("GIDS_FUSE")) fuse = atoi(env) & 3;
         if (const char* env = getenv("GIDS_MOVE_BLOCKS")) {
             const int b = atoi(env);
             if (b >= 1 && b <= (1 << 20)) move_blocks = b;
@@ -486,10 +487,13 @@ struct CacheT final : gids_cache {
     // ascending distinct IDs of ids[0..n) -> dst; count -> *n_out (device)
     void dedup(const IdT* ids, uint64_t n, IdT* dst, uint32_t* n_out, uint8_t* reuse_inc, bool keep_bitmap,
                hipStream_t s, const uint32_t* n_dev = nullptr) {
-        launch_mark<IdT>(ids, n, n_dev, store->n_rows, bitmap, ctl, s);
-        // a bitmap that one block scans needs no separate count: that block's total is the distinct count
-        const bool solo = scan_blocks(n_words) == 1;
-        if (!solo) launch_count(bitmap, n_words, blocksum, blockoff, ctl, n_out, s);
+        // a bitmap that one block scans needs no separate count: that block's total is the distinct count;
+        // one of a few dozen blocks is counted by the mark kernel's last workgroup
+        const uint32_t nb = scan_blocks(n_words);
+        const bool solo = nb == 1;
+        const bool ride = !solo && (fuse & 2) && nb <= mark_count_max_blocks();
+        launch_mark<IdT>(ids, n, n_dev, store->n_rows, bitmap, ctl, s, ride ? nb : 0, blockoff, n_out);
+        if (!solo && !ride) launch_count(bitmap, n_words, blocksum, blockoff, ctl, n_out, s);
         launch_emit<IdT>(bitmap, n_words, store->n_rows, blockoff, dst, reuse_inc, keep_bitmap ? wrank : nullptr,
                          !keep_bitmap, ctl, solo ? n_out : nullptr, s);
     }
@@ -649,18 +653,18 @@ struct CacheT final : gids_cache {
         const CacheView<IdT> c = view();
         if ((rc = mark_phase(r, 1, m))) return rc;
         const int accum_flags = threshold ? 4 | (closes ? 1 : 0) | (opens ? 2 : 0) : 0;
-        // short lists: classification, queueing and counters in one launch
-        const bool fused = n_upper <= fused_max && ways <= classify_max_ways() && rows_per_line == 1;
-        if (fused) {
-            launch_classify<IdT>(c, accum_view(), group, accum_flags, U, n_u, n_upper, out_cap, head_list, b.pl, b.hd,
-                                 static_cast<char*>(out), static_cast<IdT*>(unique), ring_dev + r, seq, m);
+        launch_probe<IdT>(c, U, n_u, n_upper, out_cap, head_list, b.pl, m);
+        launch_victim<IdT>(c, U, n_u, n_upper, b.pl, m);
+        // commit, queueing and counters: one launch, or (GIDS_FUSE without bit 0) a kernel each
+        const bool settle = (fuse & 1) != 0;
+        if (settle) {
+            launch_settle<IdT>(c, accum_view(), group, accum_flags, U, n_u, n_upper, b.pl, b.hd, static_cast<char*>(out),
+                               static_cast<IdT*>(unique), ring_dev + r, seq, m);
         } else {
-            launch_probe<IdT>(c, U, n_u, n_upper, out_cap, head_list, b.pl, m);
-            launch_victim<IdT>(c, U, n_u, n_upper, b.pl, m);
             launch_commit<IdT>(c, U, n_u, n_upper, b.pl, b.hd, m);
         }
         if (threshold == 0) {
-            if (!fused) launch_finalize(ctl, ring_dev + r, seq, n_u, 0, m);
+            if (!settle) launch_finalize(ctl, ring_dev + r, seq, n_u, 0, m);
             if ((rc = mark_phase(r, 2, m))) return rc;
             if (pipelined) {
                 HIP_TRY(hipEventRecord(ev_meta[r], meta));
@@ -673,7 +677,7 @@ struct CacheT final : gids_cache {
         } else {
             // nothing moves yet: the minibatch's rows join the open group's lists (on the metadata stream, so
             // that the next minibatch is classified while an earlier group is still moving)
-            if (!fused) {
+            if (!settle) {
                 launch_queue<IdT>(c, accum_view(), group, U, b.hd, n_upper, b.pl, static_cast<char*>(out),
                                   static_cast<IdT*>(unique), m);
                 launch_finalize(ctl, ring_dev + r, seq, n_u, accum_flags, m);

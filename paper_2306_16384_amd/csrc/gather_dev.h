@@ -103,11 +103,15 @@ __device__ __forceinline__ void queue_entry(const CacheView<IdT>& c, const Accum
     }
 }
 
+__device__ __forceinline__ uint32_t ld_agent(const uint32_t* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // The counters of one gather go to its record in host-visible memory, the minibatch index advances.
 // accum: 0 = no accumulator; otherwise bit 0 = this gather closes its group, bit 1 = it opened the group.
 // One thread, after every other write of the gather.
 __device__ __forceinline__ void publish_stats(Ctl* ctl, StatsRec* rec, uint64_t seq, uint32_t n_u, int accum) {
-    const uint32_t err = ctl->error;
+    const uint32_t err = ld_agent(&ctl->error);          // (another workgroup of the same launch may have set it)
     const uint32_t n = err ? 0 : n_u;
     rec->n_unique = n;
     rec->n_hit = ctl->cnt_hit;

@@ -28,7 +28,7 @@ struct Ctl {
     uint32_t error;         // first error a kernel found (-GIDS_E_*), 0 = none; sticky
     uint32_t ticket;        // arrival counter for "last block does the scan"
     uint32_t ticket_flush;  // ... for "last block of the group mover empties the group's lists"
-    uint32_t ticket_cls;    // ... for "last block of the fused classification publishes the counters"
+    uint32_t ticket_cls;    // ... for "last block of the settle kernel publishes the counters"
     uint32_t stamp;         // index of the minibatch being gathered (successful gathers so far)
     uint32_t cnt_hit, cnt_cpu, cnt_miss, cnt_bypass;
     uint32_t cnt_fill;      // cache lines this minibatch fills
@@ -138,9 +138,12 @@ struct SamplerState {
 
 // ---- launchers (defined in the .hip files) ---------------------------------
 
+// count_blocks > 0 (at most mark_count_max_blocks()): the mark kernel's last workgroup also does the work of
+// launch_count for a bitmap of that many scan blocks (offsets to blockoff, distinct count to *n_out)
+uint32_t mark_count_max_blocks();
 template <typename IdT>
 void launch_mark(const IdT* ids, uint64_t n, const uint32_t* n_dev, uint64_t n_rows, uint64_t* bitmap, Ctl* ctl,
-                 hipStream_t s);
+                 hipStream_t s, uint32_t count_blocks = 0, uint32_t* blockoff = nullptr, uint32_t* n_out = nullptr);
 
 void launch_count(const uint64_t* bitmap, uint64_t n_words, uint32_t* blocksum, uint32_t* blockoff, Ctl* ctl,
                   uint32_t* n_out, hipStream_t s);
@@ -188,12 +191,11 @@ template <typename IdT>
 void launch_queue(const CacheView<IdT>& c, const AccumView& a, uint32_t group, const IdT* unique, const BatchHdr* hdr,
                   uint64_t n_upper, const uint64_t* plan, char* out, IdT* unique_out, hipStream_t s);
 
-// probe + victim + commit (+ queue) + finalize in one launch, for short lists and ways <= classify_max_ways()
-uint32_t classify_max_ways();
+// commit + (with the accumulator) queueing + header and counters, in one launch
 template <typename IdT>
-void launch_classify(const CacheView<IdT>& c, const AccumView& a, uint32_t group, int accum, const IdT* unique,
-                     const uint32_t* n_u, uint64_t n_upper, uint64_t out_capacity, bool pop_window, uint64_t* plan,
-                     BatchHdr* hdr, char* out, IdT* unique_out, StatsRec* rec, uint64_t seq, hipStream_t s);
+void launch_settle(const CacheView<IdT>& c, const AccumView& a, uint32_t group, int accum, const IdT* unique,
+                   const uint32_t* n_u, uint64_t n_upper, const uint64_t* plan, BatchHdr* hdr, char* out,
+                   IdT* unique_out, StatsRec* rec, uint64_t seq, hipStream_t s);
 
 template <typename IdT>
 void launch_group_move(const CacheView<IdT>& c, const AccumView& a, uint32_t parity, uint64_t rows_upper,

@@ -173,6 +173,68 @@ __global__ __launch_bounds__(MV_THREADS) void queue_kernel(CacheView<IdT> c, Acc
     }
 }
 
+// What is left of a gather once its victims are chosen, in one launch: the commit (tag and stamp of every
+// line a miss was given, the miss mask back to zero), with the accumulator the queueing of every row, and,
+// by the last workgroup to finish, the header the row mover reads and the counters.  After this kernel the
+// next minibatch may be classified, whether or not the rows of this one have moved yet.
+template <typename IdT>
+__global__ __launch_bounds__(MV_THREADS) void settle_kernel(CacheView<IdT> c, AccumView a, uint32_t group, int accum,
+                                                            const IdT* __restrict__ unique,
+                                                            const uint32_t* __restrict__ n_u_ptr,
+                                                            const uint64_t* __restrict__ plan, BatchHdr* hdr,
+                                                            char* __restrict__ out, IdT* __restrict__ unique_out,
+                                                            StatsRec* rec, uint64_t seq) {
+    __shared__ uint32_t is_last;
+    Ctl* ctl = c.ctl;
+    const bool ok = ld_agent(&ctl->error) == 0;              // (set by earlier kernels; this one only on a list overflow)
+    const uint32_t n_all = *n_u_ptr;
+    const uint32_t n_u = ok ? n_all : 0;
+    const uint32_t stamp = ctl->stamp;
+    const bool any_miss = ctl->cnt_miss != 0;                // final: the probe has ended
+    const uint32_t lane = threadIdx.x & 63;
+    const uint64_t wave0 = ((uint64_t)blockIdx.x * MV_THREADS + threadIdx.x) >> 6;
+    const uint64_t n_waves = ((uint64_t)gridDim.x * MV_THREADS) >> 6;
+    if (any_miss || accum) {
+        for (uint64_t base = wave0 * 64; base < n_u; base += n_waves * 64) {
+            const uint64_t j = base + lane;
+            const bool valid = j < n_u;
+            uint64_t e = 0, v = 0;
+            if (valid) {
+                e = plan[j];
+                v = (uint64_t)unique[j];
+                const uint64_t kind = e >> PLAN_SHIFT;
+                if (any_miss && kind >= PLAN_INSTALL) {
+                    const uint64_t b = store_line_of(c, v);
+                    if (kind == PLAN_INSTALL) {
+                        const uint64_t line = e & PLAN_INDEX_MASK;
+                        c.tags[line] = (IdT)b;
+                        c.stamps[line] = (int32_t)stamp;
+                    }
+                    uint64_t set, round;
+                    set_and_round(c, b, &set, &round);
+                    c.missmask[set * c.words_per_set + (round >> 6)] = 0ull;
+                }
+            }
+            if (accum) queue_entry(c, a, group, valid, j, e, v, out, unique_out);
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __threadfence();
+        is_last = atomicAdd(&ctl->ticket_cls, 1u) == gridDim.x - 1;
+    }
+    __syncthreads();
+    if (!is_last || threadIdx.x != 0) return;
+    __threadfence();
+    const bool good = ld_agent(&ctl->error) == 0;
+    hdr->ok = good ? 1u : 0u;
+    hdr->n_u = good ? n_all : 0u;
+    hdr->stamp = stamp;
+    hdr->next_chunk = 0;
+    ctl->ticket_cls = 0;
+    publish_stats(ctl, rec, seq, n_all, accum);
+}
+
 // The group mover, first launch: the fills and the rcopies of one closed group.  Shaped like the row mover:
 // the first `link_blocks` workgroups are persistent and draw chunks of fills from a counter (rows that cross
 // the host link), the others copy cache lines to output rows.
@@ -328,6 +390,16 @@ void launch_queue(const CacheView<IdT>& c, const AccumView& a, uint32_t group, c
 }
 
 template <typename IdT>
+void launch_settle(const CacheView<IdT>& c, const AccumView& a, uint32_t group, int accum, const IdT* unique,
+                   const uint32_t* n_u, uint64_t n_upper, const uint64_t* plan, BatchHdr* hdr, char* out,
+                   IdT* unique_out, StatsRec* rec, uint64_t seq, hipStream_t s) {
+    // few workgroups: each ends with an atomic on one counter
+    const uint32_t grid = row_grid(n_upper, 1, 256);
+    hipLaunchKernelGGL(settle_kernel<IdT>, dim3(grid), dim3(MV_THREADS), 0, s, c, a, group, accum, unique, n_u, plan,
+                       hdr, out, unique_out, rec, seq);
+}
+
+template <typename IdT>
 void launch_group_move(const CacheView<IdT>& c, const AccumView& a, uint32_t par, uint64_t rows_upper,
                        int hbm_blocks_max, int link_blocks_max, hipStream_t s) {
     const int g = lanes_per_row(c.row_bytes);
@@ -361,6 +433,9 @@ void launch_finalize(Ctl* ctl, StatsRec* rec, uint64_t seq, const uint32_t* n_u,
                                    char*, IdT*, int, int, hipStream_t);                                             \
     template void launch_queue<IdT>(const CacheView<IdT>&, const AccumView&, uint32_t, const IdT*, const BatchHdr*, \
                                     uint64_t, const uint64_t*, char*, IdT*, hipStream_t);                           \
+    template void launch_settle<IdT>(const CacheView<IdT>&, const AccumView&, uint32_t, int, const IdT*,            \
+                                     const uint32_t*, uint64_t, const uint64_t*, BatchHdr*, char*, IdT*, StatsRec*, \
+                                     uint64_t, hipStream_t);                                                        \
     template void launch_group_move<IdT>(const CacheView<IdT>&, const AccumView&, uint32_t, uint64_t, int, int,     \
                                          hipStream_t);
 GIDS_INSTANTIATE(int32_t)
