@@ -30,10 +30,16 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 LINK_PEAK_GBS = 64.0         # PCIe Gen5 x16, nominal per direction (the box negotiates 32 GT/s x16)
 
-# HBM traffic of the row mover per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# command (see profiles/); None until such a run exists for the workload.
-MEASURED_TRAFFIC_BYTES = {"large@28000000": 572.6e6,     # profiles/move_kernel_large_pmc.txt
-                          "resident": 5266.0e6}           # profiles/move_kernel_resident_pmc.txt
+# HBM / link traffic of the row mover per launch is a counter measurement (rocprofv3 --pmc, two runs) and cannot be
+# taken inside this process; `roofline.traffic` is therefore null here, and `roofline.traffic_reference` names the
+# committed counter summary of the same command on the same workload (other minibatches, another box) with the
+# ratio of counted to algorithmic bytes found there.
+TRAFFIC_REFERENCE = {
+    "large": {"profile": "profiles/move_kernel_large_pmc.txt", "link_counted_over_algorithmic": 1.000,
+              "hbm_write_counted_over_algorithmic": 1.00},
+    "resident": {"profile": "profiles/move_kernel_resident_pmc.txt", "hbm_read_counted_over_algorithmic": 1.010,
+                 "hbm_write_counted_over_algorithmic": 1.003},
+}
 
 
 def log(*a):
@@ -113,6 +119,9 @@ def main() -> int:
     ap.add_argument("--repeat", type=int, default=1,
                     help="run the workload this many times in one process, each with a cache of its own "
                          "(the last run is the one reported; the others are logged)")
+    ap.add_argument("--others", default="auto", choices=["auto", "on", "off"],
+                    help="append the other configurations (cache-resident, medium, tiny; 20 steps each) to the same JSON "
+                         "line as `other_workloads`; auto: with the default command only")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     args = ap.parse_args()
@@ -142,6 +151,40 @@ def main() -> int:
     gids.lib()
     wl.native.build()
 
+    shared = dict(torch=torch, wl=wl, gids=gids, GatherSession=GatherSession)
+    result = run_workload(args, shared)
+    if result is None:                                          # a sweep printed its own object
+        return 0
+    plain = not (args.gpu_sampler or args.layerwise or args.consumer_ms or args.dim or args.rows_per_line > 1 or
+                 args.cache_lines or args.accum or args.nodes or args.window >= 0 or args.policy != "lru" or
+                 args.hot_by != "indegree" or args.pass_ids or args.one_stream or args.repeat > 1)
+    if args.others == "on" or (args.others == "auto" and plain and args.workload == "large"):
+        # the other configurations in the same line: the HBM-bound one, the mid-size one and the launch-bound one
+        import copy
+        result["other_workloads"] = {}
+        for name in ("resident", "medium", "tiny"):
+            if name == args.workload:
+                continue
+            sub = copy.copy(args)
+            sub.workload, sub.steps, sub.warmup, sub.cpu_seconds = name, min(args.steps, 20), min(args.warmup, 6), 4.0
+            log(f"--- other workload: {name}")
+            r = run_workload(sub, shared)
+            result["other_workloads"][name] = {
+                "value": r["value"], "unit": r["unit"], "ms_per_step": r["ms_per_step"], "steps": r["steps"],
+                "unique_ids_per_s": r["unique_ids_per_s"], "workload": r["config"]["workload"],
+                "per_step": r["per_step"], "weighted_roofline_frac": r["weighted_roofline"]["frac"],
+                "roofline": {k: r["roofline"][k] for k in ("bound", "achieved", "peak", "unit", "frac", "avg_ms")},
+                "oracle_count_mismatches": r.get("cpu_baseline", {}).get("count_mismatches_vs_gpu"),
+                "oracle_minibatches_compared": r.get("cpu_baseline", {}).get("minibatches_compared"),
+                "check": r.get("check")}
+    print(json.dumps(result))
+    return 0
+
+
+def run_workload(args, shared):
+    """Sets one configuration up (table pinned and filled, graph, hot nodes, ID lists), runs it, releases the
+    table; returns the result object (None after a sweep, which prints its own)."""
+    torch, wl, gids, GatherSession = shared["torch"], shared["wl"], shared["gids"], shared["GatherSession"]
     base = wl.CONFIGS[args.workload]
     def with_dim(c):
         if not args.dim:
@@ -199,8 +242,17 @@ def main() -> int:
     t0 = time.time()
     wl.fill_store(cfg.seed, cfg.n_nodes, cfg.dim, table, gids.gids_store_host_ptr(store))
     log(f"store: {cfg.n_nodes * R / 1e9:.2f} GB pinned and filled ({time.time() - t0:.1f} s)")
-    env = dict(link_rows_per_s=rate, link_overhead_s=overhead, torch=torch, wl=wl, gids=gids, GatherSession=GatherSession, g=g, hot=hot, table=table, store=store,
-               base=base)
+    env = dict(shared, link_rows_per_s=rate, link_overhead_s=overhead, g=g, hot=hot, table=table, store=store, base=base)
+    try:
+        return run_lists(args, env, cfg, base, g, wl, gids)
+    finally:
+        if "push_stream" in env:
+            shared["push_stream"] = env["push_stream"]          # one push stream for the whole process
+        torch.cuda.synchronize()
+        gids.gids_store_destroy(store)
+
+
+def run_lists(args, env, cfg, base, g, wl, gids):
 
     if args.sweep_skew:
         # the skew sweep: seed IDs Zipf(s) over a seeded permutation of the nodes, window depth 0 / 4 / 16
@@ -211,19 +263,27 @@ def main() -> int:
             t0 = time.time()
             raws = [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds, rank_table) for b in range(n_b)]
             log(f"zipf s={s_exp}: sampled {n_b} minibatches ({time.time() - t0:.1f} s)")
-            for w in (0, 4, 16):
-                res = run_point(args, env, cfg, w, raws, 0)
-                res["config"]["seed_zipf_s"] = s_exp
-                hit = res["per_step"]["hit"] / max(1.0, res["per_step"]["unique"])
-                points.append({"zipf_s": s_exp, "window": w, "gathered_GBs": res["value"], "hit_rate": hit,
-                               "cpu_buffer_rate": res["per_step"]["cpu_hit"] / max(1.0, res["per_step"]["unique"]),
-                               "ms_per_step": res["ms_per_step"], "weighted_roofline_frac": res["weighted_roofline"]["frac"],
-                               "oracle_count_mismatches": res.get("cpu_baseline", {}).get("count_mismatches_vs_gpu")})
-                log(json.dumps(points[-1]))
+            # every point twice: the configuration's cache (which nothing leaves within a few hundred minibatches,
+            # so the window has nothing to protect) and one of 2,048 sets, a few minibatches' misses large, where
+            # lines are evicted inside the run and the hit ratio moves with the depth
+            from dataclasses import replace
+            small = replace(cfg, cache_lines=2048 * cfg.ways)
+            for label, c in (("configuration", cfg), ("under eviction pressure", small)):
+                for w in (0, 4, 16):
+                    res = run_point(args, env, c, w, raws, 0)
+                    per = res["per_step"]
+                    points.append({"zipf_s": s_exp, "window": w, "cache": label, "cache_lines": c.cache_lines,
+                                   "gathered_GBs": res["value"], "hit_rate": per["hit"] / max(1.0, per["unique"]),
+                                   "hit_rate_of_cache_traffic": per["hit"] / max(1.0, per["unique"] - per["cpu_hit"]),
+                                   "cpu_buffer_rate": per["cpu_hit"] / max(1.0, per["unique"]),
+                                   "ms_per_step": res["ms_per_step"],
+                                   "weighted_roofline_frac": res["weighted_roofline"]["frac"],
+                                   "oracle_count_mismatches": res.get("cpu_baseline", {}).get("count_mismatches_vs_gpu")})
+                    log(json.dumps(points[-1]))
         print(json.dumps({"metric": "skew sweep: gathered GB/s and hit rate per (zipf s, window depth)", "n_gpus": 1,
                           "config": {"workload": cfg.name, "n_nodes": cfg.n_nodes, "steps": args.steps,
                                      "warmup": args.warmup}, "points": points}))
-        return 0
+        return None
 
     window = cfg.window if args.window < 0 else args.window
     prewarm = args.prewarm if args.prewarm >= 0 else (1_000_000 if args.workload == "resident" else 0)
@@ -247,8 +307,7 @@ def main() -> int:
         res = run_point(args, env, cfg, window, raws, n_pre)
         log(f"repeat {k + 1} of {args.repeat}: {res['ms_per_step']:.4f} ms per step, "
             f"weighted roofline {res['weighted_roofline']['frac']:.4f}, phases {res['roofline']['phase_ms']}")
-    print(json.dumps(run_point(args, env, cfg, window, raws, n_pre)))
-    return 0
+    return run_point(args, env, cfg, window, raws, n_pre)
 
 
 def run_point(args, env, cfg, window, raws, n_pre):
@@ -393,7 +452,7 @@ def run_point(args, env, cfg, window, raws, n_pre):
         roof = {"bound": "host_link", "achieved": mv_link / (mv_ms * 1e-3) / 1e9, "peak": LINK_PEAK_GBS}
     else:
         roof = {"bound": "hbm", "achieved": mv_hbm / (mv_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS}
-    roof.update({"unit": "GB/s", "frac": roof["achieved"] / roof["peak"], "traffic": MEASURED_TRAFFIC_BYTES.get(cfg.name),
+    roof.update({"unit": "GB/s", "frac": roof["achieved"] / roof["peak"], "traffic": None, "traffic_reference": TRAFFIC_REFERENCE.get(base.name),
                  "kernel": "move_kernel", "avg_ms": mv_ms, "link_bytes_per_launch": float(mv_link),
                  "hbm_bytes_per_launch": float(mv_hbm),
                  "phase_ms": {"dedup": float(ph[:, 0].mean()), "probe_victim": float(ph[:, 1].mean()), "move": mv_ms}})
@@ -540,14 +599,20 @@ def run_point(args, env, cfg, window, raws, n_pre):
         import oracle
         oracle.build()
         store_np = ses.store_view()
-        sim = oracle.Sim(cfg.n_nodes, cfg.cache_lines, cfg.ways, window, R, cfg.line_bytes, store_np)
+        # (a simulated cache beyond 16 GiB of host memory is left out: the oracle then runs without its data
+        # plane, counters only, and its rate excludes the row copies)
+        with_rows = cfg.cache_lines * cfg.line_bytes <= (16 << 30)
+        sim = oracle.Sim(cfg.n_nodes, cfg.cache_lines, cfg.ways, window, R, cfg.line_bytes,
+                         store_np if with_rows else None)
         sim.set_hot(hot)
         if args.rows_per_line > 1:
             sim.set_rows_per_line(args.rows_per_line)
         if args.policy == "random":
             sim.set_policy(1, cfg.seed)
+        if args.accum:
+            sim.set_accum(args.accum, 1 if args.accum_adaptive else 0)
         opushed, done, o_unique, o_time = 0, 0, 0, 0.0
-        mismatches = 0
+        mismatches, compared = 0, 0
         budget_end = time.time() + args.cpu_seconds
         for t in range(warmup + steps):
             while window and opushed < n_batches and opushed <= t + window:
@@ -556,8 +621,12 @@ def run_point(args, env, cfg, window, raws, n_pre):
             ts = time.perf_counter()
             u, rows, ost = sim.gather(raws[t])
             dt = time.perf_counter() - ts
-            if t in stats and tuple(int(x) for x in ost) != stats[t].as_tuple():
-                mismatches += 1
+            if t in stats:
+                compared += 1
+                same = tuple(int(x) for x in ost) == stats[t].as_tuple()
+                if args.accum:                                  # the accumulator's groups as well
+                    same = same and sim.accum_last[:2] == (stats[t].n_pending, stats[t].flushed)
+                mismatches += not same
             if t >= min(warmup, 2):                             # skip the cold start like the GPU leg
                 o_unique += len(u)
                 o_time += dt
@@ -567,9 +636,10 @@ def run_point(args, env, cfg, window, raws, n_pre):
         result["cpu_baseline"] = {
             "value": o_unique * R / o_time / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
             "unique_ids_per_s": o_unique / o_time, "host_cores_on_box": os.cpu_count(),
-            "sample": f"{done} minibatches of this workload (gather only: sort-unique, cache simulation, row copy; "
+            "sample": f"{done} minibatches of this workload (gather only: sort-unique, cache simulation"
+                      f"{', row copy' if with_rows else '; no row copies: the simulated cache would not fit'}; "
                       f"window pushes and sampling excluded), single thread",
-            "count_mismatches_vs_gpu": mismatches}
+            "count_mismatches_vs_gpu": mismatches, "minibatches_compared": compared}
         if mismatches:
             log(f"WARNING: {mismatches} minibatches differ from the oracle's counters")
     ses.close()
