@@ -102,6 +102,10 @@ def main() -> int:
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device copy three times (the known-size kernel that scales the "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
+    ap.add_argument("--probe-box", action="store_true",
+                    help="measure the limits of this machine that the roofline arguments rest on (pinned host memory "
+                         "a process is granted, the negotiated PCIe link, zero-copy and copy rates over it, device "
+                         "copy rates, host cores and memory), print one JSON object and exit")
     ap.add_argument("--one-stream", action="store_true", help="issue pushes and gathers on the same stream")
     ap.add_argument("--sweep-skew", action="store_true",
                     help="run the skew sweep (seed Zipf s in {0, 0.8, 1.2} x window depth in {0, 4, 16}) on the "
@@ -149,6 +153,9 @@ def main() -> int:
     from paper_2306_16384_amd.build import ensure_built
     ensure_built()
     gids.lib()
+    if args.probe_box:
+        print(json.dumps(probe_box(torch, gids)))
+        return 0
     wl.native.build()
 
     shared = dict(torch=torch, wl=wl, gids=gids, GatherSession=GatherSession)
@@ -179,6 +186,79 @@ def main() -> int:
                 "check": r.get("check")}
     print(json.dumps(result))
     return 0
+
+
+def probe_box(torch, gids):
+    """The machine's own ceilings, measured through the library's C ABI and plain device copies."""
+    import glob
+    res = {"host_cores": os.cpu_count(), "omp_num_threads": os.environ.get("OMP_NUM_THREADS")}
+    for line in open("/proc/meminfo"):
+        if line.startswith("MemTotal"):
+            res["host_memory_GiB"] = int(line.split()[1]) / 2**20
+    link = {}
+    for f in glob.glob("/sys/class/drm/card*/device/current_link_speed") + glob.glob("/sys/class/drm/card*/device/current_link_width"):
+        try:
+            link[f.split("/")[4] + "/" + os.path.basename(f)] = open(f).read().strip()
+        except OSError:
+            pass
+    res["pcie_link"] = link
+    props = torch.cuda.get_device_properties(0)
+    res["device"] = {"name": props.name, "compute_units": props.multi_processor_count, "memory_GiB": props.total_memory / 2**30}
+    # pinned host memory: stores of 8 GiB until the runtime refuses, then one store of everything that was granted
+    chunk_rows, R, stores = (8 << 30) // 2048, 2048, []
+    try:
+        while len(stores) < 40:
+            try:
+                stores.append(gids.gids_store_create(chunk_rows, R, 8))
+            except gids.GidsError as e:
+                res["pinned_chunks_refused_after_GiB"] = 8 * len(stores)
+                res["pinned_refusal"] = str(e)
+                break
+        else:
+            res["pinned_chunks_refused_after_GiB"] = None
+    finally:
+        for st in stores:
+            gids.gids_store_destroy(st)
+    granted = res.get("pinned_chunks_refused_after_GiB") or 320
+    for gib in (granted + 8, granted):
+        try:
+            st = gids.gids_store_create((gib << 30) // R, R, 8)
+            gids.gids_store_destroy(st)
+            res[f"single_store_of_{gib}_GiB"] = "granted"
+        except gids.GidsError as e:
+            res[f"single_store_of_{gib}_GiB"] = "refused"
+    # the link as the row mover's launch shape sees it (hashed 2 KiB rows of a 16 GiB table, zero-copy)
+    st = gids.gids_store_create((16 << 30) // R, R, 8)
+    try:
+        rate, overhead = gids.gids_store_calibrate(st)
+        res["zero_copy_hashed_2KiB_rows_GBs"] = rate * R / 1e9
+        res["zero_copy_overhead_us"] = overhead * 1e6
+    finally:
+        gids.gids_store_destroy(st)
+
+    def timed(fn, nbytes, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        best = 1e9
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            best = min(best, e0.elapsed_time(e1) * 1e-3)
+        return nbytes / best / 1e9
+
+    host = torch.empty(1 << 30, dtype=torch.uint8).pin_memory()
+    dev = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    res["copy_host_to_device_1GiB_GBs"] = timed(lambda: dev.copy_(host, non_blocking=True), 1 << 30)
+    res["copy_device_to_host_1GiB_GBs"] = timed(lambda: host.copy_(dev, non_blocking=True), 1 << 30)
+    a = torch.empty(2 << 30, dtype=torch.uint8, device="cuda")
+    b = torch.empty(2 << 30, dtype=torch.uint8, device="cuda")
+    res["copy_device_to_device_2GiB_read_plus_write_GBs"] = timed(lambda: b.copy_(a), 2 * (2 << 30))
+    res["fill_device_2GiB_write_GBs"] = timed(lambda: b.fill_(1), 2 << 30)
+    res["sum_device_2GiB_read_GBs"] = timed(lambda: a.view(torch.int64).sum(), 2 << 30)
+    return res
 
 
 def run_workload(args, shared):
