@@ -247,7 +247,9 @@ __global__ __launch_bounds__(MV_THREADS) void group_move_kernel(Ctl* ctl, const 
     const uint32_t row_u4 = row_bytes >> 4;
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t sub = lane % G, grp = lane / G;
-    constexpr uint32_t PER_ITER = 64 / G;
+    constexpr uint32_t PER_ITER = 64 / G;                     // rows a wave moves at once
+    // A wave reads up to 64 operations with one coalesced load (lane i holds operation base + i) and then
+    // moves their rows PER_ITER at a time, each group of G lanes taking its operation from the holder's lane.
     if (blockIdx.x < link_blocks) {
         const uint32_t n = ctl->q_fill[par];
         const uint64_t n_waves = ((uint64_t)link_blocks * MV_THREADS) >> 6;
@@ -259,22 +261,38 @@ __global__ __launch_bounds__(MV_THREADS) void group_move_kernel(Ctl* ctl, const 
             if (lane == 0) chunk = atomicAdd(&ctl->q_chunk[par], 1u);
             const uint64_t base = (uint64_t)__shfl(chunk, 0) * ch;
             if (base >= n) break;
-            for (uint32_t i = grp; i < ch; i += PER_ITER) {
-                const uint64_t k = base + i;
-                if (k >= n) break;
-                const FillOp op = fills[k];
-                char* line = op.dst_line == NO_LINE ? nullptr : cache_data + op.dst_line * line_bytes;
-                copy_row<G>(reinterpret_cast<const v4u*>(op.src), reinterpret_cast<v4u*>(op.dst_out),
+            FillOp op;
+            op.src = nullptr; op.dst_out = nullptr; op.dst_line = NO_LINE;
+            if (lane < ch && base + lane < n) op = fills[base + lane];
+            const uint32_t m = (uint32_t)(n - base < ch ? n - base : ch);
+            for (uint32_t i0 = 0; i0 < m; i0 += PER_ITER) {
+                const uint32_t i = i0 + grp;
+                const uint64_t src = __shfl((uint64_t)op.src, (int)(i & 63));
+                const uint64_t dst = __shfl((uint64_t)op.dst_out, (int)(i & 63));
+                const uint64_t dl = __shfl(op.dst_line, (int)(i & 63));
+                if (i >= m) continue;
+                char* line = dl == NO_LINE ? nullptr : cache_data + dl * line_bytes;
+                copy_row<G>(reinterpret_cast<const v4u*>(src), reinterpret_cast<v4u*>(dst),
                             reinterpret_cast<v4u*>(line), row_u4, sub);
             }
         }
     } else {
         const uint32_t n = ctl->q_rcopy[par];
-        const uint64_t g0 = ((uint64_t)(blockIdx.x - link_blocks) * MV_THREADS + threadIdx.x) / G;
-        const uint64_t n_groups = (uint64_t)(gridDim.x - link_blocks) * MV_THREADS / G;
-        for (uint64_t k = g0; k < n; k += n_groups) {
-            const CopyOp op = rcopies[k];
-            copy_row<G>(reinterpret_cast<const v4u*>(op.src), reinterpret_cast<v4u*>(op.dst), nullptr, row_u4, sub);
+        const uint64_t wave0 = ((uint64_t)(blockIdx.x - link_blocks) * MV_THREADS + threadIdx.x) >> 6;
+        const uint64_t n_waves = ((uint64_t)(gridDim.x - link_blocks) * MV_THREADS) >> 6;
+        constexpr uint32_t CH = 16;                           // operations a wave takes per step
+        for (uint64_t base = wave0 * CH; base < n; base += n_waves * CH) {
+            CopyOp op;
+            op.src = nullptr; op.dst = nullptr;
+            if (lane < CH && base + lane < n) op = rcopies[base + lane];
+            const uint32_t m = (uint32_t)(n - base < CH ? n - base : CH);
+            for (uint32_t i0 = 0; i0 < m; i0 += PER_ITER) {
+                const uint32_t i = i0 + grp;
+                const uint64_t src = __shfl((uint64_t)op.src, (int)(i & 63));
+                const uint64_t dst = __shfl((uint64_t)op.dst, (int)(i & 63));
+                if (i >= m) continue;
+                copy_row<G>(reinterpret_cast<const v4u*>(src), reinterpret_cast<v4u*>(dst), nullptr, row_u4, sub);
+            }
         }
     }
 }
@@ -407,7 +425,7 @@ void launch_group_move(const CacheView<IdT>& c, const AccumView& a, uint32_t par
     uint32_t link_ch = 64;
     while (link_ch > 4 && rows_upper / link_ch < (uint64_t)link_blocks_max * (MV_THREADS / 64)) link_ch >>= 1;
     const uint32_t link_blocks = row_grid(rows_upper, 64 / (int)link_ch, link_blocks_max);
-    const uint32_t hbm_blocks = row_grid(rows_upper, g, hbm_blocks_max < 4096 ? hbm_blocks_max : 4096);
+    const uint32_t hbm_blocks = row_grid(rows_upper, 4, hbm_blocks_max);   // 4 waves x 16 operations per workgroup step
     GIDS_DISPATCH_G(g, hipLaunchKernelGGL((group_move_kernel<G>), dim3(link_blocks + hbm_blocks), dim3(MV_THREADS), 0,
                                           s, c.ctl, a.fills[par], a.rcopies[par], c.cache_data, c.line_bytes,
                                           c.row_bytes, par, link_blocks, link_ch, 2u));
