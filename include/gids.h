@@ -266,6 +266,33 @@ int gids_gather(gids_cache* cache, const void* ids_dev, uint64_t n, void* out_de
 int gids_gather_static(gids_cache* cache, const void* ids_dev, uint64_t n, void* out_dev, uint64_t out_capacity_rows,
                        void* unique_dev, void* stream);
 
+/* Merged iterations (Section 3.2: the data preparation of consecutive
+ * iterations is merged, which takes the stop-and-go boundaries between
+ * minibatches away).  One call brings k steps of the steady-state loop,
+ *   step i:  gids_window_push(push_ids_dev[i], push_n[i])   if push_ids_dev[i] != NULL
+ *            gids_gather(NULL, 0, out_dev[i], out_capacity_rows[i], unique_dev[i], NULL)
+ * with exactly the results of those calls made one after the other (outputs,
+ * counters, cache state), and runs them as ONE accumulator group whatever the
+ * cache's accum_threshold says: a group that is open when the call arrives is
+ * closed first, the call's own group closes with its last step (gids_stats of
+ * step i: n_pending = rows of steps 0..i, flushed = 0; the last step: 0 and 1).
+ * Every output of the call is complete, in stream order, when the call's work
+ * ends.  On tables of up to 516,096 rows with ways <= 16 and one row per line
+ * the k steps take four launches in all, however large k: one that deduplicates
+ * the pushed lists (a workgroup and an LDS bitmap each), one that classifies
+ * the k minibatches one after the other, each workgroup for its own share of
+ * the cache sets, and the group mover's two.  Other caches take the per-step
+ * kernels, still as one group.
+ *   k              1 .. 32 (GIDS_ACCUM_MAX_MERGE)
+ *   push_ids_dev   NULL (no step pushes), or k pointers, NULL where a step
+ *                  pushes nothing; push_n the lists' lengths
+ *   unique_dev     NULL, or k pointers (NULL entries allowed)
+ * Needs a cache created with accum_threshold > 0 (it owns the group lists);
+ * errors as gids_window_push / gids_gather; a device-found error in step i
+ * leaves steps i.. undone and is reported in their gids_stats.status. */
+int gids_gather_many(gids_cache* cache, uint32_t k, const void* const* push_ids_dev, const uint64_t* push_n,
+                     void* const* out_dev, const uint64_t* out_capacity_rows, void* const* unique_dev, void* stream);
+
 /* The accumulator's forced launch (Section 3.2: accesses merged over several
  * minibatches go out in one launch; this is the launch without waiting for
  * the threshold).  Moves every queued row now: after the stream reaches the

@@ -14,7 +14,7 @@ GIDS_E_INVAL, GIDS_E_NOMEM, GIDS_E_RANGE, GIDS_E_ORDER, GIDS_E_FULL, GIDS_E_HIP,
 
 EXPORTS = [
     "gids_store_create", "gids_store_host_ptr", "gids_store_destroy", "gids_store_calibrate", "gids_cache_create", "gids_cache_destroy",
-    "gids_cache_reserve", "gids_cache_set_policy", "gids_cache_set_accum_mode", "gids_cpu_buffer_pin", "gids_window_push", "gids_gather", "gids_gather_static", "gids_flush", "gids_stats_read",
+    "gids_cache_reserve", "gids_cache_set_policy", "gids_cache_set_accum_mode", "gids_cpu_buffer_pin", "gids_window_push", "gids_gather", "gids_gather_static", "gids_gather_many", "gids_flush", "gids_stats_read",
     "gids_cache_gathers", "gids_cache_snapshot", "gids_cache_set_rows_per_line", "gids_profile_enable", "gids_profile_read", "gids_window_push_dev",
     "gids_graph_create", "gids_graph_destroy", "gids_sample_capacity", "gids_sample", "gids_graph_visit_scores", "gids_graph_reverse_pagerank", "gids_accum_threshold", "gids_last_error",
 ]
@@ -63,6 +63,7 @@ def lib() -> C.CDLL:
         L.gids_window_push.argtypes = [vp, vp, u64, vp]
         L.gids_gather.argtypes = [vp, vp, u64, vp, u64, vp, vp, vp]
         L.gids_gather_static.argtypes = [vp, vp, u64, vp, u64, vp, vp]
+        L.gids_gather_many.argtypes = [vp, u32, C.POINTER(vp), C.POINTER(u64), C.POINTER(vp), C.POINTER(u64), C.POINTER(vp), vp]
         L.gids_flush.argtypes = [vp, vp]
         L.gids_stats_read.argtypes = [vp, u64, C.POINTER(gids_stats)]
         L.gids_cache_gathers.restype = u64
@@ -165,6 +166,18 @@ GIDS_STATIC_MAX_IDS = 1 << 20
 def gids_gather_static(cache: int, ids_dev_ptr: int | None, n: int, out_dev_ptr: int, out_capacity_rows: int,
                        unique_dev_ptr: int | None = None, stream: int = 0) -> None:
     _check(lib().gids_gather_static(cache, ids_dev_ptr, n, out_dev_ptr, out_capacity_rows, unique_dev_ptr, stream))
+
+
+def gids_gather_many(cache: int, push_ids_dev_ptrs, push_n, out_dev_ptrs, out_capacity_rows, unique_dev_ptrs=None,
+                     stream: int = 0) -> None:
+    """k steps (push one list or None, gather the window's head) in one call; sequences of k entries"""
+    k = len(out_dev_ptrs)
+    vp_k, u64_k = C.c_void_p * k, C.c_uint64 * k
+    pushes = None if push_ids_dev_ptrs is None else vp_k(*push_ids_dev_ptrs)
+    lens = None if push_ids_dev_ptrs is None else u64_k(*[int(x) for x in push_n])
+    uniq = None if unique_dev_ptrs is None else vp_k(*unique_dev_ptrs)
+    _check(lib().gids_gather_many(cache, k, pushes, lens, vp_k(*out_dev_ptrs), u64_k(*[int(x) for x in out_capacity_rows]),
+                                  uniq, stream))
 
 
 def gids_flush(cache: int, stream: int = 0) -> None:

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgids.so")
-SOURCES = ["dedup.hip", "cache.hip", "move.hip", "sampler.hip", "api.hip"]
+SOURCES = ["dedup.hip", "cache.hip", "many.hip", "move.hip", "sampler.hip", "api.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wextra",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
@@ -28,7 +28,7 @@ def _compile(src: str) -> str:
 
 
 def build(verbose: bool = False) -> str:
-    with ThreadPoolExecutor(5) as ex:
+    with ThreadPoolExecutor(6) as ex:
         objs = list(ex.map(_compile, SOURCES))
     subprocess.check_call(["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB, *objs])
     if verbose:

@@ -128,6 +128,8 @@ struct gids_cache {
     virtual int gather(const void* ids, uint64_t n, void* out, uint64_t out_cap, void* unique, void* inverse,
                        bool no_alloc, hipStream_t s) = 0;
     virtual int flush(hipStream_t s) = 0;
+    virtual int gather_many(uint32_t k, const void* const* push_ids, const uint64_t* push_n, void* const* outs,
+                            const uint64_t* caps, void* const* uniques, hipStream_t s) = 0;
     virtual int snapshot(int64_t* tags, int64_t* stamps) = 0;
     virtual uint32_t window_count() const = 0;
 
@@ -143,6 +145,7 @@ struct gids_cache {
     // Accumulator (accum_threshold > 0): the host merges consecutive gathers into groups by the node accesses
     // (raw list entries) they bring; the rows of a group move when it closes.
     int accum_mode = GIDS_ACCUM_FIXED;
+    int group_override = 0;         // inside a merged call: 1 = this gather keeps its group open, 2 = it closes it
     uint32_t group = 0;             // index of the open group (its lists live in the buffers of parity group & 1)
     uint64_t open_nodes = 0;        // node accesses merged into the open group so far
     uint64_t open_upper = 0;        // bound on the rows queued in the open group
@@ -157,6 +160,7 @@ struct gids_cache {
     StatsRec* ring_dev = nullptr;
     hipEvent_t events[STATS_RING] = {};       // gather seq: its rows have moved (recorded on the caller's stream)
     hipEvent_t ev_meta[STATS_RING] = {};      // gather seq: its metadata kernels and counters are done
+    int ev_of[STATS_RING] = {};               // ring entry whose events cover gather seq (a merged call records one pair)
     hipEvent_t ev_hop[16] = {};               // short-lived cross-stream edges
     uint32_t hop = 0;
     // With accum_threshold == 0 the metadata kernels (dedup, probe, victim, commit, counters) run on an
@@ -236,6 +240,8 @@ struct CacheT final : gids_cache {
     // accumulator: per-line bookkeeping and the operation lists of the two groups that can exist at a time
     uint32_t* fillgrp = nullptr;
     uint32_t* hitgrp = nullptr;
+    uint64_t* many_plan = nullptr;           // plan of every step of a merged call
+    uint64_t many_plan_cap = 0;
     uint64_t queue_cap = 0;
     FillOp* fills[2] = {nullptr, nullptr};
     CopyOp* rcopies[2] = {nullptr, nullptr};
@@ -261,7 +267,7 @@ struct CacheT final : gids_cache {
         dev_free(wrank); dev_free(hotbits); dev_free(hotrank); dev_free(cache_data); dev_free(ctl);
         dev_free(blocksum); dev_free(blockoff); dev_free(hdr);
         for (int k = 0; k < 2; k++) { dev_free(ubuf[k]); dev_free(plan[k]); }
-        dev_free(fillgrp); dev_free(hitgrp);
+        dev_free(fillgrp); dev_free(hitgrp); dev_free(many_plan);
         for (int k = 0; k < 2; k++) { dev_free(fills[k]); dev_free(rcopies[k]); dev_free(wcopies[k]); }
         for (auto& e : ev_flush) if (e) (void)hipEventDestroy(e);
         for (auto& s : slots) if (s.ids) (void)hipFree(s.ids);
@@ -337,7 +343,9 @@ struct CacheT final : gids_cache {
         if (pipelined) HIP_TRY(hipStreamCreateWithFlags(&meta, hipStreamNonBlocking));
         // one slot more than lists can be buffered: the slot a push overwrites was then read by the gather
         // before the previous one, whose rows have long moved, and not by the one still moving
-        slots.resize(window + 2);
+        // (a cache with an accumulator can take a merged call, which pushes up to MANY_MAX lists before any of
+        // them is gathered: that many slots more, so that none of them lands on a list still to be gathered)
+        slots.resize(window + 2 + (threshold ? MANY_MAX : 0));
         if (const char* env = getenv("GIDS_WIDE_INDEX")) wide_index = atoi(env) != 0;
         if (const char* env = getenv("GIDS_FUSE")) fuse = atoi(env) & 3;
         if (const char* env = getenv("GIDS_MOVE_BLOCKS")) {
@@ -586,8 +594,8 @@ struct CacheT final : gids_cache {
         while (adapt_next + ACCUM_LAG < seq) {
             const uint64_t g = adapt_next;
             const int r = (int)(g % STATS_RING);
-            if (pipelined) HIP_TRY(hipEventSynchronize(ev_meta[r]));
-            HIP_TRY(hipEventSynchronize(events[r]));
+            if (pipelined) HIP_TRY(hipEventSynchronize(ev_meta[ev_of[r]]));
+            HIP_TRY(hipEventSynchronize(events[ev_of[r]]));
             const StatsRec& rec = ring_host[r];
             if (*reinterpret_cast<const volatile uint64_t*>(&rec.seq) != g) return fail(GIDS_E_HIP, "the counters of gather %llu are missing", (unsigned long long)g);
             adapt_nodes += raw_of[r];
@@ -616,6 +624,7 @@ struct CacheT final : gids_cache {
             opens = open_batches == 0;
             if ((rc = ensure_queue(open_upper + n_upper))) return rc;
             closes = open_nodes + n_raw >= limit || open_batches + 1 >= ACCUM_MAX_MERGE;
+            if (group_override) closes = group_override == 2; // a merged call decides for itself
         }
         if ((rc = follow(s))) return rc;
         hipStream_t m = s;
@@ -693,6 +702,7 @@ struct CacheT final : gids_cache {
             if ((rc = mark_phase(r, 4, s))) return rc;
         }
         prof_valid[r] = profile;
+        ev_of[r] = r;
         HIP_TRY(hipGetLastError());                           // a kernel launch that was refused
         HIP_TRY(hipEventRecord(events[r], s));
         if (head_list) {
@@ -734,6 +744,134 @@ struct CacheT final : gids_cache {
             HIP_TRY(hipEventRecord(after, meta));
         }
         return close_group(s, after);
+    }
+
+    // k steps, each "push one list (optional), gather the window's head", as one accumulator group.
+    int gather_many(uint32_t k, const void* const* push_ids, const uint64_t* push_n, void* const* outs,
+                    const uint64_t* caps, void* const* uniques, hipStream_t s) override {
+        if (!threshold) return fail(GIDS_E_INVAL, "gids_gather_many: the cache was created without an accumulator (accum_threshold == 0)");
+        if (k < 1 || k > (uint32_t)MANY_MAX) return fail(GIDS_E_INVAL, "gids_gather_many: k must be in [1, %d]", MANY_MAX);
+        if (!outs || !caps) return fail(GIDS_E_INVAL, "gids_gather_many: out_dev / out_capacity_rows is NULL");
+        // the window protocol over the whole call, before anything is enqueued
+        uint32_t cnt = count;
+        uint64_t total_upper = 0, longest = 1;
+        for (uint32_t i = 0; i < k; i++) {
+            const bool pushes = push_ids && push_ids[i];
+            if (pushes) {
+                if (push_n[i] > 0xFFFFFFF0ull) return fail(GIDS_E_INVAL, "gids_gather_many: list %u too long", i);
+                if (cnt == window + 1) return fail(GIDS_E_FULL, "gids_gather_many: step %u pushes into a full window", i);
+                cnt++;
+            }
+            if (cnt == 0) return fail(GIDS_E_ORDER, "gids_gather_many: step %u has no buffered minibatch to gather", i);
+            cnt--;
+            if (!outs[i] && caps[i]) return fail(GIDS_E_INVAL, "gids_gather_many: out_dev[%u] is NULL", i);
+        }
+        const bool fast = store->n_rows <= many_max_rows() && ways <= many_max_ways() && rows_per_line == 1 && (fuse & 1);
+        int rc;
+        if (!fast) {
+            // large tables, high associativity: the same steps through the per-step kernels, still one group
+            if (open_batches && (rc = flush(s))) return rc;
+            for (uint32_t i = 0; i < k; i++) {
+                if (push_ids && push_ids[i] && (rc = push(push_ids[i], push_n[i], nullptr, s))) return rc;
+                group_override = i + 1 < k ? 1 : 2;           // no group closes inside the call, its last step closes it
+                rc = gather(nullptr, 0, outs[i], caps[i], uniques ? uniques[i] : nullptr, nullptr, false, s);
+                group_override = 0;
+                if (rc) return rc;
+            }
+            return GIDS_OK;
+        }
+        // room: window slots of the pushed lists, the plans of all steps, the group's lists
+        if (open_batches && (rc = flush(s))) return rc;
+        {
+            uint32_t h = head, c2 = count;
+            for (uint32_t i = 0; i < k; i++) {
+                if (push_ids && push_ids[i]) {
+                    WindowSlot& sl = slots[(h + c2) % slots.size()];
+                    if ((rc = ensure_slot(sl, push_n[i]))) return rc;
+                    sl.n_raw = push_n[i];
+                    c2++;
+                }
+                const uint64_t up = std::min<uint64_t>(slots[h].n_raw, store->n_rows);
+                total_upper += up;
+                longest = std::max(longest, up);
+                h = (h + 1) % slots.size();
+                c2--;
+            }
+        }
+        if (total_upper > many_plan_cap) {
+            HIP_TRY(hipDeviceSynchronize());
+            dev_free(many_plan);
+            many_plan_cap = 0;
+            if ((rc = dev_alloc(&many_plan, total_upper + total_upper / 2))) return rc;
+            many_plan_cap = total_upper + total_upper / 2;
+        }
+        if ((rc = ensure_queue(total_upper))) return rc;
+        if ((rc = many_enqueue(k, push_ids, push_n, outs, caps, uniques, total_upper, longest, s))) sticky = rc;
+        return rc;
+    }
+
+    int many_enqueue(uint32_t k, const void* const* push_ids, const uint64_t* push_n, void* const* outs,
+                     const uint64_t* caps, void* const* uniques, uint64_t total_upper, uint64_t longest, hipStream_t s) {
+        int rc;
+        if ((rc = follow(s))) return rc;
+        hipStream_t m = s;
+        if (pipelined) {
+            m = meta;
+            if ((rc = edge(s, meta))) return rc;              // the caller's ID lists are ready in its stream's order
+        }
+        if (flush_recorded[group & 1]) HIP_TRY(hipStreamWaitEvent(m, ev_flush[group & 1], 0));
+        ManyPushes<IdT> mp;
+        ManySteps<IdT> ms;
+        ms.k = k;
+        ms.seq0 = seq;
+        uint32_t n_push = 0;
+        uint64_t off = 0;
+        for (uint32_t i = 0; i < k; i++) {
+            ms.pushed[i] = nullptr;
+            ms.pushed_slot[i] = 0;
+            if (push_ids && push_ids[i]) {
+                const uint32_t slot = (head + count) % slots.size();
+                WindowSlot& sl = slots[slot];
+                mp.ids[n_push] = static_cast<const IdT*>(push_ids[i]);
+                mp.n[n_push] = push_n[i];
+                mp.dst[n_push] = static_cast<IdT*>(sl.ids);
+                mp.slot[n_push] = slot;
+                n_push++;
+                ms.pushed[i] = static_cast<const IdT*>(sl.ids);
+                ms.pushed_slot[i] = slot;
+                sl.last_reader = -1;
+                count++;
+            }
+            const uint64_t n_raw = slots[head].n_raw;
+            ms.head[i] = static_cast<const IdT*>(slots[head].ids);
+            ms.head_slot[i] = head;
+            ms.out_capacity[i] = caps[i];
+            ms.plan_offset[i] = off;
+            off += std::min<uint64_t>(n_raw, store->n_rows);
+            ms.out[i] = static_cast<char*>(outs[i]);
+            ms.unique_out[i] = uniques ? static_cast<IdT*>(uniques[i]) : nullptr;
+            const int r = (int)((seq + i) % STATS_RING);
+            raw_of[r] = (uint32_t)n_raw;
+            prof_valid[r] = false;
+            slots[head].last_reader = (int64_t)(seq + i);
+            head = (head + 1) % slots.size();
+            count--;
+        }
+        launch_dedup_small<IdT>(mp, n_push, store->n_rows, ctl, m);
+        launch_classify_many<IdT>(view(), accum_view(), group, ms, longest, many_plan, ring_dev, STATS_RING, m);
+        HIP_TRY(hipGetLastError());
+        const int r_last = (int)((seq + k - 1) % STATS_RING);
+        for (uint32_t i = 0; i < k; i++) ev_of[(seq + i) % STATS_RING] = r_last;
+        if (pipelined) {
+            HIP_TRY(hipEventRecord(ev_meta[r_last], meta));
+            if (n_push && (rc = edge(meta, s))) return rc;    // the caller may reuse its ID buffers in stream order
+        }
+        open_upper = total_upper;
+        open_batches = k;
+        seq += k;
+        if ((rc = close_group(s, pipelined ? ev_meta[r_last] : nullptr))) return rc;
+        HIP_TRY(hipEventRecord(events[r_last], s));
+        return GIDS_OK;
     }
 
     uint32_t window_count() const override { return count; }
@@ -1047,6 +1185,13 @@ int gids_cache_set_rows_per_line(gids_cache* cache, uint32_t rows) {
     return GIDS_OK;
 }
 
+int gids_gather_many(gids_cache* cache, uint32_t k, const void* const* push_ids_dev, const uint64_t* push_n,
+                     void* const* out_dev, const uint64_t* out_capacity_rows, void* const* unique_dev, void* stream) {
+    CHECK_CACHE(cache);
+    if (push_ids_dev && !push_n) return fail(GIDS_E_INVAL, "gids_gather_many: push_n is NULL");
+    return cache->gather_many(k, push_ids_dev, push_n, out_dev, out_capacity_rows, unique_dev, static_cast<hipStream_t>(stream));
+}
+
 int gids_flush(gids_cache* cache, void* stream) {
     CHECK_CACHE(cache);
     return cache->flush(static_cast<hipStream_t>(stream));
@@ -1056,8 +1201,9 @@ int gids_stats_read(gids_cache* cache, uint64_t seq, gids_stats* stats) {
     if (!cache || !stats) return fail(GIDS_E_INVAL, "gids_stats_read: NULL argument");
     if (seq >= cache->seq || seq + STATS_RING < cache->seq) return fail(GIDS_E_INVAL, "gids_stats_read: gather %llu is not available", (unsigned long long)seq);
     const int r = (int)(seq % STATS_RING);
-    if (cache->pipelined) HIP_TRY(hipEventSynchronize(cache->ev_meta[r]));
-    HIP_TRY(hipEventSynchronize(cache->events[r]));
+    const int er = cache->ev_of[r];
+    if (cache->pipelined) HIP_TRY(hipEventSynchronize(cache->ev_meta[er]));
+    HIP_TRY(hipEventSynchronize(cache->events[er]));
     const StatsRec rec = cache->ring_host[r];
     if (rec.seq != seq) return fail(GIDS_E_INVAL, "gids_stats_read: record of gather %llu was overwritten", (unsigned long long)seq);
     stats->seq = rec.seq; stats->n_unique = rec.n_unique; stats->n_hit = rec.n_hit; stats->n_cpu_hit = rec.n_cpu_hit;

@@ -19,7 +19,8 @@ constexpr uint64_t PLAN_INDEX_MASK = (1ull << PLAN_SHIFT) - 1;
 constexpr uint32_t NO_OP = 0xFFFFFFFFu;       // "no pending fill" marker of a cache line
 constexpr uint64_t NO_LINE = ~0ull;           // a queued fill that installs nothing
 
-constexpr int MAX_WINDOW_SLOTS = 256;      // window_depth <= 254, + 2
+constexpr int MANY_MAX = 32;                // steps one merged call can bring
+constexpr int MAX_WINDOW_SLOTS = 256 + MANY_MAX;   // window_depth <= 254, + 2, + the lists a merged call pushes at once
 
 // Device-resident control block of one cache.  Kernels read every count from
 // here, so the host never has to wait for a count before launching the next.
@@ -39,6 +40,7 @@ struct Ctl {
     uint32_t q_rcopy[2];    // hits whose line already holds its bytes
     uint32_t q_wcopy[2];    // copies that must follow the link rows: hits on lines filled in the same group, ...
     uint32_t q_chunk[2];    // work counter of the group mover's link half
+    uint32_t many_cnt[MANY_MAX][5];     // per step of a merged call: hits, CPU-buffer hits, misses, bypasses, line fills
     uint32_t win_n[MAX_WINDOW_SLOTS];   // distinct count of each buffered list
 };
 
@@ -196,6 +198,35 @@ template <typename IdT>
 void launch_settle(const CacheView<IdT>& c, const AccumView& a, uint32_t group, int accum, const IdT* unique,
                    const uint32_t* n_u, uint64_t n_upper, const uint64_t* plan, BatchHdr* hdr, char* out,
                    IdT* unique_out, StatsRec* rec, uint64_t seq, hipStream_t s);
+
+// ---- merged iterations: k steps (push one list, gather the window's head) in one call
+template <typename IdT>
+struct ManyPushes {                     // the lists the call pushes, one workgroup each
+    const IdT* ids[MANY_MAX];           // raw list
+    uint64_t n[MANY_MAX];
+    IdT* dst[MANY_MAX];                 // window slot that receives the ascending distinct IDs
+    uint32_t slot[MANY_MAX];            // its entry of Ctl::win_n
+};
+template <typename IdT>
+struct ManySteps {
+    uint32_t k;
+    uint64_t seq0;                      // gather index of step 0
+    const IdT* pushed[MANY_MAX];        // distinct list pushed in step i (nullptr: none), and its count's entry
+    uint32_t pushed_slot[MANY_MAX];
+    const IdT* head[MANY_MAX];          // distinct list gathered in step i
+    uint32_t head_slot[MANY_MAX];
+    uint64_t out_capacity[MANY_MAX];
+    uint64_t plan_offset[MANY_MAX];     // where step i's plan starts in the call's plan buffer
+    char* out[MANY_MAX];
+    IdT* unique_out[MANY_MAX];
+};
+uint64_t many_max_rows();
+uint32_t many_max_ways();
+template <typename IdT>
+void launch_dedup_small(const ManyPushes<IdT>& p, uint32_t n_lists, uint64_t n_rows, Ctl* ctl, hipStream_t s);
+template <typename IdT>
+void launch_classify_many(const CacheView<IdT>& c, const AccumView& a, uint32_t group, const ManySteps<IdT>& m,
+                          uint64_t longest, uint64_t* plan_all, StatsRec* ring, uint32_t ring_size, hipStream_t s);
 
 template <typename IdT>
 void launch_group_move(const CacheView<IdT>& c, const AccumView& a, uint32_t parity, uint64_t rows_upper,

@@ -1,0 +1,374 @@
+// Merged iterations (GIDS paper, Section 3.2: the data preparation of several
+// consecutive iterations is merged so that the stop-and-go boundaries between
+// minibatches disappear).  One call brings k steps, each "push one future list,
+// gather the window's head"; here all k steps run in two launches, whatever k:
+//
+//   dedup_small   one workgroup per pushed list: the list is marked into a
+//                 bitmap in LDS (tables of up to 516,096 rows), scanned and
+//                 written out as ascending distinct IDs.  Nothing else of the
+//                 push happens here.
+//   classify_many the k steps one after the other inside one kernel.  A step's
+//                 decisions depend only on the state of the cache sets its IDs
+//                 fall into, and so does everything a step changes (tags,
+//                 stamps, the future-reuse counters of the nodes that map to a
+//                 set): the sets are dealt out to the workgroups (set s belongs
+//                 to workgroup s mod gridDim.x), every workgroup scans each
+//                 list, keeps the IDs of its own sets and walks through the
+//                 steps at its own pace, with workgroup barriers between the
+//                 phases of a step and no synchronisation between workgroups
+//                 at all.  Per step: the pushed list's future-reuse counters
+//                 +1 (Section 3.4, Fig. 6); the head list's counters -1,
+//                 CPU-buffer lookup (Section 3.3), tag probe; victims; commit
+//                 and the accumulator's queueing (every row becomes an
+//                 operation of the open group, whose mover runs after this
+//                 kernel).  One thread per ID, the `ways` tags of a set read by
+//                 that thread (ways <= 16).  The last workgroup to finish
+//                 publishes the k records of counters.
+#include "gather_dev.h"
+#include "gids_dev.h"
+
+namespace gids {
+
+namespace {
+
+constexpr int DS_THREADS = 1024;
+constexpr int DS_WORDS = 8064;             // 64-bit words of the LDS bitmap (63 KiB): 516,096 rows
+constexpr int CM_THREADS = 256;
+constexpr int CM_UNROLL = 4;               // list entries a thread fetches before it looks at any
+
+template <typename IdT>
+__global__ __launch_bounds__(DS_THREADS) void dedup_small_kernel(ManyPushes<IdT> p, uint64_t n_rows, Ctl* ctl) {
+    __shared__ unsigned long long bm[DS_WORDS];
+    __shared__ uint32_t wave_sum[DS_THREADS / 64];
+    const uint32_t tid = threadIdx.x;
+    const IdT* __restrict__ ids = p.ids[blockIdx.x];
+    const uint64_t n = p.n[blockIdx.x];
+    IdT* __restrict__ dst = p.dst[blockIdx.x];
+    const uint32_t n_words = (uint32_t)((n_rows + 63) / 64);
+    for (uint32_t w = tid; w < n_words; w += DS_THREADS) bm[w] = 0ull;
+    __syncthreads();
+    bool bad = false;
+    for (uint64_t i = tid; i < n; i += DS_THREADS) {
+        const IdT raw = ids[i];
+        if (raw < 0 || (uint64_t)raw >= n_rows) { bad = true; continue; }
+        const uint64_t v = (uint64_t)raw;
+        atomicOr(&bm[v >> 6], 1ull << (v & 63));
+    }
+    if (bad) atomicCAS(&ctl->error, 0u, 3u /* -GIDS_E_RANGE */);
+    __syncthreads();
+    // every thread takes a run of consecutive words: population count, workgroup prefix, then the bit positions
+    const uint32_t per = (n_words + DS_THREADS - 1) / DS_THREADS;
+    const uint32_t w0 = tid * per, w1 = w0 + per < n_words ? w0 + per : n_words;
+    uint32_t c = 0;
+    for (uint32_t w = w0; w < w1; w++) c += (uint32_t)__popcll(bm[w]);
+    uint32_t incl = c;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t y = __shfl_up(incl, d);
+        if ((tid & 63) >= (uint32_t)d) incl += y;
+    }
+    if ((tid & 63) == 63) wave_sum[tid >> 6] = incl;
+    __syncthreads();
+    uint32_t base = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < DS_THREADS / 64; w++) {
+        const uint32_t s = wave_sum[w];
+        if ((uint32_t)w < (tid >> 6)) base += s;
+        total += s;
+    }
+    uint32_t pos = base + incl - c;
+    for (uint32_t w = w0; w < w1; w++) {
+        unsigned long long x = bm[w];
+        while (x) {
+            dst[pos++] = (IdT)((uint64_t)w * 64 + (uint64_t)(__ffsll(x) - 1));
+            x &= x - 1;
+        }
+    }
+    if (tid == 0) ctl->win_n[p.slot[blockIdx.x]] = total;
+}
+
+template <typename IdT>
+__device__ __forceinline__ bool owns(const CacheView<IdT>& c, uint64_t set, uint32_t n_wg, uint32_t me) {
+    return c.use32 ? (uint32_t)set % n_wg == me : set % n_wg == me;
+}
+
+template <typename IdT, int WAYS>
+__global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT> c, AccumView a, uint32_t group,
+                                                                   ManySteps<IdT> m, uint64_t* __restrict__ plan_all,
+                                                                   StatsRec* ring, uint32_t ring_size) {
+    __shared__ uint32_t cnt[5];                              // hits, CPU-buffer hits, misses, bypasses, line fills
+    __shared__ uint32_t is_last;
+    Ctl* ctl = c.ctl;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t n_wg = gridDim.x, me = blockIdx.x;
+    const uint32_t stamp0 = ctl->stamp;
+    // an error left by an earlier kernel (a pushed ID out of range): nothing runs, every record reports it
+    uint32_t n_ok = ld_agent(&ctl->error) == 0 ? m.k : 0;
+    for (uint32_t i = 0; i < n_ok; i++) {
+        const int32_t stamp = (int32_t)(stamp0 + i);
+        const IdT* __restrict__ U = m.head[i];
+        const uint32_t n_u = ctl->win_n[m.head_slot[i]];
+        if (n_u > m.out_capacity[i]) {                        // the same verdict in every workgroup: this step
+            n_ok = i;                                         // and the later ones do not run
+            break;
+        }
+        uint64_t* __restrict__ plan = plan_all + m.plan_offset[i];
+        if (tid < 5) cnt[tid] = 0;
+        // ---- the list pushed in this step: one more buffered future use for each of its nodes
+        if (m.pushed[i]) {
+            const IdT* __restrict__ P = m.pushed[i];
+            const uint32_t n_p = ctl->win_n[m.pushed_slot[i]];
+            for (uint64_t base = tid; base < n_p; base += (uint64_t)CM_THREADS * CM_UNROLL) {
+                uint64_t vv[CM_UNROLL];
+#pragma unroll
+                for (int u = 0; u < CM_UNROLL; u++) {
+                    const uint64_t j = base + (uint64_t)u * CM_THREADS;
+                    vv[u] = j < n_p ? (uint64_t)P[j] : ~0ull;
+                }
+#pragma unroll
+                for (int u = 0; u < CM_UNROLL; u++) {
+                    if (vv[u] == ~0ull) continue;
+                    uint64_t set, round;
+                    set_and_round(c, vv[u], &set, &round);
+                    if (owns(c, set, n_wg, me)) c.reuse[vv[u]] = (uint8_t)(c.reuse[vv[u]] + 1);
+                }
+            }
+        }
+        __threadfence();
+        __syncthreads();
+        uint32_t hits = 0, cpus = 0, misses = 0, bypasses = 0, fills = 0;
+        // ---- probe: every ID of this workgroup's sets against the state at the start of the minibatch
+        for (uint64_t base = tid; base < n_u; base += (uint64_t)CM_THREADS * CM_UNROLL) {
+            uint64_t vv[CM_UNROLL];
+#pragma unroll
+            for (int u = 0; u < CM_UNROLL; u++) {
+                const uint64_t j = base + (uint64_t)u * CM_THREADS;
+                vv[u] = j < n_u ? (uint64_t)U[j] : ~0ull;
+            }
+#pragma unroll
+            for (int u = 0; u < CM_UNROLL; u++) {
+                const uint64_t j = base + (uint64_t)u * CM_THREADS;
+                const uint64_t v = vv[u];
+                if (v == ~0ull) continue;
+                uint64_t set, round;
+                set_and_round(c, v, &set, &round);
+                if (!owns(c, set, n_wg, me)) continue;
+                c.reuse[v] = (uint8_t)(c.reuse[v] - 1);       // this minibatch's own entry leaves the counters
+                if (c.hotbits) {
+                    const uint64_t hw = c.hotbits[v >> 6];
+                    const uint64_t bit = 1ull << (v & 63);
+                    if (hw & bit) {
+                        plan[j] = (PLAN_CPU << PLAN_SHIFT) | (c.hotrank[v >> 6] + (uint32_t)__popcll(hw & (bit - 1)));
+                        cpus++;
+                        continue;
+                    }
+                }
+                const IdT* row = c.tags + set * WAYS;
+                int way = -1;
+#pragma unroll
+                for (int w = 0; w < WAYS; w++)
+                    if ((uint64_t)row[w] == v) way = w;       // empty lines hold -1
+                if (way >= 0) {
+                    const uint64_t line = set * WAYS + (uint32_t)way;
+                    c.stamps[line] = stamp;
+                    plan[j] = (PLAN_HIT << PLAN_SHIFT) | line;
+                    hits++;
+                } else {
+                    plan[j] = PLAN_MISS_TBD << PLAN_SHIFT;
+                    atomicOr(reinterpret_cast<unsigned long long*>(c.missmask) + set * c.words_per_set + (round >> 6),
+                             1ull << (round & 63));
+                    misses++;
+                }
+            }
+        }
+        if (misses) atomicAdd(&cnt[2], misses);
+        __threadfence();
+        __syncthreads();
+        // ---- victims: the k-th miss of a set (ascending ID) takes the k-th evictable way in (stamp, way) order
+        const bool any_miss = cnt[2] != 0;
+        if (any_miss) {
+            for (uint64_t base = tid; base < n_u; base += (uint64_t)CM_THREADS * CM_UNROLL) {
+                uint64_t ee[CM_UNROLL];
+#pragma unroll
+                for (int u = 0; u < CM_UNROLL; u++) {
+                    const uint64_t j = base + (uint64_t)u * CM_THREADS;
+                    ee[u] = j < n_u ? plan[j] : 0ull;         // (entries of other workgroups' sets are skipped below)
+                }
+#pragma unroll
+                for (int u = 0; u < CM_UNROLL; u++) {
+                    const uint64_t j = base + (uint64_t)u * CM_THREADS;
+                    if (j >= n_u || (ee[u] >> PLAN_SHIFT) != PLAN_MISS_TBD) continue;
+                    const uint64_t v = (uint64_t)U[j];
+                    uint64_t set, round;
+                    set_and_round(c, v, &set, &round);
+                    if (!owns(c, set, n_wg, me)) continue;    // (what another workgroup or an earlier call left there)
+                    const uint64_t line0 = set * WAYS;
+                    IdT tg[WAYS];
+                    int32_t st[WAYS];
+#pragma unroll
+                    for (int w = 0; w < WAYS; w++) {
+                        tg[w] = c.tags[line0 + w];
+                        st[w] = c.stamps[line0 + w];
+                    }
+                    uint8_t ru[WAYS];
+#pragma unroll
+                    for (int w = 0; w < WAYS; w++) ru[w] = tg[w] < 0 ? (uint8_t)0 : c.reuse[(uint64_t)tg[w]];
+                    uint64_t key[WAYS];
+                    uint32_t n_ev = 0;
+#pragma unroll
+                    for (int w = 0; w < WAYS; w++) {
+                        const bool empty = tg[w] < 0;
+                        const bool ev = st[w] != stamp && ru[w] == 0;   // untouched in this minibatch, no buffered future use
+                        uint64_t order = (uint64_t)(uint32_t)(st[w] + 1);
+                        if (c.policy == 1)
+                            order = empty ? 0ull
+                                          : 1ull + (mix64(mix64(mix64(c.policy_key ^ (uint64_t)(uint32_t)stamp) ^ set) ^ (uint64_t)w) >> 9);
+                        key[w] = ev ? (order << 8) | (uint64_t)w : ~0ull;
+                        n_ev += ev;
+                    }
+                    uint32_t rank = 0;                        // of this miss among its set's misses, ascending ID
+                    const uint64_t* mm = c.missmask + set * c.words_per_set;
+                    const uint32_t wi = (uint32_t)(round >> 6);
+                    for (uint32_t x = 0; x < wi; x++) rank += (uint32_t)__popcll(mm[x]);
+                    rank += (uint32_t)__popcll(mm[wi] & ((1ull << (round & 63)) - 1));
+                    if (rank >= n_ev) {
+                        plan[j] = PLAN_BYPASS << PLAN_SHIFT;
+                        bypasses++;
+                    } else {
+                        int way = 0;
+#pragma unroll
+                        for (int w = 0; w < WAYS; w++) {
+                            uint32_t r = 0;
+#pragma unroll
+                            for (int o = 0; o < WAYS; o++) r += key[o] < key[w];
+                            if (key[w] != ~0ull && r == rank) way = w;
+                        }
+                        plan[j] = (PLAN_INSTALL << PLAN_SHIFT) | (line0 + (uint32_t)way);
+                        fills++;
+                    }
+                }
+            }
+            __threadfence();
+            __syncthreads();
+        }
+        // ---- publish tags and stamps, clear the miss mask, queue every row into the open group's lists
+        for (uint64_t base = 0; base < n_u; base += CM_THREADS) {    // uniform trip count: queue_entry ballots
+            const uint64_t j = base + tid;
+            bool mine = false;
+            uint64_t e = 0, v = 0;
+            if (j < n_u) {
+                v = (uint64_t)U[j];
+                uint64_t set, round;
+                set_and_round(c, v, &set, &round);
+                mine = owns(c, set, n_wg, me);
+                if (mine) {
+                    e = plan[j];
+                    const uint64_t kind = e >> PLAN_SHIFT;
+                    if (kind >= PLAN_INSTALL) {
+                        if (kind == PLAN_INSTALL) {
+                            const uint64_t line = e & PLAN_INDEX_MASK;
+                            c.tags[line] = (IdT)v;
+                            c.stamps[line] = stamp;
+                        }
+                        c.missmask[set * c.words_per_set + (round >> 6)] = 0ull;
+                    }
+                }
+            }
+            queue_entry(c, a, group, mine, j, e, v, m.out[i], m.unique_out[i]);
+        }
+        // ---- this workgroup's share of the step's counters
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            hits += __shfl_down(hits, d);
+            cpus += __shfl_down(cpus, d);
+            bypasses += __shfl_down(bypasses, d);
+            fills += __shfl_down(fills, d);
+        }
+        if ((tid & 63) == 0) {
+            if (hits) atomicAdd(&cnt[0], hits);
+            if (cpus) atomicAdd(&cnt[1], cpus);
+            if (bypasses) atomicAdd(&cnt[3], bypasses);
+            if (fills) atomicAdd(&cnt[4], fills);
+        }
+        __threadfence();
+        __syncthreads();
+        if (tid < 5 && cnt[tid]) atomicAdd(&ctl->many_cnt[i][tid], cnt[tid]);
+        __syncthreads();                                      // cnt is cleared at the top of the next step
+    }
+    // ---- the last workgroup to get here publishes the records
+    if (tid == 0) {
+        __threadfence();
+        is_last = atomicAdd(&ctl->ticket_cls, 1u) == n_wg - 1;
+    }
+    __syncthreads();
+    if (!is_last || tid != 0) return;
+    __threadfence();
+    if (n_ok < m.k && ld_agent(&ctl->error) == 0) atomicCAS(&ctl->error, 0u, 7u /* -GIDS_E_SPACE: step n_ok's output */);
+    const uint32_t err = ld_agent(&ctl->error);
+    uint32_t queued = 0;
+    for (uint32_t i = 0; i < m.k; i++) {
+        StatsRec* rec = ring + (m.seq0 + i) % ring_size;
+        const bool ran = i < n_ok;
+        const uint32_t n = ran ? ctl->win_n[m.head_slot[i]] : 0u;
+        rec->n_unique = n;
+        rec->n_hit = ld_agent(&ctl->many_cnt[i][0]);
+        rec->n_cpu_hit = ld_agent(&ctl->many_cnt[i][1]);
+        rec->n_miss = ld_agent(&ctl->many_cnt[i][2]);
+        rec->n_bypass = ld_agent(&ctl->many_cnt[i][3]);
+        rec->n_line_fills = ld_agent(&ctl->many_cnt[i][4]);
+        queued += n;
+        const bool closes = i + 1 == m.k;                     // the call's steps are one group, closed by its last
+        rec->n_pending = closes ? 0u : queued;
+        rec->flushed = closes ? 1 : 0;
+        rec->status = ran ? 0 : -(int32_t)err;
+        for (int x = 0; x < 5; x++) ctl->many_cnt[i][x] = 0;
+    }
+    ctl->q_rows = 0;
+    ctl->stamp = stamp0 + n_ok;
+    ctl->ticket_cls = 0;
+    __threadfence_system();
+    for (uint32_t i = 0; i < m.k; i++) ring[(m.seq0 + i) % ring_size].seq = m.seq0 + i;   // a record whose seq matches is complete
+    __threadfence_system();
+}
+
+}  // namespace
+
+uint64_t many_max_rows() { return (uint64_t)DS_WORDS * 64; }
+uint32_t many_max_ways() { return 16; }
+
+template <typename IdT>
+void launch_dedup_small(const ManyPushes<IdT>& p, uint32_t n_lists, uint64_t n_rows, Ctl* ctl, hipStream_t s) {
+    if (n_lists == 0) return;
+    hipLaunchKernelGGL(dedup_small_kernel<IdT>, dim3(n_lists), dim3(DS_THREADS), 0, s, p, n_rows, ctl);
+}
+
+template <typename IdT>
+void launch_classify_many(const CacheView<IdT>& c, const AccumView& a, uint32_t group, const ManySteps<IdT>& m,
+                          uint64_t longest, uint64_t* plan_all, StatsRec* ring, uint32_t ring_size, hipStream_t s) {
+    // about 64 of a list's entries per workgroup's own share; every workgroup reads every list
+    uint64_t g = (longest + 63) / 64;
+    if (g < 1) g = 1;
+    if (g > 256) g = 256;
+    if (g > c.n_sets) g = c.n_sets;                          // a workgroup without a set would only take a ticket
+#define GIDS_CLASSIFY_MANY(W)                                                                                     \
+    hipLaunchKernelGGL((classify_many_kernel<IdT, W>), dim3((uint32_t)g), dim3(CM_THREADS), 0, s, c, a, group, m,  \
+                       plan_all, ring, ring_size)
+    switch (c.ways) {
+        case 1: GIDS_CLASSIFY_MANY(1); break;
+        case 2: GIDS_CLASSIFY_MANY(2); break;
+        case 4: GIDS_CLASSIFY_MANY(4); break;
+        case 8: GIDS_CLASSIFY_MANY(8); break;
+        default: GIDS_CLASSIFY_MANY(16); break;
+    }
+#undef GIDS_CLASSIFY_MANY
+}
+
+#define GIDS_INSTANTIATE(IdT)                                                                                     \
+    template void launch_dedup_small<IdT>(const ManyPushes<IdT>&, uint32_t, uint64_t, Ctl*, hipStream_t);         \
+    template void launch_classify_many<IdT>(const CacheView<IdT>&, const AccumView&, uint32_t,                    \
+                                            const ManySteps<IdT>&, uint64_t, uint64_t*, StatsRec*, uint32_t,      \
+                                            hipStream_t);
+GIDS_INSTANTIATE(int32_t)
+GIDS_INSTANTIATE(int64_t)
+
+}  // namespace gids

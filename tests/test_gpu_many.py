@@ -1,0 +1,214 @@
+"""gids_gather_many: k steps of the steady-state loop (push one list, gather the
+window's head) in one call, as one accumulator group.  Outputs, counters and
+cache state must be those of the oracle fed the same steps one by one."""
+import os
+
+import numpy as np
+import pytest
+
+import workload as wl
+from workload import CONFIGS
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU (no CPU fallback exists)")
+    import paper_2306_16384_amd as gids
+    from paper_2306_16384_amd.session import GatherSession
+    gids.lib()
+    return torch, gids, GatherSession
+
+
+def with_env(knobs, make):
+    old = {k: os.environ.get(k) for k in knobs}
+    os.environ.update(knobs)
+    try:
+        return make()
+    finally:
+        for k, v in old.items():
+            if v is None:
+                del os.environ[k]
+            else:
+                os.environ[k] = v
+
+
+def run_many(gpu, oracle, feats, batches, *, id_dtype, lines, ways, window, ks, hot=None, policy=None, pipeline="0",
+             fuse=None, label=""):
+    """ks: the sizes of the merged calls, in order (0 = one plain push + gather step in between);
+    cycles until every list is gathered."""
+    torch, gids, GatherSession = gpu
+    n_rows = feats.shape[0]
+    feats_u8 = np.ascontiguousarray(feats).view(np.uint8).reshape(n_rows, -1)
+    R = feats_u8.shape[1]
+    n_b = len(batches)
+    print(f"[many {label}] rows={n_rows} R={R} lines={lines} ways={ways} W={window} pipe={pipeline} fuse={fuse} ks={ks}", flush=True)
+    sim = oracle.Sim(n_rows, lines, ways, window, R, R, feats_u8)
+    if hot is not None:
+        sim.set_hot(hot)
+    if policy is not None:
+        sim.set_policy(*policy)
+    want, pushed = [], 0
+    for t, raw in enumerate(batches):
+        while window and pushed < n_b and pushed <= t + window:
+            sim.push(batches[pushed])
+            pushed += 1
+        want.append(sim.gather(raw))
+    knobs = {"GIDS_PIPELINE": pipeline}
+    if fuse is not None:
+        knobs["GIDS_FUSE"] = fuse
+    ses = with_env(knobs, lambda: GatherSession(n_rows, R, id_dtype, lines, ways, R, window, 1000))
+    with ses:
+        ses.store_view()[:] = feats_u8
+        if hot is not None:
+            ses.pin_hot(hot)
+        if policy is not None:
+            ses.set_policy(*policy)
+        dev = [ses.to_device(b) for b in batches]
+        torch.cuda.synchronize()
+        push_stream = torch.cuda.Stream() if pipeline == "1" else None
+        outs = [torch.full((max(len(b), 1), R), 0xA5, dtype=torch.uint8, device="cuda") for b in batches]
+        uqs = [torch.full((max(len(b), 1),), -7, dtype=ses.torch_id, device="cuda") for b in batches]
+        seq_of, expect_acc = {}, {}
+        pushed = 0
+        if window == 0:
+            pass                                              # depth 0: every step pushes its own list just before
+        else:
+            while pushed < min(n_b, window):                  # the look-ahead, filled by plain pushes
+                ses.push(dev[pushed], stream=push_stream)
+                pushed += 1
+        t, call = 0, 0
+        while t < n_b:
+            k = ks[call % len(ks)]
+            call += 1
+            if k == 0:                                        # a plain step between merged calls
+                if pushed < n_b and pushed <= t + window:
+                    ses.push(dev[pushed], stream=push_stream)
+                    pushed += 1
+                seq_of[t] = ses.gather(None, outs[t], uqs[t])
+                expect_acc[t] = None
+                t += 1
+                continue
+            k = min(k, n_b - t)
+            pushes = []
+            for i in range(k):
+                if pushed < n_b and pushed <= t + i + window:
+                    pushes.append(dev[pushed])
+                    pushed += 1
+                else:
+                    pushes.append(None)
+            seq0 = ses.gather_many(pushes, outs[t:t + k], uqs[t:t + k])
+            rows = 0
+            for i in range(k):
+                seq_of[t + i] = seq0 + i
+                rows += len(want[t + i][0])
+                expect_acc[t + i] = (0, 1) if i == k - 1 else (rows, 0)
+            t += k
+        ses.flush()
+        torch.cuda.synchronize()
+        for t in range(n_b):
+            u, rows, stats = want[t]
+            st = ses.stats(seq_of[t])
+            assert st.status == 0
+            assert st.as_tuple() == tuple(int(x) for x in stats), (label, t, st.as_tuple(), stats.tolist())
+            if expect_acc[t] is not None:
+                assert (st.n_pending, st.flushed) == expect_acc[t], (label, t, st.n_pending, st.flushed, expect_acc[t])
+            m = len(u)
+            assert np.array_equal(uqs[t][:m].cpu().numpy(), u.astype(ses.id_dtype)), (label, t)
+            assert np.array_equal(outs[t][:m].cpu().numpy(), rows), f"{label} minibatch {t}: gathered rows differ"
+            if m < outs[t].shape[0]:
+                assert bool((outs[t][m:] == 0xA5).all())
+        tags, stamps = ses.snapshot()
+        assert np.array_equal(tags, sim.tags), label
+        assert np.array_equal(stamps, sim.stamps), label
+
+
+def zipf_lists(rng, n, n_b, size, a=1.2):
+    return [np.minimum(rng.zipf(a, size=int(rng.integers(size // 2, size + 1))) - 1, n - 1).astype(np.int64)
+            for _ in range(n_b)]
+
+
+@pytest.mark.parametrize("pipeline", ["0", "1"])
+def test_tiny_config_in_merged_calls(gpu, oracle_mod, pipeline):
+    cfg = CONFIGS["tiny"]
+    g = wl.make_graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max)
+    table = wl.normal_table(np.float32)
+    feats = wl.feature_rows(cfg.seed, np.arange(cfg.n_nodes), cfg.dim, table)
+    hot = wl.hot_nodes(g, cfg.cpu_rows)
+    batches = [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds) for b in range(48)]
+    for ks in ([8], [1, 3, 0, 32, 2], [32]):
+        run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int32, lines=cfg.cache_lines, ways=cfg.ways,
+                 window=cfg.window, ks=ks, hot=hot, pipeline=pipeline, label=f"tiny/{ks}")
+
+
+@pytest.mark.parametrize("ways,window,id_dtype,policy", [(1, 0, np.int64, None), (2, 1, np.int32, None), (4, 3, np.int64, (1, 7)),
+                                                         (8, 9, np.int32, None), (16, 2, np.int64, (1, 3)), (64, 2, np.int64, None)])
+def test_merged_calls_over_shapes(gpu, oracle_mod, ways, window, id_dtype, policy):
+    """Associativity (64 ways takes the per-step kernels), window depths beyond and below the call size, both ID
+    widths and both policies; a small cache, so that lines are hit, evicted and refilled inside one call."""
+    rng = np.random.default_rng(500 + ways + window)
+    n = 3000
+    feats = rng.integers(0, 256, size=(n, 128), dtype=np.uint8)
+    batches = zipf_lists(rng, n, 40, 500)
+    batches[7] = np.array([5], dtype=np.int64)
+    batches[11] = np.arange(n, dtype=np.int64)                 # the whole table
+    for pipeline in ("0", "1"):
+        run_many(gpu, oracle_mod, feats, batches, id_dtype=id_dtype, lines=ways * 11, ways=ways, window=window,
+                 ks=[5, 0, 13, 1], hot=rng.choice(n, 40, replace=False), policy=policy, pipeline=pipeline,
+                 label=f"ways{ways}/W{window}")
+
+
+def test_merged_calls_through_the_per_step_kernels(gpu, oracle_mod):
+    """The same calls with the merged kernels switched off (what a large table gets): one group per call."""
+    rng = np.random.default_rng(77)
+    n = 5000
+    feats = rng.integers(0, 256, size=(n, 64), dtype=np.uint8)
+    batches = zipf_lists(rng, n, 30, 700)
+    for pipeline in ("0", "1"):
+        run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=256, ways=4, window=4, ks=[6, 0, 9],
+                 hot=rng.choice(n, 60, replace=False), pipeline=pipeline, fuse="0", label="per-step")
+
+
+def test_a_table_beyond_the_lds_bitmap(gpu, oracle_mod):
+    rng = np.random.default_rng(78)
+    n = 600_000                                               # more rows than the merged dedup's bitmap holds
+    feats = rng.integers(0, 256, size=(n, 16), dtype=np.uint8)
+    batches = [rng.integers(0, n, size=3000) for _ in range(12)]
+    run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=1024, ways=8, window=2, ks=[4], label="600k")
+
+
+def test_merged_call_errors(gpu):
+    torch, gids, GatherSession = gpu
+    feats = np.arange(200 * 64, dtype=np.uint8).reshape(200, 64)
+    out = [torch.zeros((8, 64), dtype=torch.uint8, device="cuda") for _ in range(3)]
+    with GatherSession(200, 64, np.int64, 16, 4, 64, 1) as s:      # no accumulator
+        with pytest.raises(gids.GidsError) as e:
+            s.gather_many([s.to_device([1])], out[:1])
+        assert e.value.code == gids.GIDS_E_INVAL
+    with GatherSession(200, 64, np.int64, 16, 4, 64, 1, 100) as s:
+        s.store_view()[:] = feats
+        with pytest.raises(gids.GidsError) as e:                # nothing buffered and nothing pushed
+            s.gather_many([None], out[:1])
+        assert e.value.code == gids.GIDS_E_ORDER
+        with pytest.raises(gids.GidsError) as e:                # 33 steps
+            s.gather_many([None] * 33, [out[0]] * 33)
+        assert e.value.code == gids.GIDS_E_INVAL
+        assert gids.gids_cache_gathers(s.cache) == 0
+        # the second step's output is too small: step 0 stands, steps 1 and 2 report the error
+        lists = [s.to_device([1, 2, 3]), s.to_device(np.arange(20)), s.to_device([4])]
+        seq0 = s.gather_many(lists, out)
+        st0 = s.stats(seq0)
+        assert st0.as_tuple() == (3, 0, 0, 3, 0)
+        with pytest.raises(gids.GidsError) as e:
+            s.stats(seq0 + 1)
+        assert e.value.code == gids.GIDS_E_SPACE
+        torch.cuda.synchronize()
+        assert np.array_equal(out[0][:3].cpu().numpy(), feats[[1, 2, 3]])
+    with GatherSession(200, 64, np.int64, 16, 4, 64, 1, 100) as s:     # a pushed ID outside the table
+        seq0 = s.gather_many([s.to_device([1, 2]), s.to_device([7, 200])], out[:2])
+        with pytest.raises(gids.GidsError) as e:
+            s.stats(seq0)
+        assert e.value.code == gids.GIDS_E_RANGE
