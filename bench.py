@@ -88,6 +88,9 @@ def main() -> int:
     ap.add_argument("--accum", type=int, default=0,
                     help="accumulator threshold in node accesses (raw list entries) per merged group of minibatches "
                          "(0 = every gather moves its own rows)")
+    ap.add_argument("--many", type=int, default=0, metavar="K",
+                    help="issue the steps K at a time through gids_gather_many (merged iterations: one call pushes K "
+                         "lists and gathers K minibatches as one group); needs --accum > 0 for the group lists")
     ap.add_argument("--accum-adaptive", action="store_true",
                     help="read --accum as the store accesses wanted per launch (Eq. 2-3's N) and let the library "
                          "raise the node-access threshold by the redirected share (Section 3.2)")
@@ -433,7 +436,7 @@ def run_point(args, env, cfg, window, raws, n_pre):
     # (a group holds at most GIDS_ACCUM_MAX_MERGE = 32 minibatches, so a buffer is complete before its turn comes again)
     ring = 2 if args.accum == 0 else 40
     outs = [torch.empty((cap_rows, R), dtype=torch.uint8, device="cuda") for _ in range(ring)]
-    uniq = torch.empty(cap_rows, dtype=ses.torch_id, device="cuda")
+    uniqs = [torch.empty(cap_rows, dtype=ses.torch_id, device="cuda") for _ in range(ring)]
     torch.cuda.synchronize()
 
     # pushes go to their own stream (where a sampler would produce ID lists), gathers to the consumer's:
@@ -468,16 +471,49 @@ def run_point(args, env, cfg, window, raws, n_pre):
 
     def step(t):
         keep_window_full(t)                                     # push of minibatch t + W (+1 at start-up)
-        return ses.gather(dev[t] if args.pass_ids else None, outs[t % ring], uniq)
+        return ses.gather(dev[t] if args.pass_ids else None, outs[t % ring], uniqs[t % ring])
+
+    def steps_merged(t0, t1, seqs_out):
+        """minibatches [t0, t1) through gids_gather_many, args.many at a time"""
+        nonlocal pushed
+        t = t0
+        while t < t1:
+            k = min(args.many, t1 - t)
+            pushes = []
+            for i in range(k):
+                if pushed < n_batches and pushed <= t + i + window:
+                    pushes.append(dev[pushed])
+                    pushed += 1
+                else:
+                    pushes.append(None)
+            seq0 = ses.gather_many(pushes, [outs[(t + i) % ring] for i in range(k)],
+                                   [uniqs[(t + i) % ring] for i in range(k)], push_stream=push_stream)
+            for i in range(k):
+                seqs_out[t + i] = seq0 + i
+            t += k
+
+    if args.many:
+        if not args.accum or sampler is not None or args.pass_ids or not use_push:
+            raise SystemExit("--many needs --accum > 0 and the plain push / gather loop")
 
     seqs = {}
-    for t in range(warmup):
-        seqs[t] = step(t)
+    if args.many:
+        while pushed < min(n_batches, window):                  # the look-ahead, before the first merged call
+            ses.push(dev[pushed], stream=push_stream)
+            pushed += 1
+        torch.cuda.current_stream().wait_stream(push_stream)
+        steps_merged(0, warmup, seqs)
+    else:
+        for t in range(warmup):
+            seqs[t] = step(t)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
-    for t in range(warmup, warmup + steps):
-        seqs[t] = step(t)
+    if args.many:
+        steps_merged(warmup, warmup + steps, seqs)
+    else:
+        for t in range(warmup, warmup + steps):
+            seqs[t] = step(t)
     ses.flush()
     torch.cuda.current_stream().wait_stream(push_stream)       # the timed region ends when its pushes have too
     e1.record()
@@ -515,13 +551,20 @@ def run_point(args, env, cfg, window, raws, n_pre):
     # second pass with per-phase HIP events (on the launch stream) for the row mover's own roofline
     gids.gids_profile_enable(ses.cache, True)
     pseq = {}
-    for t in range(warmup + steps, warmup + 2 * steps):
-        pseq[t] = step(t)
+    if args.many:
+        steps_merged(warmup + steps, warmup + 2 * steps, pseq)
+    else:
+        for t in range(warmup + steps, warmup + 2 * steps):
+            pseq[t] = step(t)
     ses.flush()
     torch.cuda.synchronize()
     gids.gids_profile_enable(ses.cache, False)
     keep = sorted(pseq)[-min(steps, 60):]
-    ph = np.array([gids.gids_profile_read(ses.cache, pseq[t]) for t in keep])
+    if args.many:                                               # merged calls record no per-gather phase events:
+        ph = np.zeros((len(keep), 3))                           # the step time of this pass stands in for the mover's
+        ph[:, 2] = total_ms / steps
+    else:
+        ph = np.array([gids.gids_profile_read(ses.cache, pseq[t]) for t in keep])
     pst = [ses.stats(pseq[t]) for t in keep]
     mv_ms = float(ph[:, 2].mean())
     per_launch = [algorithmic_bytes(s.n_hit, s.n_cpu_hit, s.n_miss, s.n_bypass, s.n_line_fills) for s in pst]
@@ -615,7 +658,7 @@ def run_point(args, env, cfg, window, raws, n_pre):
         "unique_ids_per_s": n_unique * scale / (total_ms * 1e-3),
         "config": {"workload": cfg.name, "n_nodes": cfg.n_nodes, "row_bytes": R, "cache_lines": cfg.cache_lines,
                    "ways": cfg.ways, "line_bytes": cfg.line_bytes, "cpu_buffer_rows": cfg.cpu_rows, "window": window,
-                   "fanouts": list(cfg.fanouts), "seeds_per_batch": cfg.n_seeds, "accum_threshold": args.accum, "accum_adaptive": bool(args.accum_adaptive), "prewarm_lists": n_pre, "gpu_sampler": bool(args.gpu_sampler), "policy": args.policy, "hot_by": args.hot_by, "rows_per_line": args.rows_per_line, "id_stream": ("layerwise " + args.layerwise) if args.layerwise else "neighbourhood",
+                   "fanouts": list(cfg.fanouts), "seeds_per_batch": cfg.n_seeds, "accum_threshold": args.accum, "accum_adaptive": bool(args.accum_adaptive), "merged_calls_of": args.many, "prewarm_lists": n_pre, "gpu_sampler": bool(args.gpu_sampler), "policy": args.policy, "hot_by": args.hot_by, "rows_per_line": args.rows_per_line, "id_stream": ("layerwise " + args.layerwise) if args.layerwise else "neighbourhood",
                    "id_dtype": cfg.index_dtype, "scaled_from": base.n_nodes if cfg.n_nodes != base.n_nodes else None},
         "per_step": {"unique": n_unique * scale / steps, "hit": n_hit * scale / steps, "cpu_hit": n_cpu * scale / steps,
                      "miss": n_miss * scale / steps, "bypass": n_byp * scale / steps,
@@ -666,7 +709,7 @@ def run_point(args, env, cfg, window, raws, n_pre):
         import oracle
         t_last = max(pseq)                                        # the last minibatch gathered
         st = ses.stats(pseq[t_last])
-        u = uniq[:st.n_unique].cpu().numpy().astype(np.int64)
+        u = uniqs[t_last % ring][:st.n_unique].cpu().numpy().astype(np.int64)
         assert np.array_equal(u, np.unique(raws[t_last])), "distinct-ID list differs from sort-unique of the input"
         pick = np.unique(np.linspace(0, len(u) - 1, 64).astype(np.int64))
         got = outs[t_last % ring][torch.from_numpy(pick).cuda()].cpu().numpy()
@@ -689,7 +732,7 @@ def run_point(args, env, cfg, window, raws, n_pre):
             sim.set_rows_per_line(args.rows_per_line)
         if args.policy == "random":
             sim.set_policy(1, cfg.seed)
-        if args.accum:
+        if args.accum and not args.many:
             sim.set_accum(args.accum, 1 if args.accum_adaptive else 0)
         opushed, done, o_unique, o_time = 0, 0, 0, 0.0
         mismatches, compared = 0, 0
@@ -704,7 +747,7 @@ def run_point(args, env, cfg, window, raws, n_pre):
             if t in stats:
                 compared += 1
                 same = tuple(int(x) for x in ost) == stats[t].as_tuple()
-                if args.accum:                                  # the accumulator's groups as well
+                if args.accum and not args.many:                # the accumulator's groups as well
                     same = same and sim.accum_last[:2] == (stats[t].n_pending, stats[t].flushed)
                 mismatches += not same
             if t >= min(warmup, 2):                             # skip the cold start like the GPU leg

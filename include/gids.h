@@ -287,11 +287,18 @@ int gids_gather_static(gids_cache* cache, const void* ids_dev, uint64_t n, void*
  *   push_ids_dev   NULL (no step pushes), or k pointers, NULL where a step
  *                  pushes nothing; push_n the lists' lengths
  *   unique_dev     NULL, or k pointers (NULL entries allowed)
+ *   push_stream    the stream in whose order the pushed ID lists are ready (and
+ *                  may be reused afterwards), as for gids_window_push; `stream`
+ *                  the one in whose order the outputs are complete, as for
+ *                  gids_gather.  They may be the same; with two, the
+ *                  classification of one call overlaps the row movement of the
+ *                  call before
  * Needs a cache created with accum_threshold > 0 (it owns the group lists);
  * errors as gids_window_push / gids_gather; a device-found error in step i
  * leaves steps i.. undone and is reported in their gids_stats.status. */
 int gids_gather_many(gids_cache* cache, uint32_t k, const void* const* push_ids_dev, const uint64_t* push_n,
-                     void* const* out_dev, const uint64_t* out_capacity_rows, void* const* unique_dev, void* stream);
+                     void* const* out_dev, const uint64_t* out_capacity_rows, void* const* unique_dev, void* push_stream,
+                     void* stream);
 
 /* The accumulator's forced launch (Section 3.2: accesses merged over several
  * minibatches go out in one launch; this is the launch without waiting for

@@ -63,7 +63,7 @@ def lib() -> C.CDLL:
         L.gids_window_push.argtypes = [vp, vp, u64, vp]
         L.gids_gather.argtypes = [vp, vp, u64, vp, u64, vp, vp, vp]
         L.gids_gather_static.argtypes = [vp, vp, u64, vp, u64, vp, vp]
-        L.gids_gather_many.argtypes = [vp, u32, C.POINTER(vp), C.POINTER(u64), C.POINTER(vp), C.POINTER(u64), C.POINTER(vp), vp]
+        L.gids_gather_many.argtypes = [vp, u32, C.POINTER(vp), C.POINTER(u64), C.POINTER(vp), C.POINTER(u64), C.POINTER(vp), vp, vp]
         L.gids_flush.argtypes = [vp, vp]
         L.gids_stats_read.argtypes = [vp, u64, C.POINTER(gids_stats)]
         L.gids_cache_gathers.restype = u64
@@ -169,7 +169,7 @@ def gids_gather_static(cache: int, ids_dev_ptr: int | None, n: int, out_dev_ptr:
 
 
 def gids_gather_many(cache: int, push_ids_dev_ptrs, push_n, out_dev_ptrs, out_capacity_rows, unique_dev_ptrs=None,
-                     stream: int = 0) -> None:
+                     push_stream: int = 0, stream: int = 0) -> None:
     """k steps (push one list or None, gather the window's head) in one call; sequences of k entries"""
     k = len(out_dev_ptrs)
     vp_k, u64_k = C.c_void_p * k, C.c_uint64 * k
@@ -177,7 +177,7 @@ def gids_gather_many(cache: int, push_ids_dev_ptrs, push_n, out_dev_ptrs, out_ca
     lens = None if push_ids_dev_ptrs is None else u64_k(*[int(x) for x in push_n])
     uniq = None if unique_dev_ptrs is None else vp_k(*unique_dev_ptrs)
     _check(lib().gids_gather_many(cache, k, pushes, lens, vp_k(*out_dev_ptrs), u64_k(*[int(x) for x in out_capacity_rows]),
-                                  uniq, stream))
+                                  uniq, push_stream, stream))
 
 
 def gids_flush(cache: int, stream: int = 0) -> None:

@@ -129,7 +129,7 @@ struct gids_cache {
                        bool no_alloc, hipStream_t s) = 0;
     virtual int flush(hipStream_t s) = 0;
     virtual int gather_many(uint32_t k, const void* const* push_ids, const uint64_t* push_n, void* const* outs,
-                            const uint64_t* caps, void* const* uniques, hipStream_t s) = 0;
+                            const uint64_t* caps, void* const* uniques, hipStream_t ps, hipStream_t s) = 0;
     virtual int snapshot(int64_t* tags, int64_t* stamps) = 0;
     virtual uint32_t window_count() const = 0;
 
@@ -748,7 +748,7 @@ struct CacheT final : gids_cache {
 
     // k steps, each "push one list (optional), gather the window's head", as one accumulator group.
     int gather_many(uint32_t k, const void* const* push_ids, const uint64_t* push_n, void* const* outs,
-                    const uint64_t* caps, void* const* uniques, hipStream_t s) override {
+                    const uint64_t* caps, void* const* uniques, hipStream_t ps, hipStream_t s) override {
         if (!threshold) return fail(GIDS_E_INVAL, "gids_gather_many: the cache was created without an accumulator (accum_threshold == 0)");
         if (k < 1 || k > (uint32_t)MANY_MAX) return fail(GIDS_E_INVAL, "gids_gather_many: k must be in [1, %d]", MANY_MAX);
         if (!outs || !caps) return fail(GIDS_E_INVAL, "gids_gather_many: out_dev / out_capacity_rows is NULL");
@@ -772,7 +772,7 @@ struct CacheT final : gids_cache {
             // large tables, high associativity: the same steps through the per-step kernels, still one group
             if (open_batches && (rc = flush(s))) return rc;
             for (uint32_t i = 0; i < k; i++) {
-                if (push_ids && push_ids[i] && (rc = push(push_ids[i], push_n[i], nullptr, s))) return rc;
+                if (push_ids && push_ids[i] && (rc = push(push_ids[i], push_n[i], nullptr, ps))) return rc;
                 group_override = i + 1 < k ? 1 : 2;           // no group closes inside the call, its last step closes it
                 rc = gather(nullptr, 0, outs[i], caps[i], uniques ? uniques[i] : nullptr, nullptr, false, s);
                 group_override = 0;
@@ -806,18 +806,21 @@ struct CacheT final : gids_cache {
             many_plan_cap = total_upper + total_upper / 2;
         }
         if ((rc = ensure_queue(total_upper))) return rc;
-        if ((rc = many_enqueue(k, push_ids, push_n, outs, caps, uniques, total_upper, longest, s))) sticky = rc;
+        if ((rc = many_enqueue(k, push_ids, push_n, outs, caps, uniques, total_upper, longest, ps, s))) sticky = rc;
         return rc;
     }
 
     int many_enqueue(uint32_t k, const void* const* push_ids, const uint64_t* push_n, void* const* outs,
-                     const uint64_t* caps, void* const* uniques, uint64_t total_upper, uint64_t longest, hipStream_t s) {
+                     const uint64_t* caps, void* const* uniques, uint64_t total_upper, uint64_t longest, hipStream_t ps,
+                     hipStream_t s) {
         int rc;
+        const bool any_push = push_ids != nullptr;
+        if (any_push && (rc = follow(ps))) return rc;
         if ((rc = follow(s))) return rc;
         hipStream_t m = s;
         if (pipelined) {
             m = meta;
-            if ((rc = edge(s, meta))) return rc;              // the caller's ID lists are ready in its stream's order
+            if (any_push && (rc = edge(ps, meta))) return rc; // the caller's ID lists are ready in the push stream's order
         }
         if (flush_recorded[group & 1]) HIP_TRY(hipStreamWaitEvent(m, ev_flush[group & 1], 0));
         ManyPushes<IdT> mp;
@@ -864,7 +867,7 @@ struct CacheT final : gids_cache {
         for (uint32_t i = 0; i < k; i++) ev_of[(seq + i) % STATS_RING] = r_last;
         if (pipelined) {
             HIP_TRY(hipEventRecord(ev_meta[r_last], meta));
-            if (n_push && (rc = edge(meta, s))) return rc;    // the caller may reuse its ID buffers in stream order
+            if (n_push && (rc = edge(meta, ps))) return rc;   // the caller may reuse its ID buffers in the push stream's order
         }
         open_upper = total_upper;
         open_batches = k;
@@ -1186,10 +1189,12 @@ int gids_cache_set_rows_per_line(gids_cache* cache, uint32_t rows) {
 }
 
 int gids_gather_many(gids_cache* cache, uint32_t k, const void* const* push_ids_dev, const uint64_t* push_n,
-                     void* const* out_dev, const uint64_t* out_capacity_rows, void* const* unique_dev, void* stream) {
+                     void* const* out_dev, const uint64_t* out_capacity_rows, void* const* unique_dev, void* push_stream,
+                     void* stream) {
     CHECK_CACHE(cache);
     if (push_ids_dev && !push_n) return fail(GIDS_E_INVAL, "gids_gather_many: push_n is NULL");
-    return cache->gather_many(k, push_ids_dev, push_n, out_dev, out_capacity_rows, unique_dev, static_cast<hipStream_t>(stream));
+    return cache->gather_many(k, push_ids_dev, push_n, out_dev, out_capacity_rows, unique_dev,
+                              static_cast<hipStream_t>(push_stream), static_cast<hipStream_t>(stream));
 }
 
 int gids_flush(gids_cache* cache, void* stream) {

@@ -24,6 +24,8 @@
 //                 kernel).  One thread per ID, the `ways` tags of a set read by
 //                 that thread (ways <= 16).  The last workgroup to finish
 //                 publishes the k records of counters.
+#include <cstdlib>
+
 #include "gather_dev.h"
 #include "gids_dev.h"
 
@@ -33,7 +35,7 @@ namespace {
 
 constexpr int DS_THREADS = 1024;
 constexpr int DS_WORDS = 8064;             // 64-bit words of the LDS bitmap (63 KiB): 516,096 rows
-constexpr int CM_THREADS = 256;
+constexpr int CM_THREADS = 1024;
 constexpr int CM_UNROLL = 4;               // list entries a thread fetches before it looks at any
 
 template <typename IdT>
@@ -92,6 +94,27 @@ __device__ __forceinline__ bool owns(const CacheView<IdT>& c, uint64_t set, uint
     return c.use32 ? (uint32_t)set % n_wg == me : set % n_wg == me;
 }
 
+// the list pushed in a step: one more buffered future use for each of its nodes that this workgroup owns
+template <typename IdT>
+__device__ __forceinline__ void raise_counters(const CacheView<IdT>& c, const IdT* __restrict__ P, uint32_t n_p,
+                                               uint32_t n_wg, uint32_t me) {
+    for (uint64_t base = threadIdx.x; base < n_p; base += (uint64_t)CM_THREADS * CM_UNROLL) {
+        uint64_t vv[CM_UNROLL];
+#pragma unroll
+        for (int u = 0; u < CM_UNROLL; u++) {
+            const uint64_t j = base + (uint64_t)u * CM_THREADS;
+            vv[u] = j < n_p ? (uint64_t)P[j] : ~0ull;
+        }
+#pragma unroll
+        for (int u = 0; u < CM_UNROLL; u++) {
+            if (vv[u] == ~0ull) continue;
+            uint64_t set, round;
+            set_and_round(c, vv[u], &set, &round);
+            if (owns(c, set, n_wg, me)) c.reuse[vv[u]] = (uint8_t)(c.reuse[vv[u]] + 1);
+        }
+    }
+}
+
 template <typename IdT, int WAYS>
 __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT> c, AccumView a, uint32_t group,
                                                                    ManySteps<IdT> m, uint64_t* __restrict__ plan_all,
@@ -104,6 +127,10 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
     const uint32_t stamp0 = ctl->stamp;
     // an error left by an earlier kernel (a pushed ID out of range): nothing runs, every record reports it
     uint32_t n_ok = ld_agent(&ctl->error) == 0 ? m.k : 0;
+    // Between the phases of a step only workgroup barriers: what a phase reads was written by this same
+    // workgroup (its sets' tags, stamps and miss masks, its nodes' counters, its own list operations), and a
+    // barrier orders memory within a workgroup.  Agent-wide visibility is needed once, before the ticket.
+    if (n_ok && m.pushed[0]) raise_counters(c, m.pushed[0], ctl->win_n[m.pushed_slot[0]], n_wg, me);
     for (uint32_t i = 0; i < n_ok; i++) {
         const int32_t stamp = (int32_t)(stamp0 + i);
         const IdT* __restrict__ U = m.head[i];
@@ -114,27 +141,8 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
         }
         uint64_t* __restrict__ plan = plan_all + m.plan_offset[i];
         if (tid < 5) cnt[tid] = 0;
-        // ---- the list pushed in this step: one more buffered future use for each of its nodes
-        if (m.pushed[i]) {
-            const IdT* __restrict__ P = m.pushed[i];
-            const uint32_t n_p = ctl->win_n[m.pushed_slot[i]];
-            for (uint64_t base = tid; base < n_p; base += (uint64_t)CM_THREADS * CM_UNROLL) {
-                uint64_t vv[CM_UNROLL];
-#pragma unroll
-                for (int u = 0; u < CM_UNROLL; u++) {
-                    const uint64_t j = base + (uint64_t)u * CM_THREADS;
-                    vv[u] = j < n_p ? (uint64_t)P[j] : ~0ull;
-                }
-#pragma unroll
-                for (int u = 0; u < CM_UNROLL; u++) {
-                    if (vv[u] == ~0ull) continue;
-                    uint64_t set, round;
-                    set_and_round(c, vv[u], &set, &round);
-                    if (owns(c, set, n_wg, me)) c.reuse[vv[u]] = (uint8_t)(c.reuse[vv[u]] + 1);
-                }
-            }
-        }
-        __threadfence();
+        // (the list pushed in this step has had its counters raised already: before the loop for step 0,
+        // in the previous step's last phase otherwise)
         __syncthreads();
         uint32_t hits = 0, cpus = 0, misses = 0, bypasses = 0, fills = 0;
         // ---- probe: every ID of this workgroup's sets against the state at the start of the minibatch
@@ -182,7 +190,6 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
             }
         }
         if (misses) atomicAdd(&cnt[2], misses);
-        __threadfence();
         __syncthreads();
         // ---- victims: the k-th miss of a set (ascending ID) takes the k-th evictable way in (stamp, way) order
         const bool any_miss = cnt[2] != 0;
@@ -248,7 +255,6 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
                     }
                 }
             }
-            __threadfence();
             __syncthreads();
         }
         // ---- publish tags and stamps, clear the miss mask, queue every row into the open group's lists
@@ -276,6 +282,9 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
             }
             queue_entry(c, a, group, mine, j, e, v, m.out[i], m.unique_out[i]);
         }
+        // the next step's pushed list enters the counters now: this step's victims are chosen, and the next
+        // step's probe, which must see them, waits behind a barrier
+        if (i + 1 < m.k && m.pushed[i + 1]) raise_counters(c, m.pushed[i + 1], ctl->win_n[m.pushed_slot[i + 1]], n_wg, me);
         // ---- this workgroup's share of the step's counters
 #pragma unroll
         for (int d = 32; d >= 1; d >>= 1) {
@@ -290,7 +299,6 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
             if (bypasses) atomicAdd(&cnt[3], bypasses);
             if (fills) atomicAdd(&cnt[4], fills);
         }
-        __threadfence();
         __syncthreads();
         if (tid < 5 && cnt[tid]) atomicAdd(&ctl->many_cnt[i][tid], cnt[tid]);
         __syncthreads();                                      // cnt is cleared at the top of the next step
@@ -345,8 +353,13 @@ void launch_dedup_small(const ManyPushes<IdT>& p, uint32_t n_lists, uint64_t n_r
 template <typename IdT>
 void launch_classify_many(const CacheView<IdT>& c, const AccumView& a, uint32_t group, const ManySteps<IdT>& m,
                           uint64_t longest, uint64_t* plan_all, StatsRec* ring, uint32_t ring_size, hipStream_t s) {
-    // about 64 of a list's entries per workgroup's own share; every workgroup reads every list
-    uint64_t g = (longest + 63) / 64;
+    // about 32 of a list's entries per workgroup's own share (GIDS_MANY_SHARE); every workgroup reads every list
+    static const uint64_t per_wg = [] {
+        const char* e = getenv("GIDS_MANY_SHARE");
+        const long v = e ? atol(e) : 32;
+        return (uint64_t)(v >= 1 ? v : 32);
+    }();
+    uint64_t g = (longest + per_wg - 1) / per_wg;
     if (g < 1) g = 1;
     if (g > 256) g = 256;
     if (g > c.n_sets) g = c.n_sets;                          // a workgroup without a set would only take a ticket

@@ -93,10 +93,12 @@ class GatherSession:
             del self._keep[:-64]
         return seq
 
-    def gather_many(self, pushes, outs, uniques=None, stream: torch.cuda.Stream | None = None) -> int:
+    def gather_many(self, pushes, outs, uniques=None, stream: torch.cuda.Stream | None = None,
+                    push_stream: torch.cuda.Stream | None = None) -> int:
         """k merged steps: pushes[i] (a device ID tensor or None) is pushed, then the window's head is gathered
         into outs[i] (and uniques[i]).  Returns the sequence number of step 0."""
         stream = (stream or torch.cuda.current_stream()).cuda_stream
+        push_stream = stream if push_stream is None else push_stream.cuda_stream
         seq = B.gids_cache_gathers(self.cache)
         any_push = any(p is not None for p in pushes)
         B.gids_gather_many(self.cache,
@@ -104,7 +106,8 @@ class GatherSession:
                            [None if p is None else (p.data_ptr() or 8) for p in pushes] if any_push else None,
                            [0 if p is None else p.numel() for p in pushes],
                            [o.data_ptr() for o in outs], [o.shape[0] for o in outs],
-                           None if uniques is None else [None if u is None else u.data_ptr() for u in uniques], stream)
+                           None if uniques is None else [None if u is None else u.data_ptr() for u in uniques],
+                           push_stream, stream)
         self._keep.extend(p for p in pushes if p is not None)
         if len(self._keep) > 96:
             del self._keep[:-96]

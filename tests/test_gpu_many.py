@@ -100,7 +100,7 @@ def run_many(gpu, oracle, feats, batches, *, id_dtype, lines, ways, window, ks, 
                     pushed += 1
                 else:
                     pushes.append(None)
-            seq0 = ses.gather_many(pushes, outs[t:t + k], uqs[t:t + k])
+            seq0 = ses.gather_many(pushes, outs[t:t + k], uqs[t:t + k], push_stream=push_stream)
             rows = 0
             for i in range(k):
                 seq_of[t + i] = seq0 + i
