@@ -172,14 +172,20 @@ def main() -> int:
         # the other configurations in the same line: the HBM-bound one, the mid-size one and the launch-bound one
         import copy
         result["other_workloads"] = {}
-        for name in ("resident", "medium", "tiny"):
+        # (tiny twice: call by call, and 32 iterations merged per call, Section 3.2's remedy for small minibatches)
+        for name in ("resident", "medium", "tiny", "tiny_merged"):
             if name == args.workload:
                 continue
             sub = copy.copy(args)
             sub.workload, sub.steps, sub.warmup, sub.cpu_seconds = name, min(args.steps, 20), min(args.warmup, 6), 4.0
+            if name == "tiny_merged":
+                sub.workload, sub.accum, sub.many, sub.steps, sub.warmup = "tiny", 1, 32, 320, 32
+            elif name == "tiny":
+                sub.steps, sub.warmup = 320, 32
             log(f"--- other workload: {name}")
             r = run_workload(sub, shared)
             result["other_workloads"][name] = {
+                "merged_calls_of": sub.many,
                 "value": r["value"], "unit": r["unit"], "ms_per_step": r["ms_per_step"], "steps": r["steps"],
                 "unique_ids_per_s": r["unique_ids_per_s"], "workload": r["config"]["workload"],
                 "per_step": r["per_step"], "weighted_roofline_frac": r["weighted_roofline"]["frac"],

@@ -246,6 +246,8 @@ struct CacheT final : gids_cache {
     FillOp* fills[2] = {nullptr, nullptr};
     CopyOp* rcopies[2] = {nullptr, nullptr};
     CopyOp* wcopies[2] = {nullptr, nullptr};
+    IdT* ustage[2] = {nullptr, nullptr};     // distinct-ID lists of the group's minibatches, until the group moves
+    UniqCopies uq = {};                      // ... and where the callers want them (open group)
 
     AccumView accum_view() const {
         AccumView a;
@@ -268,7 +270,7 @@ struct CacheT final : gids_cache {
         dev_free(blocksum); dev_free(blockoff); dev_free(hdr);
         for (int k = 0; k < 2; k++) { dev_free(ubuf[k]); dev_free(plan[k]); }
         dev_free(fillgrp); dev_free(hitgrp); dev_free(many_plan);
-        for (int k = 0; k < 2; k++) { dev_free(fills[k]); dev_free(rcopies[k]); dev_free(wcopies[k]); }
+        for (int k = 0; k < 2; k++) { dev_free(fills[k]); dev_free(rcopies[k]); dev_free(wcopies[k]); dev_free(ustage[k]); }
         for (auto& e : ev_flush) if (e) (void)hipEventDestroy(e);
         for (auto& s : slots) if (s.ids) (void)hipFree(s.ids);
         if (cpubuf_host) (void)hipHostFree(cpubuf_host);
@@ -386,18 +388,21 @@ struct CacheT final : gids_cache {
         for (int k = 0; k < 2; k++) {
             FillOp* nf = nullptr;
             CopyOp *nr = nullptr, *nw = nullptr;
+            IdT* nu = nullptr;
             int rc;
-            if ((rc = dev_alloc(&nf, want)) || (rc = dev_alloc(&nr, want)) || (rc = dev_alloc(&nw, want))) {
-                dev_free(nf); dev_free(nr); dev_free(nw);
+            if ((rc = dev_alloc(&nf, want)) || (rc = dev_alloc(&nr, want)) || (rc = dev_alloc(&nw, want)) ||
+                (rc = dev_alloc(&nu, want))) {
+                dev_free(nf); dev_free(nr); dev_free(nw); dev_free(nu);
                 return rc;
             }
             if (queue_cap) {
                 HIP_TRY(hipMemcpy(nf, fills[k], queue_cap * sizeof(FillOp), hipMemcpyDeviceToDevice));
                 HIP_TRY(hipMemcpy(nr, rcopies[k], queue_cap * sizeof(CopyOp), hipMemcpyDeviceToDevice));
                 HIP_TRY(hipMemcpy(nw, wcopies[k], queue_cap * sizeof(CopyOp), hipMemcpyDeviceToDevice));
+                HIP_TRY(hipMemcpy(nu, ustage[k], queue_cap * sizeof(IdT), hipMemcpyDeviceToDevice));
             }
-            dev_free(fills[k]); dev_free(rcopies[k]); dev_free(wcopies[k]);
-            fills[k] = nf; rcopies[k] = nr; wcopies[k] = nw;
+            dev_free(fills[k]); dev_free(rcopies[k]); dev_free(wcopies[k]); dev_free(ustage[k]);
+            fills[k] = nf; rcopies[k] = nr; wcopies[k] = nw; ustage[k] = nu;
         }
         queue_cap = want;
         return GIDS_OK;
@@ -661,14 +666,23 @@ struct CacheT final : gids_cache {
         }
         const CacheView<IdT> c = view();
         if ((rc = mark_phase(r, 1, m))) return rc;
-        const int accum_flags = threshold ? 4 | (closes ? 1 : 0) | (opens ? 2 : 0) : 0;
+        const int accum_flags = threshold ? 4 | (closes ? 1 : 0) | (opens ? 2 : 0) | (int)((group & 1) << 3) | (int)(open_batches << 8) : 0;
+        // with the accumulator the distinct-ID list is staged in the group's buffer (this stream may run ahead of
+        // the caller's) and copied to the caller's buffer when the group moves
+        IdT* unique_to = static_cast<IdT*>(unique);
+        if (threshold) {
+            uq.dst[open_batches] = unique;
+            uq.src_entry[open_batches] = open_upper;
+            uq.n = open_batches + 1;
+            unique_to = unique ? ustage[group & 1] + open_upper : nullptr;
+        }
         launch_probe<IdT>(c, U, n_u, n_upper, out_cap, head_list, b.pl, m);
         launch_victim<IdT>(c, U, n_u, n_upper, b.pl, m);
         // commit, queueing and counters: one launch, or (GIDS_FUSE without bit 0) a kernel each
         const bool settle = (fuse & 1) != 0;
         if (settle) {
             launch_settle<IdT>(c, accum_view(), group, accum_flags, U, n_u, n_upper, b.pl, b.hd, static_cast<char*>(out),
-                               static_cast<IdT*>(unique), ring_dev + r, seq, m);
+                               unique_to, ring_dev + r, seq, m);
         } else {
             launch_commit<IdT>(c, U, n_u, n_upper, b.pl, b.hd, m);
         }
@@ -687,8 +701,7 @@ struct CacheT final : gids_cache {
             // nothing moves yet: the minibatch's rows join the open group's lists (on the metadata stream, so
             // that the next minibatch is classified while an earlier group is still moving)
             if (!settle) {
-                launch_queue<IdT>(c, accum_view(), group, U, b.hd, n_upper, b.pl, static_cast<char*>(out),
-                                  static_cast<IdT*>(unique), m);
+                launch_queue<IdT>(c, accum_view(), group, U, b.hd, n_upper, b.pl, static_cast<char*>(out), unique_to, m);
                 launch_finalize(ctl, ring_dev + r, seq, n_u, accum_flags, m);
             }
             if ((rc = mark_phase(r, 2, m))) return rc;
@@ -718,7 +731,8 @@ struct CacheT final : gids_cache {
     int close_group(hipStream_t s, hipEvent_t after) {
         const uint32_t par = group & 1;
         if (after) HIP_TRY(hipStreamWaitEvent(s, after, 0));
-        launch_group_move<IdT>(view(), accum_view(), par, open_upper, move_blocks, link_blocks, s);
+        launch_group_move<IdT>(view(), accum_view(), par, open_upper, move_blocks, link_blocks, uq, ustage[par], s);
+        uq.n = 0;
         HIP_TRY(hipGetLastError());
         HIP_TRY(hipEventRecord(ev_flush[par], s));
         flush_recorded[par] = true;
@@ -852,7 +866,9 @@ struct CacheT final : gids_cache {
             ms.plan_offset[i] = off;
             off += std::min<uint64_t>(n_raw, store->n_rows);
             ms.out[i] = static_cast<char*>(outs[i]);
-            ms.unique_out[i] = uniques ? static_cast<IdT*>(uniques[i]) : nullptr;
+            uq.dst[i] = uniques ? uniques[i] : nullptr;       // staged, and copied out when the group moves
+            uq.src_entry[i] = ms.plan_offset[i];
+            ms.unique_out[i] = uq.dst[i] ? ustage[group & 1] + ms.plan_offset[i] : nullptr;
             const int r = (int)((seq + i) % STATS_RING);
             raw_of[r] = (uint32_t)n_raw;
             prof_valid[r] = false;
@@ -871,6 +887,7 @@ struct CacheT final : gids_cache {
         }
         open_upper = total_upper;
         open_batches = k;
+        uq.n = k;
         seq += k;
         if ((rc = close_group(s, pipelined ? ev_meta[r_last] : nullptr))) return rc;
         HIP_TRY(hipEventRecord(events[r_last], s));

@@ -108,8 +108,9 @@ __device__ __forceinline__ uint32_t ld_agent(const uint32_t* p) {
 }
 
 // The counters of one gather go to its record in host-visible memory, the minibatch index advances.
-// accum: 0 = no accumulator; otherwise bit 0 = this gather closes its group, bit 1 = it opened the group.
-// One thread, after every other write of the gather.
+// accum: 0 = no accumulator; otherwise bit 0 = this gather closes its group, bit 1 = it opened the group, bit 3
+// = the group's parity, bits 8.. = the gather's position in its group.  One thread, after every other write of
+// the gather.
 __device__ __forceinline__ void publish_stats(Ctl* ctl, StatsRec* rec, uint64_t seq, uint32_t n_u, int accum) {
     const uint32_t err = ld_agent(&ctl->error);          // (another workgroup of the same launch may have set it)
     const uint32_t n = err ? 0 : n_u;
@@ -125,6 +126,7 @@ __device__ __forceinline__ void publish_stats(Ctl* ctl, StatsRec* rec, uint64_t 
         const bool closes = (accum & 1) != 0, opens = (accum & 2) != 0;
         queued = closes ? 0u : (opens ? 0u : ctl->q_rows) + n;
         ctl->q_rows = queued;
+        ctl->grp_nu[(accum >> 3) & 1][(accum >> 8) % MANY_MAX] = n;   // for the copy of its distinct-ID list
         flushed = closes ? 1 : 0;
     }
     rec->n_pending = queued;

@@ -40,6 +40,7 @@ struct Ctl {
     uint32_t q_rcopy[2];    // hits whose line already holds its bytes
     uint32_t q_wcopy[2];    // copies that must follow the link rows: hits on lines filled in the same group, ...
     uint32_t q_chunk[2];    // work counter of the group mover's link half
+    uint32_t grp_nu[2][MANY_MAX];   // distinct count of each minibatch of a group, in the group's order
     uint32_t many_cnt[MANY_MAX][5];     // per step of a merged call: hits, CPU-buffer hits, misses, bypasses, line fills
     uint32_t win_n[MAX_WINDOW_SLOTS];   // distinct count of each buffered list
 };
@@ -228,9 +229,17 @@ template <typename IdT>
 void launch_classify_many(const CacheView<IdT>& c, const AccumView& a, uint32_t group, const ManySteps<IdT>& m,
                           uint64_t longest, uint64_t* plan_all, StatsRec* ring, uint32_t ring_size, hipStream_t s);
 
+// The distinct-ID lists of a group's minibatches wait in a staging buffer of the group (they are produced on
+// the stream that classifies) and reach the callers' buffers with the rows, on the stream the callers gave.
+struct UniqCopies {
+    void* dst[MANY_MAX];            // caller's unique_dev of the i-th minibatch of the group, or nullptr
+    uint64_t src_entry[MANY_MAX];   // where its list starts in the staging buffer (entries)
+    uint32_t n;                     // minibatches in the group
+};
+
 template <typename IdT>
 void launch_group_move(const CacheView<IdT>& c, const AccumView& a, uint32_t parity, uint64_t rows_upper,
-                       int hbm_blocks_max, int link_blocks_max, hipStream_t s);
+                       int hbm_blocks_max, int link_blocks_max, const UniqCopies& u, const IdT* stage, hipStream_t s);
 
 uint64_t sampler_key(uint64_t seed, uint64_t tag);
 uint64_t sampler_mix(uint64_t z);

@@ -329,6 +329,7 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
         rec->n_pending = closes ? 0u : queued;
         rec->flushed = closes ? 1 : 0;
         rec->status = ran ? 0 : -(int32_t)err;
+        ctl->grp_nu[group & 1u][i] = n;
         for (int x = 0; x < 5; x++) ctl->many_cnt[i][x] = 0;
     }
     ctl->q_rows = 0;

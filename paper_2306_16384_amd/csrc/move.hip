@@ -322,6 +322,18 @@ __global__ __launch_bounds__(MV_THREADS) void group_copy_kernel(Ctl* ctl, const 
     }
 }
 
+// third launch (when a caller asked for distinct-ID lists): one workgroup per minibatch of the group copies its
+// list from the group's staging buffer to the caller's buffer
+template <typename IdT>
+__global__ __launch_bounds__(MV_THREADS) void group_uniq_kernel(const Ctl* ctl, uint32_t par, UniqCopies u,
+                                                                const IdT* __restrict__ stage) {
+    IdT* __restrict__ dst = static_cast<IdT*>(u.dst[blockIdx.x]);
+    if (!dst) return;
+    const IdT* __restrict__ src = stage + u.src_entry[blockIdx.x];
+    const uint32_t n = ctl->grp_nu[par][blockIdx.x];
+    for (uint32_t j = threadIdx.x; j < n; j += MV_THREADS) dst[j] = src[j];
+}
+
 // Link calibration: `n` rows of the host table, picked by a hash of their index, copied to a scratch
 // buffer with the link half's shape (persistent workgroups, one wavefront per row).
 template <int G>
@@ -419,7 +431,7 @@ void launch_settle(const CacheView<IdT>& c, const AccumView& a, uint32_t group, 
 
 template <typename IdT>
 void launch_group_move(const CacheView<IdT>& c, const AccumView& a, uint32_t par, uint64_t rows_upper,
-                       int hbm_blocks_max, int link_blocks_max, hipStream_t s) {
+                       int hbm_blocks_max, int link_blocks_max, const UniqCopies& u, const IdT* stage, hipStream_t s) {
     const int g = lanes_per_row(c.row_bytes);
     if (rows_upper < 1) rows_upper = 1;
     uint32_t link_ch = 64;
@@ -432,6 +444,9 @@ void launch_group_move(const CacheView<IdT>& c, const AccumView& a, uint32_t par
     const uint32_t copy_blocks = row_grid(rows_upper, g, 256);
     GIDS_DISPATCH_G(g, hipLaunchKernelGGL((group_copy_kernel<G>), dim3(copy_blocks), dim3(MV_THREADS), 0, s, c.ctl,
                                           a.wcopies[par], c.row_bytes, par));
+    bool any = false;
+    for (uint32_t i = 0; i < u.n; i++) any |= u.dst[i] != nullptr;
+    if (any) hipLaunchKernelGGL(group_uniq_kernel<IdT>, dim3(u.n), dim3(MV_THREADS), 0, s, c.ctl, par, u, stage);
 }
 
 void launch_calibrate(const char* store, uint64_t store_rows, uint32_t row_bytes, char* out, uint32_t n,
@@ -455,7 +470,7 @@ void launch_finalize(Ctl* ctl, StatsRec* rec, uint64_t seq, const uint32_t* n_u,
                                      const uint32_t*, uint64_t, const uint64_t*, BatchHdr*, char*, IdT*, StatsRec*, \
                                      uint64_t, hipStream_t);                                                        \
     template void launch_group_move<IdT>(const CacheView<IdT>&, const AccumView&, uint32_t, uint64_t, int, int,     \
-                                         hipStream_t);
+                                         const UniqCopies&, const IdT*, hipStream_t);
 GIDS_INSTANTIATE(int32_t)
 GIDS_INSTANTIATE(int64_t)
 

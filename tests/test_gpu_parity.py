@@ -310,6 +310,51 @@ def test_accumulator_lines_reused_inside_a_group(gpu, oracle_mod, pipeline):
                  label=f"accum-reuse/W2/thr{threshold}/pipe{pipeline}")
 
 
+def test_accumulator_outputs_follow_the_callers_stream(gpu, oracle_mod):
+    """With the library's internal stream on, an accumulating cache classifies ahead of the caller's stream.
+    Whatever the caller still has queued on its stream for an output buffer (here: a slow kernel, then a fill
+    of the distinct-ID buffer and of the rows) must happen before the library writes that buffer."""
+    import os
+    torch, gids, GatherSession = gpu
+    rng = np.random.default_rng(99)
+    n, R = 20_000, 256
+    feats = rand_feats(rng, n, R)
+    lists = zipf_batches(rng, n, 6, 3000, a=1.15)
+    old = os.environ.get("GIDS_PIPELINE")
+    os.environ["GIDS_PIPELINE"] = "1"
+    try:
+        ses = GatherSession(n, R, np.int64, 1024, 8, R, 2, 5000)
+    finally:
+        if old is None:
+            del os.environ["GIDS_PIPELINE"]
+        else:
+            os.environ["GIDS_PIPELINE"] = old
+    with ses:
+        ses.store_view()[:] = feats
+        dev = [ses.to_device(b) for b in lists]
+        a = torch.randn(4096, 4096, device="cuda")
+        ps = torch.cuda.Stream()
+        got, pushed = [], 0
+        for t, raw in enumerate(lists):
+            while pushed < len(lists) and pushed <= t + 2:
+                ses.push(dev[pushed], stream=ps)
+                pushed += 1
+            out = torch.empty((len(raw), R), dtype=torch.uint8, device="cuda")
+            uq = torch.empty(len(raw), dtype=torch.int64, device="cuda")
+            for _ in range(6):
+                a = a @ a * 1e-4                                # a few milliseconds on the caller's stream ...
+            out.fill_(0xA5)                                     # ... behind which the buffers are prepared
+            uq.fill_(-7)
+            ses.gather(None, out, uq)
+            got.append((out, uq))
+        ses.flush()
+        torch.cuda.synchronize()
+        for (out, uq), raw in zip(got, lists):
+            u = np.unique(raw)
+            assert np.array_equal(uq[:len(u)].cpu().numpy(), u)
+            assert np.array_equal(out[:len(u)].cpu().numpy(), feats[u])
+
+
 # ------------------------------------------------------------------- errors
 
 def test_device_found_errors(gpu, oracle_mod):
