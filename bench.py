@@ -128,7 +128,7 @@ def main() -> int:
                          "(the last run is the one reported; the others are logged)")
     ap.add_argument("--others", default="auto", choices=["auto", "on", "off"],
                     help="append the other configurations (cache-resident, medium, tiny; 20 steps each) to the same JSON "
-                         "line as `other_workloads`; auto: with the default command only")
+                         "line as `other_workloads`; auto: only when no option besides --gpus / --steps / --warmup is given")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     args = ap.parse_args()
@@ -165,10 +165,10 @@ def main() -> int:
     result = run_workload(args, shared)
     if result is None:                                          # a sweep printed its own object
         return 0
-    plain = not (args.gpu_sampler or args.layerwise or args.consumer_ms or args.dim or args.rows_per_line > 1 or
-                 args.cache_lines or args.accum or args.nodes or args.window >= 0 or args.policy != "lru" or
-                 args.hot_by != "indegree" or args.pass_ids or args.one_stream or args.repeat > 1)
-    if args.others == "on" or (args.others == "auto" and plain and args.workload == "large"):
+    # auto: only for the bare command (no option besides --gpus / --steps / --warmup), i.e. the default benchmark line
+    given = {a.split("=")[0] for a in sys.argv[1:] if a.startswith("--")}
+    plain = given <= {"--gpus", "--steps", "--warmup"}
+    if args.others == "on" or (args.others == "auto" and plain):
         # the other configurations in the same line: the HBM-bound one, the mid-size one and the launch-bound one
         import copy
         result["other_workloads"] = {}

@@ -197,8 +197,7 @@ struct gids_cache {
             return;
         }
     }
-    int fuse = 3;               // GIDS_FUSE: bit 0 = commit + queueing + counters in one launch, bit 1 = the bitmap count
-                                // inside the mark kernel (small tables)
+    int fuse = 1;               // GIDS_FUSE=0: commit, queueing and counters as a kernel each; no merged kernels
     int move_blocks = 1 << 20;  // most workgroups the row mover uses for rows that stay in HBM
     int link_blocks = 48;       // ... for rows that cross the host link (persistent)
     bool wide_index = false;    // GIDS_WIDE_INDEX=1: 64-bit set arithmetic even where 32 bits would do (for tests)
@@ -349,7 +348,7 @@ struct CacheT final : gids_cache {
         // them is gathered: that many slots more, so that none of them lands on a list still to be gathered)
         slots.resize(window + 2 + (threshold ? MANY_MAX : 0));
         if (const char* env = getenv("GIDS_WIDE_INDEX")) wide_index = atoi(env) != 0;
-        if (const char* env = getenv("GIDS_FUSE")) fuse = atoi(env) & 3;
+        if (const char* env = getenv("GIDS_FUSE")) fuse = atoi(env) & 1;
         if (const char* env = getenv("GIDS_MOVE_BLOCKS")) {
             const int b = atoi(env);
             if (b >= 1 && b <= (1 << 20)) move_blocks = b;
@@ -500,13 +499,10 @@ struct CacheT final : gids_cache {
     // ascending distinct IDs of ids[0..n) -> dst; count -> *n_out (device)
     void dedup(const IdT* ids, uint64_t n, IdT* dst, uint32_t* n_out, uint8_t* reuse_inc, bool keep_bitmap,
                hipStream_t s, const uint32_t* n_dev = nullptr) {
-        // a bitmap that one block scans needs no separate count: that block's total is the distinct count;
-        // one of a few dozen blocks is counted by the mark kernel's last workgroup
-        const uint32_t nb = scan_blocks(n_words);
-        const bool solo = nb == 1;
-        const bool ride = !solo && (fuse & 2) && nb <= mark_count_max_blocks();
-        launch_mark<IdT>(ids, n, n_dev, store->n_rows, bitmap, ctl, s, ride ? nb : 0, blockoff, n_out);
-        if (!solo && !ride) launch_count(bitmap, n_words, blocksum, blockoff, ctl, n_out, s);
+        launch_mark<IdT>(ids, n, n_dev, store->n_rows, bitmap, ctl, s);
+        // a bitmap that one block scans needs no separate count: that block's total is the distinct count
+        const bool solo = scan_blocks(n_words) == 1;
+        if (!solo) launch_count(bitmap, n_words, blocksum, blockoff, ctl, n_out, s);
         launch_emit<IdT>(bitmap, n_words, store->n_rows, blockoff, dst, reuse_inc, keep_bitmap ? wrank : nullptr,
                          !keep_bitmap, ctl, solo ? n_out : nullptr, s);
     }

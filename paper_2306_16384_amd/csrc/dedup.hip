@@ -30,9 +30,7 @@ constexpr int WORDS_PER_BLOCK = DD_THREADS * WORDS_PER_THREAD;
 template <typename IdT>
 __global__ __launch_bounds__(DD_THREADS) void mark_kernel(const IdT* __restrict__ ids, uint64_t n,
                                                           const uint32_t* __restrict__ n_dev, uint64_t n_rows,
-                                                          uint64_t* __restrict__ bitmap, Ctl* ctl, uint32_t count_blocks,
-                                                          uint64_t n_words, uint32_t* __restrict__ blockoff,
-                                                          uint32_t* __restrict__ n_out) {
+                                                          uint64_t* __restrict__ bitmap, Ctl* ctl) {
     __shared__ unsigned long long tab[TAB_SLOTS];
     if (n_dev) n = *n_dev;                // the list's length is only known on the device (n was its bound)
     __shared__ uint32_t fresh_total;
@@ -76,43 +74,6 @@ __global__ __launch_bounds__(DD_THREADS) void mark_kernel(const IdT* __restrict_
         }
     }
     if (bad) atomicCAS(&ctl->error, 0u, 3u /* -GIDS_E_RANGE */);
-    // Small tables (count_blocks > 0): the count step rides along.  The last workgroup to finish marking
-    // sums the bitmap per scan block, one wavefront per block, and writes the offsets and the distinct count
-    // that the count kernel would have written.
-    if (count_blocks == 0) return;
-    __shared__ uint32_t is_last;
-    __shared__ uint32_t sums[64];
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        __threadfence();
-        is_last = atomicAdd(&ctl->ticket, 1u) == gridDim.x - 1;
-    }
-    __syncthreads();
-    if (!is_last) return;
-    __threadfence();                      // the other workgroups' bits, not what this one's look-ups cached
-    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    for (uint32_t i = wave; i < count_blocks; i += DD_THREADS / 64) {
-        const uint64_t w0 = (uint64_t)i * WORDS_PER_BLOCK;
-        uint32_t c = 0;
-#pragma unroll
-        for (int k = 0; k < WORDS_PER_BLOCK / 64; k++) {
-            const uint64_t w = w0 + (uint64_t)k * 64 + lane;
-            if (w < n_words) c += __popcll(bitmap[w]);
-        }
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) c += __shfl_down(c, d);
-        if (lane == 0) sums[i] = c;
-    }
-    __syncthreads();
-    if (wave == 0) {
-        const uint32_t x = lane < count_blocks ? sums[lane] : 0u;
-        const uint32_t incl = wave_inclusive_scan(x);
-        if (lane < count_blocks) blockoff[lane] = incl - x;
-        if (lane == 63) {
-            *n_out = incl;
-            ctl->ticket = 0;
-        }
-    }
 }
 
 __global__ __launch_bounds__(DD_THREADS) void count_kernel(const uint64_t* __restrict__ bitmap, uint64_t n_words,
@@ -267,18 +228,14 @@ inline uint32_t blocks_for(uint64_t items, uint64_t per_block, uint32_t cap) {
 
 }  // namespace
 
-uint32_t mark_count_max_blocks() { return 64; }
-
 uint32_t scan_blocks(uint64_t n_words) { return (uint32_t)((n_words + WORDS_PER_BLOCK - 1) / WORDS_PER_BLOCK); }
 
 template <typename IdT>
 void launch_mark(const IdT* ids, uint64_t n, const uint32_t* n_dev, uint64_t n_rows, uint64_t* bitmap, Ctl* ctl,
-                 hipStream_t s, uint32_t count_blocks, uint32_t* blockoff, uint32_t* n_out) {
-    if (n == 0 && count_blocks == 0) return;
-    // with the count riding along every workgroup ends with an atomic on one counter: fewer, longer workgroups
-    const uint32_t grid = blocks_for(n, (uint64_t)DD_THREADS * MARK_ITEMS, count_blocks ? 256 : 2048);
-    hipLaunchKernelGGL(mark_kernel<IdT>, dim3(grid), dim3(DD_THREADS), 0, s, ids, n, n_dev, n_rows, bitmap, ctl,
-                       count_blocks, (n_rows + 63) / 64, blockoff, n_out);
+                 hipStream_t s) {
+    if (n == 0) return;
+    const uint32_t grid = blocks_for(n, (uint64_t)DD_THREADS * MARK_ITEMS, 2048);
+    hipLaunchKernelGGL(mark_kernel<IdT>, dim3(grid), dim3(DD_THREADS), 0, s, ids, n, n_dev, n_rows, bitmap, ctl);
 }
 
 void launch_count(const uint64_t* bitmap, uint64_t n_words, uint32_t* blocksum, uint32_t* blockoff, Ctl* ctl,
@@ -325,8 +282,7 @@ void launch_fill_i64(int64_t* p, uint64_t n, int64_t value, hipStream_t s) {
 }
 
 #define GIDS_INSTANTIATE(IdT)                                                                                      \
-    template void launch_mark<IdT>(const IdT*, uint64_t, const uint32_t*, uint64_t, uint64_t*, Ctl*, hipStream_t,  \
-                                   uint32_t, uint32_t*, uint32_t*);                                                \
+    template void launch_mark<IdT>(const IdT*, uint64_t, const uint32_t*, uint64_t, uint64_t*, Ctl*, hipStream_t); \
     template void launch_emit<IdT>(uint64_t*, uint64_t, uint64_t, const uint32_t*, IdT*, uint8_t*, uint32_t*, bool, \
                                    Ctl*, uint32_t*, hipStream_t);                                                  \
     template void launch_verify<IdT>(const IdT*, const IdT*, const uint32_t*, Ctl*, uint64_t, hipStream_t);        \

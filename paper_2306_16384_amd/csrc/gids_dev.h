@@ -141,12 +141,9 @@ struct SamplerState {
 
 // ---- launchers (defined in the .hip files) ---------------------------------
 
-// count_blocks > 0 (at most mark_count_max_blocks()): the mark kernel's last workgroup also does the work of
-// launch_count for a bitmap of that many scan blocks (offsets to blockoff, distinct count to *n_out)
-uint32_t mark_count_max_blocks();
 template <typename IdT>
 void launch_mark(const IdT* ids, uint64_t n, const uint32_t* n_dev, uint64_t n_rows, uint64_t* bitmap, Ctl* ctl,
-                 hipStream_t s, uint32_t count_blocks = 0, uint32_t* blockoff = nullptr, uint32_t* n_out = nullptr);
+                 hipStream_t s);
 
 void launch_count(const uint64_t* bitmap, uint64_t n_words, uint32_t* blocksum, uint32_t* blockoff, Ctl* ctl,
                   uint32_t* n_out, hipStream_t s);

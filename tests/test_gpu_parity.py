@@ -26,7 +26,7 @@ def run_case(gpu, oracle, feats, batches, *, id_dtype, lines, ways, line_bytes, 
              pipeline=None, push_depth0=False, wide_index=False, rows_per_line=1, accum_mode=0, fused=None):
     """Feeds the same raw ID lists to both implementations, protocol: keep window + 1 lists buffered.
     pipeline: "0" / "1" forces the library's internal stream off / on for this cache (GIDS_PIPELINE);
-    fused: True / False switches the fused kernels (settle; mark + count) on / off (GIDS_FUSE);
+    fused: True / False switches the settle kernel (commit + queueing + counters) on / off (GIDS_FUSE);
     push_depth0: at window depth 0, push every list just before its gather."""
     torch, gids, GatherSession = gpu
     n_rows = feats.shape[0]
@@ -60,7 +60,7 @@ def run_case(gpu, oracle, feats, batches, *, id_dtype, lines, ways, line_bytes, 
     if wide_index:
         knobs["GIDS_WIDE_INDEX"] = "1"                       # the arithmetic of stores with 2^32 rows and more
     if fused is not None:
-        knobs["GIDS_FUSE"] = "3" if fused else "0"          # commit + queueing + counters (and mark + count) fused, or a kernel each
+        knobs["GIDS_FUSE"] = "1" if fused else "0"          # commit + queueing + counters in one launch, or a kernel each
     old_env = {k: os.environ.get(k) for k in knobs}
     os.environ.update(knobs)
     try:
