@@ -22,14 +22,15 @@
  *     Calls that take a stream only enqueue work and return; they never block
  *     on the device unless an internal buffer has to grow (avoid that with
  *     gids_cache_reserve).  Inputs are read, and outputs are complete, in the
- *     order of the stream given to the call.  With accum_threshold == 0 the
+ *     order of the stream given to the call.  For caches of 32 MiB and more the
  *     library runs dedup, probe and victim selection on a stream of its own
  *     and orders it against the caller's streams with events, so that the
  *     classification of one minibatch overlaps the row movement of the
- *     previous one; to let it overlap, give gids_window_push a different stream
- *     (the one the sampler fills ID lists on) than gids_gather (the one that
- *     consumes the rows).  All gathers of one cache use one stream, all pushes
- *     one stream (the same or another).
+ *     previous one (of the previous group, with the accumulator); to let it
+ *     overlap, give gids_window_push a different stream (the one the sampler
+ *     fills ID lists on) than gids_gather (the one that consumes the rows).
+ *     All gathers of one cache use one stream, all pushes one stream (the same
+ *     or another).
  *   - Threads: calls on one cache (or one graph) must not overlap in time;
  *     the caller serialises them.  Different caches, graphs and stores may be
  *     used from different threads at once, and several caches may share one
@@ -277,12 +278,13 @@ int gids_gather_static(gids_cache* cache, const void* ids_dev, uint64_t n, void*
  * closed first, the call's own group closes with its last step (gids_stats of
  * step i: n_pending = rows of steps 0..i, flushed = 0; the last step: 0 and 1).
  * Every output of the call is complete, in stream order, when the call's work
- * ends.  On tables of up to 516,096 rows with ways <= 16 and one row per line
- * the k steps take four launches in all, however large k: one that deduplicates
+ * ends.  For lists of up to 8,192 raw IDs over a table whose bitmap fits a
+ * workgroup's LDS (1.3 M rows on gfx950), with ways <= 16 and one row per line,
+ * the k steps take five launches in all, however large k: one that deduplicates
  * the pushed lists (a workgroup and an LDS bitmap each), one that classifies
  * the k minibatches one after the other, each workgroup for its own share of
- * the cache sets, and the group mover's two.  Other caches take the per-step
- * kernels, still as one group.
+ * the cache sets, and the group mover's three.  Other caches and longer lists
+ * take the per-step kernels, still as one group.
  *   k              1 .. 32 (GIDS_ACCUM_MAX_MERGE)
  *   push_ids_dev   NULL (no step pushes), or k pointers, NULL where a step
  *                  pushes nothing; push_n the lists' lengths

@@ -197,6 +197,7 @@ struct gids_cache {
             return;
         }
     }
+    uint64_t many_list_max = 8192;  // merged kernels for lists up to this many raw IDs (GIDS_MANY_LIST_MAX)
     int fuse = 1;               // GIDS_FUSE=0: commit, queueing and counters as a kernel each; no merged kernels
     int move_blocks = 1 << 20;  // most workgroups the row mover uses for rows that stay in HBM
     int link_blocks = 48;       // ... for rows that cross the host link (persistent)
@@ -349,6 +350,7 @@ struct CacheT final : gids_cache {
         slots.resize(window + 2 + (threshold ? MANY_MAX : 0));
         if (const char* env = getenv("GIDS_WIDE_INDEX")) wide_index = atoi(env) != 0;
         if (const char* env = getenv("GIDS_FUSE")) fuse = atoi(env) & 1;
+        if (const char* env = getenv("GIDS_MANY_LIST_MAX")) many_list_max = (uint64_t)std::max(0ll, atoll(env));
         if (const char* env = getenv("GIDS_MOVE_BLOCKS")) {
             const int b = atoi(env);
             if (b >= 1 && b <= (1 << 20)) move_blocks = b;
@@ -776,7 +778,23 @@ struct CacheT final : gids_cache {
             cnt--;
             if (!outs[i] && caps[i]) return fail(GIDS_E_INVAL, "gids_gather_many: out_dev[%u] is NULL", i);
         }
-        const bool fast = store->n_rows <= many_max_rows() && ways <= many_max_ways() && rows_per_line == 1 && (fuse & 1);
+        // The merged kernels pay for short lists: every workgroup of the classification reads every list, which
+        // for lists of tens of thousands of IDs costs more than the launches it saves (Medium: 0.45 ms per step
+        // merged, 0.42 ms through the per-step kernels as one group).
+        uint64_t longest_raw = 0;
+        {
+            uint32_t h = head, c2 = count;
+            std::vector<uint64_t> len(slots.size());
+            for (size_t q = 0; q < slots.size(); q++) len[q] = slots[q].n_raw;
+            for (uint32_t i = 0; i < k; i++) {
+                if (push_ids && push_ids[i]) { len[(h + c2) % slots.size()] = push_n[i]; c2++; }
+                longest_raw = std::max(longest_raw, len[h]);
+                h = (h + 1) % slots.size();
+                c2--;
+            }
+        }
+        const bool fast = store->n_rows <= many_max_rows() && ways <= many_max_ways() && rows_per_line == 1 &&
+                          (fuse & 1) && longest_raw <= many_list_max;
         int rc;
         if (!fast) {
             // large tables, high associativity: the same steps through the per-step kernels, still one group

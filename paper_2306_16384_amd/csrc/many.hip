@@ -4,7 +4,8 @@
 // gather the window's head"; here all k steps run in two launches, whatever k:
 //
 //   dedup_small   one workgroup per pushed list: the list is marked into a
-//                 bitmap in LDS (tables of up to 516,096 rows), scanned and
+//                 bitmap in LDS (tables whose bitmap fits a workgroup's LDS: 1.3 M rows
+//                 on gfx950), scanned and
 //                 written out as ascending distinct IDs.  Nothing else of the
 //                 push happens here.
 //   classify_many the k steps one after the other inside one kernel.  A step's
@@ -34,13 +35,12 @@ namespace gids {
 namespace {
 
 constexpr int DS_THREADS = 1024;
-constexpr int DS_WORDS = 8064;             // 64-bit words of the LDS bitmap (63 KiB): 516,096 rows
 constexpr int CM_THREADS = 1024;
 constexpr int CM_UNROLL = 4;               // list entries a thread fetches before it looks at any
 
 template <typename IdT>
 __global__ __launch_bounds__(DS_THREADS) void dedup_small_kernel(ManyPushes<IdT> p, uint64_t n_rows, Ctl* ctl) {
-    __shared__ unsigned long long bm[DS_WORDS];
+    extern __shared__ unsigned long long bm[];               // n_words words: the launcher sizes it for the table
     __shared__ uint32_t wave_sum[DS_THREADS / 64];
     const uint32_t tid = threadIdx.x;
     const IdT* __restrict__ ids = p.ids[blockIdx.x];
@@ -342,13 +342,32 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
 
 }  // namespace
 
-uint64_t many_max_rows() { return (uint64_t)DS_WORDS * 64; }
+// rows whose bitmap fits the LDS one workgroup may take on the current device (all of a CU's on gfx950)
+uint64_t many_max_rows() {
+    static const uint64_t rows = [] {
+        int dev = 0, lds = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess || lds < 65536) {
+            (void)hipGetLastError();
+            lds = 65536;
+        }
+        return (uint64_t)(lds - 1024) * 8;                   // 1 KiB left for the kernel's other shared variables
+    }();
+    return rows;
+}
 uint32_t many_max_ways() { return 16; }
 
 template <typename IdT>
 void launch_dedup_small(const ManyPushes<IdT>& p, uint32_t n_lists, uint64_t n_rows, Ctl* ctl, hipStream_t s) {
     if (n_lists == 0) return;
-    hipLaunchKernelGGL(dedup_small_kernel<IdT>, dim3(n_lists), dim3(DS_THREADS), 0, s, p, n_rows, ctl);
+    const size_t lds = (size_t)((n_rows + 63) / 64) * sizeof(unsigned long long);
+    static bool raised = false;                               // more than the default 64 KiB has to be asked for, once
+    if (lds > 65536 && !raised) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&dedup_small_kernel<IdT>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)(many_max_rows() / 8));
+        raised = true;
+    }
+    hipLaunchKernelGGL(dedup_small_kernel<IdT>, dim3(n_lists), dim3(DS_THREADS), lds, s, p, n_rows, ctl);
 }
 
 template <typename IdT>

@@ -172,12 +172,16 @@ def test_merged_calls_through_the_per_step_kernels(gpu, oracle_mod):
                  hot=rng.choice(n, 60, replace=False), pipeline=pipeline, fuse="0", label="per-step")
 
 
-def test_a_table_beyond_the_lds_bitmap(gpu, oracle_mod):
+@pytest.mark.parametrize("n", [600_000, 1_500_000])
+def test_tables_beyond_64_kib_of_bitmap(gpu, oracle_mod, n):
+    """600,000 rows: the merged dedup's LDS bitmap needs more than the default 64 KiB of a workgroup; 1,500,000
+    rows: more than a workgroup can have, the call takes the per-step kernels.  Also lists beyond the merged
+    kernels' length limit."""
     rng = np.random.default_rng(78)
-    n = 600_000                                               # more rows than the merged dedup's bitmap holds
     feats = rng.integers(0, 256, size=(n, 16), dtype=np.uint8)
     batches = [rng.integers(0, n, size=3000) for _ in range(12)]
-    run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=1024, ways=8, window=2, ks=[4], label="600k")
+    batches[5] = rng.integers(0, n, size=20_000)
+    run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=1024, ways=8, window=2, ks=[4], label=f"{n} rows")
 
 
 def test_merged_call_errors(gpu):
