@@ -198,6 +198,7 @@ struct gids_cache {
         }
     }
     uint64_t many_list_max = 8192;  // merged kernels for lists up to this many raw IDs (GIDS_MANY_LIST_MAX)
+    uint64_t many_pool = 128 * 1024;    // LDS for a classifying workgroup's own list entries (GIDS_MANY_POOL, bytes; 0: none)
     int fuse = 1;               // GIDS_FUSE=0: commit, queueing and counters as a kernel each; no merged kernels
     int move_blocks = 1 << 20;  // most workgroups the row mover uses for rows that stay in HBM
     int link_blocks = 48;       // ... for rows that cross the host link (persistent)
@@ -351,6 +352,7 @@ struct CacheT final : gids_cache {
         if (const char* env = getenv("GIDS_WIDE_INDEX")) wide_index = atoi(env) != 0;
         if (const char* env = getenv("GIDS_FUSE")) fuse = atoi(env) & 1;
         if (const char* env = getenv("GIDS_MANY_LIST_MAX")) many_list_max = (uint64_t)std::max(0ll, atoll(env));
+        if (const char* env = getenv("GIDS_MANY_POOL")) many_pool = (uint64_t)std::max(0ll, atoll(env));
         if (const char* env = getenv("GIDS_MOVE_BLOCKS")) {
             const int b = atoi(env);
             if (b >= 1 && b <= (1 << 20)) move_blocks = b;
@@ -787,7 +789,11 @@ struct CacheT final : gids_cache {
             std::vector<uint64_t> len(slots.size());
             for (size_t q = 0; q < slots.size(); q++) len[q] = slots[q].n_raw;
             for (uint32_t i = 0; i < k; i++) {
-                if (push_ids && push_ids[i]) { len[(h + c2) % slots.size()] = push_n[i]; c2++; }
+                if (push_ids && push_ids[i]) {
+                    len[(h + c2) % slots.size()] = push_n[i];
+                    longest_raw = std::max(longest_raw, push_n[i]);
+                    c2++;
+                }
                 longest_raw = std::max(longest_raw, len[h]);
                 h = (h + 1) % slots.size();
                 c2--;
@@ -817,6 +823,7 @@ struct CacheT final : gids_cache {
                     WindowSlot& sl = slots[(h + c2) % slots.size()];
                     if ((rc = ensure_slot(sl, push_n[i]))) return rc;
                     sl.n_raw = push_n[i];
+                    longest = std::max(longest, std::min<uint64_t>(push_n[i], store->n_rows));
                     c2++;
                 }
                 const uint64_t up = std::min<uint64_t>(slots[h].n_raw, store->n_rows);
@@ -857,9 +864,23 @@ struct CacheT final : gids_cache {
         ms.seq0 = seq;
         uint32_t n_push = 0;
         uint64_t off = 0;
+        ms.n_lists = 0;
+        std::vector<int> list_of_slot(slots.size(), -1);
+        auto list_of = [&](uint32_t slot, bool is_head) {
+            int& l = list_of_slot[slot];
+            if (l < 0) {
+                l = (int)ms.n_lists++;
+                ms.list[l] = static_cast<const IdT*>(slots[slot].ids);
+                ms.list_slot[l] = (uint16_t)slot;
+                ms.list_is_head[l] = 0;
+            }
+            if (is_head) ms.list_is_head[l] = 1;
+            return (uint8_t)l;
+        };
         for (uint32_t i = 0; i < k; i++) {
             ms.pushed[i] = nullptr;
             ms.pushed_slot[i] = 0;
+            ms.pushed_list[i] = MANY_NO_LIST;
             if (push_ids && push_ids[i]) {
                 const uint32_t slot = (head + count) % slots.size();
                 WindowSlot& sl = slots[slot];
@@ -870,9 +891,11 @@ struct CacheT final : gids_cache {
                 n_push++;
                 ms.pushed[i] = static_cast<const IdT*>(sl.ids);
                 ms.pushed_slot[i] = slot;
+                ms.pushed_list[i] = list_of(slot, false);
                 sl.last_reader = -1;
                 count++;
             }
+            ms.head_list[i] = list_of(head, true);
             const uint64_t n_raw = slots[head].n_raw;
             ms.head[i] = static_cast<const IdT*>(slots[head].ids);
             ms.head_slot[i] = head;
@@ -891,13 +914,15 @@ struct CacheT final : gids_cache {
             count--;
         }
         launch_dedup_small<IdT>(mp, n_push, store->n_rows, ctl, m);
-        launch_classify_many<IdT>(view(), accum_view(), group, ms, longest, many_plan, ring_dev, STATS_RING, m);
+        // the caller's ID buffers are read by that kernel alone: the push stream goes on as soon as it is through
+        // (were it held until the classification ends, the next call's lists would be ready that much later)
+        if (pipelined && n_push && (rc = edge(meta, ps))) return rc;
+        launch_classify_many<IdT>(view(), accum_view(), group, ms, longest, many_pool, many_plan, ring_dev, STATS_RING, m);
         HIP_TRY(hipGetLastError());
         const int r_last = (int)((seq + k - 1) % STATS_RING);
         for (uint32_t i = 0; i < k; i++) ev_of[(seq + i) % STATS_RING] = r_last;
         if (pipelined) {
             HIP_TRY(hipEventRecord(ev_meta[r_last], meta));
-            if (n_push && (rc = edge(meta, ps))) return rc;   // the caller may reuse its ID buffers in the push stream's order
         }
         open_upper = total_upper;
         open_batches = k;

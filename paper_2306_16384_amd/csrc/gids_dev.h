@@ -217,14 +217,25 @@ struct ManySteps {
     uint64_t plan_offset[MANY_MAX];     // where step i's plan starts in the call's plan buffer
     char* out[MANY_MAX];
     IdT* unique_out[MANY_MAX];
+    // the distinct window slots behind `pushed` and `head` (a list pushed in one step is the head of a later
+    // one), so that a workgroup picks the IDs of its own cache sets out of every list once
+    uint32_t n_lists;
+    const IdT* list[2 * MANY_MAX];
+    uint16_t list_slot[2 * MANY_MAX];
+    uint8_t list_is_head[2 * MANY_MAX];
+    uint8_t head_list[MANY_MAX];        // step i's head, as an index into `list`
+    uint8_t pushed_list[MANY_MAX];      // the list pushed in step i (MANY_NO_LIST: none)
+    uint32_t share_cap;                 // entries of one list a workgroup can keep (<= its thread count)
 };
+constexpr uint8_t MANY_NO_LIST = 0xFF;
 uint64_t many_max_rows();
 uint32_t many_max_ways();
 template <typename IdT>
 void launch_dedup_small(const ManyPushes<IdT>& p, uint32_t n_lists, uint64_t n_rows, Ctl* ctl, hipStream_t s);
 template <typename IdT>
-void launch_classify_many(const CacheView<IdT>& c, const AccumView& a, uint32_t group, const ManySteps<IdT>& m,
-                          uint64_t longest, uint64_t* plan_all, StatsRec* ring, uint32_t ring_size, hipStream_t s);
+void launch_classify_many(const CacheView<IdT>& c, const AccumView& a, uint32_t group, ManySteps<IdT>& m,
+                          uint64_t longest, uint64_t pool_bytes, uint64_t* plan_all, StatsRec* ring, uint32_t ring_size,
+                          hipStream_t s);   // fills m.share_cap; pool_bytes = 0: every workgroup reads the lists from memory
 
 // The distinct-ID lists of a group's minibatches wait in a staging buffer of the group (they are produced on
 // the stream that classifies) and reach the callers' buffers with the rows, on the stream the callers gave.

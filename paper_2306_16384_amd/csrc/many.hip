@@ -37,6 +37,8 @@ namespace {
 constexpr int DS_THREADS = 1024;
 constexpr int CM_THREADS = 1024;
 constexpr int CM_UNROLL = 4;               // list entries a thread fetches before it looks at any
+constexpr uint32_t CM_NONE = 0xFFFFFFFFu;  // not a CPU-buffer row
+constexpr uint64_t MANY_POOL_MAX_BYTES = 128 * 1024;   // of a CU's 160 KiB of LDS
 
 template <typename IdT>
 __global__ __launch_bounds__(DS_THREADS) void dedup_small_kernel(ManyPushes<IdT> p, uint64_t n_rows, Ctl* ctl) {
@@ -98,11 +100,11 @@ __device__ __forceinline__ bool owns(const CacheView<IdT>& c, uint64_t set, uint
 template <typename IdT>
 __device__ __forceinline__ void raise_counters(const CacheView<IdT>& c, const IdT* __restrict__ P, uint32_t n_p,
                                                uint32_t n_wg, uint32_t me) {
-    for (uint64_t base = threadIdx.x; base < n_p; base += (uint64_t)CM_THREADS * CM_UNROLL) {
+    for (uint64_t base = threadIdx.x; base < n_p; base += (uint64_t)blockDim.x * CM_UNROLL) {
         uint64_t vv[CM_UNROLL];
 #pragma unroll
         for (int u = 0; u < CM_UNROLL; u++) {
-            const uint64_t j = base + (uint64_t)u * CM_THREADS;
+            const uint64_t j = base + (uint64_t)u * blockDim.x;
             vv[u] = j < n_p ? (uint64_t)P[j] : ~0ull;
         }
 #pragma unroll
@@ -115,30 +117,63 @@ __device__ __forceinline__ void raise_counters(const CacheView<IdT>& c, const Id
     }
 }
 
+// The way a missed ID takes in its set, or -1 when the set has no evictable way left for it: the k-th miss of a
+// set (ascending ID) takes the k-th evictable way in (stamp, way) order (seeded hash order under the random
+// policy).  Reads the set's stamps, the counters of the nodes it holds and its miss mask as they are now: the
+// caller has a barrier between the minibatch's probe and this.
 template <typename IdT, int WAYS>
-__global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT> c, AccumView a, uint32_t group,
-                                                                   ManySteps<IdT> m, uint64_t* __restrict__ plan_all,
-                                                                   StatsRec* ring, uint32_t ring_size) {
-    __shared__ uint32_t cnt[5];                              // hits, CPU-buffer hits, misses, bypasses, line fills
-    __shared__ uint32_t is_last;
+__device__ __forceinline__ int pick_way(const CacheView<IdT>& c, uint64_t set, uint64_t round, int32_t stamp,
+                                        const IdT (&tg)[WAYS]) {
+    const uint64_t line0 = set * WAYS;
+    int32_t st[WAYS];
+#pragma unroll
+    for (int w = 0; w < WAYS; w++) st[w] = c.stamps[line0 + w];
+    uint8_t ru[WAYS];
+#pragma unroll
+    for (int w = 0; w < WAYS; w++) ru[w] = tg[w] < 0 ? (uint8_t)0 : c.reuse[(uint64_t)tg[w]];
+    uint64_t key[WAYS];
+    uint32_t n_ev = 0;
+#pragma unroll
+    for (int w = 0; w < WAYS; w++) {
+        const bool empty = tg[w] < 0;
+        const bool ev = st[w] != stamp && ru[w] == 0;         // untouched in this minibatch, no buffered future use
+        uint64_t order = (uint64_t)(uint32_t)(st[w] + 1);
+        if (c.policy == 1)
+            order = empty ? 0ull
+                          : 1ull + (mix64(mix64(mix64(c.policy_key ^ (uint64_t)(uint32_t)stamp) ^ set) ^ (uint64_t)w) >> 9);
+        key[w] = ev ? (order << 8) | (uint64_t)w : ~0ull;
+        n_ev += ev;
+    }
+    uint32_t rank = 0;                                        // of this miss among its set's misses, ascending ID
+    const uint64_t* mm = c.missmask + set * c.words_per_set;
+    const uint32_t wi = (uint32_t)(round >> 6);
+    for (uint32_t x = 0; x < wi; x++) rank += (uint32_t)__popcll(mm[x]);
+    rank += (uint32_t)__popcll(mm[wi] & ((1ull << (round & 63)) - 1));
+    if (rank >= n_ev) return -1;
+    int way = 0;
+#pragma unroll
+    for (int w = 0; w < WAYS; w++) {
+        uint32_t r = 0;
+#pragma unroll
+        for (int o = 0; o < WAYS; o++) r += key[o] < key[w];
+        if (key[w] != ~0ull && r == rank) way = w;
+    }
+    return way;
+}
+
+// The steps for a workgroup whose share of some list did not fit its LDS: every phase of every step reads the
+// whole list from memory again and keeps what it owns; the plan entries pass between the phases through memory.
+template <typename IdT, int WAYS>
+__device__ void steps_from_memory(const CacheView<IdT>& c, const AccumView& a, uint32_t group, const ManySteps<IdT>& m,
+                                  uint64_t* __restrict__ plan_all, uint32_t n_ok, uint32_t stamp0, uint32_t* cnt) {
     Ctl* ctl = c.ctl;
     const uint32_t tid = threadIdx.x;
     const uint32_t n_wg = gridDim.x, me = blockIdx.x;
-    const uint32_t stamp0 = ctl->stamp;
-    // an error left by an earlier kernel (a pushed ID out of range): nothing runs, every record reports it
-    uint32_t n_ok = ld_agent(&ctl->error) == 0 ? m.k : 0;
-    // Between the phases of a step only workgroup barriers: what a phase reads was written by this same
-    // workgroup (its sets' tags, stamps and miss masks, its nodes' counters, its own list operations), and a
-    // barrier orders memory within a workgroup.  Agent-wide visibility is needed once, before the ticket.
     if (n_ok && m.pushed[0]) raise_counters(c, m.pushed[0], ctl->win_n[m.pushed_slot[0]], n_wg, me);
     for (uint32_t i = 0; i < n_ok; i++) {
         const int32_t stamp = (int32_t)(stamp0 + i);
         const IdT* __restrict__ U = m.head[i];
         const uint32_t n_u = ctl->win_n[m.head_slot[i]];
-        if (n_u > m.out_capacity[i]) {                        // the same verdict in every workgroup: this step
-            n_ok = i;                                         // and the later ones do not run
-            break;
-        }
         uint64_t* __restrict__ plan = plan_all + m.plan_offset[i];
         if (tid < 5) cnt[tid] = 0;
         // (the list pushed in this step has had its counters raised already: before the loop for step 0,
@@ -146,16 +181,16 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
         __syncthreads();
         uint32_t hits = 0, cpus = 0, misses = 0, bypasses = 0, fills = 0;
         // ---- probe: every ID of this workgroup's sets against the state at the start of the minibatch
-        for (uint64_t base = tid; base < n_u; base += (uint64_t)CM_THREADS * CM_UNROLL) {
+        for (uint64_t base = tid; base < n_u; base += (uint64_t)blockDim.x * CM_UNROLL) {
             uint64_t vv[CM_UNROLL];
 #pragma unroll
             for (int u = 0; u < CM_UNROLL; u++) {
-                const uint64_t j = base + (uint64_t)u * CM_THREADS;
+                const uint64_t j = base + (uint64_t)u * blockDim.x;
                 vv[u] = j < n_u ? (uint64_t)U[j] : ~0ull;
             }
 #pragma unroll
             for (int u = 0; u < CM_UNROLL; u++) {
-                const uint64_t j = base + (uint64_t)u * CM_THREADS;
+                const uint64_t j = base + (uint64_t)u * blockDim.x;
                 const uint64_t v = vv[u];
                 if (v == ~0ull) continue;
                 uint64_t set, round;
@@ -191,66 +226,33 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
         }
         if (misses) atomicAdd(&cnt[2], misses);
         __syncthreads();
-        // ---- victims: the k-th miss of a set (ascending ID) takes the k-th evictable way in (stamp, way) order
+        // ---- victims
         const bool any_miss = cnt[2] != 0;
         if (any_miss) {
-            for (uint64_t base = tid; base < n_u; base += (uint64_t)CM_THREADS * CM_UNROLL) {
+            for (uint64_t base = tid; base < n_u; base += (uint64_t)blockDim.x * CM_UNROLL) {
                 uint64_t ee[CM_UNROLL];
 #pragma unroll
                 for (int u = 0; u < CM_UNROLL; u++) {
-                    const uint64_t j = base + (uint64_t)u * CM_THREADS;
+                    const uint64_t j = base + (uint64_t)u * blockDim.x;
                     ee[u] = j < n_u ? plan[j] : 0ull;         // (entries of other workgroups' sets are skipped below)
                 }
 #pragma unroll
                 for (int u = 0; u < CM_UNROLL; u++) {
-                    const uint64_t j = base + (uint64_t)u * CM_THREADS;
+                    const uint64_t j = base + (uint64_t)u * blockDim.x;
                     if (j >= n_u || (ee[u] >> PLAN_SHIFT) != PLAN_MISS_TBD) continue;
                     const uint64_t v = (uint64_t)U[j];
                     uint64_t set, round;
                     set_and_round(c, v, &set, &round);
                     if (!owns(c, set, n_wg, me)) continue;    // (what another workgroup or an earlier call left there)
-                    const uint64_t line0 = set * WAYS;
                     IdT tg[WAYS];
-                    int32_t st[WAYS];
 #pragma unroll
-                    for (int w = 0; w < WAYS; w++) {
-                        tg[w] = c.tags[line0 + w];
-                        st[w] = c.stamps[line0 + w];
-                    }
-                    uint8_t ru[WAYS];
-#pragma unroll
-                    for (int w = 0; w < WAYS; w++) ru[w] = tg[w] < 0 ? (uint8_t)0 : c.reuse[(uint64_t)tg[w]];
-                    uint64_t key[WAYS];
-                    uint32_t n_ev = 0;
-#pragma unroll
-                    for (int w = 0; w < WAYS; w++) {
-                        const bool empty = tg[w] < 0;
-                        const bool ev = st[w] != stamp && ru[w] == 0;   // untouched in this minibatch, no buffered future use
-                        uint64_t order = (uint64_t)(uint32_t)(st[w] + 1);
-                        if (c.policy == 1)
-                            order = empty ? 0ull
-                                          : 1ull + (mix64(mix64(mix64(c.policy_key ^ (uint64_t)(uint32_t)stamp) ^ set) ^ (uint64_t)w) >> 9);
-                        key[w] = ev ? (order << 8) | (uint64_t)w : ~0ull;
-                        n_ev += ev;
-                    }
-                    uint32_t rank = 0;                        // of this miss among its set's misses, ascending ID
-                    const uint64_t* mm = c.missmask + set * c.words_per_set;
-                    const uint32_t wi = (uint32_t)(round >> 6);
-                    for (uint32_t x = 0; x < wi; x++) rank += (uint32_t)__popcll(mm[x]);
-                    rank += (uint32_t)__popcll(mm[wi] & ((1ull << (round & 63)) - 1));
-                    if (rank >= n_ev) {
+                    for (int w = 0; w < WAYS; w++) tg[w] = c.tags[set * WAYS + w];
+                    const int way = pick_way<IdT, WAYS>(c, set, round, stamp, tg);
+                    if (way < 0) {
                         plan[j] = PLAN_BYPASS << PLAN_SHIFT;
                         bypasses++;
                     } else {
-                        int way = 0;
-#pragma unroll
-                        for (int w = 0; w < WAYS; w++) {
-                            uint32_t r = 0;
-#pragma unroll
-                            for (int o = 0; o < WAYS; o++) r += key[o] < key[w];
-                            if (key[w] != ~0ull && r == rank) way = w;
-                        }
-                        plan[j] = (PLAN_INSTALL << PLAN_SHIFT) | (line0 + (uint32_t)way);
+                        plan[j] = (PLAN_INSTALL << PLAN_SHIFT) | (set * WAYS + (uint32_t)way);
                         fills++;
                     }
                 }
@@ -258,7 +260,7 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
             __syncthreads();
         }
         // ---- publish tags and stamps, clear the miss mask, queue every row into the open group's lists
-        for (uint64_t base = 0; base < n_u; base += CM_THREADS) {    // uniform trip count: queue_entry ballots
+        for (uint64_t base = 0; base < n_u; base += blockDim.x) {     // uniform trip count: queue_entry ballots
             const uint64_t j = base + tid;
             bool mine = false;
             uint64_t e = 0, v = 0;
@@ -303,6 +305,192 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
         if (tid < 5 && cnt[tid]) atomicAdd(&ctl->many_cnt[i][tid], cnt[tid]);
         __syncthreads();                                      // cnt is cleared at the top of the next step
     }
+}
+
+// one wavefront's count of a flag, added to a counter in LDS
+__device__ __forceinline__ void wave_count(uint32_t* counter, bool flag) {
+    const uint64_t b = __ballot(flag);
+    if (b && (threadIdx.x & 63) == 0) atomicAdd(counter, (uint32_t)__popcll(b));
+}
+
+template <typename IdT, int WAYS>
+__global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT> c, AccumView a, uint32_t group,
+                                                                   ManySteps<IdT> m, uint64_t* __restrict__ plan_all,
+                                                                   StatsRec* ring, uint32_t ring_size) {
+    // This workgroup's entries of every list, picked out once: share_cap slots per list (ID, position in the
+    // list, CPU-buffer row or CM_NONE), filled in no particular order.
+    extern __shared__ unsigned long long pool_raw[];
+    __shared__ uint32_t list_n[2 * MANY_MAX];                 // entries of each list
+    __shared__ uint32_t own_n[2 * MANY_MAX];                  // of which this workgroup's
+    __shared__ uint32_t cnt[MANY_MAX][5];                     // per step: hits, CPU-buffer hits, misses, bypasses, line fills
+    __shared__ uint32_t cnt_mem[5];
+    __shared__ uint32_t overflow;
+    __shared__ uint32_t is_last;
+    Ctl* ctl = c.ctl;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t n_wg = gridDim.x, me = blockIdx.x;
+    const uint32_t stamp0 = ctl->stamp;
+    const uint32_t cap = m.share_cap;
+    IdT* pool_v = reinterpret_cast<IdT*>(pool_raw);
+    uint32_t* pool_j = reinterpret_cast<uint32_t*>(pool_v + (size_t)m.n_lists * cap);
+    uint32_t* pool_cpu = pool_j + (size_t)m.n_lists * cap;
+
+    for (uint32_t l = tid; l < m.n_lists; l += blockDim.x) {
+        list_n[l] = ctl->win_n[m.list_slot[l]];
+        own_n[l] = 0;
+    }
+    for (uint32_t x = tid; x < MANY_MAX * 5; x += blockDim.x) cnt[x / 5][x % 5] = 0;
+    if (tid == 0) overflow = cap == 0;
+    __syncthreads();
+    // an error left by an earlier kernel (a pushed ID out of range): nothing runs, every record reports it.
+    // A step whose list exceeds its output: the same verdict in every workgroup, it and the later ones do not run.
+    uint32_t n_ok = ld_agent(&ctl->error) == 0 ? m.k : 0;
+    for (uint32_t i = 0; i < n_ok; i++)
+        if (list_n[m.head_list[i]] > m.out_capacity[i]) n_ok = i;
+
+    // ---- every list once: the IDs of this workgroup's sets go to its LDS
+    if (cap && n_ok) {
+        for (uint32_t l = 0; l < m.n_lists; l++) {
+            const IdT* __restrict__ L = m.list[l];
+            const uint32_t n = list_n[l];
+            for (uint32_t base = tid; base < n; base += blockDim.x * CM_UNROLL) {
+                uint64_t vv[CM_UNROLL];
+#pragma unroll
+                for (int u = 0; u < CM_UNROLL; u++) {
+                    const uint32_t j = base + (uint32_t)u * blockDim.x;
+                    vv[u] = j < n ? (uint64_t)L[j] : ~0ull;
+                }
+#pragma unroll
+                for (int u = 0; u < CM_UNROLL; u++) {
+                    if (vv[u] == ~0ull) continue;
+                    uint64_t set, round;
+                    set_and_round(c, vv[u], &set, &round);
+                    if (!owns(c, set, n_wg, me)) continue;
+                    const uint32_t pos = atomicAdd(&own_n[l], 1u);
+                    if (pos < cap) {
+                        pool_v[(size_t)l * cap + pos] = (IdT)vv[u];
+                        pool_j[(size_t)l * cap + pos] = base + (uint32_t)u * blockDim.x;
+                    } else {
+                        overflow = 1;
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+    const bool from_memory = overflow != 0;                   // the same in every thread of the workgroup
+    if (from_memory) {
+        steps_from_memory<IdT, WAYS>(c, a, group, m, plan_all, n_ok, stamp0, cnt_mem);
+    } else if (n_ok) {
+        // CPU-buffer lookup (Section 3.3) of every entry that will be gathered: the buffer is constant
+        for (uint32_t x = tid; x < m.n_lists * cap; x += blockDim.x) {
+            const uint32_t l = x / cap;
+            if (!m.list_is_head[l] || x - l * cap >= own_n[l]) continue;
+            uint32_t row = CM_NONE;
+            if (c.hotbits) {
+                const uint64_t v = (uint64_t)pool_v[x];
+                const uint64_t hw = c.hotbits[v >> 6];
+                const uint64_t bit = 1ull << (v & 63);
+                if (hw & bit) row = c.hotrank[v >> 6] + (uint32_t)__popcll(hw & (bit - 1));
+            }
+            pool_cpu[x] = row;
+        }
+        // the list pushed in step 0: one more buffered future use for each of its nodes (Section 3.4, Fig. 6)
+        if (m.pushed_list[0] != MANY_NO_LIST && tid < own_n[m.pushed_list[0]]) {
+            const uint64_t pv = (uint64_t)pool_v[(size_t)m.pushed_list[0] * cap + tid];
+            c.reuse[pv] = (uint8_t)(c.reuse[pv] + 1);
+        }
+        __syncthreads();
+        // Between the phases of a step only workgroup barriers: what a phase reads was written by this same
+        // workgroup (its sets' tags, stamps and miss masks, its nodes' counters, its own list operations), and a
+        // barrier orders memory within a workgroup.  Agent-wide visibility is needed once, before the ticket.
+        // One thread per entry; what it learns of its entry stays in its registers from phase to phase.
+        for (uint32_t i = 0; i < n_ok; i++) {
+            const int32_t stamp = (int32_t)(stamp0 + i);
+            const uint32_t h = m.head_list[i];
+            const uint32_t n_h = own_n[h];
+            const bool have = tid < n_h;
+            const bool wave_has = (tid & ~63u) < n_h;
+            uint64_t v = 0, e = 0, set = 0, round = 0;
+            uint32_t j = 0;
+            bool miss = false;
+            IdT tg[WAYS];
+#pragma unroll
+            for (int w = 0; w < WAYS; w++) tg[w] = (IdT)-1;
+            // ---- probe, against the state at the start of the minibatch
+            if (have) {
+                v = (uint64_t)pool_v[(size_t)h * cap + tid];
+                j = pool_j[(size_t)h * cap + tid];
+                const uint32_t cpu_row = pool_cpu[(size_t)h * cap + tid];
+                const uint8_t r = c.reuse[v];
+                set_and_round(c, v, &set, &round);
+                if (cpu_row != CM_NONE) {
+                    e = (PLAN_CPU << PLAN_SHIFT) | cpu_row;
+                } else {
+                    int way = -1;
+#pragma unroll
+                    for (int w = 0; w < WAYS; w++) {
+                        tg[w] = c.tags[set * WAYS + w];
+                        if ((uint64_t)tg[w] == v) way = w;    // empty lines hold -1
+                    }
+                    if (way >= 0) {
+                        const uint64_t line = set * WAYS + (uint32_t)way;
+                        c.stamps[line] = stamp;
+                        e = (PLAN_HIT << PLAN_SHIFT) | line;
+                    } else {
+                        miss = true;
+                        e = PLAN_MISS_TBD << PLAN_SHIFT;
+                        atomicOr(reinterpret_cast<unsigned long long*>(c.missmask) + set * c.words_per_set + (round >> 6),
+                                 1ull << (round & 63));
+                    }
+                }
+                c.reuse[v] = (uint8_t)(r - 1);                // this minibatch's own entry leaves the counters
+            }
+            if (wave_has) {
+                wave_count(&cnt[i][0], have && (e >> PLAN_SHIFT) == PLAN_HIT);
+                wave_count(&cnt[i][1], have && (e >> PLAN_SHIFT) == PLAN_CPU);
+                wave_count(&cnt[i][2], miss);
+            }
+            __syncthreads();
+            // ---- victims
+            if (cnt[i][2]) {
+                if (miss) {
+                    const int way = pick_way<IdT, WAYS>(c, set, round, stamp, tg);
+                    e = way < 0 ? PLAN_BYPASS << PLAN_SHIFT : (PLAN_INSTALL << PLAN_SHIFT) | (set * WAYS + (uint32_t)way);
+                }
+                if (wave_has) {
+                    wave_count(&cnt[i][3], miss && (e >> PLAN_SHIFT) == PLAN_BYPASS);
+                    wave_count(&cnt[i][4], miss && (e >> PLAN_SHIFT) == PLAN_INSTALL);
+                }
+                __syncthreads();
+            }
+            // ---- publish tags and stamps, clear the miss mask, queue every row into the open group's lists;
+            // the next step's pushed list enters the counters: this step's victims are chosen, and the next
+            // step's probe, which must see them, waits behind the barrier
+            const uint32_t pl = i + 1 < m.k ? m.pushed_list[i + 1] : MANY_NO_LIST;
+            const bool raise = pl != MANY_NO_LIST && tid < own_n[pl];
+            uint64_t pv = 0;
+            uint8_t pr = 0;
+            if (raise) {
+                pv = (uint64_t)pool_v[(size_t)pl * cap + tid];
+                pr = c.reuse[pv];
+            }
+            if (miss) {
+                if ((e >> PLAN_SHIFT) == PLAN_INSTALL) {
+                    const uint64_t line = e & PLAN_INDEX_MASK;
+                    c.tags[line] = (IdT)v;
+                    c.stamps[line] = stamp;
+                }
+                c.missmask[set * c.words_per_set + (round >> 6)] = 0ull;
+            }
+            if (wave_has) queue_entry(c, a, group, have, (uint64_t)j, e, v, m.out[i], m.unique_out[i]);
+            if (raise) c.reuse[pv] = (uint8_t)(pr + 1);
+            __syncthreads();
+        }
+        for (uint32_t x = tid; x < m.k * 5; x += blockDim.x)
+            if (cnt[x / 5][x % 5]) atomicAdd(&ctl->many_cnt[x / 5][x % 5], cnt[x / 5][x % 5]);
+        __syncthreads();
+    }
     // ---- the last workgroup to get here publishes the records
     if (tid == 0) {
         __threadfence();
@@ -317,7 +505,7 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
     for (uint32_t i = 0; i < m.k; i++) {
         StatsRec* rec = ring + (m.seq0 + i) % ring_size;
         const bool ran = i < n_ok;
-        const uint32_t n = ran ? ctl->win_n[m.head_slot[i]] : 0u;
+        const uint32_t n = ran ? list_n[m.head_list[i]] : 0u;
         rec->n_unique = n;
         rec->n_hit = ld_agent(&ctl->many_cnt[i][0]);
         rec->n_cpu_hit = ld_agent(&ctl->many_cnt[i][1]);
@@ -370,9 +558,26 @@ void launch_dedup_small(const ManyPushes<IdT>& p, uint32_t n_lists, uint64_t n_r
     hipLaunchKernelGGL(dedup_small_kernel<IdT>, dim3(n_lists), dim3(DS_THREADS), lds, s, p, n_rows, ctl);
 }
 
+namespace {
+template <typename IdT, int W>
+void launch_classify_many_ways(const CacheView<IdT>& c, const AccumView& a, uint32_t group, const ManySteps<IdT>& m,
+                               uint32_t grid, uint32_t threads, size_t lds, uint64_t* plan_all, StatsRec* ring,
+                               uint32_t ring_size, hipStream_t s) {
+    static bool raised = false;                               // more than the default 64 KiB has to be asked for, once
+    if (lds > 49152 && !raised) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&classify_many_kernel<IdT, W>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)MANY_POOL_MAX_BYTES);
+        raised = true;
+    }
+    hipLaunchKernelGGL((classify_many_kernel<IdT, W>), dim3(grid), dim3(threads), lds, s, c, a, group, m, plan_all,
+                       ring, ring_size);
+}
+}  // namespace
+
 template <typename IdT>
-void launch_classify_many(const CacheView<IdT>& c, const AccumView& a, uint32_t group, const ManySteps<IdT>& m,
-                          uint64_t longest, uint64_t* plan_all, StatsRec* ring, uint32_t ring_size, hipStream_t s) {
+void launch_classify_many(const CacheView<IdT>& c, const AccumView& a, uint32_t group, ManySteps<IdT>& m,
+                          uint64_t longest, uint64_t pool_bytes, uint64_t* plan_all, StatsRec* ring, uint32_t ring_size,
+                          hipStream_t s) {
     // about 32 of a list's entries per workgroup's own share (GIDS_MANY_SHARE); every workgroup reads every list
     static const uint64_t per_wg = [] {
         const char* e = getenv("GIDS_MANY_SHARE");
@@ -383,9 +588,24 @@ void launch_classify_many(const CacheView<IdT>& c, const AccumView& a, uint32_t 
     if (g < 1) g = 1;
     if (g > 256) g = 256;
     if (g > c.n_sets) g = c.n_sets;                          // a workgroup without a set would only take a ticket
-#define GIDS_CLASSIFY_MANY(W)                                                                                     \
-    hipLaunchKernelGGL((classify_many_kernel<IdT, W>), dim3((uint32_t)g), dim3(CM_THREADS), 0, s, c, a, group, m,  \
-                       plan_all, ring, ring_size)
+    // LDS for a workgroup's own entries: the same number of slots for each list, four times the expected share
+    // where that fits; a workgroup whose share of some list is larger reads the lists from memory instead
+    if (pool_bytes > MANY_POOL_MAX_BYTES) pool_bytes = MANY_POOL_MAX_BYTES;
+    const uint64_t entry = sizeof(IdT) + 8;
+    uint64_t cap = m.n_lists ? pool_bytes / (entry * m.n_lists) : 0;
+    const uint64_t want = 4 * ((longest + g - 1) / g);
+    if (cap > want) cap = want;
+    static const uint32_t threads = [] {                     // a multiple of 64 up to CM_THREADS (GIDS_MANY_THREADS)
+        const char* e = getenv("GIDS_MANY_THREADS");
+        const long v = e ? atol(e) : CM_THREADS;
+        return (uint32_t)(v >= 64 && v <= CM_THREADS ? v & ~63l : CM_THREADS);
+    }();
+    if (cap > threads) cap = threads;                         // one thread per entry
+    cap &= ~1ull;                                             // keeps the 32-bit arrays behind the IDs aligned
+    m.share_cap = (uint32_t)cap;
+    const size_t lds = (size_t)(cap * m.n_lists * entry);
+#define GIDS_CLASSIFY_MANY(W) \
+    launch_classify_many_ways<IdT, W>(c, a, group, m, (uint32_t)g, threads, lds, plan_all, ring, ring_size, s)
     switch (c.ways) {
         case 1: GIDS_CLASSIFY_MANY(1); break;
         case 2: GIDS_CLASSIFY_MANY(2); break;
@@ -398,9 +618,8 @@ void launch_classify_many(const CacheView<IdT>& c, const AccumView& a, uint32_t 
 
 #define GIDS_INSTANTIATE(IdT)                                                                                     \
     template void launch_dedup_small<IdT>(const ManyPushes<IdT>&, uint32_t, uint64_t, Ctl*, hipStream_t);         \
-    template void launch_classify_many<IdT>(const CacheView<IdT>&, const AccumView&, uint32_t,                    \
-                                            const ManySteps<IdT>&, uint64_t, uint64_t*, StatsRec*, uint32_t,      \
-                                            hipStream_t);
+    template void launch_classify_many<IdT>(const CacheView<IdT>&, const AccumView&, uint32_t, ManySteps<IdT>&,  \
+                                            uint64_t, uint64_t, uint64_t*, StatsRec*, uint32_t, hipStream_t);
 GIDS_INSTANTIATE(int32_t)
 GIDS_INSTANTIATE(int64_t)
 

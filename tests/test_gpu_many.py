@@ -37,7 +37,7 @@ def with_env(knobs, make):
 
 
 def run_many(gpu, oracle, feats, batches, *, id_dtype, lines, ways, window, ks, hot=None, policy=None, pipeline="0",
-             fuse=None, label=""):
+             fuse=None, pool=None, label=""):
     """ks: the sizes of the merged calls, in order (0 = one plain push + gather step in between);
     cycles until every list is gathered."""
     torch, gids, GatherSession = gpu
@@ -45,7 +45,8 @@ def run_many(gpu, oracle, feats, batches, *, id_dtype, lines, ways, window, ks, 
     feats_u8 = np.ascontiguousarray(feats).view(np.uint8).reshape(n_rows, -1)
     R = feats_u8.shape[1]
     n_b = len(batches)
-    print(f"[many {label}] rows={n_rows} R={R} lines={lines} ways={ways} W={window} pipe={pipeline} fuse={fuse} ks={ks}", flush=True)
+    print(f"[many {label}] rows={n_rows} R={R} lines={lines} ways={ways} W={window} pipe={pipeline} fuse={fuse} "
+          f"pool={pool} ks={ks}", flush=True)
     sim = oracle.Sim(n_rows, lines, ways, window, R, R, feats_u8)
     if hot is not None:
         sim.set_hot(hot)
@@ -60,6 +61,8 @@ def run_many(gpu, oracle, feats, batches, *, id_dtype, lines, ways, window, ks, 
     knobs = {"GIDS_PIPELINE": pipeline}
     if fuse is not None:
         knobs["GIDS_FUSE"] = fuse
+    if pool is not None:
+        knobs["GIDS_MANY_POOL"] = pool
     ses = with_env(knobs, lambda: GatherSession(n_rows, R, id_dtype, lines, ways, R, window, 1000))
     with ses:
         ses.store_view()[:] = feats_u8
@@ -159,6 +162,28 @@ def test_merged_calls_over_shapes(gpu, oracle_mod, ways, window, id_dtype, polic
         run_many(gpu, oracle_mod, feats, batches, id_dtype=id_dtype, lines=ways * 11, ways=ways, window=window,
                  ks=[5, 0, 13, 1], hot=rng.choice(n, 40, replace=False), policy=policy, pipeline=pipeline,
                  label=f"ways{ways}/W{window}")
+
+
+@pytest.mark.parametrize("pool", ["0", "3000", "14000"])
+def test_merged_calls_with_little_or_no_lds_for_the_lists(gpu, oracle_mod, pool):
+    """A classifying workgroup keeps its own entries of every list in LDS; one whose share of some list does not
+    fit reads the lists from memory in every phase instead.  No LDS: all of them do; 14,000 bytes: about as many
+    slots as the expected share, so workgroups of both kinds run side by side in one launch."""
+    cfg = CONFIGS["tiny"]
+    g = wl.make_graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max)
+    table = wl.normal_table(np.float32)
+    feats = wl.feature_rows(cfg.seed, np.arange(cfg.n_nodes), cfg.dim, table)
+    hot = wl.hot_nodes(g, cfg.cpu_rows)
+    batches = [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds) for b in range(40)]
+    run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int32, lines=cfg.cache_lines, ways=cfg.ways,
+             window=cfg.window, ks=[32, 3, 0, 5], hot=hot, pool=pool, label="tiny")
+    rng = np.random.default_rng(91)
+    n = 3000
+    feats = rng.integers(0, 256, size=(n, 128), dtype=np.uint8)
+    batches = zipf_lists(rng, n, 30, 500)
+    batches[9] = np.arange(n, dtype=np.int64)
+    run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=8 * 11, ways=8, window=3, ks=[7, 0, 12],
+             hot=rng.choice(n, 40, replace=False), pool=pool, pipeline="1", label="small cache")
 
 
 def test_merged_calls_through_the_per_step_kernels(gpu, oracle_mod):
