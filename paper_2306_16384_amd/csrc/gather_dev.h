@@ -7,6 +7,37 @@
 
 namespace gids {
 
+// Where queue_entry keeps what it knows of a cache line between the minibatches of a group: the group in which
+// the line's fill was queued and that fill's index, the group in which a copy out of the line was last queued.
+// The per-step kernels keep these words in device memory, indexed by line.
+struct LineWordsGlobal {
+    static constexpr bool deferred = false;                   // a line's fill is queued when the line is installed
+    uint32_t* pending;
+    uint32_t* fillgrp;
+    uint32_t* hitgrp;
+    const FillOp* fills;
+    __device__ __forceinline__ uint32_t fill_group(uint64_t line, uint32_t) const { return fillgrp[line]; }
+    __device__ __forceinline__ uint32_t hit_group(uint64_t line, uint32_t) const { return hitgrp[line]; }
+    __device__ __forceinline__ uint32_t pending_fill(uint64_t line, uint32_t) const { return pending[line]; }
+    // the output row the line's queued fill writes
+    __device__ __forceinline__ void* pending_out(uint64_t, uint32_t, uint32_t pd) const { return fills[pd].dst_out; }
+    __device__ __forceinline__ void note_fill(uint64_t line, uint32_t, uint32_t group, uint32_t q, char*) const {
+        fillgrp[line] = group;
+        pending[line] = q;
+    }
+    __device__ __forceinline__ void note_hit(uint64_t line, uint32_t, uint32_t group) const { hitgrp[line] = group; }
+};
+
+// Where queue_entry takes places in the group's three lists (0 fills, 1 rcopies, 2 wcopies) from: the lists'
+// counters in device memory, one atomic per wavefront and list.
+struct PlacesGlobal {
+    Ctl* ctl;
+    uint32_t par;
+    __device__ __forceinline__ uint32_t take(int list, uint32_t n) const {
+        return atomicAdd(list == 0 ? &ctl->q_fill[par] : list == 1 ? &ctl->q_rcopy[par] : &ctl->q_wcopy[par], n);
+    }
+};
+
 // The accumulator's treatment of plan entry j (Section 3.2: nothing moves while a group of minibatches is
 // open; every row becomes an operation in the group's lists).  Called by all 64 lanes of a wavefront
 // together, `valid` false for lanes without an entry; the lanes' entries may be any distinct j.
@@ -19,10 +50,16 @@ namespace gids {
 //            output row, so that the rcopy sees the old bytes.
 // A line installed twice in one group is filled by the last install only (the earlier fill keeps its output
 // row).  Every line is touched by at most one plan entry per minibatch, so the per-line words are written
-// without atomics.
-template <typename IdT>
-__device__ __forceinline__ void queue_entry(const CacheView<IdT>& c, const AccumView& a, uint32_t group, bool valid,
-                                            uint64_t j, uint64_t e, uint64_t v, char* __restrict__ out,
+// without atomics.  `lw` holds the per-line words, `local` is the line's index there where that is not the
+// line number; `places` hands out list positions.
+// With LineWords::deferred the fill of an installed line is not queued here: it waits in the line's words (node,
+// output row, whether it is late) until the line is installed again in the same group (then it goes out for its
+// output row only) or until the holder of the words queues what is left when the group ends; no queued operation
+// is ever read or changed again.
+template <typename IdT, typename LineWords, typename Places>
+__device__ __forceinline__ void queue_entry(const CacheView<IdT>& c, const AccumView& a, const LineWords& lw,
+                                            const Places& places, uint32_t group, bool valid, uint64_t j, uint64_t e,
+                                            uint64_t v, uint32_t local, char* __restrict__ out,
                                             IdT* __restrict__ unique_out) {
     Ctl* ctl = c.ctl;
     const uint32_t par = group & 1u;
@@ -35,21 +72,24 @@ __device__ __forceinline__ void queue_entry(const CacheView<IdT>& c, const Accum
     const bool has_line = valid && (kind == PLAN_HIT || kind == PLAN_INSTALL);
     uint32_t fg = ~0u, hg = ~0u, pd = NO_OP;
     if (has_line) {
-        fg = c.fillgrp[idx];
-        hg = c.hitgrp[idx];
-        pd = c.pending[idx];
+        fg = lw.fill_group(idx, local);
+        hg = lw.hit_group(idx, local);
+        pd = lw.pending_fill(idx, local);
     }
     const bool open_fill = has_line && fg == group;               // the line's fill is queued in this group
-    const bool is_fill = valid && kind != PLAN_HIT;
     const bool is_wait = valid && kind == PLAN_HIT && open_fill;
     const bool is_ready = valid && kind == PLAN_HIT && !open_fill;
     const bool is_late = valid && kind == PLAN_INSTALL && hg == group;   // a queued rcopy still reads the old bytes
-    const uint64_t fb = __ballot(is_fill), rb = __ballot(is_ready), wb = __ballot(is_wait || is_late);
+    // a fill now: every row that crosses the link; deferred, an installed line's own fill waits and only the one
+    // it supersedes goes out
+    const bool is_fill = valid && kind != PLAN_HIT && !(LineWords::deferred && kind == PLAN_INSTALL && !open_fill);
+    const uint64_t fb = __ballot(is_fill), rb = __ballot(is_ready),
+                   wb = __ballot(is_wait || (is_late && !LineWords::deferred));
     uint32_t fbase = 0, rbase = 0, wbase = 0;
     if (lane == 0) {
-        if (fb) fbase = atomicAdd(&ctl->q_fill[par], (uint32_t)__popcll(fb));
-        if (rb) rbase = atomicAdd(&ctl->q_rcopy[par], (uint32_t)__popcll(rb));
-        if (wb) wbase = atomicAdd(&ctl->q_wcopy[par], (uint32_t)__popcll(wb));
+        if (fb) fbase = places.take(0, (uint32_t)__popcll(fb));
+        if (rb) rbase = places.take(1, (uint32_t)__popcll(rb));
+        if (wb) wbase = places.take(2, (uint32_t)__popcll(wb));
     }
     fbase = __shfl(fbase, 0);
     rbase = __shfl(rbase, 0);
@@ -72,7 +112,12 @@ __device__ __forceinline__ void queue_entry(const CacheView<IdT>& c, const Accum
         op.dst_line = NO_LINE;
         op.late = NO_OP;
         op.pad = 0;
-        if (kind == PLAN_INSTALL) {
+        if constexpr (LineWords::deferred) {
+            if (kind == PLAN_INSTALL) {                       // the fill that waited here: its output row only
+                op.src = c.store + (uint64_t)lw.waiting_node(local) * c.row_bytes;
+                op.dst_out = lw.pending_out(idx, local, pd);
+            }
+        } else if (kind == PLAN_INSTALL) {
             if (open_fill) {                                  // superseded before it ever ran: output only
                 fills[pd].dst_line = NO_LINE;
                 const uint32_t lt = fills[pd].late;
@@ -86,21 +131,32 @@ __device__ __forceinline__ void queue_entry(const CacheView<IdT>& c, const Accum
             } else {
                 op.dst_line = idx;
             }
-            c.fillgrp[idx] = group;
-            c.pending[idx] = q;
+            lw.note_fill(idx, local, group, q, dst);
         }
         fills[q] = op;
     }
+    if constexpr (LineWords::deferred) {
+        if (valid && kind == PLAN_INSTALL) lw.wait_fill(local, group, (uint32_t)v, is_late, dst);
+    }
     if (is_wait) {
-        wcopies[w].src = fills[pd].dst_out;
+        wcopies[w].src = lw.pending_out(idx, local, pd);
         wcopies[w].dst = dst;
     }
     if (is_ready) {
         const uint32_t r = rbase + (uint32_t)__popcll(rb & below);
         rcopies[r].src = c.cache_data + idx * c.line_bytes;
         rcopies[r].dst = dst;
-        c.hitgrp[idx] = group;
+        lw.note_hit(idx, local, group);
     }
+}
+
+template <typename IdT>
+__device__ __forceinline__ void queue_entry(const CacheView<IdT>& c, const AccumView& a, uint32_t group, bool valid,
+                                            uint64_t j, uint64_t e, uint64_t v, char* __restrict__ out,
+                                            IdT* __restrict__ unique_out) {
+    const LineWordsGlobal lw{c.pending, c.fillgrp, c.hitgrp, a.fills[group & 1u]};
+    const PlacesGlobal places{c.ctl, group & 1u};
+    queue_entry(c, a, lw, places, group, valid, j, e, v, 0u, out, unique_out);
 }
 
 __device__ __forceinline__ uint32_t ld_agent(const uint32_t* p) {

@@ -197,6 +197,17 @@ void launch_settle(const CacheView<IdT>& c, const AccumView& a, uint32_t group, 
                    const uint32_t* n_u, uint64_t n_upper, const uint64_t* plan, BatchHdr* hdr, char* out,
                    IdT* unique_out, StatsRec* rec, uint64_t seq, hipStream_t s);
 
+// Division of a 32-bit number by a divisor fixed on the host: the quotient is the high half of the product with
+// ceil(2^64 / d), exact for every 32-bit dividend (d = 1 is its own case: that multiplier does not fit).
+struct FastDiv {
+    unsigned long long magic;
+    uint32_t d;
+};
+inline FastDiv make_fast_div(uint32_t d) { return FastDiv{d <= 1 ? 0ull : ~0ull / d + 1, d}; }
+__device__ __forceinline__ uint32_t fast_div(const FastDiv& f, uint32_t v) {
+    return f.d <= 1 ? v : (uint32_t)__umul64hi((unsigned long long)v, f.magic);
+}
+
 // ---- merged iterations: k steps (push one list, gather the window's head) in one call
 template <typename IdT>
 struct ManyPushes {                     // the lists the call pushes, one workgroup each
@@ -226,6 +237,11 @@ struct ManySteps {
     uint8_t head_list[MANY_MAX];        // step i's head, as an index into `list`
     uint8_t pushed_list[MANY_MAX];      // the list pushed in step i (MANY_NO_LIST: none)
     uint32_t share_cap;                 // entries of one list a workgroup can keep (<= its thread count)
+    FastDiv div_sets;                   // division by the number of sets
+    uint32_t wg_shift;                  // the launch has 2^wg_shift workgroups
+    uint32_t resident;                  // the workgroups keep their sets' state in LDS for the length of the kernel
+    uint32_t sets_per_wg;               // places for sets in that LDS: ceil(n_sets / workgroups)
+    uint32_t rounds;                    // nodes per set: ceil(n_rows / n_sets)
 };
 constexpr uint8_t MANY_NO_LIST = 0xFF;
 uint64_t many_max_rows();

@@ -37,8 +37,9 @@ namespace {
 constexpr int DS_THREADS = 1024;
 constexpr int CM_THREADS = 1024;
 constexpr int CM_UNROLL = 4;               // list entries a thread fetches before it looks at any
+constexpr int CM_SCAN = 8;                 // list entries a thread has in flight when it picks out its workgroup's
 constexpr uint32_t CM_NONE = 0xFFFFFFFFu;  // not a CPU-buffer row
-constexpr uint64_t MANY_POOL_MAX_BYTES = 128 * 1024;   // of a CU's 160 KiB of LDS
+constexpr uint64_t MANY_LDS_MAX_BYTES = 152 * 1024;    // dynamic, of a CU's 160 KiB of LDS
 
 template <typename IdT>
 __global__ __launch_bounds__(DS_THREADS) void dedup_small_kernel(ManyPushes<IdT> p, uint64_t n_rows, Ctl* ctl) {
@@ -117,27 +118,105 @@ __device__ __forceinline__ void raise_counters(const CacheView<IdT>& c, const Id
     }
 }
 
+// Where the steps of a merged call find the state they read and write: the tags and stamps of a set's lines,
+// its miss mask, the future-reuse counters of the nodes that map to it, and the words the accumulator keeps per
+// line.  `slot` names a set in that place, `node` a node's counter.
+//
+// In device memory, where the per-step kernels keep it: a set by its number, a node by its ID.
+template <typename IdT, int WAYS>
+struct StateInMemory {
+    static constexpr bool in_lds = false;
+    const CacheView<IdT>& c;
+    LineWordsGlobal lw;
+    __device__ __forceinline__ uint32_t slot_of(uint32_t set, uint32_t) const { return set; }
+    __device__ __forceinline__ uint32_t node_of(uint32_t, uint32_t, uint32_t v) const { return v; }
+    __device__ __forceinline__ uint32_t node_of_tag(uint32_t, uint32_t tag) const { return tag; }
+    __device__ __forceinline__ IdT* tags(uint32_t slot) const { return c.tags + (uint64_t)slot * WAYS; }
+    __device__ __forceinline__ int32_t* stamps(uint32_t slot) const { return c.stamps + (uint64_t)slot * WAYS; }
+    __device__ __forceinline__ uint8_t* counter(uint32_t node) const { return c.reuse + node; }
+    __device__ __forceinline__ unsigned long long* miss_words(uint32_t slot) const {
+        return reinterpret_cast<unsigned long long*>(c.missmask) + (uint64_t)slot * c.words_per_set;
+    }
+    __device__ __forceinline__ uint32_t local_line(uint32_t, int) const { return 0; }
+};
+
+// The per-line words of the accumulator for the lines of this workgroup's sets, in LDS.  Deferred: an installed
+// line's fill waits here (pend = its node, bit 31 = it fills the line late; pout = its output row) while
+// fgrp is the call's group.
+struct LineWordsLds {
+    static constexpr bool deferred = true;
+    uint32_t* pend;
+    uint32_t* fgrp;
+    uint32_t* hgrp;
+    char** pout;
+    __device__ __forceinline__ uint32_t fill_group(uint64_t, uint32_t local) const { return fgrp[local]; }
+    __device__ __forceinline__ uint32_t hit_group(uint64_t, uint32_t local) const { return hgrp[local]; }
+    __device__ __forceinline__ uint32_t pending_fill(uint64_t, uint32_t local) const { return pend[local]; }
+    __device__ __forceinline__ void* pending_out(uint64_t, uint32_t local, uint32_t) const { return pout[local]; }
+    __device__ __forceinline__ uint32_t waiting_node(uint32_t local) const { return pend[local] & 0x7FFFFFFFu; }
+    __device__ __forceinline__ void wait_fill(uint32_t local, uint32_t group, uint32_t node, bool late, char* dst) const {
+        fgrp[local] = group;
+        pend[local] = node | (late ? 0x80000000u : 0u);
+        pout[local] = dst;
+    }
+    __device__ __forceinline__ void note_fill(uint64_t, uint32_t, uint32_t, uint32_t, char*) const {}
+    __device__ __forceinline__ void note_hit(uint64_t, uint32_t local, uint32_t group) const { hgrp[local] = group; }
+};
+
+// In this workgroup's LDS, for the length of the kernel: set me + x * n_wg is slot x; the node of round r of that
+// set (ID = set + r * n_sets) is counter x * rounds + r.
+template <typename IdT, int WAYS>
+struct StateInLds {
+    static constexpr bool in_lds = true;
+    IdT* s_tag;
+    int32_t* s_stamp;
+    uint8_t* s_reuse;
+    unsigned long long* s_mm;
+    uint32_t rounds, words_per_set;
+    FastDiv div_sets;
+    LineWordsLds lw;
+    __device__ __forceinline__ uint32_t slot_of(uint32_t, uint32_t local_set) const { return local_set; }
+    __device__ __forceinline__ uint32_t node_of(uint32_t slot, uint32_t round, uint32_t) const { return slot * rounds + round; }
+    __device__ __forceinline__ uint32_t node_of_tag(uint32_t slot, uint32_t tag) const {
+        return slot * rounds + fast_div(div_sets, tag);
+    }
+    __device__ __forceinline__ IdT* tags(uint32_t slot) const { return s_tag + slot * WAYS; }
+    __device__ __forceinline__ int32_t* stamps(uint32_t slot) const { return s_stamp + slot * WAYS; }
+    __device__ __forceinline__ uint8_t* counter(uint32_t node) const { return s_reuse + node; }
+    __device__ __forceinline__ unsigned long long* miss_words(uint32_t slot) const { return s_mm + slot * words_per_set; }
+    __device__ __forceinline__ uint32_t local_line(uint32_t slot, int way) const { return slot * WAYS + (uint32_t)way; }
+};
+
+// List positions out of a stretch of each list that the workgroup took for the whole call (as many places as it
+// has entries: none of its entries needs more than one place per list); what is left of a stretch at the end is
+// filled with operations that do nothing.
+struct PlacesLocal {
+    const uint32_t* base;                                     // LDS: the stretches' first places
+    uint32_t* used;                                           // LDS: places handed out so far
+    __device__ __forceinline__ uint32_t take(int list, uint32_t n) const { return base[list] + atomicAdd(&used[list], n); }
+};
+
 // The way a missed ID takes in its set, or -1 when the set has no evictable way left for it: the k-th miss of a
 // set (ascending ID) takes the k-th evictable way in (stamp, way) order (seeded hash order under the random
 // policy).  Reads the set's stamps, the counters of the nodes it holds and its miss mask as they are now: the
 // caller has a barrier between the minibatch's probe and this.
-template <typename IdT, int WAYS>
-__device__ __forceinline__ int pick_way(const CacheView<IdT>& c, uint64_t set, uint64_t round, int32_t stamp,
-                                        const IdT (&tg)[WAYS]) {
-    const uint64_t line0 = set * WAYS;
-    int32_t st[WAYS];
+template <typename IdT, int WAYS, typename State>
+__device__ __forceinline__ int pick_way(const CacheView<IdT>& c, const State& st, uint32_t slot, uint64_t set,
+                                        uint64_t round, int32_t stamp, const IdT (&tg)[WAYS]) {
+    const int32_t* sp = st.stamps(slot);
+    int32_t stm[WAYS];
 #pragma unroll
-    for (int w = 0; w < WAYS; w++) st[w] = c.stamps[line0 + w];
+    for (int w = 0; w < WAYS; w++) stm[w] = sp[w];
     uint8_t ru[WAYS];
 #pragma unroll
-    for (int w = 0; w < WAYS; w++) ru[w] = tg[w] < 0 ? (uint8_t)0 : c.reuse[(uint64_t)tg[w]];
+    for (int w = 0; w < WAYS; w++) ru[w] = tg[w] < 0 ? (uint8_t)0 : *st.counter(st.node_of_tag(slot, (uint32_t)tg[w]));
     uint64_t key[WAYS];
     uint32_t n_ev = 0;
 #pragma unroll
     for (int w = 0; w < WAYS; w++) {
         const bool empty = tg[w] < 0;
-        const bool ev = st[w] != stamp && ru[w] == 0;         // untouched in this minibatch, no buffered future use
-        uint64_t order = (uint64_t)(uint32_t)(st[w] + 1);
+        const bool ev = stm[w] != stamp && ru[w] == 0;        // untouched in this minibatch, no buffered future use
+        uint64_t order = (uint64_t)(uint32_t)(stm[w] + 1);
         if (c.policy == 1)
             order = empty ? 0ull
                           : 1ull + (mix64(mix64(mix64(c.policy_key ^ (uint64_t)(uint32_t)stamp) ^ set) ^ (uint64_t)w) >> 9);
@@ -145,7 +224,7 @@ __device__ __forceinline__ int pick_way(const CacheView<IdT>& c, uint64_t set, u
         n_ev += ev;
     }
     uint32_t rank = 0;                                        // of this miss among its set's misses, ascending ID
-    const uint64_t* mm = c.missmask + set * c.words_per_set;
+    const unsigned long long* mm = st.miss_words(slot);
     const uint32_t wi = (uint32_t)(round >> 6);
     for (uint32_t x = 0; x < wi; x++) rank += (uint32_t)__popcll(mm[x]);
     rank += (uint32_t)__popcll(mm[wi] & ((1ull << (round & 63)) - 1));
@@ -247,7 +326,8 @@ __device__ void steps_from_memory(const CacheView<IdT>& c, const AccumView& a, u
                     IdT tg[WAYS];
 #pragma unroll
                     for (int w = 0; w < WAYS; w++) tg[w] = c.tags[set * WAYS + w];
-                    const int way = pick_way<IdT, WAYS>(c, set, round, stamp, tg);
+                    const StateInMemory<IdT, WAYS> st{c, LineWordsGlobal{c.pending, c.fillgrp, c.hitgrp, a.fills[group & 1u]}};
+                    const int way = pick_way<IdT, WAYS>(c, st, (uint32_t)set, set, round, stamp, tg);
                     if (way < 0) {
                         plan[j] = PLAN_BYPASS << PLAN_SHIFT;
                         bypasses++;
@@ -307,36 +387,181 @@ __device__ void steps_from_memory(const CacheView<IdT>& c, const AccumView& a, u
     }
 }
 
+// The barrier between two phases of a step.  With the state in LDS a phase reads nothing from device memory that
+// the kernel writes, so only the LDS traffic has to be through: the stores to the group's lists and to the
+// callers' buffers stay in flight (beside a row mover that saturates the host link their acknowledgements take
+// microseconds).
+template <bool LDS_ONLY>
+__device__ __forceinline__ void phase_barrier() {
+    if constexpr (LDS_ONLY) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+    } else {
+        __syncthreads();
+    }
+}
+
 // one wavefront's count of a flag, added to a counter in LDS
 __device__ __forceinline__ void wave_count(uint32_t* counter, bool flag) {
     const uint64_t b = __ballot(flag);
     if (b && (threadIdx.x & 63) == 0) atomicAdd(counter, (uint32_t)__popcll(b));
 }
 
+// The steps for a workgroup whose entries of every list are in its LDS pool: one thread per entry, and what it
+// learns of its entry stays in its registers from phase to phase.  Between the phases only workgroup barriers:
+// what a phase reads was written by this same workgroup (its sets' tags, stamps and miss masks, its nodes'
+// counters, its own list operations), and a barrier orders memory within a workgroup.
+template <typename IdT, int WAYS, typename State>
+__device__ __forceinline__ void steps_from_pool(const CacheView<IdT>& c, const AccumView& a, const State& st,
+                                                uint32_t group, const ManySteps<IdT>& m, uint32_t n_ok, uint32_t stamp0,
+                                                const IdT* pool_v, const uint32_t* pool_j, const uint32_t* pool_cpu,
+                                                const uint32_t* own_n, uint32_t (*cnt)[5], const PlacesLocal& places) {
+    const uint32_t tid = threadIdx.x;
+    const uint32_t cap = m.share_cap;
+    const uint32_t n_sets = (uint32_t)c.n_sets;
+    // the list pushed in step 0: one more buffered future use for each of its nodes (Section 3.4, Fig. 6)
+    if (m.pushed_list[0] != MANY_NO_LIST && tid < own_n[m.pushed_list[0]]) {
+        const uint32_t pv = (uint32_t)pool_v[(size_t)m.pushed_list[0] * cap + tid];
+        const uint32_t round = fast_div(m.div_sets, pv), set = pv - round * n_sets;
+        uint8_t* ctr = st.counter(st.node_of(st.slot_of(set, set >> m.wg_shift), round, pv));
+        *ctr = (uint8_t)(*ctr + 1);
+    }
+    phase_barrier<State::in_lds>();
+    for (uint32_t i = 0; i < n_ok; i++) {
+        const int32_t stamp = (int32_t)(stamp0 + i);
+        const uint32_t h = m.head_list[i];
+        const uint32_t n_h = own_n[h];
+        const bool have = tid < n_h;
+        const bool wave_has = (tid & ~63u) < n_h;
+        uint64_t e = 0;
+        uint32_t v = 0, j = 0, set = 0, round = 0, slot = 0, local = 0;
+        bool miss = false;
+        IdT tg[WAYS];
+#pragma unroll
+        for (int w = 0; w < WAYS; w++) tg[w] = (IdT)-1;
+        // ---- probe, against the state at the start of the minibatch
+        if (have) {
+            v = (uint32_t)pool_v[(size_t)h * cap + tid];
+            j = pool_j[(size_t)h * cap + tid];
+            const uint32_t cpu_row = pool_cpu[(size_t)h * cap + tid];
+            round = fast_div(m.div_sets, v);
+            set = v - round * n_sets;
+            slot = st.slot_of(set, set >> m.wg_shift);
+            uint8_t* ctr = st.counter(st.node_of(slot, round, v));
+            const uint8_t r = *ctr;
+            if (cpu_row != CM_NONE) {
+                e = (PLAN_CPU << PLAN_SHIFT) | cpu_row;
+            } else {
+                const IdT* row = st.tags(slot);
+                int way = -1;
+#pragma unroll
+                for (int w = 0; w < WAYS; w++) {
+                    tg[w] = row[w];
+                    if ((uint64_t)tg[w] == (uint64_t)v) way = w;   // empty lines hold -1
+                }
+                if (way >= 0) {
+                    st.stamps(slot)[way] = stamp;
+                    e = (PLAN_HIT << PLAN_SHIFT) | ((uint64_t)set * WAYS + (uint32_t)way);
+                    local = st.local_line(slot, way);
+                } else {
+                    miss = true;
+                    e = PLAN_MISS_TBD << PLAN_SHIFT;
+                    atomicOr(st.miss_words(slot) + (round >> 6), 1ull << (round & 63));
+                }
+            }
+            *ctr = (uint8_t)(r - 1);                          // this minibatch's own entry leaves the counters
+        }
+        if (wave_has) {
+            wave_count(&cnt[i][0], have && (e >> PLAN_SHIFT) == PLAN_HIT);
+            wave_count(&cnt[i][1], have && (e >> PLAN_SHIFT) == PLAN_CPU);
+            wave_count(&cnt[i][2], miss);
+        }
+        phase_barrier<State::in_lds>();
+        // ---- victims
+        if (cnt[i][2]) {
+            if (miss) {
+                const int way = pick_way<IdT, WAYS>(c, st, slot, (uint64_t)set, (uint64_t)round, stamp, tg);
+                if (way < 0) {
+                    e = PLAN_BYPASS << PLAN_SHIFT;
+                } else {
+                    e = (PLAN_INSTALL << PLAN_SHIFT) | ((uint64_t)set * WAYS + (uint32_t)way);
+                    local = st.local_line(slot, way);
+                }
+            }
+            if (wave_has) {
+                wave_count(&cnt[i][3], miss && (e >> PLAN_SHIFT) == PLAN_BYPASS);
+                wave_count(&cnt[i][4], miss && (e >> PLAN_SHIFT) == PLAN_INSTALL);
+            }
+            phase_barrier<State::in_lds>();
+        }
+        // ---- publish tags and stamps, clear the miss mask, queue every row into the open group's lists; the
+        // next step's pushed list enters the counters: this step's victims are chosen, and the next step's
+        // probe, which must see them, waits behind the barrier
+        const uint32_t pl = i + 1 < m.k ? m.pushed_list[i + 1] : MANY_NO_LIST;
+        if (pl != MANY_NO_LIST && tid < own_n[pl]) {
+            const uint32_t pv = (uint32_t)pool_v[(size_t)pl * cap + tid];
+            const uint32_t pr = fast_div(m.div_sets, pv), ps = pv - pr * n_sets;
+            uint8_t* ctr = st.counter(st.node_of(st.slot_of(ps, ps >> m.wg_shift), pr, pv));
+            *ctr = (uint8_t)(*ctr + 1);
+        }
+        if (miss) {
+            if ((e >> PLAN_SHIFT) == PLAN_INSTALL) {
+                const uint32_t way = (uint32_t)(e & PLAN_INDEX_MASK) - set * WAYS;
+                st.tags(slot)[way] = (IdT)v;
+                st.stamps(slot)[way] = stamp;
+            }
+            st.miss_words(slot)[round >> 6] = 0ull;
+        }
+        if (wave_has)
+            queue_entry(c, a, st.lw, places, group, have, (uint64_t)j, e, (uint64_t)v, local, m.out[i], m.unique_out[i]);
+        phase_barrier<State::in_lds>();
+    }
+}
+
 template <typename IdT, int WAYS>
 __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT> c, AccumView a, uint32_t group,
                                                                    ManySteps<IdT> m, uint64_t* __restrict__ plan_all,
                                                                    StatsRec* ring, uint32_t ring_size) {
-    // This workgroup's entries of every list, picked out once: share_cap slots per list (ID, position in the
-    // list, CPU-buffer row or CM_NONE), filled in no particular order.
-    extern __shared__ unsigned long long pool_raw[];
+    // Dynamic LDS.  The pool: this workgroup's entries of every list, picked out once: share_cap places per list
+    // (ID, position in the list, CPU-buffer row or CM_NONE), filled in no particular order.  With m.resident,
+    // also the state of this workgroup's sets and nodes for the length of the kernel.
+    extern __shared__ unsigned long long lds_raw[];
     __shared__ uint32_t list_n[2 * MANY_MAX];                 // entries of each list
+    __shared__ uint32_t list_off[2 * MANY_MAX + 1];           // entries of the lists before it
+    __shared__ const IdT* list_ptr[2 * MANY_MAX];
     __shared__ uint32_t own_n[2 * MANY_MAX];                  // of which this workgroup's
     __shared__ uint32_t cnt[MANY_MAX][5];                     // per step: hits, CPU-buffer hits, misses, bypasses, line fills
     __shared__ uint32_t cnt_mem[5];
     __shared__ uint32_t overflow;
     __shared__ uint32_t is_last;
+    __shared__ uint32_t place_base[3], place_used[3], place_n;
     Ctl* ctl = c.ctl;
+    // A chain of short dependent steps: where it shares a compute unit with wavefronts of a row mover, it goes first.
+    __builtin_amdgcn_s_setprio(3);
     const uint32_t tid = threadIdx.x;
     const uint32_t n_wg = gridDim.x, me = blockIdx.x;
     const uint32_t stamp0 = ctl->stamp;
     const uint32_t cap = m.share_cap;
-    IdT* pool_v = reinterpret_cast<IdT*>(pool_raw);
-    uint32_t* pool_j = reinterpret_cast<uint32_t*>(pool_v + (size_t)m.n_lists * cap);
-    uint32_t* pool_cpu = pool_j + (size_t)m.n_lists * cap;
+    const uint32_t n_sets = (uint32_t)c.n_sets;
+    const uint32_t spw = m.resident ? m.sets_per_wg : 0;      // places for sets, their lines, miss-mask words, nodes
+    const uint32_t n_l = spw * WAYS, n_mw = spw * c.words_per_set, n_nodes = spw * m.rounds;
+    const size_t n_pool = (size_t)m.n_lists * cap;
+    char** s_pout = reinterpret_cast<char**>(lds_raw);
+    unsigned long long* s_mm = lds_raw + n_l;
+    IdT* s_tag = reinterpret_cast<IdT*>(s_mm + n_mw);
+    IdT* pool_v = s_tag + n_l;
+    uint32_t* pool_j = reinterpret_cast<uint32_t*>(pool_v + n_pool);
+    uint32_t* pool_cpu = pool_j + n_pool;
+    int32_t* s_stamp = reinterpret_cast<int32_t*>(pool_cpu + n_pool);
+    uint32_t* s_pend = reinterpret_cast<uint32_t*>(s_stamp + n_l);
+    uint32_t* s_fgrp = s_pend + n_l;
+    uint32_t* s_hgrp = s_fgrp + n_l;
+    uint8_t* s_reuse = reinterpret_cast<uint8_t*>(s_hgrp + n_l);
 
     for (uint32_t l = tid; l < m.n_lists; l += blockDim.x) {
         list_n[l] = ctl->win_n[m.list_slot[l]];
+        list_ptr[l] = m.list[l];
         own_n[l] = 0;
     }
     for (uint32_t x = tid; x < MANY_MAX * 5; x += blockDim.x) cnt[x / 5][x % 5] = 0;
@@ -347,32 +572,46 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
     uint32_t n_ok = ld_agent(&ctl->error) == 0 ? m.k : 0;
     for (uint32_t i = 0; i < n_ok; i++)
         if (list_n[m.head_list[i]] > m.out_capacity[i]) n_ok = i;
-
-    // ---- every list once: the IDs of this workgroup's sets go to its LDS
-    if (cap && n_ok) {
+    if (tid == 0) {
+        uint32_t off = 0;
         for (uint32_t l = 0; l < m.n_lists; l++) {
-            const IdT* __restrict__ L = m.list[l];
-            const uint32_t n = list_n[l];
-            for (uint32_t base = tid; base < n; base += blockDim.x * CM_UNROLL) {
-                uint64_t vv[CM_UNROLL];
+            list_off[l] = off;
+            off += list_n[l];
+        }
+        list_off[m.n_lists] = off;
+    }
+    __syncthreads();
+
+    // ---- every list once: the IDs of this workgroup's sets go to its LDS.  The lists are read as one long
+    // sequence, eight entries per thread in flight whichever lists they fall into: the pass waits for memory a
+    // few times, not once per list.
+    if (cap && n_ok) {
+        const uint32_t total = list_off[m.n_lists];
+        uint32_t l = 0;                                       // the list this thread's next entry falls into
+        for (uint32_t f0 = tid; f0 < total; f0 += blockDim.x * CM_SCAN) {
+            uint32_t vv[CM_SCAN], jj[CM_SCAN], ll[CM_SCAN];
 #pragma unroll
-                for (int u = 0; u < CM_UNROLL; u++) {
-                    const uint32_t j = base + (uint32_t)u * blockDim.x;
-                    vv[u] = j < n ? (uint64_t)L[j] : ~0ull;
+            for (int u = 0; u < CM_SCAN; u++) {
+                const uint32_t f = f0 + (uint32_t)u * blockDim.x;
+                vv[u] = ~0u;
+                if (f < total) {
+                    while (f >= list_off[l + 1]) l++;
+                    ll[u] = l;
+                    jj[u] = f - list_off[l];
+                    vv[u] = (uint32_t)list_ptr[l][jj[u]];     // (a table of this kind has far fewer than 2^32 rows)
                 }
+            }
 #pragma unroll
-                for (int u = 0; u < CM_UNROLL; u++) {
-                    if (vv[u] == ~0ull) continue;
-                    uint64_t set, round;
-                    set_and_round(c, vv[u], &set, &round);
-                    if (!owns(c, set, n_wg, me)) continue;
-                    const uint32_t pos = atomicAdd(&own_n[l], 1u);
-                    if (pos < cap) {
-                        pool_v[(size_t)l * cap + pos] = (IdT)vv[u];
-                        pool_j[(size_t)l * cap + pos] = base + (uint32_t)u * blockDim.x;
-                    } else {
-                        overflow = 1;
-                    }
+            for (int u = 0; u < CM_SCAN; u++) {
+                if (vv[u] == ~0u) continue;
+                const uint32_t set = vv[u] - fast_div(m.div_sets, vv[u]) * n_sets;
+                if ((set & (n_wg - 1)) != me) continue;       // (the number of workgroups is a power of two)
+                const uint32_t pos = atomicAdd(&own_n[ll[u]], 1u);
+                if (pos < cap) {
+                    pool_v[(size_t)ll[u] * cap + pos] = (IdT)vv[u];
+                    pool_j[(size_t)ll[u] * cap + pos] = jj[u];
+                } else {
+                    overflow = 1;
                 }
             }
         }
@@ -382,113 +621,134 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
     if (from_memory) {
         steps_from_memory<IdT, WAYS>(c, a, group, m, plan_all, n_ok, stamp0, cnt_mem);
     } else if (n_ok) {
-        // CPU-buffer lookup (Section 3.3) of every entry that will be gathered: the buffer is constant
-        for (uint32_t x = tid; x < m.n_lists * cap; x += blockDim.x) {
-            const uint32_t l = x / cap;
-            if (!m.list_is_head[l] || x - l * cap >= own_n[l]) continue;
-            uint32_t row = CM_NONE;
-            if (c.hotbits) {
-                const uint64_t v = (uint64_t)pool_v[x];
-                const uint64_t hw = c.hotbits[v >> 6];
-                const uint64_t bit = 1ull << (v & 63);
-                if (hw & bit) row = c.hotrank[v >> 6] + (uint32_t)__popcll(hw & (bit - 1));
-            }
-            pool_cpu[x] = row;
+        // A stretch of each of the group's lists for this workgroup's entries, taken once: three atomics per
+        // workgroup and call instead of three per wavefront and step.
+        if (tid == 0) {
+            uint32_t n = 0;
+            for (uint32_t i = 0; i < n_ok; i++) n += own_n[m.head_list[i]];
+            const uint32_t par = group & 1u;
+            place_n = n;
+            place_base[0] = atomicAdd(&ctl->q_fill[par], n);
+            place_base[1] = atomicAdd(&ctl->q_rcopy[par], n);
+            place_base[2] = atomicAdd(&ctl->q_wcopy[par], n);
+            place_used[0] = place_used[1] = place_used[2] = 0;
         }
-        // the list pushed in step 0: one more buffered future use for each of its nodes (Section 3.4, Fig. 6)
-        if (m.pushed_list[0] != MANY_NO_LIST && tid < own_n[m.pushed_list[0]]) {
-            const uint64_t pv = (uint64_t)pool_v[(size_t)m.pushed_list[0] * cap + tid];
-            c.reuse[pv] = (uint8_t)(c.reuse[pv] + 1);
+        const PlacesLocal places{place_base, place_used};
+        // CPU-buffer lookup (Section 3.3) of every entry that will be gathered: the buffer is constant
+        // (list_off is free again: now the workgroup's entries of the lists before a list, gathered lists only)
+        if (tid == 0) {
+            uint32_t off = 0;
+            for (uint32_t l = 0; l < m.n_lists; l++) {
+                list_off[l] = off;
+                off += m.list_is_head[l] ? own_n[l] : 0u;
+            }
+            list_off[m.n_lists] = off;
         }
         __syncthreads();
-        // Between the phases of a step only workgroup barriers: what a phase reads was written by this same
-        // workgroup (its sets' tags, stamps and miss masks, its nodes' counters, its own list operations), and a
-        // barrier orders memory within a workgroup.  Agent-wide visibility is needed once, before the ticket.
-        // One thread per entry; what it learns of its entry stays in its registers from phase to phase.
-        for (uint32_t i = 0; i < n_ok; i++) {
-            const int32_t stamp = (int32_t)(stamp0 + i);
-            const uint32_t h = m.head_list[i];
-            const uint32_t n_h = own_n[h];
-            const bool have = tid < n_h;
-            const bool wave_has = (tid & ~63u) < n_h;
-            uint64_t v = 0, e = 0, set = 0, round = 0;
-            uint32_t j = 0;
-            bool miss = false;
-            IdT tg[WAYS];
-#pragma unroll
-            for (int w = 0; w < WAYS; w++) tg[w] = (IdT)-1;
-            // ---- probe, against the state at the start of the minibatch
-            if (have) {
-                v = (uint64_t)pool_v[(size_t)h * cap + tid];
-                j = pool_j[(size_t)h * cap + tid];
-                const uint32_t cpu_row = pool_cpu[(size_t)h * cap + tid];
-                const uint8_t r = c.reuse[v];
-                set_and_round(c, v, &set, &round);
-                if (cpu_row != CM_NONE) {
-                    e = (PLAN_CPU << PLAN_SHIFT) | cpu_row;
-                } else {
-                    int way = -1;
-#pragma unroll
-                    for (int w = 0; w < WAYS; w++) {
-                        tg[w] = c.tags[set * WAYS + w];
-                        if ((uint64_t)tg[w] == v) way = w;    // empty lines hold -1
-                    }
-                    if (way >= 0) {
-                        const uint64_t line = set * WAYS + (uint32_t)way;
-                        c.stamps[line] = stamp;
-                        e = (PLAN_HIT << PLAN_SHIFT) | line;
-                    } else {
-                        miss = true;
-                        e = PLAN_MISS_TBD << PLAN_SHIFT;
-                        atomicOr(reinterpret_cast<unsigned long long*>(c.missmask) + set * c.words_per_set + (round >> 6),
-                                 1ull << (round & 63));
-                    }
+        {
+            const uint32_t total = list_off[m.n_lists];
+            uint32_t l = 0;
+            for (uint32_t f = tid; f < total; f += blockDim.x) {
+                while (f >= list_off[l + 1]) l++;
+                const uint32_t x = l * cap + (f - list_off[l]);
+                uint32_t row = CM_NONE;
+                if (c.hotbits) {
+                    const uint64_t v = (uint64_t)pool_v[x];
+                    const uint64_t hw = c.hotbits[v >> 6];
+                    const uint32_t before = c.hotrank[v >> 6];    // (both loads at once)
+                    const uint64_t bit = 1ull << (v & 63);
+                    if (hw & bit) row = before + (uint32_t)__popcll(hw & (bit - 1));
                 }
-                c.reuse[v] = (uint8_t)(r - 1);                // this minibatch's own entry leaves the counters
+                pool_cpu[x] = row;
             }
-            if (wave_has) {
-                wave_count(&cnt[i][0], have && (e >> PLAN_SHIFT) == PLAN_HIT);
-                wave_count(&cnt[i][1], have && (e >> PLAN_SHIFT) == PLAN_CPU);
-                wave_count(&cnt[i][2], miss);
+        }
+        if (m.resident) {
+            // ---- the state of this workgroup's sets and nodes comes into LDS (the miss masks are clear
+            // between gathers)
+            for (uint32_t x = tid; x < n_l; x += blockDim.x) {
+                const uint32_t set = me + (x / WAYS) * n_wg;
+                if (set >= n_sets) continue;
+                const uint64_t line = (uint64_t)set * WAYS + x % WAYS;
+                s_tag[x] = c.tags[line];
+                s_stamp[x] = c.stamps[line];
+                s_pend[x] = c.pending[line];
+                s_fgrp[x] = c.fillgrp[line];
+                s_hgrp[x] = c.hitgrp[line];
+                s_pout[x] = nullptr;                          // (read only for fills queued by this call's group)
+            }
+            for (uint32_t x = tid; x < n_mw; x += blockDim.x) s_mm[x] = 0ull;
+            for (uint32_t x = tid; x < n_nodes; x += blockDim.x) {
+                const uint32_t ls = x / m.rounds;
+                const uint64_t v = (uint64_t)(me + ls * n_wg) + (uint64_t)(x - ls * m.rounds) * n_sets;
+                if (me + ls * n_wg < n_sets && v < c.n_rows) s_reuse[x] = c.reuse[v];
             }
             __syncthreads();
-            // ---- victims
-            if (cnt[i][2]) {
-                if (miss) {
-                    const int way = pick_way<IdT, WAYS>(c, set, round, stamp, tg);
-                    e = way < 0 ? PLAN_BYPASS << PLAN_SHIFT : (PLAN_INSTALL << PLAN_SHIFT) | (set * WAYS + (uint32_t)way);
+            const StateInLds<IdT, WAYS> st{s_tag, s_stamp, s_reuse, s_mm, m.rounds, c.words_per_set, m.div_sets,
+                                           LineWordsLds{s_pend, s_fgrp, s_hgrp, s_pout}};
+            steps_from_pool<IdT, WAYS>(c, a, st, group, m, n_ok, stamp0, pool_v, pool_j, pool_cpu, own_n, cnt, places);
+            // ---- the fills that still wait in the lines' words are queued (steps_from_pool ends behind a barrier)
+            for (uint32_t x = tid; x < n_l; x += blockDim.x) {
+                const uint32_t set = me + (x / WAYS) * n_wg;
+                if (set >= n_sets || s_fgrp[x] != group) continue;
+                const uint64_t line = (uint64_t)set * WAYS + x % WAYS;
+                const uint32_t node = s_pend[x] & 0x7FFFFFFFu;
+                const bool late = (s_pend[x] >> 31) != 0;
+                const uint32_t par = group & 1u;
+                const uint32_t q = places.take(0, 1u);
+                if (q < a.cap) {
+                    FillOp op;
+                    op.src = c.store + (uint64_t)node * c.row_bytes;
+                    op.dst_out = s_pout[x];
+                    op.dst_line = late ? NO_LINE : line;
+                    op.late = NO_OP;
+                    op.pad = 0;
+                    a.fills[par][q] = op;
                 }
-                if (wave_has) {
-                    wave_count(&cnt[i][3], miss && (e >> PLAN_SHIFT) == PLAN_BYPASS);
-                    wave_count(&cnt[i][4], miss && (e >> PLAN_SHIFT) == PLAN_INSTALL);
+                if (late) {                                   // after the rcopies that still read the line's old bytes
+                    const uint32_t w = places.take(2, 1u);
+                    if (w < a.cap) a.wcopies[par][w] = CopyOp{s_pout[x], c.cache_data + line * c.line_bytes};
                 }
-                __syncthreads();
+                s_pend[x] = q;                                // what the per-step kernels leave there: the fill's place
             }
-            // ---- publish tags and stamps, clear the miss mask, queue every row into the open group's lists;
-            // the next step's pushed list enters the counters: this step's victims are chosen, and the next
-            // step's probe, which must see them, waits behind the barrier
-            const uint32_t pl = i + 1 < m.k ? m.pushed_list[i + 1] : MANY_NO_LIST;
-            const bool raise = pl != MANY_NO_LIST && tid < own_n[pl];
-            uint64_t pv = 0;
-            uint8_t pr = 0;
-            if (raise) {
-                pv = (uint64_t)pool_v[(size_t)pl * cap + tid];
-                pr = c.reuse[pv];
-            }
-            if (miss) {
-                if ((e >> PLAN_SHIFT) == PLAN_INSTALL) {
-                    const uint64_t line = e & PLAN_INDEX_MASK;
-                    c.tags[line] = (IdT)v;
-                    c.stamps[line] = stamp;
-                }
-                c.missmask[set * c.words_per_set + (round >> 6)] = 0ull;
-            }
-            if (wave_has) queue_entry(c, a, group, have, (uint64_t)j, e, v, m.out[i], m.unique_out[i]);
-            if (raise) c.reuse[pv] = (uint8_t)(pr + 1);
             __syncthreads();
+            // ---- and the state goes back
+            for (uint32_t x = tid; x < n_l; x += blockDim.x) {
+                const uint32_t set = me + (x / WAYS) * n_wg;
+                if (set >= n_sets) continue;
+                const uint64_t line = (uint64_t)set * WAYS + x % WAYS;
+                c.tags[line] = s_tag[x];
+                c.stamps[line] = s_stamp[x];
+                c.pending[line] = s_pend[x];
+                c.fillgrp[line] = s_fgrp[x];
+                c.hitgrp[line] = s_hgrp[x];
+            }
+            for (uint32_t x = tid; x < n_nodes; x += blockDim.x) {
+                const uint32_t ls = x / m.rounds;
+                const uint64_t v = (uint64_t)(me + ls * n_wg) + (uint64_t)(x - ls * m.rounds) * n_sets;
+                if (me + ls * n_wg < n_sets && v < c.n_rows) c.reuse[v] = s_reuse[x];
+            }
+        } else {
+            __syncthreads();
+            const StateInMemory<IdT, WAYS> st{c, LineWordsGlobal{c.pending, c.fillgrp, c.hitgrp, a.fills[group & 1u]}};
+            steps_from_pool<IdT, WAYS>(c, a, st, group, m, n_ok, stamp0, pool_v, pool_j, pool_cpu, own_n, cnt, places);
         }
         for (uint32_t x = tid; x < m.k * 5; x += blockDim.x)
             if (cnt[x / 5][x % 5]) atomicAdd(&ctl->many_cnt[x / 5][x % 5], cnt[x / 5][x % 5]);
+        // what is left of the three stretches: operations that do nothing (the host sizes each list for every
+        // entry of the group, so the stretches always fit; were one to end beyond its list, queue_entry has
+        // reported it and nothing is written there)
+        {
+            const uint32_t par = group & 1u;
+            const uint64_t end = a.cap;
+            FillOp none;
+            none.src = nullptr; none.dst_out = nullptr; none.dst_line = NO_LINE; none.late = NO_OP; none.pad = 0;
+            for (uint64_t x = (uint64_t)place_base[0] + place_used[0] + tid; x < (uint64_t)place_base[0] + place_n && x < end; x += blockDim.x)
+                a.fills[par][x] = none;
+            for (uint64_t x = (uint64_t)place_base[1] + place_used[1] + tid; x < (uint64_t)place_base[1] + place_n && x < end; x += blockDim.x)
+                a.rcopies[par][x] = CopyOp{nullptr, nullptr};
+            for (uint64_t x = (uint64_t)place_base[2] + place_used[2] + tid; x < (uint64_t)place_base[2] + place_n && x < end; x += blockDim.x)
+                a.wcopies[par][x] = CopyOp{nullptr, nullptr};
+        }
         __syncthreads();
     }
     // ---- the last workgroup to get here publishes the records
@@ -497,22 +757,27 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
         is_last = atomicAdd(&ctl->ticket_cls, 1u) == n_wg - 1;
     }
     __syncthreads();
-    if (!is_last || tid != 0) return;
-    __threadfence();
-    if (n_ok < m.k && ld_agent(&ctl->error) == 0) atomicCAS(&ctl->error, 0u, 7u /* -GIDS_E_SPACE: step n_ok's output */);
+    if (!is_last) return;
+    // (one thread per record: the counters of a step are five loads that wait for nothing but each other)
+    if (tid == 0) {
+        __threadfence();
+        if (n_ok < m.k && ld_agent(&ctl->error) == 0) atomicCAS(&ctl->error, 0u, 7u /* -GIDS_E_SPACE: step n_ok's output */);
+    }
+    __syncthreads();
     const uint32_t err = ld_agent(&ctl->error);
-    uint32_t queued = 0;
-    for (uint32_t i = 0; i < m.k; i++) {
+    if (tid < m.k) {
+        const uint32_t i = tid;
         StatsRec* rec = ring + (m.seq0 + i) % ring_size;
         const bool ran = i < n_ok;
         const uint32_t n = ran ? list_n[m.head_list[i]] : 0u;
+        uint32_t queued = n;
+        for (uint32_t x = 0; x < i && x < n_ok; x++) queued += list_n[m.head_list[x]];
         rec->n_unique = n;
         rec->n_hit = ld_agent(&ctl->many_cnt[i][0]);
         rec->n_cpu_hit = ld_agent(&ctl->many_cnt[i][1]);
         rec->n_miss = ld_agent(&ctl->many_cnt[i][2]);
         rec->n_bypass = ld_agent(&ctl->many_cnt[i][3]);
         rec->n_line_fills = ld_agent(&ctl->many_cnt[i][4]);
-        queued += n;
         const bool closes = i + 1 == m.k;                     // the call's steps are one group, closed by its last
         rec->n_pending = closes ? 0u : queued;
         rec->flushed = closes ? 1 : 0;
@@ -520,11 +785,14 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
         ctl->grp_nu[group & 1u][i] = n;
         for (int x = 0; x < 5; x++) ctl->many_cnt[i][x] = 0;
     }
-    ctl->q_rows = 0;
-    ctl->stamp = stamp0 + n_ok;
-    ctl->ticket_cls = 0;
+    if (tid == 0) {
+        ctl->q_rows = 0;
+        ctl->stamp = stamp0 + n_ok;
+        ctl->ticket_cls = 0;
+    }
     __threadfence_system();
-    for (uint32_t i = 0; i < m.k; i++) ring[(m.seq0 + i) % ring_size].seq = m.seq0 + i;   // a record whose seq matches is complete
+    __syncthreads();
+    if (tid < m.k) ring[(m.seq0 + tid) % ring_size].seq = m.seq0 + tid;   // a record whose seq matches is complete
     __threadfence_system();
 }
 
@@ -566,7 +834,7 @@ void launch_classify_many_ways(const CacheView<IdT>& c, const AccumView& a, uint
     static bool raised = false;                               // more than the default 64 KiB has to be asked for, once
     if (lds > 49152 && !raised) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&classify_many_kernel<IdT, W>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)MANY_POOL_MAX_BYTES);
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)MANY_LDS_MAX_BYTES);
         raised = true;
     }
     hipLaunchKernelGGL((classify_many_kernel<IdT, W>), dim3(grid), dim3(threads), lds, s, c, a, group, m, plan_all,
@@ -588,22 +856,41 @@ void launch_classify_many(const CacheView<IdT>& c, const AccumView& a, uint32_t 
     if (g < 1) g = 1;
     if (g > 256) g = 256;
     if (g > c.n_sets) g = c.n_sets;                          // a workgroup without a set would only take a ticket
-    // LDS for a workgroup's own entries: the same number of slots for each list, four times the expected share
-    // where that fits; a workgroup whose share of some list is larger reads the lists from memory instead
-    if (pool_bytes > MANY_POOL_MAX_BYTES) pool_bytes = MANY_POOL_MAX_BYTES;
-    const uint64_t entry = sizeof(IdT) + 8;
-    uint64_t cap = m.n_lists ? pool_bytes / (entry * m.n_lists) : 0;
-    const uint64_t want = 4 * ((longest + g - 1) / g);
-    if (cap > want) cap = want;
+    uint32_t wg_shift = 0;                                    // a power of two: which workgroup a set belongs to and
+    while ((2ull << wg_shift) <= g) wg_shift++;               // its place there are a mask and a shift
+    g = 1ull << wg_shift;
+    m.wg_shift = wg_shift;
     static const uint32_t threads = [] {                     // a multiple of 64 up to CM_THREADS (GIDS_MANY_THREADS)
         const char* e = getenv("GIDS_MANY_THREADS");
         const long v = e ? atol(e) : CM_THREADS;
         return (uint32_t)(v >= 64 && v <= CM_THREADS ? v & ~63l : CM_THREADS);
     }();
+    static const bool resident_ok = [] {                      // GIDS_MANY_RESIDENT=0: the sets' state stays in memory
+        const char* e = getenv("GIDS_MANY_RESIDENT");
+        return !(e && atoi(e) == 0);
+    }();
+    m.div_sets = make_fast_div((uint32_t)c.n_sets);
+    // The state of a workgroup's sets for the length of the kernel, when it leaves at least half of the LDS to
+    // the lists: per line a tag, a stamp, three accumulator words and an output address; per set its miss-mask
+    // words; per node that maps to one of the sets a counter.
+    m.sets_per_wg = (uint32_t)((c.n_sets + g - 1) / g);
+    m.rounds = (uint32_t)((c.n_rows + c.n_sets - 1) / c.n_sets);
+    const uint64_t n_l = (uint64_t)m.sets_per_wg * c.ways;
+    const uint64_t state = n_l * (8 + sizeof(IdT) + 16) + (uint64_t)m.sets_per_wg * c.words_per_set * 8 +
+                           (uint64_t)m.sets_per_wg * m.rounds;
+    m.resident = resident_ok && pool_bytes && state <= MANY_LDS_MAX_BYTES / 2;
+    // LDS for a workgroup's own entries: the same number of places for each list, four times the expected share
+    // where that fits; a workgroup whose share of some list is larger reads the lists from memory instead
+    const uint64_t room = MANY_LDS_MAX_BYTES - (m.resident ? state : 0) - 16;
+    if (pool_bytes > room) pool_bytes = room;
+    const uint64_t entry = sizeof(IdT) + 8;
+    uint64_t cap = m.n_lists ? pool_bytes / (entry * m.n_lists) : 0;
+    const uint64_t want = 4 * ((longest + g - 1) / g);
+    if (cap > want) cap = want;
     if (cap > threads) cap = threads;                         // one thread per entry
     cap &= ~1ull;                                             // keeps the 32-bit arrays behind the IDs aligned
     m.share_cap = (uint32_t)cap;
-    const size_t lds = (size_t)(cap * m.n_lists * entry);
+    const size_t lds = (size_t)(cap * m.n_lists * entry + (m.resident ? state : 0) + 16);
 #define GIDS_CLASSIFY_MANY(W) \
     launch_classify_many_ways<IdT, W>(c, a, group, m, (uint32_t)g, threads, lds, plan_all, ring, ring_size, s)
     switch (c.ways) {

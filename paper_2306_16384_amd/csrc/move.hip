@@ -270,7 +270,7 @@ __global__ __launch_bounds__(MV_THREADS) void group_move_kernel(Ctl* ctl, const 
                 const uint64_t src = __shfl((uint64_t)op.src, (int)(i & 63));
                 const uint64_t dst = __shfl((uint64_t)op.dst_out, (int)(i & 63));
                 const uint64_t dl = __shfl(op.dst_line, (int)(i & 63));
-                if (i >= m) continue;
+                if (i >= m || !src) continue;                 // (a place that was taken and not needed)
                 char* line = dl == NO_LINE ? nullptr : cache_data + dl * line_bytes;
                 copy_row<G>(reinterpret_cast<const v4u*>(src), reinterpret_cast<v4u*>(dst),
                             reinterpret_cast<v4u*>(line), row_u4, sub);
@@ -290,7 +290,7 @@ __global__ __launch_bounds__(MV_THREADS) void group_move_kernel(Ctl* ctl, const 
                 const uint32_t i = i0 + grp;
                 const uint64_t src = __shfl((uint64_t)op.src, (int)(i & 63));
                 const uint64_t dst = __shfl((uint64_t)op.dst, (int)(i & 63));
-                if (i >= m) continue;
+                if (i >= m || !dst) continue;                 // (a place that was taken and not needed)
                 copy_row<G>(reinterpret_cast<const v4u*>(src), reinterpret_cast<v4u*>(dst), nullptr, row_u4, sub);
             }
         }

@@ -37,7 +37,7 @@ def with_env(knobs, make):
 
 
 def run_many(gpu, oracle, feats, batches, *, id_dtype, lines, ways, window, ks, hot=None, policy=None, pipeline="0",
-             fuse=None, pool=None, label=""):
+             fuse=None, pool=None, resident=None, label=""):
     """ks: the sizes of the merged calls, in order (0 = one plain push + gather step in between);
     cycles until every list is gathered."""
     torch, gids, GatherSession = gpu
@@ -46,7 +46,7 @@ def run_many(gpu, oracle, feats, batches, *, id_dtype, lines, ways, window, ks, 
     R = feats_u8.shape[1]
     n_b = len(batches)
     print(f"[many {label}] rows={n_rows} R={R} lines={lines} ways={ways} W={window} pipe={pipeline} fuse={fuse} "
-          f"pool={pool} ks={ks}", flush=True)
+          f"pool={pool} resident={resident} ks={ks}", flush=True)
     sim = oracle.Sim(n_rows, lines, ways, window, R, R, feats_u8)
     if hot is not None:
         sim.set_hot(hot)
@@ -63,6 +63,8 @@ def run_many(gpu, oracle, feats, batches, *, id_dtype, lines, ways, window, ks, 
         knobs["GIDS_FUSE"] = fuse
     if pool is not None:
         knobs["GIDS_MANY_POOL"] = pool
+    if resident is not None:
+        knobs["GIDS_MANY_RESIDENT"] = resident
     ses = with_env(knobs, lambda: GatherSession(n_rows, R, id_dtype, lines, ways, R, window, 1000))
     with ses:
         ses.store_view()[:] = feats_u8
@@ -164,11 +166,12 @@ def test_merged_calls_over_shapes(gpu, oracle_mod, ways, window, id_dtype, polic
                  label=f"ways{ways}/W{window}")
 
 
-@pytest.mark.parametrize("pool", ["0", "3000", "14000"])
-def test_merged_calls_with_little_or_no_lds_for_the_lists(gpu, oracle_mod, pool):
-    """A classifying workgroup keeps its own entries of every list in LDS; one whose share of some list does not
-    fit reads the lists from memory in every phase instead.  No LDS: all of them do; 14,000 bytes: about as many
-    slots as the expected share, so workgroups of both kinds run side by side in one launch."""
+@pytest.mark.parametrize("pool,resident", [("0", None), ("3000", None), ("14000", None), ("14000", "0"), (None, "0")])
+def test_merged_calls_with_little_or_no_lds(gpu, oracle_mod, pool, resident):
+    """A classifying workgroup keeps its own entries of every list in LDS, and the state of its sets as well when
+    that fits; one whose share of some list does not fit reads the lists from memory in every phase instead.  No
+    LDS: all of them do; 14,000 bytes: about as many places as the expected share, so workgroups of both kinds run
+    side by side in one launch; resident 0: the lists in LDS, the sets' state in device memory."""
     cfg = CONFIGS["tiny"]
     g = wl.make_graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max)
     table = wl.normal_table(np.float32)
@@ -176,14 +179,16 @@ def test_merged_calls_with_little_or_no_lds_for_the_lists(gpu, oracle_mod, pool)
     hot = wl.hot_nodes(g, cfg.cpu_rows)
     batches = [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds) for b in range(40)]
     run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int32, lines=cfg.cache_lines, ways=cfg.ways,
-             window=cfg.window, ks=[32, 3, 0, 5], hot=hot, pool=pool, label="tiny")
+             window=cfg.window, ks=[32, 3, 0, 5], hot=hot, pool=pool, resident=resident, label="tiny")
     rng = np.random.default_rng(91)
     n = 3000
     feats = rng.integers(0, 256, size=(n, 128), dtype=np.uint8)
     batches = zipf_lists(rng, n, 30, 500)
     batches[9] = np.arange(n, dtype=np.int64)
-    run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=8 * 11, ways=8, window=3, ks=[7, 0, 12],
-             hot=rng.choice(n, 40, replace=False), pool=pool, pipeline="1", label="small cache")
+    for policy in (None, (1, 5)):
+        run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=8 * 11, ways=8, window=3, ks=[7, 0, 12],
+                 hot=rng.choice(n, 40, replace=False), pool=pool, resident=resident, policy=policy, pipeline="1",
+                 label="small cache")
 
 
 def test_merged_calls_through_the_per_step_kernels(gpu, oracle_mod):
