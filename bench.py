@@ -449,7 +449,9 @@ def run_point(args, env, cfg, window, raws, n_pre):
     # the library then overlaps the classification of minibatch t + 1 with the row movement of minibatch t
     # small caches: the library does not overlap (unless GIDS_PIPELINE=1 forces its internal stream on)
     small = cfg.cache_lines * cfg.line_bytes < (32 << 20) and os.environ.get("GIDS_PIPELINE", "0") == "0"
-    one_stream = args.one_stream or small
+    # (merged calls classify on the library's internal stream whatever the cache size: their pushed lists come on a
+    # stream of their own as well, or the next call's classification would wait for this call's rows)
+    one_stream = args.one_stream or (small and not args.many)
     # One push stream for the whole process: HIP multiplexes streams onto a few hardware queues in creation
     # order, and a push stream that lands on the gather stream's queue has its event markers stuck behind the
     # row mover, which serialises the two (seen with the sixth stream created in a sweep).

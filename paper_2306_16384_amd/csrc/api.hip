@@ -169,6 +169,7 @@ struct gids_cache {
     bool pipelined = false;
     hipStream_t last_stream = nullptr;
     bool have_last = false;
+    bool one_stream_work = true;    // a call has queued kernels outside the internal stream since that was last brought up to date
     // Without the internal stream every kernel runs on the stream of its call: a call on another stream
     // than the previous one is ordered after it.
     int follow(hipStream_t s) {
@@ -176,6 +177,7 @@ struct gids_cache {
         if (!pipelined && have_last && s != last_stream) rc = edge(last_stream, s);
         last_stream = s;
         have_last = true;
+        one_stream_work = true;
         return rc;
     }
     // stream `to` waits for everything enqueued on `from` so far
@@ -198,6 +200,7 @@ struct gids_cache {
         }
     }
     uint64_t many_list_max = 8192;  // merged kernels for lists up to this many raw IDs (GIDS_MANY_LIST_MAX)
+    uint32_t many_meta_min = 16;        // merged calls of at least this many steps classify on the internal stream (GIDS_MANY_PIPELINE_MIN; 0: never)
     uint64_t many_pool = 128 * 1024;    // LDS for a classifying workgroup's own list entries (GIDS_MANY_POOL, bytes; 0: none)
     int fuse = 1;               // GIDS_FUSE=0: commit, queueing and counters as a kernel each; no merged kernels
     int move_blocks = 1 << 20;  // most workgroups the row mover uses for rows that stay in HBM
@@ -342,8 +345,11 @@ struct CacheT final : gids_cache {
         // Overlap costs a handful of cross-stream events per call: worth it when minibatches move megabytes.
         // Default: on for caches of 32 MiB and more; GIDS_PIPELINE=0/1 overrides.
         pipelined = lines * (uint64_t)line_bytes >= (32ull << 20);
-        if (const char* env = getenv("GIDS_PIPELINE")) pipelined = atoi(env) != 0;
-        if (pipelined) HIP_TRY(hipStreamCreateWithFlags(&meta, hipStreamNonBlocking));
+        if (const char* env = getenv("GIDS_PIPELINE")) {
+            pipelined = atoi(env) != 0;
+            if (!pipelined) many_meta_min = 0;                // 0: no internal stream at all, merged calls included
+        }
+        if (pipelined || threshold) HIP_TRY(hipStreamCreateWithFlags(&meta, hipStreamNonBlocking));
         // one slot more than lists can be buffered: the slot a push overwrites was then read by the gather
         // before the previous one, whose rows have long moved, and not by the one still moving
         // (a cache with an accumulator can take a merged call, which pushes up to MANY_MAX lists before any of
@@ -353,6 +359,7 @@ struct CacheT final : gids_cache {
         if (const char* env = getenv("GIDS_FUSE")) fuse = atoi(env) & 1;
         if (const char* env = getenv("GIDS_MANY_LIST_MAX")) many_list_max = (uint64_t)std::max(0ll, atoll(env));
         if (const char* env = getenv("GIDS_MANY_POOL")) many_pool = (uint64_t)std::max(0ll, atoll(env));
+        if (const char* env = getenv("GIDS_MANY_PIPELINE_MIN")) many_meta_min = (uint32_t)std::max(0, atoi(env));
         if (const char* env = getenv("GIDS_MOVE_BLOCKS")) {
             const int b = atoi(env);
             if (b >= 1 && b <= (1 << 20)) move_blocks = b;
@@ -850,12 +857,23 @@ struct CacheT final : gids_cache {
                      hipStream_t s) {
         int rc;
         const bool any_push = push_ids != nullptr;
-        if (any_push && (rc = follow(ps))) return rc;
-        if ((rc = follow(s))) return rc;
+        // A call of many steps classifies on the internal stream also where the cache is too small for single
+        // gathers to do so: one pair of cross-stream waits per call, and the classification of this call runs
+        // beside the row movement of the call before.
+        const bool on_meta = pipelined || (many_meta_min && k >= many_meta_min);
         hipStream_t m = s;
-        if (pipelined) {
+        if (on_meta) {
             m = meta;
+            if (!pipelined) {                                 // after whatever the one-stream calls before have queued
+                if (have_last && one_stream_work && (rc = edge(last_stream, meta))) return rc;
+                one_stream_work = false;
+                last_stream = s;                              // (this call's row movement, behind its classification)
+                have_last = true;
+            }
             if (any_push && (rc = edge(ps, meta))) return rc; // the caller's ID lists are ready in the push stream's order
+        } else {
+            if (any_push && (rc = follow(ps))) return rc;
+            if ((rc = follow(s))) return rc;
         }
         if (flush_recorded[group & 1]) HIP_TRY(hipStreamWaitEvent(m, ev_flush[group & 1], 0));
         ManyPushes<IdT> mp;
@@ -916,19 +934,17 @@ struct CacheT final : gids_cache {
         launch_dedup_small<IdT>(mp, n_push, store->n_rows, ctl, m);
         // the caller's ID buffers are read by that kernel alone: the push stream goes on as soon as it is through
         // (were it held until the classification ends, the next call's lists would be ready that much later)
-        if (pipelined && n_push && (rc = edge(meta, ps))) return rc;
+        if (on_meta && n_push && (rc = edge(meta, ps))) return rc;
         launch_classify_many<IdT>(view(), accum_view(), group, ms, longest, many_pool, many_plan, ring_dev, STATS_RING, m);
         HIP_TRY(hipGetLastError());
         const int r_last = (int)((seq + k - 1) % STATS_RING);
         for (uint32_t i = 0; i < k; i++) ev_of[(seq + i) % STATS_RING] = r_last;
-        if (pipelined) {
-            HIP_TRY(hipEventRecord(ev_meta[r_last], meta));
-        }
+        if (on_meta) HIP_TRY(hipEventRecord(ev_meta[r_last], meta));
         open_upper = total_upper;
         open_batches = k;
         uq.n = k;
         seq += k;
-        if ((rc = close_group(s, pipelined ? ev_meta[r_last] : nullptr))) return rc;
+        if ((rc = close_group(s, on_meta ? ev_meta[r_last] : nullptr))) return rc;
         HIP_TRY(hipEventRecord(events[r_last], s));
         return GIDS_OK;
     }

@@ -24,14 +24,19 @@ def gpu():
 
 
 def with_env(knobs, make):
+    """knobs: name -> value, None = not set"""
     old = {k: os.environ.get(k) for k in knobs}
-    os.environ.update(knobs)
+    for k, v in knobs.items():
+        if v is None:
+            os.environ.pop(k, None)
+        else:
+            os.environ[k] = v
     try:
         return make()
     finally:
         for k, v in old.items():
             if v is None:
-                del os.environ[k]
+                os.environ.pop(k, None)
             else:
                 os.environ[k] = v
 
@@ -58,7 +63,7 @@ def run_many(gpu, oracle, feats, batches, *, id_dtype, lines, ways, window, ks, 
             sim.push(batches[pushed])
             pushed += 1
         want.append(sim.gather(raw))
-    knobs = {"GIDS_PIPELINE": pipeline}
+    knobs = {"GIDS_PIPELINE": pipeline if pipeline in ("0", "1") else None}
     if fuse is not None:
         knobs["GIDS_FUSE"] = fuse
     if pool is not None:
@@ -74,7 +79,7 @@ def run_many(gpu, oracle, feats, batches, *, id_dtype, lines, ways, window, ks, 
             ses.set_policy(*policy)
         dev = [ses.to_device(b) for b in batches]
         torch.cuda.synchronize()
-        push_stream = torch.cuda.Stream() if pipeline == "1" else None
+        push_stream = torch.cuda.Stream() if pipeline in ("1", None) else None
         outs = [torch.full((max(len(b), 1), R), 0xA5, dtype=torch.uint8, device="cuda") for b in batches]
         uqs = [torch.full((max(len(b), 1),), -7, dtype=ses.torch_id, device="cuda") for b in batches]
         seq_of, expect_acc = {}, {}
@@ -189,6 +194,21 @@ def test_merged_calls_with_little_or_no_lds(gpu, oracle_mod, pool, resident):
         run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=8 * 11, ways=8, window=3, ks=[7, 0, 12],
                  hot=rng.choice(n, 40, replace=False), pool=pool, resident=resident, policy=policy, pipeline="1",
                  label="small cache")
+
+
+@pytest.mark.parametrize("own_push_stream", [True, False])
+def test_long_and_short_merged_calls_and_plain_steps_take_turns(gpu, oracle_mod, own_push_stream):
+    """The library's default on a small cache: calls of 16 steps and more classify on its internal stream, shorter
+    ones and plain gathers on the caller's.  Every change of stream between consecutive calls is in here."""
+    cfg = CONFIGS["tiny"]
+    g = wl.make_graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max)
+    table = wl.normal_table(np.float32)
+    feats = wl.feature_rows(cfg.seed, np.arange(cfg.n_nodes), cfg.dim, table)
+    hot = wl.hot_nodes(g, cfg.cpu_rows)
+    batches = [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds) for b in range(60)]
+    run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int32, lines=cfg.cache_lines, ways=cfg.ways,
+             window=cfg.window, ks=[16, 3, 0, 20, 0, 17, 2], hot=hot,
+             pipeline=None if own_push_stream else "unset-one-stream", label="default streams")
 
 
 def test_merged_calls_through_the_per_step_kernels(gpu, oracle_mod):
