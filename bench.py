@@ -172,14 +172,17 @@ def main() -> int:
         # the other configurations in the same line: the HBM-bound one, the mid-size one and the launch-bound one
         import copy
         result["other_workloads"] = {}
-        # (tiny twice: call by call, and 32 iterations merged per call, Section 3.2's remedy for small minibatches)
-        for name in ("resident", "medium", "tiny", "tiny_merged"):
+        # (tiny and medium twice: call by call, and 32 iterations merged per call, Section 3.2's remedy for
+        # minibatches that are small beside the cost of launching and ordering their kernels)
+        for name in ("resident", "medium", "medium_merged", "tiny", "tiny_merged"):
             if name == args.workload:
                 continue
             sub = copy.copy(args)
             sub.workload, sub.steps, sub.warmup, sub.cpu_seconds = name, min(args.steps, 20), min(args.warmup, 6), 4.0
             if name == "tiny_merged":
                 sub.workload, sub.accum, sub.many, sub.steps, sub.warmup = "tiny", 1, 32, 320, 32
+            elif name == "medium_merged":
+                sub.workload, sub.accum, sub.many, sub.steps, sub.warmup = "medium", 1, 32, 128, 32
             elif name == "tiny":
                 sub.steps, sub.warmup = 320, 32
             log(f"--- other workload: {name}")

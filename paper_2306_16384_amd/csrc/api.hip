@@ -199,8 +199,9 @@ struct gids_cache {
             return;
         }
     }
-    uint64_t many_list_max = 8192;  // merged kernels for lists up to this many raw IDs (GIDS_MANY_LIST_MAX)
+    uint64_t many_list_max = 65536; // merged kernels for lists up to this many raw IDs (GIDS_MANY_LIST_MAX)
     uint32_t many_meta_min = 16;        // merged calls of at least this many steps classify on the internal stream (GIDS_MANY_PIPELINE_MIN; 0: never)
+    bool many_pool_forced = false;
     uint64_t many_pool = 128 * 1024;    // LDS for a classifying workgroup's own list entries (GIDS_MANY_POOL, bytes; 0: none)
     int fuse = 1;               // GIDS_FUSE=0: commit, queueing and counters as a kernel each; no merged kernels
     int move_blocks = 1 << 20;  // most workgroups the row mover uses for rows that stay in HBM
@@ -358,7 +359,10 @@ struct CacheT final : gids_cache {
         if (const char* env = getenv("GIDS_WIDE_INDEX")) wide_index = atoi(env) != 0;
         if (const char* env = getenv("GIDS_FUSE")) fuse = atoi(env) & 1;
         if (const char* env = getenv("GIDS_MANY_LIST_MAX")) many_list_max = (uint64_t)std::max(0ll, atoll(env));
-        if (const char* env = getenv("GIDS_MANY_POOL")) many_pool = (uint64_t)std::max(0ll, atoll(env));
+        if (const char* env = getenv("GIDS_MANY_POOL")) {     // (as given, whether the lists fit it or not)
+            many_pool = (uint64_t)std::max(0ll, atoll(env));
+            many_pool_forced = true;
+        }
         if (const char* env = getenv("GIDS_MANY_PIPELINE_MIN")) many_meta_min = (uint32_t)std::max(0, atoi(env));
         if (const char* env = getenv("GIDS_MOVE_BLOCKS")) {
             const int b = atoi(env);
@@ -787,9 +791,9 @@ struct CacheT final : gids_cache {
             cnt--;
             if (!outs[i] && caps[i]) return fail(GIDS_E_INVAL, "gids_gather_many: out_dev[%u] is NULL", i);
         }
-        // The merged kernels pay for short lists: every workgroup of the classification reads every list, which
-        // for lists of tens of thousands of IDs costs more than the launches it saves (Medium: 0.45 ms per step
-        // merged, 0.42 ms through the per-step kernels as one group).
+        // The merged kernels want a workgroup's share of every list in its LDS (many_fits): a workgroup whose
+        // share does not fit reads all the lists from memory in every phase of every step, which for lists of
+        // tens of thousands of IDs costs more than the per-step kernels as one group.
         uint64_t longest_raw = 0;
         {
             uint32_t h = head, c2 = count;
@@ -806,8 +810,28 @@ struct CacheT final : gids_cache {
                 c2--;
             }
         }
+        uint32_t n_lists_upper = 0;                           // distinct lists the call reads: heads and pushed ones
+        {
+            std::vector<char> seen(slots.size(), 0);
+            uint32_t h = head, c2 = count;
+            for (uint32_t i = 0; i < k; i++) {
+                if (push_ids && push_ids[i]) {
+                    const size_t q = (h + c2) % slots.size();
+                    n_lists_upper += !seen[q];
+                    seen[q] = 1;
+                    c2++;
+                }
+                n_lists_upper += !seen[h];
+                seen[h] = 1;
+                h = (h + 1) % slots.size();
+                c2--;
+            }
+        }
         const bool fast = store->n_rows <= many_max_rows() && ways <= many_max_ways() && rows_per_line == 1 &&
-                          (fuse & 1) && longest_raw <= many_list_max;
+                          (fuse & 1) && longest_raw <= many_list_max &&
+                          (many_pool_forced ||
+                           many_fits(store->n_rows, n_sets, ways, words_per_set, sizeof(IdT), n_lists_upper,
+                                     std::min<uint64_t>(longest_raw, store->n_rows), many_pool));
         int rc;
         if (!fast) {
             // large tables, high associativity: the same steps through the per-step kernels, still one group

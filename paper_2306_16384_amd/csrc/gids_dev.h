@@ -245,6 +245,8 @@ struct ManySteps {
 };
 constexpr uint8_t MANY_NO_LIST = 0xFF;
 uint64_t many_max_rows();
+bool many_fits(uint64_t n_rows, uint64_t n_sets, uint32_t ways, uint32_t words_per_set, size_t id_bytes, uint32_t n_lists,
+               uint64_t longest, uint64_t pool_bytes);
 uint32_t many_max_ways();
 template <typename IdT>
 void launch_dedup_small(const ManyPushes<IdT>& p, uint32_t n_lists, uint64_t n_rows, Ctl* ctl, hipStream_t s);

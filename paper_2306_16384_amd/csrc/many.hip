@@ -1,28 +1,31 @@
 // Merged iterations (GIDS paper, Section 3.2: the data preparation of several
 // consecutive iterations is merged so that the stop-and-go boundaries between
 // minibatches disappear).  One call brings k steps, each "push one future list,
-// gather the window's head"; here all k steps run in two launches, whatever k:
+// gather the window's head"; here all k steps run in two launches, whatever k,
+// followed by the group mover's:
 //
 //   dedup_small   one workgroup per pushed list: the list is marked into a
-//                 bitmap in LDS (tables whose bitmap fits a workgroup's LDS: 1.3 M rows
-//                 on gfx950), scanned and
-//                 written out as ascending distinct IDs.  Nothing else of the
-//                 push happens here.
+//                 bitmap in LDS (tables whose bitmap fits a workgroup's LDS:
+//                 1.3 M rows on gfx950), scanned and written out as ascending
+//                 distinct IDs.  Nothing else of the push happens here.
 //   classify_many the k steps one after the other inside one kernel.  A step's
 //                 decisions depend only on the state of the cache sets its IDs
 //                 fall into, and so does everything a step changes (tags,
 //                 stamps, the future-reuse counters of the nodes that map to a
-//                 set): the sets are dealt out to the workgroups (set s belongs
-//                 to workgroup s mod gridDim.x), every workgroup scans each
-//                 list, keeps the IDs of its own sets and walks through the
-//                 steps at its own pace, with workgroup barriers between the
-//                 phases of a step and no synchronisation between workgroups
-//                 at all.  Per step: the pushed list's future-reuse counters
-//                 +1 (Section 3.4, Fig. 6); the head list's counters -1,
-//                 CPU-buffer lookup (Section 3.3), tag probe; victims; commit
-//                 and the accumulator's queueing (every row becomes an
-//                 operation of the open group, whose mover runs after this
-//                 kernel).  One thread per ID, the `ways` tags of a set read by
+//                 set, the accumulator's words per line): the sets are dealt
+//                 out to the workgroups (set s belongs to workgroup s mod
+//                 gridDim.x, a power of two), and no workgroup waits for
+//                 another.  A workgroup reads every list once and keeps the
+//                 IDs of its own sets in LDS; where it fits, the state of its
+//                 sets lives in LDS as well for the length of the kernel, and
+//                 the steps then touch device memory only to store the
+//                 group's operations.  Per step: the pushed list's
+//                 future-reuse counters +1 (Section 3.4, Fig. 6); the head
+//                 list's counters -1, CPU-buffer lookup (Section 3.3), tag
+//                 probe; victims; commit and the accumulator's queueing (every
+//                 row becomes an operation of the open group, whose mover runs
+//                 after this kernel), with workgroup barriers between the
+//                 phases.  One thread per ID, the `ways` tags of a set read by
 //                 that thread (ways <= 16).  The last workgroup to finish
 //                 publishes the k records of counters.
 #include <cstdlib>
@@ -842,24 +845,27 @@ void launch_classify_many_ways(const CacheView<IdT>& c, const AccumView& a, uint
 }
 }  // namespace
 
-template <typename IdT>
-void launch_classify_many(const CacheView<IdT>& c, const AccumView& a, uint32_t group, ManySteps<IdT>& m,
-                          uint64_t longest, uint64_t pool_bytes, uint64_t* plan_all, StatsRec* ring, uint32_t ring_size,
-                          hipStream_t s) {
-    // about 32 of a list's entries per workgroup's own share (GIDS_MANY_SHARE); every workgroup reads every list
+namespace {
+// How a merged call's classification is launched: workgroups, their threads, and what their LDS holds.
+struct ManyShape {
+    uint64_t g;             // workgroups, a power of two
+    uint32_t wg_shift;
+    uint32_t threads;
+    uint32_t sets_per_wg, rounds;
+    uint64_t state;         // bytes of a workgroup's sets' state
+    bool resident;          // ... kept in LDS for the length of the kernel
+    uint64_t cap;           // places per list for a workgroup's own entries
+    uint64_t share;         // entries of the longest list a workgroup can expect to own
+};
+
+ManyShape many_shape(uint64_t n_rows, uint64_t n_sets, uint32_t ways, uint32_t words_per_set, size_t id_bytes,
+                     uint32_t n_lists, uint64_t longest, uint64_t pool_bytes) {
+    // 16 to 32 of a list's entries per workgroup's own share (GIDS_MANY_SHARE); every workgroup reads every list
     static const uint64_t per_wg = [] {
         const char* e = getenv("GIDS_MANY_SHARE");
-        const long v = e ? atol(e) : 32;
-        return (uint64_t)(v >= 1 ? v : 32);
+        const long v = e ? atol(e) : 16;
+        return (uint64_t)(v >= 1 ? v : 16);
     }();
-    uint64_t g = (longest + per_wg - 1) / per_wg;
-    if (g < 1) g = 1;
-    if (g > 256) g = 256;
-    if (g > c.n_sets) g = c.n_sets;                          // a workgroup without a set would only take a ticket
-    uint32_t wg_shift = 0;                                    // a power of two: which workgroup a set belongs to and
-    while ((2ull << wg_shift) <= g) wg_shift++;               // its place there are a mask and a shift
-    g = 1ull << wg_shift;
-    m.wg_shift = wg_shift;
     static const uint32_t threads = [] {                     // a multiple of 64 up to CM_THREADS (GIDS_MANY_THREADS)
         const char* e = getenv("GIDS_MANY_THREADS");
         const long v = e ? atol(e) : CM_THREADS;
@@ -869,28 +875,63 @@ void launch_classify_many(const CacheView<IdT>& c, const AccumView& a, uint32_t 
         const char* e = getenv("GIDS_MANY_RESIDENT");
         return !(e && atoi(e) == 0);
     }();
-    m.div_sets = make_fast_div((uint32_t)c.n_sets);
+    ManyShape sh;
+    uint64_t g = (longest + per_wg - 1) / per_wg;
+    if (g < 1) g = 1;
+    if (g > 256) g = 256;
+    if (g > n_sets) g = n_sets;                               // a workgroup without a set would only take a ticket
+    sh.wg_shift = 0;                                          // a power of two: which workgroup a set belongs to and
+    while ((2ull << sh.wg_shift) <= g) sh.wg_shift++;         // its place there are a mask and a shift
+    sh.g = 1ull << sh.wg_shift;
+    sh.threads = threads;
     // The state of a workgroup's sets for the length of the kernel, when it leaves at least half of the LDS to
     // the lists: per line a tag, a stamp, three accumulator words and an output address; per set its miss-mask
     // words; per node that maps to one of the sets a counter.
-    m.sets_per_wg = (uint32_t)((c.n_sets + g - 1) / g);
-    m.rounds = (uint32_t)((c.n_rows + c.n_sets - 1) / c.n_sets);
-    const uint64_t n_l = (uint64_t)m.sets_per_wg * c.ways;
-    const uint64_t state = n_l * (8 + sizeof(IdT) + 16) + (uint64_t)m.sets_per_wg * c.words_per_set * 8 +
-                           (uint64_t)m.sets_per_wg * m.rounds;
-    m.resident = resident_ok && pool_bytes && state <= MANY_LDS_MAX_BYTES / 2;
+    sh.sets_per_wg = (uint32_t)((n_sets + sh.g - 1) / sh.g);
+    sh.rounds = (uint32_t)((n_rows + n_sets - 1) / n_sets);
+    const uint64_t n_l = (uint64_t)sh.sets_per_wg * ways;
+    sh.state = n_l * (8 + id_bytes + 16) + (uint64_t)sh.sets_per_wg * words_per_set * 8 +
+               (uint64_t)sh.sets_per_wg * sh.rounds;
+    sh.resident = resident_ok && pool_bytes && sh.state <= MANY_LDS_MAX_BYTES / 2;
     // LDS for a workgroup's own entries: the same number of places for each list, four times the expected share
     // where that fits; a workgroup whose share of some list is larger reads the lists from memory instead
-    const uint64_t room = MANY_LDS_MAX_BYTES - (m.resident ? state : 0) - 16;
+    const uint64_t room = MANY_LDS_MAX_BYTES - (sh.resident ? sh.state : 0) - 16;
     if (pool_bytes > room) pool_bytes = room;
-    const uint64_t entry = sizeof(IdT) + 8;
-    uint64_t cap = m.n_lists ? pool_bytes / (entry * m.n_lists) : 0;
-    const uint64_t want = 4 * ((longest + g - 1) / g);
-    if (cap > want) cap = want;
+    const uint64_t entry = id_bytes + 8;
+    sh.share = (longest + sh.g - 1) / sh.g;
+    uint64_t cap = n_lists ? pool_bytes / (entry * n_lists) : 0;
+    if (cap > 4 * sh.share + 16) cap = 4 * sh.share + 16;
     if (cap > threads) cap = threads;                         // one thread per entry
-    cap &= ~1ull;                                             // keeps the 32-bit arrays behind the IDs aligned
-    m.share_cap = (uint32_t)cap;
-    const size_t lds = (size_t)(cap * m.n_lists * entry + (m.resident ? state : 0) + 16);
+    sh.cap = cap & ~1ull;                                     // keeps the 32-bit arrays behind the IDs aligned
+    return sh;
+}
+}  // namespace
+
+// Whether the merged kernels suit a call: the workgroups' LDS has room for their expected share of every list and
+// four standard deviations more (a share is a count of independent hits on one of g residues).  Beyond that most
+// workgroups would read the lists from memory in every phase, and the per-step kernels are the better choice.
+bool many_fits(uint64_t n_rows, uint64_t n_sets, uint32_t ways, uint32_t words_per_set, size_t id_bytes, uint32_t n_lists,
+               uint64_t longest, uint64_t pool_bytes) {
+    const ManyShape sh = many_shape(n_rows, n_sets, ways, words_per_set, id_bytes, n_lists, longest, pool_bytes);
+    uint64_t dev = 0;
+    while ((dev + 1) * (dev + 1) <= sh.share) dev++;          // floor(sqrt(share))
+    return pool_bytes == 0 || sh.cap >= sh.share + 4 * (dev + 1) + 8;
+}
+
+template <typename IdT>
+void launch_classify_many(const CacheView<IdT>& c, const AccumView& a, uint32_t group, ManySteps<IdT>& m,
+                          uint64_t longest, uint64_t pool_bytes, uint64_t* plan_all, StatsRec* ring, uint32_t ring_size,
+                          hipStream_t s) {
+    const ManyShape sh = many_shape(c.n_rows, c.n_sets, c.ways, c.words_per_set, sizeof(IdT), m.n_lists, longest, pool_bytes);
+    const uint64_t g = sh.g;
+    const uint32_t threads = sh.threads;
+    m.wg_shift = sh.wg_shift;
+    m.div_sets = make_fast_div((uint32_t)c.n_sets);
+    m.sets_per_wg = sh.sets_per_wg;
+    m.rounds = sh.rounds;
+    m.resident = sh.resident;
+    m.share_cap = (uint32_t)sh.cap;
+    const size_t lds = (size_t)(sh.cap * m.n_lists * (sizeof(IdT) + 8) + (sh.resident ? sh.state : 0) + 16);
 #define GIDS_CLASSIFY_MANY(W) \
     launch_classify_many_ways<IdT, W>(c, a, group, m, (uint32_t)g, threads, lds, plan_all, ring, ring_size, s)
     switch (c.ways) {
