@@ -65,6 +65,44 @@ def drive(ses, torch, raws, window, cap_rows, row_bytes, keep):
     return outs, uniqs, stats
 
 
+def drive_merged(ses, torch, raws, window, row_bytes, k=32):
+    """The same protocol through gids_gather_many, k steps per call (each pushes the list that keeps the window
+    full and gathers the head), as bench.py --many issues them; every minibatch keeps its tensor."""
+    dev = [ses.to_device(r) for r in raws]
+    n_b = len(raws)
+    outs = {t: torch.empty((max(1, len(np.unique(raws[t]))), row_bytes), dtype=torch.uint8, device="cuda") for t in range(n_b)}
+    uniqs = {t: torch.empty(outs[t].shape[0], dtype=ses.torch_id, device="cuda") for t in range(n_b)}
+    stats, pushed, calls = {}, 0, []
+    push_stream = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    while pushed < min(n_b, window):                          # the look-ahead, before the first merged call
+        ses.push(dev[pushed], stream=push_stream)
+        pushed += 1
+    t = 0
+    while t < n_b:
+        kk = min(k, n_b - t)
+        pushes = []
+        for i in range(kk):
+            if pushed < n_b and pushed <= t + i + window:
+                pushes.append(dev[pushed])
+                pushed += 1
+            else:
+                pushes.append(None)
+        seq0 = ses.gather_many(pushes, [outs[t + i] for i in range(kk)], [uniqs[t + i] for i in range(kk)],
+                               push_stream=push_stream)
+        if calls:                                             # the counters of the call before, while this one runs
+            t0, k0, s0 = calls[-1]                            # (the library keeps those of the last 64 gathers)
+            for i in range(k0):
+                stats[t0 + i] = ses.stats(s0 + i)
+        calls.append((t, kk, seq0))
+        t += kk
+    torch.cuda.synchronize()
+    t0, k0, s0 = calls[-1]
+    for i in range(k0):
+        stats[t0 + i] = ses.stats(s0 + i)
+    return outs, uniqs, stats
+
+
 def rows_equal_store(out_dev, u, store_np, chunk=1 << 17):
     """Every gathered row against its row of the host table, the plain definition of the gather."""
     for lo in range(0, len(u), chunk):
@@ -85,7 +123,10 @@ def store_equals_closed_form(oracle_mod, cfg, store_np, table, n_sample=1500):
     assert np.array_equal(store_np[ids], want), "the host table differs from the closed-form feature rows"
 
 
-def test_medium_full_size(oracle_mod):
+@pytest.mark.parametrize("merged", [False, True])
+def test_medium_full_size(oracle_mod, merged):
+    """merged: the same 200 minibatches through gids_gather_many, 32 steps per call (the merged kernels, the
+    classification on the library's internal stream)."""
     import torch
     from paper_2306_16384_amd.session import GatherSession
     cfg = CONFIGS["medium"]
@@ -98,11 +139,14 @@ def test_medium_full_size(oracle_mod):
     cap = max(len(np.unique(r)) for r in raws)
     keep = set(range(n_b))                                    # the whole tensor of every minibatch
     with GatherSession(cfg.n_nodes, cfg.row_bytes, np.int64, cfg.cache_lines, cfg.ways, cfg.line_bytes,
-                       cfg.window) as ses:
+                       cfg.window, 1 if merged else 0) as ses:
         wl.fill_store(cfg.seed, cfg.n_nodes, cfg.dim, table, ses.store_address())
         store_equals_closed_form(oracle_mod, cfg, ses.store_view(), table)
         ses.pin_hot(hot)
-        outs, uniqs, stats_of = drive(ses, torch, raws, cfg.window, cap, cfg.row_bytes, keep)
+        if merged:
+            outs, uniqs, stats_of = drive_merged(ses, torch, raws, cfg.window, cfg.row_bytes)
+        else:
+            outs, uniqs, stats_of = drive(ses, torch, raws, cfg.window, cap, cfg.row_bytes, keep)
         sim = oracle_mod.Sim(cfg.n_nodes, cfg.cache_lines, cfg.ways, cfg.window, cfg.row_bytes, cfg.line_bytes,
                              ses.store_view())
         sim.set_hot(hot)
