@@ -302,7 +302,7 @@ def test_large_at_benchmark_size(oracle_mod, big_world):
 
 SKEW_S = (0.0, 0.8, 1.2)
 SKEW_W = (0, 4, 16)
-RESULTS = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+RESULTS = os.environ.get("GIDS_RESULTS_DIR")               # where the measured points are appended, if anywhere
 
 
 def skew_point(oracle_mod, big_world, s_exp, window, cache_lines, n_b, tag):
@@ -329,12 +329,13 @@ def skew_point(oracle_mod, big_world, s_exp, window, cache_lines, n_b, tag):
              "hit_rate_of_cache_traffic": sum(s.n_hit for s in tail) / max(1, cold),
              "bypass_rate": sum(s.n_bypass for s in tail) / uniq}
     print(f"[fullsize {label}] {json.dumps(point)}", flush=True)
-    try:
-        os.makedirs(RESULTS, exist_ok=True)
-        with open(os.path.join(RESULTS, "skew_parity_points.jsonl"), "a") as f:
-            f.write(json.dumps(dict(point, tag=tag)) + "\n")
-    except OSError:
-        pass
+    if RESULTS:
+        try:
+            os.makedirs(RESULTS, exist_ok=True)
+            with open(os.path.join(RESULTS, "skew_parity_points.jsonl"), "a") as f:
+                f.write(json.dumps(dict(point, tag=tag)) + "\n")
+        except OSError:
+            pass
     return point
 
 
