@@ -323,6 +323,11 @@ int gids_stats_read(gids_cache* cache, uint64_t seq, gids_stats* stats);
 /* Number of gathers enqueued so far (the next gather's seq). */
 uint64_t gids_cache_gathers(const gids_cache* cache);
 
+/* How the gids_gather_many calls of this cache were carried out so far: calls
+ * that ran through the merged kernels, calls that took the per-step kernels
+ * as one group (see gids_gather_many for what decides).  Either may be NULL. */
+void gids_cache_many_calls(const gids_cache* cache, uint64_t* merged_kernels, uint64_t* per_step_kernels);
+
 /* Inspection for tests and tools: blocks until the stream is idle, then copies
  * the tag (int64, -1 = empty) and last-use stamp (int64, -1 = never) of every
  * line to host arrays of `lines` entries each.  Either may be NULL. */

@@ -15,7 +15,7 @@ GIDS_E_INVAL, GIDS_E_NOMEM, GIDS_E_RANGE, GIDS_E_ORDER, GIDS_E_FULL, GIDS_E_HIP,
 EXPORTS = [
     "gids_store_create", "gids_store_host_ptr", "gids_store_destroy", "gids_store_calibrate", "gids_cache_create", "gids_cache_destroy",
     "gids_cache_reserve", "gids_cache_set_policy", "gids_cache_set_accum_mode", "gids_cpu_buffer_pin", "gids_window_push", "gids_gather", "gids_gather_static", "gids_gather_many", "gids_flush", "gids_stats_read",
-    "gids_cache_gathers", "gids_cache_snapshot", "gids_cache_set_rows_per_line", "gids_profile_enable", "gids_profile_read", "gids_window_push_dev",
+    "gids_cache_gathers", "gids_cache_many_calls", "gids_cache_snapshot", "gids_cache_set_rows_per_line", "gids_profile_enable", "gids_profile_read", "gids_window_push_dev",
     "gids_graph_create", "gids_graph_destroy", "gids_sample_capacity", "gids_sample", "gids_graph_visit_scores", "gids_graph_reverse_pagerank", "gids_accum_threshold", "gids_last_error",
 ]
 
@@ -68,6 +68,8 @@ def lib() -> C.CDLL:
         L.gids_stats_read.argtypes = [vp, u64, C.POINTER(gids_stats)]
         L.gids_cache_gathers.restype = u64
         L.gids_cache_gathers.argtypes = [vp]
+        L.gids_cache_many_calls.restype = None
+        L.gids_cache_many_calls.argtypes = [vp, C.POINTER(u64), C.POINTER(u64)]
         L.gids_cache_snapshot.argtypes = [vp, vp, vp]
         L.gids_window_push_dev.argtypes = [vp, vp, u64, vp, vp]
         L.gids_graph_create.argtypes = [u64, vp, vp, u32, C.c_int, C.POINTER(vp)]
@@ -192,6 +194,13 @@ def gids_stats_read(cache: int, seq: int) -> gids_stats:
 
 def gids_cache_gathers(cache: int) -> int:
     return int(lib().gids_cache_gathers(cache))
+
+
+def gids_cache_many_calls(cache: int) -> tuple[int, int]:
+    """(calls through the merged kernels, calls through the per-step kernels)"""
+    a, b = C.c_uint64(0), C.c_uint64(0)
+    lib().gids_cache_many_calls(cache, C.byref(a), C.byref(b))
+    return int(a.value), int(b.value)
 
 
 def gids_cache_snapshot(cache: int, tags_host_ptr: int | None, stamps_host_ptr: int | None) -> None:

@@ -138,6 +138,7 @@ struct gids_cache {
     uint32_t ways = 0, lg_ways = 0, line_bytes = 0, window = 0, words_per_set = 0;
     int sticky = GIDS_OK;
     uint64_t seq = 0;
+    uint64_t many_fast_calls = 0, many_slow_calls = 0;   // gids_gather_many: through the merged kernels / the per-step ones
     uint32_t policy = 0;            // GIDS_POLICY_*
     uint32_t rows_per_line = 1;     // node rows one cache line holds
     uint64_t policy_key = 0;
@@ -835,6 +836,7 @@ struct CacheT final : gids_cache {
         int rc;
         if (!fast) {
             // large tables, high associativity: the same steps through the per-step kernels, still one group
+            many_slow_calls++;
             if (open_batches && (rc = flush(s))) return rc;
             for (uint32_t i = 0; i < k; i++) {
                 if (push_ids && push_ids[i] && (rc = push(push_ids[i], push_n[i], nullptr, ps))) return rc;
@@ -845,6 +847,7 @@ struct CacheT final : gids_cache {
             }
             return GIDS_OK;
         }
+        many_fast_calls++;
         // room: window slots of the pushed lists, the plans of all steps, the group's lists
         if (open_batches && (rc = flush(s))) return rc;
         {
@@ -1337,6 +1340,11 @@ int gids_profile_read(gids_cache* cache, uint64_t seq, float* ms3) {
 }
 
 uint64_t gids_cache_gathers(const gids_cache* cache) { return cache ? cache->seq : 0; }
+
+void gids_cache_many_calls(const gids_cache* cache, uint64_t* merged_kernels, uint64_t* per_step_kernels) {
+    if (merged_kernels) *merged_kernels = cache ? cache->many_fast_calls : 0;
+    if (per_step_kernels) *per_step_kernels = cache ? cache->many_slow_calls : 0;
+}
 
 int gids_cache_snapshot(gids_cache* cache, int64_t* tags_host, int64_t* stamps_host) {
     if (!cache) return fail(GIDS_E_INVAL, "gids_cache_snapshot: cache is NULL");

@@ -42,7 +42,7 @@ def with_env(knobs, make):
 
 
 def run_many(gpu, oracle, feats, batches, *, id_dtype, lines, ways, window, ks, hot=None, policy=None, pipeline="0",
-             fuse=None, pool=None, resident=None, label=""):
+             fuse=None, pool=None, resident=None, expect_merged=None, label=""):
     """ks: the sizes of the merged calls, in order (0 = one plain push + gather step in between);
     cycles until every list is gathered."""
     torch, gids, GatherSession = gpu
@@ -134,6 +134,13 @@ def run_many(gpu, oracle, feats, batches, *, id_dtype, lines, ways, window, ks, 
         tags, stamps = ses.snapshot()
         assert np.array_equal(tags, sim.tags), label
         assert np.array_equal(stamps, sim.stamps), label
+        merged, per_step = gids.gids_cache_many_calls(ses.cache)
+        print(f"[many {label}] calls through the merged kernels: {merged}, through the per-step kernels: {per_step}", flush=True)
+        if expect_merged is True:
+            assert merged > 0 and per_step == 0, (label, merged, per_step)
+        if expect_merged is False:
+            assert merged == 0 and per_step > 0, (label, merged, per_step)
+        return merged, per_step
 
 
 def zipf_lists(rng, n, n_b, size, a=1.2):
@@ -151,7 +158,7 @@ def test_tiny_config_in_merged_calls(gpu, oracle_mod, pipeline):
     batches = [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds) for b in range(48)]
     for ks in ([8], [1, 3, 0, 32, 2], [32]):
         run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int32, lines=cfg.cache_lines, ways=cfg.ways,
-                 window=cfg.window, ks=ks, hot=hot, pipeline=pipeline, label=f"tiny/{ks}")
+                 window=cfg.window, ks=ks, hot=hot, pipeline=pipeline, expect_merged=True, label=f"tiny/{ks}")
 
 
 @pytest.mark.parametrize("ways,window,id_dtype,policy", [(1, 0, np.int64, None), (2, 1, np.int32, None), (4, 3, np.int64, (1, 7)),
@@ -168,7 +175,7 @@ def test_merged_calls_over_shapes(gpu, oracle_mod, ways, window, id_dtype, polic
     for pipeline in ("0", "1"):
         run_many(gpu, oracle_mod, feats, batches, id_dtype=id_dtype, lines=ways * 11, ways=ways, window=window,
                  ks=[5, 0, 13, 1], hot=rng.choice(n, 40, replace=False), policy=policy, pipeline=pipeline,
-                 label=f"ways{ways}/W{window}")
+                 expect_merged=ways <= 16, label=f"ways{ways}/W{window}")
 
 
 @pytest.mark.parametrize("pool,resident", [("0", None), ("3000", None), ("14000", None), ("14000", "0"), (None, "0")])
@@ -184,7 +191,8 @@ def test_merged_calls_with_little_or_no_lds(gpu, oracle_mod, pool, resident):
     hot = wl.hot_nodes(g, cfg.cpu_rows)
     batches = [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds) for b in range(40)]
     run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int32, lines=cfg.cache_lines, ways=cfg.ways,
-             window=cfg.window, ks=[32, 3, 0, 5], hot=hot, pool=pool, resident=resident, label="tiny")
+             window=cfg.window, ks=[32, 3, 0, 5], hot=hot, pool=pool, resident=resident, expect_merged=True,
+             label="tiny")
     rng = np.random.default_rng(91)
     n = 3000
     feats = rng.integers(0, 256, size=(n, 128), dtype=np.uint8)
@@ -193,7 +201,7 @@ def test_merged_calls_with_little_or_no_lds(gpu, oracle_mod, pool, resident):
     for policy in (None, (1, 5)):
         run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=8 * 11, ways=8, window=3, ks=[7, 0, 12],
                  hot=rng.choice(n, 40, replace=False), pool=pool, resident=resident, policy=policy, pipeline="1",
-                 label="small cache")
+                 expect_merged=True, label="small cache")
 
 
 @pytest.mark.parametrize("own_push_stream", [True, False])
@@ -208,7 +216,60 @@ def test_long_and_short_merged_calls_and_plain_steps_take_turns(gpu, oracle_mod,
     batches = [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds) for b in range(60)]
     run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int32, lines=cfg.cache_lines, ways=cfg.ways,
              window=cfg.window, ks=[16, 3, 0, 20, 0, 17, 2], hot=hot,
-             pipeline=None if own_push_stream else "unset-one-stream", label="default streams")
+             pipeline=None if own_push_stream else "unset-one-stream", expect_merged=True, label="default streams")
+
+
+N_RANDOM = int(os.environ.get("GIDS_MANY_RANDOM_CASES", "32"))
+RANDOM_TALLY = [0, 0]                                         # calls through the merged kernels / the per-step kernels
+
+
+@pytest.mark.parametrize("case", range(N_RANDOM))
+def test_random_merged_calls(gpu, oracle_mod, case):
+    """Seeded random geometry, window, list shapes, call sizes and the library's knobs for the merged kernels (the
+    draw is printed, so a failure names its case)."""
+    rng = np.random.default_rng(31_000 + case)
+    n = int(rng.choice([64, 65, 1000, 4097, 30_011, 200_003]))
+    ways = int(rng.choice([1, 2, 4, 8, 16]))
+    n_sets = int(rng.integers(1, max(2, n // (ways * int(rng.integers(1, 60))) + 2)))
+    row_bytes = int(rng.choice([16, 64, 512, 1040]))
+    window = int(rng.choice([0, 1, 2, 4, 9, 20]))
+    id_dtype = np.int32 if rng.random() < 0.5 else np.int64
+    n_hot = int(rng.integers(0, max(1, n // 8)))
+    size = int(rng.integers(1, min(3 * n, 20_000)))
+    a = float(rng.choice([1.05, 1.3, 2.0]))
+    n_b = int(rng.integers(4, 60))
+    batches = []
+    for _ in range(n_b):
+        m = int(rng.integers(0, size + 1))
+        kind = rng.random()
+        if kind < 0.4:
+            b = np.minimum(rng.zipf(a, size=m) - 1, n - 1)
+        elif kind < 0.8:
+            b = rng.integers(0, n, size=m)
+        else:                                                 # a run of neighbouring IDs: every set gets its share
+            lo = int(rng.integers(0, n))
+            b = (lo + np.arange(m)) % n
+        batches.append(b.astype(np.int64))
+    ks = [int(k) for k in rng.choice([0, 1, 2, 5, 16, 17, 32], size=int(rng.integers(1, 6)))]
+    if all(k == 0 for k in ks):
+        ks.append(32)
+    pipeline = [None, "0", "1", "unset-one-stream"][case % 4]
+    pool, resident = [(None, None), (None, "0"), ("0", None), (str(int(rng.integers(200, 40_000))), None),
+                      (None, None)][case % 5]
+    feats = rng.integers(0, 256, size=(n, row_bytes), dtype=np.uint8)
+    merged, per_step = run_many(gpu, oracle_mod, feats, batches, id_dtype=id_dtype, lines=ways * n_sets, ways=ways,
+                                window=window, ks=ks, hot=rng.choice(n, n_hot, replace=False) if n_hot else None,
+                                policy=(1, case) if rng.random() < 0.3 else None, pipeline=pipeline, pool=pool,
+                                resident=resident, label=f"random{case}")
+    RANDOM_TALLY[0] += merged
+    RANDOM_TALLY[1] += per_step
+
+
+def test_random_merged_calls_took_both_kinds_of_kernels():
+    """(runs after the random cases: most of their calls must have gone through the merged kernels)"""
+    if sum(RANDOM_TALLY) == 0:
+        pytest.skip("the random cases did not run in this process")
+    assert RANDOM_TALLY[0] > RANDOM_TALLY[1] > 0, RANDOM_TALLY
 
 
 def test_merged_calls_through_the_per_step_kernels(gpu, oracle_mod):
@@ -219,19 +280,25 @@ def test_merged_calls_through_the_per_step_kernels(gpu, oracle_mod):
     batches = zipf_lists(rng, n, 30, 700)
     for pipeline in ("0", "1"):
         run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=256, ways=4, window=4, ks=[6, 0, 9],
-                 hot=rng.choice(n, 60, replace=False), pipeline=pipeline, fuse="0", label="per-step")
+                 hot=rng.choice(n, 60, replace=False), pipeline=pipeline, fuse="0", expect_merged=False, label="per-step")
 
 
 @pytest.mark.parametrize("n", [600_000, 1_500_000])
 def test_tables_beyond_64_kib_of_bitmap(gpu, oracle_mod, n):
     """600,000 rows: the merged dedup's LDS bitmap needs more than the default 64 KiB of a workgroup; 1,500,000
-    rows: more than a workgroup can have, the call takes the per-step kernels.  Also lists beyond the merged
-    kernels' length limit."""
+    rows: more than a workgroup can have, the calls take the per-step kernels.  Then a list beyond the merged
+    kernels' length limit: the calls that read it take the per-step kernels, the others do not."""
     rng = np.random.default_rng(78)
     feats = rng.integers(0, 256, size=(n, 16), dtype=np.uint8)
     batches = [rng.integers(0, n, size=3000) for _ in range(12)]
     batches[5] = rng.integers(0, n, size=20_000)
-    run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=1024, ways=8, window=2, ks=[4], label=f"{n} rows")
+    run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=1024, ways=8, window=2, ks=[4],
+             expect_merged=n == 600_000, label=f"{n} rows")
+    if n == 600_000:
+        batches[5] = rng.integers(0, n, size=70_000)
+        merged, per_step = run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=1024, ways=8, window=2,
+                                    ks=[4], label=f"{n} rows, a list of 70,000")
+        assert merged > 0 and per_step > 0
 
 
 def test_merged_call_errors(gpu):
