@@ -286,8 +286,8 @@ int gids_gather_static(gids_cache* cache, const void* ids_dev, uint64_t n, void*
  * minibatches one after the other, each workgroup for its own share of the
  * cache sets and with that share's state in its LDS, and the group mover's
  * three.  Other caches and calls take the per-step kernels, still as one group.
- * Calls of 16 steps and more classify on the library's internal stream whatever
- * the cache size (see `push_stream`).
+ * Calls of two steps and more classify on the library's internal stream
+ * whatever the cache size (see `push_stream`).
  *   k              1 .. 32 (GIDS_ACCUM_MAX_MERGE)
  *   push_ids_dev   NULL (no step pushes), or k pointers, NULL where a step
  *                  pushes nothing; push_n the lists' lengths

@@ -201,7 +201,7 @@ struct gids_cache {
         }
     }
     uint64_t many_list_max = 65536; // merged kernels for lists up to this many raw IDs (GIDS_MANY_LIST_MAX)
-    uint32_t many_meta_min = 16;        // merged calls of at least this many steps classify on the internal stream (GIDS_MANY_PIPELINE_MIN; 0: never)
+    uint32_t many_meta_min = 2;         // merged calls of at least this many steps classify on the internal stream (GIDS_MANY_PIPELINE_MIN; 0: never)
     bool many_pool_forced = false;
     uint64_t many_pool = 128 * 1024;    // LDS for a classifying workgroup's own list entries (GIDS_MANY_POOL, bytes; 0: none)
     int fuse = 1;               // GIDS_FUSE=0: commit, queueing and counters as a kernel each; no merged kernels
@@ -884,9 +884,10 @@ struct CacheT final : gids_cache {
                      hipStream_t s) {
         int rc;
         const bool any_push = push_ids != nullptr;
-        // A call of many steps classifies on the internal stream also where the cache is too small for single
+        // A call of several steps classifies on the internal stream also where the cache is too small for single
         // gathers to do so: one pair of cross-stream waits per call, and the classification of this call runs
-        // beside the row movement of the call before.
+        // beside the row movement of the call before (Tiny, us per minibatch with / without: 39 / 49 for calls of
+        // two steps, 22 / 30 of four, 14 / 20 of eight, 10 / 15 of sixteen).
         const bool on_meta = pipelined || (many_meta_min && k >= many_meta_min);
         hipStream_t m = s;
         if (on_meta) {

@@ -42,7 +42,7 @@ def with_env(knobs, make):
 
 
 def run_many(gpu, oracle, feats, batches, *, id_dtype, lines, ways, window, ks, hot=None, policy=None, pipeline="0",
-             fuse=None, pool=None, resident=None, expect_merged=None, label=""):
+             fuse=None, pool=None, resident=None, meta_min=None, expect_merged=None, label=""):
     """ks: the sizes of the merged calls, in order (0 = one plain push + gather step in between);
     cycles until every list is gathered."""
     torch, gids, GatherSession = gpu
@@ -70,6 +70,7 @@ def run_many(gpu, oracle, feats, batches, *, id_dtype, lines, ways, window, ks, 
         knobs["GIDS_MANY_POOL"] = pool
     if resident is not None:
         knobs["GIDS_MANY_RESIDENT"] = resident
+    knobs["GIDS_MANY_PIPELINE_MIN"] = meta_min
     ses = with_env(knobs, lambda: GatherSession(n_rows, R, id_dtype, lines, ways, R, window, 1000))
     with ses:
         ses.store_view()[:] = feats_u8
@@ -204,10 +205,12 @@ def test_merged_calls_with_little_or_no_lds(gpu, oracle_mod, pool, resident):
                  expect_merged=True, label="small cache")
 
 
+@pytest.mark.parametrize("meta_min", [None, "16"])
 @pytest.mark.parametrize("own_push_stream", [True, False])
-def test_long_and_short_merged_calls_and_plain_steps_take_turns(gpu, oracle_mod, own_push_stream):
-    """The library's default on a small cache: calls of 16 steps and more classify on its internal stream, shorter
-    ones and plain gathers on the caller's.  Every change of stream between consecutive calls is in here."""
+def test_long_and_short_merged_calls_and_plain_steps_take_turns(gpu, oracle_mod, own_push_stream, meta_min):
+    """On a small cache merged calls classify on the library's internal stream (by default from two steps on, here
+    also from 16 on), shorter ones and plain gathers on the caller's.  Every change of stream between consecutive
+    calls is in here."""
     cfg = CONFIGS["tiny"]
     g = wl.make_graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max)
     table = wl.normal_table(np.float32)
@@ -216,7 +219,8 @@ def test_long_and_short_merged_calls_and_plain_steps_take_turns(gpu, oracle_mod,
     batches = [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds) for b in range(60)]
     run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int32, lines=cfg.cache_lines, ways=cfg.ways,
              window=cfg.window, ks=[16, 3, 0, 20, 0, 17, 2], hot=hot,
-             pipeline=None if own_push_stream else "unset-one-stream", expect_merged=True, label="default streams")
+             pipeline=None if own_push_stream else "unset-one-stream", meta_min=meta_min, expect_merged=True,
+             label="default streams")
 
 
 N_RANDOM = int(os.environ.get("GIDS_MANY_RANDOM_CASES", "32"))
@@ -260,7 +264,7 @@ def test_random_merged_calls(gpu, oracle_mod, case):
     merged, per_step = run_many(gpu, oracle_mod, feats, batches, id_dtype=id_dtype, lines=ways * n_sets, ways=ways,
                                 window=window, ks=ks, hot=rng.choice(n, n_hot, replace=False) if n_hot else None,
                                 policy=(1, case) if rng.random() < 0.3 else None, pipeline=pipeline, pool=pool,
-                                resident=resident, label=f"random{case}")
+                                resident=resident, meta_min=[None, "16", "0"][case % 3], label=f"random{case}")
     RANDOM_TALLY[0] += merged
     RANDOM_TALLY[1] += per_step
 
