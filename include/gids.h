@@ -281,11 +281,11 @@ int gids_gather_static(gids_cache* cache, const void* ids_dev, uint64_t n, void*
  * ends.  For lists of up to 65,536 raw IDs over a table whose bitmap fits a
  * workgroup's LDS (1.3 M rows on gfx950), with ways <= 16, one row per line
  * and LDS room for a workgroup's share of every list of the call, the k steps
- * take five launches in all, however large k: one that deduplicates the pushed
+ * take four launches in all, however large k: one that deduplicates the pushed
  * lists (a workgroup and an LDS bitmap each), one that classifies the k
  * minibatches one after the other, each workgroup for its own share of the
  * cache sets and with that share's state in its LDS, and the group mover's
- * three.  Other caches and calls take the per-step kernels, still as one group.
+ * two.  Other caches and calls take the per-step kernels, still as one group.
  * Calls of two steps and more classify on the library's internal stream
  * whatever the cache size (see `push_stream`).
  *   k              1 .. 32 (GIDS_ACCUM_MAX_MERGE)

@@ -237,13 +237,26 @@ __global__ __launch_bounds__(MV_THREADS) void settle_kernel(CacheView<IdT> c, Ac
 
 // The group mover, first launch: the fills and the rcopies of one closed group.  Shaped like the row mover:
 // the first `link_blocks` workgroups are persistent and draw chunks of fills from a counter (rows that cross
-// the host link), the others copy cache lines to output rows.
+// the host link), the next `hbm_blocks` copy cache lines to output rows; when a caller asked for distinct-ID
+// lists, one more workgroup per minibatch of the group copies its list from the group's staging buffer to the
+// caller's buffer (as 32-bit words).
 template <int G>
 __global__ __launch_bounds__(MV_THREADS) void group_move_kernel(Ctl* ctl, const FillOp* __restrict__ fills,
                                                                 const CopyOp* __restrict__ rcopies,
                                                                 char* __restrict__ cache_data, uint32_t line_bytes,
                                                                 uint32_t row_bytes, uint32_t par, uint32_t link_blocks,
-                                                                uint32_t link_ch, uint32_t link_spread) {
+                                                                uint32_t hbm_blocks, uint32_t link_ch,
+                                                                uint32_t link_spread, UniqCopies u,
+                                                                const uint32_t* __restrict__ stage, uint32_t id_words) {
+    if (blockIdx.x >= link_blocks + hbm_blocks) {
+        const uint32_t i = blockIdx.x - link_blocks - hbm_blocks;
+        uint32_t* __restrict__ dst = static_cast<uint32_t*>(u.dst[i]);
+        if (!dst) return;
+        const uint32_t* __restrict__ src = stage + u.src_entry[i] * id_words;
+        const uint64_t n = (uint64_t)ctl->grp_nu[par][i] * id_words;
+        for (uint64_t j = threadIdx.x; j < n; j += MV_THREADS) dst[j] = src[j];
+        return;
+    }
     const uint32_t row_u4 = row_bytes >> 4;
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t sub = lane % G, grp = lane / G;
@@ -279,7 +292,7 @@ __global__ __launch_bounds__(MV_THREADS) void group_move_kernel(Ctl* ctl, const 
     } else {
         const uint32_t n = ctl->q_rcopy[par];
         const uint64_t wave0 = ((uint64_t)(blockIdx.x - link_blocks) * MV_THREADS + threadIdx.x) >> 6;
-        const uint64_t n_waves = ((uint64_t)(gridDim.x - link_blocks) * MV_THREADS) >> 6;
+        const uint64_t n_waves = ((uint64_t)hbm_blocks * MV_THREADS) >> 6;
         constexpr uint32_t CH = 16;                           // operations a wave takes per step
         for (uint64_t base = wave0 * CH; base < n; base += n_waves * CH) {
             CopyOp op;
@@ -320,18 +333,6 @@ __global__ __launch_bounds__(MV_THREADS) void group_copy_kernel(Ctl* ctl, const 
             ctl->ticket_flush = 0;
         }
     }
-}
-
-// third launch (when a caller asked for distinct-ID lists): one workgroup per minibatch of the group copies its
-// list from the group's staging buffer to the caller's buffer
-template <typename IdT>
-__global__ __launch_bounds__(MV_THREADS) void group_uniq_kernel(const Ctl* ctl, uint32_t par, UniqCopies u,
-                                                                const IdT* __restrict__ stage) {
-    IdT* __restrict__ dst = static_cast<IdT*>(u.dst[blockIdx.x]);
-    if (!dst) return;
-    const IdT* __restrict__ src = stage + u.src_entry[blockIdx.x];
-    const uint32_t n = ctl->grp_nu[par][blockIdx.x];
-    for (uint32_t j = threadIdx.x; j < n; j += MV_THREADS) dst[j] = src[j];
 }
 
 // Link calibration: `n` rows of the host table, picked by a hash of their index, copied to a scratch
@@ -446,15 +447,17 @@ void launch_group_move(const CacheView<IdT>& c, const AccumView& a, uint32_t par
     while (link_ch > 4 && rows_upper / link_ch < (uint64_t)link_blocks_max * (MV_THREADS / 64)) link_ch >>= 1;
     const uint32_t link_blocks = row_grid(rows_upper, 64 / (int)link_ch, link_blocks_max);
     const uint32_t hbm_blocks = row_grid(rows_upper, 4, hbm_blocks_max);   // 4 waves x 16 operations per workgroup step
-    GIDS_DISPATCH_G(g, hipLaunchKernelGGL((group_move_kernel<G>), dim3(link_blocks + hbm_blocks), dim3(MV_THREADS), 0,
-                                          s, c.ctl, a.fills[par], a.rcopies[par], c.cache_data, c.line_bytes,
-                                          c.row_bytes, par, link_blocks, link_ch, link_spread_knob()));
+    bool any = false;
+    for (uint32_t i = 0; i < u.n; i++) any |= u.dst[i] != nullptr;
+    const uint32_t uniq_blocks = any ? u.n : 0;
+    GIDS_DISPATCH_G(g, hipLaunchKernelGGL((group_move_kernel<G>), dim3(link_blocks + hbm_blocks + uniq_blocks),
+                                          dim3(MV_THREADS), 0, s, c.ctl, a.fills[par], a.rcopies[par], c.cache_data,
+                                          c.line_bytes, c.row_bytes, par, link_blocks, hbm_blocks, link_ch,
+                                          link_spread_knob(), u, reinterpret_cast<const uint32_t*>(stage),
+                                          (uint32_t)(sizeof(IdT) / 4)));
     const uint32_t copy_blocks = row_grid(rows_upper, g, 256);
     GIDS_DISPATCH_G(g, hipLaunchKernelGGL((group_copy_kernel<G>), dim3(copy_blocks), dim3(MV_THREADS), 0, s, c.ctl,
                                           a.wcopies[par], c.row_bytes, par));
-    bool any = false;
-    for (uint32_t i = 0; i < u.n; i++) any |= u.dst[i] != nullptr;
-    if (any) hipLaunchKernelGGL(group_uniq_kernel<IdT>, dim3(u.n), dim3(MV_THREADS), 0, s, c.ctl, par, u, stage);
 }
 
 void launch_calibrate(const char* store, uint64_t store_rows, uint32_t row_bytes, char* out, uint32_t n,
