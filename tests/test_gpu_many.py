@@ -223,6 +223,82 @@ def test_long_and_short_merged_calls_and_plain_steps_take_turns(gpu, oracle_mod,
              label="default streams")
 
 
+@pytest.mark.parametrize("own_push_stream", [True, False])
+def test_two_thousand_minibatches_in_merged_calls(gpu, oracle_mod, own_push_stream):
+    """A long run of merged calls on a small cache: the rings of events and counters wrap many times, every window
+    slot and both sets of group lists are reused hundreds of times, calls of 32, 7 and 19 steps take turns; the
+    counters of every minibatch (read one call behind), sampled tensors and the final tags and stamps must equal
+    the oracle's."""
+    torch, gids, GatherSession = gpu
+    cfg = CONFIGS["tiny"]
+    g = wl.make_graph(cfg.seed, cfg.n_nodes, cfg.ell, cfg.p4, cfg.d_max)
+    table = wl.normal_table(np.float32)
+    feats = wl.feature_rows(cfg.seed, np.arange(cfg.n_nodes), cfg.dim, table).view(np.uint8).reshape(cfg.n_nodes, -1)
+    hot = wl.hot_nodes(g, cfg.cpu_rows)
+    base = [wl.sample_minibatch(g, cfg.seed, b, cfg.fanouts, cfg.n_seeds) for b in range(41)]
+    n_b, W = 2000, 6
+    lists = [base[(9 * t) % 41] for t in range(n_b)]
+    sim = oracle_mod.Sim(cfg.n_nodes, cfg.cache_lines, cfg.ways, W, cfg.row_bytes, cfg.line_bytes, feats)
+    sim.set_hot(hot)
+    want, pushed = [], 0
+    check_rows = set(range(0, n_b, 131)) | {n_b - 1}
+    for t in range(n_b):
+        while pushed < n_b and pushed <= t + W:
+            sim.push(lists[pushed])
+            pushed += 1
+        want.append(sim.gather(lists[t], want_rows=t in check_rows))
+    with GatherSession(cfg.n_nodes, cfg.row_bytes, np.int32, cfg.cache_lines, cfg.ways, cfg.line_bytes, W, 1) as ses:
+        ses.store_view()[:] = feats
+        ses.pin_hot(hot)
+        dev = [ses.to_device(b) for b in base]
+        cap = max(len(b) for b in base)
+        ps = torch.cuda.Stream() if own_push_stream else None
+        # an output must stay untouched until its call has moved its rows: two calls' worth of buffers
+        ring = [torch.empty((cap, cfg.row_bytes), dtype=torch.uint8, device="cuda") for _ in range(64)]
+        uqs = [torch.empty(cap, dtype=torch.int32, device="cuda") for _ in range(64)]
+        kept, pushed = {}, 0
+        while pushed < W:
+            ses.push(dev[(9 * pushed) % 41], stream=ps)
+            pushed += 1
+        t, call, before = 0, 0, None
+        while t < n_b:
+            k = min((32, 7, 19)[call % 3], n_b - t)
+            call += 1
+            pushes, outs, uq = [], [], []
+            for i in range(k):
+                if pushed < n_b and pushed <= t + i + W:
+                    pushes.append(dev[(9 * pushed) % 41])
+                    pushed += 1
+                else:
+                    pushes.append(None)
+                if t + i in check_rows:
+                    kept[t + i] = (torch.empty((cap, cfg.row_bytes), dtype=torch.uint8, device="cuda"),
+                                   torch.empty(cap, dtype=torch.int32, device="cuda"))
+                    outs.append(kept[t + i][0])
+                    uq.append(kept[t + i][1])
+                else:
+                    outs.append(ring[(t + i) % 64])
+                    uq.append(uqs[(t + i) % 64])
+            seq0 = ses.gather_many(pushes, outs, uq, push_stream=ps)
+            if before is not None:                            # the counters of the call before, while this one runs
+                t0, k0, s0 = before
+                for i in range(k0):
+                    assert ses.stats(s0 + i).as_tuple() == tuple(int(x) for x in want[t0 + i][2]), t0 + i
+            before = (t, k, seq0)
+            t += k
+        t0, k0, s0 = before
+        for i in range(k0):
+            assert ses.stats(s0 + i).as_tuple() == tuple(int(x) for x in want[t0 + i][2]), t0 + i
+        torch.cuda.synchronize()
+        for t in sorted(check_rows):
+            u, rows, _ = want[t]
+            assert np.array_equal(kept[t][1][:len(u)].cpu().numpy(), u.astype(np.int32)), t
+            assert np.array_equal(kept[t][0][:len(u)].cpu().numpy(), rows), t
+        tags, stamps = ses.snapshot()
+        assert np.array_equal(tags, sim.tags) and np.array_equal(stamps, sim.stamps)
+        assert gids.gids_cache_many_calls(ses.cache)[1] == 0
+
+
 N_RANDOM = int(os.environ.get("GIDS_MANY_RANDOM_CASES", "32"))
 RANDOM_TALLY = [0, 0]                                         # calls through the merged kernels / the per-step kernels
 
