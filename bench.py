@@ -174,7 +174,7 @@ def main() -> int:
         result["other_workloads"] = {}
         # (tiny and medium twice: call by call, and 32 iterations merged per call, Section 3.2's remedy for
         # minibatches that are small beside the cost of launching and ordering their kernels)
-        for name in ("resident", "medium", "medium_merged", "tiny", "tiny_merged"):
+        for name in ("skew", "skew_merged", "resident", "medium", "medium_merged", "tiny", "tiny_merged"):
             if name == args.workload:
                 continue
             sub = copy.copy(args)
@@ -183,6 +183,10 @@ def main() -> int:
                 sub.workload, sub.accum, sub.many, sub.steps, sub.warmup = "tiny", 1, 32, 320, 32
             elif name == "medium_merged":
                 sub.workload, sub.accum, sub.many, sub.steps, sub.warmup = "medium", 1, 32, 128, 32
+            elif name == "skew_merged":
+                sub.workload, sub.accum, sub.many, sub.steps, sub.warmup = "skew", 1, 32, 128, 32
+            elif name in ("skew", "medium"):
+                sub.steps, sub.warmup = 60, 16
             elif name == "tiny":
                 sub.steps, sub.warmup = 320, 32
             log(f"--- other workload: {name}")
@@ -669,7 +673,7 @@ def run_point(args, env, cfg, window, raws, n_pre):
         "unique_ids_per_s": n_unique * scale / (total_ms * 1e-3),
         "config": {"workload": cfg.name, "n_nodes": cfg.n_nodes, "row_bytes": R, "cache_lines": cfg.cache_lines,
                    "ways": cfg.ways, "line_bytes": cfg.line_bytes, "cpu_buffer_rows": cfg.cpu_rows, "window": window,
-                   "fanouts": list(cfg.fanouts), "seeds_per_batch": cfg.n_seeds, "accum_threshold": args.accum, "accum_adaptive": bool(args.accum_adaptive), "merged_calls_of": args.many, "prewarm_lists": n_pre, "gpu_sampler": bool(args.gpu_sampler), "policy": args.policy, "hot_by": args.hot_by, "rows_per_line": args.rows_per_line, "id_stream": ("layerwise " + args.layerwise) if args.layerwise else "neighbourhood",
+                   "fanouts": list(cfg.fanouts), "seeds_per_batch": cfg.n_seeds, "accum_threshold": args.accum, "accum_adaptive": bool(args.accum_adaptive), "merged_calls_of": args.many, "merged_calls_through": dict(zip(("merged_kernels", "per_step_kernels"), gids.gids_cache_many_calls(ses.cache))) if args.many else None, "prewarm_lists": n_pre, "gpu_sampler": bool(args.gpu_sampler), "policy": args.policy, "hot_by": args.hot_by, "rows_per_line": args.rows_per_line, "id_stream": ("layerwise " + args.layerwise) if args.layerwise else "neighbourhood",
                    "id_dtype": cfg.index_dtype, "scaled_from": base.n_nodes if cfg.n_nodes != base.n_nodes else None},
         "per_step": {"unique": n_unique * scale / steps, "hit": n_hit * scale / steps, "cpu_hit": n_cpu * scale / steps,
                      "miss": n_miss * scale / steps, "bypass": n_byp * scale / steps,

@@ -278,14 +278,16 @@ int gids_gather_static(gids_cache* cache, const void* ids_dev, uint64_t n, void*
  * closed first, the call's own group closes with its last step (gids_stats of
  * step i: n_pending = rows of steps 0..i, flushed = 0; the last step: 0 and 1).
  * Every output of the call is complete, in stream order, when the call's work
- * ends.  For lists of up to 65,536 raw IDs over a table whose bitmap fits a
- * workgroup's LDS (1.3 M rows on gfx950), with ways <= 16, one row per line
- * and LDS room for a workgroup's share of every list of the call, the k steps
- * take four launches in all, however large k: one that deduplicates the pushed
- * lists (a workgroup and an LDS bitmap each), one that classifies the k
- * minibatches one after the other, each workgroup for its own share of the
- * cache sets and with that share's state in its LDS, and the group mover's
- * two.  Other caches and calls take the per-step kernels, still as one group.
+ * ends.  With ways <= 16, one row per line and LDS room for a workgroup's share
+ * of every list of the call (lists of tens of thousands of distinct IDs at
+ * k = 32, of more than a hundred thousand at k <= 8), the k steps take a fixed
+ * number of launches: one that deduplicates the pushed lists (a workgroup and
+ * an LDS bitmap each; on tables beyond 1.3 M rows three launches per list
+ * through the bitmap in device memory), one that classifies the k minibatches
+ * one after the other, each workgroup for its own share of the cache sets and,
+ * where it fits, with that share's state in its LDS, and the group mover's
+ * two.  Other caches and calls take the per-step kernels, still as one group;
+ * gids_cache_many_calls tells which way the calls of a cache went.
  * Calls of two steps and more classify on the library's internal stream
  * whatever the cache size (see `push_stream`).
  *   k              1 .. 32 (GIDS_ACCUM_MAX_MERGE)

@@ -188,6 +188,24 @@ struct gids_cache {
         HIP_TRY(hipStreamWaitEvent(to, e, 0));
         return GIDS_OK;
     }
+    // Distinct IDs per raw ID in the lists of this stream: the largest ratio among the newest finished gathers
+    // (1 until one has finished).  Sizes the merged classification, which the host must launch knowing raw
+    // lengths only.
+    double distinct_ratio = 1.0;
+    void update_distinct_ratio() {
+        if (!ring_host) return;
+        double best = 0.0;
+        int seen = 0;
+        for (uint64_t g = seq; g-- > 0 && seq - g <= (uint64_t)STATS_RING && seen < 16;) {
+            const int r = (int)(g % STATS_RING);
+            const StatsRec& rec = ring_host[r];
+            if (*reinterpret_cast<const volatile uint64_t*>(&rec.seq) != g) continue;   // not finished yet
+            if (raw_of[r] == 0 || rec.status) continue;
+            best = std::max(best, (double)rec.n_unique / (double)raw_of[r]);
+            seen++;
+        }
+        if (seen) distinct_ratio = std::min(1.0, best);
+    }
     // An error a kernel found stays in the device control block, so the record of the newest finished gather
     // carries it: calls that enqueue work look there first and refuse once the host can know.
     void poll_status() {
@@ -200,10 +218,10 @@ struct gids_cache {
             return;
         }
     }
-    uint64_t many_list_max = 65536; // merged kernels for lists up to this many raw IDs (GIDS_MANY_LIST_MAX)
+    uint64_t many_list_max = 1u << 20;  // merged kernels for lists up to this many raw IDs (GIDS_MANY_LIST_MAX)
     uint32_t many_meta_min = 2;         // merged calls of at least this many steps classify on the internal stream (GIDS_MANY_PIPELINE_MIN; 0: never)
     bool many_pool_forced = false;
-    uint64_t many_pool = 128 * 1024;    // LDS for a classifying workgroup's own list entries (GIDS_MANY_POOL, bytes; 0: none)
+    uint64_t many_pool = 152 * 1024;    // LDS for a classifying workgroup's own list entries (GIDS_MANY_POOL, bytes; 0: none)
     int fuse = 1;               // GIDS_FUSE=0: commit, queueing and counters as a kernel each; no merged kernels
     int move_blocks = 1 << 20;  // most workgroups the row mover uses for rows that stay in HBM
     int link_blocks = 48;       // ... for rows that cross the host link (persistent)
@@ -828,11 +846,16 @@ struct CacheT final : gids_cache {
                 c2--;
             }
         }
-        const bool fast = store->n_rows <= many_max_rows() && ways <= many_max_ways() && rows_per_line == 1 &&
-                          (fuse & 1) && longest_raw <= many_list_max &&
+        // What the classification is sized for: the longest list's distinct IDs.  The host knows raw lengths only;
+        // the finished gathers tell how many distinct IDs a raw list of this stream tends to hold.
+        update_distinct_ratio();
+        const uint64_t longest_est = std::min<uint64_t>(store->n_rows,
+                                                        (uint64_t)std::ceil((double)longest_raw * std::min(1.0, distinct_ratio * 1.25)));
+        const bool fast = store->n_rows < (1ull << 32) && n_sets < (1ull << 32) && ways <= many_max_ways() &&
+                          rows_per_line == 1 && (fuse & 1) && longest_raw <= many_list_max &&
                           (many_pool_forced ||
                            many_fits(store->n_rows, n_sets, ways, words_per_set, sizeof(IdT), n_lists_upper,
-                                     std::min<uint64_t>(longest_raw, store->n_rows), many_pool));
+                                     std::max<uint64_t>(longest_est, 1), many_pool));
         int rc;
         if (!fast) {
             // large tables, high associativity: the same steps through the per-step kernels, still one group
@@ -875,7 +898,8 @@ struct CacheT final : gids_cache {
             many_plan_cap = total_upper + total_upper / 2;
         }
         if ((rc = ensure_queue(total_upper))) return rc;
-        if ((rc = many_enqueue(k, push_ids, push_n, outs, caps, uniques, total_upper, longest, ps, s))) sticky = rc;
+        (void)longest;
+        if ((rc = many_enqueue(k, push_ids, push_n, outs, caps, uniques, total_upper, std::max<uint64_t>(longest_est, 1), ps, s))) sticky = rc;
         return rc;
     }
 
@@ -959,7 +983,15 @@ struct CacheT final : gids_cache {
             head = (head + 1) % slots.size();
             count--;
         }
-        launch_dedup_small<IdT>(mp, n_push, store->n_rows, ctl, m);
+        if (store->n_rows <= many_max_rows()) {
+            launch_dedup_small<IdT>(mp, n_push, store->n_rows, ctl, m);
+        } else {
+            // a table whose bitmap does not fit a workgroup's LDS: the pushed lists go through the bitmap in
+            // device memory one after the other; their future-reuse counters are raised by the classification,
+            // step by step, as for the lists above
+            for (uint32_t q = 0; q < n_push; q++)
+                dedup(mp.ids[q], mp.n[q], mp.dst[q], &ctl->win_n[mp.slot[q]], nullptr, false, m);
+        }
         // the caller's ID buffers are read by that kernel alone: the push stream goes on as soon as it is through
         // (were it held until the classification ends, the next call's lists would be ready that much later)
         if (on_meta && n_push && (rc = edge(meta, ps))) return rc;

@@ -6,8 +6,10 @@
 //
 //   dedup_small   one workgroup per pushed list: the list is marked into a
 //                 bitmap in LDS (tables whose bitmap fits a workgroup's LDS:
-//                 1.3 M rows on gfx950), scanned and written out as ascending
-//                 distinct IDs.  Nothing else of the push happens here.
+//                 1.3 M rows on gfx950; larger tables go through the
+//                 per-list kernels and the bitmap in device memory), scanned
+//                 and written out as ascending distinct IDs.  Nothing else
+//                 of the push happens here.
 //   classify_many the k steps one after the other inside one kernel.  A step's
 //                 decisions depend only on the state of the cache sets its IDs
 //                 fall into, and so does everything a step changes (tags,
@@ -418,14 +420,14 @@ __device__ __forceinline__ void wave_count(uint32_t* counter, bool flag) {
 template <typename IdT, int WAYS, typename State>
 __device__ __forceinline__ void steps_from_pool(const CacheView<IdT>& c, const AccumView& a, const State& st,
                                                 uint32_t group, const ManySteps<IdT>& m, uint32_t n_ok, uint32_t stamp0,
-                                                const IdT* pool_v, const uint32_t* pool_j, const uint32_t* pool_cpu,
+                                                const uint32_t* pool_v, const uint32_t* pool_j, const uint32_t* pool_cpu,
                                                 const uint32_t* own_n, uint32_t (*cnt)[5], const PlacesLocal& places) {
     const uint32_t tid = threadIdx.x;
     const uint32_t cap = m.share_cap;
     const uint32_t n_sets = (uint32_t)c.n_sets;
     // the list pushed in step 0: one more buffered future use for each of its nodes (Section 3.4, Fig. 6)
     if (m.pushed_list[0] != MANY_NO_LIST && tid < own_n[m.pushed_list[0]]) {
-        const uint32_t pv = (uint32_t)pool_v[(size_t)m.pushed_list[0] * cap + tid];
+        const uint32_t pv = pool_v[(size_t)m.pushed_list[0] * cap + tid];
         const uint32_t round = fast_div(m.div_sets, pv), set = pv - round * n_sets;
         uint8_t* ctr = st.counter(st.node_of(st.slot_of(set, set >> m.wg_shift), round, pv));
         *ctr = (uint8_t)(*ctr + 1);
@@ -445,7 +447,7 @@ __device__ __forceinline__ void steps_from_pool(const CacheView<IdT>& c, const A
         for (int w = 0; w < WAYS; w++) tg[w] = (IdT)-1;
         // ---- probe, against the state at the start of the minibatch
         if (have) {
-            v = (uint32_t)pool_v[(size_t)h * cap + tid];
+            v = pool_v[(size_t)h * cap + tid];
             j = pool_j[(size_t)h * cap + tid];
             const uint32_t cpu_row = pool_cpu[(size_t)h * cap + tid];
             round = fast_div(m.div_sets, v);
@@ -503,7 +505,7 @@ __device__ __forceinline__ void steps_from_pool(const CacheView<IdT>& c, const A
         // probe, which must see them, waits behind the barrier
         const uint32_t pl = i + 1 < m.k ? m.pushed_list[i + 1] : MANY_NO_LIST;
         if (pl != MANY_NO_LIST && tid < own_n[pl]) {
-            const uint32_t pv = (uint32_t)pool_v[(size_t)pl * cap + tid];
+            const uint32_t pv = pool_v[(size_t)pl * cap + tid];
             const uint32_t pr = fast_div(m.div_sets, pv), ps = pv - pr * n_sets;
             uint8_t* ctr = st.counter(st.node_of(st.slot_of(ps, ps >> m.wg_shift), pr, pv));
             *ctr = (uint8_t)(*ctr + 1);
@@ -553,8 +555,8 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
     char** s_pout = reinterpret_cast<char**>(lds_raw);
     unsigned long long* s_mm = lds_raw + n_l;
     IdT* s_tag = reinterpret_cast<IdT*>(s_mm + n_mw);
-    IdT* pool_v = s_tag + n_l;
-    uint32_t* pool_j = reinterpret_cast<uint32_t*>(pool_v + n_pool);
+    uint32_t* pool_v = reinterpret_cast<uint32_t*>(s_tag + n_l);
+    uint32_t* pool_j = pool_v + n_pool;
     uint32_t* pool_cpu = pool_j + n_pool;
     int32_t* s_stamp = reinterpret_cast<int32_t*>(pool_cpu + n_pool);
     uint32_t* s_pend = reinterpret_cast<uint32_t*>(s_stamp + n_l);
@@ -611,7 +613,7 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
                 if ((set & (n_wg - 1)) != me) continue;       // (the number of workgroups is a power of two)
                 const uint32_t pos = atomicAdd(&own_n[ll[u]], 1u);
                 if (pos < cap) {
-                    pool_v[(size_t)ll[u] * cap + pos] = (IdT)vv[u];
+                    pool_v[(size_t)ll[u] * cap + pos] = vv[u];
                     pool_j[(size_t)ll[u] * cap + pos] = jj[u];
                 } else {
                     overflow = 1;
@@ -897,7 +899,7 @@ ManyShape many_shape(uint64_t n_rows, uint64_t n_sets, uint32_t ways, uint32_t w
     // where that fits; a workgroup whose share of some list is larger reads the lists from memory instead
     const uint64_t room = MANY_LDS_MAX_BYTES - (sh.resident ? sh.state : 0) - 16;
     if (pool_bytes > room) pool_bytes = room;
-    const uint64_t entry = id_bytes + 8;
+    const uint64_t entry = 12;                                // ID (as 32 bits), position in its list, CPU-buffer row
     sh.share = (longest + sh.g - 1) / sh.g;
     uint64_t cap = n_lists ? pool_bytes / (entry * n_lists) : 0;
     if (cap > 4 * sh.share + 16) cap = 4 * sh.share + 16;
@@ -931,7 +933,7 @@ void launch_classify_many(const CacheView<IdT>& c, const AccumView& a, uint32_t 
     m.rounds = sh.rounds;
     m.resident = sh.resident;
     m.share_cap = (uint32_t)sh.cap;
-    const size_t lds = (size_t)(sh.cap * m.n_lists * (sizeof(IdT) + 8) + (sh.resident ? sh.state : 0) + 16);
+    const size_t lds = (size_t)(sh.cap * m.n_lists * 12 + (sh.resident ? sh.state : 0) + 16);
 #define GIDS_CLASSIFY_MANY(W) \
     launch_classify_many_ways<IdT, W>(c, a, group, m, (uint32_t)g, threads, lds, plan_all, ring, ring_size, s)
     switch (c.ways) {

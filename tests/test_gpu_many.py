@@ -42,7 +42,7 @@ def with_env(knobs, make):
 
 
 def run_many(gpu, oracle, feats, batches, *, id_dtype, lines, ways, window, ks, hot=None, policy=None, pipeline="0",
-             fuse=None, pool=None, resident=None, meta_min=None, expect_merged=None, label=""):
+             fuse=None, pool=None, resident=None, meta_min=None, list_max=None, expect_merged=None, label=""):
     """ks: the sizes of the merged calls, in order (0 = one plain push + gather step in between);
     cycles until every list is gathered."""
     torch, gids, GatherSession = gpu
@@ -71,6 +71,7 @@ def run_many(gpu, oracle, feats, batches, *, id_dtype, lines, ways, window, ks, 
     if resident is not None:
         knobs["GIDS_MANY_RESIDENT"] = resident
     knobs["GIDS_MANY_PIPELINE_MIN"] = meta_min
+    knobs["GIDS_MANY_LIST_MAX"] = list_max
     ses = with_env(knobs, lambda: GatherSession(n_rows, R, id_dtype, lines, ways, R, window, 1000))
     with ses:
         ses.store_view()[:] = feats_u8
@@ -308,7 +309,7 @@ def test_random_merged_calls(gpu, oracle_mod, case):
     """Seeded random geometry, window, list shapes, call sizes and the library's knobs for the merged kernels (the
     draw is printed, so a failure names its case)."""
     rng = np.random.default_rng(31_000 + case)
-    n = int(rng.choice([64, 65, 1000, 4097, 30_011, 200_003]))
+    n = int(rng.choice([64, 65, 1000, 4097, 30_011, 200_003, 2_000_003]))
     ways = int(rng.choice([1, 2, 4, 8, 16]))
     n_sets = int(rng.integers(1, max(2, n // (ways * int(rng.integers(1, 60))) + 2)))
     row_bytes = int(rng.choice([16, 64, 512, 1040]))
@@ -363,22 +364,23 @@ def test_merged_calls_through_the_per_step_kernels(gpu, oracle_mod):
                  hot=rng.choice(n, 60, replace=False), pipeline=pipeline, fuse="0", expect_merged=False, label="per-step")
 
 
-@pytest.mark.parametrize("n", [600_000, 1_500_000])
+@pytest.mark.parametrize("n", [600_000, 1_500_000, 5_000_000])
 def test_tables_beyond_64_kib_of_bitmap(gpu, oracle_mod, n):
     """600,000 rows: the merged dedup's LDS bitmap needs more than the default 64 KiB of a workgroup; 1,500,000
-    rows: more than a workgroup can have, the calls take the per-step kernels.  Then a list beyond the merged
-    kernels' length limit: the calls that read it take the per-step kernels, the others do not."""
+    and 5,000,000 rows: more than a workgroup can have, the pushed lists of a call are deduplicated through the
+    bitmap in device memory, one after the other.  Then a list beyond the merged kernels' length limit (set to
+    10,000 here): the calls that read it take the per-step kernels, the others do not."""
     rng = np.random.default_rng(78)
     feats = rng.integers(0, 256, size=(n, 16), dtype=np.uint8)
     batches = [rng.integers(0, n, size=3000) for _ in range(12)]
     batches[5] = rng.integers(0, n, size=20_000)
-    run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=1024, ways=8, window=2, ks=[4],
-             expect_merged=n == 600_000, label=f"{n} rows")
-    if n == 600_000:
-        batches[5] = rng.integers(0, n, size=70_000)
-        merged, per_step = run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=1024, ways=8, window=2,
-                                    ks=[4], label=f"{n} rows, a list of 70,000")
-        assert merged > 0 and per_step > 0
+    batches[8] = np.minimum(rng.zipf(1.2, size=9000) - 1, n - 1)
+    for pipeline in ("0", "1"):
+        run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=1024, ways=8, window=2, ks=[4, 0, 3],
+                 pipeline=pipeline, expect_merged=True, label=f"{n} rows")
+    merged, per_step = run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=1024, ways=8, window=2,
+                                ks=[4], list_max="10000", label=f"{n} rows, no lists beyond 10,000")
+    assert merged > 0 and per_step > 0
 
 
 def test_merged_call_errors(gpu):
