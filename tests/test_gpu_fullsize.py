@@ -65,13 +65,20 @@ def drive(ses, torch, raws, window, cap_rows, row_bytes, keep):
     return outs, uniqs, stats
 
 
-def drive_merged(ses, torch, raws, window, row_bytes, k=32):
+def drive_merged(ses, torch, raws, window, row_bytes, k=32, keep=None, cap_rows=None):
     """The same protocol through gids_gather_many, k steps per call (each pushes the list that keeps the window
-    full and gathers the head), as bench.py --many issues them; every minibatch keeps its tensor."""
+    full and gathers the head), as bench.py --many issues them; the minibatches in `keep` (all of them when None)
+    keep their tensors, the others write to a ring of 2 k buffers of cap_rows rows."""
     dev = [ses.to_device(r) for r in raws]
     n_b = len(raws)
-    outs = {t: torch.empty((max(1, len(np.unique(raws[t]))), row_bytes), dtype=torch.uint8, device="cuda") for t in range(n_b)}
-    uniqs = {t: torch.empty(outs[t].shape[0], dtype=ses.torch_id, device="cuda") for t in range(n_b)}
+    keep = set(range(n_b)) if keep is None else keep
+    ring = [] if len(keep) == n_b else [(torch.empty((cap_rows, row_bytes), dtype=torch.uint8, device="cuda"),
+                                         torch.empty(cap_rows, dtype=ses.torch_id, device="cuda")) for _ in range(2 * k)]
+    outs = {t: torch.empty((max(1, len(np.unique(raws[t]))), row_bytes), dtype=torch.uint8, device="cuda") for t in keep}
+    uniqs = {t: torch.empty(outs[t].shape[0], dtype=ses.torch_id, device="cuda") for t in keep}
+    for t in range(n_b):
+        if t not in keep:
+            outs[t], uniqs[t] = ring[t % (2 * k)]
     stats, pushed, calls = {}, 0, []
     push_stream = torch.cuda.Stream()
     torch.cuda.synchronize()
@@ -164,6 +171,11 @@ def test_medium_full_size(oracle_mod, merged):
                 print(f"[fullsize medium] {t + 1} minibatches: counters, ID lists and whole tensors equal", flush=True)
         tags, stamps = ses.snapshot()
         assert np.array_equal(tags, sim.tags) and np.array_equal(stamps, sim.stamps)
+        if merged_k:
+            import paper_2306_16384_amd as gids
+            through = gids.gids_cache_many_calls(ses.cache)
+            print(f"[fullsize {label}] merged calls through the merged kernels: {through[0]}, the per-step kernels: {through[1]}", flush=True)
+            assert through[0] > through[1], through           # (the first call knows no distinct-per-raw ratio yet)
 
 
 def pinnable(cfg_name, sizes):
@@ -191,9 +203,11 @@ def sample_lists(g, cfg, n_b, rank_table=None):
     return raws
 
 
-def run_big(oracle_mod, cfg, store, store_np, raws, keep, hot=None, after_each=None, window=None, label=None):
+def run_big(oracle_mod, cfg, store, store_np, raws, keep, hot=None, after_each=None, window=None, label=None,
+            merged_k=0):
     """Counters of every minibatch against the oracle's simulator; on the kept minibatches the distinct-ID list
-    and every gathered row; final tags and stamps.  Returns the per-minibatch counters."""
+    and every gathered row; final tags and stamps.  Returns the per-minibatch counters.  merged_k: through
+    gids_gather_many, that many steps per call."""
     import torch
     from paper_2306_16384_amd.session import GatherSession
     n_b = len(raws)
@@ -202,10 +216,13 @@ def run_big(oracle_mod, cfg, store, store_np, raws, keep, hot=None, after_each=N
     cap = max(len(r) for r in raws)                           # raw length bounds the distinct count
     t0 = time.time()
     with GatherSession(cfg.n_nodes, cfg.row_bytes, np.int64, cfg.cache_lines, cfg.ways, cfg.line_bytes,
-                       window, store_handle=store) as ses:
+                       window, 1 if merged_k else 0, store_handle=store) as ses:
         if hot is not None:
             ses.pin_hot(hot)
-        outs, uniqs, stats_of = drive(ses, torch, raws, window, cap, cfg.row_bytes, keep)
+        if merged_k:
+            outs, uniqs, stats_of = drive_merged(ses, torch, raws, window, cfg.row_bytes, merged_k, keep, cap)
+        else:
+            outs, uniqs, stats_of = drive(ses, torch, raws, window, cap, cfg.row_bytes, keep)
         t_gpu = time.time() - t0
         sim = oracle_mod.Sim(cfg.n_nodes, cfg.cache_lines, cfg.ways, window)      # counts only
         if hot is not None:
@@ -273,7 +290,10 @@ def test_cache_resident_full_size(oracle_mod):
 def big_world(oracle_mod):
     """Large and the skew sweep share one graph, one hot set and one 57 GB table (the configurations differ in
     fanout, seeds, cache shape and window only), pinned and filled once."""
+    import torch
     import paper_2306_16384_amd as gids
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU (no CPU fallback exists)")
     cfg, store = pinnable("large", (28_000_000, 14_000_000, 7_000_000))
     try:
         print(f"[fullsize] table of {cfg.n_nodes} rows pinned", flush=True)
@@ -298,6 +318,27 @@ def test_large_at_benchmark_size(oracle_mod, big_world):
     raws = sample_lists(big_world["g"], cfg, n_b)
     run_big(oracle_mod, cfg, big_world["store"], big_world["store_np"], raws, kept_minibatches(n_b, cfg.window),
             hot=big_world["hot"])
+
+
+def test_large_in_merged_calls(oracle_mod, big_world):
+    """120 minibatches of Large through gids_gather_many, 8 steps per call: the pushed lists go through the bitmap in
+    device memory, the classification keeps its lists in LDS and the sets' state in memory."""
+    cfg = big_world["cfg"]
+    n_b = 120
+    raws = sample_lists(big_world["g"], cfg, n_b)
+    run_big(oracle_mod, cfg, big_world["store"], big_world["store_np"], raws, kept_minibatches(n_b, cfg.window),
+            hot=big_world["hot"], merged_k=8, label="large merged")
+
+
+def test_skew_in_merged_calls(oracle_mod, big_world):
+    """160 minibatches of the skew configuration (Zipf 0.8 seeds, depth 4) through gids_gather_many, 32 steps per call."""
+    base = big_world["cfg"]
+    cfg = wl.scaled(CONFIGS["skew"], base.n_nodes)
+    n_b = 160
+    rank_table = wl.synth.zipf_rank_table(cfg.n_nodes, 0.8)
+    raws = sample_lists(big_world["g"], cfg, n_b, rank_table)
+    run_big(oracle_mod, cfg, big_world["store"], big_world["store_np"], raws, kept_minibatches(n_b, cfg.window),
+            hot=big_world["hot"], merged_k=32, label="skew merged")
 
 
 SKEW_S = (0.0, 0.8, 1.2)
