@@ -2,6 +2,8 @@
 // ownership, the window FIFO and the order in which the kernels of one push or
 // gather are enqueued.  No step of the gather itself runs on the host.
 #include <algorithm>
+#include <atomic>
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
@@ -200,6 +202,7 @@ struct gids_cache {
             const int r = (int)(g % STATS_RING);
             const StatsRec& rec = ring_host[r];
             if (*reinterpret_cast<const volatile uint64_t*>(&rec.seq) != g) continue;   // not finished yet
+            std::atomic_thread_fence(std::memory_order_acquire);  // the record's fields were written before its seq
             if (raw_of[r] == 0 || rec.status) continue;
             best = std::max(best, (double)rec.n_unique / (double)raw_of[r]);
             seen++;
@@ -213,6 +216,7 @@ struct gids_cache {
         for (uint64_t g = seq; g-- > 0 && seq - g <= (uint64_t)STATS_RING;) {
             const StatsRec& rec = ring_host[g % STATS_RING];
             if (*reinterpret_cast<const volatile uint64_t*>(&rec.seq) != g) continue;   // not finished yet
+            std::atomic_thread_fence(std::memory_order_acquire);
             const int32_t st = *reinterpret_cast<const volatile int32_t*>(&rec.status);
             if (st) sticky = st;
             return;
