@@ -180,11 +180,11 @@ def main() -> int:
             sub = copy.copy(args)
             sub.workload, sub.steps, sub.warmup, sub.cpu_seconds = name, min(args.steps, 20), min(args.warmup, 6), 4.0
             if name == "tiny_merged":
-                sub.workload, sub.accum, sub.many, sub.steps, sub.warmup = "tiny", 1, 32, 320, 32
+                sub.workload, sub.accum, sub.many, sub.steps, sub.warmup = "tiny", 1, 32, 1280, 32
             elif name == "medium_merged":
-                sub.workload, sub.accum, sub.many, sub.steps, sub.warmup = "medium", 1, 32, 128, 32
+                sub.workload, sub.accum, sub.many, sub.steps, sub.warmup = "medium", 1, 32, 320, 32
             elif name == "skew_merged":
-                sub.workload, sub.accum, sub.many, sub.steps, sub.warmup = "skew", 1, 32, 128, 32
+                sub.workload, sub.accum, sub.many, sub.steps, sub.warmup = "skew", 1, 32, 192, 32
             elif name in ("skew", "medium"):
                 sub.steps, sub.warmup = 60, 16
             elif name == "tiny":
