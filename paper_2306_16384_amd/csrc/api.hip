@@ -802,7 +802,7 @@ struct CacheT final : gids_cache {
         if (!outs || !caps) return fail(GIDS_E_INVAL, "gids_gather_many: out_dev / out_capacity_rows is NULL");
         // the window protocol over the whole call, before anything is enqueued
         uint32_t cnt = count;
-        uint64_t total_upper = 0, longest = 1;
+        uint64_t total_upper = 0;
         for (uint32_t i = 0; i < k; i++) {
             const bool pushes = push_ids && push_ids[i];
             if (pushes) {
@@ -884,12 +884,10 @@ struct CacheT final : gids_cache {
                     WindowSlot& sl = slots[(h + c2) % slots.size()];
                     if ((rc = ensure_slot(sl, push_n[i]))) return rc;
                     sl.n_raw = push_n[i];
-                    longest = std::max(longest, std::min<uint64_t>(push_n[i], store->n_rows));
                     c2++;
                 }
                 const uint64_t up = std::min<uint64_t>(slots[h].n_raw, store->n_rows);
                 total_upper += up;
-                longest = std::max(longest, up);
                 h = (h + 1) % slots.size();
                 c2--;
             }
@@ -902,7 +900,6 @@ struct CacheT final : gids_cache {
             many_plan_cap = total_upper + total_upper / 2;
         }
         if ((rc = ensure_queue(total_upper))) return rc;
-        (void)longest;
         if ((rc = many_enqueue(k, push_ids, push_n, outs, caps, uniques, total_upper, std::max<uint64_t>(longest_est, 1), ps, s))) sticky = rc;
         return rc;
     }
