@@ -88,6 +88,9 @@ def main() -> int:
     ap.add_argument("--accum", type=int, default=0,
                     help="accumulator threshold in node accesses (raw list entries) per merged group of minibatches "
                          "(0 = every gather moves its own rows)")
+    ap.add_argument("--group-dedup", action="store_true",
+                    help="with --many: a CPU-buffer row that several steps of a call need crosses the link once "
+                         "(gids_cache_set_group_dedup); the roofline fractions printed still charge every access one row")
     ap.add_argument("--many", type=int, default=0, metavar="K",
                     help="issue the steps K at a time through gids_gather_many (merged iterations: one call pushes K "
                          "lists and gathers K minibatches as one group); needs --accum > 0 for the group lists")
@@ -174,7 +177,10 @@ def main() -> int:
         result["other_workloads"] = {}
         # (tiny and medium twice: call by call, and 32 iterations merged per call, Section 3.2's remedy for
         # minibatches that are small beside the cost of launching and ordering their kernels)
-        for name in ("skew", "skew_merged", "resident", "medium", "medium_merged", "tiny", "tiny_merged"):
+        # (and Large and Medium once more in merged calls in which a CPU-buffer row that several steps of a call need
+        # crosses the link once: gids_cache_set_group_dedup, outside the per-minibatch cost model)
+        for name in ("large_merged_dedup", "skew", "skew_merged", "resident", "medium", "medium_merged",
+                     "medium_merged_dedup", "tiny", "tiny_merged"):
             if name == args.workload:
                 continue
             sub = copy.copy(args)
@@ -183,6 +189,10 @@ def main() -> int:
                 sub.workload, sub.accum, sub.many, sub.steps, sub.warmup = "tiny", 1, 32, 1280, 32
             elif name == "medium_merged":
                 sub.workload, sub.accum, sub.many, sub.steps, sub.warmup = "medium", 1, 32, 320, 32
+            elif name == "large_merged_dedup":
+                sub.workload, sub.accum, sub.many, sub.group_dedup, sub.steps, sub.warmup = "large", 1, 8, True, 64, 32
+            elif name == "medium_merged_dedup":
+                sub.workload, sub.accum, sub.many, sub.group_dedup, sub.steps, sub.warmup = "medium", 1, 32, True, 320, 32
             elif name == "skew_merged":
                 sub.workload, sub.accum, sub.many, sub.steps, sub.warmup = "skew", 1, 32, 192, 32
             elif name in ("skew", "medium"):
@@ -192,7 +202,8 @@ def main() -> int:
             log(f"--- other workload: {name}")
             r = run_workload(sub, shared)
             result["other_workloads"][name] = {
-                "merged_calls_of": sub.many,
+                "merged_calls_of": sub.many, "group_dedup": bool(sub.group_dedup),
+                "weighted_roofline_frac_of_bytes_moved": r["weighted_roofline"]["frac_of_bytes_moved"],
                 "value": r["value"], "unit": r["unit"], "ms_per_step": r["ms_per_step"], "steps": r["steps"],
                 "unique_ids_per_s": r["unique_ids_per_s"], "workload": r["config"]["workload"],
                 "per_step": r["per_step"], "weighted_roofline_frac": r["weighted_roofline"]["frac"],
@@ -427,6 +438,8 @@ def run_point(args, env, cfg, window, raws, n_pre):
         ses.set_rows_per_line(args.rows_per_line)
     if args.accum and args.accum_adaptive:
         ses.set_accum_mode(gids.GIDS_ACCUM_ADAPTIVE)
+    if args.group_dedup:
+        ses.set_group_dedup(True)
     log(f"cache W={window}: created, CPU buffer {len(hot) * R / 1e9:.2f} GB pinned ({time.time() - t0:.1f} s)")
     dev = [ses.to_device(r) for r in raws[:n_batches]]
     sampler = None
@@ -544,6 +557,7 @@ def run_point(args, env, cfg, window, raws, n_pre):
     n_cpu = sum(s.n_cpu_hit for s in timed)
     n_miss = sum(s.n_miss for s in timed)
     n_byp = sum(s.n_bypass for s in timed)
+    n_again = sum(s.n_cpu_again for s in timed)                 # CPU-buffer rows that came as a copy inside device memory
     scale = steps / max(1, len(timed))
     # Bytes the method must move.  One row per line: a miss's row is read once and written to the output and
     # to its line.  Several rows per line: a filled line is read from the store and written to the cache in
@@ -673,15 +687,19 @@ def run_point(args, env, cfg, window, raws, n_pre):
         "unique_ids_per_s": n_unique * scale / (total_ms * 1e-3),
         "config": {"workload": cfg.name, "n_nodes": cfg.n_nodes, "row_bytes": R, "cache_lines": cfg.cache_lines,
                    "ways": cfg.ways, "line_bytes": cfg.line_bytes, "cpu_buffer_rows": cfg.cpu_rows, "window": window,
-                   "fanouts": list(cfg.fanouts), "seeds_per_batch": cfg.n_seeds, "accum_threshold": args.accum, "accum_adaptive": bool(args.accum_adaptive), "merged_calls_of": args.many, "merged_calls_through": dict(zip(("merged_kernels", "per_step_kernels"), gids.gids_cache_many_calls(ses.cache))) if args.many else None, "prewarm_lists": n_pre, "gpu_sampler": bool(args.gpu_sampler), "policy": args.policy, "hot_by": args.hot_by, "rows_per_line": args.rows_per_line, "id_stream": ("layerwise " + args.layerwise) if args.layerwise else "neighbourhood",
+                   "fanouts": list(cfg.fanouts), "seeds_per_batch": cfg.n_seeds, "accum_threshold": args.accum, "accum_adaptive": bool(args.accum_adaptive), "merged_calls_of": args.many, "group_dedup": bool(args.group_dedup), "merged_calls_through": dict(zip(("merged_kernels", "per_step_kernels"), gids.gids_cache_many_calls(ses.cache))) if args.many else None, "prewarm_lists": n_pre, "gpu_sampler": bool(args.gpu_sampler), "policy": args.policy, "hot_by": args.hot_by, "rows_per_line": args.rows_per_line, "id_stream": ("layerwise " + args.layerwise) if args.layerwise else "neighbourhood",
                    "id_dtype": cfg.index_dtype, "scaled_from": base.n_nodes if cfg.n_nodes != base.n_nodes else None},
         "per_step": {"unique": n_unique * scale / steps, "hit": n_hit * scale / steps, "cpu_hit": n_cpu * scale / steps,
                      "miss": n_miss * scale / steps, "bypass": n_byp * scale / steps,
-                     "line_fills": n_fills * scale / steps},
+                     "line_fills": n_fills * scale / steps, "cpu_again": n_again * scale / steps},
         "weighted_roofline": {"hbm_peak_GBs": HBM_PEAK_GBS, "link_peak_GBs": LINK_PEAK_GBS,
                               "t_roof_ms_per_step": t_roof_ms / steps, "frac": t_roof_ms / total_ms,
                               "frac_overlap_bound": t_overlap_ms / total_ms,
-                              "roofline_gathered_GBs": gathered_bytes / (t_roof_ms * 1e-3) / 1e9},
+                              "roofline_gathered_GBs": gathered_bytes / (t_roof_ms * 1e-3) / 1e9,
+                              # the same with the bytes that really moved: a CPU-buffer row that came as a copy
+                              # (gids_cache_set_group_dedup) is R less over the link and R more out of HBM
+                              "frac_of_bytes_moved": ((link_bytes - n_again * scale * R) / (LINK_PEAK_GBS * 1e9) +
+                                                      (hbm_bytes + n_again * scale * R) / (HBM_PEAK_GBS * 1e9)) * 1e3 / total_ms},
         "roofline": roof,
         "link_calibration": {"GBs": env["link_rows_per_s"] * R / 1e9, "overhead_us": env["link_overhead_s"] * 1e6,
                              "rows_for_95pct_eq2_3": gids.gids_accum_threshold(env["link_rows_per_s"],

@@ -78,7 +78,11 @@ typedef struct gids_cache gids_cache;
  * i.e. when every row of its output and of the earlier queued ones has been
  * written by then; without it they are 0 and 1.  n_line_fills = cache
  * lines this minibatch fills from the store: n_miss - n_bypass with one row
- * per line, fewer when several missing rows share a line. */
+ * per line, fewer when several missing rows share a line.  n_cpu_again (a
+ * subset of n_cpu_hit; 0 unless gids_cache_set_group_dedup is on) counts the
+ * CPU-buffer rows that an earlier step of the same merged call already brings
+ * over the link and that this minibatch receives as a copy inside device
+ * memory. */
 typedef struct gids_stats {
     uint64_t seq;       /* 0-based index of the gather call on this cache */
     uint64_t n_unique;
@@ -90,6 +94,7 @@ typedef struct gids_stats {
     int32_t flushed;
     int32_t status;     /* GIDS_OK or the GIDS_E_* the device found */
     uint64_t n_line_fills;
+    uint64_t n_cpu_again;
 } gids_stats;
 
 /* The feature table (Section 2.1: an N x D matrix, one row per node).
@@ -166,6 +171,19 @@ int gids_cache_destroy(gids_cache* cache);
 #define GIDS_ACCUM_LAG 16
 #define GIDS_ACCUM_MAX_RAISE 8
 int gids_cache_set_accum_mode(gids_cache* cache, int mode);
+
+/* Section 3.2 merges the accesses of consecutive iterations; merged, accesses to
+ * the same row of the constant CPU buffer (Section 3.3) can be served by one
+ * transfer.  on != 0: within one gids_gather_many call that runs through the
+ * merged kernels, a CPU-buffer row that several steps need crosses the host
+ * link once, for the first of them, and reaches the others' outputs as a copy
+ * of that output row inside device memory (after the call's fills).  Outputs
+ * and counters are the same either way (n_cpu_hit counts every access); what
+ * changes is the traffic over the link.  Off by default: the per-minibatch
+ * cost model of the measurements charges every CPU-buffer hit one row over the
+ * link.  Needs a cache created with accum_threshold > 0; not while a group of
+ * minibatches is open (GIDS_E_INVAL). */
+int gids_cache_set_group_dedup(gids_cache* cache, int on);
 
 /* Base replacement policy, i.e. the order in which the evictable ways of a set
  * are given to misses (window pinning applies to both; call before the first

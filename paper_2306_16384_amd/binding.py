@@ -14,7 +14,7 @@ GIDS_E_INVAL, GIDS_E_NOMEM, GIDS_E_RANGE, GIDS_E_ORDER, GIDS_E_FULL, GIDS_E_HIP,
 
 EXPORTS = [
     "gids_store_create", "gids_store_host_ptr", "gids_store_destroy", "gids_store_calibrate", "gids_cache_create", "gids_cache_destroy",
-    "gids_cache_reserve", "gids_cache_set_policy", "gids_cache_set_accum_mode", "gids_cpu_buffer_pin", "gids_window_push", "gids_gather", "gids_gather_static", "gids_gather_many", "gids_flush", "gids_stats_read",
+    "gids_cache_reserve", "gids_cache_set_policy", "gids_cache_set_accum_mode", "gids_cache_set_group_dedup", "gids_cpu_buffer_pin", "gids_window_push", "gids_gather", "gids_gather_static", "gids_gather_many", "gids_flush", "gids_stats_read",
     "gids_cache_gathers", "gids_cache_many_calls", "gids_cache_snapshot", "gids_cache_set_rows_per_line", "gids_profile_enable", "gids_profile_read", "gids_window_push_dev",
     "gids_graph_create", "gids_graph_destroy", "gids_sample_capacity", "gids_sample", "gids_graph_visit_scores", "gids_graph_reverse_pagerank", "gids_accum_threshold", "gids_last_error",
 ]
@@ -23,7 +23,7 @@ EXPORTS = [
 class gids_stats(C.Structure):
     _fields_ = [("seq", C.c_uint64), ("n_unique", C.c_uint64), ("n_hit", C.c_uint64), ("n_cpu_hit", C.c_uint64),
                 ("n_miss", C.c_uint64), ("n_bypass", C.c_uint64), ("n_pending", C.c_uint64),
-                ("flushed", C.c_int32), ("status", C.c_int32), ("n_line_fills", C.c_uint64)]
+                ("flushed", C.c_int32), ("status", C.c_int32), ("n_line_fills", C.c_uint64), ("n_cpu_again", C.c_uint64)]
 
     def as_tuple(self):
         """(n_unique, hits, CPU-buffer hits, misses, bypasses)"""
@@ -59,6 +59,7 @@ def lib() -> C.CDLL:
         L.gids_cache_set_policy.argtypes = [vp, C.c_int, u64]
         L.gids_cache_set_rows_per_line.argtypes = [vp, u32]
         L.gids_cache_set_accum_mode.argtypes = [vp, C.c_int]
+        L.gids_cache_set_group_dedup.argtypes = [vp, C.c_int]
         L.gids_cpu_buffer_pin.argtypes = [vp, vp, u64]
         L.gids_window_push.argtypes = [vp, vp, u64, vp]
         L.gids_gather.argtypes = [vp, vp, u64, vp, u64, vp, vp, vp]
@@ -142,6 +143,10 @@ GIDS_ACCUM_MAX_MERGE, GIDS_ACCUM_LAG, GIDS_ACCUM_MAX_RAISE = 32, 16, 8
 
 def gids_cache_set_accum_mode(cache: int, mode: int) -> None:
     _check(lib().gids_cache_set_accum_mode(cache, mode))
+
+
+def gids_cache_set_group_dedup(cache: int, on: bool) -> None:
+    _check(lib().gids_cache_set_group_dedup(cache, 1 if on else 0))
 
 
 def gids_cache_set_rows_per_line(cache: int, rows: int) -> None:

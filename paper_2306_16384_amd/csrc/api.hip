@@ -224,6 +224,8 @@ struct gids_cache {
     }
     uint64_t many_list_max = 1u << 20;  // merged kernels for lists up to this many raw IDs (GIDS_MANY_LIST_MAX)
     uint32_t many_meta_min = 2;         // merged calls of at least this many steps classify on the internal stream (GIDS_MANY_PIPELINE_MIN; 0: never)
+    bool group_dedup = false;           // gids_cache_set_group_dedup
+    char** cpu_first = nullptr;         // n_hot words, clear between merged calls (see CacheView::cpu_first)
     bool many_pool_forced = false;
     uint64_t many_pool = 152 * 1024;    // LDS for a classifying workgroup's own list entries (GIDS_MANY_POOL, bytes; 0: none)
     int fuse = 1;               // GIDS_FUSE=0: commit, queueing and counters as a kernel each; no merged kernels
@@ -297,7 +299,7 @@ struct CacheT final : gids_cache {
         dev_free(wrank); dev_free(hotbits); dev_free(hotrank); dev_free(cache_data); dev_free(ctl);
         dev_free(blocksum); dev_free(blockoff); dev_free(hdr);
         for (int k = 0; k < 2; k++) { dev_free(ubuf[k]); dev_free(plan[k]); }
-        dev_free(fillgrp); dev_free(hitgrp); dev_free(many_plan);
+        dev_free(fillgrp); dev_free(hitgrp); dev_free(many_plan); dev_free(cpu_first);
         for (int k = 0; k < 2; k++) { dev_free(fills[k]); dev_free(rcopies[k]); dev_free(wcopies[k]); dev_free(ustage[k]); }
         for (auto& e : ev_flush) if (e) (void)hipEventDestroy(e);
         for (auto& s : slots) if (s.ids) (void)hipFree(s.ids);
@@ -321,6 +323,7 @@ struct CacheT final : gids_cache {
         v.hotbits = n_hot ? hotbits : nullptr; v.hotrank = hotrank;
         v.cache_data = cache_data; v.store = static_cast<const char*>(store->dev);
         v.cpubuf = static_cast<const char*>(cpubuf_dev); v.ctl = ctl;
+        v.cpu_first = group_dedup ? cpu_first : nullptr;
         return v;
     }
 
@@ -859,7 +862,7 @@ struct CacheT final : gids_cache {
                           rows_per_line == 1 && (fuse & 1) && longest_raw <= many_list_max &&
                           (many_pool_forced ||
                            many_fits(store->n_rows, n_sets, ways, words_per_set, sizeof(IdT), n_lists_upper,
-                                     std::max<uint64_t>(longest_est, 1), many_pool));
+                                     std::max<uint64_t>(longest_est, 1), many_pool, group_dedup));
         int rc;
         if (!fast) {
             // large tables, high associativity: the same steps through the per-step kernels, still one group
@@ -875,6 +878,10 @@ struct CacheT final : gids_cache {
             return GIDS_OK;
         }
         many_fast_calls++;
+        if (group_dedup && n_hot && !cpu_first) {
+            if ((rc = dev_alloc(&cpu_first, n_hot))) return rc;
+            HIP_TRY(hipMemset(cpu_first, 0, n_hot * sizeof(char*)));
+        }
         // room: window slots of the pushed lists, the plans of all steps, the group's lists
         if (open_batches && (rc = flush(s))) return rc;
         {
@@ -933,6 +940,7 @@ struct CacheT final : gids_cache {
         ManySteps<IdT> ms;
         ms.k = k;
         ms.seq0 = seq;
+        ms.group_dedup = group_dedup ? 1u : 0u;
         uint32_t n_push = 0;
         uint64_t off = 0;
         ms.n_lists = 0;
@@ -1311,6 +1319,14 @@ int gids_cache_set_accum_mode(gids_cache* cache, int mode) {
     return GIDS_OK;
 }
 
+int gids_cache_set_group_dedup(gids_cache* cache, int on) {
+    CHECK_CACHE(cache);
+    if (!cache->threshold) return fail(GIDS_E_INVAL, "gids_cache_set_group_dedup: the cache was created without an accumulator (accum_threshold == 0)");
+    if (cache->open_batches) return fail(GIDS_E_INVAL, "gids_cache_set_group_dedup: a group of minibatches is open (call gids_flush first)");
+    cache->group_dedup = on != 0;
+    return GIDS_OK;
+}
+
 int gids_cache_set_rows_per_line(gids_cache* cache, uint32_t rows) {
     CHECK_CACHE(cache);
     if (rows < 1) return fail(GIDS_E_INVAL, "gids_cache_set_rows_per_line: rows must be >= 1");
@@ -1347,6 +1363,7 @@ int gids_stats_read(gids_cache* cache, uint64_t seq, gids_stats* stats) {
     stats->seq = rec.seq; stats->n_unique = rec.n_unique; stats->n_hit = rec.n_hit; stats->n_cpu_hit = rec.n_cpu_hit;
     stats->n_miss = rec.n_miss; stats->n_bypass = rec.n_bypass; stats->n_pending = rec.n_pending;
     stats->flushed = rec.flushed; stats->status = rec.status; stats->n_line_fills = rec.n_line_fills;
+    stats->n_cpu_again = rec.n_cpu_again;
     if (rec.status) {
         cache->sticky = rec.status;
         return fail(rec.status, "gather %llu failed on the device with code %d", (unsigned long long)seq, rec.status);

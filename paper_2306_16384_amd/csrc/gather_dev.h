@@ -56,11 +56,15 @@ struct PlacesGlobal {
 // output row, whether it is late) until the line is installed again in the same group (then it goes out for its
 // output row only) or until the holder of the words queues what is left when the group ends; no queued operation
 // is ever read or changed again.
+// `first_out` (per lane, or nullptr): for a CPU-buffer row, the word that remembers which output row the group's
+// first fill of that row writes (nullptr: none yet).  A later minibatch of the group that needs the same row
+// copies it from there, after the fills, instead of reading it over the link again.
+// Returns whether this lane's entry was such a copy.
 template <typename IdT, typename LineWords, typename Places>
-__device__ __forceinline__ void queue_entry(const CacheView<IdT>& c, const AccumView& a, const LineWords& lw,
+__device__ __forceinline__ bool queue_entry(const CacheView<IdT>& c, const AccumView& a, const LineWords& lw,
                                             const Places& places, uint32_t group, bool valid, uint64_t j, uint64_t e,
                                             uint64_t v, uint32_t local, char* __restrict__ out,
-                                            IdT* __restrict__ unique_out) {
+                                            IdT* __restrict__ unique_out, char** first_out = nullptr) {
     Ctl* ctl = c.ctl;
     const uint32_t par = group & 1u;
     FillOp* __restrict__ fills = a.fills[par];
@@ -82,9 +86,13 @@ __device__ __forceinline__ void queue_entry(const CacheView<IdT>& c, const Accum
     const bool is_late = valid && kind == PLAN_INSTALL && hg == group;   // a queued rcopy still reads the old bytes
     // a fill now: every row that crosses the link; deferred, an installed line's own fill waits and only the one
     // it supersedes goes out
-    const bool is_fill = valid && kind != PLAN_HIT && !(LineWords::deferred && kind == PLAN_INSTALL && !open_fill);
+    char* again_from = nullptr;                                   // the output row that already receives this CPU-buffer row
+    if (valid && kind == PLAN_CPU && first_out) again_from = *first_out;
+    const bool is_again = again_from != nullptr;
+    const bool is_fill = valid && kind != PLAN_HIT && !is_again &&
+                         !(LineWords::deferred && kind == PLAN_INSTALL && !open_fill);
     const uint64_t fb = __ballot(is_fill), rb = __ballot(is_ready),
-                   wb = __ballot(is_wait || (is_late && !LineWords::deferred));
+                   wb = __ballot(is_wait || is_again || (is_late && !LineWords::deferred));
     uint32_t fbase = 0, rbase = 0, wbase = 0;
     if (lane == 0) {
         if (fb) fbase = places.take(0, (uint32_t)__popcll(fb));
@@ -99,7 +107,7 @@ __device__ __forceinline__ void queue_entry(const CacheView<IdT>& c, const Accum
     if ((uint64_t)fbase + __popcll(fb) > a.cap || (uint64_t)rbase + __popcll(rb) > a.cap ||
         (uint64_t)wbase + __popcll(wb) > a.cap) {
         if (lane == 0) atomicCAS(&ctl->error, 0u, 7u /* -GIDS_E_SPACE */);
-        return;
+        return false;
     }
     const uint64_t below = (1ull << lane) - 1;
     char* dst = out + j * c.row_bytes;
@@ -142,12 +150,19 @@ __device__ __forceinline__ void queue_entry(const CacheView<IdT>& c, const Accum
         wcopies[w].src = lw.pending_out(idx, local, pd);
         wcopies[w].dst = dst;
     }
+    if (is_again) {
+        wcopies[w].src = again_from;
+        wcopies[w].dst = dst;
+    } else if (valid && kind == PLAN_CPU && first_out) {
+        *first_out = dst;
+    }
     if (is_ready) {
         const uint32_t r = rbase + (uint32_t)__popcll(rb & below);
         rcopies[r].src = c.cache_data + idx * c.line_bytes;
         rcopies[r].dst = dst;
         lw.note_hit(idx, local, group);
     }
+    return is_again;
 }
 
 template <typename IdT>
@@ -176,6 +191,7 @@ __device__ __forceinline__ void publish_stats(Ctl* ctl, StatsRec* rec, uint64_t 
     rec->n_miss = ctl->cnt_miss;
     rec->n_bypass = ctl->cnt_bypass;
     rec->n_line_fills = ctl->cnt_fill;
+    rec->n_cpu_again = 0;
     uint32_t queued = 0;
     int flushed = 1;
     if (accum) {                          // rows of the open group that have not moved when this gather ends

@@ -41,7 +41,7 @@ struct Ctl {
     uint32_t q_wcopy[2];    // copies that must follow the link rows: hits on lines filled in the same group, ...
     uint32_t q_chunk[2];    // work counter of the group mover's link half
     uint32_t grp_nu[2][MANY_MAX];   // distinct count of each minibatch of a group, in the group's order
-    uint32_t many_cnt[MANY_MAX][5];     // per step of a merged call: hits, CPU-buffer hits, misses, bypasses, line fills
+    uint32_t many_cnt[MANY_MAX][6];     // per step of a merged call: hits, CPU-buffer hits, misses, bypasses, line fills, CPU-buffer rows by copy
     uint32_t win_n[MAX_WINDOW_SLOTS];   // distinct count of each buffered list
 };
 
@@ -74,6 +74,7 @@ struct StatsRec {
     uint64_t seq, n_unique, n_hit, n_cpu_hit, n_miss, n_bypass, n_pending;
     int32_t flushed, status;
     uint64_t n_line_fills;
+    uint64_t n_cpu_again;
 };
 
 // Everything the gather kernels need about one cache.
@@ -100,6 +101,7 @@ struct CacheView {
     char* cache_data;       // lines * line_bytes
     const char* store;      // device-visible address of the host store
     const char* cpubuf;     // device-visible address of the CPU buffer rows (ascending ID order)
+    char** cpu_first;       // per CPU-buffer row: the output row the open group's first fill of it writes (or nullptr: not kept)
     Ctl* ctl;
 };
 
@@ -242,18 +244,19 @@ struct ManySteps {
     uint32_t resident;                  // the workgroups keep their sets' state in LDS for the length of the kernel
     uint32_t sets_per_wg;               // places for sets in that LDS: ceil(n_sets / workgroups)
     uint32_t rounds;                    // nodes per set: ceil(n_rows / n_sets)
+    uint32_t group_dedup;               // a CPU-buffer row that several steps need crosses the link once per call
 };
 constexpr uint8_t MANY_NO_LIST = 0xFF;
 uint64_t many_max_rows();
 bool many_fits(uint64_t n_rows, uint64_t n_sets, uint32_t ways, uint32_t words_per_set, size_t id_bytes, uint32_t n_lists,
-               uint64_t longest, uint64_t pool_bytes);
+               uint64_t longest, uint64_t pool_bytes, bool group_dedup);
 uint32_t many_max_ways();
 template <typename IdT>
 void launch_dedup_small(const ManyPushes<IdT>& p, uint32_t n_lists, uint64_t n_rows, Ctl* ctl, hipStream_t s);
 template <typename IdT>
 void launch_classify_many(const CacheView<IdT>& c, const AccumView& a, uint32_t group, ManySteps<IdT>& m,
                           uint64_t longest, uint64_t pool_bytes, uint64_t* plan_all, StatsRec* ring, uint32_t ring_size,
-                          hipStream_t s);   // fills m.share_cap; pool_bytes = 0: every workgroup reads the lists from memory
+                          hipStream_t s);   // fills m.share_cap (m.group_dedup: by the caller); pool_bytes = 0: every workgroup reads the lists from memory
 
 // The distinct-ID lists of a group's minibatches wait in a staging buffer of the group (they are produced on
 // the stream that classifies) and reach the callers' buffers with the rows, on the stream the callers gave.

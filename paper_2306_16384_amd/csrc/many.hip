@@ -143,6 +143,10 @@ struct StateInMemory {
         return reinterpret_cast<unsigned long long*>(c.missmask) + (uint64_t)slot * c.words_per_set;
     }
     __device__ __forceinline__ uint32_t local_line(uint32_t, int) const { return 0; }
+    // the word that remembers the output row of the call's first fill of a CPU-buffer row (nullptr: not kept)
+    __device__ __forceinline__ char** first_out(uint32_t cpu_row, uint32_t) const {
+        return c.cpu_first ? c.cpu_first + cpu_row : nullptr;
+    }
 };
 
 // The per-line words of the accumulator for the lines of this workgroup's sets, in LDS.  Deferred: an installed
@@ -180,6 +184,8 @@ struct StateInLds {
     uint32_t rounds, words_per_set;
     FastDiv div_sets;
     LineWordsLds lw;
+    char** s_first;                                           // per node of these sets, or nullptr: not kept
+    __device__ __forceinline__ char** first_out(uint32_t, uint32_t node) const { return s_first ? s_first + node : nullptr; }
     __device__ __forceinline__ uint32_t slot_of(uint32_t, uint32_t local_set) const { return local_set; }
     __device__ __forceinline__ uint32_t node_of(uint32_t slot, uint32_t round, uint32_t) const { return slot * rounds + round; }
     __device__ __forceinline__ uint32_t node_of_tag(uint32_t slot, uint32_t tag) const {
@@ -421,7 +427,7 @@ template <typename IdT, int WAYS, typename State>
 __device__ __forceinline__ void steps_from_pool(const CacheView<IdT>& c, const AccumView& a, const State& st,
                                                 uint32_t group, const ManySteps<IdT>& m, uint32_t n_ok, uint32_t stamp0,
                                                 const uint32_t* pool_v, const uint32_t* pool_j, const uint32_t* pool_cpu,
-                                                const uint32_t* own_n, uint32_t (*cnt)[5], const PlacesLocal& places) {
+                                                const uint32_t* own_n, uint32_t (*cnt)[6], const PlacesLocal& places) {
     const uint32_t tid = threadIdx.x;
     const uint32_t cap = m.share_cap;
     const uint32_t n_sets = (uint32_t)c.n_sets;
@@ -441,6 +447,7 @@ __device__ __forceinline__ void steps_from_pool(const CacheView<IdT>& c, const A
         const bool wave_has = (tid & ~63u) < n_h;
         uint64_t e = 0;
         uint32_t v = 0, j = 0, set = 0, round = 0, slot = 0, local = 0;
+        char** first = nullptr;
         bool miss = false;
         IdT tg[WAYS];
 #pragma unroll
@@ -453,10 +460,12 @@ __device__ __forceinline__ void steps_from_pool(const CacheView<IdT>& c, const A
             round = fast_div(m.div_sets, v);
             set = v - round * n_sets;
             slot = st.slot_of(set, set >> m.wg_shift);
-            uint8_t* ctr = st.counter(st.node_of(slot, round, v));
+            const uint32_t node = st.node_of(slot, round, v);
+            uint8_t* ctr = st.counter(node);
             const uint8_t r = *ctr;
             if (cpu_row != CM_NONE) {
                 e = (PLAN_CPU << PLAN_SHIFT) | cpu_row;
+                if (m.group_dedup) first = st.first_out(cpu_row, node);
             } else {
                 const IdT* row = st.tags(slot);
                 int way = -1;
@@ -518,8 +527,11 @@ __device__ __forceinline__ void steps_from_pool(const CacheView<IdT>& c, const A
             }
             st.miss_words(slot)[round >> 6] = 0ull;
         }
-        if (wave_has)
-            queue_entry(c, a, st.lw, places, group, have, (uint64_t)j, e, (uint64_t)v, local, m.out[i], m.unique_out[i]);
+        if (wave_has) {
+            const bool again = queue_entry(c, a, st.lw, places, group, have, (uint64_t)j, e, (uint64_t)v, local, m.out[i],
+                                           m.unique_out[i], first);
+            if (m.group_dedup) wave_count(&cnt[i][5], again);
+        }
         phase_barrier<State::in_lds>();
     }
 }
@@ -536,7 +548,7 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
     __shared__ uint32_t list_off[2 * MANY_MAX + 1];           // entries of the lists before it
     __shared__ const IdT* list_ptr[2 * MANY_MAX];
     __shared__ uint32_t own_n[2 * MANY_MAX];                  // of which this workgroup's
-    __shared__ uint32_t cnt[MANY_MAX][5];                     // per step: hits, CPU-buffer hits, misses, bypasses, line fills
+    __shared__ uint32_t cnt[MANY_MAX][6];                     // per step: hits, CPU-buffer hits, misses, bypasses, line fills, CPU rows by copy
     __shared__ uint32_t cnt_mem[5];
     __shared__ uint32_t overflow;
     __shared__ uint32_t is_last;
@@ -552,8 +564,10 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
     const uint32_t spw = m.resident ? m.sets_per_wg : 0;      // places for sets, their lines, miss-mask words, nodes
     const uint32_t n_l = spw * WAYS, n_mw = spw * c.words_per_set, n_nodes = spw * m.rounds;
     const size_t n_pool = (size_t)m.n_lists * cap;
+    const uint32_t n_first = m.group_dedup ? n_nodes : 0;     // (only with the state in LDS: spw is 0 otherwise)
     char** s_pout = reinterpret_cast<char**>(lds_raw);
-    unsigned long long* s_mm = lds_raw + n_l;
+    char** s_first = s_pout + n_l;
+    unsigned long long* s_mm = lds_raw + n_l + n_first;
     IdT* s_tag = reinterpret_cast<IdT*>(s_mm + n_mw);
     uint32_t* pool_v = reinterpret_cast<uint32_t*>(s_tag + n_l);
     uint32_t* pool_j = pool_v + n_pool;
@@ -569,7 +583,7 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
         list_ptr[l] = m.list[l];
         own_n[l] = 0;
     }
-    for (uint32_t x = tid; x < MANY_MAX * 5; x += blockDim.x) cnt[x / 5][x % 5] = 0;
+    for (uint32_t x = tid; x < MANY_MAX * 6; x += blockDim.x) cnt[x / 6][x % 6] = 0;
     if (tid == 0) overflow = cap == 0;
     __syncthreads();
     // an error left by an earlier kernel (a pushed ID out of range): nothing runs, every record reports it.
@@ -682,6 +696,7 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
                 s_pout[x] = nullptr;                          // (read only for fills queued by this call's group)
             }
             for (uint32_t x = tid; x < n_mw; x += blockDim.x) s_mm[x] = 0ull;
+            for (uint32_t x = tid; x < n_first; x += blockDim.x) s_first[x] = nullptr;
             for (uint32_t x = tid; x < n_nodes; x += blockDim.x) {
                 const uint32_t ls = x / m.rounds;
                 const uint64_t v = (uint64_t)(me + ls * n_wg) + (uint64_t)(x - ls * m.rounds) * n_sets;
@@ -689,7 +704,7 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
             }
             __syncthreads();
             const StateInLds<IdT, WAYS> st{s_tag, s_stamp, s_reuse, s_mm, m.rounds, c.words_per_set, m.div_sets,
-                                           LineWordsLds{s_pend, s_fgrp, s_hgrp, s_pout}};
+                                           LineWordsLds{s_pend, s_fgrp, s_hgrp, s_pout}, n_first ? s_first : nullptr};
             steps_from_pool<IdT, WAYS>(c, a, st, group, m, n_ok, stamp0, pool_v, pool_j, pool_cpu, own_n, cnt, places);
             // ---- the fills that still wait in the lines' words are queued (steps_from_pool ends behind a barrier)
             for (uint32_t x = tid; x < n_l; x += blockDim.x) {
@@ -736,9 +751,20 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
             __syncthreads();
             const StateInMemory<IdT, WAYS> st{c, LineWordsGlobal{c.pending, c.fillgrp, c.hitgrp, a.fills[group & 1u]}};
             steps_from_pool<IdT, WAYS>(c, a, st, group, m, n_ok, stamp0, pool_v, pool_j, pool_cpu, own_n, cnt, places);
+            if (m.group_dedup && c.cpu_first) {
+                // the words that remember the call's first fill of a CPU-buffer row are clear between calls
+                // (list_off still holds this workgroup's entries of the gathered lists)
+                const uint32_t total = list_off[m.n_lists];
+                uint32_t l = 0;
+                for (uint32_t f = tid; f < total; f += blockDim.x) {
+                    while (f >= list_off[l + 1]) l++;
+                    const uint32_t row = pool_cpu[l * cap + (f - list_off[l])];
+                    if (row != CM_NONE) c.cpu_first[row] = nullptr;
+                }
+            }
         }
-        for (uint32_t x = tid; x < m.k * 5; x += blockDim.x)
-            if (cnt[x / 5][x % 5]) atomicAdd(&ctl->many_cnt[x / 5][x % 5], cnt[x / 5][x % 5]);
+        for (uint32_t x = tid; x < m.k * 6; x += blockDim.x)
+            if (cnt[x / 6][x % 6]) atomicAdd(&ctl->many_cnt[x / 6][x % 6], cnt[x / 6][x % 6]);
         // what is left of the three stretches: operations that do nothing (the host sizes each list for every
         // entry of the group, so the stretches always fit; were one to end beyond its list, queue_entry has
         // reported it and nothing is written there)
@@ -783,12 +809,13 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
         rec->n_miss = ld_agent(&ctl->many_cnt[i][2]);
         rec->n_bypass = ld_agent(&ctl->many_cnt[i][3]);
         rec->n_line_fills = ld_agent(&ctl->many_cnt[i][4]);
+        rec->n_cpu_again = ld_agent(&ctl->many_cnt[i][5]);
         const bool closes = i + 1 == m.k;                     // the call's steps are one group, closed by its last
         rec->n_pending = closes ? 0u : queued;
         rec->flushed = closes ? 1 : 0;
         rec->status = ran ? 0 : -(int32_t)err;
         ctl->grp_nu[group & 1u][i] = n;
-        for (int x = 0; x < 5; x++) ctl->many_cnt[i][x] = 0;
+        for (int x = 0; x < 6; x++) ctl->many_cnt[i][x] = 0;
     }
     if (tid == 0) {
         ctl->q_rows = 0;
@@ -861,7 +888,7 @@ struct ManyShape {
 };
 
 ManyShape many_shape(uint64_t n_rows, uint64_t n_sets, uint32_t ways, uint32_t words_per_set, size_t id_bytes,
-                     uint32_t n_lists, uint64_t longest, uint64_t pool_bytes) {
+                     uint32_t n_lists, uint64_t longest, uint64_t pool_bytes, bool group_dedup) {
     // 16 to 32 of a list's entries per workgroup's own share (GIDS_MANY_SHARE); every workgroup reads every list
     static const uint64_t per_wg = [] {
         const char* e = getenv("GIDS_MANY_SHARE");
@@ -893,7 +920,7 @@ ManyShape many_shape(uint64_t n_rows, uint64_t n_sets, uint32_t ways, uint32_t w
     sh.rounds = (uint32_t)((n_rows + n_sets - 1) / n_sets);
     const uint64_t n_l = (uint64_t)sh.sets_per_wg * ways;
     sh.state = n_l * (8 + id_bytes + 16) + (uint64_t)sh.sets_per_wg * words_per_set * 8 +
-               (uint64_t)sh.sets_per_wg * sh.rounds;
+               (uint64_t)sh.sets_per_wg * sh.rounds * (group_dedup ? 9 : 1);   // (+ an output address per node)
     sh.resident = resident_ok && pool_bytes && sh.state <= MANY_LDS_MAX_BYTES / 2;
     // LDS for a workgroup's own entries: the same number of places for each list, four times the expected share
     // where that fits; a workgroup whose share of some list is larger reads the lists from memory instead
@@ -913,8 +940,8 @@ ManyShape many_shape(uint64_t n_rows, uint64_t n_sets, uint32_t ways, uint32_t w
 // four standard deviations more (a share is a count of independent hits on one of g residues).  Beyond that most
 // workgroups would read the lists from memory in every phase, and the per-step kernels are the better choice.
 bool many_fits(uint64_t n_rows, uint64_t n_sets, uint32_t ways, uint32_t words_per_set, size_t id_bytes, uint32_t n_lists,
-               uint64_t longest, uint64_t pool_bytes) {
-    const ManyShape sh = many_shape(n_rows, n_sets, ways, words_per_set, id_bytes, n_lists, longest, pool_bytes);
+               uint64_t longest, uint64_t pool_bytes, bool group_dedup) {
+    const ManyShape sh = many_shape(n_rows, n_sets, ways, words_per_set, id_bytes, n_lists, longest, pool_bytes, group_dedup);
     uint64_t dev = 0;
     while ((dev + 1) * (dev + 1) <= sh.share) dev++;          // floor(sqrt(share))
     return pool_bytes == 0 || sh.cap >= sh.share + 4 * (dev + 1) + 8;
@@ -924,7 +951,8 @@ template <typename IdT>
 void launch_classify_many(const CacheView<IdT>& c, const AccumView& a, uint32_t group, ManySteps<IdT>& m,
                           uint64_t longest, uint64_t pool_bytes, uint64_t* plan_all, StatsRec* ring, uint32_t ring_size,
                           hipStream_t s) {
-    const ManyShape sh = many_shape(c.n_rows, c.n_sets, c.ways, c.words_per_set, sizeof(IdT), m.n_lists, longest, pool_bytes);
+    const ManyShape sh = many_shape(c.n_rows, c.n_sets, c.ways, c.words_per_set, sizeof(IdT), m.n_lists, longest, pool_bytes,
+                                    m.group_dedup != 0);
     const uint64_t g = sh.g;
     const uint32_t threads = sh.threads;
     m.wg_shift = sh.wg_shift;

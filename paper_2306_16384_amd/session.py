@@ -56,6 +56,9 @@ class GatherSession:
     def set_accum_mode(self, mode: int) -> None:
         B.gids_cache_set_accum_mode(self.cache, mode)
 
+    def set_group_dedup(self, on: bool) -> None:
+        B.gids_cache_set_group_dedup(self.cache, on)
+
     def set_rows_per_line(self, rows: int) -> None:
         B.gids_cache_set_rows_per_line(self.cache, rows)
 

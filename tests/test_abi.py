@@ -57,10 +57,10 @@ def test_header_is_plain_c_and_links(tmp_path):
                            "-Wl,-rpath," + lib_dir, "-Wl,-rpath,/opt/rocm/lib"])
     out = subprocess.run([str(exe)], capture_output=True, text=True)
     assert out.returncode == 0, out.stdout + out.stderr
-    assert out.stdout.startswith("abi ok 72")              # gids_stats is 7 x u64 + 2 x i32 + u64
+    assert out.stdout.startswith("abi ok 80")              # gids_stats is 7 x u64 + 2 x i32 + 2 x u64
 
 
 def test_binding_struct_matches_the_header():
     import ctypes
     from paper_2306_16384_amd import binding
-    assert ctypes.sizeof(binding.gids_stats) == 72            # the C program above prints the header's sizeof
+    assert ctypes.sizeof(binding.gids_stats) == 80            # the C program above prints the header's sizeof

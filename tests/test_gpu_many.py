@@ -42,7 +42,7 @@ def with_env(knobs, make):
 
 
 def run_many(gpu, oracle, feats, batches, *, id_dtype, lines, ways, window, ks, hot=None, policy=None, pipeline="0",
-             fuse=None, pool=None, resident=None, meta_min=None, list_max=None, expect_merged=None, label=""):
+             fuse=None, pool=None, resident=None, meta_min=None, list_max=None, dedup=False, expect_merged=None, label=""):
     """ks: the sizes of the merged calls, in order (0 = one plain push + gather step in between);
     cycles until every list is gathered."""
     torch, gids, GatherSession = gpu
@@ -79,12 +79,14 @@ def run_many(gpu, oracle, feats, batches, *, id_dtype, lines, ways, window, ks, 
             ses.pin_hot(hot)
         if policy is not None:
             ses.set_policy(*policy)
+        if dedup:
+            ses.set_group_dedup(True)
         dev = [ses.to_device(b) for b in batches]
         torch.cuda.synchronize()
         push_stream = torch.cuda.Stream() if pipeline in ("1", None) else None
         outs = [torch.full((max(len(b), 1), R), 0xA5, dtype=torch.uint8, device="cuda") for b in batches]
         uqs = [torch.full((max(len(b), 1),), -7, dtype=ses.torch_id, device="cuda") for b in batches]
-        seq_of, expect_acc = {}, {}
+        seq_of, expect_acc, again_of = {}, {}, {}
         pushed = 0
         if window == 0:
             pass                                              # depth 0: every step pushes its own list just before
@@ -114,7 +116,12 @@ def run_many(gpu, oracle, feats, batches, *, id_dtype, lines, ways, window, ks, 
                     pushes.append(None)
             seq0 = ses.gather_many(pushes, outs[t:t + k], uqs[t:t + k], push_stream=push_stream)
             rows = 0
+            seen_hot = set()                                  # CPU-buffer rows the call's earlier steps already fetch
             for i in range(k):
+                if dedup and hot is not None:
+                    mine = set(np.intersect1d(want[t + i][0], hot).tolist())
+                    again_of[t + i] = len(mine & seen_hot)
+                    seen_hot |= mine
                 seq_of[t + i] = seq0 + i
                 rows += len(want[t + i][0])
                 expect_acc[t + i] = (0, 1) if i == k - 1 else (rows, 0)
@@ -128,6 +135,11 @@ def run_many(gpu, oracle, feats, batches, *, id_dtype, lines, ways, window, ks, 
             assert st.as_tuple() == tuple(int(x) for x in stats), (label, t, st.as_tuple(), stats.tolist())
             if expect_acc[t] is not None:
                 assert (st.n_pending, st.flushed) == expect_acc[t], (label, t, st.n_pending, st.flushed, expect_acc[t])
+            # (a workgroup that had to read the lists from memory fetches every row: only where none did)
+            if pool is None and expect_merged is True:
+                assert st.n_cpu_again == again_of.get(t, 0), (label, t, st.n_cpu_again, again_of.get(t, 0))
+            else:
+                assert st.n_cpu_again <= again_of.get(t, 0), (label, t, st.n_cpu_again, again_of.get(t, 0))
             m = len(u)
             assert np.array_equal(uqs[t][:m].cpu().numpy(), u.astype(ses.id_dtype)), (label, t)
             assert np.array_equal(outs[t][:m].cpu().numpy(), rows), f"{label} minibatch {t}: gathered rows differ"
@@ -341,7 +353,8 @@ def test_random_merged_calls(gpu, oracle_mod, case):
     merged, per_step = run_many(gpu, oracle_mod, feats, batches, id_dtype=id_dtype, lines=ways * n_sets, ways=ways,
                                 window=window, ks=ks, hot=rng.choice(n, n_hot, replace=False) if n_hot else None,
                                 policy=(1, case) if rng.random() < 0.3 else None, pipeline=pipeline, pool=pool,
-                                resident=resident, meta_min=[None, "16", "0"][case % 3], label=f"random{case}")
+                                resident=resident, meta_min=[None, "16", "0"][case % 3], dedup=case % 2 == 1,
+                                label=f"random{case}")
     RANDOM_TALLY[0] += merged
     RANDOM_TALLY[1] += per_step
 
@@ -351,6 +364,40 @@ def test_random_merged_calls_took_both_kinds_of_kernels():
     if sum(RANDOM_TALLY) == 0:
         pytest.skip("the random cases did not run in this process")
     assert RANDOM_TALLY[0] > RANDOM_TALLY[1] > 0, RANDOM_TALLY
+
+
+@pytest.mark.parametrize("resident", [None, "0"])
+def test_cpu_buffer_rows_cross_the_link_once_per_call(gpu, oracle_mod, resident):
+    """gids_cache_set_group_dedup: a large CPU buffer and heavily overlapping lists, so that most CPU-buffer rows of
+    a call are needed by several of its steps; outputs, counters and cache state must not change.  With the sets'
+    state in LDS and in device memory; switching it on and off between calls."""
+    torch, gids, GatherSession = gpu
+    rng = np.random.default_rng(5150)
+    n = 20_000
+    feats = rng.integers(0, 256, size=(n, 256), dtype=np.uint8)
+    hot = rng.choice(n, 6000, replace=False)
+    batches = [np.concatenate([rng.choice(hot, 1500), rng.integers(0, n, size=800)]).astype(np.int64) for _ in range(50)]
+    for pipeline in ("0", "1"):
+        run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=4 * 256, ways=4, window=5, ks=[32, 0, 7, 2],
+                 hot=hot, pipeline=pipeline, resident=resident, dedup=True, expect_merged=True, label="dedup")
+    with GatherSession(n, 256, np.int64, 1024, 4, 256, 0, 1) as ses:            # on, off and on again
+        ses.store_view()[:] = feats
+        ses.pin_hot(hot)
+        dev = [ses.to_device(b) for b in batches[:6]]
+        outs = [torch.zeros((len(b), 256), dtype=torch.uint8, device="cuda") for b in batches[:6]]
+        uqs = [torch.zeros(len(b), dtype=torch.int64, device="cuda") for b in batches[:6]]
+        for on, lo in ((True, 0), (False, 2), (True, 4)):
+            ses.set_group_dedup(on)
+            ses.gather_many(dev[lo:lo + 2], outs[lo:lo + 2], uqs[lo:lo + 2])
+        torch.cuda.synchronize()
+        for t in range(6):
+            u = np.unique(batches[t])
+            assert np.array_equal(uqs[t][:len(u)].cpu().numpy(), u)
+            assert np.array_equal(outs[t][:len(u)].cpu().numpy(), feats[u])
+    with GatherSession(n, 256, np.int64, 1024, 4, 256, 0) as ses:               # no accumulator
+        with pytest.raises(gids.GidsError) as e:
+            ses.set_group_dedup(True)
+        assert e.value.code == gids.GIDS_E_INVAL
 
 
 def test_merged_calls_through_the_per_step_kernels(gpu, oracle_mod):
