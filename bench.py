@@ -179,7 +179,7 @@ def main() -> int:
         # minibatches that are small beside the cost of launching and ordering their kernels)
         # (and Large and Medium once more in merged calls in which a CPU-buffer row that several steps of a call need
         # crosses the link once: gids_cache_set_group_dedup, outside the per-minibatch cost model)
-        for name in ("large_merged_dedup", "skew", "skew_merged", "resident", "medium", "medium_merged",
+        for name in ("large_merged", "large_merged_dedup", "skew", "skew_merged", "resident", "medium", "medium_merged",
                      "medium_merged_dedup", "tiny", "tiny_merged"):
             if name == args.workload:
                 continue
@@ -189,8 +189,9 @@ def main() -> int:
                 sub.workload, sub.accum, sub.many, sub.steps, sub.warmup = "tiny", 1, 32, 1280, 32
             elif name == "medium_merged":
                 sub.workload, sub.accum, sub.many, sub.steps, sub.warmup = "medium", 1, 32, 320, 32
-            elif name == "large_merged_dedup":
-                sub.workload, sub.accum, sub.many, sub.group_dedup, sub.steps, sub.warmup = "large", 1, 8, True, 64, 32
+            elif name in ("large_merged", "large_merged_dedup"):
+                sub.workload, sub.accum, sub.many, sub.steps, sub.warmup = "large", 1, 16, 96, 32
+                sub.group_dedup = name.endswith("dedup")
                 sub.cpu_seconds = 14.0                          # (the oracle replays the warm-up before it can compare)
             elif name == "medium_merged_dedup":
                 sub.workload, sub.accum, sub.many, sub.group_dedup, sub.steps, sub.warmup = "medium", 1, 32, True, 320, 32

@@ -413,6 +413,16 @@ __device__ __forceinline__ void phase_barrier() {
     }
 }
 
+// CPU-buffer lookup (Section 3.3): the row of the buffer that holds node v, or CM_NONE
+template <typename IdT>
+__device__ __forceinline__ uint32_t cpu_row_of(const CacheView<IdT>& c, uint64_t v) {
+    if (!c.hotbits) return CM_NONE;
+    const uint64_t hw = c.hotbits[v >> 6];
+    const uint32_t before = c.hotrank[v >> 6];                // (both loads at once)
+    const uint64_t bit = 1ull << (v & 63);
+    return (hw & bit) ? before + (uint32_t)__popcll(hw & (bit - 1)) : CM_NONE;
+}
+
 // one wavefront's count of a flag, added to a counter in LDS
 __device__ __forceinline__ void wave_count(uint32_t* counter, bool flag) {
     const uint64_t b = __ballot(flag);
@@ -456,7 +466,8 @@ __device__ __forceinline__ void steps_from_pool(const CacheView<IdT>& c, const A
         if (have) {
             v = pool_v[(size_t)h * cap + tid];
             j = pool_j[(size_t)h * cap + tid];
-            const uint32_t cpu_row = pool_cpu[(size_t)h * cap + tid];
+            // (looked up once per call where the pool has room for it, here otherwise)
+            const uint32_t cpu_row = pool_cpu ? pool_cpu[(size_t)h * cap + tid] : cpu_row_of(c, v);
             round = fast_div(m.div_sets, v);
             set = v - round * n_sets;
             slot = st.slot_of(set, set >> m.wg_shift);
@@ -571,8 +582,10 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
     IdT* s_tag = reinterpret_cast<IdT*>(s_mm + n_mw);
     uint32_t* pool_v = reinterpret_cast<uint32_t*>(s_tag + n_l);
     uint32_t* pool_j = pool_v + n_pool;
-    uint32_t* pool_cpu = pool_j + n_pool;
-    int32_t* s_stamp = reinterpret_cast<int32_t*>(pool_cpu + n_pool);
+    // (the CPU-buffer row of an entry is kept only beside the sets' state: where that stays in memory the steps
+    // wait for memory anyway, and the room goes to longer lists or more steps per call)
+    uint32_t* pool_cpu = m.resident ? pool_j + n_pool : nullptr;
+    int32_t* s_stamp = reinterpret_cast<int32_t*>(pool_j + n_pool + (m.resident ? n_pool : 0));
     uint32_t* s_pend = reinterpret_cast<uint32_t*>(s_stamp + n_l);
     uint32_t* s_fgrp = s_pend + n_l;
     uint32_t* s_hgrp = s_fgrp + n_l;
@@ -664,21 +677,13 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
             list_off[m.n_lists] = off;
         }
         __syncthreads();
-        {
+        if (pool_cpu) {
             const uint32_t total = list_off[m.n_lists];
             uint32_t l = 0;
             for (uint32_t f = tid; f < total; f += blockDim.x) {
                 while (f >= list_off[l + 1]) l++;
                 const uint32_t x = l * cap + (f - list_off[l]);
-                uint32_t row = CM_NONE;
-                if (c.hotbits) {
-                    const uint64_t v = (uint64_t)pool_v[x];
-                    const uint64_t hw = c.hotbits[v >> 6];
-                    const uint32_t before = c.hotrank[v >> 6];    // (both loads at once)
-                    const uint64_t bit = 1ull << (v & 63);
-                    if (hw & bit) row = before + (uint32_t)__popcll(hw & (bit - 1));
-                }
-                pool_cpu[x] = row;
+                pool_cpu[x] = cpu_row_of(c, (uint64_t)pool_v[x]);
             }
         }
         if (m.resident) {
@@ -758,7 +763,7 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
                 uint32_t l = 0;
                 for (uint32_t f = tid; f < total; f += blockDim.x) {
                     while (f >= list_off[l + 1]) l++;
-                    const uint32_t row = pool_cpu[l * cap + (f - list_off[l])];
+                    const uint32_t row = cpu_row_of(c, (uint64_t)pool_v[l * cap + (f - list_off[l])]);
                     if (row != CM_NONE) c.cpu_first[row] = nullptr;
                 }
             }
@@ -926,7 +931,7 @@ ManyShape many_shape(uint64_t n_rows, uint64_t n_sets, uint32_t ways, uint32_t w
     // where that fits; a workgroup whose share of some list is larger reads the lists from memory instead
     const uint64_t room = MANY_LDS_MAX_BYTES - (sh.resident ? sh.state : 0) - 16;
     if (pool_bytes > room) pool_bytes = room;
-    const uint64_t entry = 12;                                // ID (as 32 bits), position in its list, CPU-buffer row
+    const uint64_t entry = sh.resident ? 12 : 8;              // ID (as 32 bits), position in its list; CPU-buffer row
     sh.share = (longest + sh.g - 1) / sh.g;
     uint64_t cap = n_lists ? pool_bytes / (entry * n_lists) : 0;
     if (cap > 4 * sh.share + 16) cap = 4 * sh.share + 16;
@@ -961,7 +966,7 @@ void launch_classify_many(const CacheView<IdT>& c, const AccumView& a, uint32_t 
     m.rounds = sh.rounds;
     m.resident = sh.resident;
     m.share_cap = (uint32_t)sh.cap;
-    const size_t lds = (size_t)(sh.cap * m.n_lists * 12 + (sh.resident ? sh.state : 0) + 16);
+    const size_t lds = (size_t)(sh.cap * m.n_lists * (sh.resident ? 12 : 8) + (sh.resident ? sh.state : 0) + 16);
 #define GIDS_CLASSIFY_MANY(W) \
     launch_classify_many_ways<IdT, W>(c, a, group, m, (uint32_t)g, threads, lds, plan_all, ring, ring_size, s)
     switch (c.ways) {
