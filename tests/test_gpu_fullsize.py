@@ -202,7 +202,7 @@ def sample_lists(g, cfg, n_b, rank_table=None):
 
 
 def run_big(oracle_mod, cfg, store, store_np, raws, keep, hot=None, after_each=None, window=None, label=None,
-            merged_k=0):
+            merged_k=0, dedup=False):
     """Counters of every minibatch against the oracle's simulator; on the kept minibatches the distinct-ID list
     and every gathered row; final tags and stamps.  Returns the per-minibatch counters.  merged_k: through
     gids_gather_many, that many steps per call."""
@@ -217,6 +217,8 @@ def run_big(oracle_mod, cfg, store, store_np, raws, keep, hot=None, after_each=N
                        window, 1 if merged_k else 0, store_handle=store) as ses:
         if hot is not None:
             ses.pin_hot(hot)
+        if dedup:
+            ses.set_group_dedup(True)                         # one transfer per CPU-buffer row and merged call
         if merged_k:
             outs, uniqs, stats_of = drive_merged(ses, torch, raws, window, cfg.row_bytes, merged_k, keep, cap)
         else:
@@ -323,25 +325,33 @@ def test_large_at_benchmark_size(oracle_mod, big_world):
             hot=big_world["hot"])
 
 
-def test_large_in_merged_calls(oracle_mod, big_world):
-    """120 minibatches of Large through gids_gather_many, 8 steps per call: the pushed lists go through the bitmap in
-    device memory, the classification keeps its lists in LDS and the sets' state in memory."""
+@pytest.mark.parametrize("k,dedup", [(8, False), (16, True)])
+def test_large_in_merged_calls(oracle_mod, big_world, k, dedup):
+    """120 minibatches of Large through gids_gather_many, 8 or 16 steps per call: the pushed lists go through the
+    bitmap in device memory, the classification keeps its lists in LDS and the sets' state in memory.  dedup: a
+    CPU-buffer row that several steps of a call need crosses the link once."""
     cfg = big_world["cfg"]
     n_b = 120
-    raws = sample_lists(big_world["g"], cfg, n_b)
+    if "large120" not in big_world["lists"]:
+        big_world["lists"]["large120"] = sample_lists(big_world["g"], cfg, n_b)
+    raws = big_world["lists"]["large120"]
     run_big(oracle_mod, cfg, big_world["store"], big_world["store_np"], raws, kept_minibatches(n_b, cfg.window),
-            hot=big_world["hot"], merged_k=8, label="large merged")
+            hot=big_world["hot"], merged_k=k, dedup=dedup, label=f"large merged/{k}{'/dedup' if dedup else ''}")
 
 
-def test_skew_in_merged_calls(oracle_mod, big_world):
-    """160 minibatches of the skew configuration (Zipf 0.8 seeds, depth 4) through gids_gather_many, 32 steps per call."""
+@pytest.mark.parametrize("dedup", [False, True])
+def test_skew_in_merged_calls(oracle_mod, big_world, dedup):
+    """160 minibatches of the skew configuration (Zipf 0.8 seeds, depth 4) through gids_gather_many, 32 steps per
+    call; dedup: a CPU-buffer row that several steps of a call need crosses the link once."""
     base = big_world["cfg"]
     cfg = wl.scaled(CONFIGS["skew"], base.n_nodes)
     n_b = 160
-    rank_table = wl.synth.zipf_rank_table(cfg.n_nodes, 0.8)
-    raws = sample_lists(big_world["g"], cfg, n_b, rank_table)
+    if "skew160" not in big_world["lists"]:
+        rank_table = wl.synth.zipf_rank_table(cfg.n_nodes, 0.8)
+        big_world["lists"] = {"skew160": sample_lists(big_world["g"], cfg, n_b, rank_table)}
+    raws = big_world["lists"]["skew160"]
     run_big(oracle_mod, cfg, big_world["store"], big_world["store_np"], raws, kept_minibatches(n_b, cfg.window),
-            hot=big_world["hot"], merged_k=32, label="skew merged")
+            hot=big_world["hot"], merged_k=32, dedup=dedup, label=f"skew merged{'/dedup' if dedup else ''}")
 
 
 SKEW_S = (0.0, 0.8, 1.2)
