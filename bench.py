@@ -167,6 +167,8 @@ def main() -> int:
     shared = dict(torch=torch, wl=wl, gids=gids, GatherSession=GatherSession)
     result = run_workload(args, shared)
     if result is None:                                          # a sweep printed its own object
+        if "world" in shared:
+            gids.gids_store_destroy(shared.pop("world")["store"])
         return 0
     # auto: only for the bare command (no option besides --gpus / --steps / --warmup), i.e. the default benchmark line
     given = {a.split("=")[0] for a in sys.argv[1:] if a.startswith("--")}
@@ -213,6 +215,8 @@ def main() -> int:
                 "oracle_count_mismatches": r.get("cpu_baseline", {}).get("count_mismatches_vs_gpu"),
                 "oracle_minibatches_compared": r.get("cpu_baseline", {}).get("minibatches_compared"),
                 "check": r.get("check")}
+    if "world" in shared:
+        gids.gids_store_destroy(shared.pop("world")["store"])
     print(json.dumps(result))
     return 0
 
@@ -304,8 +308,20 @@ def run_workload(args, shared):
                        cache_lines=max(c.ways, c.cache_lines * c.line_bytes // new_r // c.ways * c.ways))
 
     cfg = with_dim(wl.scaled(base, args.nodes) if args.nodes else pick_scale(base, wl, args.max_pinned_gib))
+
+    def world_key(c):
+        """what the pinned table, the graph and the hot nodes depend on: configurations that agree in it share them"""
+        return (c.seed, c.n_nodes, c.row_bytes, c.index_dtype, c.dim, c.feat_dtype, c.ell, c.p4, c.d_max, c.cpu_rows,
+                args.hot_by, (tuple(c.fanouts), c.n_seeds) if args.hot_by != "indegree" else None)
+
+    world = shared.get("world")
+    if world is not None and world["key"] != world_key(cfg):    # (a box pins 64 GiB: one table at a time)
+        torch.cuda.synchronize()
+        gids.gids_store_destroy(world["store"])
+        world = None
+        shared.pop("world")
     # pin the store first: a box that grants less pinned memory than assumed runs at half the node count, and so on
-    while True:
+    while world is None:
         try:
             store = gids.gids_store_create(cfg.n_nodes, cfg.row_bytes, np.dtype(cfg.index_dtype).itemsize)
             break
@@ -323,6 +339,16 @@ def run_workload(args, shared):
         cfg = replace(cfg, line_bytes=P * cfg.row_bytes,
                       cache_lines=max(cfg.ways, cfg.cache_lines * cfg.line_bytes // (P * cfg.row_bytes) // cfg.ways * cfg.ways))
     R = cfg.row_bytes
+    if world is not None:
+        log(f"workload {cfg.name}: table, graph and hot nodes of the run before")
+        store, g, hot, table, rate, overhead = (world[k] for k in ("store", "g", "hot", "table", "rate", "overhead"))
+        env = dict(shared, link_rows_per_s=rate, link_overhead_s=overhead, g=g, hot=hot, table=table, store=store, base=base)
+        try:
+            return run_lists(args, env, cfg, base, g, wl, gids)
+        finally:
+            if "push_stream" in env:
+                shared["push_stream"] = env["push_stream"]
+            torch.cuda.synchronize()
     rate, overhead = gids.gids_store_calibrate(store)
     log(f"link calibration: {rate * R / 1e9:.1f} GB/s ({rate / 1e6:.1f} M rows/s), overhead {overhead * 1e6:.1f} us; "
         f"Eq. 2-3: {gids.gids_accum_threshold(rate, overhead, 0.0, 0.95):.0f} link rows in flight for 95 % of it")
@@ -352,13 +378,13 @@ def run_workload(args, shared):
     wl.fill_store(cfg.seed, cfg.n_nodes, cfg.dim, table, gids.gids_store_host_ptr(store))
     log(f"store: {cfg.n_nodes * R / 1e9:.2f} GB pinned and filled ({time.time() - t0:.1f} s)")
     env = dict(shared, link_rows_per_s=rate, link_overhead_s=overhead, g=g, hot=hot, table=table, store=store, base=base)
+    shared["world"] = dict(key=world_key(cfg), store=store, g=g, hot=hot, table=table, rate=rate, overhead=overhead)
     try:
         return run_lists(args, env, cfg, base, g, wl, gids)
     finally:
         if "push_stream" in env:
             shared["push_stream"] = env["push_stream"]          # one push stream for the whole process
         torch.cuda.synchronize()
-        gids.gids_store_destroy(store)
 
 
 def run_lists(args, env, cfg, base, g, wl, gids):
