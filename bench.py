@@ -194,6 +194,8 @@ def main() -> int:
             elif name in ("large_merged", "large_merged_dedup"):
                 sub.workload, sub.accum, sub.many, sub.steps, sub.warmup = "large", 1, 16, 96, 32
                 sub.group_dedup = name.endswith("dedup")
+                if sub.group_dedup:                             # (the more steps per call, the more rows they share)
+                    sub.many, sub.steps = 32, 128
                 sub.cpu_seconds = 14.0                          # (the oracle replays the warm-up before it can compare)
             elif name == "medium_merged_dedup":
                 sub.workload, sub.accum, sub.many, sub.group_dedup, sub.steps, sub.warmup = "medium", 1, 32, True, 320, 32

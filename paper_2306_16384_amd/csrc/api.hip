@@ -227,6 +227,7 @@ struct gids_cache {
     bool group_dedup = false;           // gids_cache_set_group_dedup
     char** cpu_first = nullptr;         // n_hot words, clear between merged calls (see CacheView::cpu_first)
     bool many_pool_forced = false;
+    uint32_t many_chunk_forced = 0;     // GIDS_MANY_CHUNK: steps per classification launch where the sets' state is in memory
     uint64_t many_pool = 152 * 1024;    // LDS for a classifying workgroup's own list entries (GIDS_MANY_POOL, bytes; 0: none)
     int fuse = 1;               // GIDS_FUSE=0: commit, queueing and counters as a kernel each; no merged kernels
     int move_blocks = 1 << 20;  // most workgroups the row mover uses for rows that stay in HBM
@@ -390,6 +391,7 @@ struct CacheT final : gids_cache {
             many_pool_forced = true;
         }
         if (const char* env = getenv("GIDS_MANY_PIPELINE_MIN")) many_meta_min = (uint32_t)std::max(0, atoi(env));
+        if (const char* env = getenv("GIDS_MANY_CHUNK")) many_chunk_forced = (uint32_t)std::max(0, atoi(env));
         if (const char* env = getenv("GIDS_MOVE_BLOCKS")) {
             const int b = atoi(env);
             if (b >= 1 && b <= (1 << 20)) move_blocks = b;
@@ -836,33 +838,60 @@ struct CacheT final : gids_cache {
                 c2--;
             }
         }
-        uint32_t n_lists_upper = 0;                           // distinct lists the call reads: heads and pushed ones
+        // the window slots the steps will read, as many_enqueue will assign them
+        std::vector<int> pushed_at(k, -1), head_at(k, 0);
         {
-            std::vector<char> seen(slots.size(), 0);
             uint32_t h = head, c2 = count;
             for (uint32_t i = 0; i < k; i++) {
                 if (push_ids && push_ids[i]) {
-                    const size_t q = (h + c2) % slots.size();
-                    n_lists_upper += !seen[q];
-                    seen[q] = 1;
+                    pushed_at[i] = (int)((h + c2) % slots.size());
                     c2++;
                 }
-                n_lists_upper += !seen[h];
-                seen[h] = 1;
+                head_at[i] = (int)h;
                 h = (h + 1) % slots.size();
                 c2--;
             }
         }
+        auto lists_between = [&](uint32_t a, uint32_t b) {    // distinct lists the steps [a, b) read
+            std::vector<char> seen(slots.size(), 0);
+            uint32_t n = 0;
+            for (uint32_t i = a; i < b; i++) {
+                if (pushed_at[i] >= 0 && !seen[pushed_at[i]]) { seen[pushed_at[i]] = 1; n++; }
+                if (!seen[head_at[i]]) { seen[head_at[i]] = 1; n++; }
+            }
+            return n;
+        };
         // What the classification is sized for: the longest list's distinct IDs.  The host knows raw lengths only;
         // the finished gathers tell how many distinct IDs a raw list of this stream tends to hold.
         update_distinct_ratio();
-        const uint64_t longest_est = std::min<uint64_t>(store->n_rows,
-                                                        (uint64_t)std::ceil((double)longest_raw * std::min(1.0, distinct_ratio * 1.25)));
-        const bool fast = store->n_rows < (1ull << 32) && n_sets < (1ull << 32) && ways <= many_max_ways() &&
-                          rows_per_line == 1 && (fuse & 1) && longest_raw <= many_list_max &&
-                          (many_pool_forced ||
-                           many_fits(store->n_rows, n_sets, ways, words_per_set, sizeof(IdT), n_lists_upper,
-                                     std::max<uint64_t>(longest_est, 1), many_pool, group_dedup));
+        const uint64_t longest_est = std::max<uint64_t>(1, std::min<uint64_t>(store->n_rows,
+            (uint64_t)std::ceil((double)longest_raw * std::min(1.0, distinct_ratio * 1.25))));
+        // steps per launch of the classification: all of them where their lists fit a workgroup's LDS together;
+        // fewer where the sets' state stays in device memory anyway (a launch then leaves nothing behind in LDS
+        // that the next would miss); 0: the per-step kernels
+        uint32_t chunk = 0;
+        if (store->n_rows < (1ull << 32) && n_sets < (1ull << 32) && ways <= many_max_ways() && rows_per_line == 1 &&
+            (fuse & 1) && longest_raw <= many_list_max) {
+            bool in_lds = false;
+            auto fits = [&](uint32_t n_lists) {
+                return many_fits(store->n_rows, n_sets, ways, words_per_set, sizeof(IdT), n_lists, longest_est, many_pool,
+                                 group_dedup, &in_lds);
+            };
+            const bool all_fit = fits(lists_between(0, k));
+            if (many_chunk_forced && many_chunk_forced < k && !in_lds) {
+                chunk = many_chunk_forced;
+            } else if (many_pool_forced || all_fit) {
+                chunk = k;
+            } else if (!in_lds) {
+                for (uint32_t c : {16u, 8u, 4u}) {
+                    if (c >= k) continue;
+                    uint32_t most = 0;
+                    for (uint32_t a = 0; a < k; a += c) most = std::max(most, lists_between(a, std::min(k, a + c)));
+                    if (fits(most)) { chunk = c; break; }
+                }
+            }
+        }
+        const bool fast = chunk != 0;
         int rc;
         if (!fast) {
             // large tables, high associativity: the same steps through the per-step kernels, still one group
@@ -907,11 +936,11 @@ struct CacheT final : gids_cache {
             many_plan_cap = total_upper + total_upper / 2;
         }
         if ((rc = ensure_queue(total_upper))) return rc;
-        if ((rc = many_enqueue(k, push_ids, push_n, outs, caps, uniques, total_upper, std::max<uint64_t>(longest_est, 1), ps, s))) sticky = rc;
+        if ((rc = many_enqueue(k, chunk, push_ids, push_n, outs, caps, uniques, total_upper, std::max<uint64_t>(longest_est, 1), ps, s))) sticky = rc;
         return rc;
     }
 
-    int many_enqueue(uint32_t k, const void* const* push_ids, const uint64_t* push_n, void* const* outs,
+    int many_enqueue(uint32_t k, uint32_t chunk, const void* const* push_ids, const uint64_t* push_n, void* const* outs,
                      const uint64_t* caps, void* const* uniques, uint64_t total_upper, uint64_t longest, hipStream_t ps,
                      hipStream_t s) {
         int rc;
@@ -936,30 +965,14 @@ struct CacheT final : gids_cache {
             if ((rc = follow(s))) return rc;
         }
         if (flush_recorded[group & 1]) HIP_TRY(hipStreamWaitEvent(m, ev_flush[group & 1], 0));
+        // the steps' bookkeeping (window slots, outputs, staging of the distinct-ID lists) and the pushed lists
         ManyPushes<IdT> mp;
-        ManySteps<IdT> ms;
-        ms.k = k;
-        ms.seq0 = seq;
-        ms.group_dedup = group_dedup ? 1u : 0u;
+        struct Step { int pushed_slot; uint32_t head_slot; uint64_t plan_offset; };
+        std::vector<Step> steps(k);
         uint32_t n_push = 0;
         uint64_t off = 0;
-        ms.n_lists = 0;
-        std::vector<int> list_of_slot(slots.size(), -1);
-        auto list_of = [&](uint32_t slot, bool is_head) {
-            int& l = list_of_slot[slot];
-            if (l < 0) {
-                l = (int)ms.n_lists++;
-                ms.list[l] = static_cast<const IdT*>(slots[slot].ids);
-                ms.list_slot[l] = (uint16_t)slot;
-                ms.list_is_head[l] = 0;
-            }
-            if (is_head) ms.list_is_head[l] = 1;
-            return (uint8_t)l;
-        };
         for (uint32_t i = 0; i < k; i++) {
-            ms.pushed[i] = nullptr;
-            ms.pushed_slot[i] = 0;
-            ms.pushed_list[i] = MANY_NO_LIST;
+            steps[i].pushed_slot = -1;
             if (push_ids && push_ids[i]) {
                 const uint32_t slot = (head + count) % slots.size();
                 WindowSlot& sl = slots[slot];
@@ -968,23 +981,16 @@ struct CacheT final : gids_cache {
                 mp.dst[n_push] = static_cast<IdT*>(sl.ids);
                 mp.slot[n_push] = slot;
                 n_push++;
-                ms.pushed[i] = static_cast<const IdT*>(sl.ids);
-                ms.pushed_slot[i] = slot;
-                ms.pushed_list[i] = list_of(slot, false);
+                steps[i].pushed_slot = (int)slot;
                 sl.last_reader = -1;
                 count++;
             }
-            ms.head_list[i] = list_of(head, true);
             const uint64_t n_raw = slots[head].n_raw;
-            ms.head[i] = static_cast<const IdT*>(slots[head].ids);
-            ms.head_slot[i] = head;
-            ms.out_capacity[i] = caps[i];
-            ms.plan_offset[i] = off;
+            steps[i].head_slot = head;
+            steps[i].plan_offset = off;
             off += std::min<uint64_t>(n_raw, store->n_rows);
-            ms.out[i] = static_cast<char*>(outs[i]);
             uq.dst[i] = uniques ? uniques[i] : nullptr;       // staged, and copied out when the group moves
-            uq.src_entry[i] = ms.plan_offset[i];
-            ms.unique_out[i] = uq.dst[i] ? ustage[group & 1] + ms.plan_offset[i] : nullptr;
+            uq.src_entry[i] = steps[i].plan_offset;
             const int r = (int)((seq + i) % STATS_RING);
             raw_of[r] = (uint32_t)n_raw;
             prof_valid[r] = false;
@@ -1004,7 +1010,53 @@ struct CacheT final : gids_cache {
         // the caller's ID buffers are read by that kernel alone: the push stream goes on as soon as it is through
         // (were it held until the classification ends, the next call's lists would be ready that much later)
         if (on_meta && n_push && (rc = edge(meta, ps))) return rc;
-        launch_classify_many<IdT>(view(), accum_view(), group, ms, longest, many_pool, many_plan, ring_dev, STATS_RING, m);
+        // the classification: one launch for the steps [a, b) at a time (all of them where their lists fit a
+        // workgroup's LDS together), the group staying open in between
+        for (uint32_t a = 0; a < k; a += chunk) {
+            const uint32_t b = std::min(k, a + chunk);
+            ManySteps<IdT> ms;
+            ms.k = b - a;
+            ms.seq0 = seq + a;
+            ms.step0 = a;
+            ms.closes_group = b == k ? 1u : 0u;
+            ms.group_dedup = group_dedup ? 1u : 0u;
+            ms.n_lists = 0;
+            std::vector<int> list_of_slot(slots.size(), -1);
+            auto list_of = [&](uint32_t slot, bool is_head) {
+                int& l = list_of_slot[slot];
+                if (l < 0) {
+                    l = (int)ms.n_lists++;
+                    ms.list[l] = static_cast<const IdT*>(slots[slot].ids);
+                    ms.list_slot[l] = (uint16_t)slot;
+                    ms.list_is_head[l] = 0;
+                }
+                if (is_head) ms.list_is_head[l] = 1;
+                return (uint8_t)l;
+            };
+            for (uint32_t i = a; i < b; i++) {
+                const uint32_t x = i - a;
+                ms.pushed[x] = nullptr;
+                ms.pushed_slot[x] = 0;
+                ms.pushed_list[x] = MANY_NO_LIST;
+                if (steps[i].pushed_slot >= 0) {
+                    const uint32_t slot = (uint32_t)steps[i].pushed_slot;
+                    ms.pushed[x] = static_cast<const IdT*>(slots[slot].ids);
+                    ms.pushed_slot[x] = slot;
+                    ms.pushed_list[x] = list_of(slot, false);
+                }
+                ms.head_list[x] = list_of(steps[i].head_slot, true);
+                ms.head[x] = static_cast<const IdT*>(slots[steps[i].head_slot].ids);
+                ms.head_slot[x] = steps[i].head_slot;
+                ms.out_capacity[x] = caps[i];
+                ms.plan_offset[x] = steps[i].plan_offset;
+                ms.out[x] = static_cast<char*>(outs[i]);
+                ms.unique_out[x] = uq.dst[i] ? ustage[group & 1] + steps[i].plan_offset : nullptr;
+            }
+            launch_classify_many<IdT>(view(), accum_view(), group, ms, longest, many_pool, many_plan, ring_dev, STATS_RING, m);
+        }
+        // (a call in several launches: the words that remember the first fill of a CPU-buffer row are cleared here)
+        if (chunk < k && group_dedup && cpu_first)
+            launch_fill_i64(reinterpret_cast<int64_t*>(cpu_first), n_hot, 0, m);
         HIP_TRY(hipGetLastError());
         const int r_last = (int)((seq + k - 1) % STATS_RING);
         for (uint32_t i = 0; i < k; i++) ev_of[(seq + i) % STATS_RING] = r_last;

@@ -245,11 +245,15 @@ struct ManySteps {
     uint32_t sets_per_wg;               // places for sets in that LDS: ceil(n_sets / workgroups)
     uint32_t rounds;                    // nodes per set: ceil(n_rows / n_sets)
     uint32_t group_dedup;               // a CPU-buffer row that several steps need crosses the link once per call
+    // a call whose lists do not fit a workgroup's LDS all at once is classified in several launches, each with the
+    // steps [step0, step0 + k) of the call; the group stays open between them
+    uint32_t step0;
+    uint32_t closes_group;              // this launch holds the call's last step
 };
 constexpr uint8_t MANY_NO_LIST = 0xFF;
 uint64_t many_max_rows();
 bool many_fits(uint64_t n_rows, uint64_t n_sets, uint32_t ways, uint32_t words_per_set, size_t id_bytes, uint32_t n_lists,
-               uint64_t longest, uint64_t pool_bytes, bool group_dedup);
+               uint64_t longest, uint64_t pool_bytes, bool group_dedup, bool* state_in_lds = nullptr);
 uint32_t many_max_ways();
 template <typename IdT>
 void launch_dedup_small(const ManyPushes<IdT>& p, uint32_t n_lists, uint64_t n_rows, Ctl* ctl, hipStream_t s);

@@ -756,8 +756,9 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
             __syncthreads();
             const StateInMemory<IdT, WAYS> st{c, LineWordsGlobal{c.pending, c.fillgrp, c.hitgrp, a.fills[group & 1u]}};
             steps_from_pool<IdT, WAYS>(c, a, st, group, m, n_ok, stamp0, pool_v, pool_j, pool_cpu, own_n, cnt, places);
-            if (m.group_dedup && c.cpu_first) {
+            if (m.group_dedup && c.cpu_first && m.step0 == 0 && m.closes_group) {
                 // the words that remember the call's first fill of a CPU-buffer row are clear between calls
+                // (a call in several launches: the host clears the table behind the last)
                 // (list_off still holds this workgroup's entries of the gathered lists)
                 const uint32_t total = list_off[m.n_lists];
                 uint32_t l = 0;
@@ -806,7 +807,7 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
         StatsRec* rec = ring + (m.seq0 + i) % ring_size;
         const bool ran = i < n_ok;
         const uint32_t n = ran ? list_n[m.head_list[i]] : 0u;
-        uint32_t queued = n;
+        uint32_t queued = (m.step0 ? ctl->q_rows : 0u) + n;     // (rows the call's earlier launches queued)
         for (uint32_t x = 0; x < i && x < n_ok; x++) queued += list_n[m.head_list[x]];
         rec->n_unique = n;
         rec->n_hit = ld_agent(&ctl->many_cnt[i][0]);
@@ -815,15 +816,18 @@ __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT
         rec->n_bypass = ld_agent(&ctl->many_cnt[i][3]);
         rec->n_line_fills = ld_agent(&ctl->many_cnt[i][4]);
         rec->n_cpu_again = ld_agent(&ctl->many_cnt[i][5]);
-        const bool closes = i + 1 == m.k;                     // the call's steps are one group, closed by its last
+        const bool closes = m.closes_group && i + 1 == m.k;   // the call's steps are one group, closed by its last
         rec->n_pending = closes ? 0u : queued;
         rec->flushed = closes ? 1 : 0;
         rec->status = ran ? 0 : -(int32_t)err;
-        ctl->grp_nu[group & 1u][i] = n;
+        ctl->grp_nu[group & 1u][m.step0 + i] = n;
         for (int x = 0; x < 6; x++) ctl->many_cnt[i][x] = 0;
     }
+    __syncthreads();                                          // (every record has read the rows queued before)
     if (tid == 0) {
-        ctl->q_rows = 0;
+        uint32_t all = m.step0 ? ctl->q_rows : 0u;
+        for (uint32_t x = 0; x < n_ok; x++) all += list_n[m.head_list[x]];
+        ctl->q_rows = m.closes_group ? 0u : all;
         ctl->stamp = stamp0 + n_ok;
         ctl->ticket_cls = 0;
     }
@@ -945,8 +949,9 @@ ManyShape many_shape(uint64_t n_rows, uint64_t n_sets, uint32_t ways, uint32_t w
 // four standard deviations more (a share is a count of independent hits on one of g residues).  Beyond that most
 // workgroups would read the lists from memory in every phase, and the per-step kernels are the better choice.
 bool many_fits(uint64_t n_rows, uint64_t n_sets, uint32_t ways, uint32_t words_per_set, size_t id_bytes, uint32_t n_lists,
-               uint64_t longest, uint64_t pool_bytes, bool group_dedup) {
+               uint64_t longest, uint64_t pool_bytes, bool group_dedup, bool* state_in_lds) {
     const ManyShape sh = many_shape(n_rows, n_sets, ways, words_per_set, id_bytes, n_lists, longest, pool_bytes, group_dedup);
+    if (state_in_lds) *state_in_lds = sh.resident;
     uint64_t dev = 0;
     while ((dev + 1) * (dev + 1) <= sh.share) dev++;          // floor(sqrt(share))
     return pool_bytes == 0 || sh.cap >= sh.share + 4 * (dev + 1) + 8;

@@ -42,7 +42,7 @@ def with_env(knobs, make):
 
 
 def run_many(gpu, oracle, feats, batches, *, id_dtype, lines, ways, window, ks, hot=None, policy=None, pipeline="0",
-             fuse=None, pool=None, resident=None, meta_min=None, list_max=None, dedup=False, expect_merged=None, label=""):
+             fuse=None, pool=None, resident=None, meta_min=None, list_max=None, dedup=False, chunk=None, expect_merged=None, label=""):
     """ks: the sizes of the merged calls, in order (0 = one plain push + gather step in between);
     cycles until every list is gathered."""
     torch, gids, GatherSession = gpu
@@ -72,6 +72,7 @@ def run_many(gpu, oracle, feats, batches, *, id_dtype, lines, ways, window, ks, 
         knobs["GIDS_MANY_RESIDENT"] = resident
     knobs["GIDS_MANY_PIPELINE_MIN"] = meta_min
     knobs["GIDS_MANY_LIST_MAX"] = list_max
+    knobs["GIDS_MANY_CHUNK"] = chunk
     ses = with_env(knobs, lambda: GatherSession(n_rows, R, id_dtype, lines, ways, R, window, 1000))
     with ses:
         ses.store_view()[:] = feats_u8
@@ -354,6 +355,7 @@ def test_random_merged_calls(gpu, oracle_mod, case):
                                 window=window, ks=ks, hot=rng.choice(n, n_hot, replace=False) if n_hot else None,
                                 policy=(1, case) if rng.random() < 0.3 else None, pipeline=pipeline, pool=pool,
                                 resident=resident, meta_min=[None, "16", "0"][case % 3], dedup=case % 2 == 1,
+                                chunk=[None, None, "3", "8"][case % 4] if resident == "0" else None,
                                 label=f"random{case}")
     RANDOM_TALLY[0] += merged
     RANDOM_TALLY[1] += per_step
@@ -398,6 +400,24 @@ def test_cpu_buffer_rows_cross_the_link_once_per_call(gpu, oracle_mod, resident)
         with pytest.raises(gids.GidsError) as e:
             ses.set_group_dedup(True)
         assert e.value.code == gids.GIDS_E_INVAL
+
+
+@pytest.mark.parametrize("chunk,dedup", [("4", False), ("5", True), ("16", True)])
+def test_a_call_classified_in_several_launches(gpu, oracle_mod, chunk, dedup):
+    """Where the sets' state stays in device memory a call whose lists do not fit a workgroup's LDS together is
+    classified a few steps per launch, the group staying open in between (here forced: GIDS_MANY_CHUNK).  Lines
+    installed in one launch and hit, evicted or installed again in a later one of the same call; n_pending across
+    the launches; CPU-buffer rows remembered from launch to launch."""
+    rng = np.random.default_rng(626)
+    n = 9000
+    feats = rng.integers(0, 256, size=(n, 128), dtype=np.uint8)
+    hot = rng.choice(n, 2000, replace=False)
+    batches = [np.concatenate([rng.choice(hot, 400), np.minimum(rng.zipf(1.3, size=700) - 1, n - 1)]).astype(np.int64)
+               for _ in range(56)]
+    for pipeline in ("0", "1"):
+        run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=8 * 16, ways=8, window=3, ks=[32, 0, 13, 7],
+                 hot=hot, pipeline=pipeline, resident="0", chunk=chunk, dedup=dedup, expect_merged=True,
+                 label=f"chunks of {chunk}")
 
 
 def test_merged_calls_through_the_per_step_kernels(gpu, oracle_mod):
