@@ -298,8 +298,9 @@ int gids_gather_static(gids_cache* cache, const void* ids_dev, uint64_t n, void*
  * Every output of the call is complete, in stream order, when the call's work
  * ends.  With ways <= 16, one row per line and LDS room for a workgroup's share
  * of every list of the call (lists of tens of thousands of distinct IDs at
- * k = 32, of more than a hundred thousand at k <= 16), the k steps take a fixed
- * number of launches: one that deduplicates the pushed lists (a workgroup and
+ * k = 32, of more than a hundred thousand at k <= 16; where the sets' state is
+ * in device memory anyway a longer call is classified 16, 8 or 4 steps per
+ * launch), the k steps take a fixed number of launches: one that deduplicates the pushed lists (a workgroup and
  * an LDS bitmap each; on tables beyond 1.3 M rows three launches per list
  * through the bitmap in device memory), one that classifies the k minibatches
  * one after the other, each workgroup for its own share of the cache sets and,

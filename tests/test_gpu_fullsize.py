@@ -325,11 +325,12 @@ def test_large_at_benchmark_size(oracle_mod, big_world):
             hot=big_world["hot"])
 
 
-@pytest.mark.parametrize("k,dedup", [(8, False), (16, True)])
+@pytest.mark.parametrize("k,dedup", [(8, False), (32, True)])
 def test_large_in_merged_calls(oracle_mod, big_world, k, dedup):
-    """120 minibatches of Large through gids_gather_many, 8 or 16 steps per call: the pushed lists go through the
-    bitmap in device memory, the classification keeps its lists in LDS and the sets' state in memory.  dedup: a
-    CPU-buffer row that several steps of a call need crosses the link once."""
+    """120 minibatches of Large through gids_gather_many, 8 or 32 steps per call (32: classified 16 steps per
+    launch): the pushed lists go through the bitmap in device memory, the classification keeps its lists in LDS
+    and the sets' state in memory.  dedup: a CPU-buffer row that several steps of a call need crosses the link
+    once."""
     cfg = big_world["cfg"]
     n_b = 120
     if "large120" not in big_world["lists"]:
