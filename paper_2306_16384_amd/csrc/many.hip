@@ -551,9 +551,10 @@ template <typename IdT, int WAYS>
 __global__ __launch_bounds__(CM_THREADS) void classify_many_kernel(CacheView<IdT> c, AccumView a, uint32_t group,
                                                                    ManySteps<IdT> m, uint64_t* __restrict__ plan_all,
                                                                    StatsRec* ring, uint32_t ring_size) {
-    // Dynamic LDS.  The pool: this workgroup's entries of every list, picked out once: share_cap places per list
-    // (ID, position in the list, CPU-buffer row or CM_NONE), filled in no particular order.  With m.resident,
-    // also the state of this workgroup's sets and nodes for the length of the kernel.
+    // Dynamic LDS.  The pool: this workgroup's entries of every list of the launch, picked out once: share_cap places
+    // per list (ID, position in the list), filled in no particular order.  With m.resident, also the entries'
+    // CPU-buffer rows (or CM_NONE), the state of this workgroup's sets and nodes for the length of the kernel and,
+    // with m.group_dedup, a word per node for the output row of the call's first fill of it.
     extern __shared__ unsigned long long lds_raw[];
     __shared__ uint32_t list_n[2 * MANY_MAX];                 // entries of each list
     __shared__ uint32_t list_off[2 * MANY_MAX + 1];           // entries of the lists before it
