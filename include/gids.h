@@ -80,7 +80,7 @@ typedef struct gids_cache gids_cache;
  * lines this minibatch fills from the store: n_miss - n_bypass with one row
  * per line, fewer when several missing rows share a line.  n_cpu_again (a
  * subset of n_cpu_hit; 0 unless gids_cache_set_group_dedup is on) counts the
- * CPU-buffer rows that an earlier step of the same merged call already brings
+ * CPU-buffer rows that an earlier minibatch of the same group already brings
  * over the link and that this minibatch receives as a copy inside device
  * memory. */
 typedef struct gids_stats {
@@ -174,15 +174,17 @@ int gids_cache_set_accum_mode(gids_cache* cache, int mode);
 
 /* Section 3.2 merges the accesses of consecutive iterations; merged, accesses to
  * the same row of the constant CPU buffer (Section 3.3) can be served by one
- * transfer.  on != 0: within one gids_gather_many call that runs through the
- * merged kernels, a CPU-buffer row that several steps need crosses the host
- * link once, for the first of them, and reaches the others' outputs as a copy
- * of that output row inside device memory (after the call's fills).  Outputs
- * and counters are the same either way (n_cpu_hit counts every access); what
- * changes is the traffic over the link.  Off by default: the per-minibatch
- * cost model of the measurements charges every CPU-buffer hit one row over the
- * link.  Needs a cache created with accum_threshold > 0; not while a group of
- * minibatches is open (GIDS_E_INVAL). */
+ * transfer.  on != 0: within one group of minibatches (a gids_gather_many call,
+ * or the gathers that accum_threshold puts into one group) a CPU-buffer row
+ * that several of them need crosses the host link once, for the first of
+ * them, and reaches the others' outputs as a copy of that output row inside
+ * device memory (with the group's other dependent copies, after its fills).
+ * Outputs and counters are the same either way (n_cpu_hit counts every access,
+ * n_cpu_again those served by a copy); what changes is the traffic over the
+ * link.  Off by default: the per-minibatch cost model of the measurements
+ * charges every CPU-buffer hit one row over the link.  Needs a cache created
+ * with accum_threshold > 0; not while a group of minibatches is open
+ * (GIDS_E_INVAL). */
 int gids_cache_set_group_dedup(gids_cache* cache, int on);
 
 /* Base replacement policy, i.e. the order in which the evictable ways of a set

@@ -423,6 +423,15 @@ struct CacheT final : gids_cache {
     }
 
     // room for `rows` operations in each list of both groups; what is queued survives a move
+    // the table behind gids_cache_set_group_dedup, once it is asked for and a CPU buffer exists
+    int ensure_cpu_first() {
+        if (!group_dedup || !n_hot || cpu_first) return GIDS_OK;
+        int rc = dev_alloc(&cpu_first, n_hot);
+        if (rc) return rc;
+        HIP_TRY(hipMemset(cpu_first, 0, n_hot * sizeof(char*)));
+        return GIDS_OK;
+    }
+
     int ensure_queue(uint64_t rows) {
         if (rows <= queue_cap) return GIDS_OK;
         HIP_TRY(hipDeviceSynchronize());
@@ -667,6 +676,7 @@ struct CacheT final : gids_cache {
             if ((rc = accum_limit(&limit))) return rc;
             opens = open_batches == 0;
             if ((rc = ensure_queue(open_upper + n_upper))) return rc;
+            if ((rc = ensure_cpu_first())) return rc;
             closes = open_nodes + n_raw >= limit || open_batches + 1 >= ACCUM_MAX_MERGE;
             if (group_override) closes = group_override == 2; // a merged call decides for itself
         }
@@ -743,6 +753,8 @@ struct CacheT final : gids_cache {
                 launch_queue<IdT>(c, accum_view(), group, U, b.hd, n_upper, b.pl, static_cast<char*>(out), unique_to, m);
                 launch_finalize(ctl, ring_dev + r, seq, n_u, accum_flags, m);
             }
+            // (the words that remember the group's first fill of a CPU-buffer row are clear between groups)
+            if (closes && group_dedup && cpu_first) launch_fill_i64(reinterpret_cast<int64_t*>(cpu_first), n_hot, 0, m);
             if ((rc = mark_phase(r, 2, m))) return rc;
             raw_of[r] = (uint32_t)n_raw;
             open_nodes += n_raw;
@@ -791,6 +803,7 @@ struct CacheT final : gids_cache {
     int flush_enqueue(hipStream_t s) {
         int rc = follow(s);
         if (rc) return rc;
+        if (group_dedup && cpu_first) launch_fill_i64(reinterpret_cast<int64_t*>(cpu_first), n_hot, 0, pipelined ? meta : s);
         hipEvent_t after = nullptr;
         if (pipelined) {                                      // everything the open group's gathers queued
             after = ev_hop[hop++ % 16];
@@ -907,10 +920,7 @@ struct CacheT final : gids_cache {
             return GIDS_OK;
         }
         many_fast_calls++;
-        if (group_dedup && n_hot && !cpu_first) {
-            if ((rc = dev_alloc(&cpu_first, n_hot))) return rc;
-            HIP_TRY(hipMemset(cpu_first, 0, n_hot * sizeof(char*)));
-        }
+        if ((rc = ensure_cpu_first())) return rc;
         // room: window slots of the pushed lists, the plans of all steps, the group's lists
         if (open_batches && (rc = flush(s))) return rc;
         {

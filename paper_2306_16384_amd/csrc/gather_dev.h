@@ -165,13 +165,22 @@ __device__ __forceinline__ bool queue_entry(const CacheView<IdT>& c, const Accum
     return is_again;
 }
 
+// The same with everything in device memory, as the per-step kernels use it.  once_per_group: a CPU-buffer row
+// that an earlier minibatch of the open group already fetches comes as a copy (CacheView::cpu_first, which the
+// host clears when the group closes); the wavefront's count of such rows goes to Ctl::cnt_again.
 template <typename IdT>
 __device__ __forceinline__ void queue_entry(const CacheView<IdT>& c, const AccumView& a, uint32_t group, bool valid,
                                             uint64_t j, uint64_t e, uint64_t v, char* __restrict__ out,
-                                            IdT* __restrict__ unique_out) {
+                                            IdT* __restrict__ unique_out, bool once_per_group = false) {
     const LineWordsGlobal lw{c.pending, c.fillgrp, c.hitgrp, a.fills[group & 1u]};
     const PlacesGlobal places{c.ctl, group & 1u};
-    queue_entry(c, a, lw, places, group, valid, j, e, v, 0u, out, unique_out);
+    char** first = nullptr;
+    if (once_per_group && c.cpu_first && valid && (e >> PLAN_SHIFT) == PLAN_CPU) first = c.cpu_first + (e & PLAN_INDEX_MASK);
+    const bool again = queue_entry(c, a, lw, places, group, valid, j, e, v, 0u, out, unique_out, first);
+    if (once_per_group && c.cpu_first) {
+        const uint64_t b = __ballot(again);
+        if (b && (threadIdx.x & 63) == 0) atomicAdd(&c.ctl->cnt_again, (uint32_t)__popcll(b));
+    }
 }
 
 __device__ __forceinline__ uint32_t ld_agent(const uint32_t* p) {
@@ -191,7 +200,7 @@ __device__ __forceinline__ void publish_stats(Ctl* ctl, StatsRec* rec, uint64_t 
     rec->n_miss = ctl->cnt_miss;
     rec->n_bypass = ctl->cnt_bypass;
     rec->n_line_fills = ctl->cnt_fill;
-    rec->n_cpu_again = 0;
+    rec->n_cpu_again = ctl->cnt_again;
     uint32_t queued = 0;
     int flushed = 1;
     if (accum) {                          // rows of the open group that have not moved when this gather ends
@@ -208,7 +217,7 @@ __device__ __forceinline__ void publish_stats(Ctl* ctl, StatsRec* rec, uint64_t 
     rec->seq = seq;                       // written last: a record whose seq matches is complete
     __threadfence_system();
     if (!err) ctl->stamp += 1;
-    ctl->cnt_hit = ctl->cnt_cpu = ctl->cnt_miss = ctl->cnt_bypass = ctl->cnt_fill = 0;
+    ctl->cnt_hit = ctl->cnt_cpu = ctl->cnt_miss = ctl->cnt_bypass = ctl->cnt_fill = ctl->cnt_again = 0;
 }
 
 }  // namespace gids

@@ -33,6 +33,7 @@ struct Ctl {
     uint32_t stamp;         // index of the minibatch being gathered (successful gathers so far)
     uint32_t cnt_hit, cnt_cpu, cnt_miss, cnt_bypass;
     uint32_t cnt_fill;      // cache lines this minibatch fills
+    uint32_t cnt_again;     // CPU-buffer rows this minibatch receives as copies of an earlier fill of its group
     // accumulator: rows of the minibatches merged so far (the open group), and the lengths of the three
     // operation lists of the two groups that can exist at a time (the open one and the one being moved)
     uint32_t q_rows;

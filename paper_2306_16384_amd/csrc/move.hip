@@ -169,7 +169,7 @@ __global__ __launch_bounds__(MV_THREADS) void queue_kernel(CacheView<IdT> c, Acc
             e = plan[j];
             v = (uint64_t)unique[j];
         }
-        queue_entry(c, a, group, valid, j, e, v, out, unique_out);
+        queue_entry(c, a, group, valid, j, e, v, out, unique_out, true);
     }
 }
 
@@ -215,7 +215,7 @@ __global__ __launch_bounds__(MV_THREADS) void settle_kernel(CacheView<IdT> c, Ac
                     c.missmask[set * c.words_per_set + (round >> 6)] = 0ull;
                 }
             }
-            if (accum) queue_entry(c, a, group, valid, j, e, v, out, unique_out);
+            if (accum) queue_entry(c, a, group, valid, j, e, v, out, unique_out, true);
         }
     }
     __syncthreads();

@@ -42,7 +42,7 @@ def with_env(knobs, make):
 
 
 def run_many(gpu, oracle, feats, batches, *, id_dtype, lines, ways, window, ks, hot=None, policy=None, pipeline="0",
-             fuse=None, pool=None, resident=None, meta_min=None, list_max=None, dedup=False, chunk=None, expect_merged=None, label=""):
+             fuse=None, pool=None, resident=None, meta_min=None, list_max=None, dedup=False, chunk=None, exact_again=False, expect_merged=None, label=""):
     """ks: the sizes of the merged calls, in order (0 = one plain push + gather step in between);
     cycles until every list is gathered."""
     torch, gids, GatherSession = gpu
@@ -123,6 +123,8 @@ def run_many(gpu, oracle, feats, batches, *, id_dtype, lines, ways, window, ks, 
                     mine = set(np.intersect1d(want[t + i][0], hot).tolist())
                     again_of[t + i] = len(mine & seen_hot)
                     seen_hot |= mine
+                else:
+                    again_of[t + i] = 0
                 seq_of[t + i] = seq0 + i
                 rows += len(want[t + i][0])
                 expect_acc[t + i] = (0, 1) if i == k - 1 else (rows, 0)
@@ -136,11 +138,14 @@ def run_many(gpu, oracle, feats, batches, *, id_dtype, lines, ways, window, ks, 
             assert st.as_tuple() == tuple(int(x) for x in stats), (label, t, st.as_tuple(), stats.tolist())
             if expect_acc[t] is not None:
                 assert (st.n_pending, st.flushed) == expect_acc[t], (label, t, st.n_pending, st.flushed, expect_acc[t])
-            # (a workgroup that had to read the lists from memory fetches every row: only where none did)
-            if pool is None and expect_merged is True:
-                assert st.n_cpu_again == again_of.get(t, 0), (label, t, st.n_cpu_again, again_of.get(t, 0))
-            else:
-                assert st.n_cpu_again <= again_of.get(t, 0), (label, t, st.n_cpu_again, again_of.get(t, 0))
+            # (plain steps between the calls belong to groups of their own: not modelled here; a workgroup that
+            # had to read the lists from memory fetches every row: equality only where none did)
+            if t in again_of and exact_again:
+                assert st.n_cpu_again == again_of[t], (label, t, st.n_cpu_again, again_of[t])
+            elif t in again_of:
+                assert st.n_cpu_again <= again_of[t], (label, t, st.n_cpu_again, again_of[t])
+            elif not dedup:
+                assert st.n_cpu_again == 0
             m = len(u)
             assert np.array_equal(uqs[t][:m].cpu().numpy(), u.astype(ses.id_dtype)), (label, t)
             assert np.array_equal(outs[t][:m].cpu().numpy(), rows), f"{label} minibatch {t}: gathered rows differ"
@@ -381,7 +386,8 @@ def test_cpu_buffer_rows_cross_the_link_once_per_call(gpu, oracle_mod, resident)
     batches = [np.concatenate([rng.choice(hot, 1500), rng.integers(0, n, size=800)]).astype(np.int64) for _ in range(50)]
     for pipeline in ("0", "1"):
         run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=4 * 256, ways=4, window=5, ks=[32, 0, 7, 2],
-                 hot=hot, pipeline=pipeline, resident=resident, dedup=True, expect_merged=True, label="dedup")
+                 hot=hot, pipeline=pipeline, resident=resident, dedup=True, exact_again=True, expect_merged=True,
+                 label="dedup")
     with GatherSession(n, 256, np.int64, 1024, 4, 256, 0, 1) as ses:            # on, off and on again
         ses.store_view()[:] = feats
         ses.pin_hot(hot)
@@ -416,8 +422,8 @@ def test_a_call_classified_in_several_launches(gpu, oracle_mod, chunk, dedup):
                for _ in range(56)]
     for pipeline in ("0", "1"):
         run_many(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=8 * 16, ways=8, window=3, ks=[32, 0, 13, 7],
-                 hot=hot, pipeline=pipeline, resident="0", chunk=chunk, dedup=dedup, expect_merged=True,
-                 label=f"chunks of {chunk}")
+                 hot=hot, pipeline=pipeline, resident="0", chunk=chunk, dedup=dedup, exact_again=True,
+                 expect_merged=True, label=f"chunks of {chunk}")
 
 
 def test_merged_calls_through_the_per_step_kernels(gpu, oracle_mod):

@@ -23,7 +23,8 @@ def gpu():
 
 def run_case(gpu, oracle, feats, batches, *, id_dtype, lines, ways, line_bytes, window, threshold=0, hot=None,
              use_head=False, with_inverse=False, check_state=True, two_streams=False, policy=None, label="",
-             pipeline=None, push_depth0=False, wide_index=False, rows_per_line=1, accum_mode=0, fused=None):
+             pipeline=None, push_depth0=False, wide_index=False, rows_per_line=1, accum_mode=0, fused=None,
+             dedup=False):
     """Feeds the same raw ID lists to both implementations, protocol: keep window + 1 lists buffered.
     pipeline: "0" / "1" forces the library's internal stream off / on for this cache (GIDS_PIPELINE);
     fused: True / False switches the settle kernel (commit + queueing + counters) on / off (GIDS_FUSE);
@@ -82,6 +83,8 @@ def run_case(gpu, oracle, feats, batches, *, id_dtype, lines, ways, line_bytes, 
             ses.set_rows_per_line(rows_per_line)
         if threshold and accum_mode:
             ses.set_accum_mode(accum_mode)
+        if dedup:
+            ses.set_group_dedup(True)                         # one transfer per CPU-buffer row and group
         dev = [ses.to_device(b) for b in batches]
         torch.cuda.synchronize()
         push_stream = torch.cuda.Stream() if two_streams else None
@@ -100,10 +103,17 @@ def run_case(gpu, oracle, feats, batches, *, id_dtype, lines, ways, line_bytes, 
             outs.append(out); uniqs.append(uq); invs.append(inv if ids_arg is not None else None)
         ses.flush()
         torch.cuda.synchronize()
+        seen_hot = set()                                      # CPU-buffer rows the open group already fetches
         for t, raw in enumerate(batches):
             want_u, want_rows, want_stats = want[t]
             st = ses.stats(seqs[t])
             assert st.status == 0
+            if dedup and hot is not None and len(hot):
+                mine = set(np.intersect1d(want_u, hot).tolist())
+                assert st.n_cpu_again == len(mine & seen_hot), (label, t, st.n_cpu_again, len(mine & seen_hot))
+                seen_hot = set() if accum[t][1] else seen_hot | mine      # (the oracle's groups: closed by this gather?)
+            else:
+                assert st.n_cpu_again == 0
             assert st.as_tuple() == tuple(int(x) for x in want_stats), (label, t, st.as_tuple(), want_stats.tolist())
             assert st.n_line_fills == line_fills[t], (label, t, st.n_line_fills, line_fills[t])
             m = len(want_u)
@@ -310,6 +320,25 @@ def test_accumulator_lines_reused_inside_a_group(gpu, oracle_mod, pipeline):
                  label=f"accum-reuse/W2/thr{threshold}/pipe{pipeline}")
 
 
+@pytest.mark.parametrize("pipeline", ["0", "1"])
+def test_accumulator_fetches_a_cpu_buffer_row_once_per_group(gpu, oracle_mod, pipeline):
+    """gids_cache_set_group_dedup with single gathers: a CPU-buffer row that an earlier minibatch of the open group
+    already fetches comes as a copy of that output row.  Outputs, counters, groups and cache state as without it;
+    n_cpu_again equals its definition over the oracle's groups.  Fixed and adaptive thresholds, one launch or a
+    kernel each for commit, queueing and counters."""
+    rng = np.random.default_rng(4711)
+    n, R = 6000, 128
+    feats = rand_feats(rng, n, R)
+    hot = rng.choice(n, 1500, replace=False)
+    batches = [np.concatenate([rng.choice(hot, int(rng.integers(50, 400))), rng.integers(0, n, size=300)]).astype(np.int64)
+               for _ in range(50)]
+    batches[7] = np.array([], dtype=np.int64)
+    for threshold, mode, fused in ((900, 0, True), (5000, 0, False), (2500, 1, True), (10**9, 0, True)):
+        run_case(gpu, oracle_mod, feats, batches, id_dtype=np.int64, lines=64 * 4, ways=4, line_bytes=R, window=3,
+                 threshold=threshold, accum_mode=mode, hot=hot, use_head=True, two_streams=True, pipeline=pipeline,
+                 fused=fused, dedup=True, label=f"once-per-group/thr{threshold}/mode{mode}/pipe{pipeline}")
+
+
 def test_accumulator_outputs_follow_the_callers_stream(gpu, oracle_mod):
     """With the library's internal stream on, an accumulating cache classifies ahead of the caller's stream.
     Whatever the caller still has queued on its stream for an output buffer (here: a slow kernel, then a fill
@@ -489,7 +518,7 @@ def test_random_configurations(gpu, oracle_mod, case):
              hot=rng.choice(n, n_hot, replace=False) if n_hot else None,
              use_head=bool(use_head_override or (window and rng.random() < 0.5)), with_inverse=bool(rng.random() < 0.5),
              two_streams=bool(rng.random() < 0.5), policy=(1, case) if rng.random() < 0.3 else None,
-             label=f"random{case}", **extra)
+             dedup=bool(threshold and case % 2 == 0), label=f"random{case}", **extra)
 
 
 def test_link_calibration_is_sane(gpu):
