@@ -191,7 +191,7 @@ struct gids_cache {
         return GIDS_OK;
     }
     // Distinct IDs per raw ID in the lists of this stream: the largest ratio among the newest finished gathers
-    // (1 until one has finished).  Sizes the merged classification, which the host must launch knowing raw
+    // (1 until one has finished, and approached from there).  Sizes the merged classification, which the host must launch knowing raw
     // lengths only.
     double distinct_ratio = 1.0;
     void update_distinct_ratio() {
@@ -207,7 +207,8 @@ struct gids_cache {
             best = std::max(best, (double)rec.n_unique / (double)raw_of[r]);
             seen++;
         }
-        if (seen) distinct_ratio = std::min(1.0, best);
+        // (falls by three tenths per call at most: a few lists of many repeats do not undersize the calls after them)
+        if (seen) distinct_ratio = std::min(1.0, std::max(best, 0.7 * distinct_ratio));
     }
     // An error a kernel found stays in the device control block, so the record of the newest finished gather
     // carries it: calls that enqueue work look there first and refuse once the host can know.
